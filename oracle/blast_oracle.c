@@ -1,0 +1,260 @@
+/*
+ * CPU oracle for the block-sparse MLP path of BLaST (arxiv 2507.03117).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, written to be checked against the
+ * paper by eye.  It shares no code with the HIP library, is never called by the
+ * product path, and exists so that GPU results can be compared with something
+ * independent.  Callers: the test-suite, the smoke check and the benchmark's
+ * cpu_baseline leg.
+ *
+ * What it computes (all pointers are HOST pointers):
+ *   - block scores  = squared Frobenius norm of each b x b block  (Sec. 3.2)
+ *   - block mask    = keep the highest-scoring blocks until the requested
+ *                     sparsity is reached                           (Sec. 3.2)
+ *   - packing       = row-pointer / column-index / block-value arrays of the
+ *                     masked weight (BSR of the out x in weight, which is the
+ *                     paper's BCSC of its transposed weight)  (Sec. 3.2, 3.4.1)
+ *   - SpMM          = Y = W~ X with W~ the dense masked weight; the kernel of
+ *                     Sec. 3.4 "never computes on absent tiles", i.e. it reaches
+ *                     exactly this dense result, so the oracle is the definition:
+ *                     expand to dense, naive triple loop, fp64.
+ *   - MLP           = Eq. (1): Y = W~down ( act(W~gate X) (.) (W~up X) ), with the
+ *                     intermediate H rounded once to bf16 (the precision in which
+ *                     it enters the second contraction on the device).
+ *
+ * Readings of points the paper leaves open (kept identical in the HIP library
+ * by specification, not by shared code):
+ *   - number of dropped blocks for sparsity s over N blocks: ceil(s*N), computed
+ *     in integers on basis points: s_bp = round(s*1e4), n_zero = ceil(s_bp*N/1e4).
+ *   - ranking by the squared norm in fp64; ties broken by the lower linear block
+ *     index (block_row * NBc + block_col) being kept first.
+ *   - a kept block is stored even if all its values are zero.
+ *
+ * OpenMP is used only to run independent output rows on several cores; every
+ * individual sum is a sequential fp64 loop in index order.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static inline double bf16_to_f64(uint16_t h) {
+  uint32_t u = ((uint32_t)h) << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+/* fp32 -> bf16, round to nearest even (no NaN handling needed for finite data). */
+static inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  uint32_t lsb = (u >> 16) & 1u;
+  u += 0x7FFFu + lsb;
+  return (uint16_t)(u >> 16);
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* Sec. 3.2: "drop the lowest scoring blocks until we reach sparsity s". */
+int64_t oracle_n_keep(int64_t n_blocks, double sparsity) {
+  int64_t s_bp = (int64_t)llround(sparsity * 10000.0);
+  int64_t n_zero = (s_bp * n_blocks + 9999) / 10000;
+  if (n_zero > n_blocks) n_zero = n_blocks;
+  if (n_zero < 0) n_zero = 0;
+  return n_blocks - n_zero;
+}
+
+/* Sec. 3.2: each b x b block is scored by its Frobenius norm; we rank by the
+ * square (same order, no sqrt).  Sum in row-major order inside the block. */
+void oracle_block_scores(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b,
+                         double* score /* [rows/b][cols/b] */) {
+  int64_t nbr = rows / b, nbc = cols / b;
+  for (int64_t br = 0; br < nbr; ++br)
+    for (int64_t bc = 0; bc < nbc; ++bc) {
+      double s = 0.0;
+      for (int32_t i = 0; i < b; ++i)
+        for (int32_t j = 0; j < b; ++j) {
+          double w = bf16_to_f64(W[(br * b + i) * ldw + bc * b + j]);
+          s += w * w;
+        }
+      score[br * nbc + bc] = s;
+    }
+}
+
+typedef struct {
+  double score;
+  int64_t idx;
+} scored_t;
+
+static int cmp_scored(const void* pa, const void* pb) {
+  const scored_t* a = (const scored_t*)pa;
+  const scored_t* b = (const scored_t*)pb;
+  if (a->score > b->score) return -1; /* higher score first */
+  if (a->score < b->score) return 1;
+  if (a->idx < b->idx) return -1; /* then lower index first */
+  if (a->idx > b->idx) return 1;
+  return 0;
+}
+
+/* Full sort of (score desc, index asc); keep the first n_keep.  Returns n_keep.
+ * gap_out (may be NULL) receives the relative gap between the last kept and the
+ * first dropped score, so a test can reject inputs whose selection hangs on
+ * rounding. */
+int64_t oracle_topk_mask(const double* score, int64_t n_blocks, double sparsity, uint8_t* mask, double* gap_out) {
+  int64_t n_keep = oracle_n_keep(n_blocks, sparsity);
+  scored_t* a = (scored_t*)malloc(sizeof(scored_t) * (size_t)(n_blocks > 0 ? n_blocks : 1));
+  for (int64_t i = 0; i < n_blocks; ++i) {
+    a[i].score = score[i];
+    a[i].idx = i;
+  }
+  qsort(a, (size_t)n_blocks, sizeof(scored_t), cmp_scored);
+  memset(mask, 0, (size_t)n_blocks);
+  for (int64_t i = 0; i < n_keep; ++i) mask[a[i].idx] = 1;
+  if (gap_out) {
+    if (n_keep > 0 && n_keep < n_blocks && a[n_keep - 1].score > 0.0)
+      *gap_out = (a[n_keep - 1].score - a[n_keep].score) / a[n_keep - 1].score;
+    else
+      *gap_out = 1.0;
+  }
+  free(a);
+  return n_keep;
+}
+
+/* Sec. 3.2 / 3.4.1: compressed block format of W (.) mask.  For each block row in
+ * order, the kept block columns in ascending order; block values row-major, raw
+ * bf16 bit patterns.  row_order = block rows by stored-block count, descending,
+ * stable (the load-balance schedule).  Returns nnz. */
+int64_t oracle_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, const uint8_t* mask,
+                    int32_t* row_ptr, int32_t* col_idx, uint16_t* vals, int32_t* row_order) {
+  int64_t nbr = rows / b, nbc = cols / b, nnz = 0;
+  row_ptr[0] = 0;
+  for (int64_t br = 0; br < nbr; ++br) {
+    for (int64_t bc = 0; bc < nbc; ++bc) {
+      if (!mask[br * nbc + bc]) continue;
+      if (col_idx) col_idx[nnz] = (int32_t)bc;
+      if (vals)
+        for (int32_t i = 0; i < b; ++i)
+          for (int32_t j = 0; j < b; ++j)
+            vals[(nnz * b + i) * b + j] = W[(br * b + i) * ldw + bc * b + j];
+      ++nnz;
+    }
+    row_ptr[br + 1] = (int32_t)nnz;
+  }
+  if (row_order) {
+    /* stable insertion sort by count descending */
+    for (int64_t r = 0; r < nbr; ++r) {
+      int32_t cnt = row_ptr[r + 1] - row_ptr[r];
+      int64_t p = r;
+      while (p > 0) {
+        int32_t q = row_order[p - 1];
+        if (row_ptr[q + 1] - row_ptr[q] >= cnt) break;
+        row_order[p] = q;
+        --p;
+      }
+      row_order[p] = (int32_t)r;
+    }
+  }
+  return nnz;
+}
+
+/* Inverse of oracle_pack: dense rows x cols matrix of bf16 bit patterns, zero
+ * (bit pattern 0) outside stored blocks. */
+void oracle_unpack(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr, const int32_t* col_idx,
+                   const uint16_t* vals, uint16_t* Wd /* [rows][cols] */) {
+  int64_t nbr = rows / b;
+  memset(Wd, 0, sizeof(uint16_t) * (size_t)rows * (size_t)cols);
+  for (int64_t br = 0; br < nbr; ++br)
+    for (int64_t k = row_ptr[br]; k < row_ptr[br + 1]; ++k) {
+      int64_t bc = col_idx[k];
+      for (int32_t i = 0; i < b; ++i)
+        for (int32_t j = 0; j < b; ++j) Wd[(br * b + i) * cols + bc * b + j] = vals[(k * b + i) * b + j];
+    }
+}
+
+/* Y[i][t] = sum_k Wd[i][k] * X(k,t), fp64, k ascending.  X element (k,t) lives at
+ * X[k*sxk + t*sxt].  Y is [rows][T] row-major fp64. */
+static void dense_matmul_bf16(const uint16_t* Wd, int64_t rows, int64_t cols, const uint16_t* X, int64_t sxk,
+                              int64_t sxt, int64_t T, double* Y) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t t = 0; t < T; ++t) {
+      double s = 0.0;
+      for (int64_t k = 0; k < cols; ++k) s += bf16_to_f64(Wd[i * cols + k]) * bf16_to_f64(X[k * sxk + t * sxt]);
+      Y[i * T + t] = s;
+    }
+}
+
+/* Sec. 3.4: block-sparse Y = W X, as the dense masked product. */
+void oracle_spmm(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr, const int32_t* col_idx,
+                 const uint16_t* vals, const uint16_t* X, int64_t sxk, int64_t sxt, int64_t T,
+                 double* Y /* [rows][T] */) {
+  uint16_t* Wd = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)rows * (size_t)cols);
+  oracle_unpack(rows, cols, b, row_ptr, col_idx, vals, Wd);
+  dense_matmul_bf16(Wd, rows, cols, X, sxk, sxt, T, Y);
+  free(Wd);
+}
+
+/* The same contraction with fp32 accumulators: bounds what fp32 accumulation
+ * (the device's precision) can cost relative to the fp64 result. */
+void oracle_spmm_f32acc(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr, const int32_t* col_idx,
+                        const uint16_t* vals, const uint16_t* X, int64_t sxk, int64_t sxt, int64_t T,
+                        double* Y /* [rows][T] */) {
+  uint16_t* Wd = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)rows * (size_t)cols);
+  oracle_unpack(rows, cols, b, row_ptr, col_idx, vals, Wd);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t t = 0; t < T; ++t) {
+      float s = 0.0f;
+      for (int64_t k = 0; k < cols; ++k)
+        s += (float)bf16_to_f64(Wd[i * cols + k]) * (float)bf16_to_f64(X[k * sxk + t * sxt]);
+      Y[i * T + t] = (double)s;
+    }
+  free(Wd);
+}
+
+/* activation codes: 0 = SiLU (x * sigmoid(x)), 1 = GELU (erf form), 2 = ReLU */
+double oracle_act(int32_t act, double g) {
+  switch (act) {
+    case 0: return g / (1.0 + exp(-g));
+    case 1: return 0.5 * g * (1.0 + erf(g / sqrt(2.0)));
+    case 2: return g > 0.0 ? g : 0.0;
+    default: return NAN;
+  }
+}
+
+/* Eq. (1) with weights stored out x in:  G = W~g X, U = W~u X, H = bf16(act(G) * U),
+ * Y = W~d H.  E = hidden, I = intermediate.  gate/up are I x E, down is E x I.
+ * H_bits (may be NULL) receives the rounded intermediate, [I][T]. */
+void oracle_mlp(int64_t E, int64_t I, int32_t b,
+                const int32_t* g_row_ptr, const int32_t* g_col_idx, const uint16_t* g_vals,
+                const int32_t* u_row_ptr, const int32_t* u_col_idx, const uint16_t* u_vals,
+                const int32_t* d_row_ptr, const int32_t* d_col_idx, const uint16_t* d_vals,
+                const uint16_t* X, int64_t sxk, int64_t sxt, int64_t T, int32_t act,
+                double* Y /* [E][T] */, uint16_t* H_bits /* [I][T] or NULL */) {
+  size_t it = (size_t)I * (size_t)T;
+  double* G = (double*)malloc(sizeof(double) * (it ? it : 1));
+  double* U = (double*)malloc(sizeof(double) * (it ? it : 1));
+  uint16_t* H = (uint16_t*)malloc(sizeof(uint16_t) * (it ? it : 1));
+  oracle_spmm(I, E, b, g_row_ptr, g_col_idx, g_vals, X, sxk, sxt, T, G);
+  oracle_spmm(I, E, b, u_row_ptr, u_col_idx, u_vals, X, sxk, sxt, T, U);
+  for (size_t p = 0; p < it; ++p) {
+    double h = oracle_act(act, G[p]) * U[p];
+    H[p] = f32_to_bf16_rne((float)h); /* fp64 -> fp32 (RNE) -> bf16 (RNE) */
+  }
+  /* H is [I][T] row-major: element (k = i, t) at H[i*T + t] */
+  oracle_spmm(E, I, b, d_row_ptr, d_col_idx, d_vals, H, T, 1, T, Y);
+  if (H_bits) memcpy(H_bits, H, sizeof(uint16_t) * it);
+  free(G);
+  free(U);
+  free(H);
+}

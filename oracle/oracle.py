@@ -1,0 +1,163 @@
+"""ctypes front-end of the C oracle (oracle/blast_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: used by tests/, the smoke check and the benchmark's
+cpu_baseline leg.  The product path never imports this module.
+
+Conventions: weights are `out x in` row-major bf16 bit patterns (uint16);
+X is passed as a logical K x T matrix through element strides; results are
+fp64 arrays of logical shape [rows, T].
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(_build.build())
+        i64, i32, dbl, vp = C.c_int64, C.c_int32, C.c_double, C.c_void_p
+        L.oracle_num_threads.restype = C.c_int
+        L.oracle_n_keep.restype = i64
+        L.oracle_n_keep.argtypes = [i64, dbl]
+        L.oracle_block_scores.restype = None
+        L.oracle_block_scores.argtypes = [vp, i64, i64, i64, i32, vp]
+        L.oracle_topk_mask.restype = i64
+        L.oracle_topk_mask.argtypes = [vp, i64, dbl, vp, vp]
+        L.oracle_pack.restype = i64
+        L.oracle_pack.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, vp, vp]
+        L.oracle_unpack.restype = None
+        L.oracle_unpack.argtypes = [i64, i64, i32, vp, vp, vp, vp]
+        for name in ("oracle_spmm", "oracle_spmm_f32acc"):
+            f = getattr(L, name)
+            f.restype = None
+            f.argtypes = [i64, i64, i32, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.oracle_act.restype = dbl
+        L.oracle_act.argtypes = [i32, dbl]
+        L.oracle_mlp.restype = None
+        L.oracle_mlp.argtypes = [i64, i64, i32] + [vp] * 9 + [vp, i64, i64, i64, i32, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def n_keep(n_blocks: int, sparsity: float) -> int:
+    return int(lib().oracle_n_keep(n_blocks, float(sparsity)))
+
+
+def block_scores(W: np.ndarray, b: int) -> np.ndarray:
+    W = np.ascontiguousarray(W, dtype=np.uint16)
+    rows, cols = W.shape
+    assert rows % b == 0 and cols % b == 0
+    score = np.empty((rows // b, cols // b), dtype=np.float64)
+    lib().oracle_block_scores(_p(W), cols, rows, cols, b, _p(score))
+    return score
+
+
+def topk_mask(score: np.ndarray, sparsity: float) -> Tuple[np.ndarray, float]:
+    score = np.ascontiguousarray(score, dtype=np.float64)
+    mask = np.empty(score.shape, dtype=np.uint8)
+    gap = C.c_double(0.0)
+    lib().oracle_topk_mask(_p(score), score.size, float(sparsity), _p(mask), C.byref(gap))
+    return mask, float(gap.value)
+
+
+@dataclass
+class Bsr:
+    rows: int
+    cols: int
+    b: int
+    row_ptr: np.ndarray  # int32 [rows/b + 1]
+    col_idx: np.ndarray  # int32 [nnz]
+    vals: np.ndarray  # uint16 [nnz, b, b]
+    row_order: np.ndarray  # int32 [rows/b]
+
+    @property
+    def nnz(self) -> int:
+        return int(self.col_idx.size)
+
+
+def pack(W: np.ndarray, b: int, mask: np.ndarray) -> Bsr:
+    W = np.ascontiguousarray(W, dtype=np.uint16)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    rows, cols = W.shape
+    nbr, nbc = rows // b, cols // b
+    assert mask.shape == (nbr, nbc)
+    nnz = int(np.count_nonzero(mask))
+    row_ptr = np.empty(nbr + 1, dtype=np.int32)
+    col_idx = np.empty(nnz, dtype=np.int32)
+    vals = np.empty((nnz, b, b), dtype=np.uint16)
+    row_order = np.empty(nbr, dtype=np.int32)
+    got = lib().oracle_pack(_p(W), cols, rows, cols, b, _p(mask), _p(row_ptr), _p(col_idx), _p(vals), _p(row_order))
+    assert got == nnz
+    return Bsr(rows, cols, b, row_ptr, col_idx, vals, row_order)
+
+
+def pack_topk(W: np.ndarray, b: int, sparsity: float) -> Tuple[Bsr, np.ndarray, float]:
+    mask, gap = topk_mask(block_scores(W, b), sparsity)
+    return pack(W, b, mask), mask, gap
+
+
+def unpack(m: Bsr) -> np.ndarray:
+    Wd = np.empty((m.rows, m.cols), dtype=np.uint16)
+    lib().oracle_unpack(m.rows, m.cols, m.b, _p(m.row_ptr), _p(m.col_idx), _p(m.vals), _p(Wd))
+    return Wd
+
+
+def _x_strides(X: np.ndarray, layout: str) -> Tuple[int, int, int, int]:
+    """X as logical K x T.  layout 'token_major': X is [T, K]; 'feature_major': X is [K, T]."""
+    assert X.dtype == np.uint16 and X.ndim == 2 and X.flags.c_contiguous
+    if layout == "token_major":
+        T, K = X.shape
+        return K, T, 1, K
+    if layout == "feature_major":
+        K, T = X.shape
+        return K, T, T, 1
+    raise ValueError(layout)
+
+
+def spmm(m: Bsr, X: np.ndarray, layout: str = "token_major", f32acc: bool = False) -> np.ndarray:
+    """Returns Y as fp64 [rows, T]."""
+    K, T, sxk, sxt = _x_strides(X, layout)
+    assert K == m.cols
+    Y = np.zeros((m.rows, T), dtype=np.float64)
+    fn = lib().oracle_spmm_f32acc if f32acc else lib().oracle_spmm
+    fn(m.rows, m.cols, m.b, _p(m.row_ptr), _p(m.col_idx), _p(m.vals), _p(X), sxk, sxt, T, _p(Y))
+    return Y
+
+
+ACT = {"silu": 0, "gelu": 1, "relu": 2}
+
+
+def act(name: str, g: float) -> float:
+    return float(lib().oracle_act(ACT[name], float(g)))
+
+
+def mlp(gate: Bsr, up: Bsr, down: Bsr, X: np.ndarray, layout: str = "token_major", activation: str = "silu",
+        return_h: bool = False):
+    """Returns Y as fp64 [E, T] (and H bf16 bits [I, T] if asked)."""
+    K, T, sxk, sxt = _x_strides(X, layout)
+    E, I, b = gate.cols, gate.rows, gate.b
+    assert K == E and up.rows == I and up.cols == E and down.rows == E and down.cols == I
+    assert up.b == b and down.b == b
+    Y = np.zeros((E, T), dtype=np.float64)
+    H = np.zeros((I, T), dtype=np.uint16) if return_h else None
+    lib().oracle_mlp(E, I, b, _p(gate.row_ptr), _p(gate.col_idx), _p(gate.vals), _p(up.row_ptr), _p(up.col_idx),
+                     _p(up.vals), _p(down.row_ptr), _p(down.col_idx), _p(down.vals), _p(X), sxk, sxt, T,
+                     ACT[activation], _p(Y), _p(H))
+    return (Y, H) if return_h else Y

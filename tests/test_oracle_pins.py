@@ -1,0 +1,356 @@
+"""Pins for the CPU oracle: every check compares the oracle with something that
+is NOT the oracle (a library routine, a closed form, an exact brute force in
+rational arithmetic, an invariant of the mathematics).  No GPU needed."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+from oracle import oracle as orc
+from paper_2507_03117_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def f64(bits):
+    return synth.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def expand(mask, b):
+    return np.kron(mask, np.ones((b, b), dtype=mask.dtype))
+
+
+# ---------------------------------------------------------------- drop counts (ceil reading)
+@pytest.mark.parametrize("n,s,keep", [
+    (4096, 0.90, 409), (6144, 0.70, 1843), (6144, 0.80, 1228), (6144, 0.90, 614), (6144, 0.95, 307),
+    (3584, 0.95, 179), (53248, 0.95, 2662), (10, 0.0, 10), (10, 1.0, 0), (7, 0.5, 3), (3, 0.34, 1),
+])
+def test_n_keep_table(n, s, keep):
+    # closed form: n_keep = n - ceil(s*n) with s in exact basis points
+    assert orc.n_keep(n, s) == keep
+    assert keep == n - math.ceil(Fraction(round(s * 10000), 10000) * n)
+    assert synth.n_zero_blocks(n, s) == n - keep
+
+
+# ---------------------------------------------------------------- block scores
+def test_scores_closed_forms():
+    b = 4
+    W = np.zeros((8, 12), dtype=np.float32)
+    W[:4, :4] = 1.0  # score b*b
+    W[:4, 4:8] = np.arange(16).reshape(4, 4)  # sum k^2 = 1240
+    W[4:, 8:] = -0.5  # 16 * 0.25
+    W[4, 0] = 3.0  # single entry
+    s = orc.block_scores(synth.f32_to_bf16_bits(W), b)
+    assert s.tolist() == [[16.0, 1240.0, 0.0], [9.0, 0.0, 4.0]]
+
+
+def test_scores_match_numpy_and_expectation():
+    rng = np.random.default_rng(1)
+    Wb = synth.gauss_bf16(rng, (256, 384), 0.02)
+    b = 32
+    s = orc.block_scores(Wb, b)
+    ref = (f64(Wb) ** 2).reshape(8, b, 12, b).sum(axis=(1, 3))
+    np.testing.assert_allclose(s, ref, rtol=1e-13)
+    # E[score] = b^2 * sigma^2
+    assert abs(s.mean() / (b * b * 0.02 ** 2) - 1.0) < 0.03
+
+
+# ---------------------------------------------------------------- top-k selection
+def test_topk_equals_python_full_sort_and_threshold_property():
+    rng = np.random.default_rng(2)
+    score = rng.random((16, 24))
+    score[3, 5] = score[7, 7] = score[0, 1]  # exact ties
+    for s in (0.0, 0.3, 0.5, 0.9, 0.95, 1.0):
+        mask, gap = orc.topk_mask(score, s)
+        n = score.size
+        keep = n - math.ceil(Fraction(round(s * 10000), 10000) * n)
+        assert int(mask.sum()) == keep
+        flat = score.ravel()
+        order = sorted(range(n), key=lambda i: (-flat[i], i))
+        ref = np.zeros(n, dtype=np.uint8)
+        ref[order[:keep]] = 1
+        assert np.array_equal(mask.ravel(), ref)
+        if 0 < keep < n:
+            assert flat[mask.ravel() == 1].min() >= flat[mask.ravel() == 0].max()
+
+
+def test_topk_tie_break_prefers_lower_index():
+    score = np.zeros((2, 4))  # all tied (e.g. all-zero blocks)
+    mask, _ = orc.topk_mask(score, 0.5)
+    assert mask.ravel().tolist() == [1, 1, 1, 1, 0, 0, 0, 0]
+    score = np.array([[1.0, 5.0, 1.0, 1.0]])
+    mask, _ = orc.topk_mask(score, 0.5)
+    assert mask.ravel().tolist() == [1, 1, 0, 0]
+
+
+def test_topk_gap_reported():
+    score = np.array([[4.0, 3.0, 2.0, 1.0]])
+    _, gap = orc.topk_mask(score, 0.5)
+    assert gap == pytest.approx((3.0 - 2.0) / 3.0)
+
+
+# ---------------------------------------------------------------- packing
+@pytest.mark.parametrize("b", [1, 2, 16, 32])
+def test_pack_roundtrip_and_scipy_indices(b):
+    rng = np.random.default_rng(10 + b)
+    rows, cols = 8 * b, 12 * b
+    Wb = synth.gauss_bf16(rng, (rows, cols), 0.02)
+    Wb[Wb == 0] = 0x3C00  # no exact zeros, so scipy's structure equals the mask
+    Wb[Wb == 0x8000] = 0x3C00
+    mask = synth.uniform_mask(rng, 8, 12, 0.7)
+    mask[2, :] = 0  # an empty block row
+    m = orc.pack(Wb, b, mask)
+    # invariants
+    assert m.row_ptr[0] == 0 and m.row_ptr[-1] == m.nnz == int(mask.sum())
+    assert np.all(np.diff(m.row_ptr) >= 0)
+    for r in range(8):
+        c = m.col_idx[m.row_ptr[r]:m.row_ptr[r + 1]]
+        assert np.all(np.diff(c) > 0) and np.all(c < 12) and np.all(c >= 0)
+        assert np.array_equal(c, np.nonzero(mask[r])[0])
+    # round trip bit-for-bit
+    Wm = Wb * expand(mask, b).astype(np.uint16)
+    assert np.array_equal(orc.unpack(m), Wm)
+    # library routine
+    dense = f64(Wm)
+    if b == 1:
+        ref = sp.csr_matrix(dense)
+    else:
+        ref = sp.bsr_matrix(dense, blocksize=(b, b))
+    ref.sort_indices()
+    assert np.array_equal(ref.indptr, m.row_ptr)
+    assert np.array_equal(ref.indices, m.col_idx)
+    if b > 1:
+        assert np.array_equal(ref.data, f64(m.vals))  # blocks row-major, same order
+    # schedule: stable sort by count, descending
+    cnt = np.diff(m.row_ptr)
+    assert np.array_equal(m.row_order, np.argsort(-cnt, kind="stable"))
+    assert cnt[m.row_order[-1]] == 0
+
+
+def test_pack_keeps_all_zero_block():
+    b = 2
+    W = np.zeros((4, 4), dtype=np.uint16)
+    mask = np.array([[1, 0], [0, 1]], dtype=np.uint8)
+    m = orc.pack(W, b, mask)
+    assert m.nnz == 2 and m.col_idx.tolist() == [0, 1] and m.row_ptr.tolist() == [0, 1, 2]
+
+
+def test_full_and_empty_masks():
+    rng = np.random.default_rng(3)
+    b = 4
+    Wb = synth.gauss_bf16(rng, (16, 8), 0.02)
+    Xb = synth.gauss_bf16(rng, (5, 8), 1.0)
+    full, _, _ = orc.pack_topk(Wb, b, 0.0)
+    assert full.nnz == 8 and np.array_equal(orc.unpack(full), Wb)
+    Y = orc.spmm(full, Xb)
+    np.testing.assert_allclose(Y, f64(Wb) @ f64(Xb).T, rtol=1e-12, atol=1e-300)
+    empty, _, _ = orc.pack_topk(Wb, b, 1.0)
+    assert empty.nnz == 0 and not empty.row_ptr.any()
+    assert not orc.spmm(empty, Xb).any()
+
+
+# ---------------------------------------------------------------- SpMM
+def test_spmm_dense_case_equals_numpy_both_layouts():
+    rng = np.random.default_rng(4)
+    b = 16
+    Wb = synth.gauss_bf16(rng, (64, 96), 0.02)
+    Xb = synth.gauss_bf16(rng, (7, 96), 1.0)  # token-major [T, K]
+    mask = synth.uniform_mask(rng, 4, 6, 0.5)
+    m = orc.pack(Wb, b, mask)
+    ref = (f64(Wb) * expand(mask, b)) @ f64(Xb).T
+    np.testing.assert_allclose(orc.spmm(m, Xb, "token_major"), ref, rtol=1e-12, atol=1e-15)
+    Xf = np.ascontiguousarray(Xb.T)  # feature-major [K, T]
+    np.testing.assert_allclose(orc.spmm(m, Xf, "feature_major"), ref, rtol=1e-12, atol=1e-15)
+
+
+def _brute_spmm(Wi, mask, b, Xi):
+    """Exact rational evaluation, written independently (pure Python)."""
+    M, K = len(Wi), len(Wi[0])
+    T = len(Xi[0])
+    Y = [[Fraction(0)] * T for _ in range(M)]
+    for i in range(M):
+        for k in range(K):
+            if mask[i // b][k // b]:
+                for t in range(T):
+                    Y[i][t] += Fraction(Wi[i][k]) * Fraction(Xi[k][t])
+    return Y
+
+
+@pytest.mark.parametrize("M,K,b,T,seed", [(2, 2, 1, 1, 0), (4, 6, 2, 3, 1), (8, 4, 4, 2, 2), (6, 8, 2, 1, 3), (8, 8, 4, 3, 4)])
+def test_spmm_brute_force_exact(M, K, b, T, seed):
+    rng = np.random.default_rng(seed)
+    Wi = rng.integers(-8, 9, size=(M, K))  # small integers are exact in bf16
+    Xi = rng.integers(-8, 9, size=(K, T))
+    mask = (rng.random((M // b, K // b)) < 0.6).astype(np.uint8)
+    m = orc.pack(synth.f32_to_bf16_bits(Wi.astype(np.float32)), b, mask)
+    Xf = synth.f32_to_bf16_bits(Xi.astype(np.float32))  # feature-major [K, T]
+    Y = orc.spmm(m, Xf, "feature_major")
+    ref = _brute_spmm(Wi.tolist(), mask.tolist(), b, Xi.tolist())
+    for i in range(M):
+        for t in range(T):
+            assert Fraction(Y[i, t]) == ref[i][t]
+
+
+def test_token_independence_bitwise():
+    w, mask, x = synth.small_case(5, 64, 96, 16, 0.6, 9)
+    m = orc.pack(w, 16, mask)
+    full = orc.spmm(m, x)
+    cols = [7, 0, 3]
+    sub = orc.spmm(m, np.ascontiguousarray(x[cols]))
+    assert np.array_equal(full[:, cols], sub)
+
+
+def test_transpose_symmetry():
+    # Sec. 3.4.1: Y = XW and Y = WX are the same kernel mirrored.
+    w, mask, x = synth.small_case(6, 48, 80, 16, 0.5, 5)
+    m = orc.pack(w, 16, mask)
+    Y = orc.spmm(m, x)  # [rows, T]
+    Wt = (f64(w) * expand(mask, 16)).T  # paper's orientation: in x out
+    np.testing.assert_allclose(Y.T, f64(x) @ Wt, rtol=1e-12, atol=1e-15)
+    # BSR(W) <-> BCSC(W^T): scipy's BSC-like view via transpose
+    csc = sp.bsr_matrix(Wt.T, blocksize=(16, 16))
+    csc.sort_indices()
+    assert np.array_equal(csc.indptr, m.row_ptr) and np.array_equal(csc.indices, m.col_idx)
+
+
+def test_linearity_identity_permutation():
+    rng = np.random.default_rng(7)
+    b = 8
+    w, mask, x1 = synth.small_case(7, 32, 48, b, 0.5, 4)
+    x2 = synth.gauss_bf16(rng, x1.shape, 1.0)
+    m = orc.pack(w, b, mask)
+    # linearity in X needs exactly representable sums: use x2 := 2 * x1 (exact in bf16) and a zero
+    x_twice = synth.f32_to_bf16_bits(2.0 * synth.bf16_bits_to_f32(x1))
+    np.testing.assert_allclose(orc.spmm(m, x_twice), 2.0 * orc.spmm(m, x1), rtol=1e-15)
+    # additivity in W over disjoint masks
+    mask_a = mask.copy()
+    mask_a[:, ::2] = 0
+    mask_b = mask - mask_a
+    ya = orc.spmm(orc.pack(w, b, mask_a), x2)
+    yb = orc.spmm(orc.pack(w, b, mask_b), x2)
+    np.testing.assert_allclose(ya + yb, orc.spmm(m, x2), rtol=1e-12, atol=1e-15)
+    # block-diagonal identity copies X
+    n = 32
+    eye = synth.f32_to_bf16_bits(np.eye(n, dtype=np.float32))
+    xe = synth.gauss_bf16(rng, (5, n), 1.0)
+    me = orc.pack(eye, b, np.eye(n // b, dtype=np.uint8))
+    assert np.array_equal(orc.spmm(me, xe), f64(xe).T)
+    # permuting block columns of W with the matching row blocks of X leaves Y unchanged
+    perm = rng.permutation(48 // b)
+    idx = (perm[:, None] * b + np.arange(b)[None, :]).ravel()
+    mp = orc.pack(np.ascontiguousarray(w[:, idx]), b, np.ascontiguousarray(mask[:, perm]))
+    np.testing.assert_allclose(orc.spmm(mp, np.ascontiguousarray(x2[:, idx])), orc.spmm(m, x2), rtol=1e-12, atol=1e-15)
+
+
+def test_spmm_statistics_config1_shape():
+    # RMS(Y) ~ sigma_w * sqrt(b * mean blocks per row) for unit-variance X
+    wl = synth.WORKLOADS["linear_1024x4096_b32_s90"]
+    lin = synth.make_linear(wl)
+    x = synth.make_x(wl, 8)
+    m = orc.pack(lin.W, wl.b, lin.mask)
+    assert m.nnz == 409
+    Y = orc.spmm(m, x)
+    rms = math.sqrt(float((Y ** 2).mean()))
+    assert abs(rms / (0.02 * math.sqrt(32 * 409 / 32)) - 1.0) < 0.05
+
+
+def test_f32_accumulation_bound():
+    w, mask, x = synth.small_case(8, 128, 1024, 32, 0.5, 6)
+    m = orc.pack(w, 32, mask)
+    y64 = orc.spmm(m, x)
+    y32 = orc.spmm(m, x, f32acc=True)
+    rel = np.linalg.norm(y32 - y64) / np.linalg.norm(y64)
+    assert 0 < rel < 1e-5
+
+
+# ---------------------------------------------------------------- activations and the MLP
+def test_activation_golden_values():
+    for line in open(os.path.join(GOLDEN, "activation_values.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, x, v = line.split()
+        assert orc.act(name, float(x)) == pytest.approx(float(v), rel=1e-14, abs=1e-300)
+    # global minimum of SiLU
+    xs = np.linspace(-3, 0, 30001)
+    vals = np.array([orc.act("silu", float(t)) for t in xs])
+    assert abs(xs[vals.argmin()] + 1.27846) < 2e-4 and abs(vals.min() + 0.27846) < 1e-5
+
+
+def _np_mlp(wg, wu, wd, xb, act):
+    X = f64(xb).T  # [E, T]
+    G, U = wg @ X, wu @ X
+    if act == "silu":
+        a = G / (1.0 + np.exp(-G))
+    elif act == "gelu":
+        a = 0.5 * G * (1.0 + np.vectorize(math.erf)(G / math.sqrt(2.0)))
+    else:
+        a = np.maximum(G, 0.0)
+    H = f64(synth.f32_to_bf16_bits((a * U).astype(np.float32)))
+    return wd @ H, H
+
+
+@pytest.mark.parametrize("act", ["silu", "gelu", "relu"])
+def test_mlp_equals_numpy_dense_formula(act):
+    rng = np.random.default_rng(11)
+    E, I, b, T = 64, 128, 16, 6
+    g, u, d = (synth.gauss_bf16(rng, s, 0.2) for s in ((I, E), (I, E), (E, I)))
+    mg, mu, md = (synth.uniform_mask(rng, *s, 0.5) for s in ((I // b, E // b), (I // b, E // b), (E // b, I // b)))
+    mg[1, :] = 0  # empty gate row -> H row zero
+    xb = synth.gauss_bf16(rng, (T, E), 1.0)
+    pg, pu, pd = orc.pack(g, b, mg), orc.pack(u, b, mu), orc.pack(d, b, md)
+    Y, H = orc.mlp(pg, pu, pd, xb, activation=act, return_h=True)
+    Yref, Href = _np_mlp(f64(g) * expand(mg, b), f64(u) * expand(mu, b), f64(d) * expand(md, b), xb, act)
+    # H may differ from numpy's only where exp/erf differ in the last ulp before rounding: allow none here
+    assert np.array_equal(f64(H), Href)
+    np.testing.assert_allclose(Y, Yref, rtol=1e-12, atol=1e-15)
+    assert not f64(H)[b:2 * b].any()
+    # feature-major input gives the same result
+    Y2 = orc.mlp(pg, pu, pd, np.ascontiguousarray(xb.T), layout="feature_major", activation=act)
+    assert np.array_equal(Y, Y2)
+
+
+def test_mlp_special_cases():
+    rng = np.random.default_rng(12)
+    n, b, T = 32, 8, 5
+    eye = synth.f32_to_bf16_bits(np.eye(n, dtype=np.float32))
+    diag = np.eye(n // b, dtype=np.uint8)
+    pe = orc.pack(eye, b, diag)
+    xb = synth.gauss_bf16(rng, (T, n), 1.0)
+    x = f64(xb).T
+    # identity weights: Y = bf16(silu(x) * x)
+    Y = orc.mlp(pe, pe, pe, xb)
+    ref = f64(synth.f32_to_bf16_bits((x / (1 + np.exp(-x)) * x).astype(np.float32)))
+    assert np.array_equal(Y, ref)
+    # zero gate or zero X => zero output
+    zero = orc.pack(np.zeros((n, n), dtype=np.uint16), b, diag)
+    assert not orc.mlp(zero, pe, pe, xb).any()
+    assert not orc.mlp(pe, pe, pe, np.zeros_like(xb)).any()
+
+
+def test_h_rounding_is_nearest_even():
+    # identity MLP turns H = bf16(silu(x) * x) into the output, so the rounding is observable.
+    # relu: H = bf16(x * x); choose x with x*x exactly half-way between two bf16 values.
+    n, b = 8, 8
+    eye = synth.f32_to_bf16_bits(np.eye(n, dtype=np.float32))
+    pe = orc.pack(eye, b, np.ones((1, 1), dtype=np.uint8))
+    # x = 1 + 2^-4 -> x^2 = 1 + 2^-3 + 2^-8 : tie between 1+2^-3 (even mantissa 0x10) and 1+2^-3+2^-7 -> even wins
+    # x = 1 + 2^-4 + 2^-5 -> x^2 = 1 + 2^-3 + 2^-4 + 2^-8*(1 + 2 + ... ) computed exactly below
+    xs = np.array([1 + 2 ** -4, 1 + 3 * 2 ** -5, 1.5, 1 + 2 ** -7], dtype=np.float32)
+    xb = np.zeros((1, n), dtype=np.uint16)
+    xb[0, :4] = synth.f32_to_bf16_bits(xs)
+    Y = orc.mlp(pe, pe, pe, xb, activation="relu")[:, 0]
+    for j, xv in enumerate(xs.tolist()):
+        sq = Fraction(xv) ** 2
+        ulp = Fraction(2) ** (math.floor(math.log2(sq)) - 7)
+        lo = (sq // ulp) * ulp
+        hi = lo + ulp
+        if sq - lo < hi - sq:
+            want = lo
+        elif sq - lo > hi - sq:
+            want = hi
+        else:
+            want = lo if (lo / ulp) % 2 == 0 else hi
+        assert Fraction(Y[j]) == want, (j, xv)
