@@ -1,0 +1,179 @@
+/*
+ * blast.h -- C ABI of the MI355X (gfx950) block-sparse MLP library.
+ *
+ * The library implements the hot path of BLaST (arxiv 2507.03117): block-norm
+ * pruning + packing of a weight matrix into a block-compressed format
+ * (Sec. 3.2, Sec. 3.4.1), the block-sparse matrix product built on it
+ * (Sec. 3.4, Listing 2) and the fused block-sparse SwiGLU MLP (Eq. (1),
+ * Sec. 3.4.3).
+ *
+ * Conventions
+ *  - Weights are `out x in`, row-major, like a linear layer's weight: W is
+ *    rows x cols and the product is Y = W * X with X: cols x T, Y: rows x T.
+ *    The paper writes Y = X W with W `in x out` stored BCSC; BSR of the
+ *    `out x in` matrix is the same object (each block transposed), and the
+ *    paper notes the two orientations are mirror images (Sec. 3.4.1).
+ *  - bf16 values travel as uint16_t bit patterns.
+ *  - Unless a parameter says HOST, every pointer is a DEVICE pointer into memory
+ *    owned by the caller.  The library never allocates or frees device memory,
+ *    keeps no global state, and only enqueues work on the given stream
+ *    (`stream` is a hipStream_t passed as void*; NULL = the default stream).
+ *  - Every call returns 0 (BLAST_OK) or a negative error code.  When an error is
+ *    returned nothing has been enqueued, except where stated for
+ *    BLAST_ERR_CAPACITY and BLAST_ERR_HIP.
+ *  - Buffers must stay alive and unmodified until the stream has executed the
+ *    enqueued work.  Calls on distinct streams may run concurrently from
+ *    different host threads as long as their output/workspace buffers differ.
+ */
+#ifndef BLAST_H_
+#define BLAST_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- error codes ------------------------------------------------------- */
+#define BLAST_OK 0
+#define BLAST_ERR_INVALID_ARG (-1)       /* null pointer, negative size, ld too small, bad enum, misalignment */
+#define BLAST_ERR_SHAPE (-2)             /* rows/cols not a multiple of b; MLP matrices inconsistent */
+#define BLAST_ERR_UNSUPPORTED_BLOCK (-3) /* block size outside {16, 32, 64, 128} */
+#define BLAST_ERR_CAPACITY (-4)          /* nnz_cap smaller than the number of kept blocks */
+#define BLAST_ERR_WORKSPACE (-5)         /* workspace / aux buffer missing or too small */
+#define BLAST_ERR_HIP (-6)               /* HIP runtime error; text via blast_strerror */
+
+/* ---- enums -------------------------------------------------------------- */
+#define BLAST_PACK_MASK 0           /* keep exactly the blocks flagged in block_mask */
+#define BLAST_PACK_TOPK_FROBENIUS 1 /* keep the highest-Frobenius-norm blocks (Sec. 3.2) */
+
+#define BLAST_TOKEN_MAJOR 0   /* element (k, t) at X[t*ld + k]: the [tokens, features] activation tensor */
+#define BLAST_FEATURE_MAJOR 1 /* element (k, t) at X[k*ld + t] */
+
+#define BLAST_F32 0
+#define BLAST_BF16 1
+
+#define BLAST_ACT_SILU 0 /* x * sigmoid(x), Eq. (1) */
+#define BLAST_ACT_GELU 1 /* x/2 * (1 + erf(x / sqrt 2)) */
+#define BLAST_ACT_RELU 2
+
+/*
+ * Packed block-sparse matrix (Sec. 3.2: the pruned weight W_new in block
+ * compressed form; Sec. 3.4.1).  A plain view: all arrays are caller-owned
+ * device memory; the struct itself is host memory and is read at call time.
+ */
+typedef struct blast_bsr_view {
+  int64_t rows, cols;       /* logical size; both multiples of b */
+  int32_t b;                /* block edge: 16, 32, 64 or 128 */
+  int32_t reserved;         /* set to 0 */
+  int64_t nnz;              /* number of stored blocks */
+  const int32_t* row_ptr;   /* [rows/b + 1], row_ptr[0] = 0, non-decreasing, row_ptr[rows/b] = nnz */
+  const int32_t* col_idx;   /* [nnz], block-column of each stored block, strictly ascending inside a block row */
+  const uint16_t* vals;     /* [nnz * b * b] bf16, block k occupies vals[k*b*b ..], row-major inside the block;
+                               must be 16-byte aligned */
+  const int32_t* row_order; /* [rows/b] block rows by stored-block count, descending (schedule); may be NULL */
+  const void* aux;          /* column-grouped index written by blast_bsr_pack (blast_bsr_aux_bytes bytes);
+                               may be NULL for blast_bsr_spmm; blast_sparse_mlp needs it on W_down only
+                               when it reports so through BLAST_ERR_WORKSPACE (see there) */
+} blast_bsr_view;
+
+/* Human-readable text for an error code.  For BLAST_ERR_HIP the text of the
+ * last HIP error seen by the calling thread is appended.  Never NULL. */
+const char* blast_strerror(int code);
+
+/* Number of blocks kept for a target sparsity over n_blocks blocks (Sec. 3.2:
+ * "drop the lowest scoring blocks until sparsity s is reached"): the drop count
+ * is ceil(s * n_blocks) with s taken in basis points, s_bp = round(s * 1e4),
+ * n_zero = ceil(s_bp * n_blocks / 1e4).  Returns -1 if sparsity is outside [0, 1]
+ * or n_blocks < 0.  Pure host arithmetic. */
+int64_t blast_n_keep(int64_t n_blocks, double sparsity);
+
+/* Bytes of the `aux` buffer for a matrix with the given block grid and capacity. */
+size_t blast_bsr_aux_bytes(int64_t rows, int64_t cols, int32_t b, int64_t nnz_cap);
+
+/*
+ * Sizes needed by blast_bsr_pack (all outputs HOST pointers, any may be NULL).
+ *   nnz_cap   : TOPK -> exactly blast_n_keep(); MASK -> (rows/b)*(cols/b), the upper bound
+ *               (a caller that knows its mask's population may allocate less).
+ *   aux_bytes : blast_bsr_aux_bytes() for that nnz_cap.
+ *   ws_bytes  : scratch needed during the call.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK.
+ */
+int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, double sparsity,
+                         int64_t* nnz_cap, size_t* aux_bytes, size_t* ws_bytes);
+
+/*
+ * Prune and pack a dense bf16 weight (Sec. 3.2 generate_masks() pruning half +
+ * prune_weights(); Sec. 3.4.1 storage format).
+ *
+ *   W, ldw      dense weight, element (i, j) at W[i*ldw + j]; ldw >= cols, ldw % 8 == 0, W 16-byte aligned.
+ *   mode        BLAST_PACK_MASK: block_mask [rows/b][cols/b] uint8 (nonzero = keep) is the structure;
+ *               a kept block is stored even when all its values are zero.
+ *               BLAST_PACK_TOPK_FROBENIUS: block_mask is ignored (may be NULL).  Each block is scored by
+ *               its squared Frobenius norm accumulated in fp64; the blast_n_keep() highest are kept;
+ *               equal scores are ordered by linear block index (block_row * (cols/b) + block_col), lower
+ *               first.  Weights must be finite.
+ *   sparsity    target fraction of dropped blocks in [0, 1] (TOPK only).
+ *   row_ptr     out [rows/b + 1]
+ *   col_idx     out [nnz_cap]
+ *   vals        out [nnz_cap * b * b], 16-byte aligned
+ *   row_order   out [rows/b]: stable sort of block rows by stored-block count, descending (empty rows last)
+ *   aux         out, aux_bytes >= blast_bsr_aux_bytes(rows, cols, b, nnz_cap), 16-byte aligned; may be NULL
+ *               (then no column-grouped index is produced)
+ *   nnz_out     HOST, receives the number of stored blocks (also on BLAST_ERR_CAPACITY)
+ *   ws          scratch of at least the ws_bytes reported by blast_bsr_pack_bound, 16-byte aligned
+ *
+ * The call synchronises `stream` once (to learn nnz); when it returns BLAST_OK
+ * the remaining work is enqueued, not necessarily finished.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, CAPACITY (row_ptr has
+ * been written, col_idx/vals/row_order/aux have not), HIP.
+ */
+int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
+                   const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx, uint16_t* vals,
+                   int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap, int64_t* nnz_out, void* ws,
+                   size_t ws_bytes, void* stream);
+
+/*
+ * Block-sparse product Y = W * X (Sec. 3.4, Listing 2: for every output tile,
+ * loop over the stored blocks of its block row, load the block and the matching
+ * slice of X through the index array, accumulate).  bf16 x bf16 products,
+ * fp32 accumulation.  Rows of an empty block row are written as zeros.
+ *
+ *   X, ldx, x_layout   activation, cols x T, layout per BLAST_TOKEN_MAJOR / BLAST_FEATURE_MAJOR.
+ *                      The fast path needs TOKEN_MAJOR, ldx % 8 == 0 and X 16-byte aligned; other
+ *                      inputs are handled by a slower load path with identical results.
+ *   T                  number of tokens (columns of X), >= 0; T == 0 is a no-op.
+ *   Y, ldy, y_dtype    output rows x T in the SAME layout as X; fp32 (BLAST_F32) or bf16 (BLAST_BF16,
+ *                      rounded to nearest even from the fp32 accumulator).
+ *   ws, ws_bytes       at least blast_bsr_spmm_workspace() bytes (may be 0 -> ws may be NULL).
+ * Never synchronises.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
+ */
+int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, void* Y,
+                   int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes, void* stream);
+int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_bytes /* HOST */);
+
+/*
+ * Fused block-sparse gated MLP, Eq. (1):  Y = Wdown * ( act(Wgate * X) (.) (Wup * X) ).
+ * Wgate, Wup: I x E;  Wdown: E x I;  X: E x T;  Y: E x T;  all three share one block size.
+ * G = Wgate*X and U = Wup*X are accumulated in fp32 and never rounded; H = act(G)*U is
+ * computed in fp32 and rounded ONCE to bf16 (nearest even) to enter the second product;
+ * Y is accumulated in fp32 (Sec. 3.4.3: the nonlinearity is fused into the product kernel).
+ * An empty gate or up block row gives a zero row of H; empty Wdown block rows give zero rows of Y.
+ *
+ *   act                BLAST_ACT_SILU (the paper's Eq. (1)), BLAST_ACT_GELU, BLAST_ACT_RELU.
+ *   X / Y layout       as in blast_bsr_spmm.
+ *   ws, ws_bytes       at least blast_sparse_mlp_workspace() bytes, 256-byte aligned.
+ * Never synchronises.  Errors: INVALID_ARG, SHAPE (including inconsistent I/E/b between the three
+ * matrices), UNSUPPORTED_BLOCK, WORKSPACE, HIP.
+ */
+int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
+                     const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy,
+                     int32_t y_dtype, void* ws, size_t ws_bytes, void* stream);
+int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
+                               int64_t T, size_t* ws_bytes /* HOST */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLAST_H_ */

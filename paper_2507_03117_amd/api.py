@@ -1,0 +1,204 @@
+"""Thin Python binding of the C ABI declared in include/blast.h.
+
+Argument marshalling only: torch supplies device memory and the current stream;
+every step of the path runs inside libblast_hip.so.  There is no CPU fallback:
+if the library is missing or fails to load, every entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libblast_hip.so")
+
+PACK_MASK, PACK_TOPK_FROBENIUS = 0, 1
+TOKEN_MAJOR, FEATURE_MAJOR = 0, 1
+F32, BF16 = 0, 1
+ACT = {"silu": 0, "gelu": 1, "relu": 2}
+
+EXPORTS = (
+    "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
+    "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
+)
+
+
+class BlastError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lib().blast_strerror(code).decode()} (code {code})")
+
+
+class BsrView(C.Structure):
+    _fields_ = [
+        ("rows", C.c_int64), ("cols", C.c_int64), ("b", C.c_int32), ("reserved", C.c_int32), ("nnz", C.c_int64),
+        ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("vals", C.c_void_p), ("row_order", C.c_void_p),
+        ("aux", C.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    """Load libblast_hip.so (built by paper_2507_03117_amd/build.py); raise loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2507_03117_amd.build` "
+                "(hipcc, gfx950).  There is no CPU fallback.")
+        L = C.CDLL(LIB_PATH)
+        i64, i32, dbl, vp, sz = C.c_int64, C.c_int32, C.c_double, C.c_void_p, C.c_size_t
+        pv = C.POINTER(BsrView)
+        L.blast_strerror.restype = C.c_char_p
+        L.blast_strerror.argtypes = [C.c_int]
+        L.blast_n_keep.restype = i64
+        L.blast_n_keep.argtypes = [i64, dbl]
+        L.blast_bsr_aux_bytes.restype = sz
+        L.blast_bsr_aux_bytes.argtypes = [i64, i64, i32, i64]
+        L.blast_bsr_pack_bound.restype = C.c_int
+        L.blast_bsr_pack_bound.argtypes = [i64, i64, i32, i32, dbl, C.POINTER(i64), C.POINTER(sz), C.POINTER(sz)]
+        L.blast_bsr_pack.restype = C.c_int
+        L.blast_bsr_pack.argtypes = [vp, i64, i64, i64, i32, i32, vp, dbl, vp, vp, vp, vp, vp, sz, i64,
+                                     C.POINTER(i64), vp, sz, vp]
+        L.blast_bsr_spmm.restype = C.c_int
+        L.blast_bsr_spmm.argtypes = [pv, vp, i64, i32, i64, vp, i64, i32, vp, sz, vp]
+        L.blast_bsr_spmm_workspace.restype = C.c_int
+        L.blast_bsr_spmm_workspace.argtypes = [pv, i64, C.POINTER(sz)]
+        L.blast_sparse_mlp.restype = C.c_int
+        L.blast_sparse_mlp.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
+        L.blast_sparse_mlp_workspace.restype = C.c_int
+        L.blast_sparse_mlp_workspace.argtypes = [pv, pv, pv, i64, C.POINTER(sz)]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise BlastError(rc, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def n_keep(n_blocks: int, sparsity: float) -> int:
+    return int(lib().blast_n_keep(n_blocks, float(sparsity)))
+
+
+@dataclass
+class PackedBsr:
+    """Device-resident packed matrix: tensors own the memory, `view()` is what the C ABI reads."""
+    rows: int
+    cols: int
+    b: int
+    nnz: int
+    row_ptr: torch.Tensor  # int32 [rows/b + 1]
+    col_idx: torch.Tensor  # int32 [cap]
+    vals: torch.Tensor  # int16 (bf16 bits) [cap * b * b]
+    row_order: torch.Tensor  # int32 [rows/b]
+    aux: Optional[torch.Tensor]  # uint8
+
+    def view(self) -> BsrView:
+        return BsrView(self.rows, self.cols, self.b, 0, self.nnz, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+                       self.vals.data_ptr(), self.row_order.data_ptr(),
+                       self.aux.data_ptr() if self.aux is not None else None)
+
+    def weight_bytes(self) -> int:
+        return self.nnz * self.b * self.b * 2
+
+
+def bsr_pack(W: torch.Tensor, b: int, *, mask: Optional[torch.Tensor] = None, sparsity: Optional[float] = None,
+             nnz_cap: Optional[int] = None, with_aux: bool = True) -> PackedBsr:
+    """blast_bsr_pack.  W: [rows, cols] bf16 (or int16 bit patterns) on the GPU.
+    Exactly one of `mask` (uint8 [rows/b, cols/b] on the GPU) and `sparsity` selects the mode."""
+    L = lib()
+    assert W.is_cuda and W.dim() == 2 and W.stride(1) == 1 and W.element_size() == 2
+    assert (mask is None) != (sparsity is None), "give exactly one of mask / sparsity"
+    rows, cols = W.shape
+    mode = PACK_MASK if mask is not None else PACK_TOPK_FROBENIUS
+    s = 0.0 if sparsity is None else float(sparsity)
+    cap, auxb, wsb = C.c_int64(0), C.c_size_t(0), C.c_size_t(0)
+    _check(L.blast_bsr_pack_bound(rows, cols, b, mode, s, C.byref(cap), C.byref(auxb), C.byref(wsb)),
+           "blast_bsr_pack_bound")
+    if mask is not None:
+        assert mask.is_cuda and mask.dtype == torch.uint8 and mask.is_contiguous()
+    cap_v = int(cap.value) if nnz_cap is None else int(nnz_cap)
+    aux_bytes = int(L.blast_bsr_aux_bytes(rows, cols, b, cap_v))
+    dev = W.device
+    row_ptr = torch.empty(rows // b + 1, dtype=torch.int32, device=dev)
+    col_idx = torch.empty(max(cap_v, 1), dtype=torch.int32, device=dev)
+    vals = torch.empty(max(cap_v, 1) * b * b, dtype=torch.int16, device=dev)
+    row_order = torch.empty(max(rows // b, 1), dtype=torch.int32, device=dev)
+    aux = torch.empty(max(aux_bytes, 16), dtype=torch.uint8, device=dev) if with_aux else None
+    ws = torch.empty(int(wsb.value), dtype=torch.uint8, device=dev)
+    nnz = C.c_int64(-1)
+    rc = L.blast_bsr_pack(_ptr(W), W.stride(0), rows, cols, b, mode, _ptr(mask), s, _ptr(row_ptr), _ptr(col_idx),
+                          _ptr(vals), _ptr(row_order), _ptr(aux), aux_bytes if with_aux else 0, cap_v, C.byref(nnz),
+                          _ptr(ws), ws.numel(), _stream())
+    _check(rc, "blast_bsr_pack")
+    torch.cuda.current_stream().synchronize()  # ws is released on return
+    return PackedBsr(rows, cols, b, int(nnz.value), row_ptr, col_idx, vals, row_order, aux)
+
+
+def _layout_dims(X: torch.Tensor, layout: int):
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1 and X.element_size() == 2
+    if layout == TOKEN_MAJOR:
+        return X.shape[0], X.shape[1], X.stride(0)  # T, K, ld
+    return X.shape[1], X.shape[0], X.stride(0)
+
+
+def _alloc_out(rows: int, T: int, layout: int, out_dtype: torch.dtype, dev) -> torch.Tensor:
+    shape = (T, rows) if layout == TOKEN_MAJOR else (rows, T)
+    return torch.empty(shape, dtype=out_dtype, device=dev)
+
+
+def bsr_spmm(W: PackedBsr, X: torch.Tensor, *, layout: int = TOKEN_MAJOR, out_dtype: torch.dtype = torch.float32,
+             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_bsr_spmm: Y = W * X.  X is [T, cols] (TOKEN_MAJOR) or [cols, T] (FEATURE_MAJOR), bf16."""
+    L = lib()
+    T, K, ldx = _layout_dims(X, layout)
+    assert K == W.cols
+    Y = out if out is not None else _alloc_out(W.rows, T, layout, out_dtype, X.device)
+    v = W.view()
+    wsb = C.c_size_t(0)
+    _check(L.blast_bsr_spmm_workspace(C.byref(v), T, C.byref(wsb)), "blast_bsr_spmm_workspace")
+    ws = torch.empty(int(wsb.value), dtype=torch.uint8, device=X.device) if wsb.value else None
+    _check(L.blast_bsr_spmm(C.byref(v), _ptr(X), ldx, layout, T, _ptr(Y), Y.stride(0),
+                            BF16 if Y.dtype == torch.bfloat16 else F32, _ptr(ws), int(wsb.value), _stream()),
+           "blast_bsr_spmm")
+    return Y
+
+
+def mlp_workspace_bytes(gate: PackedBsr, up: PackedBsr, down: PackedBsr, T: int) -> int:
+    vg, vu, vd = gate.view(), up.view(), down.view()
+    wsb = C.c_size_t(0)
+    _check(lib().blast_sparse_mlp_workspace(C.byref(vg), C.byref(vu), C.byref(vd), T, C.byref(wsb)),
+           "blast_sparse_mlp_workspace")
+    return int(wsb.value)
+
+
+def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor, *, layout: int = TOKEN_MAJOR,
+               act: str = "silu", out_dtype: torch.dtype = torch.float32, out: Optional[torch.Tensor] = None,
+               ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_sparse_mlp: Y = Wdown * (act(Wgate * X) (.) (Wup * X))."""
+    L = lib()
+    T, K, ldx = _layout_dims(X, layout)
+    assert K == gate.cols
+    Y = out if out is not None else _alloc_out(down.rows, T, layout, out_dtype, X.device)
+    vg, vu, vd = gate.view(), up.view(), down.view()
+    if ws is None:
+        ws = torch.empty(max(mlp_workspace_bytes(gate, up, down, T), 256), dtype=torch.uint8, device=X.device)
+    _check(L.blast_sparse_mlp(C.byref(vg), C.byref(vu), C.byref(vd), _ptr(X), ldx, layout, T, ACT[act], _ptr(Y),
+                              Y.stride(0), BF16 if Y.dtype == torch.bfloat16 else F32, _ptr(ws), ws.numel(),
+                              _stream()), "blast_sparse_mlp")
+    return Y

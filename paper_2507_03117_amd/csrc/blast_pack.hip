@@ -1,0 +1,409 @@
+// Block-norm pruning and packing of a dense bf16 weight into the block-compressed
+// format (BLaST Sec. 3.2: score each b x b block by its Frobenius norm, drop the
+// lowest until the target sparsity is reached; Sec. 3.4.1: compressed block
+// storage from which the product kernel derives its work).
+//
+// Everything runs on the device, on the caller's stream:
+//   score  -> one workgroup per block, 16-byte loads, fp64 sum of squares
+//   select -> exact radix select on the fp64 bit patterns + index-ordered tie-break
+//   count  -> per block-row / block-column populations, exclusive scans
+//   fill   -> ordered compaction of column indices, gather of block values
+//   order  -> rank block rows by population (schedule for load balance)
+//   csc    -> column-grouped index of the same blocks (used by the fused MLP)
+#include "blast_common.h"
+
+namespace {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// Exclusive scan of one int per thread over the whole workgroup (blockDim.x a
+// multiple of 64, at most 1024).  `wave_tot` is LDS scratch of >= 16 ints.
+// Returns the exclusive prefix; `total` receives the workgroup sum.
+__device__ __forceinline__ int block_exscan(int v, int* wave_tot, int& total) {
+  const int lane = lane_id(), wave = threadIdx.x / kWave, nw = blockDim.x / kWave;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(inc, d, kWave);
+    if (lane >= d) inc += o;
+  }
+  __syncthreads();  // protect wave_tot from the previous use
+  if (lane == kWave - 1) wave_tot[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int w = 0; w < nw; ++w) {
+    int t = wave_tot[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  total = tot;
+  return base + inc - v;
+}
+
+__device__ __forceinline__ double sq_bf16_pair(uint32_t w) {
+  // two bf16 packed in a dword; each widened exactly to fp32, squared in fp64
+  double lo = (double)__uint_as_float(w << 16);
+  double hi = (double)__uint_as_float(w & 0xFFFF0000u);
+  return lo * lo + hi * hi;
+}
+
+// One workgroup per block: squared Frobenius norm in fp64.  The summation tree
+// depends only on b, so equal blocks get equal scores wherever they sit.
+__global__ __launch_bounds__(256) void k_block_scores(const uint16_t* __restrict__ W, int64_t ldw, int nbc, int b,
+                                                      double* __restrict__ score) {
+  __shared__ double red[256];
+  const int64_t blk = blockIdx.x;
+  const int64_t br = blk / nbc, bc = blk % nbc;
+  const uint16_t* base = W + br * b * ldw + bc * b;
+  const int cpr = b / 8, nchunks = b * cpr;
+  double s = 0.0;
+  for (int c = threadIdx.x; c < nchunks; c += 256) {
+    const int i = c / cpr, j8 = c % cpr;
+    const uint4 v = *reinterpret_cast<const uint4*>(base + (int64_t)i * ldw + j8 * 8);
+    s += (sq_bf16_pair(v.x) + sq_bf16_pair(v.y)) + (sq_bf16_pair(v.z) + sq_bf16_pair(v.w));
+  }
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int d = 128; d > 0; d >>= 1) {
+    if ((int)threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) score[blk] = red[0];
+}
+
+__global__ void k_fill_u8(uint8_t* p, int64_t n, uint8_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// Exact selection of the n_keep highest scores (0 < n_keep < n).  Scores are
+// non-negative doubles, so their bit patterns order like unsigned integers.
+// An 8-pass most-significant-digit radix select finds the n_keep-th largest
+// pattern; everything above it is kept, and of the entries equal to it the
+// first ones in index order fill the remaining quota.
+__global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__ score, int64_t n, int64_t n_keep,
+                                                      uint8_t* __restrict__ mask) {
+  __shared__ unsigned hist[256];
+  __shared__ unsigned long long s_prefix;
+  __shared__ long long s_remaining;
+  __shared__ int wave_tot[16];
+  __shared__ long long s_running;
+  const unsigned long long* key = reinterpret_cast<const unsigned long long*>(score);
+  if (threadIdx.x == 0) {
+    s_prefix = 0ull;
+    s_remaining = n_keep;
+    s_running = 0;
+  }
+  for (int pass = 7; pass >= 0; --pass) {
+    if (threadIdx.x < 256) hist[threadIdx.x] = 0u;
+    __syncthreads();
+    const unsigned long long prefix = s_prefix;
+    const unsigned long long himask = (pass == 7) ? 0ull : (~0ull << (8 * (pass + 1)));
+    for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
+      const unsigned long long k = key[i];
+      if ((k & himask) == prefix) atomicAdd(&hist[(unsigned)(k >> (8 * pass)) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      long long cum = 0, rem = s_remaining;
+      int d = 255;
+      for (; d > 0; --d) {
+        if (cum + (long long)hist[d] >= rem) break;
+        cum += hist[d];
+      }
+      s_remaining = rem - cum;
+      s_prefix = prefix | ((unsigned long long)d << (8 * pass));
+    }
+    __syncthreads();
+  }
+  const unsigned long long kth = s_prefix;
+  const long long need_eq = s_remaining;
+  for (int64_t base = 0; base < n; base += blockDim.x) {
+    const int64_t i = base + threadIdx.x;
+    const unsigned long long k = (i < n) ? key[i] : 0ull;
+    const int eq = (i < n && k == kth) ? 1 : 0;
+    int total;
+    const long long pos = s_running + block_exscan(eq, wave_tot, total);
+    if (i < n) mask[i] = (k > kth || (eq && pos < need_eq)) ? 1 : 0;
+    __syncthreads();
+    if (threadIdx.x == 0) s_running += total;
+    __syncthreads();
+  }
+}
+
+// One wave per line: population of mask along a row (stride 1) or a column (stride nbc).
+__global__ __launch_bounds__(256) void k_line_counts(const uint8_t* __restrict__ mask, int n_lines, int line_len,
+                                                     int64_t line_stride, int64_t elem_stride, int* __restrict__ cnt) {
+  const int line = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (line >= n_lines) return;
+  int c = 0;
+  for (int j = lane_id(); j < line_len; j += kWave) c += mask[line * line_stride + j * elem_stride] ? 1 : 0;
+#pragma unroll
+  for (int d = kWave / 2; d > 0; d >>= 1) c += __shfl_xor(c, d, kWave);
+  if (lane_id() == 0) cnt[line] = c;
+}
+
+// Single workgroup: ptr[0..n] = exclusive scan of cnt[0..n).  total_out (may be null) gets ptr[n].
+__global__ __launch_bounds__(1024) void k_exscan(const int* __restrict__ cnt, int n, int* __restrict__ ptr,
+                                                 int* __restrict__ total_out) {
+  __shared__ int wave_tot[16];
+  __shared__ int s_running;
+  if (threadIdx.x == 0) s_running = 0;
+  __syncthreads();
+  for (int base = 0; base < n; base += blockDim.x) {
+    const int i = base + threadIdx.x;
+    const int v = (i < n) ? cnt[i] : 0;
+    int total;
+    const int ex = s_running + block_exscan(v, wave_tot, total);
+    if (i < n) ptr[i] = ex;
+    __syncthreads();
+    if (threadIdx.x == 0) s_running += total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    ptr[n] = s_running;
+    if (total_out) *total_out = s_running;
+  }
+}
+
+// One workgroup per block row: kept block columns, ascending, into col_idx; the
+// owning block row of every stored block into blk_row (for the gather).
+__global__ __launch_bounds__(256) void k_fill_cols(const uint8_t* __restrict__ mask, int nbc,
+                                                   const int* __restrict__ row_ptr, int* __restrict__ col_idx,
+                                                   int* __restrict__ blk_row, int64_t nnz_cap) {
+  __shared__ int wave_tot[16];
+  const int br = blockIdx.x;
+  const int start = row_ptr[br];
+  int running = 0;
+  for (int base = 0; base < nbc; base += blockDim.x) {
+    const int c = base + threadIdx.x;
+    const int f = (c < nbc && mask[(int64_t)br * nbc + c]) ? 1 : 0;
+    int total;
+    const int pos = running + block_exscan(f, wave_tot, total);
+    if (f) {
+      const int64_t k = (int64_t)start + pos;
+      if (k < nnz_cap) {
+        col_idx[k] = c;
+        blk_row[k] = br;
+      }
+    }
+    running += total;
+  }
+}
+
+// One workgroup per stored block: copy its b x b values, row-major, 16 bytes per lane.
+__global__ __launch_bounds__(256) void k_gather_blocks(const uint16_t* __restrict__ W, int64_t ldw, int b,
+                                                       const int* __restrict__ col_idx, const int* __restrict__ blk_row,
+                                                       uint16_t* __restrict__ vals) {
+  const int64_t k = blockIdx.x;
+  const int64_t br = blk_row[k], bc = col_idx[k];
+  const uint16_t* src = W + br * b * ldw + bc * b;
+  uint16_t* dst = vals + k * b * b;
+  const int cpr = b / 8, nchunks = b * cpr;
+  for (int c = threadIdx.x; c < nchunks; c += 256) {
+    const int i = c / cpr, j8 = c % cpr;
+    *reinterpret_cast<uint4*>(dst + (int64_t)c * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)i * ldw + j8 * 8);
+  }
+}
+
+// row_order[rank] = r with rank = number of rows that sort before r under
+// (population descending, row index ascending) -- a stable sort by counting.
+__global__ __launch_bounds__(256) void k_row_order(const int* __restrict__ row_ptr, int nbr, int* __restrict__ row_order) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= nbr) return;
+  const int cr = row_ptr[r + 1] - row_ptr[r];
+  int rank = 0;
+  for (int q = 0; q < nbr; ++q) {
+    const int cq = row_ptr[q + 1] - row_ptr[q];
+    rank += (cq > cr || (cq == cr && q < r)) ? 1 : 0;
+  }
+  row_order[rank] = r;
+}
+
+// One workgroup per block column: its stored blocks by ascending block row; for
+// each, the block row and the position k of the block in vals / col_idx.
+__global__ __launch_bounds__(256) void k_fill_csc(const uint8_t* __restrict__ mask, int nbr, int nbc,
+                                                  const int* __restrict__ row_ptr, const int* __restrict__ col_idx,
+                                                  const int* __restrict__ col_ptr, int* __restrict__ csc_row,
+                                                  int* __restrict__ csc_blk, int64_t nnz_cap) {
+  __shared__ int wave_tot[16];
+  const int c = blockIdx.x;
+  const int start = col_ptr[c];
+  int running = 0;
+  for (int base = 0; base < nbr; base += blockDim.x) {
+    const int r = base + threadIdx.x;
+    const int f = (r < nbr && mask[(int64_t)r * nbc + c]) ? 1 : 0;
+    int total;
+    const int pos = running + block_exscan(f, wave_tot, total);
+    if (f) {
+      int lo = row_ptr[r], hi = row_ptr[r + 1] - 1;  // col_idx ascending in the row: find c
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (col_idx[mid] < c) lo = mid + 1; else hi = mid;
+      }
+      const int64_t e = (int64_t)start + pos;
+      if (e < nnz_cap) {
+        csc_row[e] = r;
+        csc_blk[e] = lo;
+      }
+    }
+    running += total;
+  }
+}
+
+struct PackWs {
+  size_t scores_off, mask_off, rcnt_off, ccnt_off, blk_row_off, scalars_off, bytes;
+};
+
+PackWs pack_ws_layout(int64_t nbr, int64_t nbc, int32_t mode, int64_t nnz_cap) {
+  using blast::align_up;
+  const size_t n = (size_t)nbr * (size_t)nbc;
+  PackWs L;
+  size_t off = 0;
+  L.scores_off = off;
+  if (mode == BLAST_PACK_TOPK_FROBENIUS) off += align_up(8 * n, 256);
+  L.mask_off = off;
+  if (mode == BLAST_PACK_TOPK_FROBENIUS) off += align_up(n, 256);
+  L.rcnt_off = off;
+  off += align_up(4 * (size_t)nbr, 256);
+  L.ccnt_off = off;
+  off += align_up(4 * (size_t)nbc, 256);
+  L.blk_row_off = off;
+  off += align_up(4 * (size_t)(nnz_cap > 0 ? nnz_cap : 1), 256);
+  L.scalars_off = off;
+  off += 256;
+  L.bytes = off;
+  return L;
+}
+
+int check_shape(int64_t rows, int64_t cols, int32_t b) {
+  if (rows < 0 || cols < 0) return BLAST_ERR_INVALID_ARG;
+  if (!blast::supported_block(b)) return BLAST_ERR_UNSUPPORTED_BLOCK;
+  if (rows % b || cols % b) return BLAST_ERR_SHAPE;
+  if (rows / b > INT32_MAX / 2 || cols / b > INT32_MAX / 2 || (rows / b) * (cols / b) > (int64_t)INT32_MAX)
+    return BLAST_ERR_INVALID_ARG;
+  return BLAST_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t blast_n_keep(int64_t n_blocks, double sparsity) {
+  if (n_blocks < 0 || !(sparsity >= 0.0 && sparsity <= 1.0)) return -1;
+  const int64_t s_bp = (int64_t)(sparsity * 10000.0 + 0.5);
+  const int64_t n_zero = (int64_t)(((__int128)s_bp * n_blocks + 9999) / 10000);
+  return n_blocks - (n_zero > n_blocks ? n_blocks : n_zero);
+}
+
+extern "C" size_t blast_bsr_aux_bytes(int64_t rows, int64_t cols, int32_t b, int64_t nnz_cap) {
+  if (check_shape(rows, cols, b) != BLAST_OK || nnz_cap < 0) return 0;
+  return blast::aux_layout(cols / b, nnz_cap).bytes;
+}
+
+extern "C" int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, double sparsity,
+                                    int64_t* nnz_cap, size_t* aux_bytes, size_t* ws_bytes) {
+  if (mode != BLAST_PACK_MASK && mode != BLAST_PACK_TOPK_FROBENIUS) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_shape(rows, cols, b)) return rc;
+  const int64_t nbr = rows / b, nbc = cols / b, n = nbr * nbc;
+  int64_t cap = n;
+  if (mode == BLAST_PACK_TOPK_FROBENIUS) {
+    cap = blast_n_keep(n, sparsity);
+    if (cap < 0) return BLAST_ERR_INVALID_ARG;
+  }
+  if (nnz_cap) *nnz_cap = cap;
+  if (aux_bytes) *aux_bytes = blast::aux_layout(nbc, cap).bytes;
+  if (ws_bytes) *ws_bytes = pack_ws_layout(nbr, nbc, mode, cap).bytes;
+  return BLAST_OK;
+}
+
+extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
+                              const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx,
+                              uint16_t* vals, int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap,
+                              int64_t* nnz_out, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (mode != BLAST_PACK_MASK && mode != BLAST_PACK_TOPK_FROBENIUS) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_shape(rows, cols, b)) return rc;
+  if (!row_ptr || !nnz_out || nnz_cap < 0) return BLAST_ERR_INVALID_ARG;
+  const int64_t nbr = rows / b, nbc = cols / b, n = nbr * nbc;
+  if (n > 0 && (!W || ldw < cols || ldw % 8 || !blast::aligned(W, 16))) return BLAST_ERR_INVALID_ARG;
+  if (mode == BLAST_PACK_MASK && n > 0 && !block_mask) return BLAST_ERR_INVALID_ARG;
+  int64_t n_keep = -1;
+  if (mode == BLAST_PACK_TOPK_FROBENIUS) {
+    n_keep = blast_n_keep(n, sparsity);
+    if (n_keep < 0) return BLAST_ERR_INVALID_ARG;
+  }
+  if (nnz_cap > 0 && (!col_idx || !vals || !blast::aligned(vals, 16))) return BLAST_ERR_INVALID_ARG;
+  if (nbr > 0 && !row_order) return BLAST_ERR_INVALID_ARG;
+  const PackWs L = pack_ws_layout(nbr, nbc, mode, nnz_cap);
+  if (!ws || ws_bytes < L.bytes || !blast::aligned(ws, 16)) return BLAST_ERR_WORKSPACE;
+  const blast::AuxLayout A = blast::aux_layout(nbc, nnz_cap);
+  if (aux && (aux_bytes < A.bytes || !blast::aligned(aux, 16))) return BLAST_ERR_WORKSPACE;
+
+  char* wsb = static_cast<char*>(ws);
+  double* scores = reinterpret_cast<double*>(wsb + L.scores_off);
+  int* rcnt = reinterpret_cast<int*>(wsb + L.rcnt_off);
+  int* ccnt = reinterpret_cast<int*>(wsb + L.ccnt_off);
+  int* blk_row = reinterpret_cast<int*>(wsb + L.blk_row_off);
+  int* nnz_dev = reinterpret_cast<int*>(wsb + L.scalars_off);
+  const uint8_t* mask = block_mask;
+
+  if (mode == BLAST_PACK_TOPK_FROBENIUS) {
+    uint8_t* m = reinterpret_cast<uint8_t*>(wsb + L.mask_off);
+    mask = m;
+    if (n > 0) {
+      if (n_keep == 0 || n_keep == n) {
+        k_fill_u8<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(m, n, n_keep == n ? 1 : 0);
+        BLAST_LAUNCH_CHECK("k_fill_u8");
+      } else {
+        k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(W, ldw, (int)nbc, b, scores);
+        BLAST_LAUNCH_CHECK("k_block_scores");
+        k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, m);
+        BLAST_LAUNCH_CHECK("k_select_topk");
+      }
+    }
+  }
+
+  if (nbr > 0) {
+    k_line_counts<<<dim3((unsigned)((nbr + 3) / 4)), dim3(256), 0, stream>>>(mask, (int)nbr, (int)nbc, nbc, 1, rcnt);
+    BLAST_LAUNCH_CHECK("k_line_counts(rows)");
+  }
+  k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(rcnt, (int)nbr, row_ptr, nnz_dev);
+  BLAST_LAUNCH_CHECK("k_exscan(rows)");
+  int nnz_host = 0;
+  BLAST_HIP_TRY(hipMemcpyAsync(&nnz_host, nnz_dev, sizeof(int), hipMemcpyDeviceToHost, stream));
+  BLAST_HIP_TRY(hipStreamSynchronize(stream));
+  *nnz_out = nnz_host;
+  if (nnz_host > nnz_cap) return BLAST_ERR_CAPACITY;
+
+  if (nbr > 0) {
+    k_fill_cols<<<dim3((unsigned)nbr), dim3(256), 0, stream>>>(mask, (int)nbc, row_ptr, col_idx, blk_row, nnz_cap);
+    BLAST_LAUNCH_CHECK("k_fill_cols");
+    k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, (int)nbr, row_order);
+    BLAST_LAUNCH_CHECK("k_row_order");
+  }
+  if (nnz_host > 0) {
+    k_gather_blocks<<<dim3((unsigned)nnz_host), dim3(256), 0, stream>>>(W, ldw, b, col_idx, blk_row, vals);
+    BLAST_LAUNCH_CHECK("k_gather_blocks");
+  }
+  if (aux) {
+    char* ab = static_cast<char*>(aux);
+    int* col_ptr = reinterpret_cast<int*>(ab + A.col_ptr_off);
+    int* csc_row = reinterpret_cast<int*>(ab + A.csc_row_off);
+    int* csc_blk = reinterpret_cast<int*>(ab + A.csc_blk_off);
+    if (nbc > 0 && nbr > 0) {
+      k_line_counts<<<dim3((unsigned)((nbc + 3) / 4)), dim3(256), 0, stream>>>(mask, (int)nbc, (int)nbr, 1, nbc, ccnt);
+      BLAST_LAUNCH_CHECK("k_line_counts(cols)");
+    } else if (nbc > 0) {
+      BLAST_HIP_TRY(hipMemsetAsync(ccnt, 0, sizeof(int) * (size_t)nbc, stream));
+    }
+    k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(ccnt, (int)nbc, col_ptr, nullptr);
+    BLAST_LAUNCH_CHECK("k_exscan(cols)");
+    if (nbc > 0 && nnz_host > 0) {
+      k_fill_csc<<<dim3((unsigned)nbc), dim3(256), 0, stream>>>(mask, (int)nbr, (int)nbc, row_ptr, col_idx, col_ptr,
+                                                                csc_row, csc_blk, nnz_cap);
+      BLAST_LAUNCH_CHECK("k_fill_csc");
+    }
+  }
+  return BLAST_OK;
+}

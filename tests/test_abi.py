@@ -1,0 +1,90 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import oracle as orc
+from paper_2507_03117_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    txt = open(os.path.join(ROOT, "include", "blast.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(blast_[a-z0-9_]+)\s*\(", txt)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = api.lib()
+    syms = declared_symbols()
+    assert set(syms) == set(api.EXPORTS)
+    for s in syms:
+        assert hasattr(L, s), s
+
+
+def test_strerror_texts():
+    L = api.lib()
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
+        t = L.blast_strerror(code)
+        assert t and len(t) > 1
+        seen.add(t)
+    assert len(seen) == 8
+
+
+@pytest.mark.parametrize("n,s", [(4096, 0.9), (6144, 0.7), (6144, 0.8), (6144, 0.9), (6144, 0.95), (3584, 0.95),
+                                 (53248, 0.95), (10, 0.0), (10, 1.0), (7, 0.5), (3, 0.34), (12345, 0.3333)])
+def test_n_keep_matches_oracle(n, s):
+    assert api.n_keep(n, s) == orc.n_keep(n, s)
+
+
+def test_n_keep_rejects_bad_sparsity():
+    assert api.n_keep(10, -0.1) == -1 and api.n_keep(10, 1.5) == -1 and api.n_keep(-1, 0.5) == -1
+
+
+def test_pack_bound_and_errors():
+    L = api.lib()
+    cap, auxb, wsb = C.c_int64(0), C.c_size_t(0), C.c_size_t(0)
+    assert L.blast_bsr_pack_bound(8192, 2048, 64, api.PACK_TOPK_FROBENIUS, 0.9, C.byref(cap), C.byref(auxb), C.byref(wsb)) == 0
+    assert cap.value == 409 and auxb.value >= 4 * (32 + 1 + 2 * 409) and wsb.value >= 9 * 4096
+    assert L.blast_bsr_pack_bound(8192, 2048, 64, api.PACK_MASK, 0.0, C.byref(cap), None, None) == 0
+    assert cap.value == 4096
+    assert L.blast_bsr_pack_bound(8192, 2050, 64, 0, 0.0, None, None, None) == -2  # shape
+    assert L.blast_bsr_pack_bound(8192, 2048, 48, 0, 0.0, None, None, None) == -3  # block
+    assert L.blast_bsr_pack_bound(8192, 2048, 64, 7, 0.0, None, None, None) == -1  # mode
+    assert L.blast_bsr_pack_bound(8192, 2048, 64, 1, 1.5, None, None, None) == -1  # sparsity
+    assert L.blast_bsr_aux_bytes(8192, 2048, 64, 4096) >= 4 * (32 + 1 + 2 * 4096)
+
+
+def test_spmm_and_mlp_argument_errors_return_before_any_launch():
+    L = api.lib()
+    v = api.BsrView(128, 128, 64, 0, 0, None, None, None, None, None)
+    # null row_ptr
+    assert L.blast_bsr_spmm(C.byref(v), None, 128, 0, 4, None, 128, 0, None, 0, None) == -1
+    assert L.blast_bsr_spmm(None, None, 128, 0, 4, None, 128, 0, None, 0, None) == -1
+    dummy = (C.c_int32 * 4)()
+    v.row_ptr = C.cast(dummy, C.c_void_p)
+    assert L.blast_bsr_spmm(C.byref(v), None, 128, 0, 4, None, 128, 0, None, 0, None) == -1  # X null
+    assert L.blast_bsr_spmm(C.byref(v), None, 128, 5, 0, None, 128, 0, None, 0, None) == -1  # layout enum
+    assert L.blast_bsr_spmm(C.byref(v), None, 128, 0, -1, None, 128, 0, None, 0, None) == -1  # T < 0
+    assert L.blast_bsr_spmm(C.byref(v), None, 128, 0, 0, None, 128, 0, None, 0, None) == 0  # T == 0 is a no-op
+    bad = api.BsrView(100, 128, 64, 0, 0, v.row_ptr, None, None, None, None)
+    assert L.blast_bsr_spmm(C.byref(bad), None, 128, 0, 4, None, 128, 0, None, 0, None) == -2
+    bad = api.BsrView(96, 96, 48, 0, 0, v.row_ptr, None, None, None, None)
+    assert L.blast_bsr_spmm(C.byref(bad), None, 128, 0, 4, None, 128, 0, None, 0, None) == -3
+    # MLP: inconsistent shapes
+    g = api.BsrView(256, 128, 64, 0, 0, v.row_ptr, None, None, None, None)
+    d_ok = api.BsrView(128, 256, 64, 0, 0, v.row_ptr, None, None, None, None)
+    d_bad = api.BsrView(128, 128, 64, 0, 0, v.row_ptr, None, None, None, None)
+    assert L.blast_sparse_mlp(C.byref(g), C.byref(g), C.byref(d_bad), None, 128, 0, 4, 0, None, 128, 0, None, 0, None) == -2
+    assert L.blast_sparse_mlp(C.byref(g), C.byref(g), C.byref(d_ok), None, 128, 0, 4, 9, None, 128, 0, None, 0, None) == -1
+    ws = C.c_size_t(0)
+    assert L.blast_sparse_mlp_workspace(C.byref(g), C.byref(g), C.byref(d_ok), 16, C.byref(ws)) == 0
+    assert ws.value >= 16 * 256 * 2
+    # pack: null outputs / bad ld are rejected up front
+    nnz = C.c_int64(0)
+    assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, 0, None) == -1

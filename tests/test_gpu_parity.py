@@ -1,0 +1,267 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Index arrays bit-exact; outputs within
+rel-Frobenius <= 1e-3 and max-abs <= 1e-2 * RMS (tests/helpers.py)."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2507_03117_amd import synth
+from tests.helpers import bits_of, check_close, mask_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    import torch
+
+    assert torch.cuda.is_available()
+    from paper_2507_03117_amd import api as _api
+
+    _api.lib()
+    return _api
+
+
+def pack_both(api, W, b, mask=None, sparsity=None):
+    """Pack on the device and with the oracle; assert bit-exact structure and values."""
+    if mask is not None:
+        ref = orc.pack(W, b, mask)
+        dev = api.bsr_pack(to_dev(W), b, mask=mask_dev(mask))
+    else:
+        ref, ref_mask, gap = orc.pack_topk(W, b, sparsity)
+        assert gap > 1e-9, "selection hangs on rounding: reseed"
+        dev = api.bsr_pack(to_dev(W), b, sparsity=sparsity)
+    assert dev.nnz == ref.nnz
+    assert np.array_equal(dev.row_ptr.cpu().numpy(), ref.row_ptr)
+    assert np.array_equal(dev.col_idx.cpu().numpy()[: ref.nnz], ref.col_idx)
+    assert np.array_equal(bits_of(dev.vals)[: ref.nnz * b * b].reshape(ref.nnz, b, b), ref.vals)
+    if ref.row_order.size:
+        assert np.array_equal(dev.row_order.cpu().numpy()[: ref.row_order.size], ref.row_order)
+    return dev, ref
+
+
+def check_aux(dev, ref):
+    """The column-grouped index lists the same blocks, by column then ascending row."""
+    nbc = ref.cols // ref.b
+    aux = dev.aux.cpu().numpy()
+    cap = dev.col_idx.numel() if ref.nnz else 0
+    a16 = lambda x: (x + 15) // 16 * 16
+    col_ptr = aux[: 4 * (nbc + 1)].view(np.int32)
+    off = a16(4 * (nbc + 1))
+    csc_row = aux[off: off + 4 * ref.nnz].view(np.int32)
+    off += a16(4 * max(cap, ref.nnz))
+    csc_blk = aux[off: off + 4 * ref.nnz].view(np.int32)
+    rows_of_blk = np.repeat(np.arange(ref.rows // ref.b), np.diff(ref.row_ptr))
+    order = np.lexsort((rows_of_blk, ref.col_idx))  # by column, then row
+    assert np.array_equal(col_ptr, np.concatenate([[0], np.cumsum(np.bincount(ref.col_idx, minlength=nbc))]))
+    assert np.array_equal(csc_blk, order.astype(np.int32))
+    assert np.array_equal(csc_row, rows_of_blk[order].astype(np.int32))
+
+
+# ------------------------------------------------------------------ packing
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_pack_mask_mode(api, b, sparsity):
+    rng = np.random.default_rng(100 + b)
+    nbr, nbc = 7, 11
+    W = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.02)
+    mask = synth.uniform_mask(rng, nbr, nbc, sparsity)
+    if 0 < sparsity < 1:
+        mask[3, :] = 0
+        mask[5, :] = 1
+    dev, ref = pack_both(api, W, b, mask=mask)
+    check_aux(dev, ref)
+
+
+@pytest.mark.parametrize("b,rows,cols,sparsity", [(16, 256, 512, 0.7), (32, 1024, 4096, 0.9), (64, 2048, 1024, 0.95),
+                                                  (128, 1024, 2048, 0.8), (64, 512, 512, 0.0), (64, 512, 512, 1.0)])
+def test_pack_topk_mode(api, b, rows, cols, sparsity):
+    rng = np.random.default_rng(200 + b)
+    W = synth.gauss_bf16(rng, (rows, cols), 0.02)
+    dev, ref = pack_both(api, W, b, sparsity=sparsity)
+    assert ref.nnz == orc.n_keep((rows // b) * (cols // b), sparsity)
+    check_aux(dev, ref)
+
+
+def test_pack_topk_ties_and_zero_blocks(api):
+    # all-zero blocks tie at score 0 and duplicated blocks tie exactly: lower linear index wins
+    rng = np.random.default_rng(7)
+    b, nbr, nbc = 32, 6, 8
+    W = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.02)
+    Wv = W.reshape(nbr, b, nbc, b)
+    Wv[0, :, 2:7, :] = 0
+    Wv[4, :, :, :] = 0
+    Wv[2, :, 1, :] = Wv[1, :, 5, :]
+    Wv[5, :, 6, :] = Wv[1, :, 5, :]
+    for s in (0.1, 0.5, 0.8, 0.9):
+        ref_mask, _ = orc.topk_mask(orc.block_scores(W, b), s)
+        ref = orc.pack(W, b, ref_mask)
+        dev = api.bsr_pack(to_dev(W), b, sparsity=s)
+        assert dev.nnz == ref.nnz
+        assert np.array_equal(dev.row_ptr.cpu().numpy(), ref.row_ptr)
+        assert np.array_equal(dev.col_idx.cpu().numpy()[: ref.nnz], ref.col_idx)
+
+
+def test_pack_strided_weight_and_capacity_error(api):
+    import torch
+
+    rng = np.random.default_rng(8)
+    b = 32
+    Wfull = synth.gauss_bf16(rng, (128, 256 + 64), 0.02)
+    W = Wfull[:, :256]
+    mask = synth.uniform_mask(rng, 4, 8, 0.5)
+    ref = orc.pack(np.ascontiguousarray(W), b, mask)
+    dev = api.bsr_pack(to_dev(Wfull)[:, :256], b, mask=mask_dev(mask))  # ldw = 320
+    assert np.array_equal(bits_of(dev.vals)[: ref.nnz * b * b].reshape(ref.nnz, b, b), ref.vals)
+    with pytest.raises(api.BlastError) as ei:
+        api.bsr_pack(to_dev(np.ascontiguousarray(W)), b, mask=mask_dev(mask), nnz_cap=ref.nnz - 1)
+    assert ei.value.code == -4
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ SpMM
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+@pytest.mark.parametrize("T", [1, 3, 17, 64, 100, 300])
+def test_spmm_small_shapes(api, b, T):
+    import torch
+
+    nbr, nbc = 5, 6
+    w, mask, x = synth.small_case(1000 + b + T, nbr * b, nbc * b, b, 0.5, T, empty_rows=(1,), full_rows=(3,))
+    dev, ref = pack_both(api, w, b, mask=mask)
+    y_or = orc.spmm(ref, x)  # [rows, T]
+    y = api.bsr_spmm(dev, to_dev(x))  # [T, rows] fp32
+    torch.cuda.synchronize()
+    yh = y.cpu().numpy()
+    check_close(yh.T, y_or, f"spmm b={b} T={T}")
+    assert not yh[:, b:2 * b].any()  # empty block row is written as exact zeros
+
+
+@pytest.mark.parametrize("b,T", [(32, 5), (64, 70), (128, 33)])
+def test_spmm_feature_major_and_bf16_out(api, b, T):
+    import torch
+
+    w, mask, x = synth.small_case(2000 + b, 4 * b, 3 * b, b, 0.4, T)
+    dev, ref = pack_both(api, w, b, mask=mask)
+    y_or = orc.spmm(ref, x)
+    xf = np.ascontiguousarray(x.T)  # [K, T]
+    y = api.bsr_spmm(dev, to_dev(xf), layout=api.FEATURE_MAJOR)  # [rows, T]
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy(), y_or, "feature-major")
+    # bf16 output: the fp32 accumulator rounded to nearest even -> within one bf16 ulp of the rounded oracle
+    yb = api.bsr_spmm(dev, to_dev(x), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    got = synth.bf16_bits_to_f32(bits_of(yb)).astype(np.float64).T
+    want = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(y_or.astype(np.float32))).astype(np.float64)
+    ulp = np.maximum(np.abs(want), 1e-30) * 2.0 ** -7
+    assert (np.abs(got - want) <= ulp).all()
+
+
+def test_spmm_unaligned_token_major_uses_slow_loads(api):
+    import torch
+
+    b, T = 32, 9
+    w, mask, x = synth.small_case(31, 3 * b, 4 * b, b, 0.3, T)
+    dev, ref = pack_both(api, w, b, mask=mask)
+    xpad = np.zeros((T, 4 * b + 3), dtype=np.uint16)
+    xpad[:, : 4 * b] = x
+    xd = to_dev(xpad)[:, : 4 * b]  # ldx = 131: not a multiple of 8
+    y = api.bsr_spmm(dev, xd)
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, orc.spmm(ref, x), "unaligned ldx")
+
+
+def test_spmm_dense_and_empty_matrix(api):
+    import torch
+
+    b, T = 64, 40
+    w, _, x = synth.small_case(32, 3 * b, 2 * b, b, 0.0, T)
+    dev, ref = pack_both(api, w, b, sparsity=0.0)
+    y = api.bsr_spmm(dev, to_dev(x))
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, orc.spmm(ref, x), "dense")
+    dev0, ref0 = pack_both(api, w, b, sparsity=1.0)
+    y0 = api.bsr_spmm(dev0, to_dev(x), out=torch.full((T, 3 * b), float("nan"), device="cuda:0"))
+    torch.cuda.synchronize()
+    assert not y0.cpu().numpy().any()
+
+
+def test_spmm_config1_linear(api):
+    import torch
+
+    wl = synth.WORKLOADS["linear_1024x4096_b32_s90"]
+    lin = synth.make_linear(wl)
+    x = synth.make_x(wl, 64)
+    dev, ref = pack_both(api, lin.W, wl.b, mask=lin.mask)
+    assert ref.nnz == 409
+    y = api.bsr_spmm(dev, to_dev(x))
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, orc.spmm(ref, x), "config 1")
+    # the literal "4096 x 64" feature-major reading of the same configuration
+    yf = api.bsr_spmm(dev, to_dev(np.ascontiguousarray(x.T)), layout=api.FEATURE_MAJOR)
+    torch.cuda.synchronize()
+    check_close(yf.cpu().numpy(), orc.spmm(ref, x), "config 1 feature-major")
+
+
+# ------------------------------------------------------------------ fused MLP
+def _mlp_case(api, seed, E, I, b, sparsity, T, act="silu", layout="token_major", poison=True):
+    import torch
+
+    rng = np.random.default_rng(seed)
+    g, u, d = (synth.gauss_bf16(rng, s, 0.05) for s in ((I, E), (I, E), (E, I)))
+    mg, mu = (synth.uniform_mask(rng, I // b, E // b, sparsity) for _ in range(2))
+    md = synth.uniform_mask(rng, E // b, I // b, sparsity)
+    if I // b > 2:
+        mg[1, :] = 0  # empty gate block row -> zero H rows
+        md[:, 2] = 0  # H rows nobody consumes
+    if E // b > 1:
+        md[1, :] = 0  # empty down block row -> zero Y rows
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    dg, rg = pack_both(api, g, b, mask=mg)
+    du, ru = pack_both(api, u, b, mask=mu)
+    dd, rd = pack_both(api, d, b, mask=md)
+    y_or = orc.mlp(rg, ru, rd, x, activation=act)
+    if layout == "token_major":
+        out = torch.full((T, E), float("nan"), device="cuda:0") if poison else None
+        y = api.sparse_mlp(dg, du, dd, to_dev(x), act=act, out=out).cpu().numpy().T
+    else:
+        y = api.sparse_mlp(dg, du, dd, to_dev(np.ascontiguousarray(x.T)), act=act, layout=api.FEATURE_MAJOR).cpu().numpy()
+    torch.cuda.synchronize()
+    check_close(y, y_or, f"mlp E={E} I={I} b={b} T={T} {act} {layout}")
+    if E // b > 1:
+        assert not y[b:2 * b].any()
+
+
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+@pytest.mark.parametrize("T", [1, 16, 33, 130, 300])
+def test_mlp_small(api, b, T):
+    _mlp_case(api, 3000 + b + T, 4 * b, 6 * b, b, 0.5, T)
+
+
+@pytest.mark.parametrize("act", ["silu", "gelu", "relu"])
+def test_mlp_activations_and_layouts(api, act):
+    _mlp_case(api, 3100, 256, 512, 64, 0.6, 37, act=act)
+    _mlp_case(api, 3101, 256, 512, 64, 0.6, 37, act=act, layout="feature_major")
+
+
+def test_mlp_dense_and_all_pruned(api):
+    _mlp_case(api, 3200, 128, 256, 64, 0.0, 20)
+    _mlp_case(api, 3201, 128, 256, 64, 1.0, 20)
+
+
+def test_mlp_repeatable(api):
+    import torch
+
+    wl = synth.WORKLOADS["llama1b_b64_s90"]
+    rng = np.random.default_rng(5)
+    E, I, b, T = 512, 1024, 64, 48
+    g, u, d = (synth.gauss_bf16(rng, s, 0.03) for s in ((I, E), (I, E), (E, I)))
+    x = to_dev(synth.gauss_bf16(rng, (T, E), 1.0))
+    dg = api.bsr_pack(to_dev(g), b, sparsity=0.8)
+    du = api.bsr_pack(to_dev(u), b, sparsity=0.8)
+    dd = api.bsr_pack(to_dev(d), b, sparsity=0.8)
+    y1 = api.sparse_mlp(dg, du, dd, x).clone()
+    for _ in range(3):
+        y2 = api.sparse_mlp(dg, du, dd, x)
+        torch.cuda.synchronize()
+        check_close(y2.cpu().numpy(), y1.cpu().numpy().astype(np.float64), "repeat")
+    assert wl.b == 64
