@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused block-sparse SwiGLU MLP on one MI355X.
+
+A step = one pass of the MLP of Eq. (1) (gate/up products, activation, down
+product; output written) through the C ABI over one synthetic batch already
+resident in HBM.  Packing is done once before the timed region, like loading a
+checkpoint; its throughput is reported separately in "pack".
+
+Workload (benchmark configs[1]): Llama-3.2-1B-shaped MLP, hidden 2048,
+intermediate 8192, 64x64 blocks, 90 % uniform-random block sparsity.  The
+headline `value` is the prefill case T = 2048 (effective TFLOP/s on stored
+blocks); the decode token counts 1, 16, 128 are timed the same way and reported
+under "decode" as algorithmic HBM GB/s.
+
+Cold-HBM protocol: every step uses a different copy of the packed block values
+(>= 768 MB in rotation), so no step re-reads weights still sitting in the
+256 MB last-level cache.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch sequence from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), scaled by the
+# factor a plain copy kernel of known size reads on the same counters.  Filled from profiles/*.txt.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def hip_runtime():
+    import torch  # noqa: F401  (loads the HIP runtime this process uses)
+
+    for name in ("libamdhip64.so.7", "libamdhip64.so"):
+        try:
+            return C.CDLL(name)
+        except OSError:
+            continue
+    raise RuntimeError("cannot open the HIP runtime")
+
+
+class Events:
+    """hipEvent_t triples recorded by blast_sparse_mlp_events on the launch stream."""
+
+    def __init__(self, n_steps: int):
+        self.hip = hip_runtime()
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.triples = []
+        for _ in range(n_steps):
+            arr = (C.c_void_p * 3)()
+            for j in range(3):
+                ev = C.c_void_p()
+                assert self.hip.hipEventCreate(C.byref(ev)) == 0
+                arr[j] = ev
+            self.triples.append(arr)
+
+    def elapsed(self, a, b) -> float:
+        ms = C.c_float()
+        assert self.hip.hipEventSynchronize(b) == 0
+        assert self.hip.hipEventElapsedTime(C.byref(ms), a, b) == 0
+        return float(ms.value)
+
+    def destroy(self):
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        for arr in self.triples:
+            for j in range(3):
+                self.hip.hipEventDestroy(arr[j])
+
+
+def rotated_copies(p, n_copies):
+    """Same structure, distinct addresses for the block values."""
+    import copy
+
+    out = [p]
+    for _ in range(n_copies - 1):
+        q = copy.copy(p)
+        q.vals = p.vals.clone()
+        out.append(q)
+    return out
+
+
+def time_mlp(api, torch, sets, x, T, steps, warmup, ws):
+    """Returns (wall ms per step, mean ms of phase 1, mean ms of phase 2, mean ms of the pass from events)."""
+    E = sets[0][2].rows
+    y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
+    ev = Events(steps)
+    n = len(sets)
+    for i in range(warmup):
+        g, u, d = sets[i % n]
+        api.sparse_mlp(g, u, d, x, out=y, ws=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        g, u, d = sets[(warmup + i) % n]
+        api.sparse_mlp(g, u, d, x, out=y, ws=ws, events=ev.triples[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    p1 = sum(ev.elapsed(t[0], t[1]) for t in ev.triples) / steps
+    p2 = sum(ev.elapsed(t[1], t[2]) for t in ev.triples) / steps
+    tot = sum(ev.elapsed(t[0], t[2]) for t in ev.triples) / steps
+    ev.destroy()
+    return wall_ms, p1, p2, tot
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama1b_b64_s90")
+    ap.add_argument("--tokens", type=int, default=2048, help="token count of the headline step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=96)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2507_03117_amd import api, synth
+    from tests.helpers import mask_dev, to_dev
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    api.lib()
+    wl = synth.WORKLOADS[args.workload]
+    assert wl.kind == "mlp"
+    inp = synth.make_mlp(wl)
+    b = wl.b
+
+    # ---- pack once (timed separately) ------------------------------------------------------
+    def pack(lin):
+        if lin.mask is not None:
+            return api.bsr_pack(to_dev(lin.W), b, mask=mask_dev(lin.mask))
+        return api.bsr_pack(to_dev(lin.W), b, sparsity=lin.sparsity)
+
+    dW = [to_dev(l.W) for l in (inp.gate, inp.up, inp.down)]
+    dM = [mask_dev(l.mask) if l.mask is not None else None for l in (inp.gate, inp.up, inp.down)]
+    packed = []
+    for w_, m_, l in zip(dW, dM, (inp.gate, inp.up, inp.down)):
+        packed.append(api.bsr_pack(w_, b, mask=m_) if m_ is not None else api.bsr_pack(w_, b, sparsity=l.sparsity))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 5
+    for _ in range(reps):
+        for w_, l in zip(dW, (inp.gate, inp.up, inp.down)):
+            api.bsr_pack(w_, b, sparsity=l.sparsity)  # the scoring mode: reads every dense weight once
+    torch.cuda.synchronize()
+    pack_ms = (time.perf_counter() - t0) * 1e3 / reps
+    dense_bytes = sum(int(w_.numel()) * 2 for w_ in dW)
+    del dW
+    g, u, d = packed
+    nnz = g.nnz + u.nnz + d.nnz
+    w_bytes = nnz * b * b * 2
+    n_copies = max(2, -(-768 * 1024 * 1024 // w_bytes))
+    sets = list(zip(rotated_copies(g, n_copies), rotated_copies(u, n_copies), rotated_copies(d, n_copies)))
+
+    def run_T(T, steps, warmup):
+        x = to_dev(synth.make_x(wl, T))
+        ws = torch.empty(max(api.mlp_workspace_bytes(g, u, d, T), 256), dtype=torch.uint8, device="cuda:0")
+        wall_ms, p1, p2, tot = time_mlp(api, torch, sets, x, T, steps, warmup, ws)
+        flops = 2.0 * b * b * T * nnz
+        alg_bytes = w_bytes + 4 * nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
+        return dict(T=T, ms_per_step=wall_ms, ms_events=tot, ms_gate_up=p1, ms_down=p2, flops=flops,
+                    alg_bytes=alg_bytes)
+
+    T = args.tokens
+    head = run_T(T, args.steps, args.warmup)
+    tflops = head["flops"] / (head["ms_per_step"] * 1e-3) / 1e12
+
+    # roofline of the dominant kernel (gate/up product + activation: 2/3 of the stored blocks)
+    gu_flops = 2.0 * b * b * T * (g.nnz + u.nnz)
+    gu_tflops = gu_flops / (head["ms_gate_up"] * 1e-3) / 1e12
+    mfma_bound = T >= 512
+    if mfma_bound:
+        roofline = dict(bound="mfma", kernel="k_spmm_tile<64,dual> (gate/up + activation)", achieved=gu_tflops,
+                        peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=gu_tflops / PEAK_BF16_TFLOPS,
+                        avg_kernel_ms=head["ms_gate_up"], traffic=MEASURED_TRAFFIC_BYTES.get(("gate_up", T)))
+    else:
+        gbs = head["alg_bytes"] / (head["ms_events"] * 1e-3) / 1e9
+        roofline = dict(bound="hbm", kernel="whole MLP pass", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=gbs / PEAK_HBM_GBS, avg_kernel_ms=head["ms_events"],
+                        traffic=MEASURED_TRAFFIC_BYTES.get(("mlp", T)))
+
+    out = {
+        "metric": "fused BSR MLP effective TFLOP/s (stored blocks only), prefill T=%d" % T,
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b,
+                   "sparsity": wl.sparsity, "mask": wl.mask_kind, "tokens": T, "nnz_blocks": nnz,
+                   "x_layout": "token_major", "y_dtype": "f32", "weight_copies_in_rotation": n_copies},
+        "frac_of_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "phases_ms": {"gate_up_act": head["ms_gate_up"], "down": head["ms_down"], "pass_events": head["ms_events"]},
+        "roofline": roofline,
+        "pack": {"ms_three_matrices_topk": pack_ms, "dense_GBps": dense_bytes / (pack_ms * 1e-3) / 1e9,
+                 "frac_hbm": dense_bytes / (pack_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+    }
+
+    if not args.no_decode:
+        dec = []
+        for Td in (t for t in wl.tokens if t <= 128):
+            r = run_T(Td, max(args.steps, 50), args.warmup)
+            gbs = r["alg_bytes"] / (r["ms_events"] * 1e-3) / 1e9
+            dec.append({"T": Td, "ms_per_step": r["ms_per_step"], "ms_events": r["ms_events"],
+                        "ms_gate_up": r["ms_gate_up"], "ms_down": r["ms_down"], "alg_MB": r["alg_bytes"] / 1e6,
+                        "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
+                        "TFLOPs": r["flops"] / (r["ms_events"] * 1e-3) / 1e12})
+        out["decode"] = dec
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+
+        Ts = min(args.cpu_sample_tokens, T)
+        rg = orc.pack(inp.gate.W, b, inp.gate.mask) if inp.gate.mask is not None else orc.pack_topk(inp.gate.W, b, wl.sparsity)[0]
+        ru = orc.pack(inp.up.W, b, inp.up.mask) if inp.up.mask is not None else orc.pack_topk(inp.up.W, b, wl.sparsity)[0]
+        rd = orc.pack(inp.down.W, b, inp.down.mask) if inp.down.mask is not None else orc.pack_topk(inp.down.W, b, wl.sparsity)[0]
+        xs = synth.make_x(wl, T)[:Ts]
+        t0 = time.perf_counter()
+        y_or = orc.mlp(rg, ru, rd, np.ascontiguousarray(xs))
+        sec = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": 2.0 * b * b * Ts * nnz / sec / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(),
+            "kind": "oracle", "seconds": sec,
+            "sample": "first %d of %d tokens, all rows; dense masked fp64 triple loop (it also multiplies the zeros)" % (Ts, T),
+        }
+        # the same sample doubles as a parity check of the timed launch configuration
+        x = to_dev(synth.make_x(wl, T))
+        y = api.sparse_mlp(g, u, d, x)
+        torch.cuda.synchronize()
+        yh = y[:Ts].cpu().numpy().astype(np.float64).T
+        out["parity_on_sample"] = {
+            "rel_fro": float(np.linalg.norm(yh - y_or) / np.linalg.norm(y_or)),
+            "max_abs_over_rms": float(np.abs(yh - y_or).max() / np.sqrt((y_or ** 2).mean())),
+        }
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

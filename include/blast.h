@@ -173,6 +173,28 @@ int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, con
 int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
                                int64_t T, size_t* ws_bytes /* HOST */);
 
+/*
+ * blast_sparse_mlp with three caller-created hipEvent_t recorded on `stream`, so that a caller can
+ * time the phases of Eq. (1) inside its own timed region:
+ *   events[0] before the first kernel, events[1] after the kernel that finishes H = act(G) (.) U
+ *   (Sec. 3.4.3), events[2] after the kernel that finishes Y.  When one kernel does both, events[1]
+ *   and events[2] are recorded back to back after it.  `events` is a HOST array of 3 hipEvent_t.
+ * Same arguments, results and errors as blast_sparse_mlp otherwise.
+ */
+int blast_sparse_mlp_events(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
+                            const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y,
+                            int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes, void* stream,
+                            void* const* events);
+
+/*
+ * The gated first half of Eq. (1) on its own (Sec. 3.4.3: the nonlinearity that follows the product is
+ * fused into the product kernel):  H = act(Wgate * X) (.) (Wup * X), rounded once to bf16.
+ * Wgate and Wup have the same shape and block size.  H is rows x T bf16 in the same layout as X.
+ * Never synchronises.  Errors as blast_bsr_spmm.
+ */
+int blast_bsr_gated_spmm(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const uint16_t* X, int64_t ldx,
+                         int32_t x_layout, int64_t T, int32_t act, uint16_t* H, int64_t ldh, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

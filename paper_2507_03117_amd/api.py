@@ -24,6 +24,7 @@ ACT = {"silu": 0, "gelu": 1, "relu": 2}
 EXPORTS = (
     "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
+    "blast_sparse_mlp_events", "blast_bsr_gated_spmm",
 )
 
 
@@ -74,6 +75,10 @@ def lib():
         L.blast_sparse_mlp.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
         L.blast_sparse_mlp_workspace.restype = C.c_int
         L.blast_sparse_mlp_workspace.argtypes = [pv, pv, pv, i64, C.POINTER(sz)]
+        L.blast_sparse_mlp_events.restype = C.c_int
+        L.blast_sparse_mlp_events.argtypes = L.blast_sparse_mlp.argtypes + [C.POINTER(vp)]
+        L.blast_bsr_gated_spmm.restype = C.c_int
+        L.blast_bsr_gated_spmm.argtypes = [pv, pv, vp, i64, i32, i64, i32, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -189,8 +194,9 @@ def mlp_workspace_bytes(gate: PackedBsr, up: PackedBsr, down: PackedBsr, T: int)
 
 def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor, *, layout: int = TOKEN_MAJOR,
                act: str = "silu", out_dtype: torch.dtype = torch.float32, out: Optional[torch.Tensor] = None,
-               ws: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """blast_sparse_mlp: Y = Wdown * (act(Wgate * X) (.) (Wup * X))."""
+               ws: Optional[torch.Tensor] = None, events=None) -> torch.Tensor:
+    """blast_sparse_mlp: Y = Wdown * (act(Wgate * X) (.) (Wup * X)).
+    `events`: optional ctypes array of 3 hipEvent_t -> blast_sparse_mlp_events."""
     L = lib()
     T, K, ldx = _layout_dims(X, layout)
     assert K == gate.cols
@@ -198,7 +204,23 @@ def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor,
     vg, vu, vd = gate.view(), up.view(), down.view()
     if ws is None:
         ws = torch.empty(max(mlp_workspace_bytes(gate, up, down, T), 256), dtype=torch.uint8, device=X.device)
-    _check(L.blast_sparse_mlp(C.byref(vg), C.byref(vu), C.byref(vd), _ptr(X), ldx, layout, T, ACT[act], _ptr(Y),
-                              Y.stride(0), BF16 if Y.dtype == torch.bfloat16 else F32, _ptr(ws), ws.numel(),
-                              _stream()), "blast_sparse_mlp")
+    args = (C.byref(vg), C.byref(vu), C.byref(vd), _ptr(X), ldx, layout, T, ACT[act], _ptr(Y), Y.stride(0),
+            BF16 if Y.dtype == torch.bfloat16 else F32, _ptr(ws), ws.numel(), _stream())
+    if events is None:
+        _check(L.blast_sparse_mlp(*args), "blast_sparse_mlp")
+    else:
+        _check(L.blast_sparse_mlp_events(*args, events), "blast_sparse_mlp_events")
     return Y
+
+
+def bsr_gated_spmm(gate: PackedBsr, up: PackedBsr, X: torch.Tensor, *, layout: int = TOKEN_MAJOR, act: str = "silu",
+                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_bsr_gated_spmm: H = act(Wgate * X) (.) (Wup * X), bf16, same layout as X."""
+    L = lib()
+    T, K, ldx = _layout_dims(X, layout)
+    assert K == gate.cols
+    H = out if out is not None else _alloc_out(gate.rows, T, layout, torch.bfloat16, X.device)
+    vg, vu = gate.view(), up.view()
+    _check(L.blast_bsr_gated_spmm(C.byref(vg), C.byref(vu), _ptr(X), ldx, layout, T, ACT[act], _ptr(H), H.stride(0),
+                                  _stream()), "blast_bsr_gated_spmm")
+    return H

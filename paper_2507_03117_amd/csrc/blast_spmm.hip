@@ -350,10 +350,10 @@ extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const bla
   return BLAST_OK;
 }
 
-extern "C" int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
-                                const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y,
-                                int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes, void* stream_) {
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
+namespace {
+
+int check_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown, const uint16_t* X,
+              int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype) {
   if (int rc = check_view(Wgate)) return rc;
   if (int rc = check_view(Wup)) return rc;
   if (int rc = check_view(Wdown)) return rc;
@@ -366,24 +366,42 @@ extern "C" int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_vie
   if (y_dtype != BLAST_F32 && y_dtype != BLAST_BF16) return BLAST_ERR_INVALID_ARG;
   if (int rc = check_dense(X, ldx, x_layout, E, T)) return rc;
   if (int rc = check_dense(Y, ldy, x_layout, E, T)) return rc;
+  return BLAST_OK;
+}
+
+// H = act(Wgate X) (.) (Wup X), bf16, strides given by (h_layout, ldh).
+int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const uint16_t* X, int64_t ldx,
+                  int32_t x_layout, int64_t T, int32_t act, uint16_t* H, int64_t ldh, int32_t h_layout,
+                  hipStream_t stream) {
+  TileArgs g{};
+  g.m0 = mat_of(Wgate);
+  g.m1 = mat_of(Wup);
+  g.row_order = Wgate->row_order;
+  set_x(g, X, ldx, x_layout);
+  set_y(g, H, ldh, h_layout, BLAST_BF16);
+  g.T = (int)T;
+  g.nbr = (int)(Wgate->rows / Wgate->b);
+  g.act = act;
+  return dispatch_tile<true>(Wgate->b, g, stream);
+}
+
+int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
+                const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy,
+                int32_t y_dtype, void* ws, size_t ws_bytes, hipStream_t stream, void* const* events) {
+  if (int rc = check_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype)) return rc;
+  const int64_t I = Wgate->rows, E = Wgate->cols;
+  const int32_t b = Wgate->b;
   if (T == 0 || E == 0) return BLAST_OK;
   size_t need = 0;
   blast_sparse_mlp_workspace(Wgate, Wup, Wdown, T, &need);
   if (need > 0 && (!ws || ws_bytes < need || !blast::aligned(ws, 256))) return BLAST_ERR_WORKSPACE;
   uint16_t* H = static_cast<uint16_t*>(ws);
 
+  if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[0]), stream));
   if (I > 0) {
-    TileArgs g{};
-    g.m0 = mat_of(Wgate);
-    g.m1 = mat_of(Wup);
-    g.row_order = Wgate->row_order;
-    set_x(g, X, ldx, x_layout);
-    set_y(g, H, I, BLAST_TOKEN_MAJOR, BLAST_BF16);
-    g.T = (int)T;
-    g.nbr = (int)(I / b);
-    g.act = act;
-    if (int rc = dispatch_tile<true>(b, g, stream)) return rc;
+    if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream)) return rc;
   }
+  if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));
   TileArgs d{};
   d.m0 = mat_of(Wdown);
   d.row_order = Wdown->row_order;
@@ -392,5 +410,39 @@ extern "C" int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_vie
   d.T = (int)T;
   d.nbr = (int)(E / b);
   d.act = 0;
-  return dispatch_tile<false>(b, d, stream);
+  if (int rc = dispatch_tile<false>(b, d, stream)) return rc;
+  if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
+  return BLAST_OK;
+}
+
+}  // namespace
+
+extern "C" int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
+                                const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y,
+                                int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes, void* stream_) {
+  return enqueue_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, ws_bytes,
+                     static_cast<hipStream_t>(stream_), nullptr);
+}
+
+extern "C" int blast_sparse_mlp_events(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
+                                       const blast_bsr_view* Wdown, const uint16_t* X, int64_t ldx, int32_t x_layout,
+                                       int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                                       size_t ws_bytes, void* stream_, void* const* events) {
+  if (!events || !events[0] || !events[1] || !events[2]) return BLAST_ERR_INVALID_ARG;
+  return enqueue_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, ws_bytes,
+                     static_cast<hipStream_t>(stream_), events);
+}
+
+extern "C" int blast_bsr_gated_spmm(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const uint16_t* X,
+                                    int64_t ldx, int32_t x_layout, int64_t T, int32_t act, uint16_t* H, int64_t ldh,
+                                    void* stream_) {
+  if (int rc = check_view(Wgate)) return rc;
+  if (int rc = check_view(Wup)) return rc;
+  if (Wup->rows != Wgate->rows || Wup->cols != Wgate->cols || Wup->b != Wgate->b) return BLAST_ERR_SHAPE;
+  if (T < 0 || T > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
+  if (act != BLAST_ACT_SILU && act != BLAST_ACT_GELU && act != BLAST_ACT_RELU) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_dense(X, ldx, x_layout, Wgate->cols, T)) return rc;
+  if (int rc = check_dense(H, ldh, x_layout, Wgate->rows, T)) return rc;
+  if (T == 0 || Wgate->rows == 0) return BLAST_OK;
+  return enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, ldh, x_layout, static_cast<hipStream_t>(stream_));
 }
