@@ -122,7 +122,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=2048, help="token count of the headline step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=96)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--copies", type=int, default=0,
+                    help="weight copies in rotation (0 = enough for 768 MB: cold HBM; 1 = warm caches)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -166,7 +168,7 @@ def main():
     g, u, d = packed
     nnz = g.nnz + u.nnz + d.nnz
     w_bytes = nnz * b * b * 2
-    n_copies = max(2, -(-768 * 1024 * 1024 // w_bytes))
+    n_copies = args.copies if args.copies > 0 else max(2, -(-768 * 1024 * 1024 // w_bytes))
     sets = list(zip(rotated_copies(g, n_copies), rotated_copies(u, n_copies), rotated_copies(d, n_copies)))
 
     def run_T(T, steps, warmup):

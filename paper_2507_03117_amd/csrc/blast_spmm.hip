@@ -12,225 +12,13 @@
 // consecutive lanes, so token-major stores are 128-byte coalesced.
 #include "blast_common.h"
 
+#include "kern_common.h"
+#include "kern_tile.h"
+#include "kern_stream.h"
+
+using namespace blast_dev;
+
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-struct MatDev {
-  const int* row_ptr;
-  const int* col_idx;
-  const uint16_t* vals;
-};
-
-struct TileArgs {
-  MatDev m0, m1;         // m1 only for the dual (gate/up) kernel
-  const int* row_order;  // may be null
-  const uint16_t* X;
-  int64_t sxt, sxk;      // element strides of X along tokens / features
-  void* Y;
-  int64_t syt, syi;      // element strides of Y along tokens / rows
-  int y_bf16;
-  int T;
-  int nbr;               // block rows of the output
-  int ntt;               // token tiles
-  int act;
-  int x_vec;             // 1: 16-byte loads of X are legal (sxk == 1, aligned)
-};
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ float apply_act(int act, float g) {
-  if (act == BLAST_ACT_SILU) return g / (1.0f + __expf(-g));
-  if (act == BLAST_ACT_GELU) return 0.5f * g * (1.0f + erff(g * 0.70710678118654752440f));
-  return g > 0.0f ? g : 0.0f;
-}
-
-template <int B>
-struct TileCfg {
-  static constexpr int TOKW = (B == 128) ? 2 : 4;       // waves along tokens
-  static constexpr int ROWW = 4 / TOKW;                 // waves along weight rows
-  static constexpr int WT_ROW = (B >= 64) ? 64 : B;     // weight rows per wave
-  static constexpr int NI = (WT_ROW + 31) / 32;         // 32-row MFMA tiles per wave
-  static constexpr int MI = 2;                          // 32-token MFMA tiles per wave
-  static constexpr int TT = TOKW * 64;                  // tokens per workgroup tile
-  static constexpr int LD = B + 8;                      // LDS row pitch in bf16 (16-byte pad: conflict-free b128 reads)
-  static constexpr int CPR = B / 8;                     // 16-byte chunks per row
-  static constexpr int NCHW = B * CPR;                  // chunks in a weight block
-  static constexpr int NCHX = TT * CPR;                 // chunks in an X tile
-  static constexpr int WPT = (NCHW + 255) / 256;
-  static constexpr int XPT = (NCHX + 255) / 256;
-  static constexpr int KSTEPS = B / 16;
-  static constexpr size_t LDS_BYTES = (size_t)(TT + B) * LD * 2;
-};
-
-template <int B>
-struct Staged {
-  uint4 w[TileCfg<B>::WPT];
-  uint4 x[TileCfg<B>::XPT];
-};
-
-// Global -> registers for stored block k of a matrix (its values and the X slice it selects).
-template <int B>
-__device__ __forceinline__ void load_stage(const TileArgs& a, const MatDev& m, int k, int t0, Staged<B>& s) {
-  using C = TileCfg<B>;
-  const int tid = threadIdx.x;
-  const uint16_t* wblk = m.vals + (int64_t)k * B * B;
-  const int64_t c = m.col_idx[k];
-#pragma unroll
-  for (int j = 0; j < C::WPT; ++j) {
-    const int idx = tid + 256 * j;
-    if (C::NCHW % 256 == 0 || idx < C::NCHW) s.w[j] = *reinterpret_cast<const uint4*>(wblk + (int64_t)idx * 8);
-  }
-#pragma unroll
-  for (int j = 0; j < C::XPT; ++j) {
-    const int idx = tid + 256 * j;
-    const int tok = idx / C::CPR, c8 = idx % C::CPR;
-    const int t = t0 + tok;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (t < a.T) {
-      if (a.x_vec) {
-        v = *reinterpret_cast<const uint4*>(a.X + (int64_t)t * a.sxt + c * B + c8 * 8);
-      } else {
-        const uint16_t* p = a.X + (int64_t)t * a.sxt + (c * B + c8 * 8) * a.sxk;
-        uint32_t e[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) e[q] = p[q * a.sxk];
-        v = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
-      }
-    }
-    s.x[j] = v;
-  }
-}
-
-template <int B>
-__device__ __forceinline__ void store_stage(uint16_t* Xs, uint16_t* Ws, const Staged<B>& s) {
-  using C = TileCfg<B>;
-  const int tid = threadIdx.x;
-#pragma unroll
-  for (int j = 0; j < C::WPT; ++j) {
-    const int idx = tid + 256 * j;
-    if (C::NCHW % 256 == 0 || idx < C::NCHW)
-      *reinterpret_cast<uint4*>(Ws + (idx / C::CPR) * C::LD + (idx % C::CPR) * 8) = s.w[j];
-  }
-#pragma unroll
-  for (int j = 0; j < C::XPT; ++j) {
-    const int idx = tid + 256 * j;
-    *reinterpret_cast<uint4*>(Xs + (idx / C::CPR) * C::LD + (idx % C::CPR) * 8) = s.x[j];
-  }
-}
-
-// acc[mi][ni] += Xtile(wave's 64 tokens) * Wblock(wave's rows)^T from LDS.
-template <int B>
-__device__ __forceinline__ void mma_stage(const uint16_t* Xs, const uint16_t* Ws, int tw, int rw,
-                                          f32x16 (&acc)[TileCfg<B>::MI][TileCfg<B>::NI]) {
-  using C = TileCfg<B>;
-  const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
-#pragma unroll
-  for (int kk = 0; kk < C::KSTEPS; ++kk) {
-    bf16x8 af[C::MI], bfg[C::NI];
-#pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi)
-      af[mi] = *reinterpret_cast<const bf16x8*>(Xs + (tw * 64 + mi * 32 + l32) * C::LD + kk * 16 + lh * 8);
-#pragma unroll
-    for (int ni = 0; ni < C::NI; ++ni) {
-      if (C::WT_ROW >= 32 || l32 < C::WT_ROW) {
-        bfg[ni] = *reinterpret_cast<const bf16x8*>(Ws + (rw * C::WT_ROW + ni * 32 + l32) * C::LD + kk * 16 + lh * 8);
-      } else {
-        bfg[ni] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-      }
-    }
-#pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfg[ni], acc[mi][ni], 0, 0, 0);
-  }
-}
-
-// All stored blocks of block row r of matrix m, register-prefetched one block ahead.
-template <int B>
-__device__ __forceinline__ void run_row(const TileArgs& a, const MatDev& m, int r, int t0, uint16_t* Xs, uint16_t* Ws,
-                                        int tw, int rw, f32x16 (&acc)[TileCfg<B>::MI][TileCfg<B>::NI]) {
-  const int kb = m.row_ptr[r], ke = m.row_ptr[r + 1];
-  Staged<B> st;
-  if (kb < ke) load_stage<B>(a, m, kb, t0, st);
-  for (int k = kb; k < ke; ++k) {
-    __syncthreads();  // everyone is done reading the previous stage
-    store_stage<B>(Xs, Ws, st);
-    __syncthreads();
-    if (k + 1 < ke) load_stage<B>(a, m, k + 1, t0, st);
-    mma_stage<B>(Xs, Ws, tw, rw, acc);
-  }
-}
-
-// One workgroup = one (block row, token tile).  DUAL: two matrices with the same
-// shape share the tile; the epilogue writes bf16 act(acc0) * acc1.
-template <int B, bool DUAL>
-__global__ __launch_bounds__(256) void k_spmm_tile(const TileArgs a) {
-  using C = TileCfg<B>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* Xs = reinterpret_cast<uint16_t*>(smem);
-  uint16_t* Ws = Xs + C::TT * C::LD;
-
-  const int wg = blockIdx.x;
-  const int rank = wg / a.ntt, tt = wg % a.ntt;
-  const int r = a.row_order ? a.row_order[rank] : rank;
-  const int t0 = tt * C::TT;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
-  const int tw = wave % C::TOKW, rw = wave / C::TOKW;
-
-  f32x16 acc0[C::MI][C::NI];
-#pragma unroll
-  for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = 0.0f;
-  run_row<B>(a, a.m0, r, t0, Xs, Ws, tw, rw, acc0);
-
-  if (DUAL) {
-    f32x16 acc1[C::MI][C::NI];
-#pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc1[mi][ni][j] = 0.0f;
-    run_row<B>(a, a.m1, r, t0, Xs, Ws, tw, rw, acc1);
-#pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = apply_act(a.act, acc0[mi][ni][j]) * acc1[mi][ni][j];
-  }
-
-  // Result layout of the 32x32 MFMA: lane -> column (weight row) l32, register j -> token 8*(j/4) + 4*lh + j%4.
-  if (C::WT_ROW < 32 && l32 >= C::WT_ROW) return;
-#pragma unroll
-  for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < C::NI; ++ni) {
-      const int64_t row = (int64_t)r * B + rw * C::WT_ROW + ni * 32 + l32;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int tok = t0 + tw * 64 + mi * 32 + 8 * (j / 4) + 4 * lh + (j % 4);
-        if (tok < a.T) {
-          const float v = acc0[mi][ni][j];
-          const int64_t off = (int64_t)tok * a.syt + row * a.syi;
-          if (a.y_bf16)
-            reinterpret_cast<uint16_t*>(a.Y)[off] = f32_to_bf16_rne(v);
-          else
-            reinterpret_cast<float*>(a.Y)[off] = v;
-        }
-      }
-    }
-}
 
 template <int B, bool DUAL>
 int launch_tile(TileArgs a, hipStream_t stream) {
@@ -250,8 +38,55 @@ int launch_tile(TileArgs a, hipStream_t stream) {
   return BLAST_OK;
 }
 
+int cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+template <int B, bool DUAL>
+int launch_stream(TileArgs a, hipStream_t stream) {
+  using C = StreamCfg<B>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
+    attr_set = true;
+  }
+  a.ntt = (a.T + C::TT - 1) / C::TT;
+  const int64_t n_items = (int64_t)a.ntt * a.nbr;
+  if (n_items <= 0) return BLAST_OK;
+  if (n_items > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
+  int shift = -1;
+  for (int q = 0; q < 31; ++q)
+    if ((1 << q) == a.ntt) shift = q;
+  StreamArgs sa{a, (int)n_items, shift};
+  int64_t grid = (n_items + 7) / 8 * 8;
+  const int64_t resident = (int64_t)cu_count() * C::WG_PER_CU / 8 * 8;
+  if (grid > resident) grid = resident;
+  k_spmm_stream<B, DUAL><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
+  BLAST_LAUNCH_CHECK("k_spmm_stream");
+  return BLAST_OK;
+}
+
 template <bool DUAL>
 int dispatch_tile(int b, const TileArgs& a, hipStream_t stream) {
+  // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
+  const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
+  if (a.x_vec && a.T > 0 && small_x) {
+    switch (b) {
+      case 32: return launch_stream<32, DUAL>(a, stream);
+      case 64: return launch_stream<64, DUAL>(a, stream);
+      case 128: return launch_stream<128, DUAL>(a, stream);
+      default: break;
+    }
+  }
   switch (b) {
     case 16: return launch_tile<16, DUAL>(a, stream);
     case 32: return launch_tile<32, DUAL>(a, stream);
@@ -297,9 +132,11 @@ void set_x(TileArgs& a, const uint16_t* X, int64_t ldx, int32_t layout) {
 void set_y(TileArgs& a, void* Y, int64_t ldy, int32_t layout, int32_t y_dtype) {
   a.Y = Y;
   a.y_bf16 = (y_dtype == BLAST_BF16) ? 1 : 0;
+  a.y_vec = 0;
   if (layout == BLAST_TOKEN_MAJOR) {
     a.syt = ldy;
     a.syi = 1;
+    a.y_vec = (ldy % 4 == 0 && blast::aligned(Y, 16)) ? 1 : 0;
   } else {
     a.syt = 1;
     a.syi = ldy;

@@ -1,0 +1,53 @@
+// Device-side helpers shared by the product kernels.
+#pragma once
+#include "blast_common.h"
+
+namespace blast_dev {
+
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct MatDev {
+  const int* row_ptr;
+  const int* col_idx;
+  const uint16_t* vals;
+};
+
+struct TileArgs {
+  MatDev m0, m1;         // m1 only for the dual (gate/up) kernel
+  const int* row_order;  // may be null
+  const uint16_t* X;
+  int64_t sxt, sxk;      // element strides of X along tokens / features
+  void* Y;
+  int64_t syt, syi;      // element strides of Y along tokens / rows
+  int y_bf16;
+  int T;
+  int nbr;               // block rows of the output
+  int ntt;               // token tiles
+  int act;
+  int x_vec;             // 1: 16-byte loads of X are legal (sxk == 1, aligned)
+  int y_vec;             // 1: four consecutive rows of one token may be stored as one vector (syi == 1, aligned)
+};
+
+// Index arrays are read-only for the lifetime of a launch: reading them through the
+// constant address space lets uniform loads go through the scalar unit, so they never
+// sit in the vector-memory counter that the DMA pipeline is tracked with.
+__device__ __forceinline__ int ld_idx(const int* p, int i) {
+  return reinterpret_cast<const __attribute__((address_space(4))) int*>(reinterpret_cast<uintptr_t>(p))[i];
+}
+
+// fp32 -> bf16, round to nearest even (the hardware conversion of gfx950).
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  const __bf16 h = static_cast<__bf16>(f);
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ float apply_act(int act, float g) {
+  if (act == BLAST_ACT_SILU) return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+  if (act == BLAST_ACT_GELU) return 0.5f * g * (1.0f + erff(g * 0.70710678118654752440f));
+  return g > 0.0f ? g : 0.0f;
+}
+
+
+}  // namespace blast_dev
