@@ -15,6 +15,7 @@
 #include "kern_common.h"
 #include "kern_tile.h"
 #include "kern_stream.h"
+#include "kern_decode.h"
 
 using namespace blast_dev;
 
@@ -75,10 +76,49 @@ int launch_stream(TileArgs a, hipStream_t stream) {
   return BLAST_OK;
 }
 
+template <int B, bool DUAL, int NTT>
+int launch_decode_ntt(const TileArgs& a, hipStream_t stream) {
+  DecArgs d{};
+  d.m0 = a.m0;
+  d.m1 = a.m1;
+  d.X = a.X;
+  d.sxt = a.sxt;
+  d.Y = a.Y;
+  d.syt = a.syt;
+  d.syi = a.syi;
+  d.y_bf16 = a.y_bf16;
+  d.T = a.T;
+  d.act = a.act;
+  const int64_t grid = (int64_t)a.nbr * (B / 16);
+  if (grid <= 0) return BLAST_OK;
+  if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
+  k_decode<B, DUAL, NTT><<<dim3((unsigned)grid), dim3(256), 0, stream>>>(d);
+  BLAST_LAUNCH_CHECK("k_decode");
+  return BLAST_OK;
+}
+
+template <int B, bool DUAL>
+int launch_decode(const TileArgs& a, hipStream_t stream) {
+  if (a.T <= 16) return launch_decode_ntt<B, DUAL, 1>(a, stream);
+  if (a.T <= 32) return launch_decode_ntt<B, DUAL, 2>(a, stream);
+  if (a.T <= 64) return launch_decode_ntt<B, DUAL, 4>(a, stream);
+  return launch_decode_ntt<B, DUAL, 8>(a, stream);
+}
+
+constexpr int kDecodeMaxTokens = 32;  // beyond this the streaming kernel is faster (measured)
+
 template <bool DUAL>
 int dispatch_tile(int b, const TileArgs& a, hipStream_t stream) {
   // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
+  if (a.x_vec && a.T > 0 && a.T <= kDecodeMaxTokens && small_x) {
+    switch (b) {
+      case 32: return launch_decode<32, DUAL>(a, stream);
+      case 64: return launch_decode<64, DUAL>(a, stream);
+      case 128: return launch_decode<128, DUAL>(a, stream);
+      default: break;
+    }
+  }
   if (a.x_vec && a.T > 0 && small_x) {
     switch (b) {
       case 32: return launch_stream<32, DUAL>(a, stream);
