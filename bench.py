@@ -34,7 +34,13 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch sequence from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), scaled by the
 # factor a plain copy kernel of known size reads on the same counters.  Filled from profiles/*.txt.
-MEASURED_TRAFFIC_BYTES = {}
+# Source: profiles/bench_llama1b_b64_s90_hbm_traffic.txt (read x2.0, write x1.0; counters sit between each XCD's
+# L2 and the fabric).  Keys: (kernel, tokens) of the default workload.
+MEASURED_TRAFFIC_BYTES = {
+    ("gate_up", 2048): 63.41e6 + 39.84e6,
+    ("mlp", 1): (7.12e6 + 0.14e6) + (4.30e6 + 0.07e6),
+    ("mlp", 16): (7.12e6 + 0.14e6) + (4.30e6 + 0.07e6),
+}
 
 
 def hip_runtime():
@@ -154,7 +160,8 @@ def main():
     dM = [mask_dev(l.mask) if l.mask is not None else None for l in (inp.gate, inp.up, inp.down)]
     packed = []
     for w_, m_, l in zip(dW, dM, (inp.gate, inp.up, inp.down)):
-        packed.append(api.bsr_pack(w_, b, mask=m_) if m_ is not None else api.bsr_pack(w_, b, sparsity=l.sparsity))
+        packed.append(api.bsr_pack(w_, b, mask=m_, nnz_cap=int(l.mask.sum())) if m_ is not None
+                      else api.bsr_pack(w_, b, sparsity=l.sparsity))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     reps = 5
@@ -189,9 +196,9 @@ def main():
     gu_tflops = gu_flops / (head["ms_gate_up"] * 1e-3) / 1e12
     mfma_bound = T >= 512
     if mfma_bound:
-        roofline = dict(bound="mfma", kernel="k_spmm_tile<64,dual> (gate/up + activation)", achieved=gu_tflops,
+        roofline = dict(bound="mfma", kernel="k_spmm_stream<%d,dual> (gate/up + activation)" % b, achieved=gu_tflops,
                         peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=gu_tflops / PEAK_BF16_TFLOPS,
-                        avg_kernel_ms=head["ms_gate_up"], traffic=MEASURED_TRAFFIC_BYTES.get(("gate_up", T)))
+                        avg_kernel_ms=head["ms_gate_up"], traffic=MEASURED_TRAFFIC_BYTES.get(("gate_up", T)) if args.workload == "llama1b_b64_s90" else None)
     else:
         gbs = head["alg_bytes"] / (head["ms_events"] * 1e-3) / 1e9
         roofline = dict(bound="hbm", kernel="whole MLP pass", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
@@ -221,6 +228,7 @@ def main():
             dec.append({"T": Td, "ms_per_step": r["ms_per_step"], "ms_events": r["ms_events"],
                         "ms_gate_up": r["ms_gate_up"], "ms_down": r["ms_down"], "alg_MB": r["alg_bytes"] / 1e6,
                         "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get(("mlp", Td)) if args.workload == "llama1b_b64_s90" else None,
                         "TFLOPs": r["flops"] / (r["ms_events"] * 1e-3) / 1e12})
         out["decode"] = dec
 
