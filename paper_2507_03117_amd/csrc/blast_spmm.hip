@@ -51,12 +51,12 @@ int cu_count() {
   return cached[dev];
 }
 
-template <int B, bool DUAL>
-int launch_stream(TileArgs a, hipStream_t stream) {
-  using C = StreamCfg<B>;
+template <int B, bool DUAL, int TW>
+int launch_stream_tw(TileArgs a, hipStream_t stream) {
+  using C = StreamCfg<B, TW>;
   static bool attr_set = false;
   if (!attr_set) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL>),
+    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
@@ -71,9 +71,23 @@ int launch_stream(TileArgs a, hipStream_t stream) {
   int64_t grid = (n_items + 7) / 8 * 8;
   const int64_t resident = (int64_t)cu_count() * C::WG_PER_CU / 8 * 8;
   if (grid > resident) grid = resident;
-  k_spmm_stream<B, DUAL><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
+  k_spmm_stream<B, DUAL, TW><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
   BLAST_LAUNCH_CHECK("k_spmm_stream");
   return BLAST_OK;
+}
+
+template <int B, bool DUAL>
+int launch_stream(const TileArgs& a, hipStream_t stream) {
+  if constexpr (B == 128) {
+    return launch_stream_tw<B, DUAL, 2>(a, stream);
+  } else if constexpr (B == 64) {
+    // 128-token tiles when 256-token tiles would leave workgroup slots empty
+    const int64_t wide_items = (int64_t)((a.T + 255) / 256) * a.nbr;
+    if (wide_items < (int64_t)cu_count() * 2) return launch_stream_tw<B, DUAL, 2>(a, stream);
+    return launch_stream_tw<B, DUAL, 4>(a, stream);
+  } else {
+    return launch_stream_tw<B, DUAL, 4>(a, stream);
+  }
 }
 
 template <int B, bool DUAL, int NTT>

@@ -26,11 +26,16 @@ namespace blast_dev {
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding).
 #define BLAST_VMCNT(n) (0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
-template <int B>
+// TW = waves along the token dimension (4: 256-token tiles, 2: 128-token tiles).  Wide tiles read each
+// weight block once per 256 tokens; narrow tiles double the number of items, which matters when a
+// matrix has fewer (block row, token tile) pairs than the chip has workgroup slots.
+template <int B, int TW>
 struct StreamCfg {
-  static constexpr int TOKW = (B == 128) ? 2 : 4;  // waves along tokens
+  static_assert(TW == 2 || TW == 4, "two or four waves along tokens");
+  static_assert(B / (4 / TW) >= 32, "a wave needs at least 32 weight rows");
+  static constexpr int TOKW = TW;                  // waves along tokens
   static constexpr int ROWW = 4 / TOKW;            // waves along weight rows
-  static constexpr int WT_ROW = (B >= 64) ? 64 : 32;
+  static constexpr int WT_ROW = B / ROWW;          // weight rows per wave
   static constexpr int NI = WT_ROW / 32;
   static constexpr int MI = 2;
   static constexpr int TT = TOKW * 64;             // tokens per workgroup tile
@@ -44,7 +49,9 @@ struct StreamCfg {
   static constexpr int W_BYTES = B * ROW_BYTES;
   static constexpr int X_BYTES = TT * ROW_BYTES;
   static constexpr int STAGE = W_BYTES + X_BYTES;
-  static constexpr int NSTAGE = 2;
+  // as many stages as fit in half of a CU's LDS (two workgroups per CU), at most 4
+  static constexpr int NSTAGE_FIT = (80 * 1024) / STAGE;
+  static constexpr int NSTAGE = NSTAGE_FIT >= 4 ? 4 : (NSTAGE_FIT >= 2 ? NSTAGE_FIT : 2);
   static constexpr int W_INSTR = W_BYTES / 1024;
   static constexpr int X_INSTR = X_BYTES / 1024;
   static constexpr int WQ = (W_INSTR + 3) / 4;     // copy instructions per wave and step (weights)
@@ -126,9 +133,9 @@ struct StepCursor {
   }
 };
 
-template <int B, bool DUAL>
-__global__ __launch_bounds__(256, StreamCfg<B>::WG_PER_CU) void k_spmm_stream(const StreamArgs sa) {
-  using C = StreamCfg<B>;
+template <int B, bool DUAL, int TW>
+__global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_stream(const StreamArgs sa) {
+  using C = StreamCfg<B, TW>;
   const TileArgs& a = sa.t;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
