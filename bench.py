@@ -173,6 +173,7 @@ def main():
     dense_bytes = sum(int(w_.numel()) * 2 for w_ in dW)
     del dW
     g, u, d = packed
+    g = api.with_joint_row_order(g, u)
     nnz = g.nnz + u.nnz + d.nnz
     w_bytes = nnz * b * b * 2
     n_copies = args.copies if args.copies > 0 else max(2, -(-768 * 1024 * 1024 // w_bytes))

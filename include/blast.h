@@ -135,6 +135,16 @@ int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, i
                    size_t ws_bytes, void* stream);
 
 /*
+ * Schedule for two matrices that are multiplied together row by row (W_gate and W_up of Eq. (1)):
+ * row_order[rank] = block rows sorted by the SUM of their stored-block counts, descending, stable.
+ * Passing it as Wgate->row_order lets the gated product balance its workgroups on the work they really
+ * do (Sec. 3.4.1 derives the launch grid from the stored blocks for the same reason).  A and B must have the
+ * same number of rows and the same block size.  row_order: out, [rows/b].  Enqueues one small kernel;
+ * never synchronises.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, HIP.
+ */
+int blast_bsr_joint_row_order(const blast_bsr_view* A, const blast_bsr_view* B, int32_t* row_order, void* stream);
+
+/*
  * Block-sparse product Y = W * X (Sec. 3.4, Listing 2: for every output tile,
  * loop over the stored blocks of its block row, load the block and the matching
  * slice of X through the index array, accumulate).  bf16 x bf16 products,

@@ -24,7 +24,7 @@ ACT = {"silu": 0, "gelu": 1, "relu": 2}
 EXPORTS = (
     "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
-    "blast_sparse_mlp_events", "blast_bsr_gated_spmm",
+    "blast_sparse_mlp_events", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
 
@@ -77,6 +77,8 @@ def lib():
         L.blast_sparse_mlp_workspace.argtypes = [pv, pv, pv, i64, C.POINTER(sz)]
         L.blast_sparse_mlp_events.restype = C.c_int
         L.blast_sparse_mlp_events.argtypes = L.blast_sparse_mlp.argtypes + [C.POINTER(vp)]
+        L.blast_bsr_joint_row_order.restype = C.c_int
+        L.blast_bsr_joint_row_order.argtypes = [pv, pv, vp, vp]
         L.blast_bsr_gated_spmm.restype = C.c_int
         L.blast_bsr_gated_spmm.argtypes = [pv, pv, vp, i64, i32, i64, i32, vp, i64, vp]
         _lib = L
@@ -153,6 +155,18 @@ def bsr_pack(W: torch.Tensor, b: int, *, mask: Optional[torch.Tensor] = None, sp
     _check(rc, "blast_bsr_pack")
     torch.cuda.current_stream().synchronize()  # ws is released on return
     return PackedBsr(rows, cols, b, int(nnz.value), row_ptr, col_idx, vals, row_order, aux)
+
+
+def with_joint_row_order(gate: PackedBsr, up: PackedBsr) -> PackedBsr:
+    """blast_bsr_joint_row_order: the same packed gate matrix (shared arrays) whose schedule accounts for
+    the blocks of `up` as well.  Use the result as the `gate` argument of sparse_mlp / bsr_gated_spmm."""
+    import dataclasses
+
+    order = torch.empty_like(gate.row_order)
+    vg, vu = gate.view(), up.view()
+    _check(lib().blast_bsr_joint_row_order(C.byref(vg), C.byref(vu), _ptr(order), _stream()),
+           "blast_bsr_joint_row_order")
+    return dataclasses.replace(gate, row_order=order)
 
 
 def _layout_dims(X: torch.Tensor, layout: int):

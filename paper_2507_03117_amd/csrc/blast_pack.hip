@@ -210,13 +210,17 @@ __global__ __launch_bounds__(256) void k_gather_blocks(const uint16_t* __restric
 
 // row_order[rank] = r with rank = number of rows that sort before r under
 // (population descending, row index ascending) -- a stable sort by counting.
-__global__ __launch_bounds__(256) void k_row_order(const int* __restrict__ row_ptr, int nbr, int* __restrict__ row_order) {
+// row_ptr2 (may be null) adds the populations of a second matrix with the same block rows.
+__global__ __launch_bounds__(256) void k_row_order(const int* __restrict__ row_ptr, const int* __restrict__ row_ptr2,
+                                                   int nbr, int* __restrict__ row_order) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= nbr) return;
-  const int cr = row_ptr[r + 1] - row_ptr[r];
+  int cr = row_ptr[r + 1] - row_ptr[r];
+  if (row_ptr2) cr += row_ptr2[r + 1] - row_ptr2[r];
   int rank = 0;
   for (int q = 0; q < nbr; ++q) {
-    const int cq = row_ptr[q + 1] - row_ptr[q];
+    int cq = row_ptr[q + 1] - row_ptr[q];
+    if (row_ptr2) cq += row_ptr2[q + 1] - row_ptr2[q];
     rank += (cq > cr || (cq == cr && q < r)) ? 1 : 0;
   }
   row_order[rank] = r;
@@ -379,7 +383,7 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   if (nbr > 0) {
     k_fill_cols<<<dim3((unsigned)nbr), dim3(256), 0, stream>>>(mask, (int)nbc, row_ptr, col_idx, blk_row, nnz_cap);
     BLAST_LAUNCH_CHECK("k_fill_cols");
-    k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, (int)nbr, row_order);
+    k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, nullptr, (int)nbr, row_order);
     BLAST_LAUNCH_CHECK("k_row_order");
   }
   if (nnz_host > 0) {
@@ -405,5 +409,20 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
       BLAST_LAUNCH_CHECK("k_fill_csc");
     }
   }
+  return BLAST_OK;
+}
+
+extern "C" int blast_bsr_joint_row_order(const blast_bsr_view* A, const blast_bsr_view* Bm, int32_t* row_order,
+                                         void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!A || !Bm || !A->row_ptr || !Bm->row_ptr) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_shape(A->rows, A->cols, A->b)) return rc;
+  if (A->rows != Bm->rows || A->b != Bm->b) return BLAST_ERR_SHAPE;
+  const int64_t nbr = A->rows / A->b;
+  if (nbr == 0) return BLAST_OK;
+  if (!row_order) return BLAST_ERR_INVALID_ARG;
+  k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(A->row_ptr, Bm->row_ptr, (int)nbr,
+                                                                              row_order);
+  BLAST_LAUNCH_CHECK("k_row_order(joint)");
   return BLAST_OK;
 }

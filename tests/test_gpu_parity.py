@@ -248,6 +248,29 @@ def test_mlp_dense_and_all_pruned(api):
     _mlp_case(api, 3201, 128, 256, 64, 1.0, 20)
 
 
+def test_joint_row_order(api):
+    import torch
+
+    rng = np.random.default_rng(77)
+    b, nbr, nbc = 32, 40, 12
+    g, u = (synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.05) for _ in range(2))
+    mg, mu = (synth.uniform_mask(rng, nbr, nbc, 0.6) for _ in range(2))
+    mg[3, :] = 0
+    mu[3, :] = 0
+    dg, rg = pack_both(api, g, b, mask=mg)
+    du, ru = pack_both(api, u, b, mask=mu)
+    gj = api.with_joint_row_order(dg, du)
+    torch.cuda.synchronize()
+    cnt = np.diff(rg.row_ptr) + np.diff(ru.row_ptr)
+    assert np.array_equal(gj.row_order.cpu().numpy(), np.argsort(-cnt, kind="stable"))
+    # results do not depend on the schedule
+    x = synth.gauss_bf16(rng, (300, nbc * b), 1.0)
+    h1 = api.bsr_gated_spmm(dg, du, to_dev(x))
+    h2 = api.bsr_gated_spmm(gj, du, to_dev(x))
+    torch.cuda.synchronize()
+    assert torch.equal(h1.view(torch.int16), h2.view(torch.int16))
+
+
 def test_mlp_repeatable(api):
     import torch
 
