@@ -66,16 +66,16 @@ extern "C" {
 typedef struct blast_bsr_view {
   int64_t rows, cols;       /* logical size; both multiples of b */
   int32_t b;                /* block edge: 16, 32, 64 or 128 */
-  int32_t reserved;         /* set to 0 */
+  int32_t heavy_rows;       /* number of block rows cut into several chunks, as reported by blast_bsr_pack;
+                               0 = unknown or none (rows are then never split) */
   int64_t nnz;              /* number of stored blocks */
   const int32_t* row_ptr;   /* [rows/b + 1], row_ptr[0] = 0, non-decreasing, row_ptr[rows/b] = nnz */
   const int32_t* col_idx;   /* [nnz], block-column of each stored block, strictly ascending inside a block row */
   const uint16_t* vals;     /* [nnz * b * b] bf16, block k occupies vals[k*b*b ..], row-major inside the block;
                                must be 16-byte aligned */
   const int32_t* row_order; /* [rows/b] block rows by stored-block count, descending (schedule); may be NULL */
-  const void* aux;          /* column-grouped index written by blast_bsr_pack (blast_bsr_aux_bytes bytes);
-                               may be NULL for blast_bsr_spmm; blast_sparse_mlp needs it on W_down only
-                               when it reports so through BLAST_ERR_WORKSPACE (see there) */
+  const void* aux;          /* chunk plan + column-grouped index written by blast_bsr_pack
+                               (blast_bsr_aux_bytes bytes); may be NULL: rows are then never split */
 } blast_bsr_view;
 
 /* Human-readable text for an error code.  For BLAST_ERR_HIP the text of the
@@ -120,8 +120,11 @@ int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, do
  *   vals        out [nnz_cap * b * b], 16-byte aligned
  *   row_order   out [rows/b]: stable sort of block rows by stored-block count, descending (empty rows last)
  *   aux         out, aux_bytes >= blast_bsr_aux_bytes(rows, cols, b, nnz_cap), 16-byte aligned; may be NULL
- *               (then no column-grouped index is produced)
+ *               (then neither the chunk plan nor the column-grouped index is produced)
  *   nnz_out     HOST, receives the number of stored blocks (also on BLAST_ERR_CAPACITY)
+ *   heavy_rows_out  HOST, may be NULL: number of block rows holding more than 16 stored blocks; with `aux`
+ *               these rows are cut into chunks of 16 blocks that the product kernels schedule separately
+ *               ("reduces load imbalance", Sec. 3.4.1).  Copy it into blast_bsr_view.heavy_rows.  0 without aux.
  *   ws          scratch of at least the ws_bytes reported by blast_bsr_pack_bound, 16-byte aligned
  *
  * The call synchronises `stream` once (to learn nnz); when it returns BLAST_OK
@@ -131,8 +134,8 @@ int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, do
  */
 int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
                    const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx, uint16_t* vals,
-                   int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap, int64_t* nnz_out, void* ws,
-                   size_t ws_bytes, void* stream);
+                   int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap, int64_t* nnz_out,
+                   int32_t* heavy_rows_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Schedule for two matrices that are multiplied together row by row (W_gate and W_up of Eq. (1)):

@@ -36,7 +36,7 @@ class BlastError(RuntimeError):
 
 class BsrView(C.Structure):
     _fields_ = [
-        ("rows", C.c_int64), ("cols", C.c_int64), ("b", C.c_int32), ("reserved", C.c_int32), ("nnz", C.c_int64),
+        ("rows", C.c_int64), ("cols", C.c_int64), ("b", C.c_int32), ("heavy_rows", C.c_int32), ("nnz", C.c_int64),
         ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("vals", C.c_void_p), ("row_order", C.c_void_p),
         ("aux", C.c_void_p),
     ]
@@ -66,7 +66,7 @@ def lib():
         L.blast_bsr_pack_bound.argtypes = [i64, i64, i32, i32, dbl, C.POINTER(i64), C.POINTER(sz), C.POINTER(sz)]
         L.blast_bsr_pack.restype = C.c_int
         L.blast_bsr_pack.argtypes = [vp, i64, i64, i64, i32, i32, vp, dbl, vp, vp, vp, vp, vp, sz, i64,
-                                     C.POINTER(i64), vp, sz, vp]
+                                     C.POINTER(i64), C.POINTER(i32), vp, sz, vp]
         L.blast_bsr_spmm.restype = C.c_int
         L.blast_bsr_spmm.argtypes = [pv, vp, i64, i32, i64, vp, i64, i32, vp, sz, vp]
         L.blast_bsr_spmm_workspace.restype = C.c_int
@@ -114,9 +114,10 @@ class PackedBsr:
     vals: torch.Tensor  # int16 (bf16 bits) [cap * b * b]
     row_order: torch.Tensor  # int32 [rows/b]
     aux: Optional[torch.Tensor]  # uint8
+    heavy_rows: int = 0  # block rows cut into several chunks (reported by the packer)
 
     def view(self) -> BsrView:
-        return BsrView(self.rows, self.cols, self.b, 0, self.nnz, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+        return BsrView(self.rows, self.cols, self.b, self.heavy_rows, self.nnz, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
                        self.vals.data_ptr(), self.row_order.data_ptr(),
                        self.aux.data_ptr() if self.aux is not None else None)
 
@@ -148,13 +149,13 @@ def bsr_pack(W: torch.Tensor, b: int, *, mask: Optional[torch.Tensor] = None, sp
     row_order = torch.empty(max(rows // b, 1), dtype=torch.int32, device=dev)
     aux = torch.empty(max(aux_bytes, 16), dtype=torch.uint8, device=dev) if with_aux else None
     ws = torch.empty(int(wsb.value), dtype=torch.uint8, device=dev)
-    nnz = C.c_int64(-1)
+    nnz, heavy = C.c_int64(-1), C.c_int32(0)
     rc = L.blast_bsr_pack(_ptr(W), W.stride(0), rows, cols, b, mode, _ptr(mask), s, _ptr(row_ptr), _ptr(col_idx),
                           _ptr(vals), _ptr(row_order), _ptr(aux), aux_bytes if with_aux else 0, cap_v, C.byref(nnz),
-                          _ptr(ws), ws.numel(), _stream())
+                          C.byref(heavy), _ptr(ws), ws.numel(), _stream())
     _check(rc, "blast_bsr_pack")
     torch.cuda.current_stream().synchronize()  # ws is released on return
-    return PackedBsr(rows, cols, b, int(nnz.value), row_ptr, col_idx, vals, row_order, aux)
+    return PackedBsr(rows, cols, b, int(nnz.value), row_ptr, col_idx, vals, row_order, aux, int(heavy.value))
 
 
 def with_joint_row_order(gate: PackedBsr, up: PackedBsr) -> PackedBsr:

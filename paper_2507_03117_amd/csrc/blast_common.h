@@ -15,17 +15,34 @@ inline bool supported_block(int32_t b) { return b == 16 || b == 32 || b == 64 ||
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Layout of the column-grouped index ("aux") that pack writes for a matrix with
-// NBc block columns and capacity nnz_cap:  col_ptr[NBc+1] | csc_row[nnz_cap] | csc_blk[nnz_cap]
+// Block rows holding more than kChunkBlocks stored blocks are cut into chunks of at most that many
+// blocks; a chunk is the unit of work of the streaming product, so one very long row cannot become the
+// critical path of a launch (its chunks add their partial sums into the output atomically).
+constexpr int kChunkBlocks = 16;
+
+// Layout of the "aux" buffer that pack writes for a matrix with NBr block rows, NBc block columns and
+// nnz stored blocks (every offset can be recomputed from the packed view alone):
+//   chunk plan:            hdr[4] = {n_chunks, heavy_rows, kChunkBlocks, 0} |
+//                          chunk_row[cap] (bit 31: the row has several chunks) | chunk_kb[cap] | chunk_ke[cap]
+//                          in schedule order (rows by population, descending), cap = NBr + NBr*NBc/kChunkBlocks + 1
+//   column-grouped index:  col_ptr[NBc+1] | csc_row[nnz] | csc_blk[nnz]
+// The buffer is sized with nnz = nnz_cap; the arrays are placed with the actual nnz.
 struct AuxLayout {
-  size_t col_ptr_off, csc_row_off, csc_blk_off, bytes;
+  size_t hdr_off, chunk_row_off, chunk_kb_off, chunk_ke_off, col_ptr_off, csc_row_off, csc_blk_off, bytes;
+  int64_t chunk_cap;
 };
-inline AuxLayout aux_layout(int64_t nbc, int64_t nnz_cap) {
+inline AuxLayout aux_layout(int64_t nbr, int64_t nbc, int64_t nnz) {
   AuxLayout L;
-  L.col_ptr_off = 0;
-  L.csc_row_off = align_up(sizeof(int32_t) * (size_t)(nbc + 1), 16);
-  L.csc_blk_off = L.csc_row_off + align_up(sizeof(int32_t) * (size_t)nnz_cap, 16);
-  L.bytes = L.csc_blk_off + align_up(sizeof(int32_t) * (size_t)nnz_cap, 16);
+  L.chunk_cap = nbr + (nbr * nbc) / kChunkBlocks + 1;
+  const size_t cb = align_up(sizeof(int32_t) * (size_t)L.chunk_cap, 16);
+  L.hdr_off = 0;
+  L.chunk_row_off = 16;
+  L.chunk_kb_off = L.chunk_row_off + cb;
+  L.chunk_ke_off = L.chunk_kb_off + cb;
+  L.col_ptr_off = L.chunk_ke_off + cb;
+  L.csc_row_off = L.col_ptr_off + align_up(sizeof(int32_t) * (size_t)(nbc + 1), 16);
+  L.csc_blk_off = L.csc_row_off + align_up(sizeof(int32_t) * (size_t)nnz, 16);
+  L.bytes = L.csc_blk_off + align_up(sizeof(int32_t) * (size_t)nnz, 16);
   return L;
 }
 

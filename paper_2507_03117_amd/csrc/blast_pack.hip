@@ -257,6 +257,54 @@ __global__ __launch_bounds__(256) void k_fill_csc(const uint8_t* __restrict__ ma
   }
 }
 
+// Single workgroup: cut the block rows, in schedule order, into chunks of at most `chunk` blocks.
+// hdr = {n_chunks, heavy_rows, chunk, 0}.  An empty row still gets one (empty) chunk: its output has
+// to be written.
+__global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row_ptr, const int* __restrict__ row_order,
+                                                     int nbr, int chunk, int* __restrict__ hdr,
+                                                     int* __restrict__ chunk_row, int* __restrict__ chunk_kb,
+                                                     int* __restrict__ chunk_ke, int64_t chunk_cap) {
+  __shared__ int wave_tot[16];
+  __shared__ int s_running, s_heavy;
+  if (threadIdx.x == 0) {
+    s_running = 0;
+    s_heavy = 0;
+  }
+  __syncthreads();
+  for (int base = 0; base < nbr; base += blockDim.x) {
+    const int rank = base + threadIdx.x;
+    int r = 0, kb = 0, ke = 0, nch = 0;
+    if (rank < nbr) {
+      r = row_order[rank];
+      kb = row_ptr[r];
+      ke = row_ptr[r + 1];
+      nch = (ke - kb + chunk - 1) / chunk;
+      if (nch < 1) nch = 1;
+      if (nch > 1) atomicAdd(&s_heavy, 1);
+    }
+    int total;
+    const int first = s_running + block_exscan(nch, wave_tot, total);
+    for (int j = 0; j < nch; ++j) {
+      const int64_t e = (int64_t)first + j;
+      if (e < chunk_cap) {
+        chunk_row[e] = r | (nch > 1 ? (int)0x80000000u : 0);
+        const int b0 = kb + j * chunk;
+        chunk_kb[e] = b0;
+        chunk_ke[e] = (b0 + chunk < ke) ? b0 + chunk : ke;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) s_running += total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    hdr[0] = s_running;
+    hdr[1] = s_heavy;
+    hdr[2] = chunk;
+    hdr[3] = 0;
+  }
+}
+
 struct PackWs {
   size_t scores_off, mask_off, rcnt_off, ccnt_off, blk_row_off, scalars_off, bytes;
 };
@@ -302,7 +350,7 @@ extern "C" int64_t blast_n_keep(int64_t n_blocks, double sparsity) {
 
 extern "C" size_t blast_bsr_aux_bytes(int64_t rows, int64_t cols, int32_t b, int64_t nnz_cap) {
   if (check_shape(rows, cols, b) != BLAST_OK || nnz_cap < 0) return 0;
-  return blast::aux_layout(cols / b, nnz_cap).bytes;
+  return blast::aux_layout(rows / b, cols / b, nnz_cap).bytes;
 }
 
 extern "C" int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, double sparsity,
@@ -316,7 +364,7 @@ extern "C" int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32
     if (cap < 0) return BLAST_ERR_INVALID_ARG;
   }
   if (nnz_cap) *nnz_cap = cap;
-  if (aux_bytes) *aux_bytes = blast::aux_layout(nbc, cap).bytes;
+  if (aux_bytes) *aux_bytes = blast::aux_layout(nbr, nbc, cap).bytes;
   if (ws_bytes) *ws_bytes = pack_ws_layout(nbr, nbc, mode, cap).bytes;
   return BLAST_OK;
 }
@@ -324,7 +372,7 @@ extern "C" int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32
 extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
                               const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx,
                               uint16_t* vals, int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap,
-                              int64_t* nnz_out, void* ws, size_t ws_bytes, void* stream_) {
+                              int64_t* nnz_out, int32_t* heavy_rows_out, void* ws, size_t ws_bytes, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (mode != BLAST_PACK_MASK && mode != BLAST_PACK_TOPK_FROBENIUS) return BLAST_ERR_INVALID_ARG;
   if (int rc = check_shape(rows, cols, b)) return rc;
@@ -341,7 +389,7 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   if (nbr > 0 && !row_order) return BLAST_ERR_INVALID_ARG;
   const PackWs L = pack_ws_layout(nbr, nbc, mode, nnz_cap);
   if (!ws || ws_bytes < L.bytes || !blast::aligned(ws, 16)) return BLAST_ERR_WORKSPACE;
-  const blast::AuxLayout A = blast::aux_layout(nbc, nnz_cap);
+  const blast::AuxLayout A = blast::aux_layout(nbr, nbc, nnz_cap);
   if (aux && (aux_bytes < A.bytes || !blast::aligned(aux, 16))) return BLAST_ERR_WORKSPACE;
 
   char* wsb = static_cast<char*>(ws);
@@ -374,17 +422,34 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   }
   k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(rcnt, (int)nbr, row_ptr, nnz_dev);
   BLAST_LAUNCH_CHECK("k_exscan(rows)");
-  int nnz_host = 0;
-  BLAST_HIP_TRY(hipMemcpyAsync(&nnz_host, nnz_dev, sizeof(int), hipMemcpyDeviceToHost, stream));
+  // The schedule and the chunk plan depend on the populations only: they are written before the
+  // synchronisation so that the number of heavy rows comes back to the host with nnz.
+  int host_vals[2] = {0, 0};
+  int* hdr_dev = nullptr;
+  if (nbr > 0) {
+    k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, nullptr, (int)nbr, row_order);
+    BLAST_LAUNCH_CHECK("k_row_order");
+  }
+  if (aux) {
+    char* ab = static_cast<char*>(aux);
+    hdr_dev = reinterpret_cast<int*>(ab + A.hdr_off);
+    k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr, row_order, (int)nbr, blast::kChunkBlocks, hdr_dev,
+                                                     reinterpret_cast<int*>(ab + A.chunk_row_off),
+                                                     reinterpret_cast<int*>(ab + A.chunk_kb_off),
+                                                     reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap);
+    BLAST_LAUNCH_CHECK("k_chunk_plan");
+    BLAST_HIP_TRY(hipMemcpyAsync(&host_vals[1], hdr_dev + 1, sizeof(int), hipMemcpyDeviceToHost, stream));
+  }
+  BLAST_HIP_TRY(hipMemcpyAsync(&host_vals[0], nnz_dev, sizeof(int), hipMemcpyDeviceToHost, stream));
   BLAST_HIP_TRY(hipStreamSynchronize(stream));
+  const int nnz_host = host_vals[0];
   *nnz_out = nnz_host;
+  if (heavy_rows_out) *heavy_rows_out = aux ? host_vals[1] : 0;
   if (nnz_host > nnz_cap) return BLAST_ERR_CAPACITY;
 
   if (nbr > 0) {
     k_fill_cols<<<dim3((unsigned)nbr), dim3(256), 0, stream>>>(mask, (int)nbc, row_ptr, col_idx, blk_row, nnz_cap);
     BLAST_LAUNCH_CHECK("k_fill_cols");
-    k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, nullptr, (int)nbr, row_order);
-    BLAST_LAUNCH_CHECK("k_row_order");
   }
   if (nnz_host > 0) {
     k_gather_blocks<<<dim3((unsigned)nnz_host), dim3(256), 0, stream>>>(W, ldw, b, col_idx, blk_row, vals);
@@ -392,9 +457,10 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   }
   if (aux) {
     char* ab = static_cast<char*>(aux);
-    int* col_ptr = reinterpret_cast<int*>(ab + A.col_ptr_off);
-    int* csc_row = reinterpret_cast<int*>(ab + A.csc_row_off);
-    int* csc_blk = reinterpret_cast<int*>(ab + A.csc_blk_off);
+    const blast::AuxLayout An = blast::aux_layout(nbr, nbc, nnz_host);  // the index is placed by the actual nnz
+    int* col_ptr = reinterpret_cast<int*>(ab + An.col_ptr_off);
+    int* csc_row = reinterpret_cast<int*>(ab + An.csc_row_off);
+    int* csc_blk = reinterpret_cast<int*>(ab + An.csc_blk_off);
     if (nbc > 0 && nbr > 0) {
       k_line_counts<<<dim3((unsigned)((nbc + 3) / 4)), dim3(256), 0, stream>>>(mask, (int)nbc, (int)nbr, 1, nbc, ccnt);
       BLAST_LAUNCH_CHECK("k_line_counts(cols)");

@@ -51,43 +51,65 @@ int cu_count() {
   return cached[dev];
 }
 
-template <int B, bool DUAL, int TW>
-int launch_stream_tw(TileArgs a, hipStream_t stream) {
+// Chunk plan of a packed matrix, as pointers into its aux buffer (null when it is not to be used).
+struct ChunkPlan {
+  const int* hdr = nullptr;
+  const int* chunk_row = nullptr;
+  const int* chunk_kb = nullptr;
+  const int* chunk_ke = nullptr;
+  int64_t max_chunks = 0;  // host-side upper bound of hdr[0]
+};
+
+template <int B, bool DUAL, int TW, bool CHUNK>
+int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
   using C = StreamCfg<B, TW>;
   static bool attr_set = false;
   if (!attr_set) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW>),
+    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
   a.ntt = (a.T + C::TT - 1) / C::TT;
-  const int64_t n_items = (int64_t)a.ntt * a.nbr;
+  const int64_t n_items = (int64_t)a.ntt * (CHUNK ? plan.max_chunks : (int64_t)a.nbr);
   if (n_items <= 0) return BLAST_OK;
   if (n_items > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
   int shift = -1;
   for (int q = 0; q < 31; ++q)
     if ((1 << q) == a.ntt) shift = q;
-  StreamArgs sa{a, (int)n_items, shift};
+  StreamArgs sa{a, (int)n_items, shift, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
   int64_t grid = (n_items + 7) / 8 * 8;
   const int64_t resident = (int64_t)cu_count() * C::WG_PER_CU / 8 * 8;
   if (grid > resident) grid = resident;
-  k_spmm_stream<B, DUAL, TW><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
+  if (CHUNK) {
+    k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
+    BLAST_LAUNCH_CHECK("k_zero_shared_rows");
+  }
+  k_spmm_stream<B, DUAL, TW, CHUNK><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
   BLAST_LAUNCH_CHECK("k_spmm_stream");
   return BLAST_OK;
 }
 
-template <int B, bool DUAL>
-int launch_stream(const TileArgs& a, hipStream_t stream) {
+template <int B, bool DUAL, bool CHUNK>
+int launch_stream_c(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   if constexpr (B == 128) {
-    return launch_stream_tw<B, DUAL, 2>(a, stream);
+    return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, stream);
   } else if constexpr (B == 64) {
     // 128-token tiles when 256-token tiles would leave workgroup slots empty
     const int64_t wide_items = (int64_t)((a.T + 255) / 256) * a.nbr;
-    if (wide_items < (int64_t)cu_count() * 2) return launch_stream_tw<B, DUAL, 2>(a, stream);
-    return launch_stream_tw<B, DUAL, 4>(a, stream);
+    if (wide_items < (int64_t)cu_count() * 2) return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, stream);
+    return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, stream);
   } else {
-    return launch_stream_tw<B, DUAL, 4>(a, stream);
+    return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, stream);
   }
+}
+
+template <int B, bool DUAL>
+int launch_stream(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
+  if constexpr (!DUAL) {
+    // rows cut into chunks accumulate with fp32 atomics: only for fp32 output
+    if (plan.hdr && !a.y_bf16) return launch_stream_c<B, false, true>(a, plan, stream);
+  }
+  return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, stream);
 }
 
 template <int B, bool DUAL, int NTT>
@@ -122,7 +144,7 @@ int launch_decode(const TileArgs& a, hipStream_t stream) {
 constexpr int kDecodeMaxTokens = 32;  // beyond this the streaming kernel is faster (measured)
 
 template <bool DUAL>
-int dispatch_tile(int b, const TileArgs& a, hipStream_t stream) {
+int dispatch_tile(int b, const TileArgs& a, hipStream_t stream, const ChunkPlan& plan = ChunkPlan{}) {
   // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
   if (a.x_vec && a.T > 0 && a.T <= kDecodeMaxTokens && small_x) {
@@ -135,9 +157,9 @@ int dispatch_tile(int b, const TileArgs& a, hipStream_t stream) {
   }
   if (a.x_vec && a.T > 0 && small_x) {
     switch (b) {
-      case 32: return launch_stream<32, DUAL>(a, stream);
-      case 64: return launch_stream<64, DUAL>(a, stream);
-      case 128: return launch_stream<128, DUAL>(a, stream);
+      case 32: return launch_stream<32, DUAL>(a, plan, stream);
+      case 64: return launch_stream<64, DUAL>(a, plan, stream);
+      case 128: return launch_stream<128, DUAL>(a, plan, stream);
       default: break;
     }
   }
@@ -199,6 +221,21 @@ void set_y(TileArgs& a, void* Y, int64_t ldy, int32_t layout, int32_t y_dtype) {
 
 MatDev mat_of(const blast_bsr_view* v) { return MatDev{v->row_ptr, v->col_idx, v->vals}; }
 
+// The chunk plan is used only when the packer reported rows that are actually cut.
+ChunkPlan plan_of(const blast_bsr_view* v) {
+  ChunkPlan p;
+  if (!v->aux || v->heavy_rows <= 0) return p;
+  const int64_t nbr = v->rows / v->b, nbc = v->cols / v->b;
+  const blast::AuxLayout L = blast::aux_layout(nbr, nbc, v->nnz);
+  const char* ab = static_cast<const char*>(v->aux);
+  p.hdr = reinterpret_cast<const int*>(ab + L.hdr_off);
+  p.chunk_row = reinterpret_cast<const int*>(ab + L.chunk_row_off);
+  p.chunk_kb = reinterpret_cast<const int*>(ab + L.chunk_kb_off);
+  p.chunk_ke = reinterpret_cast<const int*>(ab + L.chunk_ke_off);
+  p.max_chunks = nbr + v->nnz / blast::kChunkBlocks;
+  return p;
+}
+
 }  // namespace
 
 extern "C" int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_bytes) {
@@ -227,7 +264,7 @@ extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_
   a.T = (int)T;
   a.nbr = (int)(W->rows / W->b);
   a.act = 0;
-  return dispatch_tile<false>(W->b, a, stream);
+  return dispatch_tile<false>(W->b, a, stream, plan_of(W));
 }
 
 extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
@@ -301,7 +338,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   d.T = (int)T;
   d.nbr = (int)(E / b);
   d.act = 0;
-  if (int rc = dispatch_tile<false>(b, d, stream)) return rc;
+  if (int rc = dispatch_tile<false>(b, d, stream, plan_of(Wdown))) return rc;
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
   return BLAST_OK;
 }

@@ -67,8 +67,13 @@ struct StreamCfg {
 
 struct StreamArgs {
   TileArgs t;
-  int n_items;    // nbr * ntt
+  int n_items;    // nbr * ntt (without a chunk plan)
   int ntt_shift;  // log2(ntt) when ntt is a power of two, else -1
+  // chunk plan written by the packer (CHUNK instances only): hdr[0] = number of chunks
+  const int* hdr;
+  const int* chunk_row;  // block row of the chunk; bit 31 set when the row has several chunks
+  const int* chunk_kb;   // first stored block of the chunk
+  const int* chunk_ke;   // one past its last stored block
 };
 
 // item -> (rank in the row schedule, token tile) without an integer division in the common case
@@ -93,7 +98,7 @@ __device__ __forceinline__ int item_of(int w, int round, int G) {
 }
 
 // Position of the loader in the flattened stream of steps.
-template <int NSLICE, bool DUAL>
+template <int NSLICE, bool DUAL, bool CHUNK>
 struct StepCursor {
   int round, r, tile, phase, k, kend, slice;
   bool valid;
@@ -104,7 +109,8 @@ struct StepCursor {
     kend = ld_idx(m.row_ptr, r + 1);
   }
   // Move to the first step at or after the current position (skips empty phases and items).
-  __device__ __forceinline__ void settle(const TileArgs& a, int n_items, int ntt_shift, int w, int G) {
+  __device__ __forceinline__ void settle(const StreamArgs& sa, int n_items, int w, int G) {
+    const TileArgs& a = sa.t;
     while (valid && k >= kend) {
       if (DUAL && phase == 0) {
         phase = 1;
@@ -117,26 +123,36 @@ struct StepCursor {
           break;
         }
         int rank;
-        split_item(it, a.ntt, ntt_shift, rank, tile);
-        r = a.row_order ? ld_idx(a.row_order, rank) : rank;
+        split_item(it, a.ntt, sa.ntt_shift, rank, tile);
         phase = 0;
-        enter_phase(a);
+        if (CHUNK) {
+          r = ld_idx(sa.chunk_row, rank) & 0x7FFFFFFF;
+          k = ld_idx(sa.chunk_kb, rank);
+          kend = ld_idx(sa.chunk_ke, rank);
+        } else {
+          r = a.row_order ? ld_idx(a.row_order, rank) : rank;
+          enter_phase(a);
+        }
       }
     }
   }
-  __device__ __forceinline__ void advance(const TileArgs& a, int n_items, int ntt_shift, int w, int G) {
+  __device__ __forceinline__ void advance(const StreamArgs& sa, int n_items, int w, int G) {
     if (++slice == NSLICE) {
       slice = 0;
       ++k;
-      settle(a, n_items, ntt_shift, w, G);
+      settle(sa, n_items, w, G);
     }
   }
 };
 
-template <int B, bool DUAL, int TW>
+// CHUNK: the items are (chunk of a block row, token tile) pairs from the packer's chunk plan instead of
+// (block row, token tile); a row made of several chunks adds its partial sums into a zeroed fp32 output.
+template <int B, bool DUAL, int TW, bool CHUNK>
 __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_stream(const StreamArgs sa) {
+  static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
   using C = StreamCfg<B, TW>;
   const TileArgs& a = sa.t;
+  const int n_items = CHUNK ? ld_idx(sa.hdr, 0) * a.ntt : sa.n_items;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int w = blockIdx.x, G = gridDim.x;
@@ -190,7 +206,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     for (int q = 0; q < C::XQ; ++q) BLAST_GLDS16(xcol + xoff[q], st + C::W_BYTES + (q * 4 + wave) * 1024);
   };
 
-  StepCursor<C::NSLICE, DUAL> ld;
+  StepCursor<C::NSLICE, DUAL, CHUNK> ld;
   ld.round = -1;
   ld.phase = DUAL ? 1 : 0;
   ld.k = ld.kend = 0;
@@ -198,7 +214,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
   ld.tile = 0;
   ld.slice = 0;
   ld.valid = true;
-  ld.settle(a, sa.n_items, sa.ntt_shift, w, G);
+  ld.settle(sa, n_items, w, G);
   int ld_c = 0;
   int issued = 0, done = 0;
   auto issue_next = [&]() {
@@ -206,7 +222,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     if (ld.slice == 0) ld_c = ld_idx(m.col_idx, ld.k);
     issue(m, ld.k, ld_c, ld.slice, ld.tile, issued % C::NSTAGE);
     ++issued;
-    ld.advance(a, sa.n_items, sa.ntt_shift, w, G);
+    ld.advance(sa, n_items, w, G);
   };
 #pragma unroll 1
   for (int p = 0; p < C::NSTAGE - 1; ++p)
@@ -254,10 +270,20 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
   // ---- compute: item by item -------------------------------------------------------------
   for (int round = 0;; ++round) {
     const int it = item_of(w, round, G);
-    if (it >= sa.n_items) break;
+    if (it >= n_items) break;
     int rank, tile;
     split_item(it, a.ntt, sa.ntt_shift, rank, tile);
-    const int r = a.row_order ? ld_idx(a.row_order, rank) : rank;
+    int r, n0;
+    bool shared_row = false;  // other chunks add into the same output rows
+    if (CHUNK) {
+      const int cr = ld_idx(sa.chunk_row, rank);
+      r = cr & 0x7FFFFFFF;
+      shared_row = cr < 0;
+      n0 = (ld_idx(sa.chunk_ke, rank) - ld_idx(sa.chunk_kb, rank)) * C::NSLICE;
+    } else {
+      r = a.row_order ? ld_idx(a.row_order, rank) : rank;
+      n0 = (ld_idx(a.m0.row_ptr, r + 1) - ld_idx(a.m0.row_ptr, r)) * C::NSLICE;
+    }
     const int t0 = tile * C::TT;
 
     f32x16 acc0[C::MI][C::NI];
@@ -267,10 +293,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
       for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = 0.0f;
-    {
-      const int n0 = (ld_idx(a.m0.row_ptr, r + 1) - ld_idx(a.m0.row_ptr, r)) * C::NSLICE;
-      for (int s = 0; s < n0; ++s) do_step(acc0);
-    }
+    for (int s = 0; s < n0; ++s) do_step(acc0);
     if (DUAL) {
       f32x16 acc1[C::MI][C::NI];
 #pragma unroll
@@ -303,7 +326,9 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     // A store instruction therefore writes 32 consecutive rows of one token: full 64/128-byte segments.
     const bool full = (t0 + C::TT <= a.T);
     auto put = [&](unsigned char* p, float v) {
-      if (a.y_bf16)
+      if (CHUNK && shared_row)
+        atomicAdd(reinterpret_cast<float*>(p), v);  // fp32 output, zeroed before the launch
+      else if (a.y_bf16)
         *reinterpret_cast<uint16_t*>(p) = f32_to_bf16_rne(v);
       else
         *reinterpret_cast<float*>(p) = v;
@@ -323,6 +348,25 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
           if (full || tokb + dt < a.T) put(p0 + dt * tok_pitch, acc0[mi][ni][j]);
         }
     }
+  }
+}
+
+// Zeroes the fp32 output rows of every block row that is cut into several chunks (its chunks then add
+// into them).  Grid: x = upper bound of the number of chunks, y = slabs of 64 tokens.
+template <int B>
+__global__ __launch_bounds__(256) void k_zero_shared_rows(const StreamArgs sa) {
+  const TileArgs& a = sa.t;
+  const int ci = blockIdx.x;
+  if (ci >= ld_idx(sa.hdr, 0)) return;
+  const int cr = ld_idx(sa.chunk_row, ci);
+  if (cr >= 0) return;  // a single-chunk row is stored, not accumulated
+  const int r = cr & 0x7FFFFFFF;
+  if (ld_idx(sa.chunk_kb, ci) != ld_idx(a.m0.row_ptr, r)) return;  // only the first chunk of the row zeroes
+  float* Y = reinterpret_cast<float*>(a.Y);
+  const int t0 = blockIdx.y * 64;
+  for (int e = threadIdx.x; e < 64 * B; e += 256) {
+    const int t = t0 + e / B, i = e % B;
+    if (t < a.T) Y[(int64_t)t * a.syt + ((int64_t)r * B + i) * a.syi] = 0.0f;
   }
 }
 

@@ -50,7 +50,7 @@ def test_pack_bound_and_errors():
     L = api.lib()
     cap, auxb, wsb = C.c_int64(0), C.c_size_t(0), C.c_size_t(0)
     assert L.blast_bsr_pack_bound(8192, 2048, 64, api.PACK_TOPK_FROBENIUS, 0.9, C.byref(cap), C.byref(auxb), C.byref(wsb)) == 0
-    assert cap.value == 409 and auxb.value >= 4 * (32 + 1 + 2 * 409) and wsb.value >= 9 * 4096
+    assert cap.value == 409 and auxb.value >= 4 * (32 + 1 + 2 * 409) + 12 * (128 + 4096 // 16) and wsb.value >= 9 * 4096
     assert L.blast_bsr_pack_bound(8192, 2048, 64, api.PACK_MASK, 0.0, C.byref(cap), None, None) == 0
     assert cap.value == 4096
     assert L.blast_bsr_pack_bound(8192, 2050, 64, 0, 0.0, None, None, None) == -2  # shape
@@ -87,4 +87,4 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     assert ws.value >= 16 * 256 * 2
     # pack: null outputs / bad ld are rejected up front
     nnz = C.c_int64(0)
-    assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, 0, None) == -1
+    assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, None, 0, None) == -1

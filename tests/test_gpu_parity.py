@@ -40,18 +40,42 @@ def pack_both(api, W, b, mask=None, sparsity=None):
     return dev, ref
 
 
+CHUNK = 16  # blocks per chunk of the packer's chunk plan
+
+
 def check_aux(dev, ref):
-    """The column-grouped index lists the same blocks, by column then ascending row."""
-    nbc = ref.cols // ref.b
+    """aux = chunk plan (rows in schedule order cut into chunks of <= 16 blocks) followed by the
+    column-grouped index (the same blocks by column, then ascending row)."""
+    nbr, nbc = ref.rows // ref.b, ref.cols // ref.b
     aux = dev.aux.cpu().numpy()
-    cap = dev.col_idx.numel() if ref.nnz else 0
     a16 = lambda x: (x + 15) // 16 * 16
-    col_ptr = aux[: 4 * (nbc + 1)].view(np.int32)
-    off = a16(4 * (nbc + 1))
+    cap = nbr + (nbr * nbc) // CHUNK + 1
+    hdr = aux[:16].view(np.int32)
+    off = 16
+    chunk_row = aux[off: off + 4 * cap].view(np.int32)
+    off += a16(4 * cap)
+    chunk_kb = aux[off: off + 4 * cap].view(np.int32)
+    off += a16(4 * cap)
+    chunk_ke = aux[off: off + 4 * cap].view(np.int32)
+    off += a16(4 * cap)
+    # expected plan, written from the definition
+    exp = []
+    cnt = np.diff(ref.row_ptr)
+    for r in ref.row_order:
+        kb, ke = int(ref.row_ptr[r]), int(ref.row_ptr[r + 1])
+        nch = max(1, -(-(ke - kb) // CHUNK))
+        for j in range(nch):
+            exp.append((int(r), nch > 1, kb + j * CHUNK, min(kb + (j + 1) * CHUNK, ke)))
+    assert hdr[0] == len(exp) and hdr[1] == int((cnt > CHUNK).sum()) == dev.heavy_rows and hdr[2] == CHUNK
+    n = len(exp)
+    assert [(int(c) & 0x7FFFFFFF, int(c) < 0, int(a), int(b_)) for c, a, b_ in
+            zip(chunk_row[:n], chunk_kb[:n], chunk_ke[:n])] == exp
+    col_ptr = aux[off: off + 4 * (nbc + 1)].view(np.int32)
+    off += a16(4 * (nbc + 1))
     csc_row = aux[off: off + 4 * ref.nnz].view(np.int32)
-    off += a16(4 * max(cap, ref.nnz))
+    off += a16(4 * ref.nnz)
     csc_blk = aux[off: off + 4 * ref.nnz].view(np.int32)
-    rows_of_blk = np.repeat(np.arange(ref.rows // ref.b), np.diff(ref.row_ptr))
+    rows_of_blk = np.repeat(np.arange(nbr), np.diff(ref.row_ptr))
     order = np.lexsort((rows_of_blk, ref.col_idx))  # by column, then row
     assert np.array_equal(col_ptr, np.concatenate([[0], np.cumsum(np.bincount(ref.col_idx, minlength=nbc))]))
     assert np.array_equal(csc_blk, order.astype(np.int32))
@@ -183,6 +207,35 @@ def test_spmm_dense_and_empty_matrix(api):
     y0 = api.bsr_spmm(dev0, to_dev(x), out=torch.full((T, 3 * b), float("nan"), device="cuda:0"))
     torch.cuda.synchronize()
     assert not y0.cpu().numpy().any()
+
+
+@pytest.mark.parametrize("b,nbc,T", [(32, 70, 300), (64, 40, 520), (128, 36, 200)])
+def test_spmm_heavy_rows_are_chunked(api, b, nbc, T):
+    """Rows with more than 16 stored blocks are cut into chunks that add their partial sums atomically."""
+    import torch
+
+    rng = np.random.default_rng(900 + b)
+    nbr = 6
+    mask = synth.uniform_mask(rng, nbr, nbc, 0.9)
+    mask[0, :] = 1          # a full row: several chunks
+    mask[2, : nbc // 2] = 1  # a second heavy row
+    mask[4, :] = 0          # an empty row
+    w = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.02)
+    x = synth.gauss_bf16(rng, (T, nbc * b), 1.0)
+    dev, ref = pack_both(api, w, b, mask=mask)
+    check_aux(dev, ref)
+    assert dev.heavy_rows >= 2
+    y_or = orc.spmm(ref, x)
+    for _ in range(2):  # the output buffer starts poisoned both times
+        y = api.bsr_spmm(dev, to_dev(x), out=torch.full((T, nbr * b), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, y_or, f"chunked b={b}")
+    assert not y.cpu().numpy()[:, 4 * b:5 * b].any()
+    # bf16 output takes the unsplit path and still agrees
+    yb = api.bsr_spmm(dev, to_dev(x), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    got = synth.bf16_bits_to_f32(bits_of(yb)).astype(np.float64).T
+    assert np.abs(got - y_or).max() <= 2.0 ** -7 * np.abs(y_or).max()
 
 
 def test_spmm_config1_linear(api):
