@@ -66,8 +66,8 @@ extern "C" {
 typedef struct blast_bsr_view {
   int64_t rows, cols;       /* logical size; both multiples of b */
   int32_t b;                /* block edge: 16, 32, 64 or 128 */
-  int32_t heavy_rows;       /* number of block rows cut into several chunks, as reported by blast_bsr_pack;
-                               0 = unknown or none (rows are then never split) */
+  int32_t max_row_blocks;   /* stored blocks of the fullest block row, as reported by blast_bsr_pack;
+                               0 = unknown (rows are then never split into chunks) */
   int64_t nnz;              /* number of stored blocks */
   const int32_t* row_ptr;   /* [rows/b + 1], row_ptr[0] = 0, non-decreasing, row_ptr[rows/b] = nnz */
   const int32_t* col_idx;   /* [nnz], block-column of each stored block, strictly ascending inside a block row */
@@ -122,9 +122,10 @@ int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, do
  *   aux         out, aux_bytes >= blast_bsr_aux_bytes(rows, cols, b, nnz_cap), 16-byte aligned; may be NULL
  *               (then neither the chunk plan nor the column-grouped index is produced)
  *   nnz_out     HOST, receives the number of stored blocks (also on BLAST_ERR_CAPACITY)
- *   heavy_rows_out  HOST, may be NULL: number of block rows holding more than 16 stored blocks; with `aux`
- *               these rows are cut into chunks of 16 blocks that the product kernels schedule separately
- *               ("reduces load imbalance", Sec. 3.4.1).  Copy it into blast_bsr_view.heavy_rows.  0 without aux.
+ *   max_row_blocks_out  HOST, may be NULL: stored blocks of the fullest block row (0 without aux).  Copy it
+ *               into blast_bsr_view.max_row_blocks: with `aux`, block rows of more than 16 blocks are cut into
+ *               chunks of 16, and the product schedules chunks instead of rows when that row would otherwise
+ *               be the critical path of the launch (the load balance Sec. 3.4.1 asks of the launch grid).
  *   ws          scratch of at least the ws_bytes reported by blast_bsr_pack_bound, 16-byte aligned
  *
  * The call synchronises `stream` once (to learn nnz); when it returns BLAST_OK
@@ -135,7 +136,7 @@ int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, do
 int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
                    const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx, uint16_t* vals,
                    int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap, int64_t* nnz_out,
-                   int32_t* heavy_rows_out, void* ws, size_t ws_bytes, void* stream);
+                   int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Schedule for two matrices that are multiplied together row by row (W_gate and W_up of Eq. (1)):

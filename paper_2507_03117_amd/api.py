@@ -36,7 +36,7 @@ class BlastError(RuntimeError):
 
 class BsrView(C.Structure):
     _fields_ = [
-        ("rows", C.c_int64), ("cols", C.c_int64), ("b", C.c_int32), ("heavy_rows", C.c_int32), ("nnz", C.c_int64),
+        ("rows", C.c_int64), ("cols", C.c_int64), ("b", C.c_int32), ("max_row_blocks", C.c_int32), ("nnz", C.c_int64),
         ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("vals", C.c_void_p), ("row_order", C.c_void_p),
         ("aux", C.c_void_p),
     ]
@@ -114,10 +114,10 @@ class PackedBsr:
     vals: torch.Tensor  # int16 (bf16 bits) [cap * b * b]
     row_order: torch.Tensor  # int32 [rows/b]
     aux: Optional[torch.Tensor]  # uint8
-    heavy_rows: int = 0  # block rows cut into several chunks (reported by the packer)
+    max_row_blocks: int = 0  # stored blocks of the fullest block row (reported by the packer)
 
     def view(self) -> BsrView:
-        return BsrView(self.rows, self.cols, self.b, self.heavy_rows, self.nnz, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+        return BsrView(self.rows, self.cols, self.b, self.max_row_blocks, self.nnz, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
                        self.vals.data_ptr(), self.row_order.data_ptr(),
                        self.aux.data_ptr() if self.aux is not None else None)
 

@@ -22,7 +22,7 @@ constexpr int kChunkBlocks = 16;
 
 // Layout of the "aux" buffer that pack writes for a matrix with NBr block rows, NBc block columns and
 // nnz stored blocks (every offset can be recomputed from the packed view alone):
-//   chunk plan:            hdr[4] = {n_chunks, heavy_rows, kChunkBlocks, 0} |
+//   chunk plan:            hdr[4] = {n_chunks, max_row_blocks, kChunkBlocks, 0} |
 //                          chunk_row[cap] (bit 31: the row has several chunks) | chunk_kb[cap] | chunk_ke[cap]
 //                          in schedule order (rows by population, descending), cap = NBr + NBr*NBc/kChunkBlocks + 1
 //   column-grouped index:  col_ptr[NBc+1] | csc_row[nnz] | csc_blk[nnz]

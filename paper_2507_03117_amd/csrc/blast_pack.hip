@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256) void k_fill_csc(const uint8_t* __restrict__ ma
 }
 
 // Single workgroup: cut the block rows, in schedule order, into chunks of at most `chunk` blocks.
-// hdr = {n_chunks, heavy_rows, chunk, 0}.  An empty row still gets one (empty) chunk: its output has
+// hdr = {n_chunks, max_row_blocks, chunk, 0}.  An empty row still gets one (empty) chunk: its output has
 // to be written.
 __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row_ptr, const int* __restrict__ row_order,
                                                      int nbr, int chunk, int* __restrict__ hdr,
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
       ke = row_ptr[r + 1];
       nch = (ke - kb + chunk - 1) / chunk;
       if (nch < 1) nch = 1;
-      if (nch > 1) atomicAdd(&s_heavy, 1);
+      atomicMax(&s_heavy, ke - kb);
     }
     int total;
     const int first = s_running + block_exscan(nch, wave_tot, total);
@@ -372,7 +372,7 @@ extern "C" int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32
 extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
                               const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx,
                               uint16_t* vals, int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap,
-                              int64_t* nnz_out, int32_t* heavy_rows_out, void* ws, size_t ws_bytes, void* stream_) {
+                              int64_t* nnz_out, int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (mode != BLAST_PACK_MASK && mode != BLAST_PACK_TOPK_FROBENIUS) return BLAST_ERR_INVALID_ARG;
   if (int rc = check_shape(rows, cols, b)) return rc;
@@ -423,7 +423,7 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(rcnt, (int)nbr, row_ptr, nnz_dev);
   BLAST_LAUNCH_CHECK("k_exscan(rows)");
   // The schedule and the chunk plan depend on the populations only: they are written before the
-  // synchronisation so that the number of heavy rows comes back to the host with nnz.
+  // synchronisation so that the longest row's length comes back to the host with nnz.
   int host_vals[2] = {0, 0};
   int* hdr_dev = nullptr;
   if (nbr > 0) {
@@ -444,7 +444,7 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   BLAST_HIP_TRY(hipStreamSynchronize(stream));
   const int nnz_host = host_vals[0];
   *nnz_out = nnz_host;
-  if (heavy_rows_out) *heavy_rows_out = aux ? host_vals[1] : 0;
+  if (max_row_blocks_out) *max_row_blocks_out = aux ? host_vals[1] : 0;
   if (nnz_host > nnz_cap) return BLAST_ERR_CAPACITY;
 
   if (nbr > 0) {

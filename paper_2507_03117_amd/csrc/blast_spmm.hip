@@ -221,11 +221,16 @@ void set_y(TileArgs& a, void* Y, int64_t ldy, int32_t layout, int32_t y_dtype) {
 
 MatDev mat_of(const blast_bsr_view* v) { return MatDev{v->row_ptr, v->col_idx, v->vals}; }
 
-// The chunk plan is used only when the packer reported rows that are actually cut.
-ChunkPlan plan_of(const blast_bsr_view* v) {
+// The chunk plan is used when the fullest block row, taken as one work item, would outlast twice the
+// average load of a workgroup slot: then it is the critical path and worth the atomics.  Uniformly
+// filled matrices keep the plain row schedule.
+ChunkPlan plan_of(const blast_bsr_view* v, int64_t T) {
   ChunkPlan p;
-  if (!v->aux || v->heavy_rows <= 0) return p;
+  if (!v->aux || v->max_row_blocks <= blast::kChunkBlocks) return p;
   const int64_t nbr = v->rows / v->b, nbc = v->cols / v->b;
+  const int64_t tiles = (T + 255) / 256;
+  const double avg_per_slot = (double)v->nnz * (double)tiles / (2.0 * cu_count());
+  if ((double)v->max_row_blocks <= 2.0 * avg_per_slot) return p;
   const blast::AuxLayout L = blast::aux_layout(nbr, nbc, v->nnz);
   const char* ab = static_cast<const char*>(v->aux);
   p.hdr = reinterpret_cast<const int*>(ab + L.hdr_off);
@@ -264,7 +269,7 @@ extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_
   a.T = (int)T;
   a.nbr = (int)(W->rows / W->b);
   a.act = 0;
-  return dispatch_tile<false>(W->b, a, stream, plan_of(W));
+  return dispatch_tile<false>(W->b, a, stream, plan_of(W, T));
 }
 
 extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
@@ -338,7 +343,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   d.T = (int)T;
   d.nbr = (int)(E / b);
   d.act = 0;
-  if (int rc = dispatch_tile<false>(b, d, stream, plan_of(Wdown))) return rc;
+  if (int rc = dispatch_tile<false>(b, d, stream, plan_of(Wdown, T))) return rc;
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
   return BLAST_OK;
 }
