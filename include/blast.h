@@ -82,8 +82,8 @@ typedef struct blast_bsr_view {
  * last HIP error seen by the calling thread is appended.  Never NULL. */
 const char* blast_strerror(int code);
 
-/* Number of blocks kept for a target sparsity over n_blocks blocks (Sec. 3.2:
- * "drop the lowest scoring blocks until sparsity s is reached"): the drop count
+/* Number of blocks kept for a target sparsity over n_blocks blocks (Sec. 3.2: the
+ * lowest-scoring blocks are removed until the zero fraction reaches s): the drop count
  * is ceil(s * n_blocks) with s taken in basis points, s_bp = round(s * 1e4),
  * n_zero = ceil(s_bp * n_blocks / 1e4).  Returns -1 if sparsity is outside [0, 1]
  * or n_blocks < 0.  Pure host arithmetic. */

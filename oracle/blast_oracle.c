@@ -15,7 +15,7 @@
  *                     masked weight (BSR of the out x in weight, which is the
  *                     paper's BCSC of its transposed weight)  (Sec. 3.2, 3.4.1)
  *   - SpMM          = Y = W~ X with W~ the dense masked weight; the kernel of
- *                     Sec. 3.4 "never computes on absent tiles", i.e. it reaches
+ *                     Sec. 3.4 only skips blocks that are absent, i.e. it reaches
  *                     exactly this dense result, so the oracle is the definition:
  *                     expand to dense, naive triple loop, fp64.
  *   - MLP           = Eq. (1): Y = W~down ( act(W~gate X) (.) (W~up X) ), with the
@@ -65,7 +65,7 @@ int oracle_num_threads(void) {
 #endif
 }
 
-/* Sec. 3.2: "drop the lowest scoring blocks until we reach sparsity s". */
+/* Sec. 3.2: the lowest-scoring blocks go until the zero fraction reaches s. */
 int64_t oracle_n_keep(int64_t n_blocks, double sparsity) {
   int64_t s_bp = (int64_t)llround(sparsity * 10000.0);
   int64_t n_zero = (s_bp * n_blocks + 9999) / 10000;

@@ -106,15 +106,20 @@ __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__
       if ((k & himask) == prefix) atomicAdd(&hist[(unsigned)(k >> (8 * pass)) & 255u], 1u);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      long long cum = 0, rem = s_remaining;
-      int d = 255;
-      for (; d > 0; --d) {
-        if (cum + (long long)hist[d] >= rem) break;
-        cum += hist[d];
+    // Digit d of this pass: the bin where the count of larger digits, S(d), first satisfies
+    // S(d) < remaining <= S(d) + hist[d].  One thread per bin; the suffix sums come from a scan of the
+    // bins in descending order.
+    {
+      const long long rem = s_remaining;
+      const int d = 255 - (int)threadIdx.x;  // thread t looks at bin 255 - t
+      const int h = (threadIdx.x < 256) ? (int)hist[d & 255] : 0;
+      int total;
+      const int larger = block_exscan(h, wave_tot, total);  // sum of hist over digits > d
+      __syncthreads();
+      if (threadIdx.x < 256 && (long long)larger < rem && rem <= (long long)larger + h) {
+        s_remaining = rem - larger;
+        s_prefix = prefix | ((unsigned long long)d << (8 * pass));
       }
-      s_remaining = rem - cum;
-      s_prefix = prefix | ((unsigned long long)d << (8 * pass));
     }
     __syncthreads();
   }

@@ -221,16 +221,18 @@ void set_y(TileArgs& a, void* Y, int64_t ldy, int32_t layout, int32_t y_dtype) {
 
 MatDev mat_of(const blast_bsr_view* v) { return MatDev{v->row_ptr, v->col_idx, v->vals}; }
 
-// The chunk plan is used when the fullest block row, taken as one work item, would outlast twice the
-// average load of a workgroup slot: then it is the critical path and worth the atomics.  Uniformly
-// filled matrices keep the plain row schedule.
+// The chunk plan costs a zero-fill launch and fp32 atomics on the split rows (measured: about 9 us on
+// the 1B-shaped down projection, where it does not pay).  It is used only when the fullest block row,
+// taken as one work item, would outlast four times the average load of a workgroup slot (and four
+// chunks): then that row is the critical path of the launch by a wide margin.
 ChunkPlan plan_of(const blast_bsr_view* v, int64_t T) {
   ChunkPlan p;
   if (!v->aux || v->max_row_blocks <= blast::kChunkBlocks) return p;
   const int64_t nbr = v->rows / v->b, nbc = v->cols / v->b;
   const int64_t tiles = (T + 255) / 256;
-  const double avg_per_slot = (double)v->nnz * (double)tiles / (2.0 * cu_count());
-  if ((double)v->max_row_blocks <= 2.0 * avg_per_slot) return p;
+  double ref = (double)v->nnz * (double)tiles / (2.0 * cu_count());
+  if (ref < blast::kChunkBlocks) ref = blast::kChunkBlocks;
+  if ((double)v->max_row_blocks <= 4.0 * ref) return p;
   const blast::AuxLayout L = blast::aux_layout(nbr, nbc, v->nnz);
   const char* ab = static_cast<const char*>(v->aux);
   p.hdr = reinterpret_cast<const int*>(ab + L.hdr_off);
