@@ -128,7 +128,8 @@ int launch_decode_ntt(const TileArgs& a, hipStream_t stream) {
   const int64_t grid = (int64_t)a.nbr * (B / 16);
   if (grid <= 0) return BLAST_OK;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
-  k_decode<B, DUAL, NTT><<<dim3((unsigned)grid), dim3(256), 0, stream>>>(d);
+  const unsigned groups = (unsigned)((a.T + NTT * 16 - 1) / (NTT * 16));
+  k_decode<B, DUAL, NTT><<<dim3((unsigned)grid, groups), dim3(256), 0, stream>>>(d);
   BLAST_LAUNCH_CHECK("k_decode");
   return BLAST_OK;
 }
@@ -136,18 +137,19 @@ int launch_decode_ntt(const TileArgs& a, hipStream_t stream) {
 template <int B, bool DUAL>
 int launch_decode(const TileArgs& a, hipStream_t stream) {
   if (a.T <= 16) return launch_decode_ntt<B, DUAL, 1>(a, stream);
-  if (a.T <= 32) return launch_decode_ntt<B, DUAL, 2>(a, stream);
-  if (a.T <= 64) return launch_decode_ntt<B, DUAL, 4>(a, stream);
-  return launch_decode_ntt<B, DUAL, 8>(a, stream);
+  return launch_decode_ntt<B, DUAL, 2>(a, stream);  // groups of 32 tokens along gridDim.y
 }
 
-constexpr int kDecodeMaxTokens = 32;  // beyond this the streaming kernel is faster (measured)
+// Measured crossover with the streaming kernel on the 1B-shaped MLP: the gated (two-matrix) product at
+// about 48 tokens, the single-matrix product beyond 128.
+constexpr int kDecodeMaxTokensDual = 48;
+constexpr int kDecodeMaxTokens = 128;  // beyond this the streaming kernel takes over
 
 template <bool DUAL>
 int dispatch_tile(int b, const TileArgs& a, hipStream_t stream, const ChunkPlan& plan = ChunkPlan{}) {
   // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
-  if (a.x_vec && a.T > 0 && a.T <= kDecodeMaxTokens && small_x) {
+  if (a.x_vec && a.T > 0 && a.T <= (DUAL ? kDecodeMaxTokensDual : kDecodeMaxTokens) && small_x) {
     switch (b) {
       case 32: return launch_decode<32, DUAL>(a, stream);
       case 64: return launch_decode<64, DUAL>(a, stream);

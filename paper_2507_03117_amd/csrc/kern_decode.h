@@ -1,4 +1,4 @@
-// Decode kernel: block-sparse product for a handful of tokens (T <= 128).
+// Decode kernel: block-sparse product for a handful of tokens (T <= 128 or so).
 //
 // At these token counts the product is bound by streaming the stored blocks out
 // of HBM once (the paper's abstract: data movement dominates), so the kernel is
@@ -40,6 +40,9 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   constexpr int NM = DUAL ? 2 : 1;
   __shared__ float red[3][NM][NTT][4][64];
 
+  // blockIdx.y selects a group of NTT * 16 tokens: more tokens mean more workgroups, each re-reading its
+  // weight slice (the first read comes from HBM, the others from cache)
+  const int t_base = blockIdx.y * (NTT * 16);
   const int unit = blockIdx.x;
   const int r = unit / SLICES, q = unit % SLICES;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l16 = lane & 15, g = lane >> 4;
@@ -63,7 +66,7 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   uint32_t xoff[NTT];
 #pragma unroll
   for (int tt = 0; tt < NTT; ++tt) {
-    int t = tt * 16 + l16;
+    int t = t_base + tt * 16 + l16;
     t = t < a.T ? t : a.T - 1;
     xoff[tt] = ((uint32_t)t * (uint32_t)a.sxt + (uint32_t)g * 8u) * 2u;
   }
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   for (int tt = 0; tt < NTT; ++tt)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int tok = tt * 16 + 4 * g + j;
+      const int tok = t_base + tt * 16 + 4 * g + j;
       if (tok < a.T) {
         float v = acc[0][tt][j];
         if (DUAL) v = apply_act(a.act, v) * acc[NM - 1][tt][j];
