@@ -37,7 +37,7 @@ PEAK_HBM_GBS = 8000.0
 # Source: profiles/bench_llama1b_b64_s90_hbm_traffic.txt (read x2.0, write x1.0; counters sit between each XCD's
 # L2 and the fabric).  Keys: (kernel, tokens) of the default workload.
 MEASURED_TRAFFIC_BYTES = {
-    ("gate_up", 2048): 63.41e6 + 39.84e6,
+    ("gate_up", 2048): 63.60e6 + 38.29e6,
     ("mlp", 1): (7.12e6 + 0.14e6) + (4.30e6 + 0.07e6),
     ("mlp", 16): (7.12e6 + 0.14e6) + (4.30e6 + 0.07e6),
 }
