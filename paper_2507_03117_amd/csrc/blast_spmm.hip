@@ -80,6 +80,8 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
   int64_t grid = (n_items + 7) / 8 * 8;
   const int64_t resident = (int64_t)cu_count() * C::WG_PER_CU / 8 * 8;
   if (grid > resident) grid = resident;
+  // a workgroup keeps the descriptors of its items one per lane: at most 64 rounds
+  if (grid * 64 < n_items) grid = ((n_items + 63) / 64 + 7) / 8 * 8;
   if (CHUNK) {
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");

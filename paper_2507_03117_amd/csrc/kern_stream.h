@@ -97,50 +97,92 @@ __device__ __forceinline__ int item_of(int w, int round, int G) {
   return round * G + (g2 << 3) + (w & 7);
 }
 
+// Descriptors of the items of one workgroup, one round per lane (every wave keeps its own copy, read
+// with v_readlane).  They are fetched once at kernel start with ordinary vector loads, so that no
+// dependent chain of index loads (schedule -> row pointers -> first column) is left on the path of the
+// loader when it crosses an item or phase boundary.  The host sizes the grid so that a workgroup has at
+// most 64 rounds.
+struct ItemTable {
+  int r;        // block row (bit 31: CHUNK row shared with other chunks)
+  int tile;     // token tile
+  int k0, e0;   // stored blocks [k0, e0) of the first matrix (or of the chunk)
+  int k1, e1;   // of the second matrix (DUAL)
+  int c0, c1;   // block column of the first stored block of each phase
+  int n_rounds; // uniform: rounds of this workgroup
+};
+
+template <bool DUAL, bool CHUNK>
+__device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n_items, int w, int G, int lane) {
+  const TileArgs& a = sa.t;
+  ItemTable t{};
+  const int it = item_of(w, lane, G);
+  const bool ok = it < n_items;
+  int rank = 0;
+  if (ok) split_item(it, a.ntt, sa.ntt_shift, rank, t.tile);
+  if (ok) {
+    if (CHUNK) {
+      t.r = sa.chunk_row[rank];
+      t.k0 = sa.chunk_kb[rank];
+      t.e0 = sa.chunk_ke[rank];
+    } else {
+      t.r = a.row_order ? a.row_order[rank] : rank;
+      t.k0 = a.m0.row_ptr[t.r];
+      t.e0 = a.m0.row_ptr[t.r + 1];
+      if (DUAL) {
+        t.k1 = a.m1.row_ptr[t.r];
+        t.e1 = a.m1.row_ptr[t.r + 1];
+      }
+    }
+    if (t.k0 < t.e0) t.c0 = a.m0.col_idx[t.k0];
+    if (DUAL && t.k1 < t.e1) t.c1 = a.m1.col_idx[t.k1];
+  }
+  // items of a workgroup grow with the round, so the valid rounds are a prefix
+  t.n_rounds = __builtin_popcountll(__ballot(ok));
+  return t;
+}
+
+#define BLAST_LANE(v, j) __builtin_amdgcn_readlane((v), (j))
+
 // Position of the loader in the flattened stream of steps.
-template <int NSLICE, bool DUAL, bool CHUNK>
+template <int NSLICE, bool DUAL>
 struct StepCursor {
-  int round, r, tile, phase, k, kend, slice;
+  int round, tile, phase, k, kend, slice, c, c_next;
   bool valid;
 
-  __device__ __forceinline__ void enter_phase(const TileArgs& a) {
-    const MatDev& m = (DUAL && phase == 1) ? a.m1 : a.m0;
-    k = ld_idx(m.row_ptr, r);
-    kend = ld_idx(m.row_ptr, r + 1);
-  }
   // Move to the first step at or after the current position (skips empty phases and items).
-  __device__ __forceinline__ void settle(const StreamArgs& sa, int n_items, int w, int G) {
-    const TileArgs& a = sa.t;
+  __device__ __forceinline__ void settle(const ItemTable& t) {
     while (valid && k >= kend) {
       if (DUAL && phase == 0) {
         phase = 1;
-        enter_phase(a);
+        k = BLAST_LANE(t.k1, round);
+        kend = BLAST_LANE(t.e1, round);
+        c = BLAST_LANE(t.c1, round);
       } else {
         ++round;
-        const int it = item_of(w, round, G);
-        if (it >= n_items) {
+        if (round >= t.n_rounds) {
           valid = false;
           break;
         }
-        int rank;
-        split_item(it, a.ntt, sa.ntt_shift, rank, tile);
         phase = 0;
-        if (CHUNK) {
-          r = ld_idx(sa.chunk_row, rank) & 0x7FFFFFFF;
-          k = ld_idx(sa.chunk_kb, rank);
-          kend = ld_idx(sa.chunk_ke, rank);
-        } else {
-          r = a.row_order ? ld_idx(a.row_order, rank) : rank;
-          enter_phase(a);
-        }
+        tile = BLAST_LANE(t.tile, round);
+        k = BLAST_LANE(t.k0, round);
+        kend = BLAST_LANE(t.e0, round);
+        c = BLAST_LANE(t.c0, round);
       }
     }
   }
-  __device__ __forceinline__ void advance(const StreamArgs& sa, int n_items, int w, int G) {
+  // Called when block k has just been issued for the first time: ask for the column of block k+1.
+  __device__ __forceinline__ void prefetch_col(const TileArgs& a) {
+    if (k + 1 < kend) c_next = ld_idx(((DUAL && phase == 1) ? a.m1 : a.m0).col_idx, k + 1);
+  }
+  __device__ __forceinline__ void advance(const ItemTable& t) {
     if (++slice == NSLICE) {
       slice = 0;
       ++k;
-      settle(sa, n_items, w, G);
+      if (k < kend)
+        c = c_next;
+      else
+        settle(t);
     }
   }
 };
@@ -156,7 +198,10 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int w = blockIdx.x, G = gridDim.x;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+  // the wave index is uniform: keeping it in a scalar register makes every LDS destination of the copy
+  // instructions scalar arithmetic instead of vector arithmetic plus a lane read
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tw = wave % C::TOKW, rw = wave / C::TOKW;
 
   // ---- per-lane constants --------------------------------------------------------------
@@ -182,6 +227,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     woff[q] = (uint32_t)(row * B + ((cp_slot ^ C::key(row)) << 3)) * 2u;
   }
   int xoff_tile = -1;
+  const uint32_t sxt32 = (uint32_t)a.sxt;
   auto set_tile = [&](int tile) {
     if (tile == xoff_tile) return;
     xoff_tile = tile;
@@ -190,7 +236,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
       const int row = (q * 4 + wave) * C::RPI + cp_rr;
       int t = tile * C::TT + row;
       t = t < a.T ? t : a.T - 1;  // clamp: rows past T are never stored
-      xoff[q] = ((uint32_t)t * (uint32_t)a.sxt + (uint32_t)((cp_slot ^ C::key(row)) << 3)) * 2u;
+      xoff[q] = ((uint32_t)t * sxt32 + (uint32_t)((cp_slot ^ C::key(row)) << 3)) * 2u;
     }
   };
   auto issue = [&](const MatDev& m, int k, int c, int slice, int tile, int stage) {
@@ -206,23 +252,24 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     for (int q = 0; q < C::XQ; ++q) BLAST_GLDS16(xcol + xoff[q], st + C::W_BYTES + (q * 4 + wave) * 1024);
   };
 
-  StepCursor<C::NSLICE, DUAL, CHUNK> ld;
+  const ItemTable tab = load_item_table<DUAL, CHUNK>(sa, n_items, w, G, lane);
+
+  StepCursor<C::NSLICE, DUAL> ld;
   ld.round = -1;
   ld.phase = DUAL ? 1 : 0;
   ld.k = ld.kend = 0;
-  ld.r = 0;
   ld.tile = 0;
   ld.slice = 0;
+  ld.c = ld.c_next = 0;
   ld.valid = true;
-  ld.settle(sa, n_items, w, G);
-  int ld_c = 0;
+  ld.settle(tab);
   int issued = 0, done = 0;
   auto issue_next = [&]() {
     const MatDev& m = (DUAL && ld.phase == 1) ? a.m1 : a.m0;
-    if (ld.slice == 0) ld_c = ld_idx(m.col_idx, ld.k);
-    issue(m, ld.k, ld_c, ld.slice, ld.tile, issued % C::NSTAGE);
+    issue(m, ld.k, ld.c, ld.slice, ld.tile, issued % C::NSTAGE);
+    if (ld.slice == 0) ld.prefetch_col(a);
     ++issued;
-    ld.advance(sa, n_items, w, G);
+    ld.advance(tab);
   };
 #pragma unroll 1
   for (int p = 0; p < C::NSTAGE - 1; ++p)
@@ -268,22 +315,12 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
   };
 
   // ---- compute: item by item -------------------------------------------------------------
-  for (int round = 0;; ++round) {
-    const int it = item_of(w, round, G);
-    if (it >= n_items) break;
-    int rank, tile;
-    split_item(it, a.ntt, sa.ntt_shift, rank, tile);
-    int r, n0;
-    bool shared_row = false;  // other chunks add into the same output rows
-    if (CHUNK) {
-      const int cr = ld_idx(sa.chunk_row, rank);
-      r = cr & 0x7FFFFFFF;
-      shared_row = cr < 0;
-      n0 = (ld_idx(sa.chunk_ke, rank) - ld_idx(sa.chunk_kb, rank)) * C::NSLICE;
-    } else {
-      r = a.row_order ? ld_idx(a.row_order, rank) : rank;
-      n0 = (ld_idx(a.m0.row_ptr, r + 1) - ld_idx(a.m0.row_ptr, r)) * C::NSLICE;
-    }
+  for (int round = 0; round < tab.n_rounds; ++round) {
+    const int tile = BLAST_LANE(tab.tile, round);
+    const int rr = BLAST_LANE(tab.r, round);
+    const int r = CHUNK ? (rr & 0x7FFFFFFF) : rr;
+    const bool shared_row = CHUNK && rr < 0;  // other chunks add into the same output rows
+    const int n0 = (BLAST_LANE(tab.e0, round) - BLAST_LANE(tab.k0, round)) * C::NSLICE;
     const int t0 = tile * C::TT;
 
     f32x16 acc0[C::MI][C::NI];
@@ -302,7 +339,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
         for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
           for (int j = 0; j < 16; ++j) acc1[mi][ni][j] = 0.0f;
-      const int n1 = (ld_idx(a.m1.row_ptr, r + 1) - ld_idx(a.m1.row_ptr, r)) * C::NSLICE;
+      const int n1 = (BLAST_LANE(tab.e1, round) - BLAST_LANE(tab.k1, round)) * C::NSLICE;
       for (int s = 0; s < n1; ++s) do_step(acc1);
       if (a.act == BLAST_ACT_SILU) {
 #pragma unroll
