@@ -128,6 +128,7 @@ def main():
     ap.add_argument("--tokens", type=int, default=2048, help="token count of the headline step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--decode-tokens", default="", help="comma-separated decode token counts (default: the workload's)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--copies", type=int, default=0,
                     help="weight copies in rotation (0 = enough for 768 MB: cold HBM; 1 = warm caches)")
@@ -223,7 +224,8 @@ def main():
 
     if not args.no_decode:
         dec = []
-        for Td in (t for t in wl.tokens if t <= 128):
+        dec_T = [int(t) for t in args.decode_tokens.split(",") if t] or [t for t in wl.tokens if t <= 128]
+        for Td in dec_T:
             r = run_T(Td, max(args.steps, 50), args.warmup)
             gbs = r["alg_bytes"] / (r["ms_events"] * 1e-3) / 1e9
             dec.append({"T": Td, "ms_per_step": r["ms_per_step"], "ms_events": r["ms_events"],

@@ -131,7 +131,14 @@ int launch_decode_ntt(const TileArgs& a, hipStream_t stream) {
   if (grid <= 0) return BLAST_OK;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
   const unsigned groups = (unsigned)((a.T + NTT * 16 - 1) / (NTT * 16));
-  k_decode<B, DUAL, NTT><<<dim3((unsigned)grid, groups), dim3(256), 0, stream>>>(d);
+  using C = DecCfg<B, DUAL, NTT>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
+    attr_set = true;
+  }
+  k_decode<B, DUAL, NTT><<<dim3((unsigned)grid, groups), dim3(256), C::LDS_BYTES, stream>>>(d);
   BLAST_LAUNCH_CHECK("k_decode");
   return BLAST_OK;
 }
