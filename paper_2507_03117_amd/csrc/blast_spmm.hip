@@ -114,11 +114,12 @@ int launch_stream(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
   return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, stream);
 }
 
-template <int B, bool DUAL, int NTT>
-int launch_decode_ntt(const TileArgs& a, hipStream_t stream) {
+template <int B, bool DUAL, int NTT, bool CHUNK>
+int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   DecArgs d{};
   d.m0 = a.m0;
   d.m1 = a.m1;
+  d.row_order = a.row_order;
   d.X = a.X;
   d.sxt = a.sxt;
   d.Y = a.Y;
@@ -127,26 +128,42 @@ int launch_decode_ntt(const TileArgs& a, hipStream_t stream) {
   d.y_bf16 = a.y_bf16;
   d.T = a.T;
   d.act = a.act;
-  const int64_t grid = (int64_t)a.nbr * (B / 16);
+  d.hdr = plan.hdr;
+  d.chunk_row = plan.chunk_row;
+  d.chunk_kb = plan.chunk_kb;
+  d.chunk_ke = plan.chunk_ke;
+  const int64_t grid = (CHUNK ? plan.max_chunks : (int64_t)a.nbr) * (B / 16);
   if (grid <= 0) return BLAST_OK;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
   const unsigned groups = (unsigned)((a.T + NTT * 16 - 1) / (NTT * 16));
   using C = DecCfg<B, DUAL, NTT>;
   static bool attr_set = false;
   if (!attr_set) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT>),
+    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
-  k_decode<B, DUAL, NTT><<<dim3((unsigned)grid, groups), dim3(256), C::LDS_BYTES, stream>>>(d);
+  if (CHUNK) {
+    StreamArgs sa{a, 0, -1, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
+    k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
+    BLAST_LAUNCH_CHECK("k_zero_shared_rows");
+  }
+  k_decode<B, DUAL, NTT, CHUNK><<<dim3((unsigned)grid, groups), dim3(256), C::LDS_BYTES, stream>>>(d);
   BLAST_LAUNCH_CHECK("k_decode");
   return BLAST_OK;
 }
 
 template <int B, bool DUAL>
-int launch_decode(const TileArgs& a, hipStream_t stream) {
-  if (a.T <= 16) return launch_decode_ntt<B, DUAL, 1>(a, stream);
-  return launch_decode_ntt<B, DUAL, 2>(a, stream);  // groups of 32 tokens along gridDim.y
+int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
+  if constexpr (!DUAL) {
+    // rows cut into chunks accumulate with fp32 atomics: only for fp32 output
+    if (plan.hdr && !a.y_bf16) {
+      if (a.T <= 16) return launch_decode_ntt<B, false, 1, true>(a, plan, stream);
+      return launch_decode_ntt<B, false, 2, true>(a, plan, stream);
+    }
+  }
+  if (a.T <= 16) return launch_decode_ntt<B, DUAL, 1, false>(a, ChunkPlan{}, stream);
+  return launch_decode_ntt<B, DUAL, 2, false>(a, ChunkPlan{}, stream);  // groups of 32 tokens along gridDim.y
 }
 
 // Measured crossover with the streaming kernel on the 1B-shaped MLP: the gated (two-matrix) product at
@@ -160,9 +177,9 @@ int dispatch_tile(int b, const TileArgs& a, hipStream_t stream, const ChunkPlan&
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
   if (a.x_vec && a.T > 0 && a.T <= (DUAL ? kDecodeMaxTokensDual : kDecodeMaxTokens) && small_x) {
     switch (b) {
-      case 32: return launch_decode<32, DUAL>(a, stream);
-      case 64: return launch_decode<64, DUAL>(a, stream);
-      case 128: return launch_decode<128, DUAL>(a, stream);
+      case 32: return launch_decode<32, DUAL>(a, plan, stream);
+      case 64: return launch_decode<64, DUAL>(a, plan, stream);
+      case 128: return launch_decode<128, DUAL>(a, plan, stream);
       default: break;
     }
   }

@@ -3,24 +3,26 @@
 // At these token counts the product is bound by streaming the stored blocks out
 // of HBM once (the paper's abstract: data movement dominates), so the kernel is
 // organised around the memory pipeline:
-//  - one workgroup per (block row, 16-row slice); its four waves deal the stored
-//    blocks of the row among themselves, so even a row with a single block keeps
-//    a wave busy and a row with many blocks is read by four waves at once;
-//  - a 16-row slice of a block is contiguous in memory (16 B rows): a wave copies
-//    it global -> LDS with wave-wide 1 KiB requests (whole 128-byte lines, the
-//    request shape the L1 path handles best) and reads the matrix-core operand
-//    fragments back from LDS; no other wave touches that LDS region, so no
-//    barrier is involved, only the wave's own memory counter;
-//  - rounds of BPR blocks are double buffered: the copies of the next round are
-//    in flight while the current one is multiplied;
-//  - activations (a few KiB, cache resident) are read as the second operand,
-//    16 tokens per matrix instruction (v_mfma_f32_16x16x32_bf16);
+//  - one workgroup per (block row, 16-row slice), or per (chunk of a block row,
+//    16-row slice) when the packer's chunk plan is in use; its four waves deal the
+//    stored blocks among themselves, so even a row with a single block keeps a
+//    wave busy and a long row is read by four waves at once;
+//  - a 16-row slice of a block is contiguous in memory: a wave copies it
+//    global -> LDS with wave-wide 1 KiB requests (whole 128-byte lines, the
+//    request shape the L1 path handles best), and copies the matching activation
+//    tile (16 tokens x B) the same way; nothing passes through registers, so the
+//    only ordering device is the wave's own memory counter, which this code
+//    controls completely;
+//  - every wave owns a ring of NSLOT (slice + activation tile) slots in LDS: the
+//    copies of the next NSLOT-1 blocks are in flight while one block is
+//    multiplied; no other wave touches a wave's ring, so there is no barrier;
+//  - 16-byte chunks are XOR-swizzled inside their row on the global-address side
+//    of the copy, so that the operand-fragment reads do not pile onto one bank;
+//  - the products run on v_mfma_f32_16x16x32_bf16, 16 tokens per instruction;
 //  - the four partial sums meet in LDS; wave 0 applies the epilogue.
 // Same arithmetic as the tile kernels: bf16 products, fp32 accumulation,
 // activation on the fp32 sums, one rounding to bf16 where the output is bf16.
 #pragma once
-#include <type_traits>
-
 #include "kern_common.h"
 #include "kern_stream.h"
 
@@ -29,57 +31,81 @@ namespace blast_dev {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct DecArgs {
-  MatDev m0, m1;  // m1 only for the dual (gate/up) kernel
+  MatDev m0, m1;         // m1 only for the dual (gate/up) kernel
+  const int* row_order;  // block rows by population, fullest first (may be null)
   const uint16_t* X;
-  int64_t sxt;    // elements between tokens (token-major, 16-byte aligned rows)
+  int64_t sxt;           // elements between tokens (token-major, 16-byte aligned rows)
   void* Y;
   int64_t syt, syi;
   int y_bf16;
   int T;
   int act;
+  // chunk plan written by the packer (CHUNK instances only): hdr[0] = number of chunks
+  const int* hdr;
+  const int* chunk_row;  // block row of the chunk; bit 31 set when the row has several chunks
+  const int* chunk_kb;   // first stored block of the chunk
+  const int* chunk_ke;   // one past its last stored block
 };
 
 template <int B, bool DUAL, int NTT>
 struct DecCfg {
   static constexpr int SLICES = B / 16;       // 16-row slices per block row
   static constexpr int KST = B / 32;          // 32-wide k-steps per block
-  static constexpr int SLB = 16 * B * 2;      // bytes of one 16-row slice of a block
+  static constexpr int SLB = 16 * B * 2;      // bytes of one 16-row slice of a block (= of a 16-token activation tile)
   static constexpr int NI = SLB / 1024;       // wave-wide copy instructions per slice
-  static constexpr int BPR = (B == 128) ? 2 : 4;  // blocks per wave and round
+  static constexpr int CPRW = B / 8;          // 16-byte chunks per row
+  static constexpr int SLOT = SLB * (1 + NTT);
+  static constexpr int NSLOT = (B == 128) ? 2 : ((NTT == 1) ? 4 : 3);
+  static constexpr int OPS = NI * (1 + NTT);  // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;
-  static constexpr int PER_ROUND = BPR * (NI + KST * NTT);  // vector-memory operations a wave issues per round
-  static constexpr int W_LDS = 4 * 2 * BPR * SLB;           // [wave][buffer][block of the round][slice]
+  static constexpr int RING_LDS = 4 * NSLOT * SLOT;
   static constexpr int RED_LDS = 3 * NM * NTT * 4 * 64 * 4;
-  static constexpr size_t LDS_BYTES = (size_t)W_LDS + RED_LDS;
-  static_assert(SLB % 1024 == 0 && PER_ROUND < 64, "copy granularity / counter range");
+  static constexpr size_t LDS_BYTES = (size_t)RING_LDS + RED_LDS;
+  static_assert(SLB % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
+  // swizzle key of a row (mod 16): distinct for rows that would otherwise share banks
+  __device__ static __forceinline__ int key(int row) { return ((row & 15) / (16 / (CPRW < 16 ? CPRW : 16))) % CPRW; }
 };
 
-template <int B, bool DUAL, int NTT>
+template <int B, bool DUAL, int NTT, bool CHUNK>
 __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
+  static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
   using C = DecCfg<B, DUAL, NTT>;
-  constexpr int KST = C::KST, BPR = C::BPR, NM = C::NM;
+  constexpr int KST = C::KST, NM = C::NM, NI = C::NI, NSLOT = C::NSLOT;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::W_LDS);
+  float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::RING_LDS);
 
   // blockIdx.y selects a group of NTT * 16 tokens: more tokens mean more workgroups, each re-reading its
   // weight slice (the first read comes from HBM, the others from cache)
   const int t_base = blockIdx.y * (NTT * 16);
   const int unit = blockIdx.x;
-  const int r = unit / C::SLICES, q = unit % C::SLICES;
+  const int q = unit % C::SLICES;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63, l16 = lane & 15, g = lane >> 4;
-  unsigned char* wlds = smem + wave * (2 * BPR * C::SLB);
+  unsigned char* ring = smem + wave * (NSLOT * C::SLOT);
 
-  const int kb0 = ld_idx(a.m0.row_ptr, r), n0 = ld_idx(a.m0.row_ptr, r + 1) - kb0;
-  int kb1 = 0, n1 = 0;
-  if (DUAL) {
-    kb1 = ld_idx(a.m1.row_ptr, r);
-    n1 = ld_idx(a.m1.row_ptr, r + 1) - kb1;
+  int r, kb0, n0, kb1 = 0, n1 = 0;
+  bool shared_row = false;
+  if (CHUNK) {
+    const int ci = unit / C::SLICES;
+    if (ci >= ld_idx(a.hdr, 0)) return;  // the grid is sized by an upper bound of the number of chunks
+    const int cr = ld_idx(a.chunk_row, ci);
+    r = cr & 0x7FFFFFFF;
+    shared_row = cr < 0;
+    kb0 = ld_idx(a.chunk_kb, ci);
+    n0 = ld_idx(a.chunk_ke, ci) - kb0;
+  } else {
+    const int rank = unit / C::SLICES;
+    r = a.row_order ? ld_idx(a.row_order, rank) : rank;
+    kb0 = ld_idx(a.m0.row_ptr, r);
+    n0 = ld_idx(a.m0.row_ptr, r + 1) - kb0;
+    if (DUAL) {
+      kb1 = ld_idx(a.m1.row_ptr, r);
+      n1 = ld_idx(a.m1.row_ptr, r + 1) - kb1;
+    }
   }
   const int n = n0 + n1;
   // this wave's blocks are i = wave + 4 j, j < cnt
   const int cnt = n > wave ? (n - wave + 3) >> 2 : 0;
-  const int rounds = (cnt + BPR - 1) / BPR;
 
   f32x4 acc[NM][NTT];
 #pragma unroll
@@ -87,93 +113,89 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
 #pragma unroll
     for (int tt = 0; tt < NTT; ++tt) acc[m][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // per-lane byte offsets: inside a slice for the copy (contiguous), inside an activation row, and of
-  // this lane's operand fragment inside the LDS image of a slice (row l16, 16-byte chunk 4 s + g)
-  const uint32_t cp_off = (uint32_t)(q * C::SLB + lane * 16);
-  const uint32_t frag_off = (uint32_t)(l16 * B * 2 + g * 16);
-  uint32_t xoff[NTT];
+  // ---- per-lane constants ----------------------------------------------------------------
+  // Copy side: instruction ni of a tile writes LDS bytes [ni*1024 + lane*16, +16), i.e. position
+  // p = ni*64 + lane in 16-byte units = (row p / CPRW, slot p % CPRW); it fetches chunk slot ^ key(row)
+  // of that row.  Weight rows are B*2 bytes apart, activation rows sxt*2 bytes (clamped to the last token).
+  uint32_t woff[NI], xoff[NTT * NI];
 #pragma unroll
-  for (int tt = 0; tt < NTT; ++tt) {
-    int t = t_base + tt * 16 + l16;
-    t = t < a.T ? t : a.T - 1;
-    xoff[tt] = ((uint32_t)t * (uint32_t)a.sxt + (uint32_t)g * 8u) * 2u;
+  for (int ni = 0; ni < NI; ++ni) {
+    const int p = ni * 64 + lane, row = p / C::CPRW, slot = p % C::CPRW;
+    woff[ni] = (uint32_t)(q * C::SLB + row * (B * 2) + ((slot ^ C::key(row)) << 4));
   }
+#pragma unroll
+  for (int xi = 0; xi < NTT * NI; ++xi) {
+    const int p = xi * 64 + lane, row = p / C::CPRW, slot = p % C::CPRW;
+    int t = t_base + row;
+    t = t < a.T ? t : a.T - 1;
+    xoff[xi] = (uint32_t)t * (uint32_t)a.sxt * 2u + (uint32_t)((slot ^ C::key(row)) << 4);
+  }
+  // Fragment side: row l16, chunk 4 s + g of a tile image (weights and activations alike).
+  uint32_t foff[KST];
+#pragma unroll
+  for (int s = 0; s < KST; ++s) foff[s] = (uint32_t)(l16 * (B * 2) + (((4 * s + g) ^ C::key(l16)) << 4));
 
-  bf16x8 xf[2][BPR][NTT][KST];
-  // Requests of one round.  Every round issues the same number of operations (slots past the wave's
-  // last block repeat it: a cache hit), so the counter value that means "the previous round has
-  // landed" is a compile-time constant.
-  auto issue = [&](int rd, auto buf_c) {
-    constexpr int buf = decltype(buf_c)::value;
+  // ---- ring -----------------------------------------------------------------------------
+  auto issue = [&](int j) {
+    const int i = wave + 4 * j;
+    const bool second = DUAL && i >= n0;
+    const MatDev& m = second ? a.m1 : a.m0;
+    const int k = second ? kb1 + (i - n0) : kb0 + i;
+    const int col = ld_idx(m.col_idx, k);
+    unsigned char* slot = ring + (j % NSLOT) * C::SLOT;
+    const unsigned char* wblk = reinterpret_cast<const unsigned char*>(m.vals) + (int64_t)k * (B * B * 2);
 #pragma unroll
-    for (int p = 0; p < BPR; ++p) {
-      int j = rd * BPR + p;
-      j = j < cnt ? j : cnt - 1;
-      const int i = wave + 4 * j;
-      const bool second = DUAL && i >= n0;
-      const MatDev& m = second ? a.m1 : a.m0;
-      const int k = second ? kb1 + (i - n0) : kb0 + i;
-      const int col = ld_idx(m.col_idx, k);
-      const unsigned char* xcol = reinterpret_cast<const unsigned char*>(a.X) + (int64_t)col * (B * 2);
+    for (int ni = 0; ni < NI; ++ni) BLAST_GLDS16(wblk + woff[ni], slot + ni * 1024);
+    const unsigned char* xcol = reinterpret_cast<const unsigned char*>(a.X) + (int64_t)col * (B * 2);
 #pragma unroll
-      for (int tt = 0; tt < NTT; ++tt)
-#pragma unroll
-        for (int s = 0; s < KST; ++s) xf[buf][p][tt][s] = *reinterpret_cast<const bf16x8*>(xcol + xoff[tt] + s * 64);
-      const unsigned char* wblk = reinterpret_cast<const unsigned char*>(m.vals) + (int64_t)k * (B * B * 2);
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-        BLAST_GLDS16(wblk + cp_off + ni * 1024, wlds + (buf * BPR + p) * C::SLB + ni * 1024);
-    }
+    for (int xi = 0; xi < NTT * NI; ++xi) BLAST_GLDS16(xcol + xoff[xi], slot + C::SLB + xi * 1024);
   };
-  // Straight-line on purpose: a slot past the wave's last block, or a block of the other matrix,
-  // multiplies a zeroed operand instead of branching around the matrix instruction (the arithmetic
-  // is unchanged: adding 0 * x to an fp32 sum is exact; matrix instructions are not the bottleneck
-  // at these token counts).
-  auto compute = [&](int rd, auto buf_c) {
-    constexpr int buf = decltype(buf_c)::value;
+
+#pragma unroll 1
+  for (int j = 0; j < NSLOT - 1; ++j)
+    if (j < cnt) issue(j);
+
+#pragma unroll 1
+  for (int j = 0; j < cnt; ++j) {
+    // fragment reads of the previous block have returned before its slot is handed back to the copier
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    if (j + NSLOT - 1 < cnt) issue(j + NSLOT - 1);
+    // copies retire in issue order: "at most (blocks issued after j) * OPS outstanding" = block j has landed
+    const int later = (cnt - 1 - j) < (NSLOT - 1) ? (cnt - 1 - j) : (NSLOT - 1);
+    if (later >= 3)
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(3 * C::OPS < 63 ? 3 * C::OPS : 63));
+    else if (later == 2)
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(2 * C::OPS));
+    else if (later == 1)
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(C::OPS));
+    else
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
+    asm volatile("" ::: "memory");
+    const unsigned char* slot = ring + (j % NSLOT) * C::SLOT;
+    const bool second = DUAL && (wave + 4 * j) >= n0;
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    // Straight-line on purpose: a block of the other matrix multiplies a zeroed operand instead of
+    // branching around the matrix instruction (adding 0 * x to an fp32 sum is exact, and matrix
+    // instructions are not the bottleneck at these token counts).
 #pragma unroll
-    for (int p = 0; p < BPR; ++p) {
-      const int j = rd * BPR + p;
-      const bool valid = j < cnt;
-      const bool second = DUAL && (wave + 4 * j) >= n0;
+    for (int s = 0; s < KST; ++s) {
+      const bf16x8 wf = *reinterpret_cast<const bf16x8*>(slot + foff[s]);
+      const bf16x8 w0 = second ? zero : wf;
 #pragma unroll
-      for (int s = 0; s < KST; ++s) {
-        const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wlds + (buf * BPR + p) * C::SLB + frag_off + s * 64);
-        const bf16x8 w0 = (valid && !second) ? wf : zero;
-#pragma unroll
-        for (int tt = 0; tt < NTT; ++tt)
-          acc[0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[buf][p][tt][s], w0, acc[0][tt], 0, 0, 0);
+      for (int tt = 0; tt < NTT; ++tt) {
+        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(slot + C::SLB * (1 + tt) + foff[s]);
+        acc[0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, w0, acc[0][tt], 0, 0, 0);
         if (DUAL) {
-          const bf16x8 w1 = (valid && second) ? wf : zero;
-#pragma unroll
-          for (int tt = 0; tt < NTT; ++tt)
-            acc[NM - 1][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[buf][p][tt][s], w1, acc[NM - 1][tt], 0, 0, 0);
+          const bf16x8 w1 = second ? wf : zero;
+          acc[NM - 1][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, w1, acc[NM - 1][tt], 0, 0, 0);
         }
       }
     }
-  };
-  using Buf0 = std::integral_constant<int, 0>;
-  using Buf1 = std::integral_constant<int, 1>;
-  // One pipeline stage: start the next round (if any) into the other buffer, wait for this one, multiply.
-  auto stage = [&](int rd, auto cur, auto nxt) {
-    if (rd + 1 < rounds) {
-      issue(rd + 1, nxt);
-      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(C::PER_ROUND));
-    } else {
-      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
-    }
     asm volatile("" ::: "memory");
-    compute(rd, cur);
-    asm volatile("" ::: "memory");
-  };
-  if (rounds > 0) issue(0, Buf0{});
-  for (int rd = 0; rd < rounds; rd += 2) {
-    stage(rd, Buf0{}, Buf1{});
-    if (rd + 1 < rounds) stage(rd + 1, Buf1{}, Buf0{});
   }
 
-  // 3. the four partial sums meet in LDS
+  // ---- the four partial sums meet in LDS ---------------------------------------------------
   if (wave > 0) {
 #pragma unroll
     for (int m = 0; m < NM; ++m)
@@ -192,7 +214,7 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
       for (int j = 0; j < 4; ++j)
         acc[m][tt][j] += (red[0][m][tt][j][lane] + red[1][m][tt][j][lane]) + red[2][m][tt][j][lane];
 
-  // 4. epilogue.  Result layout of the 16x16 tile: lane -> weight row l16, register j -> token 4*g + j.
+  // ---- epilogue.  Result layout of the 16x16 tile: lane -> weight row l16, register j -> token 4*g + j.
   const int64_t row = (int64_t)r * B + q * 16 + l16;
 #pragma unroll
   for (int tt = 0; tt < NTT; ++tt)
@@ -203,7 +225,9 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
         float v = acc[0][tt][j];
         if (DUAL) v = apply_act(a.act, v) * acc[NM - 1][tt][j];
         const int64_t off = (int64_t)tok * a.syt + row * a.syi;
-        if (a.y_bf16)
+        if (CHUNK && shared_row)
+          atomicAdd(reinterpret_cast<float*>(a.Y) + off, v);  // fp32 output, zeroed before the launch
+        else if (a.y_bf16)
           reinterpret_cast<uint16_t*>(a.Y)[off] = f32_to_bf16_rne(v);
         else
           reinterpret_cast<float*>(a.Y)[off] = v;
