@@ -114,7 +114,7 @@ int launch_stream(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
   return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, stream);
 }
 
-template <int B, bool DUAL, int NTT, bool CHUNK>
+template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL = false>
 int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   DecArgs d{};
   d.m0 = a.m0;
@@ -132,14 +132,17 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   d.chunk_row = plan.chunk_row;
   d.chunk_kb = plan.chunk_kb;
   d.chunk_ke = plan.chunk_ke;
-  const int64_t grid = (CHUNK ? plan.max_chunks : (int64_t)a.nbr) * (B / 16);
-  if (grid <= 0) return BLAST_OK;
+  const int64_t units = (CHUNK ? plan.max_chunks : (int64_t)a.nbr) * (B / 16);
+  if (units <= 0) return BLAST_OK;
+  const int64_t groups = (a.T + NTT * 16 - 1) / (NTT * 16);
+  const int64_t grid = (units + 7) / 8 * 8 * groups;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
-  const unsigned groups = (unsigned)((a.T + NTT * 16 - 1) / (NTT * 16));
-  using C = DecCfg<B, DUAL, NTT>;
+  d.n_units = (int)units;
+  d.groups = (int)groups;
+  using C = DecCfg<B, DUAL, NTT, XSMALL>;
   static bool attr_set = false;
   if (!attr_set) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK>),
+    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
@@ -148,7 +151,7 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
   }
-  k_decode<B, DUAL, NTT, CHUNK><<<dim3((unsigned)grid, groups), dim3(256), C::LDS_BYTES, stream>>>(d);
+  k_decode<B, DUAL, NTT, CHUNK, XSMALL><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(d);
   BLAST_LAUNCH_CHECK("k_decode");
   return BLAST_OK;
 }
@@ -158,11 +161,18 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
   if constexpr (!DUAL) {
     // rows cut into chunks accumulate with fp32 atomics: only for fp32 output
     if (plan.hdr && !a.y_bf16) {
-      if (a.T <= 16) return launch_decode_ntt<B, false, 1, true>(a, plan, stream);
+      if constexpr (B >= 64) {
+        if (a.T <= 512 / B) return launch_decode_ntt<B, false, 1, true, true>(a, plan, stream);
+      }
+      if (a.T <= 16 || B == 128) return launch_decode_ntt<B, false, 1, true>(a, plan, stream);
       return launch_decode_ntt<B, false, 2, true>(a, plan, stream);
     }
   }
-  if (a.T <= 16) return launch_decode_ntt<B, DUAL, 1, false>(a, ChunkPlan{}, stream);
+  if constexpr (B >= 64) {
+    if (a.T <= 512 / B) return launch_decode_ntt<B, DUAL, 1, false, true>(a, ChunkPlan{}, stream);
+  }
+  // 128-wide blocks: two token tiles per slot would leave room for one workgroup per CU only
+  if (a.T <= 16 || B == 128) return launch_decode_ntt<B, DUAL, 1, false>(a, ChunkPlan{}, stream);
   return launch_decode_ntt<B, DUAL, 2, false>(a, ChunkPlan{}, stream);  // groups of 32 tokens along gridDim.y
 }
 

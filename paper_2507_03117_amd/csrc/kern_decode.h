@@ -40,6 +40,8 @@ struct DecArgs {
   int y_bf16;
   int T;
   int act;
+  int n_units;   // (block rows or chunk slots) * slices
+  int groups;    // token groups of NTT * 16 tokens
   // chunk plan written by the packer (CHUNK instances only): hdr[0] = number of chunks
   const int* hdr;
   const int* chunk_row;  // block row of the chunk; bit 31 set when the row has several chunks
@@ -47,16 +49,23 @@ struct DecArgs {
   const int* chunk_ke;   // one past its last stored block
 };
 
-template <int B, bool DUAL, int NTT>
+// XSMALL: the activation tile of a block holds only as many token rows as one copy instruction brings
+// (512 / B); valid when T does not exceed that.  It shrinks a ring slot, hence allows a deeper ring or
+// more workgroups per CU at the token counts that matter most for decoding.
+template <int B, bool DUAL, int NTT, bool XSMALL = false>
 struct DecCfg {
+  static_assert(!XSMALL || (NTT == 1 && B >= 64), "small activation tiles: one token group, at least 8 chunks per row");
   static constexpr int SLICES = B / 16;       // 16-row slices per block row
   static constexpr int KST = B / 32;          // 32-wide k-steps per block
   static constexpr int SLB = 16 * B * 2;      // bytes of one 16-row slice of a block (= of a 16-token activation tile)
   static constexpr int NI = SLB / 1024;       // wave-wide copy instructions per slice
   static constexpr int CPRW = B / 8;          // 16-byte chunks per row
-  static constexpr int SLOT = SLB * (1 + NTT);
-  static constexpr int NSLOT = (B == 128) ? 2 : ((NTT == 1) ? 4 : 3);
-  static constexpr int OPS = NI * (1 + NTT);  // copy instructions per block and wave
+  static constexpr int XR = XSMALL ? 512 / B : 16 * NTT;  // token rows of the activation tile
+  static constexpr int XB = XR * B * 2;                   // its bytes
+  static constexpr int NIX = XB / 1024;                   // copy instructions per activation tile
+  static constexpr int SLOT = SLB + XB;
+  static constexpr int NSLOT = (B == 128) ? (XSMALL ? 3 : 2) : ((NTT == 1) ? 4 : 3);
+  static constexpr int OPS = NI + NIX;        // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * NSLOT * SLOT;
   static constexpr int RED_LDS = 3 * NM * NTT * 4 * 64 * 4;
@@ -66,18 +75,22 @@ struct DecCfg {
   __device__ static __forceinline__ int key(int row) { return ((row & 15) / (16 / (CPRW < 16 ? CPRW : 16))) % CPRW; }
 };
 
-template <int B, bool DUAL, int NTT, bool CHUNK>
+template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL>
 __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
-  using C = DecCfg<B, DUAL, NTT>;
+  using C = DecCfg<B, DUAL, NTT, XSMALL>;
   constexpr int KST = C::KST, NM = C::NM, NI = C::NI, NSLOT = C::NSLOT;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::RING_LDS);
 
-  // blockIdx.y selects a group of NTT * 16 tokens: more tokens mean more workgroups, each re-reading its
-  // weight slice (the first read comes from HBM, the others from cache)
-  const int t_base = blockIdx.y * (NTT * 16);
-  const int unit = blockIdx.x;
+  // More tokens than one tile holds mean more workgroups per unit, each re-reading the unit's weight
+  // slices.  Workgroup ids are dealt round-robin to the 8 XCDs, so the token groups of one unit are
+  // placed 8 ids apart: same XCD, dispatched together - the re-reads hit that XCD's L2.
+  const int blk = blockIdx.x, span = 8 * a.groups;
+  const int rem = blk % span;
+  const int unit = (blk / span) * 8 + (rem & 7);
+  if (unit >= a.n_units) return;
+  const int t_base = (rem >> 3) * (NTT * 16);
   const int q = unit % C::SLICES;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63, l16 = lane & 15, g = lane >> 4;
@@ -117,23 +130,28 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   // Copy side: instruction ni of a tile writes LDS bytes [ni*1024 + lane*16, +16), i.e. position
   // p = ni*64 + lane in 16-byte units = (row p / CPRW, slot p % CPRW); it fetches chunk slot ^ key(row)
   // of that row.  Weight rows are B*2 bytes apart, activation rows sxt*2 bytes (clamped to the last token).
-  uint32_t woff[NI], xoff[NTT * NI];
+  uint32_t woff[NI], xoff[C::NIX];
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
     const int p = ni * 64 + lane, row = p / C::CPRW, slot = p % C::CPRW;
     woff[ni] = (uint32_t)(q * C::SLB + row * (B * 2) + ((slot ^ C::key(row)) << 4));
   }
 #pragma unroll
-  for (int xi = 0; xi < NTT * NI; ++xi) {
+  for (int xi = 0; xi < C::NIX; ++xi) {
     const int p = xi * 64 + lane, row = p / C::CPRW, slot = p % C::CPRW;
     int t = t_base + row;
     t = t < a.T ? t : a.T - 1;
     xoff[xi] = (uint32_t)t * (uint32_t)a.sxt * 2u + (uint32_t)((slot ^ C::key(row)) << 4);
   }
-  // Fragment side: row l16, chunk 4 s + g of a tile image (weights and activations alike).
-  uint32_t foff[KST];
+  // Fragment side: row l16, chunk 4 s + g of a tile image.  A small activation tile has fewer rows than
+  // the matrix instruction has token lanes: the lanes past it re-read rows whose results are never stored.
+  uint32_t foff[KST], fxoff[KST];
+  const int xrow = XSMALL ? (l16 % C::XR) : l16;
 #pragma unroll
-  for (int s = 0; s < KST; ++s) foff[s] = (uint32_t)(l16 * (B * 2) + (((4 * s + g) ^ C::key(l16)) << 4));
+  for (int s = 0; s < KST; ++s) {
+    foff[s] = (uint32_t)(l16 * (B * 2) + (((4 * s + g) ^ C::key(l16)) << 4));
+    fxoff[s] = (uint32_t)(xrow * (B * 2) + (((4 * s + g) ^ C::key(xrow)) << 4));
+  }
 
   // ---- ring -----------------------------------------------------------------------------
   auto issue = [&](int j) {
@@ -148,7 +166,7 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
     for (int ni = 0; ni < NI; ++ni) BLAST_GLDS16(wblk + woff[ni], slot + ni * 1024);
     const unsigned char* xcol = reinterpret_cast<const unsigned char*>(a.X) + (int64_t)col * (B * 2);
 #pragma unroll
-    for (int xi = 0; xi < NTT * NI; ++xi) BLAST_GLDS16(xcol + xoff[xi], slot + C::SLB + xi * 1024);
+    for (int xi = 0; xi < C::NIX; ++xi) BLAST_GLDS16(xcol + xoff[xi], slot + C::SLB + xi * 1024);
   };
 
 #pragma unroll 1
@@ -184,7 +202,7 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
       const bf16x8 w0 = second ? zero : wf;
 #pragma unroll
       for (int tt = 0; tt < NTT; ++tt) {
-        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(slot + C::SLB * (1 + tt) + foff[s]);
+        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(slot + C::SLB * (1 + tt) + fxoff[s]);
         acc[0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, w0, acc[0][tt], 0, 0, 0);
         if (DUAL) {
           const bf16x8 w1 = second ? wf : zero;

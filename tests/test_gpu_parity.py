@@ -210,7 +210,7 @@ def test_spmm_dense_and_empty_matrix(api):
 
 
 @pytest.mark.parametrize("b,nbc,T", [(32, 70, 300), (64, 40, 520), (128, 36, 200), (64, 72, 300),
-                                     (32, 70, 9), (32, 70, 40), (64, 72, 1), (64, 72, 16), (64, 72, 100), (128, 66, 20)])
+                                     (32, 70, 9), (32, 70, 40), (64, 72, 1), (64, 72, 7), (64, 72, 16), (64, 72, 100), (128, 66, 3), (128, 66, 20)])
 def test_spmm_heavy_rows_are_chunked(api, b, nbc, T):
     """Rows with more than 16 stored blocks are cut into chunks that add their partial sums atomically."""
     import torch
