@@ -11,6 +11,7 @@
 // row-major).  The fp32 result tile then has consecutive weight rows in
 // consecutive lanes, so token-major stores are 128-byte coalesced.
 #include "blast_common.h"
+#include <stdlib.h>
 
 #include "kern_common.h"
 #include "kern_tile.h"
@@ -185,7 +186,9 @@ template <bool DUAL>
 int dispatch_tile(int b, const TileArgs& a, hipStream_t stream, const ChunkPlan& plan = ChunkPlan{}) {
   // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
-  if (a.x_vec && a.T > 0 && a.T <= (DUAL ? kDecodeMaxTokensDual : kDecodeMaxTokens) && small_x) {
+  static const int dbg_dual = getenv("BLAST_DBG_DMAX_DUAL") ? atoi(getenv("BLAST_DBG_DMAX_DUAL")) : kDecodeMaxTokensDual;
+  static const int dbg_single = getenv("BLAST_DBG_DMAX") ? atoi(getenv("BLAST_DBG_DMAX")) : kDecodeMaxTokens;
+  if (a.x_vec && a.T > 0 && a.T <= (DUAL ? dbg_dual : dbg_single) && small_x) {
     switch (b) {
       case 32: return launch_decode<32, DUAL>(a, plan, stream);
       case 64: return launch_decode<64, DUAL>(a, plan, stream);

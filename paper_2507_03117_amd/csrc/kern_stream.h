@@ -143,48 +143,19 @@ __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n
 
 #define BLAST_LANE(v, j) __builtin_amdgcn_readlane((v), (j))
 
-// Position of the loader in the flattened stream of steps.
-template <int NSLICE, bool DUAL>
-struct StepCursor {
-  int round, tile, phase, k, kend, slice, c, c_next;
+// Position of the loader in the flattened stream of steps, kept as running addresses so that the
+// common case (the next block of the same row) costs a handful of scalar additions: a "run" is the
+// list of stored blocks of one (item, matrix) pair.
+struct Loader {
+  const unsigned char* wptr;  // first byte of the current block's values
+  const int* cptr;            // its entry in the column index array
+  int rem;                    // blocks left in the run, the current one included
+  int c, c_next;              // block column of the current block / of the one after it
+  int slice;                  // contraction slice of the current block
+  int tile;                   // token tile of the run
+  int round, phase;           // which run this is
+  uint32_t stage_off;         // LDS byte offset of the stage the next step is copied into
   bool valid;
-
-  // Move to the first step at or after the current position (skips empty phases and items).
-  __device__ __forceinline__ void settle(const ItemTable& t) {
-    while (valid && k >= kend) {
-      if (DUAL && phase == 0) {
-        phase = 1;
-        k = BLAST_LANE(t.k1, round);
-        kend = BLAST_LANE(t.e1, round);
-        c = BLAST_LANE(t.c1, round);
-      } else {
-        ++round;
-        if (round >= t.n_rounds) {
-          valid = false;
-          break;
-        }
-        phase = 0;
-        tile = BLAST_LANE(t.tile, round);
-        k = BLAST_LANE(t.k0, round);
-        kend = BLAST_LANE(t.e0, round);
-        c = BLAST_LANE(t.c0, round);
-      }
-    }
-  }
-  // Called when block k has just been issued for the first time: ask for the column of block k+1.
-  __device__ __forceinline__ void prefetch_col(const TileArgs& a) {
-    if (k + 1 < kend) c_next = ld_idx(((DUAL && phase == 1) ? a.m1 : a.m0).col_idx, k + 1);
-  }
-  __device__ __forceinline__ void advance(const ItemTable& t) {
-    if (++slice == NSLICE) {
-      slice = 0;
-      ++k;
-      if (k < kend)
-        c = c_next;
-      else
-        settle(t);
-    }
-  }
 };
 
 // CHUNK: the items are (chunk of a block row, token tile) pairs from the packer's chunk plan instead of
@@ -239,58 +210,99 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
       xoff[q] = ((uint32_t)t * sxt32 + (uint32_t)((cp_slot ^ C::key(row)) << 3)) * 2u;
     }
   };
-  auto issue = [&](const MatDev& m, int k, int c, int slice, int tile, int stage) {
-    unsigned char* st = smem + stage * C::STAGE;
-    const unsigned char* wblk =
-        reinterpret_cast<const unsigned char*>(m.vals) + (int64_t)k * (B * B * 2) + slice * (C::KS * 2);
-#pragma unroll
-    for (int q = 0; q < C::WQ; ++q) BLAST_GLDS16(wblk + woff[q], st + winstr[q] * 1024);
-    set_tile(tile);
-    const unsigned char* xcol =
-        reinterpret_cast<const unsigned char*>(a.X) + (int64_t)c * (B * 2) + slice * (C::KS * 2);
-#pragma unroll
-    for (int q = 0; q < C::XQ; ++q) BLAST_GLDS16(xcol + xoff[q], st + C::W_BYTES + (q * 4 + wave) * 1024);
-  };
-
   const ItemTable tab = load_item_table<DUAL, CHUNK>(sa, n_items, w, G, lane);
 
-  StepCursor<C::NSLICE, DUAL> ld;
+  Loader ld;
   ld.round = -1;
   ld.phase = DUAL ? 1 : 0;
-  ld.k = ld.kend = 0;
-  ld.tile = 0;
+  ld.rem = 0;
   ld.slice = 0;
+  ld.tile = 0;
   ld.c = ld.c_next = 0;
+  ld.stage_off = 0;
+  ld.wptr = nullptr;
+  ld.cptr = nullptr;
   ld.valid = true;
-  ld.settle(tab);
-  int issued = 0, done = 0;
-  auto issue_next = [&]() {
-    const MatDev& m = (DUAL && ld.phase == 1) ? a.m1 : a.m0;
-    issue(m, ld.k, ld.c, ld.slice, ld.tile, issued % C::NSTAGE);
-    if (ld.slice == 0) ld.prefetch_col(a);
-    ++issued;
-    ld.advance(tab);
+  // Moves the loader to the first block of the next non-empty run (rare: once per row and matrix).
+  auto next_run = [&]() {
+    for (;;) {
+      int k, e;
+      const MatDev* m;
+      if (DUAL && ld.phase == 0) {
+        ld.phase = 1;
+        k = BLAST_LANE(tab.k1, ld.round);
+        e = BLAST_LANE(tab.e1, ld.round);
+        ld.c = BLAST_LANE(tab.c1, ld.round);
+        m = &a.m1;
+      } else {
+        ++ld.round;
+        if (ld.round >= tab.n_rounds) {
+          ld.valid = false;
+          return;
+        }
+        ld.phase = 0;
+        ld.tile = BLAST_LANE(tab.tile, ld.round);
+        k = BLAST_LANE(tab.k0, ld.round);
+        e = BLAST_LANE(tab.e0, ld.round);
+        ld.c = BLAST_LANE(tab.c0, ld.round);
+        m = &a.m0;
+      }
+      if (k < e) {
+        ld.rem = e - k;
+        ld.wptr = reinterpret_cast<const unsigned char*>(m->vals) + (int64_t)k * (B * B * 2);
+        ld.cptr = m->col_idx + k;
+        ld.c_next = ld_idx(ld.cptr, ld.rem > 1 ? 1 : 0);
+        set_tile(ld.tile);
+        return;
+      }
+    }
   };
+  // Issues the copies of the loader's current step and moves it one step on.
+  int ahead = 0;  // steps issued and not yet consumed
+  auto issue_next = [&]() {
+    unsigned char* st = smem + ld.stage_off;
+    const unsigned char* wblk = ld.wptr + ld.slice * (C::KS * 2);
+#pragma unroll
+    for (int q = 0; q < C::WQ; ++q) BLAST_GLDS16(wblk + woff[q], st + winstr[q] * 1024);
+    const unsigned char* xcol =
+        reinterpret_cast<const unsigned char*>(a.X) + (int64_t)ld.c * (B * 2) + ld.slice * (C::KS * 2);
+#pragma unroll
+    for (int q = 0; q < C::XQ; ++q) BLAST_GLDS16(xcol + xoff[q], st + C::W_BYTES + (q * 4 + wave) * 1024);
+    ld.stage_off = (ld.stage_off + C::STAGE == (uint32_t)C::LDS_BYTES) ? 0u : ld.stage_off + C::STAGE;
+    ++ahead;
+    if (C::NSLICE > 1) {
+      if (++ld.slice < C::NSLICE) return;
+      ld.slice = 0;
+    }
+    if (--ld.rem > 0) {
+      ld.wptr += B * B * 2;
+      ++ld.cptr;
+      ld.c = ld.c_next;
+      ld.c_next = ld_idx(ld.cptr, ld.rem > 1 ? 1 : 0);  // the last block of a run re-reads its own entry
+    } else {
+      next_run();
+    }
+  };
+  next_run();
 #pragma unroll 1
   for (int p = 0; p < C::NSTAGE - 1; ++p)
     if (ld.valid) issue_next();
 
   // One step of the stream: wait for its data, let another step's copies go, multiply.
+  uint32_t cstage_off = 0;
   auto do_step = [&](f32x16 (&acc)[C::MI][C::NI]) {
     // Copies retire in issue order, so "at most (later steps in flight) * LPS outstanding" means
-    // this step's copies have landed (stores of an epilogue can only make the wait stricter).
-    const int later = issued - done - 1;
-    if (later >= 2)
-      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(2 * C::LPS));
-    else if (later == 1)
-      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(C::LPS));
+    // this step's copies have landed (stores of an epilogue can only make the wait stricter).  In
+    // the steady state NSTAGE-2 later steps are in flight at this point; the tail waits for all.
+    if (C::NSTAGE > 2 && ahead == C::NSTAGE - 1)
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT((C::NSTAGE - 2) * C::LPS));
     else
       __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
     __builtin_amdgcn_s_barrier();  // everyone's copies have landed; nobody still reads the stage reused next
     asm volatile("" ::: "memory");
-    const int stage = done % C::NSTAGE;
     if (ld.valid) issue_next();
-    const unsigned char* st = smem + stage * C::STAGE;
+    const unsigned char* st = smem + cstage_off;
+    cstage_off = (cstage_off + C::STAGE == (uint32_t)C::LDS_BYTES) ? 0u : cstage_off + C::STAGE;
     const unsigned char* Ws = st;
     const unsigned char* Xs = st + C::W_BYTES;
     bf16x8 af[C::KSTEPS][C::MI], bfg[C::KSTEPS][C::NI];
@@ -310,8 +322,20 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
 #pragma unroll
         for (int ni = 0; ni < C::NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][mi], bfg[kk][ni], acc[mi][ni], 0, 0, 0);
+    // Shape of the schedule inside this block: the fragment reads of the first two k-steps go out
+    // together, then every matrix instruction is paired with one read of the later k-steps, so that
+    // LDS latency hides behind matrix work instead of being waited for read by read.
+    constexpr int kReads = C::KSTEPS * (C::MI + C::NI), kMfma = C::KSTEPS * C::MI * C::NI;
+    constexpr int kLead = kReads / 2;
+    __builtin_amdgcn_sched_group_barrier(0x100, kLead, 0);
+#pragma unroll
+    for (int i = 0; i < kReads - kLead; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, kMfma - (kReads - kLead), 0);
     asm volatile("" ::: "memory");
-    ++done;
+    --ahead;
   };
 
   // ---- compute: item by item -------------------------------------------------------------
