@@ -11,7 +11,6 @@
 // row-major).  The fp32 result tile then has consecutive weight rows in
 // consecutive lanes, so token-major stores are 128-byte coalesced.
 #include "blast_common.h"
-#include <stdlib.h>
 
 #include "kern_common.h"
 #include "kern_tile.h"
@@ -177,18 +176,29 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
   return launch_decode_ntt<B, DUAL, 2, false>(a, ChunkPlan{}, stream);  // groups of 32 tokens along gridDim.y
 }
 
-// Measured crossover with the streaming kernel on the 1B-shaped MLP: the gated (two-matrix) product at
-// about 48 tokens, the single-matrix product beyond 128.
-constexpr int kDecodeMaxTokensDual = 48;
-constexpr int kDecodeMaxTokens = 128;  // beyond this the streaming kernel takes over
+// Crossover with the streaming kernel, from token sweeps on the 1B-shaped MLP.  The decode kernel
+// re-reads a matrix once per group of 16 or 32 tokens (from cache), the streaming kernel once per 256:
+//  - up to 32 tokens the decode kernel always wins;
+//  - the single-matrix product stays ahead up to 256 tokens as long as those re-reads are small
+//    (the launch is latency bound; 13.8 us against 16.5 us at 256 tokens on a 3.3 MB matrix);
+//  - the gated product (two matrices, twice the blocks per workgroup) crosses over at about 40 tokens.
+constexpr int kDecodeAlwaysTokens = 32;
+constexpr int kDecodeMaxTokens = 256;
+constexpr int64_t kDecodeMaxRereadBytes = (int64_t)64 << 20;
 
 template <bool DUAL>
-int dispatch_tile(int b, const TileArgs& a, hipStream_t stream, const ChunkPlan& plan = ChunkPlan{}) {
+bool decode_applies(int b, const TileArgs& a, int64_t nnz) {
+  if (a.T <= kDecodeAlwaysTokens) return true;
+  if (DUAL || a.T > kDecodeMaxTokens) return false;
+  const int64_t group = (b == 128) ? 16 : 32;
+  return nnz * b * b * 2 * ((a.T + group - 1) / group) <= kDecodeMaxRereadBytes;
+}
+
+template <bool DUAL>
+int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, const ChunkPlan& plan = ChunkPlan{}) {
   // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
-  static const int dbg_dual = getenv("BLAST_DBG_DMAX_DUAL") ? atoi(getenv("BLAST_DBG_DMAX_DUAL")) : kDecodeMaxTokensDual;
-  static const int dbg_single = getenv("BLAST_DBG_DMAX") ? atoi(getenv("BLAST_DBG_DMAX")) : kDecodeMaxTokens;
-  if (a.x_vec && a.T > 0 && a.T <= (DUAL ? dbg_dual : dbg_single) && small_x) {
+  if (a.x_vec && a.T > 0 && small_x && decode_applies<DUAL>(b, a, nnz)) {
     switch (b) {
       case 32: return launch_decode<32, DUAL>(a, plan, stream);
       case 64: return launch_decode<64, DUAL>(a, plan, stream);
@@ -312,7 +322,7 @@ extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_
   a.T = (int)T;
   a.nbr = (int)(W->rows / W->b);
   a.act = 0;
-  return dispatch_tile<false>(W->b, a, stream, plan_of(W, T));
+  return dispatch_tile<false>(W->b, a, W->nnz, stream, plan_of(W, T));
 }
 
 extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
@@ -358,7 +368,7 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
   g.T = (int)T;
   g.nbr = (int)(Wgate->rows / Wgate->b);
   g.act = act;
-  return dispatch_tile<true>(Wgate->b, g, stream);
+  return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream);
 }
 
 int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
@@ -386,7 +396,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   d.T = (int)T;
   d.nbr = (int)(E / b);
   d.act = 0;
-  if (int rc = dispatch_tile<false>(b, d, stream, plan_of(Wdown, T))) return rc;
+  if (int rc = dispatch_tile<false>(b, d, Wdown->nnz, stream, plan_of(Wdown, T))) return rc;
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
   return BLAST_OK;
 }
