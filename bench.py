@@ -119,6 +119,42 @@ def time_mlp(api, torch, sets, x, T, steps, warmup, ws):
     return wall_ms, p1, p2, tot
 
 
+def decode_sweep(workload: str, tokens, steps: int, warmup: int):
+    """Decode-sized passes of another workload, packed here: list of per-token-count records."""
+    import torch
+
+    from paper_2507_03117_amd import api, synth
+    from tests.helpers import mask_dev, to_dev
+
+    wl = synth.WORKLOADS[workload]
+    inp = synth.make_mlp(wl)
+    b = wl.b
+    packed = []
+    for l in (inp.gate, inp.up, inp.down):
+        w_ = to_dev(l.W)
+        packed.append(api.bsr_pack(w_, b, mask=mask_dev(l.mask), nnz_cap=int(l.mask.sum())) if l.mask is not None
+                      else api.bsr_pack(w_, b, sparsity=l.sparsity))
+        del w_
+    del inp
+    g, u, d = packed
+    g = api.with_joint_row_order(g, u)
+    nnz = g.nnz + u.nnz + d.nnz
+    w_bytes = nnz * b * b * 2
+    n_copies = max(2, -(-768 * 1024 * 1024 // w_bytes))
+    sets = list(zip(rotated_copies(g, n_copies), rotated_copies(u, n_copies), rotated_copies(d, n_copies)))
+    out = []
+    for T in tokens:
+        x = to_dev(synth.make_x(wl, T))
+        ws = torch.empty(max(api.mlp_workspace_bytes(g, u, d, T), 256), dtype=torch.uint8, device="cuda:0")
+        wall_ms, p1, p2, tot = time_mlp(api, torch, sets, x, T, steps, warmup, ws)
+        alg_bytes = w_bytes + 4 * nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
+        gbs = alg_bytes / (tot * 1e-3) / 1e9
+        out.append({"T": T, "ms_per_step": wall_ms, "ms_events": tot, "ms_gate_up": p1, "ms_down": p2,
+                    "alg_MB": alg_bytes / 1e6, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS})
+    return {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
+            "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +164,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=2048, help="token count of the headline step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-large-decode", action="store_true",
+                    help="skip the decode passes of the 405B-class layer (the case where weight bytes, not launch "
+                         "latency, set the time)")
     ap.add_argument("--decode-tokens", default="", help="comma-separated decode token counts (default: the workload's)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--copies", type=int, default=0,
@@ -260,6 +299,11 @@ def main():
             "rel_fro": float(np.linalg.norm(yh - y_or) / np.linalg.norm(y_or)),
             "max_abs_over_rms": float(np.abs(yh - y_or).max() / np.sqrt((y_or ** 2).mean())),
         }
+
+    if not args.no_large_decode and args.workload == "llama1b_b64_s90":
+        del sets
+        torch.cuda.empty_cache()
+        out["decode_hbm_bound"] = decode_sweep("llama405b_b128_s95_zipf", (1, 16), 30, 5)
 
     print(json.dumps(out))
 
