@@ -37,9 +37,11 @@ PEAK_HBM_GBS = 8000.0
 # Source: profiles/bench_llama1b_b64_s90_hbm_traffic.txt (read x2.0, write x1.0; counters sit between each XCD's
 # L2 and the fabric).  Keys: (kernel, tokens) of the default workload.
 MEASURED_TRAFFIC_BYTES = {
-    ("gate_up", 2048): 63.60e6 + 38.29e6,
-    ("mlp", 1): (7.12e6 + 0.14e6) + (4.30e6 + 0.07e6),
-    ("mlp", 16): (7.12e6 + 0.14e6) + (4.30e6 + 0.07e6),
+    ("gate_up", 2048): 63.49e6 + 38.10e6,
+    ("mlp", 1): 6.90e6 + 3.53e6,
+    ("mlp", 16): (7.39e6 + 0.26e6) + (5.08e6 + 0.13e6),
+    ("llama405b_b128_s95_zipf", 1): (175.59e6 + 0.11e6) + (88.61e6 + 0.13e6 + 0.11e6),
+    ("llama405b_b128_s95_zipf", 16): (181.38e6 + 1.70e6) + (112.17e6 + 2.01e6 + 0.11e6),
 }
 
 
@@ -150,7 +152,8 @@ def decode_sweep(workload: str, tokens, steps: int, warmup: int):
         alg_bytes = w_bytes + 4 * nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
         gbs = alg_bytes / (tot * 1e-3) / 1e9
         out.append({"T": T, "ms_per_step": wall_ms, "ms_events": tot, "ms_gate_up": p1, "ms_down": p2,
-                    "alg_MB": alg_bytes / 1e6, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS})
+                    "alg_MB": alg_bytes / 1e6, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, T))})
     return {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
             "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
 
