@@ -161,6 +161,9 @@ int blast_bsr_joint_row_order(const blast_bsr_view* A, const blast_bsr_view* B, 
  *   Y, ldy, y_dtype    output rows x T in the SAME layout as X; fp32 (BLAST_F32) or bf16 (BLAST_BF16,
  *                      rounded to nearest even from the fp32 accumulator).
  *   ws, ws_bytes       at least blast_bsr_spmm_workspace() bytes (may be 0 -> ws may be NULL).
+ * When W carries `aux` and a very full block row (see max_row_blocks), that row's chunks add their partial
+ * sums into an fp32 Y with atomics in no fixed order: such rows are reproducible up to fp32 rounding of that
+ * sum only (bf16 output and the gated product never take that path).
  * Never synchronises.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */
 int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, void* Y,
@@ -191,8 +194,7 @@ int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view
  * blast_sparse_mlp with three caller-created hipEvent_t recorded on `stream`, so that a caller can
  * time the phases of Eq. (1) inside its own timed region:
  *   events[0] before the first kernel, events[1] after the kernel that finishes H = act(G) (.) U
- *   (Sec. 3.4.3), events[2] after the kernel that finishes Y.  When one kernel does both, events[1]
- *   and events[2] are recorded back to back after it.  `events` is a HOST array of 3 hipEvent_t.
+ *   (Sec. 3.4.3), events[2] after the kernel that finishes Y.  `events` is a HOST array of 3 hipEvent_t.
  * Same arguments, results and errors as blast_sparse_mlp otherwise.
  */
 int blast_sparse_mlp_events(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,

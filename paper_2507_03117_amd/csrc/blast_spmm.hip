@@ -21,15 +21,23 @@ using namespace blast_dev;
 
 namespace {
 
+// Raises a kernel's dynamic-LDS limit once per device (the attribute is per device; setting it again
+// is harmless, so a race between host threads only repeats the call).
+int ensure_lds_limit(const void* kernel, size_t bytes, bool (&done)[64]) {
+  int dev = 0;
+  BLAST_HIP_TRY(hipGetDevice(&dev));
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && done[dev]) return BLAST_OK;
+  BLAST_HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  if (tracked) done[dev] = true;
+  return BLAST_OK;
+}
+
 template <int B, bool DUAL>
 int launch_tile(TileArgs a, hipStream_t stream) {
   using C = TileCfg<B>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
-  if (!attr_set) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_tile<B, DUAL>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-    attr_set = true;
-  }
+  static bool lds_set[64] = {};
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_tile<B, DUAL>), C::LDS_BYTES, lds_set)) return rc;
   a.ntt = (a.T + C::TT - 1) / C::TT;
   const int64_t grid = (int64_t)a.ntt * a.nbr;
   if (grid <= 0) return BLAST_OK;
@@ -63,12 +71,9 @@ struct ChunkPlan {
 template <int B, bool DUAL, int TW, bool CHUNK>
 int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
   using C = StreamCfg<B, TW>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-    attr_set = true;
-  }
+  static bool lds_set[64] = {};
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK>), C::LDS_BYTES, lds_set))
+    return rc;
   a.ntt = (a.T + C::TT - 1) / C::TT;
   const int64_t n_items = (int64_t)a.ntt * (CHUNK ? plan.max_chunks : (int64_t)a.nbr);
   if (n_items <= 0) return BLAST_OK;
@@ -140,12 +145,10 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   d.n_units = (int)units;
   d.groups = (int)groups;
   using C = DecCfg<B, DUAL, NTT, XSMALL>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-    attr_set = true;
-  }
+  static bool lds_set[64] = {};
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL>), C::LDS_BYTES,
+                                lds_set))
+    return rc;
   if (CHUNK) {
     StreamArgs sa{a, 0, -1, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
