@@ -386,6 +386,46 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     // Result layout: lane -> weight row l32 (+32 ni), register j -> token 8*(j/4) + 4*lh + j%4 (+32 mi).
     // A store instruction therefore writes 32 consecutive rows of one token: full 64/128-byte segments.
     const bool full = (t0 + C::TT <= a.T);
+    // Fast path (whole token tile, rows contiguous in memory, no atomics, offsets inside the tile fit 32
+    // bits): one uniform 64-bit base per item and a 32-bit lane offset per store, so that a stored value
+    // costs a conversion, an add and the store instead of 64-bit address arithmetic and predication.
+    if (full && a.y_fast && !(CHUNK && shared_row)) {
+      const uint32_t esz = a.y_bf16 ? 2u : 4u;
+      uint32_t pitch = (uint32_t)a.syt * esz;
+      // opaque to the optimiser: otherwise the 32 multiples of the pitch are computed once before the
+      // loop over items and kept (spilled) for the whole kernel
+      asm volatile("" : "+s"(pitch));
+      unsigned char* base = reinterpret_cast<unsigned char*>(a.Y) + (int64_t)t0 * a.syt * esz;
+      if (a.y_bf16) {
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni) {
+          const uint32_t off0 = (uint32_t)(r * B + rw * C::WT_ROW + ni * 32 + l32) * 2u + (uint32_t)(tw * 64 + 4 * lh) * pitch;
+#pragma unroll
+          for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const uint32_t dt = mi * 32 + 8 * (j / 4) + (j % 4);
+              // the token step goes into the uniform base, the lane offset stays one register
+              unsigned char* bj = base + __builtin_amdgcn_readfirstlane(dt * pitch);
+              *reinterpret_cast<uint16_t*>(bj + off0) = f32_to_bf16_rne(acc0[mi][ni][j]);
+            }
+        }
+      } else {
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni) {
+          const uint32_t off0 = (uint32_t)(r * B + rw * C::WT_ROW + ni * 32 + l32) * 4u + (uint32_t)(tw * 64 + 4 * lh) * pitch;
+#pragma unroll
+          for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const uint32_t dt = mi * 32 + 8 * (j / 4) + (j % 4);
+              unsigned char* bj = base + __builtin_amdgcn_readfirstlane(dt * pitch);
+              *reinterpret_cast<float*>(bj + off0) = acc0[mi][ni][j];
+            }
+        }
+      }
+      continue;
+    }
     auto put = [&](unsigned char* p, float v) {
       if (CHUNK && shared_row)
         atomicAdd(reinterpret_cast<float*>(p), v);  // fp32 output, zeroed before the launch
