@@ -165,6 +165,7 @@ def decode_sweep(workload: str, tokens, steps: int, warmup: int):
         gbs = alg_bytes / (tot * 1e-3) / 1e9
         out.append({"T": T, "ms_per_step": wall_ms, "ms_events": tot, "ms_gate_up": p1, "ms_down": p2,
                     "alg_MB": alg_bytes / 1e6, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
+                    "GBps_wall": alg_bytes / (wall_ms * 1e-3) / 1e9,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, T))})
     return {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
             "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
@@ -285,6 +286,7 @@ def main():
             dec.append({"T": Td, "ms_per_step": r["ms_per_step"], "ms_events": r["ms_events"],
                         "ms_gate_up": r["ms_gate_up"], "ms_down": r["ms_down"], "alg_MB": r["alg_bytes"] / 1e6,
                         "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
+                        "GBps_wall": r["alg_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9,
                         "traffic": MEASURED_TRAFFIC_BYTES.get(("mlp", Td)) if args.workload == "llama1b_b64_s90" else None,
                         "TFLOPs": r["flops"] / (r["ms_events"] * 1e-3) / 1e12})
         out["decode"] = dec

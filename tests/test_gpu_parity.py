@@ -209,6 +209,27 @@ def test_spmm_dense_and_empty_matrix(api):
     assert not y0.cpu().numpy().any()
 
 
+@pytest.mark.parametrize("b", [32, 64, 128])
+@pytest.mark.parametrize("T", [1, 40, 256, 257, 600])
+def test_spmm_strided_operands(api, b, T):
+    """Activations and outputs that are column slices of wider buffers (ld > width); what lies beside the
+    output columns must stay untouched.  Covers the tile boundaries of the kernel choice (256 / 257 tokens)."""
+    import torch
+
+    nbr, nbc = 4, 6
+    w, mask, x = synth.small_case(5000 + b + T, nbr * b, nbc * b, b, 0.5, T, empty_rows=(2,))
+    dev, ref = pack_both(api, w, b, mask=mask)
+    y_or = orc.spmm(ref, x)
+    xw = torch.full((T, nbc * b + 64), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    xw[:, 32:32 + nbc * b] = to_dev(x).view(torch.bfloat16)
+    yw = torch.full((T, nbr * b + 40), -3.0, dtype=torch.float32, device="cuda:0")
+    y = api.bsr_spmm(dev, xw[:, 32:32 + nbc * b], out=yw[:, 8:8 + nbr * b])
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, y_or, f"strided b={b} T={T}")
+    yh = yw.cpu().numpy()
+    assert (yh[:, :8] == -3.0).all() and (yh[:, 8 + nbr * b:] == -3.0).all()
+
+
 @pytest.mark.parametrize("b,nbc,T", [(32, 70, 300), (64, 40, 520), (128, 36, 200), (64, 72, 300),
                                      (32, 70, 9), (32, 70, 40), (64, 72, 1), (64, 72, 7), (64, 72, 16), (64, 72, 100), (128, 66, 3), (128, 66, 20)])
 def test_spmm_heavy_rows_are_chunked(api, b, nbc, T):
