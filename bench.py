@@ -162,10 +162,10 @@ def decode_sweep(workload: str, tokens, steps: int, warmup: int):
         ws = torch.empty(max(api.mlp_workspace_bytes(g, u, d, T), 256), dtype=torch.uint8, device="cuda:0")
         wall_ms, p1, p2, tot = time_mlp(api, torch, sets, x, T, steps, warmup, ws)
         alg_bytes = w_bytes + 4 * nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
-        gbs = alg_bytes / (tot * 1e-3) / 1e9
+        gbs = alg_bytes / (wall_ms * 1e-3) / 1e9  # wall clock of the timed loop
         out.append({"T": T, "ms_per_step": wall_ms, "ms_events": tot, "ms_gate_up": p1, "ms_down": p2,
                     "alg_MB": alg_bytes / 1e6, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
-                    "GBps_wall": alg_bytes / (wall_ms * 1e-3) / 1e9,
+                    "GBps_events": alg_bytes / (tot * 1e-3) / 1e9,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, T))})
     return {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
             "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
@@ -258,7 +258,7 @@ def main():
                         avg_kernel_ms=head["ms_gate_up"], traffic=MEASURED_TRAFFIC_BYTES.get(("gate_up", T)) if args.workload == "llama1b_b64_s90" else None)
     else:
         gbs = head["alg_bytes"] / (head["ms_events"] * 1e-3) / 1e9
-        roofline = dict(bound="hbm", kernel="whole MLP pass", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
+        roofline = dict(bound="hbm", kernel="whole MLP pass (event interval)", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=gbs / PEAK_HBM_GBS, avg_kernel_ms=head["ms_events"],
                         traffic=MEASURED_TRAFFIC_BYTES.get(("mlp", T)))
 
@@ -282,11 +282,11 @@ def main():
         dec_T = [int(t) for t in args.decode_tokens.split(",") if t] or [t for t in wl.tokens if t <= 128]
         for Td in dec_T:
             r = run_T(Td, max(args.steps, 100), args.warmup)
-            gbs = r["alg_bytes"] / (r["ms_events"] * 1e-3) / 1e9
+            gbs = r["alg_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9  # wall clock of the timed loop
             dec.append({"T": Td, "ms_per_step": r["ms_per_step"], "ms_events": r["ms_events"],
                         "ms_gate_up": r["ms_gate_up"], "ms_down": r["ms_down"], "alg_MB": r["alg_bytes"] / 1e6,
                         "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
-                        "GBps_wall": r["alg_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9,
+                        "GBps_events": r["alg_bytes"] / (r["ms_events"] * 1e-3) / 1e9,
                         "traffic": MEASURED_TRAFFIC_BYTES.get(("mlp", Td)) if args.workload == "llama1b_b64_s90" else None,
                         "TFLOPs": r["flops"] / (r["ms_events"] * 1e-3) / 1e12})
         out["decode"] = dec

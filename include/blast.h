@@ -180,7 +180,12 @@ int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_byte
  *
  *   act                BLAST_ACT_SILU (the paper's Eq. (1)), BLAST_ACT_GELU, BLAST_ACT_RELU.
  *   X / Y layout       as in blast_bsr_spmm.
- *   ws, ws_bytes       at least blast_sparse_mlp_workspace() bytes, 256-byte aligned.
+ *   ws, ws_bytes       at least blast_sparse_mlp_workspace() bytes, 256-byte aligned.  Scratch: its contents
+ *                      need no initialisation and mean nothing afterwards; two calls that may overlap in
+ *                      time (different streams) need different workspaces.
+ * Up to one token tile (T <= 32, or 16 for b = 128) with token-major, 16-byte aligned X the whole of Eq. (1)
+ * runs as one kernel launch: the workgroups of the second product wait inside the kernel until the slices of
+ * H they read have been published (a bounded wait; should it ever expire, their output rows are NaN).
  * Never synchronises.  Errors: INVALID_ARG, SHAPE (including inconsistent I/E/b between the three
  * matrices), UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */
@@ -194,7 +199,8 @@ int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view
  * blast_sparse_mlp with three caller-created hipEvent_t recorded on `stream`, so that a caller can
  * time the phases of Eq. (1) inside its own timed region:
  *   events[0] before the first kernel, events[1] after the kernel that finishes H = act(G) (.) U
- *   (Sec. 3.4.3), events[2] after the kernel that finishes Y.  `events` is a HOST array of 3 hipEvent_t.
+ *   (Sec. 3.4.3), events[2] after the kernel that finishes Y.  In the single-launch form events[1] is
+ *   recorded right after events[0], before the kernel.  `events` is a HOST array of 3 hipEvent_t.
  * Same arguments, results and errors as blast_sparse_mlp otherwise.
  */
 int blast_sparse_mlp_events(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,

@@ -12,6 +12,8 @@
 // consecutive lanes, so token-major stores are 128-byte coalesced.
 #include "blast_common.h"
 
+#include <atomic>
+
 #include "kern_common.h"
 #include "kern_tile.h"
 #include "kern_stream.h"
@@ -336,8 +338,10 @@ extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const bla
   if (int rc = check_view(Wup)) return rc;
   if (int rc = check_view(Wdown)) return rc;
   if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
-  // H = act(G) * U in bf16, token-major [T][I]
-  *ws_bytes = blast::align_up((size_t)T * (size_t)Wgate->rows * 2, 256);
+  // H = act(G) * U in bf16, token-major [T][I]; then the publication slots of the single-launch form
+  // (one 64-bit word per 16 rows of H) and two status words
+  *ws_bytes = blast::align_up((size_t)T * (size_t)Wgate->rows * 2, 256) +
+              blast::align_up((size_t)(Wgate->rows / 16) * 8, 256) + 256;
   return BLAST_OK;
 }
 
@@ -376,6 +380,74 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
   return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream);
 }
 
+// Every single-launch MLP gets its own token (never 0): a slot of the workspace says "published" only
+// when it holds the token of the running launch, so the slots need no clearing between launches and no
+// initialisation (a stale or random word equals a fresh 64-bit token with probability 2^-64).
+unsigned long long next_token() {
+  static std::atomic<unsigned long long> counter{0x243F6A8885A308D3ull};
+  return counter.fetch_add(0x9E3779B97F4A7C15ull) | 1ull;
+}
+
+template <int B, int NTT, bool XSMALL>
+int launch_mlp_decode(const DecArgs& p, const DecArgs& c, hipStream_t stream) {
+  using CP = DecCfg<B, true, NTT, XSMALL, true>;
+  static bool lds_set[64] = {};
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_mlp_decode<B, NTT, XSMALL>), CP::LDS_BYTES, lds_set))
+    return rc;
+  const int64_t grid = (int64_t)p.n_units + c.n_units;
+  if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
+  k_mlp_decode<B, NTT, XSMALL><<<dim3((unsigned)grid), dim3(256), CP::LDS_BYTES, stream>>>(p, c);
+  BLAST_LAUNCH_CHECK("k_mlp_decode");
+  return BLAST_OK;
+}
+
+// The single-launch form of the MLP for one token tile.  Applies when both products would take the
+// decode kernel's fast path anyway and no row of Wdown is cut into chunks.
+template <int B>
+int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
+                       const TileArgs& g, const TileArgs& d, uint16_t* H, unsigned long long* slots, int* err,
+                       hipStream_t stream) {
+  DecArgs p{}, c{};
+  p.m0 = g.m0;
+  p.m1 = g.m1;
+  p.row_order = g.row_order;
+  p.X = g.X;
+  p.sxt = g.sxt;
+  p.Y = H;
+  p.syt = Wgate->rows;
+  p.syi = 1;
+  p.y_bf16 = 1;
+  p.T = g.T;
+  p.act = g.act;
+  p.n_units = (int)(Wgate->rows / B) * (B / 16);
+  p.groups = 1;
+  p.slots = slots;
+  p.token = next_token();
+  p.sync_err = err;
+  c.m0 = d.m0;
+  c.row_order = d.row_order;
+  c.X = H;
+  c.sxt = Wgate->rows;
+  c.Y = d.Y;
+  c.syt = d.syt;
+  c.syi = d.syi;
+  c.y_bf16 = d.y_bf16;
+  c.T = d.T;
+  c.act = 0;
+  c.n_units = (int)(Wdown->rows / B) * (B / 16);
+  c.groups = 1;
+  c.slots = slots;
+  c.token = p.token;
+  c.sync_err = err;
+  (void)Wup;
+  if constexpr (B >= 64) {
+    if (g.T <= 512 / B) return launch_mlp_decode<B, 1, true>(p, c, stream);
+  }
+  if (g.T <= 16) return launch_mlp_decode<B, 1, false>(p, c, stream);
+  if constexpr (B != 128) return launch_mlp_decode<B, 2, false>(p, c, stream);
+  return BLAST_ERR_INVALID_ARG;
+}
+
 int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
                 const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy,
                 int32_t y_dtype, void* ws, size_t ws_bytes, hipStream_t stream, void* const* events) {
@@ -389,6 +461,36 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   uint16_t* H = static_cast<uint16_t*>(ws);
 
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[0]), stream));
+  const int64_t one_tile = (b == 128) ? 16 : 32;
+  if (I > 0 && T <= one_tile && (b == 32 || b == 64 || b == 128) && x_layout == BLAST_TOKEN_MAJOR && ldx % 8 == 0 &&
+      blast::aligned(X, 16) && T * ldx * 2 < ((int64_t)1 << 32) && !plan_of(Wdown, T).hdr) {
+    TileArgs g{}, d{};
+    g.m0 = mat_of(Wgate);
+    g.m1 = mat_of(Wup);
+    g.row_order = Wgate->row_order;
+    set_x(g, X, ldx, x_layout);
+    g.T = (int)T;
+    g.act = act;
+    d.m0 = mat_of(Wdown);
+    d.row_order = Wdown->row_order;
+    set_y(d, Y, ldy, x_layout, y_dtype);
+    d.T = (int)T;
+    char* wsb = static_cast<char*>(ws);
+    const size_t h_bytes = blast::align_up((size_t)T * (size_t)I * 2, 256);
+    unsigned long long* slots = reinterpret_cast<unsigned long long*>(wsb + h_bytes);
+    int* err = reinterpret_cast<int*>(wsb + h_bytes + blast::align_up((size_t)(I / 16) * 8, 256));
+    // one kernel does both phases: events[1] falls before it
+    if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));
+    int rc;
+    switch (b) {
+      case 32: rc = enqueue_mlp_decode<32>(Wgate, Wup, Wdown, g, d, H, slots, err, stream); break;
+      case 64: rc = enqueue_mlp_decode<64>(Wgate, Wup, Wdown, g, d, H, slots, err, stream); break;
+      default: rc = enqueue_mlp_decode<128>(Wgate, Wup, Wdown, g, d, H, slots, err, stream); break;
+    }
+    if (rc) return rc;
+    if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
+    return BLAST_OK;
+  }
   if (I > 0) {
     if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream)) return rc;
   }

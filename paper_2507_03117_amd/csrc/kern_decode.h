@@ -47,12 +47,22 @@ struct DecArgs {
   const int* chunk_row;  // block row of the chunk; bit 31 set when the row has several chunks
   const int* chunk_kb;   // first stored block of the chunk
   const int* chunk_ke;   // one past its last stored block
+  // single-launch MLP only: one 64-bit slot per (block row of H, 16-row slice); the producer of that
+  // slice stores `token` there once its part of H is visible device-wide, consumers wait for it
+  unsigned long long* slots;
+  unsigned long long token;
+  int* sync_err;         // set to 1 if a consumer gave up waiting (the result is then invalid)
 };
+
+enum DecRole { kDecAlone = 0, kDecProducer = 1, kDecConsumer = 2 };
+constexpr int kDecMaxSpins = 1 << 19;  // polls of ~0.3 us each before a consumer gives up (never hang the GPU)
 
 // XSMALL: the activation tile of a block holds only as many token rows as one copy instruction brings
 // (512 / B); valid when T does not exceed that.  It shrinks a ring slot, hence allows a deeper ring or
 // more workgroups per CU at the token counts that matter most for decoding.
-template <int B, bool DUAL, int NTT, bool XSMALL = false>
+// FUSED: the instance runs inside the single-launch MLP, where a smaller ring lets the producer and the
+// consumer workgroups of one layer be resident together.
+template <int B, bool DUAL, int NTT, bool XSMALL = false, bool FUSED = false>
 struct DecCfg {
   static_assert(!XSMALL || (NTT == 1 && B >= 64), "small activation tiles: one token group, at least 8 chunks per row");
   static constexpr int SLICES = B / 16;       // 16-row slices per block row
@@ -64,7 +74,7 @@ struct DecCfg {
   static constexpr int XB = XR * B * 2;                   // its bytes
   static constexpr int NIX = XB / 1024;                   // copy instructions per activation tile
   static constexpr int SLOT = SLB + XB;
-  static constexpr int NSLOT = (B == 128) ? (XSMALL ? 3 : 2) : ((NTT == 1) ? 4 : 3);
+  static constexpr int NSLOT = FUSED ? ((B == 128) ? 2 : 3) : ((B == 128) ? (XSMALL ? 3 : 2) : ((NTT == 1) ? 4 : 3));
   static constexpr int OPS = NI + NIX;        // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * NSLOT * SLOT;
@@ -75,22 +85,17 @@ struct DecCfg {
   __device__ static __forceinline__ int key(int row) { return ((row & 15) / (16 / (CPRW < 16 ? CPRW : 16))) % CPRW; }
 };
 
-template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL>
-__global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
+// The work of one workgroup: unit = (block row or chunk, 16-row slice), tokens [t_base, t_base + 16 NTT).
+// ROLE: alone (an ordinary launch); producer / consumer (the two halves of the single-launch MLP: the
+// producer publishes its slice of H, the consumer waits for the slices of H its blocks will read).
+template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL, int ROLE>
+__device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, const int t_base, unsigned char* smem) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
-  using C = DecCfg<B, DUAL, NTT, XSMALL>;
+  static_assert(ROLE == kDecAlone || (ROLE == kDecProducer && DUAL) || (ROLE == kDecConsumer && !DUAL && !CHUNK),
+                "producers are gated products, consumers plain ones");
+  using C = DecCfg<B, DUAL, NTT, XSMALL, ROLE != kDecAlone>;
   constexpr int KST = C::KST, NM = C::NM, NI = C::NI, NSLOT = C::NSLOT;
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::RING_LDS);
-
-  // More tokens than one tile holds mean more workgroups per unit, each re-reading the unit's weight
-  // slices.  Workgroup ids are dealt round-robin to the 8 XCDs, so the token groups of one unit are
-  // placed 8 ids apart: same XCD, dispatched together - the re-reads hit that XCD's L2.
-  const int blk = blockIdx.x, span = 8 * a.groups;
-  const int rem = blk % span;
-  const int unit = (blk / span) * 8 + (rem & 7);
-  if (unit >= a.n_units) return;
-  const int t_base = (rem >> 3) * (NTT * 16);
   const int q = unit % C::SLICES;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63, l16 = lane & 15, g = lane >> 4;
@@ -169,6 +174,45 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
     for (int xi = 0; xi < C::NIX; ++xi) BLAST_GLDS16(xcol + xoff[xi], slot + C::SLB + xi * 1024);
   };
 
+  if (ROLE == kDecConsumer) {
+    // Pull this wave's weight slices towards the L2 while H is still being produced (they do not depend
+    // on it), then wait until every slice of H that its blocks read has been published.
+    uint32_t warm = 0;
+#pragma unroll 1
+    for (int j = 0; j < cnt; ++j) {
+      const int k = kb0 + wave + 4 * j;
+      const unsigned char* wblk = reinterpret_cast<const unsigned char*>(a.m0.vals) + (int64_t)k * (B * B * 2);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) warm ^= *reinterpret_cast<const uint32_t*>(wblk + woff[ni]);
+    }
+    bool gave_up = false;
+#pragma unroll 1
+    for (int j = 0; j < cnt; ++j) {
+      const int col = ld_idx(a.m0.col_idx, kb0 + wave + 4 * j);
+      const unsigned long long* sl = a.slots + (int64_t)col * C::SLICES;
+      int spins = 0;
+      for (;;) {
+        const unsigned long long v =
+            lane < C::SLICES ? __hip_atomic_load(sl + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.token;
+        if (__ballot(v != a.token) == 0) break;
+        if (++spins > kDecMaxSpins) {
+          gave_up = true;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+      }
+    }
+    if (gave_up) {
+      // never observed; if it happens the output rows of this unit become NaN instead of plausible numbers
+      if (lane == 0) __hip_atomic_store(a.sync_err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int tt = 0; tt < NTT; ++tt) acc[0][tt] = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
+    }
+    // keeps the warming loads alive; the value never matches
+    if (warm == 0x9E3779B9u && a.T < 0) a.sync_err[1] = 1;
+    asm volatile("" ::: "memory");
+  }
+
 #pragma unroll 1
   for (int j = 0; j < NSLOT - 1; ++j)
     if (j < cnt) issue(j);
@@ -243,7 +287,10 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
         float v = acc[0][tt][j];
         if (DUAL) v = apply_act(a.act, v) * acc[NM - 1][tt][j];
         const int64_t off = (int64_t)tok * a.syt + row * a.syi;
-        if (CHUNK && shared_row)
+        if (ROLE == kDecProducer)  // written through to where every XCD sees it
+          __hip_atomic_store(reinterpret_cast<uint16_t*>(a.Y) + off, f32_to_bf16_rne(v), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        else if (CHUNK && shared_row)
           atomicAdd(reinterpret_cast<float*>(a.Y) + off, v);  // fp32 output, zeroed before the launch
         else if (a.y_bf16)
           reinterpret_cast<uint16_t*>(a.Y)[off] = f32_to_bf16_rne(v);
@@ -251,6 +298,41 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
           reinterpret_cast<float*>(a.Y)[off] = v;
       }
     }
+  if (ROLE == kDecProducer) {
+    // all of this wave's stores have been acknowledged before the slot says so
+    __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
+    asm volatile("" ::: "memory");
+    if (lane == 0)
+      __hip_atomic_store(a.slots + (int64_t)r * C::SLICES + q, a.token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL>
+__global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  // More tokens than one tile holds mean more workgroups per unit, each re-reading the unit's weight
+  // slices.  Workgroup ids are dealt round-robin to the 8 XCDs, so the token groups of one unit are
+  // placed 8 ids apart: same XCD, dispatched together - the re-reads hit that XCD's L2.
+  const int blk = blockIdx.x, span = 8 * a.groups;
+  const int rem = blk % span;
+  const int unit = (blk / span) * 8 + (rem & 7);
+  if (unit >= a.n_units) return;
+  decode_unit<B, DUAL, NTT, CHUNK, XSMALL, kDecAlone>(a, unit, (rem >> 3) * (NTT * 16), smem);
+}
+
+// Single-launch MLP for one token tile (T <= 16 NTT): workgroups [0, n_units) compute H = act(G) (.) U
+// slice by slice (args `p`), workgroups [n_units, n_units + c.n_units) the down projection (args `c`,
+// whose X is that H).  A consumer only ever waits for producers, which wait for nothing and have lower
+// workgroup ids, hence are dispatched first: the wait always ends (and is bounded besides).
+template <int B, int NTT, bool XSMALL>
+__global__ __launch_bounds__(256) void k_mlp_decode(const DecArgs p, const DecArgs c) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int blk = blockIdx.x;
+  if (blk < p.n_units) {
+    decode_unit<B, true, NTT, false, XSMALL, kDecProducer>(p, blk, 0, smem);
+  } else if (blk - p.n_units < c.n_units) {
+    decode_unit<B, false, NTT, false, XSMALL, kDecConsumer>(c, blk - p.n_units, 0, smem);
+  }
 }
 
 }  // namespace blast_dev
