@@ -307,7 +307,7 @@ def _mlp_case(api, seed, E, I, b, sparsity, T, act="silu", layout="token_major",
 
 
 @pytest.mark.parametrize("b", [16, 32, 64, 128])
-@pytest.mark.parametrize("T", [1, 16, 33, 130, 300])
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 130, 300])
 def test_mlp_small(api, b, T):
     _mlp_case(api, 3000 + b + T, 4 * b, 6 * b, b, 0.5, T)
 
@@ -344,6 +344,27 @@ def test_joint_row_order(api):
     h2 = api.bsr_gated_spmm(gj, du, to_dev(x))
     torch.cuda.synchronize()
     assert torch.equal(h1.view(torch.int16), h2.view(torch.int16))
+
+
+@pytest.mark.parametrize("b,T", [(64, 1), (64, 16), (64, 29), (128, 3), (128, 16)])
+def test_mlp_one_launch_reuses_workspace(api, b, T):
+    """The single-launch form hands H over inside the kernel through the caller's workspace: calls that
+    reuse one workspace with different activations must each see their own H (no stale slots or lines)."""
+    import torch
+
+    rng = np.random.default_rng(7000 + b + T)
+    E, I = 4 * b, 6 * b
+    g, u, d = (synth.gauss_bf16(rng, s, 0.05) for s in ((I, E), (I, E), (E, I)))
+    mg, mu, md = (synth.uniform_mask(rng, r // b, c // b, 0.5) for r, c in ((I, E), (I, E), (E, I)))
+    dg, rg = pack_both(api, g, b, mask=mg)
+    du, ru = pack_both(api, u, b, mask=mu)
+    dd, rd = pack_both(api, d, b, mask=md)
+    ws = torch.full((max(api.mlp_workspace_bytes(dg, du, dd, T), 256),), 0xA5, dtype=torch.uint8, device="cuda:0")
+    for rep in range(4):
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        y = api.sparse_mlp(dg, du, dd, to_dev(x), ws=ws, out=torch.full((T, E), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, orc.mlp(rg, ru, rd, x), f"one launch b={b} T={T} call {rep}")
 
 
 def test_mlp_repeatable(api):
