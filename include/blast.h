@@ -186,6 +186,7 @@ int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_byte
  * Up to one token tile (T <= 32, or 16 for b = 128) with token-major, 16-byte aligned X the whole of Eq. (1)
  * runs as one kernel launch: the workgroups of the second product wait inside the kernel until the slices of
  * H they read have been published (a bounded wait; should it ever expire, their output rows are NaN).
+ * While `stream` is being captured into a graph the two-launch form is recorded instead.
  * Never synchronises.  Errors: INVALID_ARG, SHAPE (including inconsistent I/E/b between the three
  * matrices), UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */

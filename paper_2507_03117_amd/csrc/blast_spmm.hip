@@ -462,9 +462,17 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
 
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[0]), stream));
   const int64_t one_tile = (b == 128) ? 16 : 32;
+  // A captured launch would carry its token into every replay of the graph, and a replay would then find the
+  // slots of the previous replay already "published": while capturing, the two-launch form is recorded.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cap) != hipSuccess) {
+    (void)hipGetLastError();
+    cap = hipStreamCaptureStatusNone;
+  }
   // (b >= 64: a token's slice of one block column of H then fills whole 128-byte lines, so a line is never
   // read by one consumer while the producers of a neighbouring column are still writing the rest of it)
-  if (I > 0 && T <= one_tile && (b == 64 || b == 128) && x_layout == BLAST_TOKEN_MAJOR && ldx % 8 == 0 &&
+  if (I > 0 && T <= one_tile && cap == hipStreamCaptureStatusNone && (b == 64 || b == 128) &&
+      x_layout == BLAST_TOKEN_MAJOR && ldx % 8 == 0 &&
       blast::aligned(X, 16) && T * ldx * 2 < ((int64_t)1 << 32) && !plan_of(Wdown, T).hdr) {
     TileArgs g{}, d{};
     g.m0 = mat_of(Wgate);

@@ -367,6 +367,41 @@ def test_mlp_one_launch_reuses_workspace(api, b, T):
         check_close(y.cpu().numpy().T, orc.mlp(rg, ru, rd, x), f"one launch b={b} T={T} call {rep}")
 
 
+@pytest.mark.parametrize("T", [8, 300])
+def test_mlp_under_graph_capture(api, T):
+    """The call records into a graph (no allocation, no synchronisation, no per-launch host state that a
+    replay would repeat) and every replay, with new activations, matches the oracle."""
+    import torch
+
+    rng = np.random.default_rng(7100 + T)
+    b, E, I = 64, 256, 384
+    g, u, d = (synth.gauss_bf16(rng, s, 0.05) for s in ((I, E), (I, E), (E, I)))
+    mg, mu, md = (synth.uniform_mask(rng, r // b, c // b, 0.5) for r, c in ((I, E), (I, E), (E, I)))
+    dg, rg = pack_both(api, g, b, mask=mg)
+    du, ru = pack_both(api, u, b, mask=mu)
+    dd, rd = pack_both(api, d, b, mask=md)
+    ws = torch.empty(max(api.mlp_workspace_bytes(dg, du, dd, T), 256), dtype=torch.uint8, device="cuda:0")
+    xs = to_dev(synth.gauss_bf16(rng, (T, E), 1.0))
+    y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        api.sparse_mlp(dg, du, dd, xs, out=y, ws=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        api.sparse_mlp(dg, du, dd, xs, out=y, ws=ws)
+    for rep in range(3):
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        xs.copy_(to_dev(x))
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, orc.mlp(rg, ru, rd, x), f"graph replay {rep} T={T}")
+
+
 def test_mlp_repeatable(api):
     import torch
 
