@@ -264,13 +264,11 @@ void set_x(TileArgs& a, const uint16_t* X, int64_t ldx, int32_t layout) {
 void set_y(TileArgs& a, void* Y, int64_t ldy, int32_t layout, int32_t y_dtype) {
   a.Y = Y;
   a.y_bf16 = (y_dtype == BLAST_BF16) ? 1 : 0;
-  a.y_vec = 0;
   a.y_fast = 0;
   if (layout == BLAST_TOKEN_MAJOR) {
     a.syt = ldy;
     a.syi = 1;
     a.y_fast = ((int64_t)256 * ldy * 4 + ldy * 4 < ((int64_t)1 << 31)) ? 1 : 0;
-    a.y_vec = (ldy % 4 == 0 && blast::aligned(Y, 16)) ? 1 : 0;
   } else {
     a.syt = 1;
     a.syi = ldy;

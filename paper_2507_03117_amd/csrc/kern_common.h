@@ -27,7 +27,6 @@ struct TileArgs {
   int ntt;               // token tiles
   int act;
   int x_vec;             // 1: 16-byte loads of X are legal (sxk == 1, aligned)
-  int y_vec;             // 1: four consecutive rows of one token may be stored as one vector (syi == 1, aligned)
   int y_fast;            // 1: syi == 1 and every byte offset inside a 256-token slab of Y fits 31 bits
 };
 
