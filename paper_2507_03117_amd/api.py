@@ -117,9 +117,17 @@ class PackedBsr:
     max_row_blocks: int = 0  # stored blocks of the fullest block row (reported by the packer)
 
     def view(self) -> BsrView:
-        return BsrView(self.rows, self.cols, self.b, self.max_row_blocks, self.nnz, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
-                       self.vals.data_ptr(), self.row_order.data_ptr(),
-                       self.aux.data_ptr() if self.aux is not None else None)
+        """The C struct for this matrix; rebuilt only when an address or a scalar field has changed (a
+        decode-sized call is otherwise dominated by marshalling on the host)."""
+        key = (self.rows, self.cols, self.b, self.max_row_blocks, self.nnz, self.row_ptr.data_ptr(),
+               self.col_idx.data_ptr(), self.vals.data_ptr(), self.row_order.data_ptr(),
+               self.aux.data_ptr() if self.aux is not None else None)
+        cached = self.__dict__.get("_view_cache")
+        if cached is not None and cached[0] == key:
+            return cached[1]
+        v = BsrView(*key)
+        self.__dict__["_view_cache"] = (key, v)
+        return v
 
     def weight_bytes(self) -> int:
         return self.nnz * self.b * self.b * 2
