@@ -291,16 +291,21 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
   // One step of the stream: wait for its data, let another step's copies go, multiply.
   uint32_t cstage_off = 0;
   auto do_step = [&](f32x16 (&acc)[C::MI][C::NI]) {
-    // Copies retire in issue order, so "at most (later steps in flight) * LPS outstanding" means
-    // this step's copies have landed (stores of an epilogue can only make the wait stricter).  In
-    // the steady state NSTAGE-2 later steps are in flight at this point; the tail waits for all.
-    if (C::NSTAGE > 2 && ahead == C::NSTAGE - 1)
-      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT((C::NSTAGE - 2) * C::LPS));
-    else
-      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
-    __builtin_amdgcn_s_barrier();  // everyone's copies have landed; nobody still reads the stage reused next
+    // The stage that the previous step was multiplied out of is refilled first (once every wave has
+    // left it), so that the copies of NSTAGE steps are in flight while this step's are awaited: with
+    // two stages that is twice the bytes in flight of issuing after the wait, for one more barrier.
+    __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (ld.valid) issue_next();
+    // Copies retire in issue order, so "at most (later steps in flight) * LPS outstanding" means
+    // this step's copies have landed (stores of an epilogue can only make the wait stricter).  In
+    // the steady state NSTAGE-1 later steps are in flight at this point; the tail waits for all.
+    if (ahead == C::NSTAGE)
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT((C::NSTAGE - 1) * C::LPS));
+    else
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
+    __builtin_amdgcn_s_barrier();  // everyone's copies of this step have landed
+    asm volatile("" ::: "memory");
     const unsigned char* st = smem + cstage_off;
     cstage_off = (cstage_off + C::STAGE == (uint32_t)C::LDS_BYTES) ? 0u : cstage_off + C::STAGE;
     const unsigned char* Ws = st;
