@@ -268,7 +268,8 @@ __global__ __launch_bounds__(256) void k_fill_csc(const uint8_t* __restrict__ ma
 __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row_ptr, const int* __restrict__ row_order,
                                                      int nbr, int chunk, int* __restrict__ hdr,
                                                      int* __restrict__ chunk_row, int* __restrict__ chunk_kb,
-                                                     int* __restrict__ chunk_ke, int64_t chunk_cap) {
+                                                     int* __restrict__ chunk_ke, int64_t chunk_cap,
+                                                     int* __restrict__ max_row_out) {
   __shared__ int wave_tot[16];
   __shared__ int s_running, s_heavy;
   if (threadIdx.x == 0) {
@@ -305,6 +306,7 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
   if (threadIdx.x == 0) {
     hdr[0] = s_running;
     hdr[1] = s_heavy;
+    *max_row_out = s_heavy;  // next to nnz, so that one copy brings both to the host
     hdr[2] = chunk;
     hdr[3] = 0;
   }
@@ -441,12 +443,26 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
     k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr, row_order, (int)nbr, blast::kChunkBlocks, hdr_dev,
                                                      reinterpret_cast<int*>(ab + A.chunk_row_off),
                                                      reinterpret_cast<int*>(ab + A.chunk_kb_off),
-                                                     reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap);
+                                                     reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap,
+                                                     nnz_dev + 1);
     BLAST_LAUNCH_CHECK("k_chunk_plan");
-    BLAST_HIP_TRY(hipMemcpyAsync(&host_vals[1], hdr_dev + 1, sizeof(int), hipMemcpyDeviceToHost, stream));
   }
-  BLAST_HIP_TRY(hipMemcpyAsync(&host_vals[0], nnz_dev, sizeof(int), hipMemcpyDeviceToHost, stream));
+  // The two scalars come back through a small pinned buffer (one per host thread, allocated on first use
+  // and kept): a copy into pageable memory costs the call tens of microseconds more.
+  static thread_local int* pinned = nullptr;
+  if (!pinned) {
+    void* p = nullptr;
+    if (hipHostMalloc(&p, 64, hipHostMallocDefault) == hipSuccess) {
+      pinned = static_cast<int*>(p);
+    } else {
+      (void)hipGetLastError();
+    }
+  }
+  int* landing = pinned ? pinned : host_vals;
+  BLAST_HIP_TRY(hipMemcpyAsync(landing, nnz_dev, (aux ? 2 : 1) * sizeof(int), hipMemcpyDeviceToHost, stream));
   BLAST_HIP_TRY(hipStreamSynchronize(stream));
+  host_vals[0] = landing[0];
+  if (aux) host_vals[1] = landing[1];
   const int nnz_host = host_vals[0];
   *nnz_out = nnz_host;
   if (max_row_blocks_out) *max_row_blocks_out = aux ? host_vals[1] : 0;
