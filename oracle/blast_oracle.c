@@ -258,3 +258,22 @@ void oracle_mlp(int64_t E, int64_t I, int32_t b,
   free(U);
   free(H);
 }
+
+/* Two-matrix MLP (Sec. 2.1: two or three weight matrices; Sec. 3.4.3: two projections with an element-wise
+ * nonlinearity in between), weights stored out x in:  G = W~1 X, H = bf16(act(G)), Y = W~2 H.
+ * W1 is I x E, W2 is E x I.  H_bits (may be NULL) receives the rounded intermediate, [I][T]. */
+void oracle_mlp2(int64_t E, int64_t I, int32_t b,
+                 const int32_t* w1_row_ptr, const int32_t* w1_col_idx, const uint16_t* w1_vals,
+                 const int32_t* w2_row_ptr, const int32_t* w2_col_idx, const uint16_t* w2_vals,
+                 const uint16_t* X, int64_t sxk, int64_t sxt, int64_t T, int32_t act,
+                 double* Y /* [E][T] */, uint16_t* H_bits /* [I][T] or NULL */) {
+  size_t it = (size_t)I * (size_t)T;
+  double* G = (double*)malloc(sizeof(double) * (it ? it : 1));
+  uint16_t* H = (uint16_t*)malloc(sizeof(uint16_t) * (it ? it : 1));
+  oracle_spmm(I, E, b, w1_row_ptr, w1_col_idx, w1_vals, X, sxk, sxt, T, G);
+  for (size_t p = 0; p < it; ++p) H[p] = f32_to_bf16_rne((float)oracle_act(act, G[p]));
+  oracle_spmm(E, I, b, w2_row_ptr, w2_col_idx, w2_vals, H, T, 1, T, Y);
+  if (H_bits) memcpy(H_bits, H, sizeof(uint16_t) * it);
+  free(G);
+  free(H);
+}

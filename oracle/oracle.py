@@ -44,6 +44,8 @@ def lib():
         L.oracle_act.argtypes = [i32, dbl]
         L.oracle_mlp.restype = None
         L.oracle_mlp.argtypes = [i64, i64, i32] + [vp] * 9 + [vp, i64, i64, i64, i32, vp, vp]
+        L.oracle_mlp2.restype = None
+        L.oracle_mlp2.argtypes = [i64, i64, i32] + [vp] * 6 + [vp, i64, i64, i64, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -160,4 +162,17 @@ def mlp(gate: Bsr, up: Bsr, down: Bsr, X: np.ndarray, layout: str = "token_major
     lib().oracle_mlp(E, I, b, _p(gate.row_ptr), _p(gate.col_idx), _p(gate.vals), _p(up.row_ptr), _p(up.col_idx),
                      _p(up.vals), _p(down.row_ptr), _p(down.col_idx), _p(down.vals), _p(X), sxk, sxt, T,
                      ACT[activation], _p(Y), _p(H))
+    return (Y, H) if return_h else Y
+
+
+def mlp2(w1: Bsr, w2: Bsr, X: np.ndarray, layout: str = "token_major", activation: str = "gelu",
+         return_h: bool = False):
+    """Two-matrix MLP Y = W2 * act(W1 * X) (Sec. 2.1 / Sec. 3.4.3): fp64 [E, T] (and H bf16 bits [I, T] if asked)."""
+    K, T, sxk, sxt = _x_strides(X, layout)
+    E, I, b = w1.cols, w1.rows, w1.b
+    assert K == E and w2.rows == E and w2.cols == I and w2.b == b
+    Y = np.zeros((E, T), dtype=np.float64)
+    H = np.zeros((I, T), dtype=np.uint16) if return_h else None
+    lib().oracle_mlp2(E, I, b, _p(w1.row_ptr), _p(w1.col_idx), _p(w1.vals), _p(w2.row_ptr), _p(w2.col_idx),
+                      _p(w2.vals), _p(X), sxk, sxt, T, ACT[activation], _p(Y), _p(H))
     return (Y, H) if return_h else Y

@@ -354,3 +354,85 @@ def test_h_rounding_is_nearest_even():
         else:
             want = lo if (lo / ulp) % 2 == 0 else hi
         assert Fraction(Y[j]) == want, (j, xv)
+
+
+# ---- two-matrix MLP  Y = W2 act(W1 X)  (Sec. 2.1, Sec. 3.4.3) ----
+
+def _np_act(G, act):
+    if act == "silu":
+        return G / (1.0 + np.exp(-G))
+    if act == "gelu":
+        return 0.5 * G * (1.0 + np.vectorize(math.erf)(G / math.sqrt(2.0)))
+    return np.maximum(G, 0.0)
+
+
+@pytest.mark.parametrize("act", ["gelu", "relu", "silu"])
+def test_mlp2_equals_numpy_dense_formula(act):
+    rng = np.random.default_rng(21)
+    E, I, b, T = 48, 96, 16, 7
+    w1, w2 = (synth.gauss_bf16(rng, s, 0.25) for s in ((I, E), (E, I)))
+    m1, m2 = (synth.uniform_mask(rng, *s, 0.5) for s in ((I // b, E // b), (E // b, I // b)))
+    m1[2, :] = 0  # empty W1 row: act(0) = 0 for all three functions -> H rows zero
+    xb = synth.gauss_bf16(rng, (T, E), 1.0)
+    p1, p2 = orc.pack(w1, b, m1), orc.pack(w2, b, m2)
+    Y, H = orc.mlp2(p1, p2, xb, activation=act, return_h=True)
+    X = f64(xb).T
+    G = (f64(w1) * expand(m1, b)) @ X
+    Href = f64(synth.f32_to_bf16_bits(_np_act(G, act).astype(np.float32)))
+    assert np.array_equal(f64(H), Href)
+    np.testing.assert_allclose(Y, (f64(w2) * expand(m2, b)) @ Href, rtol=1e-12, atol=1e-15)
+    assert not f64(H)[2 * b:3 * b].any()
+    Y2 = orc.mlp2(p1, p2, np.ascontiguousarray(xb.T), layout="feature_major", activation=act)
+    assert np.array_equal(Y, Y2)
+
+
+def test_mlp2_special_cases():
+    rng = np.random.default_rng(22)
+    n, b, T = 32, 8, 5
+    eye = synth.f32_to_bf16_bits(np.eye(n, dtype=np.float32))
+    diag = np.eye(n // b, dtype=np.uint8)
+    pe = orc.pack(eye, b, diag)
+    xb = synth.gauss_bf16(rng, (T, n), 1.0)
+    x = f64(xb).T
+    # identity weights, relu: Y = max(x, 0) exactly (bf16 in, bf16 out)
+    assert np.array_equal(orc.mlp2(pe, pe, xb, activation="relu"), np.maximum(x, 0.0))
+    # W1 = -identity, relu, x >= 0  ->  zero
+    neg = orc.pack(synth.f32_to_bf16_bits(-np.eye(n, dtype=np.float32)), b, diag)
+    xpos = synth.f32_to_bf16_bits(np.abs(x.T).astype(np.float32))
+    assert not orc.mlp2(neg, pe, xpos, activation="relu").any()
+    # gelu is odd up to x:  gelu(x) - gelu(-x) = x;  with identity weights the two outputs differ by x within bf16 rounding
+    yp = orc.mlp2(pe, pe, xb, activation="gelu")
+    yn = orc.mlp2(neg, pe, xb, activation="gelu")
+    assert np.max(np.abs((yp - yn) - x)) <= 2.0 ** -8 * np.max(np.abs(x)) * 2
+    # the second matrix is linear: scaling W2 by 2 doubles Y exactly, a permutation W2 permutes rows of H
+    two = orc.pack(synth.f32_to_bf16_bits(2 * np.eye(n, dtype=np.float32)), b, diag)
+    assert np.array_equal(orc.mlp2(pe, two, xb, activation="silu"), 2 * orc.mlp2(pe, pe, xb, activation="silu"))
+    perm = rng.permutation(n)
+    P = np.zeros((n, n), dtype=np.float32)
+    P[np.arange(n), perm] = 1
+    pp = orc.pack(synth.f32_to_bf16_bits(P), b, np.ones((n // b, n // b), dtype=np.uint8))
+    Yh, H = orc.mlp2(pe, pp, xb, activation="silu", return_h=True)
+    assert np.array_equal(Yh, f64(H)[perm])
+    # zero input -> zero output (act(0) = 0)
+    assert not orc.mlp2(pe, pe, np.zeros_like(xb)).any()
+
+
+def test_mlp2_is_the_gated_mlp_with_a_constant_up_projection():
+    # The three-matrix form with U == 1 everywhere reduces to the two-matrix form.  Make W_up X = 1 by
+    # appending a constant-one feature to X and giving W_up a single 1 in that column of every row.
+    rng = np.random.default_rng(23)
+    E, I, b, T = 32, 64, 8, 6
+    w1 = synth.gauss_bf16(rng, (I, E), 0.3)
+    w1f = f64(w1)
+    w1f[:, E - b:] = 0  # last block column unused by W1, so the constant feature does not leak into G
+    w1 = synth.f32_to_bf16_bits(w1f.astype(np.float32))
+    w2 = synth.gauss_bf16(rng, (E, I), 0.3)
+    up = np.zeros((I, E), dtype=np.float32)
+    up[:, E - 1] = 1.0
+    xf = f64(synth.gauss_bf16(rng, (T, E), 1.0))
+    xf[:, E - 1] = 1.0
+    xb = synth.f32_to_bf16_bits(xf.astype(np.float32))
+    full = lambda r, c: np.ones((r // b, c // b), dtype=np.uint8)
+    p1, pu, p2 = orc.pack(w1, b, full(I, E)), orc.pack(synth.f32_to_bf16_bits(up), b, full(I, E)), orc.pack(w2, b, full(E, I))
+    for act in ("silu", "gelu", "relu"):
+        assert np.array_equal(orc.mlp2(p1, p2, xb, activation=act), orc.mlp(p1, pu, p2, xb, activation=act))
