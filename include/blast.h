@@ -197,6 +197,21 @@ int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view
                                int64_t T, size_t* ws_bytes /* HOST */);
 
 /*
+ * Two-matrix MLP (Sec. 2.1: an MLP block has two or three weight matrices; Sec. 3.4.3: two projections
+ * with an element-wise nonlinearity between them, fused into the first product):
+ *   H = bf16(act(W1 X)),  Y = W2 H.
+ * W1 is I x E, W2 is E x I, both packed with the same block size.  Arithmetic, layouts, workspace rules,
+ * the single-launch form for one token tile, graph-capture behaviour and errors are those of
+ * blast_sparse_mlp (with W1 in the place of Wgate and no Wup); an empty block row of W1 gives a zero
+ * row of H since act(0) = 0 for all three activations.
+ */
+int blast_sparse_mlp2(const blast_bsr_view* W1, const blast_bsr_view* W2, const uint16_t* X, int64_t ldx,
+                      int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                      size_t ws_bytes, void* stream);
+int blast_sparse_mlp2_workspace(const blast_bsr_view* W1, const blast_bsr_view* W2, int64_t T,
+                                size_t* ws_bytes /* HOST */);
+
+/*
  * blast_sparse_mlp with three caller-created hipEvent_t recorded on `stream`, so that a caller can
  * time the phases of Eq. (1) inside its own timed region:
  *   events[0] before the first kernel, events[1] after the kernel that finishes H = act(G) (.) U

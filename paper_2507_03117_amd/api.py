@@ -24,7 +24,7 @@ ACT = {"silu": 0, "gelu": 1, "relu": 2}
 EXPORTS = (
     "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
-    "blast_sparse_mlp_events", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
+    "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
 
@@ -75,6 +75,10 @@ def lib():
         L.blast_sparse_mlp.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
         L.blast_sparse_mlp_workspace.restype = C.c_int
         L.blast_sparse_mlp_workspace.argtypes = [pv, pv, pv, i64, C.POINTER(sz)]
+        L.blast_sparse_mlp2.restype = C.c_int
+        L.blast_sparse_mlp2.argtypes = [pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
+        L.blast_sparse_mlp2_workspace.restype = C.c_int
+        L.blast_sparse_mlp2_workspace.argtypes = [pv, pv, i64, C.POINTER(sz)]
         L.blast_sparse_mlp_events.restype = C.c_int
         L.blast_sparse_mlp_events.argtypes = L.blast_sparse_mlp.argtypes + [C.POINTER(vp)]
         L.blast_bsr_joint_row_order.restype = C.c_int
@@ -233,6 +237,30 @@ def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor,
         _check(L.blast_sparse_mlp(*args), "blast_sparse_mlp")
     else:
         _check(L.blast_sparse_mlp_events(*args, events), "blast_sparse_mlp_events")
+    return Y
+
+
+def mlp2_workspace_bytes(w1: PackedBsr, w2: PackedBsr, T: int) -> int:
+    v1, v2 = w1.view(), w2.view()
+    wsb = C.c_size_t(0)
+    _check(lib().blast_sparse_mlp2_workspace(C.byref(v1), C.byref(v2), T, C.byref(wsb)), "blast_sparse_mlp2_workspace")
+    return int(wsb.value)
+
+
+def sparse_mlp2(w1: PackedBsr, w2: PackedBsr, X: torch.Tensor, *, layout: int = TOKEN_MAJOR, act: str = "gelu",
+                out_dtype: torch.dtype = torch.float32, out: Optional[torch.Tensor] = None,
+                ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_sparse_mlp2: Y = W2 * act(W1 * X)."""
+    L = lib()
+    T, K, ldx = _layout_dims(X, layout)
+    assert K == w1.cols
+    Y = out if out is not None else _alloc_out(w2.rows, T, layout, out_dtype, X.device)
+    v1, v2 = w1.view(), w2.view()
+    if ws is None:
+        ws = torch.empty(max(mlp2_workspace_bytes(w1, w2, T), 256), dtype=torch.uint8, device=X.device)
+    _check(L.blast_sparse_mlp2(C.byref(v1), C.byref(v2), _ptr(X), ldx, layout, T, ACT[act], _ptr(Y), Y.stride(0),
+                               BF16 if Y.dtype == torch.bfloat16 else F32, _ptr(ws), ws.numel(), _stream()),
+           "blast_sparse_mlp2")
     return Y
 
 

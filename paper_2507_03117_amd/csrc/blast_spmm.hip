@@ -38,12 +38,22 @@ int ensure_lds_limit(const void* kernel, size_t bytes, bool (&done)[64]) {
 template <int B, bool DUAL>
 int launch_tile(TileArgs a, hipStream_t stream) {
   using C = TileCfg<B>;
-  static bool lds_set[64] = {};
-  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_tile<B, DUAL>), C::LDS_BYTES, lds_set)) return rc;
   a.ntt = (a.T + C::TT - 1) / C::TT;
   const int64_t grid = (int64_t)a.ntt * a.nbr;
   if (grid <= 0) return BLAST_OK;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
+  if constexpr (!DUAL) {
+    if (a.act >= 0) {  // single matrix with an activation on the output
+      static bool lds_set_post[64] = {};
+      if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_tile<B, false, true>), C::LDS_BYTES, lds_set_post))
+        return rc;
+      k_spmm_tile<B, false, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(a);
+      BLAST_LAUNCH_CHECK("k_spmm_tile");
+      return BLAST_OK;
+    }
+  }
+  static bool lds_set[64] = {};
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_tile<B, DUAL>), C::LDS_BYTES, lds_set)) return rc;
   k_spmm_tile<B, DUAL><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(a);
   BLAST_LAUNCH_CHECK("k_spmm_tile");
   return BLAST_OK;
@@ -73,9 +83,6 @@ struct ChunkPlan {
 template <int B, bool DUAL, int TW, bool CHUNK>
 int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
   using C = StreamCfg<B, TW>;
-  static bool lds_set[64] = {};
-  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK>), C::LDS_BYTES, lds_set))
-    return rc;
   a.ntt = (a.T + C::TT - 1) / C::TT;
   const int64_t n_items = (int64_t)a.ntt * (CHUNK ? plan.max_chunks : (int64_t)a.nbr);
   if (n_items <= 0) return BLAST_OK;
@@ -93,6 +100,20 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
   }
+  if constexpr (!DUAL && !CHUNK) {
+    if (a.act >= 0) {  // single matrix with an activation on the output
+      static bool lds_set_post[64] = {};
+      if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, false, TW, false, true>), C::LDS_BYTES,
+                                    lds_set_post))
+        return rc;
+      k_spmm_stream<B, false, TW, false, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
+      BLAST_LAUNCH_CHECK("k_spmm_stream");
+      return BLAST_OK;
+    }
+  }
+  static bool lds_set[64] = {};
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK>), C::LDS_BYTES, lds_set))
+    return rc;
   k_spmm_stream<B, DUAL, TW, CHUNK><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
   BLAST_LAUNCH_CHECK("k_spmm_stream");
   return BLAST_OK;
@@ -115,8 +136,8 @@ int launch_stream_c(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream
 template <int B, bool DUAL>
 int launch_stream(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   if constexpr (!DUAL) {
-    // rows cut into chunks accumulate with fp32 atomics: only for fp32 output
-    if (plan.hdr && !a.y_bf16) return launch_stream_c<B, false, true>(a, plan, stream);
+    // rows cut into chunks accumulate with fp32 atomics: only for fp32 output without an activation
+    if (plan.hdr && !a.y_bf16 && a.act < 0) return launch_stream_c<B, false, true>(a, plan, stream);
   }
   return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, stream);
 }
@@ -147,6 +168,17 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   d.n_units = (int)units;
   d.groups = (int)groups;
   using C = DecCfg<B, DUAL, NTT, XSMALL>;
+  if constexpr (!DUAL && !CHUNK) {
+    if (a.act >= 0) {  // single matrix with an activation on the output
+      static bool lds_set_post[64] = {};
+      if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, false, NTT, false, XSMALL, true>),
+                                    C::LDS_BYTES, lds_set_post))
+        return rc;
+      k_decode<B, false, NTT, false, XSMALL, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(d);
+      BLAST_LAUNCH_CHECK("k_decode");
+      return BLAST_OK;
+    }
+  }
   static bool lds_set[64] = {};
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL>), C::LDS_BYTES,
                                 lds_set))
@@ -164,8 +196,8 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
 template <int B, bool DUAL>
 int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   if constexpr (!DUAL) {
-    // rows cut into chunks accumulate with fp32 atomics: only for fp32 output
-    if (plan.hdr && !a.y_bf16) {
+    // rows cut into chunks accumulate with fp32 atomics: only for fp32 output without an activation
+    if (plan.hdr && !a.y_bf16 && a.act < 0) {
       if constexpr (B >= 64) {
         if (a.T <= 512 / B) return launch_decode_ntt<B, false, 1, true, true>(a, plan, stream);
       }
@@ -326,9 +358,19 @@ extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_
   set_y(a, Y, ldy, x_layout, y_dtype);
   a.T = (int)T;
   a.nbr = (int)(W->rows / W->b);
-  a.act = 0;
+  a.act = -1;
   return dispatch_tile<false>(W->b, a, W->nnz, stream, plan_of(W, T));
 }
+
+namespace {
+
+// H in bf16, token-major [T][I]; then the publication slots of the single-launch form (one 64-bit word
+// per 16 rows of H) and two status words
+size_t mlp_workspace_bytes(int64_t I, int64_t T) {
+  return blast::align_up((size_t)T * (size_t)I * 2, 256) + blast::align_up((size_t)(I / 16) * 8, 256) + 256;
+}
+
+}  // namespace
 
 extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
                                           const blast_bsr_view* Wdown, int64_t T, size_t* ws_bytes) {
@@ -336,10 +378,16 @@ extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const bla
   if (int rc = check_view(Wup)) return rc;
   if (int rc = check_view(Wdown)) return rc;
   if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
-  // H = act(G) * U in bf16, token-major [T][I]; then the publication slots of the single-launch form
-  // (one 64-bit word per 16 rows of H) and two status words
-  *ws_bytes = blast::align_up((size_t)T * (size_t)Wgate->rows * 2, 256) +
-              blast::align_up((size_t)(Wgate->rows / 16) * 8, 256) + 256;
+  *ws_bytes = mlp_workspace_bytes(Wgate->rows, T);
+  return BLAST_OK;
+}
+
+extern "C" int blast_sparse_mlp2_workspace(const blast_bsr_view* W1, const blast_bsr_view* W2, int64_t T,
+                                           size_t* ws_bytes) {
+  if (int rc = check_view(W1)) return rc;
+  if (int rc = check_view(W2)) return rc;
+  if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
+  *ws_bytes = mlp_workspace_bytes(W1->rows, T);
   return BLAST_OK;
 }
 
@@ -348,12 +396,13 @@ namespace {
 int check_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown, const uint16_t* X,
               int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype) {
   if (int rc = check_view(Wgate)) return rc;
-  if (int rc = check_view(Wup)) return rc;
+  if (Wup)
+    if (int rc = check_view(Wup)) return rc;
   if (int rc = check_view(Wdown)) return rc;
   const int64_t I = Wgate->rows, E = Wgate->cols;
   const int32_t b = Wgate->b;
-  if (Wup->rows != I || Wup->cols != E || Wdown->rows != E || Wdown->cols != I || Wup->b != b || Wdown->b != b)
-    return BLAST_ERR_SHAPE;
+  if (Wup && (Wup->rows != I || Wup->cols != E || Wup->b != b)) return BLAST_ERR_SHAPE;
+  if (Wdown->rows != E || Wdown->cols != I || Wdown->b != b) return BLAST_ERR_SHAPE;
   if (T < 0 || T > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
   if (act != BLAST_ACT_SILU && act != BLAST_ACT_GELU && act != BLAST_ACT_RELU) return BLAST_ERR_INVALID_ARG;
   if (y_dtype != BLAST_F32 && y_dtype != BLAST_BF16) return BLAST_ERR_INVALID_ARG;
@@ -362,19 +411,20 @@ int check_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blas
   return BLAST_OK;
 }
 
-// H = act(Wgate X) (.) (Wup X), bf16, strides given by (h_layout, ldh).
+// H = act(Wgate X) (.) (Wup X), or H = act(Wgate X) when Wup is null; bf16, strides given by (h_layout, ldh).
 int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const uint16_t* X, int64_t ldx,
                   int32_t x_layout, int64_t T, int32_t act, uint16_t* H, int64_t ldh, int32_t h_layout,
                   hipStream_t stream) {
   TileArgs g{};
   g.m0 = mat_of(Wgate);
-  g.m1 = mat_of(Wup);
+  if (Wup) g.m1 = mat_of(Wup);
   g.row_order = Wgate->row_order;
   set_x(g, X, ldx, x_layout);
   set_y(g, H, ldh, h_layout, BLAST_BF16);
   g.T = (int)T;
   g.nbr = (int)(Wgate->rows / Wgate->b);
   g.act = act;
+  if (!Wup) return dispatch_tile<false>(Wgate->b, g, Wgate->nnz, stream);
   return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream);
 }
 
@@ -386,22 +436,23 @@ unsigned long long next_token() {
   return counter.fetch_add(0x9E3779B97F4A7C15ull) | 1ull;
 }
 
-template <int B, int NTT, bool XSMALL>
+template <int B, int NTT, bool XSMALL, bool GATED>
 int launch_mlp_decode(const DecArgs& p, const DecArgs& c, hipStream_t stream) {
-  using CP = DecCfg<B, true, NTT, XSMALL, true>;
+  using CP = DecCfg<B, GATED, NTT, XSMALL, true>;  // the producer's footprint is never below the consumer's
   static bool lds_set[64] = {};
-  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_mlp_decode<B, NTT, XSMALL>), CP::LDS_BYTES, lds_set))
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_mlp_decode<B, NTT, XSMALL, GATED>), CP::LDS_BYTES,
+                                lds_set))
     return rc;
   const int64_t grid = (int64_t)p.n_units + c.n_units;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
-  k_mlp_decode<B, NTT, XSMALL><<<dim3((unsigned)grid), dim3(256), CP::LDS_BYTES, stream>>>(p, c);
+  k_mlp_decode<B, NTT, XSMALL, GATED><<<dim3((unsigned)grid), dim3(256), CP::LDS_BYTES, stream>>>(p, c);
   BLAST_LAUNCH_CHECK("k_mlp_decode");
   return BLAST_OK;
 }
 
 // The single-launch form of the MLP for one token tile.  Applies when both products would take the
 // decode kernel's fast path anyway and no row of Wdown is cut into chunks.
-template <int B>
+template <int B, bool GATED>
 int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
                        const TileArgs& g, const TileArgs& d, uint16_t* H, unsigned long long* slots, int* err,
                        hipStream_t stream) {
@@ -431,7 +482,7 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
   c.syi = d.syi;
   c.y_bf16 = d.y_bf16;
   c.T = d.T;
-  c.act = 0;
+  c.act = -1;
   c.n_units = (int)(Wdown->rows / B) * (B / 16);
   c.groups = 1;
   c.slots = slots;
@@ -439,10 +490,10 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
   c.sync_err = err;
   (void)Wup;
   if constexpr (B >= 64) {
-    if (g.T <= 512 / B) return launch_mlp_decode<B, 1, true>(p, c, stream);
+    if (g.T <= 512 / B) return launch_mlp_decode<B, 1, true, GATED>(p, c, stream);
   }
-  if (g.T <= 16) return launch_mlp_decode<B, 1, false>(p, c, stream);
-  if constexpr (B != 128) return launch_mlp_decode<B, 2, false>(p, c, stream);
+  if (g.T <= 16) return launch_mlp_decode<B, 1, false, GATED>(p, c, stream);
+  if constexpr (B != 128) return launch_mlp_decode<B, 2, false, GATED>(p, c, stream);
   return BLAST_ERR_INVALID_ARG;
 }
 
@@ -453,8 +504,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   const int64_t I = Wgate->rows, E = Wgate->cols;
   const int32_t b = Wgate->b;
   if (T == 0 || E == 0) return BLAST_OK;
-  size_t need = 0;
-  blast_sparse_mlp_workspace(Wgate, Wup, Wdown, T, &need);
+  const size_t need = mlp_workspace_bytes(I, T);
   if (need > 0 && (!ws || ws_bytes < need || !blast::aligned(ws, 256))) return BLAST_ERR_WORKSPACE;
   uint16_t* H = static_cast<uint16_t*>(ws);
 
@@ -474,7 +524,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
       blast::aligned(X, 16) && T * ldx * 2 < ((int64_t)1 << 32) && !plan_of(Wdown, T).hdr) {
     TileArgs g{}, d{};
     g.m0 = mat_of(Wgate);
-    g.m1 = mat_of(Wup);
+    if (Wup) g.m1 = mat_of(Wup);
     g.row_order = Wgate->row_order;
     set_x(g, X, ldx, x_layout);
     g.T = (int)T;
@@ -490,9 +540,12 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
     // one kernel does both phases: events[1] falls before it
     if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));
     int rc;
-    switch (b) {
-      case 64: rc = enqueue_mlp_decode<64>(Wgate, Wup, Wdown, g, d, H, slots, err, stream); break;
-      default: rc = enqueue_mlp_decode<128>(Wgate, Wup, Wdown, g, d, H, slots, err, stream); break;
+    if (Wup) {
+      rc = (b == 64) ? enqueue_mlp_decode<64, true>(Wgate, Wup, Wdown, g, d, H, slots, err, stream)
+                     : enqueue_mlp_decode<128, true>(Wgate, Wup, Wdown, g, d, H, slots, err, stream);
+    } else {
+      rc = (b == 64) ? enqueue_mlp_decode<64, false>(Wgate, Wup, Wdown, g, d, H, slots, err, stream)
+                     : enqueue_mlp_decode<128, false>(Wgate, Wup, Wdown, g, d, H, slots, err, stream);
     }
     if (rc) return rc;
     if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
@@ -509,7 +562,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   set_y(d, Y, ldy, x_layout, y_dtype);
   d.T = (int)T;
   d.nbr = (int)(E / b);
-  d.act = 0;
+  d.act = -1;
   if (int rc = dispatch_tile<false>(b, d, Wdown->nnz, stream, plan_of(Wdown, T))) return rc;
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
   return BLAST_OK;
@@ -520,7 +573,15 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
 extern "C" int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
                                 const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y,
                                 int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes, void* stream_) {
+  if (!Wup) return BLAST_ERR_INVALID_ARG;
   return enqueue_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, ws_bytes,
+                     static_cast<hipStream_t>(stream_), nullptr);
+}
+
+extern "C" int blast_sparse_mlp2(const blast_bsr_view* W1, const blast_bsr_view* W2, const uint16_t* X, int64_t ldx,
+                                 int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype,
+                                 void* ws, size_t ws_bytes, void* stream_) {
+  return enqueue_mlp(W1, nullptr, W2, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, ws_bytes,
                      static_cast<hipStream_t>(stream_), nullptr);
 }
 
@@ -528,7 +589,7 @@ extern "C" int blast_sparse_mlp_events(const blast_bsr_view* Wgate, const blast_
                                        const blast_bsr_view* Wdown, const uint16_t* X, int64_t ldx, int32_t x_layout,
                                        int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
                                        size_t ws_bytes, void* stream_, void* const* events) {
-  if (!events || !events[0] || !events[1] || !events[2]) return BLAST_ERR_INVALID_ARG;
+  if (!Wup || !events || !events[0] || !events[1] || !events[2]) return BLAST_ERR_INVALID_ARG;
   return enqueue_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, ws_bytes,
                      static_cast<hipStream_t>(stream_), events);
 }

@@ -25,7 +25,7 @@ struct TileArgs {
   int T;
   int nbr;               // block rows of the output
   int ntt;               // token tiles
-  int act;
+  int act;               // gated product: the activation of the gate; single matrix: < 0 none, else applied to the output
   int x_vec;             // 1: 16-byte loads of X are legal (sxk == 1, aligned)
   int y_fast;            // 1: syi == 1 and every byte offset inside a 256-token slab of Y fits 31 bits
 };

@@ -39,7 +39,7 @@ struct DecArgs {
   int64_t syt, syi;
   int y_bf16;
   int T;
-  int act;
+  int act;       // as in TileArgs
   int n_units;   // (block rows or chunk slots) * slices
   int groups;    // token groups of NTT * 16 tokens
   // chunk plan written by the packer (CHUNK instances only): hdr[0] = number of chunks
@@ -88,11 +88,15 @@ struct DecCfg {
 // The work of one workgroup: unit = (block row or chunk, 16-row slice), tokens [t_base, t_base + 16 NTT).
 // ROLE: alone (an ordinary launch); producer / consumer (the two halves of the single-launch MLP: the
 // producer publishes its slice of H, the consumer waits for the slices of H its blocks will read).
-template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL, int ROLE>
+// POST: a single-matrix product whose sums go through the activation a.act before they are stored (the
+// first half of a two-matrix MLP).
+template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL, int ROLE, bool POST = false>
 __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, const int t_base, unsigned char* smem) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
-  static_assert(ROLE == kDecAlone || (ROLE == kDecProducer && DUAL) || (ROLE == kDecConsumer && !DUAL && !CHUNK),
-                "producers are gated products, consumers plain ones");
+  static_assert(!POST || (!DUAL && !CHUNK), "an activation on the output needs complete sums of a single matrix");
+  static_assert(ROLE == kDecAlone || (ROLE == kDecProducer && !CHUNK && (DUAL || POST)) ||
+                    (ROLE == kDecConsumer && !DUAL && !CHUNK && !POST),
+                "producers compute the activated intermediate, consumers a plain product");
   using C = DecCfg<B, DUAL, NTT, XSMALL, ROLE != kDecAlone>;
   constexpr int KST = C::KST, NM = C::NM, NI = C::NI, NSLOT = C::NSLOT;
   float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::RING_LDS);
@@ -286,6 +290,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
       if (tok < a.T) {
         float v = acc[0][tt][j];
         if (DUAL) v = apply_act(a.act, v) * acc[NM - 1][tt][j];
+        if (POST) v = apply_act(a.act, v);
         const int64_t off = (int64_t)tok * a.syt + row * a.syi;
         if (ROLE == kDecProducer)  // written through to where every XCD sees it
           __hip_atomic_store(reinterpret_cast<uint16_t*>(a.Y) + off, f32_to_bf16_rne(v), __ATOMIC_RELAXED,
@@ -307,7 +312,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   }
 }
 
-template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL>
+template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL, bool POST = false>
 __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // More tokens than one tile holds mean more workgroups per unit, each re-reading the unit's weight
@@ -317,19 +322,19 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   const int rem = blk % span;
   const int unit = (blk / span) * 8 + (rem & 7);
   if (unit >= a.n_units) return;
-  decode_unit<B, DUAL, NTT, CHUNK, XSMALL, kDecAlone>(a, unit, (rem >> 3) * (NTT * 16), smem);
+  decode_unit<B, DUAL, NTT, CHUNK, XSMALL, kDecAlone, POST>(a, unit, (rem >> 3) * (NTT * 16), smem);
 }
 
-// Single-launch MLP for one token tile (T <= 16 NTT): workgroups [0, n_units) compute H = act(G) (.) U
-// slice by slice (args `p`), workgroups [n_units, n_units + c.n_units) the down projection (args `c`,
-// whose X is that H).  A consumer only ever waits for producers, which wait for nothing and have lower
+// Single-launch MLP for one token tile (T <= 16 NTT): workgroups [0, n_units) compute H slice by slice
+// (args `p`; H = act(G) (.) U with GATED, H = act(W1 X) without), workgroups [n_units, n_units + c.n_units)
+// the last projection (args `c`, whose X is that H).  A consumer only ever waits for producers, which wait for nothing and have lower
 // workgroup ids, hence are dispatched first: the wait always ends (and is bounded besides).
-template <int B, int NTT, bool XSMALL>
+template <int B, int NTT, bool XSMALL, bool GATED = true>
 __global__ __launch_bounds__(256) void k_mlp_decode(const DecArgs p, const DecArgs c) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int blk = blockIdx.x;
   if (blk < p.n_units) {
-    decode_unit<B, true, NTT, false, XSMALL, kDecProducer>(p, blk, 0, smem);
+    decode_unit<B, GATED, NTT, false, XSMALL, kDecProducer, !GATED>(p, blk, 0, smem);
   } else if (blk - p.n_units < c.n_units) {
     decode_unit<B, false, NTT, false, XSMALL, kDecConsumer>(c, blk - p.n_units, 0, smem);
   }

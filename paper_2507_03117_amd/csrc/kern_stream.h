@@ -160,9 +160,12 @@ struct Loader {
 
 // CHUNK: the items are (chunk of a block row, token tile) pairs from the packer's chunk plan instead of
 // (block row, token tile); a row made of several chunks adds its partial sums into a zeroed fp32 output.
-template <int B, bool DUAL, int TW, bool CHUNK>
+// POST: a single-matrix product whose result goes through the activation a.act before it is stored
+// (the first half of a two-matrix MLP).
+template <int B, bool DUAL, int TW, bool CHUNK, bool POST = false>
 __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_stream(const StreamArgs sa) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
+  static_assert(!POST || (!DUAL && !CHUNK), "an activation on the output needs complete sums of a single matrix");
   using C = StreamCfg<B, TW>;
   const TileArgs& a = sa.t;
   const int n_items = CHUNK ? ld_idx(sa.hdr, 0) * a.ntt : sa.n_items;
@@ -385,6 +388,31 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
           for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = apply_act(a.act, acc0[mi][ni][j]) * acc1[mi][ni][j];
+      }
+    }
+    if (POST) {
+      // the branch on the activation stays outside the unrolled loops: one copy of each function body
+      if (a.act == BLAST_ACT_GELU) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = apply_act(BLAST_ACT_GELU, acc0[mi][ni][j]);
+      } else if (a.act == BLAST_ACT_SILU) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = apply_act(BLAST_ACT_SILU, acc0[mi][ni][j]);
+      } else {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = apply_act(BLAST_ACT_RELU, acc0[mi][ni][j]);
       }
     }
 

@@ -126,8 +126,9 @@ __device__ __forceinline__ void run_row(const TileArgs& a, const MatDev& m, int 
 
 // One workgroup = one (block row, token tile).  DUAL: two matrices with the same
 // shape share the tile; the epilogue writes bf16 act(acc0) * acc1.
-template <int B, bool DUAL>
+template <int B, bool DUAL, bool POST = false>
 __global__ __launch_bounds__(256) void k_spmm_tile(const TileArgs a) {
+  static_assert(!(POST && DUAL), "an activation on the output belongs to the single-matrix product");
   using C = TileCfg<B>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Xs = reinterpret_cast<uint16_t*>(smem);
@@ -164,6 +165,14 @@ __global__ __launch_bounds__(256) void k_spmm_tile(const TileArgs a) {
       for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = apply_act(a.act, acc0[mi][ni][j]) * acc1[mi][ni][j];
+  }
+  if (POST) {
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = apply_act(a.act, acc0[mi][ni][j]);
   }
 
   // Result layout of the 32x32 MFMA: lane -> column (weight row) l32, register j -> token 8*(j/4) + 4*lh + j%4.

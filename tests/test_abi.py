@@ -82,9 +82,18 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     d_bad = api.BsrView(128, 128, 64, 0, 0, v.row_ptr, None, None, None, None)
     assert L.blast_sparse_mlp(C.byref(g), C.byref(g), C.byref(d_bad), None, 128, 0, 4, 0, None, 128, 0, None, 0, None) == -2
     assert L.blast_sparse_mlp(C.byref(g), C.byref(g), C.byref(d_ok), None, 128, 0, 4, 9, None, 128, 0, None, 0, None) == -1
+    assert L.blast_sparse_mlp(C.byref(g), None, C.byref(d_ok), None, 128, 0, 4, 0, None, 128, 0, None, 0, None) == -1
     ws = C.c_size_t(0)
     assert L.blast_sparse_mlp_workspace(C.byref(g), C.byref(g), C.byref(d_ok), 16, C.byref(ws)) == 0
     assert ws.value >= 16 * 256 * 2
+    # two-matrix MLP: same checks
+    assert L.blast_sparse_mlp2(C.byref(g), C.byref(d_bad), None, 128, 0, 4, 1, None, 128, 0, None, 0, None) == -2
+    assert L.blast_sparse_mlp2(C.byref(g), C.byref(d_ok), None, 128, 0, 4, 9, None, 128, 0, None, 0, None) == -1
+    assert L.blast_sparse_mlp2(C.byref(g), None, None, 128, 0, 4, 1, None, 128, 0, None, 0, None) == -1
+    assert L.blast_sparse_mlp2(C.byref(g), C.byref(d_ok), None, 128, 0, 0, 1, None, 128, 0, None, 0, None) == 0  # T == 0
+    ws2 = C.c_size_t(0)
+    assert L.blast_sparse_mlp2_workspace(C.byref(g), C.byref(d_ok), 16, C.byref(ws2)) == 0
+    assert ws2.value == ws.value
     # pack: null outputs / bad ld are rejected up front
     nnz = C.c_int64(0)
     assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, None, 0, None) == -1

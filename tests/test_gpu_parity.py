@@ -419,3 +419,133 @@ def test_mlp_repeatable(api):
         torch.cuda.synchronize()
         check_close(y2.cpu().numpy(), y1.cpu().numpy().astype(np.float64), "repeat")
     assert wl.b == 64
+
+
+# ------------------------------------------------------------------ two-matrix MLP  Y = W2 act(W1 X)
+def _mlp2_case(api, seed, E, I, b, sparsity, T, act="gelu", layout="token_major", out_dtype="f32", scale=0.05):
+    import torch
+
+    rng = np.random.default_rng(seed)
+    w1, w2 = (synth.gauss_bf16(rng, s, scale) for s in ((I, E), (E, I)))
+    m1 = synth.uniform_mask(rng, I // b, E // b, sparsity)
+    m2 = synth.uniform_mask(rng, E // b, I // b, sparsity)
+    if I // b > 2:
+        m1[1, :] = 0  # empty W1 block row -> zero H rows (act(0) = 0)
+        m2[:, 2] = 0  # H rows nobody consumes
+    if E // b > 1:
+        m2[1, :] = 0  # empty W2 block row -> zero Y rows
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    d1, r1 = pack_both(api, w1, b, mask=m1)
+    d2, r2 = pack_both(api, w2, b, mask=m2)
+    y_or = orc.mlp2(r1, r2, x, activation=act)
+    tdt = torch.float32 if out_dtype == "f32" else torch.bfloat16
+    if layout == "token_major":
+        out = torch.full((T, E), float("nan"), device="cuda:0", dtype=tdt)
+        y = api.sparse_mlp2(d1, d2, to_dev(x), act=act, out=out).float().cpu().numpy().T
+    else:
+        y = api.sparse_mlp2(d1, d2, to_dev(np.ascontiguousarray(x.T)), act=act, layout=api.FEATURE_MAJOR,
+                            out_dtype=tdt).float().cpu().numpy()
+    torch.cuda.synchronize()
+    what = f"mlp2 E={E} I={I} b={b} T={T} {act} {layout} {out_dtype}"
+    if out_dtype == "f32":
+        check_close(y, y_or, what)
+    else:
+        # one more rounding of Y to bf16: half an ulp (2^-9 relative) per element
+        assert np.isfinite(y).all(), what
+        assert np.all(np.abs(y - y_or) <= 2.0 ** -8 * np.abs(y_or) + 1e-2 * np.sqrt((y_or ** 2).mean())), what
+        assert np.linalg.norm(y - y_or) <= 4e-3 * np.linalg.norm(y_or), what
+    if E // b > 1:
+        assert not y[b:2 * b].any()
+
+
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 130, 300])
+def test_mlp2_small(api, b, T):
+    _mlp2_case(api, 8000 + b + T, 4 * b, 6 * b, b, 0.5, T)
+
+
+@pytest.mark.parametrize("act", ["silu", "gelu", "relu"])
+@pytest.mark.parametrize("T", [7, 37, 280])
+def test_mlp2_activations_and_layouts(api, act, T):
+    # weights scaled so that pre-activations spread over [-3, 3]: both tails of each function are exercised
+    _mlp2_case(api, 8100 + T, 256, 512, 64, 0.6, T, act=act, scale=0.12)
+    _mlp2_case(api, 8101 + T, 256, 512, 64, 0.6, T, act=act, layout="feature_major", scale=0.12)
+    _mlp2_case(api, 8102 + T, 256, 512, 32, 0.6, T, act=act, out_dtype="bf16", scale=0.12)
+
+
+def test_mlp2_dense_and_all_pruned(api):
+    _mlp2_case(api, 8200, 128, 256, 64, 0.0, 20)
+    _mlp2_case(api, 8201, 128, 256, 64, 1.0, 20)
+    _mlp2_case(api, 8202, 256, 512, 128, 0.0, 300)
+
+
+@pytest.mark.parametrize("b,T", [(64, 1), (64, 16), (64, 29), (128, 3), (128, 16)])
+def test_mlp2_one_launch_reuses_workspace(api, b, T):
+    """Single-launch form of the two-matrix MLP: repeated calls on one workspace, and interleaved with the
+    three-matrix form on the same workspace, each see their own H."""
+    import torch
+
+    rng = np.random.default_rng(8300 + b + T)
+    E, I = 4 * b, 6 * b
+    w1, wu, w2 = (synth.gauss_bf16(rng, s, 0.08) for s in ((I, E), (I, E), (E, I)))
+    m1, mu, m2 = (synth.uniform_mask(rng, r // b, c // b, 0.5) for r, c in ((I, E), (I, E), (E, I)))
+    d1, r1 = pack_both(api, w1, b, mask=m1)
+    du, ru = pack_both(api, wu, b, mask=mu)
+    d2, r2 = pack_both(api, w2, b, mask=m2)
+    assert api.mlp2_workspace_bytes(d1, d2, T) == api.mlp_workspace_bytes(d1, du, d2, T)
+    ws = torch.full((max(api.mlp2_workspace_bytes(d1, d2, T), 256),), 0x5A, dtype=torch.uint8, device="cuda:0")
+    for rep in range(4):
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        y = api.sparse_mlp2(d1, d2, to_dev(x), ws=ws, out=torch.full((T, E), float("nan"), device="cuda:0"))
+        y3 = api.sparse_mlp(d1, du, d2, to_dev(x), ws=ws, out=torch.full((T, E), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, orc.mlp2(r1, r2, x), f"mlp2 one launch b={b} T={T} call {rep}")
+        check_close(y3.cpu().numpy().T, orc.mlp(r1, ru, r2, x), f"mlp after mlp2 b={b} T={T} call {rep}")
+
+
+@pytest.mark.parametrize("T", [8, 300])
+def test_mlp2_under_graph_capture(api, T):
+    import torch
+
+    rng = np.random.default_rng(8400 + T)
+    b, E, I = 64, 256, 384
+    w1, w2 = (synth.gauss_bf16(rng, s, 0.08) for s in ((I, E), (E, I)))
+    m1, m2 = (synth.uniform_mask(rng, r // b, c // b, 0.5) for r, c in ((I, E), (E, I)))
+    d1, r1 = pack_both(api, w1, b, mask=m1)
+    d2, r2 = pack_both(api, w2, b, mask=m2)
+    ws = torch.empty(max(api.mlp2_workspace_bytes(d1, d2, T), 256), dtype=torch.uint8, device="cuda:0")
+    xs = to_dev(synth.gauss_bf16(rng, (T, E), 1.0))
+    y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        api.sparse_mlp2(d1, d2, xs, out=y, ws=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        api.sparse_mlp2(d1, d2, xs, out=y, ws=ws)
+    for rep in range(3):
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        xs.copy_(to_dev(x))
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, orc.mlp2(r1, r2, x), f"mlp2 graph replay {rep} T={T}")
+
+
+def test_mlp2_topk_packed_gpt2_shape(api):
+    """E = 768, I = 3072 (a GPT-2-small MLP block, Sec. 5.2), packed on the device by block norm at 90 %."""
+    import torch
+
+    rng = np.random.default_rng(8500)
+    E, I, b = 768, 3072, 64
+    w1, w2 = (synth.gauss_bf16(rng, s, 0.04) for s in ((I, E), (E, I)))
+    d1, r1 = pack_both(api, w1, b, sparsity=0.9)
+    d2, r2 = pack_both(api, w2, b, sparsity=0.9)
+    for T in (4, 100, 513):
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        y = api.sparse_mlp2(d1, d2, to_dev(x))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, orc.mlp2(r1, r2, x), f"mlp2 gpt2 shape T={T}")
