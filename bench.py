@@ -171,6 +171,67 @@ def decode_sweep(workload: str, tokens, steps: int, warmup: int):
             "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
 
 
+def two_matrix_mlp(workload: str, steps: int, warmup: int, cpu: bool):
+    """Y = W2 act(W1 X) (GELU) on a GPT-2-shaped block: wall-clock time per pass at the workload's token
+    counts, plus the oracle's time and the parity of the timed configuration on a token sample."""
+    import numpy as np
+    import torch
+
+    from paper_2507_03117_amd import api, synth
+    from tests.helpers import mask_dev, to_dev
+
+    wl = synth.WORKLOADS[workload]
+    l1, l2 = synth.make_mlp2(wl)
+    b = wl.b
+    p1 = api.bsr_pack(to_dev(l1.W), b, mask=mask_dev(l1.mask))
+    p2 = api.bsr_pack(to_dev(l2.W), b, mask=mask_dev(l2.mask))
+    nnz = p1.nnz + p2.nnz
+    w_bytes = nnz * b * b * 2
+    n_copies = max(2, -(-768 * 1024 * 1024 // w_bytes))
+    sets = list(zip(rotated_copies(p1, n_copies), rotated_copies(p2, n_copies)))
+    n = len(sets)
+    passes = []
+    for T in wl.tokens:
+        x = to_dev(synth.make_x(wl, T))
+        ws = torch.empty(max(api.mlp2_workspace_bytes(p1, p2, T), 256), dtype=torch.uint8, device="cuda:0")
+        y = torch.empty((T, wl.hidden), dtype=torch.float32, device="cuda:0")
+        for i in range(warmup):
+            api.sparse_mlp2(*sets[i % n], x, act="gelu", out=y, ws=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            api.sparse_mlp2(*sets[(warmup + i) % n], x, act="gelu", out=y, ws=ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        flops = 2.0 * b * b * T * nnz
+        alg_bytes = w_bytes + 4 * nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
+        passes.append({"T": T, "ms_per_step": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12,
+                       "frac_mfma": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                       "GBps": alg_bytes / (ms * 1e-3) / 1e9, "frac_hbm": alg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+    out = {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
+           "mask": wl.mask_kind, "activation": "gelu", "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies,
+           "passes": passes}
+    if cpu:
+        from oracle import oracle as orc
+
+        T = max(wl.tokens)
+        Ts = min(1024, T)
+        r1, r2 = orc.pack(l1.W, b, l1.mask), orc.pack(l2.W, b, l2.mask)
+        xs = synth.make_x(wl, T)
+        t0 = time.perf_counter()
+        y_or = orc.mlp2(r1, r2, np.ascontiguousarray(xs[:Ts]), activation="gelu")
+        sec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * b * b * Ts * nnz / sec / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(),
+                               "kind": "oracle", "seconds": sec,
+                               "sample": "first %d of %d tokens, all rows; dense masked fp64 triple loop" % (Ts, T)}
+        yd = api.sparse_mlp2(p1, p2, to_dev(xs), act="gelu")
+        torch.cuda.synchronize()
+        yh = yd[:Ts].cpu().numpy().astype(np.float64).T
+        out["parity_on_sample"] = {"rel_fro": float(np.linalg.norm(yh - y_or) / np.linalg.norm(y_or)),
+                                   "max_abs_over_rms": float(np.abs(yh - y_or).max() / np.sqrt((y_or ** 2).mean()))}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,6 +244,7 @@ def main():
     ap.add_argument("--no-large-decode", action="store_true",
                     help="skip the decode passes of the 405B-class layer (the case where weight bytes, not launch "
                          "latency, set the time)")
+    ap.add_argument("--no-mlp2", action="store_true", help="skip the two-matrix MLP (GPT-2-shaped) passes")
     ap.add_argument("--decode-tokens", default="", help="comma-separated decode token counts (default: the workload's)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--copies", type=int, default=0,
@@ -321,6 +383,10 @@ def main():
         del sets
         torch.cuda.empty_cache()
         out["decode_hbm_bound"] = decode_sweep("llama405b_b128_s95_zipf", (1, 16), 30, 5)
+
+    if not args.no_mlp2 and args.workload == "llama1b_b64_s90":
+        torch.cuda.empty_cache()
+        out["two_matrix_mlp"] = two_matrix_mlp("gpt2xl_b64_s80", args.steps, args.warmup, not args.no_cpu_baseline)
 
     print(json.dumps(out))
 

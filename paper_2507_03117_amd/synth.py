@@ -134,7 +134,7 @@ class Workload:
 
     name: str
     config_id: int
-    kind: str  # "linear" | "mlp"
+    kind: str  # "linear" | "mlp" (gate/up/down) | "mlp2" (two matrices)
     hidden: int  # E (for "linear": cols K)
     inter: int  # I (for "linear": rows M)
     b: int
@@ -153,6 +153,9 @@ WORKLOADS: Dict[str, Workload] = {
     "llama3b_b64_s90": Workload("llama3b_b64_s90", 2, "mlp", 3072, 8192, 64, 0.90, "topk", (4096,)),
     "llama3b_b64_s95": Workload("llama3b_b64_s95", 2, "mlp", 3072, 8192, 64, 0.95, "topk", (4096,)),
     "llama8b_b128_s95": Workload("llama8b_b128_s95", 3, "mlp", 4096, 14336, 128, 0.95, "uniform", (1, 2, 4, 8, 16, 32)),
+    # two-matrix MLP of a GPT2-XL block (E = 1600, I = 4E), 80 % sparsity as in the paper's pretraining run;
+    # b = 64 because 1600 is not a multiple of 128
+    "gpt2xl_b64_s80": Workload("gpt2xl_b64_s80", 5, "mlp2", 1600, 6400, 64, 0.80, "uniform", (1, 16, 2048)),
     "llama405b_b128_s95_zipf": Workload("llama405b_b128_s95_zipf", 4, "mlp", 16384, 53248, 128, 0.95, "zipf", (2048,)),
 }
 
@@ -222,6 +225,17 @@ def make_mlp(wl: Workload, seed: Optional[int] = None, fill_all: Optional[bool] 
     d = _dense_or_sparse_weight(st[2], e, i, b, wl.w_std, md, fill_all)
     return MlpInputs(LinearInputs(g, mg, b, wl.sparsity), LinearInputs(u, mu, b, wl.sparsity),
                      LinearInputs(d, md, b, wl.sparsity))
+
+
+def make_mlp2(wl: Workload, seed: Optional[int] = None) -> Tuple[LinearInputs, LinearInputs]:
+    """(W1: I x E, W2: E x I) of a two-matrix MLP."""
+    st = _streams(wl, seed)
+    e, i, b = wl.hidden, wl.inter, wl.b
+    m1 = make_mask(st[4], wl, i // b, e // b)
+    m2 = make_mask(st[6], wl, e // b, i // b)
+    w1 = _dense_or_sparse_weight(st[0], i, e, b, wl.w_std, m1, True)
+    w2 = _dense_or_sparse_weight(st[2], e, i, b, wl.w_std, m2, True)
+    return LinearInputs(w1, m1, b, wl.sparsity), LinearInputs(w2, m2, b, wl.sparsity)
 
 
 def make_x(wl: Workload, tokens: int, seed: Optional[int] = None) -> np.ndarray:

@@ -134,3 +134,26 @@ def test_gated_spmm_matches_oracle_h(api):
         assert (diff <= ulp + slack).all()
         assert (diff > 0).mean() < 0.02
     _CACHE.clear()
+
+
+@pytest.mark.parametrize("T", [1, 16, 2048])
+def test_gpt2xl_two_matrix_mlp(api, T):
+    """Two-matrix MLP (Sec. 2.1 / Sec. 3.4.3) at the GPT2-XL block shape, GELU, in the configuration bench.py times."""
+    import torch
+
+    name = "gpt2xl_b64_s80"
+    if name not in _CACHE:
+        _CACHE.clear()
+        wl = synth.WORKLOADS[name]
+        _CACHE[name] = (wl, [_pack_pair(api, l, wl.b) for l in synth.make_mlp2(wl)])
+    wl, ((d1, r1), (d2, r2)) = _CACHE[name]
+    assert r1.nnz == r2.nnz == 500  # floor(0.2 * 25 * 100)
+    x = synth.make_x(wl, T)
+    y = api.sparse_mlp2(d1, d2, to_dev(x), act="gelu", out=torch.full((T, wl.hidden), float("nan"), device="cuda:0"))
+    torch.cuda.synchronize()
+    sel = np.arange(T) if T <= 64 else np.unique(np.concatenate(([0, T - 1], np.random.default_rng(T).choice(T, 62, replace=False))))
+    y_or = orc.mlp2(r1, r2, np.ascontiguousarray(x[sel]), activation="gelu")
+    y_h = y.cpu().numpy()
+    assert np.isfinite(y_h).all()
+    fro, mx = check_close(y_h[sel].T, y_or, f"{name} T={T}")
+    print(f"{name} T={T}: rel_fro={fro:.2e} max_abs/rms={mx:.2e} on {sel.size} tokens")
