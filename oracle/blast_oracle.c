@@ -277,3 +277,47 @@ void oracle_mlp2(int64_t E, int64_t I, int32_t b,
   free(G);
   free(H);
 }
+
+/* ---- backward pass on the same pruned weight (Sec. 3.2: the pruned matrix is the one used in forward and
+ * backward propagation; Sec. 3.4: the product with the sparse matrix on the other side is the symmetric
+ * kernel).  With Y = W~ X:  dX = W~^T dY  and  dW~ = dY X^T on the kept blocks (a dropped block holds no
+ * weight, so it receives no gradient). ---- */
+
+/* dX[k][t] = sum_i Wd[i][k] * dY(i,t), fp64, i ascending: the dense masked definition.  dY element (i,t)
+ * lives at dY[i*syi + t*syt].  dX is [cols][T] row-major fp64. */
+void oracle_spmm_t(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr, const int32_t* col_idx,
+                   const uint16_t* vals, const uint16_t* dY, int64_t syi, int64_t syt, int64_t T,
+                   double* dX /* [cols][T] */) {
+  uint16_t* Wd = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)(rows * cols > 0 ? rows * cols : 1));
+  oracle_unpack(rows, cols, b, row_ptr, col_idx, vals, Wd);
+#pragma omp parallel for schedule(static)
+  for (int64_t k = 0; k < cols; ++k)
+    for (int64_t t = 0; t < T; ++t) {
+      double s = 0.0;
+      for (int64_t i = 0; i < rows; ++i) s += bf16_to_f64(Wd[i * cols + k]) * bf16_to_f64(dY[i * syi + t * syt]);
+      dX[k * T + t] = s;
+    }
+  free(Wd);
+}
+
+/* Gradient of the stored blocks: for the q-th stored block, at block row r and block column c,
+ *   dvals[q][i][j] = sum_t dY(r*b + i, t) * X(c*b + j, t),  fp64, t ascending
+ * i.e. the entries of the dense dY X^T that fall on kept blocks, in storage order. */
+void oracle_sddmm(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr, const int32_t* col_idx,
+                  const uint16_t* dY, int64_t syi, int64_t syt, const uint16_t* X, int64_t sxk, int64_t sxt,
+                  int64_t T, double* dvals /* [nnz][b][b] */) {
+  (void)cols;
+  int64_t nbr = rows / b;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t r = 0; r < nbr; ++r)
+    for (int64_t q = row_ptr[r]; q < row_ptr[r + 1]; ++q) {
+      int64_t c = col_idx[q];
+      for (int32_t i = 0; i < b; ++i)
+        for (int32_t j = 0; j < b; ++j) {
+          double s = 0.0;
+          for (int64_t t = 0; t < T; ++t)
+            s += bf16_to_f64(dY[(r * b + i) * syi + t * syt]) * bf16_to_f64(X[(c * b + j) * sxk + t * sxt]);
+          dvals[(q * b + i) * b + j] = s;
+        }
+    }
+}

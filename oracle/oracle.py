@@ -44,6 +44,10 @@ def lib():
         L.oracle_act.argtypes = [i32, dbl]
         L.oracle_mlp.restype = None
         L.oracle_mlp.argtypes = [i64, i64, i32] + [vp] * 9 + [vp, i64, i64, i64, i32, vp, vp]
+        L.oracle_spmm_t.restype = None
+        L.oracle_spmm_t.argtypes = [i64, i64, i32, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.oracle_sddmm.restype = None
+        L.oracle_sddmm.argtypes = [i64, i64, i32, vp, vp, vp, i64, i64, vp, i64, i64, i64, vp]
         L.oracle_mlp2.restype = None
         L.oracle_mlp2.argtypes = [i64, i64, i32] + [vp] * 6 + [vp, i64, i64, i64, i32, vp, vp]
         _lib = L
@@ -176,3 +180,24 @@ def mlp2(w1: Bsr, w2: Bsr, X: np.ndarray, layout: str = "token_major", activatio
     lib().oracle_mlp2(E, I, b, _p(w1.row_ptr), _p(w1.col_idx), _p(w1.vals), _p(w2.row_ptr), _p(w2.col_idx),
                       _p(w2.vals), _p(X), sxk, sxt, T, ACT[activation], _p(Y), _p(H))
     return (Y, H) if return_h else Y
+
+
+def spmm_t(w: Bsr, dY: np.ndarray, layout: str = "token_major") -> np.ndarray:
+    """Backward of Y = W~ X with respect to X: dX = W~^T dY (Sec. 3.2, Sec. 3.4), fp64 [cols, T].
+    dY is [T, rows] (token_major) or [rows, T] (feature_major), bf16 bits."""
+    M, T, syi, syt = _x_strides(dY, layout)
+    assert M == w.rows
+    dX = np.zeros((w.cols, T), dtype=np.float64)
+    lib().oracle_spmm_t(w.rows, w.cols, w.b, _p(w.row_ptr), _p(w.col_idx), _p(w.vals), _p(dY), syi, syt, T, _p(dX))
+    return dX
+
+
+def sddmm(w: Bsr, dY: np.ndarray, X: np.ndarray, layout: str = "token_major") -> np.ndarray:
+    """Backward with respect to the stored blocks: the entries of dY X^T on the kept blocks (Sec. 3.2),
+    fp64 [nnz, b, b] in storage order.  Only the structure of `w` is used."""
+    M, T, syi, syt = _x_strides(dY, layout)
+    K, T2, sxk, sxt = _x_strides(X, layout)
+    assert M == w.rows and K == w.cols and T == T2
+    dv = np.zeros((w.nnz, w.b, w.b), dtype=np.float64)
+    lib().oracle_sddmm(w.rows, w.cols, w.b, _p(w.row_ptr), _p(w.col_idx), _p(dY), syi, syt, _p(X), sxk, sxt, T, _p(dv))
+    return dv

@@ -436,3 +436,117 @@ def test_mlp2_is_the_gated_mlp_with_a_constant_up_projection():
     p1, pu, p2 = orc.pack(w1, b, full(I, E)), orc.pack(synth.f32_to_bf16_bits(up), b, full(I, E)), orc.pack(w2, b, full(E, I))
     for act in ("silu", "gelu", "relu"):
         assert np.array_equal(orc.mlp2(p1, p2, xb, activation=act), orc.mlp(p1, pu, p2, xb, activation=act))
+
+
+# ---- backward pass on the pruned weight (Sec. 3.2, Sec. 3.4): dX = W~^T dY, dW~ = (dY X^T) on kept blocks ----
+
+def _int_bf16(rng, shape, lo=-4, hi=5):
+    """Small integers as bf16 bits: every product and sum below stays exact in fp64 (and in fp32)."""
+    return synth.f32_to_bf16_bits(rng.integers(lo, hi, size=shape).astype(np.float32))
+
+
+def test_spmm_t_equals_numpy_and_the_forward_product_of_the_transpose():
+    rng = np.random.default_rng(31)
+    M, K, b, T = 96, 64, 16, 9
+    W = synth.gauss_bf16(rng, (M, K), 0.3)
+    mask = synth.uniform_mask(rng, M // b, K // b, 0.5)
+    mask[2, :] = 0  # empty block row
+    mask[:, 1] = 0  # empty block column -> zero rows of dX
+    p = orc.pack(W, b, mask)
+    dY = synth.gauss_bf16(rng, (T, M), 1.0)
+    dX = orc.spmm_t(p, dY)
+    ref = (f64(W) * expand(mask, b)).T @ f64(dY).T
+    np.testing.assert_allclose(dX, ref, rtol=1e-12, atol=1e-14)
+    assert not dX[b:2 * b].any()
+    # feature-major dY, same numbers
+    assert np.array_equal(dX, orc.spmm_t(p, np.ascontiguousarray(dY.T), layout="feature_major"))
+    # the forward product of the packed transpose (summation order is the same: ascending row of W)
+    pt = orc.pack(np.ascontiguousarray(W.T), b, np.ascontiguousarray(mask.T))
+    assert np.array_equal(dX, orc.spmm(pt, dY))
+
+
+def test_spmm_t_is_the_adjoint_of_spmm_exactly():
+    # <dY, W X> == <W^T dY, X> for any dY, X; with small-integer data both sides are exact integers
+    rng = np.random.default_rng(32)
+    M, K, b, T = 64, 96, 32, 5
+    W = _int_bf16(rng, (M, K))
+    mask = synth.uniform_mask(rng, M // b, K // b, 0.4)
+    p = orc.pack(W, b, mask)
+    X, dY = _int_bf16(rng, (T, K)), _int_bf16(rng, (T, M))
+    lhs = float((f64(dY).T * orc.spmm(p, X)).sum())
+    rhs = float((orc.spmm_t(p, dY) * f64(X).T).sum())
+    assert lhs == rhs and lhs == round(lhs)
+
+
+def test_sddmm_equals_numpy_on_kept_blocks():
+    rng = np.random.default_rng(33)
+    M, K, b, T = 64, 96, 16, 11
+    W = synth.gauss_bf16(rng, (M, K), 0.3)
+    mask = synth.uniform_mask(rng, M // b, K // b, 0.6)
+    mask[1, :] = 0
+    p = orc.pack(W, b, mask)
+    X, dY = synth.gauss_bf16(rng, (T, K), 1.0), synth.gauss_bf16(rng, (T, M), 1.0)
+    dv = orc.sddmm(p, dY, X)
+    full = f64(dY).T @ f64(X)  # [M, K] = dY X^T in the (feature, token) convention
+    assert dv.shape == (p.nnz, b, b)
+    q = 0
+    for r in range(M // b):
+        for c in range(K // b):
+            if mask[r, c]:
+                assert p.col_idx[q] == c and p.row_ptr[r] <= q < p.row_ptr[r + 1]
+                np.testing.assert_allclose(dv[q], full[r * b:(r + 1) * b, c * b:(c + 1) * b], rtol=1e-12, atol=1e-14)
+                q += 1
+    assert q == p.nnz
+    dv2 = orc.sddmm(p, np.ascontiguousarray(dY.T), np.ascontiguousarray(X.T), layout="feature_major")
+    assert np.array_equal(dv, dv2)
+
+
+def test_sddmm_is_the_exact_derivative_of_the_linear_loss():
+    # L(W~) = <dY, W~ X> is linear in every stored weight: bumping one stored entry by 1 changes L by exactly
+    # its gradient entry.  Integer data keeps everything exact.  Also: a rank-one case with a closed form.
+    rng = np.random.default_rng(34)
+    M, K, b, T = 32, 48, 16, 4
+    W = _int_bf16(rng, (M, K))
+    mask = synth.uniform_mask(rng, M // b, K // b, 0.5)
+    p = orc.pack(W, b, mask)
+    X, dY = _int_bf16(rng, (T, K)), _int_bf16(rng, (T, M))
+    dv = orc.sddmm(p, dY, X)
+    L0 = float((f64(dY).T * orc.spmm(p, X)).sum())
+    rr, cc = np.nonzero(mask)
+    for q, i, j in [(0, 0, 0), (p.nnz - 1, b - 1, b - 1), (p.nnz // 2, 3, 7), (1, 15, 2)]:
+        Wf = f64(W).copy()
+        Wf[rr[q] * b + i, cc[q] * b + j] += 1.0
+        p1 = orc.pack(synth.f32_to_bf16_bits(Wf.astype(np.float32)), b, mask)
+        L1 = float((f64(dY).T * orc.spmm(p1, X)).sum())
+        assert L1 - L0 == dv[q, i, j], (q, i, j)
+    # one token: dW = dy x^T (outer product) on kept blocks
+    x1, dy1 = _int_bf16(rng, (1, K)), _int_bf16(rng, (1, M))
+    dv1 = orc.sddmm(p, dy1, x1)
+    outer = np.outer(f64(dy1)[0], f64(x1)[0])
+    for q in range(p.nnz):
+        assert np.array_equal(dv1[q], outer[rr[q] * b:(rr[q] + 1) * b, cc[q] * b:(cc[q] + 1) * b])
+
+
+@pytest.mark.parametrize("M,K,b,T,seed", [(8, 8, 4, 3, 1), (8, 12, 4, 2, 2)])
+def test_backward_brute_force_exact(M, K, b, T, seed):
+    # exact rational arithmetic, plain Python loops, tiny sizes
+    rng = np.random.default_rng(40 + seed)
+    W = synth.gauss_bf16(rng, (M, K), 1.0)
+    mask = synth.uniform_mask(rng, M // b, K // b, 0.5)
+    p = orc.pack(W, b, mask)
+    X, dY = synth.gauss_bf16(rng, (T, K), 1.0), synth.gauss_bf16(rng, (T, M), 1.0)
+    Wi = [[Fraction(float(v)) for v in row] for row in f64(W)]
+    Xi = [[Fraction(float(v)) for v in row] for row in f64(X)]
+    Yi = [[Fraction(float(v)) for v in row] for row in f64(dY)]
+    dX = orc.spmm_t(p, dY)
+    for k in range(K):
+        for t in range(T):
+            s = sum((Wi[i][k] * Yi[t][i] for i in range(M) if mask[i // b, k // b]), Fraction(0))
+            assert abs(Fraction(float(dX[k, t])) - s) <= abs(s) * Fraction(1, 2 ** 45) + Fraction(1, 2 ** 60)
+    dv = orc.sddmm(p, dY, X)
+    rr, cc = np.nonzero(mask)
+    for q in range(p.nnz):
+        for i in range(b):
+            for j in range(b):
+                s = sum((Yi[t][rr[q] * b + i] * Xi[t][cc[q] * b + j] for t in range(T)), Fraction(0))
+                assert abs(Fraction(float(dv[q, i, j])) - s) <= abs(s) * Fraction(1, 2 ** 45) + Fraction(1, 2 ** 60)
