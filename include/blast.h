@@ -139,6 +139,49 @@ int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, i
                    int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Packed transpose.  Sec. 3.2: the pruned matrix is the one used in forward AND backward propagation;
+ * Sec. 3.4 / 3.4.1: which compressed format suits depends on the side the sparse matrix is multiplied
+ * from, and the kernel for the other side is the symmetric one.  This call builds, from a packed W~
+ * (rows x cols), the packed W~^T (cols x rows): the same stored blocks grouped by block column, every
+ * block turned.  The backward product with respect to the activations,
+ *     dX = W~^T dY,
+ * is then blast_bsr_spmm on the result (dY in the place of X, [T][rows] token-major or [rows][T]).
+ *
+ *   W                 a packed matrix WITH its aux buffer (the column-grouped index is read from it).
+ *   row_ptr_t         out, [cols/b + 1]
+ *   col_idx_t         out, [W->nnz]   block-row indices of W, ascending inside each block column
+ *   vals_t            out, [W->nnz * b * b], 16-byte aligned; block e = transpose of the e-th block of W in
+ *                     column-grouped order
+ *   row_order_t       out, [cols/b]   schedule of the transpose (block columns of W by population)
+ *   aux_t             out, may be NULL; at least blast_bsr_aux_bytes(cols, rows, b, W->nnz) bytes
+ *   max_row_blocks_t_out  HOST, may be NULL: stored blocks of the fullest block column of W (0 without
+ *                     aux_t); goes into the view's max_row_blocks.  Asking for it makes the call wait for
+ *                     `stream` (one small copy); otherwise the call never synchronises.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE (W->aux missing, aux_t too small), HIP.
+ */
+int blast_bsr_transpose(const blast_bsr_view* W, int32_t* row_ptr_t, int32_t* col_idx_t, uint16_t* vals_t,
+                        int32_t* row_order_t, void* aux_t, size_t aux_t_bytes, int32_t* max_row_blocks_t_out /* HOST */,
+                        void* stream);
+
+/*
+ * Gradient of the stored blocks (Sec. 3.2: the backward pass uses the same sparsity pattern; a dropped
+ * block holds no weight and receives no gradient).  With Y = W~ X:
+ *     dvals[q][i][j] = sum_t dY(r*b + i, t) * X(c*b + j, t)      for the q-th stored block, at (r, c),
+ * the entries of dY X^T that fall on kept blocks, in the storage order of W->vals.  bf16 operands, fp32
+ * accumulation, fp32 result.  Only the structure of W is read (row_ptr, col_idx, nnz), not its values.
+ *
+ *   dY, X, layout     BLAST_TOKEN_MAJOR: dY is [T][rows] with row pitch ldy, X is [T][cols] with pitch ldx
+ *                     (the tuned path needs b >= 32, both 16-byte aligned with pitches that are multiples
+ *                     of 8); BLAST_FEATURE_MAJOR: [rows][T] / [cols][T].  Other cases take a plain kernel.
+ *   dvals             out, fp32 [W->nnz][b][b], 16-byte aligned; overwritten.  T = 0 gives zeros.
+ * When the matrix has few blocks the tokens are cut into chunks whose partial sums meet through fp32
+ * atomic additions: the result is then reproducible only up to the rounding of the summation order.
+ * Never synchronises, allocates nothing.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, HIP.
+ */
+int blast_bsr_sddmm(const blast_bsr_view* W, const uint16_t* dY, int64_t ldy, const uint16_t* X, int64_t ldx,
+                    int32_t layout, int64_t T, float* dvals, void* stream);
+
+/*
  * Schedule for two matrices that are multiplied together row by row (W_gate and W_up of Eq. (1)):
  * row_order[rank] = block rows sorted by the SUM of their stored-block counts, descending, stable.
  * Passing it as Wgate->row_order lets the gated product balance its workgroups on the work they really

@@ -24,7 +24,7 @@ ACT = {"silu": 0, "gelu": 1, "relu": 2}
 EXPORTS = (
     "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
-    "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
+    "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
 
@@ -79,6 +79,10 @@ def lib():
         L.blast_sparse_mlp2.argtypes = [pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
         L.blast_sparse_mlp2_workspace.restype = C.c_int
         L.blast_sparse_mlp2_workspace.argtypes = [pv, pv, i64, C.POINTER(sz)]
+        L.blast_bsr_transpose.restype = C.c_int
+        L.blast_bsr_transpose.argtypes = [pv, vp, vp, vp, vp, vp, sz, C.POINTER(C.c_int32), vp]
+        L.blast_bsr_sddmm.restype = C.c_int
+        L.blast_bsr_sddmm.argtypes = [pv, vp, i64, vp, i64, i32, i64, vp, vp]
         L.blast_sparse_mlp_events.restype = C.c_int
         L.blast_sparse_mlp_events.argtypes = L.blast_sparse_mlp.argtypes + [C.POINTER(vp)]
         L.blast_bsr_joint_row_order.restype = C.c_int
@@ -180,6 +184,39 @@ def with_joint_row_order(gate: PackedBsr, up: PackedBsr) -> PackedBsr:
     _check(lib().blast_bsr_joint_row_order(C.byref(vg), C.byref(vu), _ptr(order), _stream()),
            "blast_bsr_joint_row_order")
     return dataclasses.replace(gate, row_order=order)
+
+
+def bsr_transpose(W: PackedBsr) -> PackedBsr:
+    """blast_bsr_transpose: the packed W~^T; bsr_spmm on it computes dX = W~^T dY."""
+    L = lib()
+    assert W.aux is not None, "pack with with_aux=True: the transpose reads the column-grouped index"
+    b, dev = W.b, W.row_ptr.device
+    n = max(W.nnz, 1)
+    row_ptr = torch.empty(W.cols // b + 1, dtype=torch.int32, device=dev)
+    col_idx = torch.empty(n, dtype=torch.int32, device=dev)
+    vals = torch.empty(n * b * b, dtype=torch.int16, device=dev)
+    row_order = torch.empty(max(W.cols // b, 1), dtype=torch.int32, device=dev)
+    aux_bytes = int(L.blast_bsr_aux_bytes(W.cols, W.rows, b, W.nnz))
+    aux = torch.empty(max(aux_bytes, 16), dtype=torch.uint8, device=dev)
+    heavy = C.c_int32(0)
+    v = W.view()
+    _check(L.blast_bsr_transpose(C.byref(v), _ptr(row_ptr), _ptr(col_idx), _ptr(vals), _ptr(row_order), _ptr(aux),
+                                 aux_bytes, C.byref(heavy), _stream()), "blast_bsr_transpose")
+    return PackedBsr(W.cols, W.rows, b, W.nnz, row_ptr, col_idx, vals, row_order, aux, int(heavy.value))
+
+
+def bsr_sddmm(W: PackedBsr, dY: torch.Tensor, X: torch.Tensor, *, layout: int = TOKEN_MAJOR,
+              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_bsr_sddmm: gradient of the stored blocks, fp32 [nnz, b, b] (entries of dY X^T on kept blocks)."""
+    L = lib()
+    T, M, ldy = _layout_dims(dY, layout)
+    T2, K, ldx = _layout_dims(X, layout)
+    assert M == W.rows and K == W.cols and T == T2
+    dv = out if out is not None else torch.empty((W.nnz, W.b, W.b), dtype=torch.float32, device=X.device)
+    assert dv.dtype == torch.float32 and dv.is_contiguous() and dv.numel() == W.nnz * W.b * W.b
+    v = W.view()
+    _check(L.blast_bsr_sddmm(C.byref(v), _ptr(dY), ldy, _ptr(X), ldx, layout, T, _ptr(dv), _stream()), "blast_bsr_sddmm")
+    return dv
 
 
 def _layout_dims(X: torch.Tensor, layout: int):

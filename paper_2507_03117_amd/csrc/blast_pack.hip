@@ -312,6 +312,33 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
   }
 }
 
+// One workgroup per stored block of the transposed matrix: block e of the output is the transpose of
+// block src_blk[e] of the input.  Rows are read and written whole; the turn happens in LDS (row pitch
+// b + 2 elements, so that a column walk does not stay on one bank).
+__global__ __launch_bounds__(256) void k_transpose_blocks(const uint16_t* __restrict__ vals, int b,
+                                                          const int* __restrict__ src_blk,
+                                                          uint16_t* __restrict__ vals_t) {
+  extern __shared__ uint16_t tile[];
+  const int pitch = b + 2;
+  const uint16_t* src = vals + (int64_t)src_blk[blockIdx.x] * b * b;
+  uint16_t* dst = vals_t + (int64_t)blockIdx.x * b * b;
+  for (int idx = threadIdx.x; idx < b * b; idx += blockDim.x) tile[(idx / b) * pitch + idx % b] = src[idx];
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < b * b; idx += blockDim.x) dst[idx] = tile[(idx % b) * pitch + idx / b];
+}
+
+// out[i] = in[i]
+__global__ __launch_bounds__(256) void k_copy_i32(const int* __restrict__ in, int64_t n, int* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = in[i];
+}
+
+// inv[perm[e]] = e
+__global__ __launch_bounds__(256) void k_invert_perm(const int* __restrict__ perm, int64_t n, int* __restrict__ inv) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < n) inv[perm[e]] = (int)e;
+}
+
 struct PackWs {
   size_t scores_off, mask_off, rcnt_off, ccnt_off, blk_row_off, scalars_off, bytes;
 };
@@ -511,5 +538,69 @@ extern "C" int blast_bsr_joint_row_order(const blast_bsr_view* A, const blast_bs
   k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(A->row_ptr, Bm->row_ptr, (int)nbr,
                                                                               row_order);
   BLAST_LAUNCH_CHECK("k_row_order(joint)");
+  return BLAST_OK;
+}
+
+extern "C" int blast_bsr_transpose(const blast_bsr_view* W, int32_t* row_ptr_t, int32_t* col_idx_t, uint16_t* vals_t,
+                                   int32_t* row_order_t, void* aux_t, size_t aux_t_bytes,
+                                   int32_t* max_row_blocks_t_out, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!W || !W->row_ptr || W->nnz < 0 || W->nnz > INT32_MAX) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_shape(W->rows, W->cols, W->b)) return rc;
+  const int64_t nbr = W->rows / W->b, nbc = W->cols / W->b, nnz = W->nnz;
+  const int b = W->b;
+  if (!W->aux) return BLAST_ERR_WORKSPACE;  // the column-grouped index of the packer is the input here
+  if (!row_ptr_t || (nbc > 0 && !row_order_t)) return BLAST_ERR_INVALID_ARG;
+  if (nnz > 0 && (!W->col_idx || !W->vals || !col_idx_t || !vals_t || !blast::aligned(vals_t, 16) ||
+                  !blast::aligned(W->vals, 16)))
+    return BLAST_ERR_INVALID_ARG;
+  const blast::AuxLayout A = blast::aux_layout(nbr, nbc, nnz);   // of the input
+  const blast::AuxLayout At = blast::aux_layout(nbc, nbr, nnz);  // of the output
+  if (aux_t && (aux_t_bytes < At.bytes || !blast::aligned(aux_t, 16))) return BLAST_ERR_WORKSPACE;
+  const char* ab = static_cast<const char*>(W->aux);
+  const int* col_ptr = reinterpret_cast<const int*>(ab + A.col_ptr_off);
+  const int* csc_row = reinterpret_cast<const int*>(ab + A.csc_row_off);
+  const int* csc_blk = reinterpret_cast<const int*>(ab + A.csc_blk_off);
+  auto blocks_for = [](int64_t n) { return dim3((unsigned)((n + 255) / 256)); };
+
+  // BSR of the transpose = the column-grouped (BCSC) view of the input, with every block turned
+  k_copy_i32<<<blocks_for(nbc + 1), dim3(256), 0, stream>>>(col_ptr, nbc + 1, row_ptr_t);
+  BLAST_LAUNCH_CHECK("k_copy_i32(row_ptr_t)");
+  if (nnz > 0) {
+    k_copy_i32<<<blocks_for(nnz), dim3(256), 0, stream>>>(csc_row, nnz, col_idx_t);
+    BLAST_LAUNCH_CHECK("k_copy_i32(col_idx_t)");
+    k_transpose_blocks<<<dim3((unsigned)nnz), dim3(256), (size_t)b * (b + 2) * 2, stream>>>(W->vals, b, csc_blk, vals_t);
+    BLAST_LAUNCH_CHECK("k_transpose_blocks");
+  }
+  if (nbc > 0) {
+    k_row_order<<<blocks_for(nbc), dim3(256), 0, stream>>>(row_ptr_t, nullptr, (int)nbc, row_order_t);
+    BLAST_LAUNCH_CHECK("k_row_order(transpose)");
+  }
+  int heavy = 0;
+  if (aux_t) {
+    char* at = static_cast<char*>(aux_t);
+    int* hdr = reinterpret_cast<int*>(at + At.hdr_off);
+    k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr_t, row_order_t, (int)nbc, blast::kChunkBlocks, hdr,
+                                                     reinterpret_cast<int*>(at + At.chunk_row_off),
+                                                     reinterpret_cast<int*>(at + At.chunk_kb_off),
+                                                     reinterpret_cast<int*>(at + At.chunk_ke_off), At.chunk_cap,
+                                                     hdr + 1);
+    BLAST_LAUNCH_CHECK("k_chunk_plan(transpose)");
+    // the column-grouped index of the transpose is the row-grouped one of the input
+    k_copy_i32<<<blocks_for(nbr + 1), dim3(256), 0, stream>>>(W->row_ptr, nbr + 1,
+                                                              reinterpret_cast<int*>(at + At.col_ptr_off));
+    BLAST_LAUNCH_CHECK("k_copy_i32(col_ptr_t)");
+    if (nnz > 0) {
+      k_copy_i32<<<blocks_for(nnz), dim3(256), 0, stream>>>(W->col_idx, nnz, reinterpret_cast<int*>(at + At.csc_row_off));
+      BLAST_LAUNCH_CHECK("k_copy_i32(csc_row_t)");
+      k_invert_perm<<<blocks_for(nnz), dim3(256), 0, stream>>>(csc_blk, nnz, reinterpret_cast<int*>(at + At.csc_blk_off));
+      BLAST_LAUNCH_CHECK("k_invert_perm");
+    }
+    if (max_row_blocks_t_out) {
+      BLAST_HIP_TRY(hipMemcpyAsync(&heavy, hdr + 1, sizeof(int), hipMemcpyDeviceToHost, stream));
+      BLAST_HIP_TRY(hipStreamSynchronize(stream));
+    }
+  }
+  if (max_row_blocks_t_out) *max_row_blocks_t_out = heavy;
   return BLAST_OK;
 }

@@ -94,6 +94,16 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     ws2 = C.c_size_t(0)
     assert L.blast_sparse_mlp2_workspace(C.byref(g), C.byref(d_ok), 16, C.byref(ws2)) == 0
     assert ws2.value == ws.value
+    # backward entry points
+    assert L.blast_bsr_transpose(None, None, None, None, None, None, 0, None, None) == -1
+    assert L.blast_bsr_transpose(C.byref(g), None, None, None, None, None, 0, None, None) == -5  # no aux on the input
+    assert L.blast_bsr_sddmm(None, None, 128, None, 128, 0, 4, None, None) == -1
+    assert L.blast_bsr_sddmm(C.byref(g), None, 128, None, 128, 0, 4, None, None) == 0  # nnz == 0: nothing to do
+    g1 = api.BsrView(256, 128, 64, 0, 1, v.row_ptr, v.row_ptr, None, None, None)
+    assert L.blast_bsr_sddmm(C.byref(g1), None, 256, None, 128, 0, 4, None, None) == -1  # dvals null
+    assert L.blast_bsr_sddmm(C.byref(g1), None, 256, None, 128, 7, 4, None, None) == -1  # layout enum
+    bad48 = api.BsrView(96, 96, 48, 0, 1, v.row_ptr, v.row_ptr, None, None, None)
+    assert L.blast_bsr_sddmm(C.byref(bad48), None, 96, None, 96, 0, 4, None, None) == -3
     # pack: null outputs / bad ld are rejected up front
     nnz = C.c_int64(0)
     assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, None, 0, None) == -1
