@@ -115,14 +115,21 @@ def time_mlp(api, torch, sets, x, T, steps, warmup, ws):
     marked = list(range(0, steps, EVENT_EVERY))
     ev = Events(len(marked))
     n = len(sets)
+    # arguments marshalled once per (weight set, event triple): the timed loop is one foreign call per step
+    plain = [api.prepare_sparse_mlp(g, u, d, x, y, ws) for g, u, d in sets]
+    calls = []
+    for i in range(steps):
+        if i % EVENT_EVERY == 0:
+            g, u, d = sets[(warmup + i) % n]
+            calls.append(api.prepare_sparse_mlp(g, u, d, x, y, ws, events=ev.triples[i // EVENT_EVERY]))
+        else:
+            calls.append(plain[(warmup + i) % n])
     for i in range(warmup):
-        g, u, d = sets[i % n]
-        api.sparse_mlp(g, u, d, x, out=y, ws=ws)
+        plain[i % n]()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
-        g, u, d = sets[(warmup + i) % n]
-        api.sparse_mlp(g, u, d, x, out=y, ws=ws, events=ev.triples[i // EVENT_EVERY] if i % EVENT_EVERY == 0 else None)
+    for call in calls:
+        call()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     k = len(marked)
@@ -232,6 +239,86 @@ def two_matrix_mlp(workload: str, steps: int, warmup: int, cpu: bool):
     return out
 
 
+def backward_products(workload: str, T: int, steps: int, warmup: int, cpu: bool):
+    """Backward pass of one sparse projection (the gate matrix of the workload): the packed transpose (once per
+    re-packing), dX = W~^T dY and the gradient of the stored blocks, each timed between two hipEvents around
+    `steps` launches; the oracle timed beside them on a sample, which doubles as a parity check."""
+    import numpy as np
+    import torch
+
+    from paper_2507_03117_amd import api, synth
+    from tests.helpers import mask_dev, to_dev
+
+    wl = synth.WORKLOADS[workload]
+    lin = synth.make_mlp(wl).gate
+    b = wl.b
+    p = api.bsr_pack(to_dev(lin.W), b, mask=mask_dev(lin.mask)) if lin.mask is not None else \
+        api.bsr_pack(to_dev(lin.W), b, sparsity=lin.sparsity)
+    rng = np.random.default_rng(synth.BASE_SEED + 77)
+    x_h = synth.make_x(wl, T)
+    dy_h = synth.gauss_bf16(rng, (T, wl.inter), 1.0)
+    X, dY = to_dev(x_h), to_dev(dy_h)
+    pt = api.bsr_transpose(p)
+    dX = torch.empty((T, wl.hidden), dtype=torch.float32, device="cuda:0")
+    dv = torch.empty((p.nnz, b, b), dtype=torch.float32, device="cuda:0")
+
+    def timed(fn, n, w):
+        for _ in range(w):
+            fn()
+        ev = Events(1)
+        hip, stream = ev.hip, C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        torch.cuda.synchronize()
+        hip.hipEventRecord(ev.triples[0][0], stream)
+        for _ in range(n):
+            fn()
+        hip.hipEventRecord(ev.triples[0][1], stream)
+        torch.cuda.synchronize()
+        ms = ev.elapsed(ev.triples[0][0], ev.triples[0][1]) / n
+        ev.destroy()
+        return ms
+
+    flops = 2.0 * b * b * T * p.nnz
+    ms_t = timed(lambda: api.bsr_transpose(p), 5, 2)
+    ms_dx = timed(lambda: api.bsr_spmm(pt, dY, out=dX), steps, warmup)
+    ms_dw = timed(lambda: api.bsr_sddmm(p, dY, X, out=dv), steps, warmup)
+    out = {"workload": wl.name, "matrix": "gate (%d x %d)" % (wl.inter, wl.hidden), "block": b, "tokens": T,
+           "nnz_blocks": p.nnz, "transpose_ms": ms_t,
+           "dX": {"ms": ms_dx, "TFLOPs": flops / (ms_dx * 1e-3) / 1e12, "frac_mfma": flops / (ms_dx * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+           "dW": {"ms": ms_dw, "TFLOPs": flops / (ms_dw * 1e-3) / 1e12, "frac_mfma": flops / (ms_dw * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}}
+    if cpu:
+        from oracle import oracle as orc
+
+        ref = orc.pack(lin.W, b, lin.mask) if lin.mask is not None else orc.pack_topk(lin.W, b, wl.sparsity)[0]
+        sel = np.unique(np.concatenate(([0, T - 1], rng.choice(T, min(T, 62), replace=False))))
+        t0 = time.perf_counter()
+        dx_or = orc.spmm_t(ref, np.ascontiguousarray(dy_h[sel]))
+        sec_dx = time.perf_counter() - t0
+        qs = np.unique(np.concatenate(([0, ref.nnz - 1], rng.choice(ref.nnz, min(ref.nnz, 30), replace=False))))
+        rr = np.repeat(np.arange(wl.inter // b), np.diff(ref.row_ptr))
+        sub = np.zeros((wl.inter // b, wl.hidden // b), dtype=np.uint8)
+        sub[rr[qs], ref.col_idx[qs]] = 1
+        ref_sub = orc.pack(lin.W, b, sub)
+        t0 = time.perf_counter()
+        dv_or = orc.sddmm(ref_sub, dy_h, x_h)
+        sec_dw = time.perf_counter() - t0
+        api.bsr_spmm(pt, dY, out=dX)
+        api.bsr_sddmm(p, dY, X, out=dv)
+        torch.cuda.synchronize()
+        dxh = dX.cpu().numpy()[sel].astype(np.float64).T
+        dvh = dv.cpu().numpy()[qs].astype(np.float64)
+        out["cpu_baseline"] = {
+            "dX": {"value": 2.0 * b * b * sel.size * ref.nnz / sec_dx / 1e12, "unit": "TFLOP/s", "seconds": sec_dx,
+                   "sample": "%d of %d tokens, all rows; dense masked fp64 loop" % (sel.size, T)},
+            "dW": {"value": 2.0 * b * b * T * qs.size / sec_dw / 1e12, "unit": "TFLOP/s", "seconds": sec_dw,
+                   "sample": "%d of %d stored blocks, all tokens; fp64 loop" % (qs.size, ref.nnz)},
+            "cores": orc.num_threads(), "kind": "oracle"}
+        out["parity_on_sample"] = {
+            "dX_rel_fro": float(np.linalg.norm(dxh - dx_or) / np.linalg.norm(dx_or)),
+            "dW_rel_fro": float(np.linalg.norm(dvh - dv_or) / np.linalg.norm(dv_or))}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +332,7 @@ def main():
                     help="skip the decode passes of the 405B-class layer (the case where weight bytes, not launch "
                          "latency, set the time)")
     ap.add_argument("--no-mlp2", action="store_true", help="skip the two-matrix MLP (GPT-2-shaped) passes")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward-pass products of the gate matrix")
     ap.add_argument("--decode-tokens", default="", help="comma-separated decode token counts (default: the workload's)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--copies", type=int, default=0,
@@ -387,6 +475,10 @@ def main():
     if not args.no_mlp2 and args.workload == "llama1b_b64_s90":
         torch.cuda.empty_cache()
         out["two_matrix_mlp"] = two_matrix_mlp("gpt2xl_b64_s80", args.steps, args.warmup, not args.no_cpu_baseline)
+
+    if not args.no_backward and args.workload == "llama1b_b64_s90":
+        torch.cuda.empty_cache()
+        out["backward"] = backward_products(args.workload, T, args.steps, args.warmup, not args.no_cpu_baseline)
 
     print(json.dumps(out))
 

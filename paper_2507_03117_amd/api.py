@@ -277,6 +277,38 @@ def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor,
     return Y
 
 
+class PreparedCall:
+    """A C-ABI call with its arguments marshalled once: calling it costs one foreign call.  For loops that
+    repeat a launch with the same buffers (decode steps, benchmarks), where argument conversion on the host
+    would otherwise take longer than the kernels.  Holds references to every tensor it points into."""
+
+    __slots__ = ("_fn", "_args", "_where", "_keep")
+
+    def __init__(self, fn, where, args, keep):
+        self._fn, self._where, self._args, self._keep = fn, where, args, keep
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != 0:
+            raise BlastError(rc, self._where)
+
+
+def prepare_sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor, out: torch.Tensor,
+                       ws: torch.Tensor, *, layout: int = TOKEN_MAJOR, act: str = "silu", events=None) -> PreparedCall:
+    """blast_sparse_mlp (or blast_sparse_mlp_events) on the current stream with fixed buffers, as a PreparedCall."""
+    L = lib()
+    T, K, ldx = _layout_dims(X, layout)
+    assert K == gate.cols
+    vg, vu, vd = gate.view(), up.view(), down.view()
+    args = [C.byref(vg), C.byref(vu), C.byref(vd), _ptr(X), C.c_int64(ldx), C.c_int32(layout), C.c_int64(T),
+            C.c_int32(ACT[act]), _ptr(out), C.c_int64(out.stride(0)),
+            C.c_int32(BF16 if out.dtype == torch.bfloat16 else F32), _ptr(ws), C.c_size_t(ws.numel()), _stream()]
+    keep = (vg, vu, vd, gate, up, down, X, out, ws, events)
+    if events is None:
+        return PreparedCall(L.blast_sparse_mlp, "blast_sparse_mlp", tuple(args), keep)
+    return PreparedCall(L.blast_sparse_mlp_events, "blast_sparse_mlp_events", tuple(args + [events]), keep)
+
+
 def mlp2_workspace_bytes(w1: PackedBsr, w2: PackedBsr, T: int) -> int:
     v1, v2 = w1.view(), w2.view()
     wsb = C.c_size_t(0)

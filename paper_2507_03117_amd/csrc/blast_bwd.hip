@@ -32,11 +32,12 @@ int launch_sddmm(SddmmArgs a, hipStream_t stream) {
     if (dev >= 0 && dev < 64) lds_set[dev] = true;
   }
   const int64_t sub_units = (int64_t)a.nnz * C::SUB * C::SUB;
-  // Token chunks: enough wave-sized units for every SIMD of the chip to hold two, as long as a chunk
-  // keeps at least 256 tokens (below that the atomics on the output cost more than the idle units).
-  const int64_t want = (int64_t)cu_count_bwd() * 8;
+  // Token chunks across workgroups (on top of the four waves of a workgroup): only when there are fewer
+  // units than CUs, and never below 512 tokens per chunk - the atomics on the output cost more than
+  // idle workgroup slots otherwise.
+  const int64_t want = (int64_t)cu_count_bwd();
   int64_t tsplit = (want + sub_units - 1) / sub_units;
-  const int64_t max_split = (a.T + 255) / 256;
+  const int64_t max_split = (a.T + 511) / 512;
   if (tsplit > max_split) tsplit = max_split;
   if (tsplit < 1) tsplit = 1;
   int64_t chunk = ((a.T + tsplit - 1) / tsplit + C::KT - 1) / C::KT * C::KT;
@@ -51,7 +52,7 @@ int launch_sddmm(SddmmArgs a, hipStream_t stream) {
     k_zero_f32<<<dim3((unsigned)((n / 4 + 255) / 256 + 1)), dim3(256), 0, stream>>>(a.dvals, n);
     BLAST_LAUNCH_CHECK("k_zero_f32");
   }
-  k_sddmm<B><<<dim3((unsigned)((units + 3) / 4)), dim3(256), C::LDS_BYTES, stream>>>(a);
+  k_sddmm<B><<<dim3((unsigned)((units + 7) / 8 * 8)), dim3(256), C::LDS_BYTES, stream>>>(a);
   BLAST_LAUNCH_CHECK("k_sddmm");
   return BLAST_OK;
 }
