@@ -144,8 +144,8 @@ int64_t oracle_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, 
       if (col_idx) col_idx[nnz] = (int32_t)bc;
       if (vals)
         for (int32_t i = 0; i < b; ++i)
-          for (int32_t j = 0; j < b; ++j)
-            vals[(nnz * b + i) * b + j] = W[(br * b + i) * ldw + bc * b + j];
+          for (int32_t j = 0; j < b; ++j) /* mask code 2: a regrown block, stored with zero values (Sec. 3.2) */
+            vals[(nnz * b + i) * b + j] = mask[br * nbc + bc] == 2 ? 0 : W[(br * b + i) * ldw + bc * b + j];
       ++nnz;
     }
     row_ptr[br + 1] = (int32_t)nnz;
@@ -320,4 +320,38 @@ void oracle_sddmm(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr,
           dvals[(q * b + i) * b + j] = s;
         }
     }
+}
+
+/* ---- one round of the blocked prune-and-grow mask update (Sec. 3.2, the generate_masks() step) ----
+ * S(W): the blocks of W that survive pruning to sparsity s (top blocks by Frobenius norm);
+ * S(G): the same selection applied to the gradient G;
+ * D = S(G) \ S(W): blocks the gradient ranks high but the weight does not - they are regrown.
+ * mask[blk] = 1 for blocks of S(W), 2 for blocks of D (kept in the structure, values start at zero), 0 else. */
+void oracle_generate_masks(const uint16_t* W, int64_t ldw, const uint16_t* G, int64_t ldg, int64_t rows, int64_t cols,
+                           int32_t b, double sparsity, uint8_t* mask /* [rows/b][cols/b] */) {
+  int64_t n = (rows / b) * (cols / b);
+  double* sw = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+  double* sg = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+  uint8_t* mw = (uint8_t*)malloc((size_t)(n > 0 ? n : 1));
+  uint8_t* mg = (uint8_t*)malloc((size_t)(n > 0 ? n : 1));
+  oracle_block_scores(W, ldw, rows, cols, b, sw);
+  oracle_block_scores(G, ldg, rows, cols, b, sg);
+  oracle_topk_mask(sw, n, sparsity, mw, NULL);
+  oracle_topk_mask(sg, n, sparsity, mg, NULL);
+  for (int64_t i = 0; i < n; ++i) mask[i] = mw[i] ? 1 : (mg[i] ? 2 : 0);
+  free(sw);
+  free(sg);
+  free(mw);
+  free(mg);
+}
+
+/* Eq. (2): s(i) = s_max + (s_init - s_max) * (1 - i / (m - d))^3.  The paper gives no value past i = m - d,
+ * where the cube would turn negative and push s above s_max: the iteration is held at the ends of [0, m - d]. */
+double oracle_sparsity_schedule(int64_t i, int64_t m, int64_t d, double s_init, double s_max) {
+  int64_t span = m - d;
+  if (span <= 0) return s_max;
+  if (i < 0) i = 0;
+  if (i > span) i = span;
+  double f = 1.0 - (double)i / (double)span;
+  return s_max + (s_init - s_max) * f * f * f;
 }

@@ -48,6 +48,10 @@ def lib():
         L.oracle_spmm_t.argtypes = [i64, i64, i32, vp, vp, vp, vp, i64, i64, i64, vp]
         L.oracle_sddmm.restype = None
         L.oracle_sddmm.argtypes = [i64, i64, i32, vp, vp, vp, i64, i64, vp, i64, i64, i64, vp]
+        L.oracle_generate_masks.restype = None
+        L.oracle_generate_masks.argtypes = [vp, i64, vp, i64, i64, i64, i32, dbl, vp]
+        L.oracle_sparsity_schedule.restype = dbl
+        L.oracle_sparsity_schedule.argtypes = [i64, i64, i64, dbl, dbl]
         L.oracle_mlp2.restype = None
         L.oracle_mlp2.argtypes = [i64, i64, i32] + [vp] * 6 + [vp, i64, i64, i64, i32, vp, vp]
         _lib = L
@@ -201,3 +205,20 @@ def sddmm(w: Bsr, dY: np.ndarray, X: np.ndarray, layout: str = "token_major") ->
     dv = np.zeros((w.nnz, w.b, w.b), dtype=np.float64)
     lib().oracle_sddmm(w.rows, w.cols, w.b, _p(w.row_ptr), _p(w.col_idx), _p(dY), syi, syt, _p(X), sxk, sxt, T, _p(dv))
     return dv
+
+
+def generate_masks(W: np.ndarray, G: np.ndarray, b: int, sparsity: float) -> np.ndarray:
+    """One mask update of blocked prune-and-grow (Sec. 3.2): uint8 [rows/b, cols/b], 1 = kept by the weight's
+    own ranking, 2 = regrown (ranked high by the gradient only; stored as zeros), 0 = dropped."""
+    W = np.ascontiguousarray(W, dtype=np.uint16)
+    G = np.ascontiguousarray(G, dtype=np.uint16)
+    assert W.shape == G.shape
+    rows, cols = W.shape
+    mask = np.empty((rows // b, cols // b), dtype=np.uint8)
+    lib().oracle_generate_masks(_p(W), cols, _p(G), cols, rows, cols, b, float(sparsity), _p(mask))
+    return mask
+
+
+def sparsity_schedule(i: int, m: int, d: int, s_init: float, s_max: float) -> float:
+    """Eq. (2), with the iteration held inside [0, m - d]."""
+    return float(lib().oracle_sparsity_schedule(int(i), int(m), int(d), float(s_init), float(s_max)))

@@ -550,3 +550,67 @@ def test_backward_brute_force_exact(M, K, b, T, seed):
             for j in range(b):
                 s = sum((Yi[t][rr[q] * b + i] * Xi[t][cc[q] * b + j] for t in range(T)), Fraction(0))
                 assert abs(Fraction(float(dv[q, i, j])) - s) <= abs(s) * Fraction(1, 2 ** 45) + Fraction(1, 2 ** 60)
+
+
+# ---- blocked prune-and-grow mask update and the sparsity schedule (Sec. 3.2, Eq. (2)) ----
+
+def test_generate_masks_is_union_of_the_two_selections():
+    rng = np.random.default_rng(51)
+    M, K, b, s = 128, 96, 16, 0.75
+    W, G = synth.gauss_bf16(rng, (M, K), 1.0), synth.gauss_bf16(rng, (M, K), 1.0)
+    m = orc.generate_masks(W, G, b, s)
+    mw, _ = orc.topk_mask(orc.block_scores(W, b), s)
+    mg, _ = orc.topk_mask(orc.block_scores(G, b), s)
+    n_keep = orc.n_keep(mw.size, s)
+    assert np.array_equal(m == 1, mw.reshape(m.shape).astype(bool))
+    assert np.array_equal(m == 2, (mg.reshape(m.shape) == 1) & (mw.reshape(m.shape) == 0))  # the set difference
+    assert np.array_equal(m != 0, (mw | mg).reshape(m.shape).astype(bool))
+    assert int((m == 1).sum()) == n_keep and n_keep <= int((m != 0).sum()) <= 2 * n_keep
+    # independent numpy ranking: stable argsort of (-score, index)
+    def np_topk(A):
+        sc = (f64(A).reshape(M // b, b, K // b, b) ** 2).sum(axis=(1, 3)).ravel()
+        keep = np.argsort(-sc, kind="stable")[:n_keep]
+        out = np.zeros(sc.size, dtype=bool)
+        out[keep] = True
+        return out.reshape(M // b, K // b)
+    assert np.array_equal(m == 1, np_topk(W)) and np.array_equal(m != 0, np_topk(W) | np_topk(G))
+
+
+def test_generate_masks_special_cases():
+    rng = np.random.default_rng(52)
+    M, K, b, s = 64, 64, 16, 0.5
+    W = synth.gauss_bf16(rng, (M, K), 1.0)
+    # gradient ranks like the weight: nothing to regrow
+    assert not (orc.generate_masks(W, W, b, s) == 2).any()
+    # gradient mass only on the blocks the weight drops: exactly those come back (n_keep of them at s = 0.5)
+    mw, _ = orc.topk_mask(orc.block_scores(W, b), s)
+    mw = mw.reshape(M // b, K // b)
+    Gf = np.kron(1 - mw, np.ones((b, b))) * (1.0 + np.arange(M * K).reshape(M, K) % 7)
+    m = orc.generate_masks(W, synth.f32_to_bf16_bits(Gf.astype(np.float32)), b, s)
+    assert np.array_equal(m == 2, mw == 0) and (m != 0).all()
+    # s = 0: everything kept by the weight itself; s = 1: nothing survives and nothing regrows
+    assert (orc.generate_masks(W, W, b, 0.0) == 1).all()
+    assert not orc.generate_masks(W, synth.gauss_bf16(rng, (M, K), 1.0), b, 1.0).any()
+    # packing a regrown block stores zeros (they must not change the current transform)
+    m2 = np.zeros((M // b, K // b), dtype=np.uint8)
+    m2[0, 1], m2[2, 3] = 1, 2
+    p = orc.pack(W, b, m2)
+    assert p.nnz == 2 and np.array_equal(p.vals[0], W[:b, b:2 * b]) and not p.vals[1].any()
+    x = synth.gauss_bf16(rng, (3, K), 1.0)
+    m1 = m2.copy()
+    m1[2, 3] = 0
+    assert np.array_equal(orc.spmm(p, x), orc.spmm(orc.pack(W, b, m1), x))
+
+
+def test_sparsity_schedule_closed_forms():
+    # Eq. (2): s(0) = s_init, s(m - d) = s_max, halfway the cube leaves an eighth of the distance
+    m, d, s0, s1 = 9000, 1000, 0.1, 0.8
+    assert orc.sparsity_schedule(0, m, d, s0, s1) == pytest.approx(s0, abs=1e-15)
+    assert orc.sparsity_schedule(m - d, m, d, s0, s1) == s1
+    assert orc.sparsity_schedule((m - d) // 2, m, d, s0, s1) == pytest.approx(s1 + (s0 - s1) / 8, abs=1e-15)
+    assert orc.sparsity_schedule(2000, m, d, s0, s1) == pytest.approx(s1 + (s0 - s1) * Fraction(3, 4) ** 3, abs=1e-15)
+    vals = [orc.sparsity_schedule(i, m, d, s0, s1) for i in range(0, m + 1, 250)]
+    assert all(a <= b_ + 1e-15 for a, b_ in zip(vals, vals[1:]))  # sparsity never decreases
+    assert all(s0 - 1e-15 <= v <= s1 + 1e-15 for v in vals)
+    # held at the ends: the cube is not followed past i = m - d
+    assert orc.sparsity_schedule(m, m, d, s0, s1) == s1 and orc.sparsity_schedule(-5, m, d, s0, s1) == pytest.approx(s0)
