@@ -377,7 +377,27 @@ def main():
     torch.cuda.synchronize()
     pack_ms = (time.perf_counter() - t0) * 1e3 / reps
     dense_bytes = sum(int(w_.numel()) * 2 for w_ in dW)
-    del dW
+    # one prune-and-grow mask update of the gate matrix (reads W and a gradient-shaped tensor once each)
+    g_h = synth.gauss_bf16(np.random.default_rng(synth.BASE_SEED + 5), inp.gate.W.shape, 1e-3)
+    dG = to_dev(g_h)
+    api.generate_masks(dW[0], dG, b, wl.sparsity)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        api.generate_masks(dW[0], dG, b, wl.sparsity)
+    torch.cuda.synchronize()
+    masks_ms = (time.perf_counter() - t0) * 1e3 / reps
+    masks_bytes = 2 * int(dW[0].numel()) * 2
+    masks_cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+
+        t0 = time.perf_counter()
+        m_or = orc.generate_masks(inp.gate.W, g_h, b, wl.sparsity)
+        masks_cpu = {"seconds": time.perf_counter() - t0, "kind": "oracle", "cores": 1,
+                     "sample": "the whole gate matrix and gradient",
+                     "identical_to_device": bool(np.array_equal(m_or, api.generate_masks(dW[0], dG, b, wl.sparsity).cpu().numpy()))}
+    del dW, dG
     g, u, d = packed
     g = api.with_joint_row_order(g, u)
     nnz = g.nnz + u.nnz + d.nnz
@@ -424,7 +444,10 @@ def main():
         "phases_ms": {"gate_up_act": head["ms_gate_up"], "down": head["ms_down"], "pass_events": head["ms_events"]},
         "roofline": roofline,
         "pack": {"ms_three_matrices_topk": pack_ms, "dense_GBps": dense_bytes / (pack_ms * 1e-3) / 1e9,
-                 "frac_hbm": dense_bytes / (pack_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+                 "frac_hbm": dense_bytes / (pack_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                 "generate_masks": {"ms_gate_matrix": masks_ms, "GBps": masks_bytes / (masks_ms * 1e-3) / 1e9,
+                                    "frac_hbm": masks_bytes / (masks_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                    "cpu_baseline": masks_cpu}},
     }
 
     if not args.no_decode:

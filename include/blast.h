@@ -109,7 +109,8 @@ int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, do
  *
  *   W, ldw      dense weight, element (i, j) at W[i*ldw + j]; ldw >= cols, ldw % 8 == 0, W 16-byte aligned.
  *   mode        BLAST_PACK_MASK: block_mask [rows/b][cols/b] uint8 (nonzero = keep) is the structure;
- *               a kept block is stored even when all its values are zero.
+ *               a kept block is stored even when all its values are zero; the value 2 marks a regrown
+ *               block (Sec. 3.2), which is stored as zeros whatever W holds there.
  *               BLAST_PACK_TOPK_FROBENIUS: block_mask is ignored (may be NULL).  Each block is scored by
  *               its squared Frobenius norm accumulated in fp64; the blast_n_keep() highest are kept;
  *               equal scores are ordered by linear block index (block_row * (cols/b) + block_col), lower
@@ -137,6 +138,29 @@ int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, i
                    const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx, uint16_t* vals,
                    int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap, int64_t* nnz_out,
                    int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One mask update of blocked prune-and-grow (Sec. 3.2, the generate_masks() step of the training loop):
+ *   S(W) = the blocks of W kept at `sparsity` by block Frobenius norm (same count, ranking and tie rule as
+ *          BLAST_PACK_TOPK_FROBENIUS), S(G) = the same selection on the gradient G, D = S(G) \ S(W).
+ *   mask_out[block] = 1 for S(W), 2 for D (regrown: kept in the structure, values start at zero), 0 otherwise.
+ * Feeding mask_out to blast_bsr_pack in BLAST_PACK_MASK mode packs W_new: blocks with code 2 are stored as
+ * zeros, so they do not change the current product.
+ *   W, G        bf16 [rows][cols], row pitches ldw / ldg (multiples of 8), 16-byte aligned
+ *   mask_out    out, uint8 [rows/b][cols/b]
+ *   ws          at least blast_generate_masks_workspace(rows, cols, b) bytes, 16-byte aligned
+ * Never synchronises.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
+ */
+int blast_generate_masks(const uint16_t* W, int64_t ldw, const uint16_t* G, int64_t ldg, int64_t rows, int64_t cols,
+                         int32_t b, double sparsity, uint8_t* mask_out, void* ws, size_t ws_bytes, void* stream);
+size_t blast_generate_masks_workspace(int64_t rows, int64_t cols, int32_t b);
+
+/*
+ * Eq. (2): sparsity at training iteration i,  s(i) = s_max + (s_init - s_max) * (1 - i / (m - d))^3,
+ * with i held inside [0, m - d] (the paper gives no value past m - d, where the cube would exceed s_max).
+ * Host arithmetic only.
+ */
+double blast_sparsity_schedule(int64_t i, int64_t m, int64_t d, double s_init, double s_max);
 
 /*
  * Packed transpose.  Sec. 3.2: the pruned matrix is the one used in forward AND backward propagation;

@@ -24,7 +24,8 @@ ACT = {"silu": 0, "gelu": 1, "relu": 2}
 EXPORTS = (
     "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
-    "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
+    "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm",
+    "blast_generate_masks", "blast_generate_masks_workspace", "blast_sparsity_schedule", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
 
@@ -79,6 +80,12 @@ def lib():
         L.blast_sparse_mlp2.argtypes = [pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
         L.blast_sparse_mlp2_workspace.restype = C.c_int
         L.blast_sparse_mlp2_workspace.argtypes = [pv, pv, i64, C.POINTER(sz)]
+        L.blast_generate_masks.restype = C.c_int
+        L.blast_generate_masks.argtypes = [vp, i64, vp, i64, i64, i64, i32, C.c_double, vp, vp, sz, vp]
+        L.blast_generate_masks_workspace.restype = sz
+        L.blast_generate_masks_workspace.argtypes = [i64, i64, i32]
+        L.blast_sparsity_schedule.restype = C.c_double
+        L.blast_sparsity_schedule.argtypes = [i64, i64, i64, C.c_double, C.c_double]
         L.blast_bsr_transpose.restype = C.c_int
         L.blast_bsr_transpose.argtypes = [pv, vp, vp, vp, vp, vp, sz, C.POINTER(C.c_int32), vp]
         L.blast_bsr_sddmm.restype = C.c_int
@@ -184,6 +191,26 @@ def with_joint_row_order(gate: PackedBsr, up: PackedBsr) -> PackedBsr:
     _check(lib().blast_bsr_joint_row_order(C.byref(vg), C.byref(vu), _ptr(order), _stream()),
            "blast_bsr_joint_row_order")
     return dataclasses.replace(gate, row_order=order)
+
+
+def generate_masks(W: torch.Tensor, G: torch.Tensor, b: int, sparsity: float) -> torch.Tensor:
+    """blast_generate_masks: uint8 [rows/b, cols/b]; 1 = kept by the weight's ranking, 2 = regrown, 0 = dropped."""
+    L = lib()
+    for t in (W, G):
+        assert t.is_cuda and t.dim() == 2 and t.stride(1) == 1 and t.element_size() == 2
+    assert W.shape == G.shape
+    rows, cols = W.shape
+    mask = torch.empty((rows // b, cols // b), dtype=torch.uint8, device=W.device)
+    ws = torch.empty(max(int(L.blast_generate_masks_workspace(rows, cols, b)), 16), dtype=torch.uint8, device=W.device)
+    _check(L.blast_generate_masks(_ptr(W), W.stride(0), _ptr(G), G.stride(0), rows, cols, b, float(sparsity),
+                                  _ptr(mask), _ptr(ws), ws.numel(), _stream()), "blast_generate_masks")
+    torch.cuda.current_stream().synchronize()  # ws is released on return
+    return mask
+
+
+def sparsity_schedule(i: int, m: int, d: int, s_init: float, s_max: float) -> float:
+    """blast_sparsity_schedule: Eq. (2)."""
+    return float(lib().blast_sparsity_schedule(int(i), int(m), int(d), float(s_init), float(s_max)))
 
 
 def bsr_transpose(W: PackedBsr) -> PackedBsr:

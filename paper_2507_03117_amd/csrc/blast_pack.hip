@@ -198,19 +198,30 @@ __global__ __launch_bounds__(256) void k_fill_cols(const uint8_t* __restrict__ m
   }
 }
 
-// One workgroup per stored block: copy its b x b values, row-major, 16 bytes per lane.
+// One workgroup per stored block: copy its b x b values, row-major, 16 bytes per lane.  A block whose mask
+// code is 2 (regrown, BLaST Sec. 3.2) is stored as zeros: it joins the structure without changing the product.
 __global__ __launch_bounds__(256) void k_gather_blocks(const uint16_t* __restrict__ W, int64_t ldw, int b,
                                                        const int* __restrict__ col_idx, const int* __restrict__ blk_row,
+                                                       const uint8_t* __restrict__ mask, int nbc,
                                                        uint16_t* __restrict__ vals) {
   const int64_t k = blockIdx.x;
   const int64_t br = blk_row[k], bc = col_idx[k];
   const uint16_t* src = W + br * b * ldw + bc * b;
   uint16_t* dst = vals + k * b * b;
   const int cpr = b / 8, nchunks = b * cpr;
+  const bool zero = mask[br * nbc + bc] == 2;
   for (int c = threadIdx.x; c < nchunks; c += 256) {
     const int i = c / cpr, j8 = c % cpr;
-    *reinterpret_cast<uint4*>(dst + (int64_t)c * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)i * ldw + j8 * 8);
+    *reinterpret_cast<uint4*>(dst + (int64_t)c * 8) =
+        zero ? uint4{0u, 0u, 0u, 0u} : *reinterpret_cast<const uint4*>(src + (int64_t)i * ldw + j8 * 8);
   }
+}
+
+// out = 1 where the weight's own selection keeps the block, 2 where only the gradient's does, else 0
+__global__ __launch_bounds__(256) void k_merge_masks(const uint8_t* __restrict__ mw, const uint8_t* __restrict__ mg,
+                                                     int64_t n, uint8_t* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = mw[i] ? 1 : (mg[i] ? 2 : 0);
 }
 
 // row_order[rank] = r with rank = number of rows that sort before r under
@@ -500,7 +511,7 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
     BLAST_LAUNCH_CHECK("k_fill_cols");
   }
   if (nnz_host > 0) {
-    k_gather_blocks<<<dim3((unsigned)nnz_host), dim3(256), 0, stream>>>(W, ldw, b, col_idx, blk_row, vals);
+    k_gather_blocks<<<dim3((unsigned)nnz_host), dim3(256), 0, stream>>>(W, ldw, b, col_idx, blk_row, mask, (int)nbc, vals);
     BLAST_LAUNCH_CHECK("k_gather_blocks");
   }
   if (aux) {
@@ -603,4 +614,60 @@ extern "C" int blast_bsr_transpose(const blast_bsr_view* W, int32_t* row_ptr_t, 
   }
   if (max_row_blocks_t_out) *max_row_blocks_t_out = heavy;
   return BLAST_OK;
+}
+
+// ---- one mask update of blocked prune-and-grow (BLaST Sec. 3.2, generate_masks()) ----
+
+extern "C" size_t blast_generate_masks_workspace(int64_t rows, int64_t cols, int32_t b) {
+  if (check_shape(rows, cols, b) != BLAST_OK) return 0;
+  const size_t n = (size_t)(rows / b) * (size_t)(cols / b);
+  return blast::align_up(8 * (n > 0 ? n : 1), 256) + 2 * blast::align_up(n > 0 ? n : 1, 256);
+}
+
+extern "C" int blast_generate_masks(const uint16_t* W, int64_t ldw, const uint16_t* G, int64_t ldg, int64_t rows,
+                                    int64_t cols, int32_t b, double sparsity, uint8_t* mask_out, void* ws,
+                                    size_t ws_bytes, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (int rc = check_shape(rows, cols, b)) return rc;
+  const int64_t nbc = cols / b, n = (rows / b) * nbc;
+  const int64_t n_keep = blast_n_keep(n, sparsity);
+  if (n_keep < 0) return BLAST_ERR_INVALID_ARG;
+  if (n == 0) return BLAST_OK;
+  if (!W || !G || !mask_out || ldw < cols || ldg < cols || ldw % 8 || ldg % 8 || !blast::aligned(W, 16) ||
+      !blast::aligned(G, 16))
+    return BLAST_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < blast_generate_masks_workspace(rows, cols, b) || !blast::aligned(ws, 16))
+    return BLAST_ERR_WORKSPACE;
+  char* wsb = static_cast<char*>(ws);
+  double* scores = reinterpret_cast<double*>(wsb);
+  uint8_t* mw = reinterpret_cast<uint8_t*>(wsb + blast::align_up(8 * (size_t)n, 256));
+  uint8_t* mg = mw + blast::align_up((size_t)n, 256);
+  const dim3 per_elem((unsigned)((n + 255) / 256));
+  if (n_keep == 0 || n_keep == n) {  // nothing survives and nothing regrows, or everything is kept by W itself
+    k_fill_u8<<<per_elem, dim3(256), 0, stream>>>(mask_out, n, n_keep == n ? 1 : 0);
+    BLAST_LAUNCH_CHECK("k_fill_u8");
+    return BLAST_OK;
+  }
+  k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(W, ldw, (int)nbc, b, scores);
+  BLAST_LAUNCH_CHECK("k_block_scores(W)");
+  k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, mw);
+  BLAST_LAUNCH_CHECK("k_select_topk(W)");
+  k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(G, ldg, (int)nbc, b, scores);
+  BLAST_LAUNCH_CHECK("k_block_scores(G)");
+  k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, mg);
+  BLAST_LAUNCH_CHECK("k_select_topk(G)");
+  k_merge_masks<<<per_elem, dim3(256), 0, stream>>>(mw, mg, n, mask_out);
+  BLAST_LAUNCH_CHECK("k_merge_masks");
+  return BLAST_OK;
+}
+
+// Eq. (2).  Past i = m - d the cube would turn negative and push s above s_max; the iteration is held
+// inside [0, m - d].
+extern "C" double blast_sparsity_schedule(int64_t i, int64_t m, int64_t d, double s_init, double s_max) {
+  const int64_t span = m - d;
+  if (span <= 0) return s_max;
+  if (i < 0) i = 0;
+  if (i > span) i = span;
+  const double f = 1.0 - (double)i / (double)span;
+  return s_max + (s_init - s_max) * f * f * f;
 }

@@ -104,6 +104,15 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     assert L.blast_bsr_sddmm(C.byref(g1), None, 256, None, 128, 7, 4, None, None) == -1  # layout enum
     bad48 = api.BsrView(96, 96, 48, 0, 1, v.row_ptr, v.row_ptr, None, None, None)
     assert L.blast_bsr_sddmm(C.byref(bad48), None, 96, None, 96, 0, 4, None, None) == -3
+    # mask update: shape / argument checks, and the schedule (host arithmetic, runs without a GPU)
+    assert L.blast_generate_masks(None, 128, None, 128, 128, 128, 64, 0.5, None, None, 0, None) == -1
+    assert L.blast_generate_masks(None, 128, None, 128, 100, 128, 64, 0.5, None, None, 0, None) == -2
+    assert L.blast_generate_masks(None, 128, None, 128, 128, 128, 64, 1.5, None, None, 0, None) == -1
+    assert L.blast_generate_masks_workspace(128, 128, 64) >= 4 * 8 + 2 * 4
+    assert L.blast_sparsity_schedule(0, 9000, 1000, 0.1, 0.8) == pytest.approx(0.1, abs=1e-15)
+    assert L.blast_sparsity_schedule(8000, 9000, 1000, 0.1, 0.8) == 0.8
+    assert L.blast_sparsity_schedule(9000, 9000, 1000, 0.1, 0.8) == 0.8
+    assert L.blast_sparsity_schedule(4000, 9000, 1000, 0.1, 0.8) == pytest.approx(0.8 - 0.7 / 8, abs=1e-15)
     # pack: null outputs / bad ld are rejected up front
     nnz = C.c_int64(0)
     assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, None, 0, None) == -1
