@@ -121,8 +121,12 @@ int64_t oracle_topk_mask(const double* score, int64_t n_blocks, double sparsity,
   memset(mask, 0, (size_t)n_blocks);
   for (int64_t i = 0; i < n_keep; ++i) mask[a[i].idx] = 1;
   if (gap_out) {
-    if (n_keep > 0 && n_keep < n_blocks && a[n_keep - 1].score > 0.0)
-      *gap_out = (a[n_keep - 1].score - a[n_keep].score) / a[n_keep - 1].score;
+    /* relative to the larger magnitude of the two, so that it also means something for negative scores
+     * (pooled sensitivities may have any sign); identical for the non-negative Frobenius scores */
+    double den = 0.0;
+    if (n_keep > 0 && n_keep < n_blocks) den = fmax(fabs(a[n_keep - 1].score), fabs(a[n_keep].score));
+    if (den > 0.0)
+      *gap_out = (a[n_keep - 1].score - a[n_keep].score) / den;
     else
       *gap_out = 1.0;
   }
@@ -354,4 +358,21 @@ double oracle_sparsity_schedule(int64_t i, int64_t m, int64_t d, double s_init, 
   if (i > span) i = span;
   double f = 1.0 - (double)i / (double)span;
   return s_max + (s_init - s_max) * f * f * f;
+}
+
+/* ---- block scores from a sensitivity matrix (Sec. 3.3: the per-weight sensitivities form a matrix of the
+ * weight's shape, which is cut into b x b blocks; a block's score is the 2D average pooling of its entries;
+ * the blocks with the least score are pruned). ---- */
+
+/* score[br][bc] = mean of S over the block, fp64, row-major order inside the block.  S is fp32 [rows][lds]. */
+void oracle_pooled_scores(const float* S, int64_t lds, int64_t rows, int64_t cols, int32_t b,
+                          double* score /* [rows/b][cols/b] */) {
+  int64_t nbr = rows / b, nbc = cols / b;
+  for (int64_t br = 0; br < nbr; ++br)
+    for (int64_t bc = 0; bc < nbc; ++bc) {
+      double s = 0.0;
+      for (int32_t i = 0; i < b; ++i)
+        for (int32_t j = 0; j < b; ++j) s += (double)S[(br * b + i) * lds + bc * b + j];
+      score[br * nbc + bc] = s / ((double)b * (double)b);
+    }
 }

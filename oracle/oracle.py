@@ -52,6 +52,8 @@ def lib():
         L.oracle_generate_masks.argtypes = [vp, i64, vp, i64, i64, i64, i32, dbl, vp]
         L.oracle_sparsity_schedule.restype = dbl
         L.oracle_sparsity_schedule.argtypes = [i64, i64, i64, dbl, dbl]
+        L.oracle_pooled_scores.restype = None
+        L.oracle_pooled_scores.argtypes = [vp, i64, i64, i64, i32, vp]
         L.oracle_mlp2.restype = None
         L.oracle_mlp2.argtypes = [i64, i64, i32] + [vp] * 6 + [vp, i64, i64, i64, i32, vp, vp]
         _lib = L
@@ -222,3 +224,20 @@ def generate_masks(W: np.ndarray, G: np.ndarray, b: int, sparsity: float) -> np.
 def sparsity_schedule(i: int, m: int, d: int, s_init: float, s_max: float) -> float:
     """Eq. (2), with the iteration held inside [0, m - d]."""
     return float(lib().oracle_sparsity_schedule(int(i), int(m), int(d), float(s_init), float(s_max)))
+
+
+def pooled_scores(S: np.ndarray, b: int) -> np.ndarray:
+    """2D average pooling of a sensitivity matrix over b x b blocks (Sec. 3.3): fp64 [rows/b, cols/b]."""
+    S = np.ascontiguousarray(S, dtype=np.float32)
+    rows, cols = S.shape
+    sc = np.empty((rows // b, cols // b), dtype=np.float64)
+    lib().oracle_pooled_scores(_p(S), cols, rows, cols, b, _p(sc))
+    return sc
+
+
+def pooled_topk_mask(S: np.ndarray, b: int, sparsity: float) -> Tuple[np.ndarray, float]:
+    """Keep the blocks with the highest pooled sensitivity (same count and tie rule as the Frobenius ranking).
+    Returns (uint8 mask [rows/b, cols/b], relative score gap at the keep/drop boundary)."""
+    sc = pooled_scores(S, b)
+    mask, gap = topk_mask(sc, sparsity)
+    return mask.reshape(sc.shape), gap

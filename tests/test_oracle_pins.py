@@ -614,3 +614,44 @@ def test_sparsity_schedule_closed_forms():
     assert all(s0 - 1e-15 <= v <= s1 + 1e-15 for v in vals)
     # held at the ends: the cube is not followed past i = m - d
     assert orc.sparsity_schedule(m, m, d, s0, s1) == s1 and orc.sparsity_schedule(-5, m, d, s0, s1) == pytest.approx(s0)
+
+
+# ---- block scores by 2D average pooling of a sensitivity matrix (Sec. 3.3) ----
+
+def test_pooled_scores_equal_numpy_mean_and_frobenius_ranking():
+    rng = np.random.default_rng(61)
+    M, K, b = 96, 64, 16
+    S = rng.standard_normal((M, K)).astype(np.float32)  # sensitivities of either sign
+    sc = orc.pooled_scores(S, b)
+    ref = S.astype(np.float64).reshape(M // b, b, K // b, b).mean(axis=(1, 3))
+    np.testing.assert_allclose(sc, ref, rtol=1e-13, atol=1e-16)
+    # a constant block pools to the constant; a one-hot block to 1 / b^2
+    S2 = np.zeros((2 * b, 2 * b), dtype=np.float32)
+    S2[:b, :b] = -3.5
+    S2[b + 3, b + 5] = 1.0
+    sc2 = orc.pooled_scores(S2, b)
+    assert sc2[0, 0] == -3.5 and sc2[1, 1] == 1.0 / (b * b) and sc2[0, 1] == 0.0 and sc2[1, 0] == 0.0
+    # pooling the squared weights ranks exactly like the Frobenius norm: same mask
+    W = synth.gauss_bf16(rng, (M, K), 1.0)
+    Wsq = (f64(W) ** 2).astype(np.float32)  # bf16 squared is exact in fp32
+    for s in (0.25, 0.5, 0.9):
+        m_pool, _ = orc.pooled_topk_mask(Wsq, b, s)
+        m_fro, _ = orc.topk_mask(orc.block_scores(W, b), s)
+        assert np.array_equal(m_pool, m_fro.reshape(m_pool.shape))
+
+
+def test_pooled_topk_mask_ranking_and_ties():
+    rng = np.random.default_rng(62)
+    M, K, b, s = 64, 64, 8, 0.6
+    S = rng.standard_normal((M, K)).astype(np.float32)
+    m, gap = orc.pooled_topk_mask(S, b, s)
+    n = (M // b) * (K // b)
+    n_keep = orc.n_keep(n, s)
+    ref = S.astype(np.float64).reshape(M // b, b, K // b, b).mean(axis=(1, 3)).ravel()
+    keep = np.argsort(-ref, kind="stable")[:n_keep]
+    want = np.zeros(n, dtype=np.uint8)
+    want[keep] = 1
+    assert np.array_equal(m.ravel(), want) and int(m.sum()) == n_keep and gap > 0
+    # all blocks equal: the lowest indices survive
+    m_eq, gap_eq = orc.pooled_topk_mask(np.full((M, K), -1.25, dtype=np.float32), b, s)
+    assert np.array_equal(np.nonzero(m_eq.ravel())[0], np.arange(n_keep)) and gap_eq == 0.0
