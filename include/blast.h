@@ -163,6 +163,21 @@ size_t blast_generate_masks_workspace(int64_t rows, int64_t cols, int32_t b);
 double blast_sparsity_schedule(int64_t i, int64_t m, int64_t d, double s_init, double s_max);
 
 /*
+ * Block selection from a sensitivity matrix (Sec. 3.3): S holds one fp32 sensitivity per weight; a block's
+ * score is the 2D average pooling (mean) of its b x b entries, accumulated in fp64; the blast_n_keep()
+ * highest-scoring blocks are kept, equal scores ordered by linear block index, lower first (the rule of
+ * BLAST_PACK_TOPK_FROBENIUS).  Sensitivities may have any sign but must be finite.  How S is computed
+ * (curvature estimates, gradients) is the caller's business.
+ *   S, lds      fp32 [rows][cols], row pitch lds (multiple of 4), 16-byte aligned
+ *   mask_out    out, uint8 [rows/b][cols/b], 1 = keep; feed it to blast_bsr_pack in BLAST_PACK_MASK mode
+ *   ws          at least blast_pooled_topk_mask_workspace(rows, cols, b) bytes, 16-byte aligned
+ * Never synchronises.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
+ */
+int blast_pooled_topk_mask(const float* S, int64_t lds, int64_t rows, int64_t cols, int32_t b, double sparsity,
+                           uint8_t* mask_out, void* ws, size_t ws_bytes, void* stream);
+size_t blast_pooled_topk_mask_workspace(int64_t rows, int64_t cols, int32_t b);
+
+/*
  * Packed transpose.  Sec. 3.2: the pruned matrix is the one used in forward AND backward propagation;
  * Sec. 3.4 / 3.4.1: which compressed format suits depends on the side the sparse matrix is multiplied
  * from, and the kernel for the other side is the symmetric one.  This call builds, from a packed W~

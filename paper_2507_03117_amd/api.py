@@ -25,7 +25,8 @@ EXPORTS = (
     "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
     "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm",
-    "blast_generate_masks", "blast_generate_masks_workspace", "blast_sparsity_schedule", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
+    "blast_generate_masks", "blast_generate_masks_workspace", "blast_sparsity_schedule",
+    "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
 
@@ -86,6 +87,10 @@ def lib():
         L.blast_generate_masks_workspace.argtypes = [i64, i64, i32]
         L.blast_sparsity_schedule.restype = C.c_double
         L.blast_sparsity_schedule.argtypes = [i64, i64, i64, C.c_double, C.c_double]
+        L.blast_pooled_topk_mask.restype = C.c_int
+        L.blast_pooled_topk_mask.argtypes = [vp, i64, i64, i64, i32, C.c_double, vp, vp, sz, vp]
+        L.blast_pooled_topk_mask_workspace.restype = sz
+        L.blast_pooled_topk_mask_workspace.argtypes = [i64, i64, i32]
         L.blast_bsr_transpose.restype = C.c_int
         L.blast_bsr_transpose.argtypes = [pv, vp, vp, vp, vp, vp, sz, C.POINTER(C.c_int32), vp]
         L.blast_bsr_sddmm.restype = C.c_int
@@ -204,6 +209,19 @@ def generate_masks(W: torch.Tensor, G: torch.Tensor, b: int, sparsity: float) ->
     ws = torch.empty(max(int(L.blast_generate_masks_workspace(rows, cols, b)), 16), dtype=torch.uint8, device=W.device)
     _check(L.blast_generate_masks(_ptr(W), W.stride(0), _ptr(G), G.stride(0), rows, cols, b, float(sparsity),
                                   _ptr(mask), _ptr(ws), ws.numel(), _stream()), "blast_generate_masks")
+    torch.cuda.current_stream().synchronize()  # ws is released on return
+    return mask
+
+
+def pooled_topk_mask(S: torch.Tensor, b: int, sparsity: float) -> torch.Tensor:
+    """blast_pooled_topk_mask: keep the blocks with the highest mean sensitivity; uint8 [rows/b, cols/b]."""
+    L = lib()
+    assert S.is_cuda and S.dim() == 2 and S.stride(1) == 1 and S.dtype == torch.float32
+    rows, cols = S.shape
+    mask = torch.empty((rows // b, cols // b), dtype=torch.uint8, device=S.device)
+    ws = torch.empty(max(int(L.blast_pooled_topk_mask_workspace(rows, cols, b)), 16), dtype=torch.uint8, device=S.device)
+    _check(L.blast_pooled_topk_mask(_ptr(S), S.stride(0), rows, cols, b, float(sparsity), _ptr(mask), _ptr(ws),
+                                    ws.numel(), _stream()), "blast_pooled_topk_mask")
     torch.cuda.current_stream().synchronize()  # ws is released on return
     return mask
 

@@ -73,13 +73,43 @@ __global__ __launch_bounds__(256) void k_block_scores(const uint16_t* __restrict
   if (threadIdx.x == 0) score[blk] = red[0];
 }
 
+// One workgroup per block: mean of an fp32 sensitivity matrix over the block (2D average pooling,
+// BLaST Sec. 3.3), accumulated in fp64 with the same tree as the Frobenius scores.
+__global__ __launch_bounds__(256) void k_pooled_scores(const float* __restrict__ S, int64_t lds, int nbc, int b,
+                                                       double* __restrict__ score) {
+  __shared__ double red[256];
+  const int64_t blk = blockIdx.x;
+  const int64_t br = blk / nbc, bc = blk % nbc;
+  const float* base = S + br * b * lds + bc * b;
+  const int cpr = b / 4, nchunks = b * cpr;
+  double s = 0.0;
+  for (int c = threadIdx.x; c < nchunks; c += 256) {
+    const int i = c / cpr, j4 = c % cpr;
+    const float4 v = *reinterpret_cast<const float4*>(base + (int64_t)i * lds + j4 * 4);
+    s += ((double)v.x + (double)v.y) + ((double)v.z + (double)v.w);
+  }
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int d = 128; d > 0; d >>= 1) {
+    if ((int)threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) score[blk] = red[0] / ((double)b * (double)b) + 0.0;  // + 0.0: no negative zero
+}
+
 __global__ void k_fill_u8(uint8_t* p, int64_t n, uint8_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
 
-// Exact selection of the n_keep highest scores (0 < n_keep < n).  Scores are
-// non-negative doubles, so their bit patterns order like unsigned integers.
+// Bit pattern of a double mapped to an unsigned integer with the same order (any finite sign; -0.0 is
+// canonicalised to +0.0 by the scoring kernels, so equal scores have equal keys).
+__device__ __forceinline__ unsigned long long order_key(unsigned long long bits) {
+  return (bits >> 63) ? ~bits : (bits | 0x8000000000000000ull);
+}
+
+// Exact selection of the n_keep highest scores (0 < n_keep < n), compared through
+// order-preserving integer keys.
 // An 8-pass most-significant-digit radix select finds the n_keep-th largest
 // pattern; everything above it is kept, and of the entries equal to it the
 // first ones in index order fill the remaining quota.
@@ -102,7 +132,7 @@ __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__
     const unsigned long long prefix = s_prefix;
     const unsigned long long himask = (pass == 7) ? 0ull : (~0ull << (8 * (pass + 1)));
     for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
-      const unsigned long long k = key[i];
+      const unsigned long long k = order_key(key[i]);
       if ((k & himask) == prefix) atomicAdd(&hist[(unsigned)(k >> (8 * pass)) & 255u], 1u);
     }
     __syncthreads();
@@ -127,7 +157,7 @@ __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__
   const long long need_eq = s_remaining;
   for (int64_t base = 0; base < n; base += blockDim.x) {
     const int64_t i = base + threadIdx.x;
-    const unsigned long long k = (i < n) ? key[i] : 0ull;
+    const unsigned long long k = (i < n) ? order_key(key[i]) : 0ull;
     const int eq = (i < n && k == kth) ? 1 : 0;
     int total;
     const long long pos = s_running + block_exscan(eq, wave_tot, total);
@@ -670,4 +700,36 @@ extern "C" double blast_sparsity_schedule(int64_t i, int64_t m, int64_t d, doubl
   if (i > span) i = span;
   const double f = 1.0 - (double)i / (double)span;
   return s_max + (s_init - s_max) * f * f * f;
+}
+
+// ---- block selection from a sensitivity matrix (BLaST Sec. 3.3) ----
+
+extern "C" size_t blast_pooled_topk_mask_workspace(int64_t rows, int64_t cols, int32_t b) {
+  if (check_shape(rows, cols, b) != BLAST_OK) return 0;
+  const size_t n = (size_t)(rows / b) * (size_t)(cols / b);
+  return blast::align_up(8 * (n > 0 ? n : 1), 256);
+}
+
+extern "C" int blast_pooled_topk_mask(const float* S, int64_t lds, int64_t rows, int64_t cols, int32_t b,
+                                      double sparsity, uint8_t* mask_out, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (int rc = check_shape(rows, cols, b)) return rc;
+  const int64_t nbc = cols / b, n = (rows / b) * nbc;
+  const int64_t n_keep = blast_n_keep(n, sparsity);
+  if (n_keep < 0) return BLAST_ERR_INVALID_ARG;
+  if (n == 0) return BLAST_OK;
+  if (!S || !mask_out || lds < cols || lds % 4 || !blast::aligned(S, 16)) return BLAST_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < blast_pooled_topk_mask_workspace(rows, cols, b) || !blast::aligned(ws, 16))
+    return BLAST_ERR_WORKSPACE;
+  if (n_keep == 0 || n_keep == n) {
+    k_fill_u8<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(mask_out, n, n_keep == n ? 1 : 0);
+    BLAST_LAUNCH_CHECK("k_fill_u8");
+    return BLAST_OK;
+  }
+  double* scores = static_cast<double*>(ws);
+  k_pooled_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(S, lds, (int)nbc, b, scores);
+  BLAST_LAUNCH_CHECK("k_pooled_scores");
+  k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, mask_out);
+  BLAST_LAUNCH_CHECK("k_select_topk(pooled)");
+  return BLAST_OK;
 }

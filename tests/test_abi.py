@@ -113,6 +113,9 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     assert L.blast_sparsity_schedule(8000, 9000, 1000, 0.1, 0.8) == 0.8
     assert L.blast_sparsity_schedule(9000, 9000, 1000, 0.1, 0.8) == 0.8
     assert L.blast_sparsity_schedule(4000, 9000, 1000, 0.1, 0.8) == pytest.approx(0.8 - 0.7 / 8, abs=1e-15)
+    assert L.blast_pooled_topk_mask(None, 128, 128, 128, 64, 0.5, None, None, 0, None) == -1
+    assert L.blast_pooled_topk_mask(None, 128, 128, 100, 64, 0.5, None, None, 0, None) == -2
+    assert L.blast_pooled_topk_mask_workspace(128, 128, 64) >= 4 * 8
     # pack: null outputs / bad ld are rejected up front
     nnz = C.c_int64(0)
     assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, None, 0, None) == -1

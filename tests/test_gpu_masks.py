@@ -97,3 +97,42 @@ def test_pack_with_regrown_blocks_and_one_training_round(api):
     dv_or = orc.sddmm(ref, dY, x)
     check_close(dv.cpu().numpy().reshape(1, -1), dv_or.reshape(1, -1), "gradient of W_new")
     assert np.abs(dv.cpu().numpy()[grown]).max() > 0
+
+
+@pytest.mark.parametrize("b,rows,cols,s", [(16, 256, 512, 0.7), (32, 1024, 2048, 0.9), (64, 2048, 1024, 0.5),
+                                           (128, 1024, 1536, 0.8), (64, 512, 512, 0.0), (64, 512, 512, 1.0)])
+def test_pooled_topk_mask_matches_oracle(api, b, rows, cols, s):
+    """Sec. 3.3: block scores by average pooling of a sensitivity matrix (either sign), then the top blocks."""
+    import torch
+
+    rng = np.random.default_rng(9950 + b + rows)
+    S = (rng.standard_normal((rows, cols)) * 1e-3).astype(np.float32)  # block means of either sign
+    want, gap = orc.pooled_topk_mask(S, b, s)
+    assert gap > 1e-9, "selection hangs on rounding: reseed"
+    m = api.pooled_topk_mask(torch.from_numpy(S).to("cuda:0"), b, s)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy(), want)
+    if 0.0 < s < 1.0:
+        sc = orc.pooled_scores(S, b)
+        assert (sc[want == 1] < 0).any() or (sc[want == 0] < 0).any()  # negative scores took part in the ranking
+
+
+def test_pooled_topk_mask_ties_and_pack(api):
+    import torch
+
+    b, nbr, nbc = 32, 6, 10
+    rng = np.random.default_rng(9960)
+    # every block constant, values drawn from three levels (one negative, and a zero level): many exact ties
+    levels = np.array([-0.5, 0.0, 0.25], dtype=np.float32)
+    S = np.kron(levels[rng.integers(0, 3, size=(nbr, nbc))], np.ones((b, b), dtype=np.float32)).astype(np.float32)
+    for s in (0.2, 0.5, 0.8):
+        want, _ = orc.pooled_topk_mask(S, b, s)
+        m = api.pooled_topk_mask(torch.from_numpy(S).to("cuda:0"), b, s)
+        torch.cuda.synchronize()
+        assert np.array_equal(m.cpu().numpy(), want), s
+    # the mask drives the packer like any other
+    W = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.05)
+    dev = api.bsr_pack(to_dev(W), b, mask=m)
+    ref = orc.pack(W, b, want)
+    torch.cuda.synchronize()
+    assert dev.nnz == ref.nnz and np.array_equal(dev.col_idx.cpu().numpy()[: ref.nnz], ref.col_idx)
