@@ -376,3 +376,71 @@ void oracle_pooled_scores(const float* S, int64_t lds, int64_t rows, int64_t col
       score[br * nbc + bc] = s / ((double)b * (double)b);
     }
 }
+
+/* ---- 8-bit floating point (the paper runs its kernel in float8_e5m2 as well: Sec. 5.1) ----
+ * E5M2: 1 sign bit, 5 exponent bits (bias 15), 2 mantissa bits; subnormals, infinities and NaN as in IEEE
+ * half precision, of which it is the upper byte.  Largest finite value 1.75 * 2^15 = 57344, smallest
+ * subnormal 2^-16. */
+
+/* Exact value of a code. */
+double oracle_e5m2_to_f64(uint8_t c) {
+  int sign = c >> 7, e = (c >> 2) & 31, m = c & 3;
+  double v;
+  if (e == 31) v = m ? NAN : INFINITY;
+  else if (e == 0) v = ldexp((double)m, -16);            /* subnormal: m * 2^-14 * 2^-2 */
+  else v = ldexp(1.0 + (double)m / 4.0, e - 15);
+  return sign ? -v : v;
+}
+
+/* Round to nearest, ties to the code with an even mantissa; magnitudes that round past the largest finite
+ * value become infinity (IEEE rounding).  Written on the value, not on bit patterns: scale so that the
+ * spacing of representable numbers around |x| is 1, round to an integer with ties to even, rebuild. */
+uint8_t oracle_f64_to_e5m2(double x) {
+  uint8_t sign = (uint8_t)(signbit(x) ? 0x80 : 0);
+  if (isnan(x)) return (uint8_t)(sign | 0x7E);
+  double a = fabs(x);
+  if (isinf(a)) return (uint8_t)(sign | 0x7C);
+  if (a == 0.0) return sign;
+  int ex;
+  frexp(a, &ex);            /* a = f * 2^ex, f in [0.5, 1)  ->  a in [2^(ex-1), 2^ex) */
+  int e = ex - 1;           /* unbiased exponent of a */
+  if (e < -14) e = -14;     /* subnormal range shares the spacing of the lowest normal binade */
+  double q = ldexp(a, 2 - e);                 /* spacing 2^(e-2) -> 1 */
+  double r = nearbyint(q);                    /* default rounding mode: to nearest, ties to even */
+  /* r in [0, 8]; r = 8 means the value rounded up into the next binade */
+  int64_t n = (int64_t)r;
+  int biased = e + 15;                        /* >= 1 */
+  if (n < 4) {                                /* subnormal (only possible when e == -14) */
+    return (uint8_t)(sign | (uint8_t)n);
+  }
+  if (n == 8) { n = 4; biased += 1; }
+  if (biased >= 31) return (uint8_t)(sign | 0x7C);
+  return (uint8_t)(sign | (biased << 2) | (n - 4));
+}
+
+void oracle_quantize_e5m2(const float* x, int64_t n, uint8_t* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = oracle_f64_to_e5m2((double)x[i]);
+}
+
+/* Y = W~ X with both operands in E5M2: the dense masked product of the decoded values, fp64.  vals8 holds the
+ * stored blocks like the bf16 format does ([nnz][b][b], row-major), one byte per value; X element (k,t) lives
+ * at X8[k*sxk + t*sxt]. */
+void oracle_spmm_e5m2(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr, const int32_t* col_idx,
+                      const uint8_t* vals8, const uint8_t* X8, int64_t sxk, int64_t sxt, int64_t T,
+                      double* Y /* [rows][T] */) {
+  int64_t nbr = rows / b;
+  double* Wd = (double*)calloc((size_t)(rows * cols > 0 ? rows * cols : 1), sizeof(double));
+  for (int64_t br = 0; br < nbr; ++br)
+    for (int64_t k = row_ptr[br]; k < row_ptr[br + 1]; ++k)
+      for (int32_t i = 0; i < b; ++i)
+        for (int32_t j = 0; j < b; ++j)
+          Wd[(br * b + i) * cols + (int64_t)col_idx[k] * b + j] = oracle_e5m2_to_f64(vals8[(k * b + i) * b + j]);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t t = 0; t < T; ++t) {
+      double s = 0.0;
+      for (int64_t k = 0; k < cols; ++k) s += Wd[i * cols + k] * oracle_e5m2_to_f64(X8[k * sxk + t * sxt]);
+      Y[i * T + t] = s;
+    }
+  free(Wd);
+}

@@ -54,6 +54,14 @@ def lib():
         L.oracle_sparsity_schedule.argtypes = [i64, i64, i64, dbl, dbl]
         L.oracle_pooled_scores.restype = None
         L.oracle_pooled_scores.argtypes = [vp, i64, i64, i64, i32, vp]
+        L.oracle_e5m2_to_f64.restype = dbl
+        L.oracle_e5m2_to_f64.argtypes = [C.c_uint8]
+        L.oracle_f64_to_e5m2.restype = C.c_uint8
+        L.oracle_f64_to_e5m2.argtypes = [dbl]
+        L.oracle_quantize_e5m2.restype = None
+        L.oracle_quantize_e5m2.argtypes = [vp, i64, vp]
+        L.oracle_spmm_e5m2.restype = None
+        L.oracle_spmm_e5m2.argtypes = [i64, i64, i32, vp, vp, vp, vp, i64, i64, i64, vp]
         L.oracle_mlp2.restype = None
         L.oracle_mlp2.argtypes = [i64, i64, i32] + [vp] * 6 + [vp, i64, i64, i64, i32, vp, vp]
         _lib = L
@@ -241,3 +249,35 @@ def pooled_topk_mask(S: np.ndarray, b: int, sparsity: float) -> Tuple[np.ndarray
     sc = pooled_scores(S, b)
     mask, gap = topk_mask(sc, sparsity)
     return mask.reshape(sc.shape), gap
+
+
+def e5m2_decode(codes: np.ndarray) -> np.ndarray:
+    """Exact fp64 values of E5M2 codes (any shape)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    f = lib().oracle_e5m2_to_f64
+    return np.array([f(int(c)) for c in range(256)], dtype=np.float64)[codes]
+
+
+def e5m2_quantize(x: np.ndarray) -> np.ndarray:
+    """fp32 values -> E5M2 codes, round to nearest even, overflow to infinity (Sec. 5.1 dtype)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint8)
+    lib().oracle_quantize_e5m2(_p(x), x.size, _p(out))
+    return out
+
+
+def spmm_e5m2(w: Bsr, vals8: np.ndarray, X8: np.ndarray, layout: str = "token_major") -> np.ndarray:
+    """Y = W~ X with E5M2 block values `vals8` [nnz, b, b] on the structure of `w` and E5M2 activations: fp64 [rows, T]."""
+    vals8 = np.ascontiguousarray(vals8, dtype=np.uint8)
+    X8 = np.ascontiguousarray(X8, dtype=np.uint8)
+    assert vals8.shape == (w.nnz, w.b, w.b) and X8.ndim == 2
+    if layout == "token_major":
+        T, K = X8.shape
+        sxk, sxt = 1, K
+    else:
+        K, T = X8.shape
+        sxk, sxt = T, 1
+    assert K == w.cols
+    Y = np.zeros((w.rows, T), dtype=np.float64)
+    lib().oracle_spmm_e5m2(w.rows, w.cols, w.b, _p(w.row_ptr), _p(w.col_idx), _p(vals8), _p(X8), sxk, sxt, T, _p(Y))
+    return Y
