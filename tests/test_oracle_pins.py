@@ -655,3 +655,75 @@ def test_pooled_topk_mask_ranking_and_ties():
     # all blocks equal: the lowest indices survive
     m_eq, gap_eq = orc.pooled_topk_mask(np.full((M, K), -1.25, dtype=np.float32), b, s)
     assert np.array_equal(np.nonzero(m_eq.ravel())[0], np.arange(n_keep)) and gap_eq == 0.0
+
+
+# ---- E5M2 (the 8-bit floating-point type of Sec. 5.1) ----
+
+def test_e5m2_known_codes_and_roundtrip():
+    dec = orc.e5m2_decode(np.arange(256, dtype=np.uint8))
+    # format facts: bias 15, 2 mantissa bits, IEEE-style subnormals / inf / nan
+    table = {0x00: 0.0, 0x01: 2.0 ** -16, 0x03: 3 * 2.0 ** -16, 0x04: 2.0 ** -14, 0x38: 0.5, 0x3C: 1.0, 0x3D: 1.25,
+             0x3E: 1.5, 0x3F: 1.75, 0x40: 2.0, 0xC0: -2.0, 0x7B: 57344.0, 0xFB: -57344.0}
+    for code, val in table.items():
+        assert dec[code] == val, hex(code)
+    assert np.isinf(dec[0x7C]) and dec[0x7C] > 0 and np.isinf(dec[0xFC]) and dec[0xFC] < 0 and np.isnan(dec[0x7D])
+    # E5M2 is the upper byte of IEEE half precision
+    half = (np.arange(256, dtype=np.uint16) << 8).view(np.float16).astype(np.float64)
+    fin = np.isfinite(half)
+    assert np.array_equal(dec[fin], half[fin])
+    # every finite code encodes to itself; positive codes are strictly increasing
+    fin_codes = np.nonzero(np.isfinite(dec))[0].astype(np.uint8)
+    assert np.array_equal(orc.e5m2_quantize(dec[fin_codes].astype(np.float32)), fin_codes)
+    assert np.all(np.diff(dec[:0x7C]) > 0)
+
+
+def test_e5m2_rounding_is_nearest_even_against_enumeration():
+    dec = orc.e5m2_decode(np.arange(256, dtype=np.uint8))
+    pos = [(Fraction(float(dec[c])), c) for c in range(0x7C)]  # finite non-negative codes, ascending
+    rng = np.random.default_rng(71)
+    xs = np.concatenate([
+        rng.standard_normal(4000).astype(np.float32) * np.float32(0.02),       # weights: deep in the subnormal range too
+        rng.standard_normal(2000).astype(np.float32),
+        (rng.standard_normal(500) * 2e4).astype(np.float32),
+        np.array([1.125, 1.375, 1.625, 1.875, 2.0 ** -17, 3 * 2.0 ** -17, 5 * 2.0 ** -17, 7 * 2.0 ** -17,  # exact ties
+                  2.0 ** -18, 61439.0, 57344.0, 59392.0, 0.0, -0.0], dtype=np.float32)])
+    got = orc.e5m2_quantize(xs)
+    for x, g in zip(xs.tolist(), got.tolist()):
+        a = abs(Fraction(x))
+        sign = 0x80 if math.copysign(1.0, x) < 0 else 0
+        # nearest representable magnitude by exhaustive search; ties -> even mantissa (even code)
+        best = min(pos, key=lambda vc: (abs(vc[0] - a), vc[1] & 1))
+        if a >= Fraction(61440):   # halfway between the largest finite value and 2^16: rounds to infinity
+            want = sign | 0x7C
+        else:
+            want = sign | best[1]
+        assert g == want, (x, hex(g), hex(want))
+    # the listed ties, spelled out
+    assert orc.e5m2_quantize(np.array([1.125, 1.375, 2.0 ** -17, 3 * 2.0 ** -17], dtype=np.float32)).tolist() == [0x3C, 0x3E, 0x00, 0x02]
+    assert orc.e5m2_quantize(np.array([61439.0, 61440.0, 1e9], dtype=np.float32)).tolist() == [0x7B, 0x7C, 0x7C]
+
+
+def test_spmm_e5m2_equals_numpy_on_decoded_values():
+    rng = np.random.default_rng(72)
+    M, K, b, T = 64, 96, 16, 7
+    W = synth.gauss_bf16(rng, (M, K), 0.3)
+    mask = synth.uniform_mask(rng, M // b, K // b, 0.5)
+    mask[1, :] = 0
+    p = orc.pack(W, b, mask)
+    vals8 = orc.e5m2_quantize(f64(p.vals).astype(np.float32))
+    X8 = orc.e5m2_quantize(rng.standard_normal((T, K)).astype(np.float32))
+    Y = orc.spmm_e5m2(p, vals8, X8)
+    # dense reference from decoded values scattered by the index arrays
+    Wd = np.zeros((M, K))
+    rr = np.repeat(np.arange(M // b), np.diff(p.row_ptr))
+    for q in range(p.nnz):
+        Wd[rr[q] * b:(rr[q] + 1) * b, p.col_idx[q] * b:(p.col_idx[q] + 1) * b] = orc.e5m2_decode(vals8[q])
+    np.testing.assert_allclose(Y, Wd @ orc.e5m2_decode(X8).T, rtol=1e-12, atol=1e-15)
+    assert not Y[b:2 * b].any()
+    assert np.array_equal(Y, orc.spmm_e5m2(p, vals8, np.ascontiguousarray(X8.T), layout="feature_major"))
+    # values that are exact in E5M2 (small powers of two and their multiples): same numbers as the bf16 product
+    Wp = synth.f32_to_bf16_bits(rng.choice([-2.0, -1.0, -0.5, 0.0, 0.5, 1.0, 1.5], size=(M, K)).astype(np.float32))
+    Xp = rng.choice([-1.0, 0.25, 0.5, 1.0, 3.0], size=(T, K)).astype(np.float32)
+    pp = orc.pack(Wp, b, mask)
+    assert np.array_equal(orc.spmm_e5m2(pp, orc.e5m2_quantize(f64(pp.vals).astype(np.float32)), orc.e5m2_quantize(Xp)),
+                          orc.spmm(pp, synth.f32_to_bf16_bits(Xp)))
