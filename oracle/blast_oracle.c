@@ -377,7 +377,7 @@ void oracle_pooled_scores(const float* S, int64_t lds, int64_t rows, int64_t col
     }
 }
 
-/* ---- 8-bit floating point (the paper runs its kernel in float8_e5m2 as well: Sec. 5.1) ----
+/* ---- 8-bit floating point (the paper runs its kernel in float8_e5m2 as well: Sec. 5.2) ----
  * E5M2: 1 sign bit, 5 exponent bits (bias 15), 2 mantissa bits; subnormals, infinities and NaN as in IEEE
  * half precision, of which it is the upper byte.  Largest finite value 1.75 * 2^15 = 57344, smallest
  * subnormal 2^-16. */

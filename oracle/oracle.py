@@ -259,7 +259,7 @@ def e5m2_decode(codes: np.ndarray) -> np.ndarray:
 
 
 def e5m2_quantize(x: np.ndarray) -> np.ndarray:
-    """fp32 values -> E5M2 codes, round to nearest even, overflow to infinity (Sec. 5.1 dtype)."""
+    """fp32 values -> E5M2 codes, round to nearest even, overflow to infinity (Sec. 5.2 dtype)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     out = np.empty(x.shape, dtype=np.uint8)
     lib().oracle_quantize_e5m2(_p(x), x.size, _p(out))

@@ -536,7 +536,7 @@ def test_mlp2_under_graph_capture(api, T):
 
 
 def test_mlp2_topk_packed_gpt2_shape(api):
-    """E = 768, I = 3072 (a GPT-2-small MLP block, Sec. 5.2), packed on the device by block norm at 90 %."""
+    """E = 768, I = 3072 (a GPT-2-small MLP block, one of the models of Sec. 4), packed on the device by block norm at 90 %."""
     import torch
 
     rng = np.random.default_rng(8500)

@@ -657,7 +657,7 @@ def test_pooled_topk_mask_ranking_and_ties():
     assert np.array_equal(np.nonzero(m_eq.ravel())[0], np.arange(n_keep)) and gap_eq == 0.0
 
 
-# ---- E5M2 (the 8-bit floating-point type of Sec. 5.1) ----
+# ---- E5M2 (the 8-bit floating-point type of Sec. 5.2) ----
 
 def test_e5m2_known_codes_and_roundtrip():
     dec = orc.e5m2_decode(np.arange(256, dtype=np.uint8))
