@@ -178,6 +178,29 @@ int blast_pooled_topk_mask(const float* S, int64_t lds, int64_t rows, int64_t co
 size_t blast_pooled_topk_mask_workspace(int64_t rows, int64_t cols, int32_t b);
 
 /*
+ * E5M2 (8-bit floating point; Sec. 5.2 reports the kernel in float8_e5m2 next to the 16-bit types).
+ * E5M2 = 1 sign, 5 exponent (bias 15), 2 mantissa bits, subnormals / infinities / NaN as in IEEE half
+ * precision, of which a code is the upper byte.
+ *
+ * blast_quantize_e5m2: out[i] = E5M2(in[i]) for bf16 input, round to nearest with ties to the even
+ * mantissa, magnitudes of 61440 and above become infinity.  Serves the block values of a packed matrix
+ * (W->vals, nnz*b*b values: the structure arrays are shared with the bf16 form) and activations alike.
+ * Never synchronises.  Errors: INVALID_ARG, HIP.
+ *
+ * blast_bsr_spmm_e5m2: Y = W~ X as in blast_bsr_spmm with both operands in E5M2 and fp32 accumulation.
+ *   W          structure of the packed matrix (row_ptr, col_idx, row_order, nnz, b; W->vals is not read)
+ *   vals8      E5M2 block values, [W->nnz][b][b], one byte each, same order as W->vals
+ *   X8, ldx    E5M2 activations, [T][cols] (token-major) or [cols][T], row pitch ldx bytes
+ *   Y, ldy     as in blast_bsr_spmm (fp32 or bf16, same layout as X8)
+ * The tuned kernel needs b >= 64, token-major operands, 16-byte aligned pointers and ldx % 16 == 0; other
+ * cases take a plain kernel.  Never synchronises, allocates nothing.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, HIP.
+ */
+int blast_quantize_e5m2(const uint16_t* in_bf16, int64_t n, uint8_t* out, void* stream);
+int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8, const uint8_t* X8, int64_t ldx, int32_t x_layout,
+                        int64_t T, void* Y, int64_t ldy, int32_t y_dtype, void* stream);
+
+/*
  * Packed transpose.  Sec. 3.2: the pruned matrix is the one used in forward AND backward propagation;
  * Sec. 3.4 / 3.4.1: which compressed format suits depends on the side the sparse matrix is multiplied
  * from, and the kernel for the other side is the symmetric one.  This call builds, from a packed W~

@@ -26,7 +26,7 @@ EXPORTS = (
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
     "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm",
     "blast_generate_masks", "blast_generate_masks_workspace", "blast_sparsity_schedule",
-    "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
+    "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_quantize_e5m2", "blast_bsr_spmm_e5m2", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
 
@@ -91,6 +91,10 @@ def lib():
         L.blast_pooled_topk_mask.argtypes = [vp, i64, i64, i64, i32, C.c_double, vp, vp, sz, vp]
         L.blast_pooled_topk_mask_workspace.restype = sz
         L.blast_pooled_topk_mask_workspace.argtypes = [i64, i64, i32]
+        L.blast_quantize_e5m2.restype = C.c_int
+        L.blast_quantize_e5m2.argtypes = [vp, i64, vp, vp]
+        L.blast_bsr_spmm_e5m2.restype = C.c_int
+        L.blast_bsr_spmm_e5m2.argtypes = [pv, vp, vp, i64, i32, i64, vp, i64, i32, vp]
         L.blast_bsr_transpose.restype = C.c_int
         L.blast_bsr_transpose.argtypes = [pv, vp, vp, vp, vp, vp, sz, C.POINTER(C.c_int32), vp]
         L.blast_bsr_sddmm.restype = C.c_int
@@ -229,6 +233,31 @@ def pooled_topk_mask(S: torch.Tensor, b: int, sparsity: float) -> torch.Tensor:
 def sparsity_schedule(i: int, m: int, d: int, s_init: float, s_max: float) -> float:
     """blast_sparsity_schedule: Eq. (2)."""
     return float(lib().blast_sparsity_schedule(int(i), int(m), int(d), float(s_init), float(s_max)))
+
+
+def quantize_e5m2(x: torch.Tensor) -> torch.Tensor:
+    """blast_quantize_e5m2: bf16 (or int16 bit patterns) tensor -> uint8 E5M2 codes of the same shape."""
+    assert x.is_cuda and x.is_contiguous() and x.element_size() == 2
+    out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _check(lib().blast_quantize_e5m2(_ptr(x), x.numel(), _ptr(out), _stream()), "blast_quantize_e5m2")
+    return out
+
+
+def bsr_spmm_e5m2(W: PackedBsr, vals8: torch.Tensor, X8: torch.Tensor, *, layout: int = TOKEN_MAJOR,
+                  out_dtype: torch.dtype = torch.float32, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_bsr_spmm_e5m2: Y = W * X with E5M2 block values `vals8` (quantize_e5m2(W.vals)) and E5M2 activations."""
+    assert X8.is_cuda and X8.dim() == 2 and X8.stride(1) == 1 and X8.dtype == torch.uint8
+    assert vals8.dtype == torch.uint8 and vals8.numel() >= W.nnz * W.b * W.b
+    if layout == TOKEN_MAJOR:
+        T, K = X8.shape
+    else:
+        K, T = X8.shape
+    assert K == W.cols
+    Y = out if out is not None else _alloc_out(W.rows, T, layout, out_dtype, X8.device)
+    v = W.view()
+    _check(lib().blast_bsr_spmm_e5m2(C.byref(v), _ptr(vals8), _ptr(X8), X8.stride(0), layout, T, _ptr(Y), Y.stride(0),
+                                     BF16 if Y.dtype == torch.bfloat16 else F32, _stream()), "blast_bsr_spmm_e5m2")
+    return Y
 
 
 def bsr_transpose(W: PackedBsr) -> PackedBsr:

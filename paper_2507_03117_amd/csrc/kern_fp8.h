@@ -1,0 +1,294 @@
+// Block-sparse product with both operands in E5M2 (8-bit floating point: the second data type the paper
+// runs its kernel in, BLaST Sec. 5.2): Y = W~ X, fp32 accumulation.
+//
+// Same loop as the bf16 product (Sec. 3.4: every output tile walks the stored blocks of its block row),
+// organised like the stored-block-gradient kernel: a wave accumulates a 64-token x 64-row tile (2 x 2
+// register blocking of 32x32x16 matrix instructions) from a private ring of LDS stages filled by LDS-DMA
+// copies; there is no barrier in the loop, the wave's memory counter is the only synchronisation.
+//  - A stage is a 32-deep contraction slice: 64 weight rows x 32 bytes and 64 tokens x 32 bytes, 2 KiB each.
+//  - A lane reads one 16-byte chunk per operand row (16 contraction indices) and feeds its two halves to
+//    two matrix instructions; lanes 0-31 take the first chunk of a row, lanes 32-63 the second.  Both
+//    operands use the same assignment, so every contraction index meets its partner exactly once.
+//  - The two chunks of a row are swapped in LDS for rows 4-7 of every 8 (on the global-address side of the
+//    copy): the eight rows one read cycle touches then cover all banks.
+// One byte per value halves every byte count of the bf16 kernels (HBM, L2 -> LDS, LDS -> registers) per
+// multiply-add, which is what bounds them.
+//  - KSPLIT = false (many tokens): a workgroup owns (block row, 64-row sub-block, 256 tokens), one 64-token
+//    tile per wave; the four waves read the same weight tiles (L1 hits).
+//  - KSPLIT = true (up to a few token tiles): a workgroup owns (block row, sub-block, 64 tokens) and its
+//    four waves deal the stages among themselves; the partial sums are added in LDS in a fixed order.
+#pragma once
+#include "kern_common.h"
+#include "kern_stream.h"
+
+namespace blast_dev {
+
+struct Fp8Args {
+  const int* row_ptr;
+  const int* col_idx;
+  const int* row_order;  // may be null
+  const uint8_t* vals;   // [nnz][b][b] E5M2
+  const uint8_t* X;      // token-major [T][cols] E5M2, row pitch ldx bytes (multiple of 16)
+  int64_t ldx;
+  void* Y;               // token-major [T][rows], row pitch ldy elements
+  int64_t ldy;
+  int y_bf16;
+  int T;
+  int n_units;           // (block rows) * SUB
+  int groups;            // token groups per unit (256 tokens each without KSPLIT, 64 with)
+};
+
+template <int B>
+struct Fp8Cfg {
+  static_assert(B == 64 || B == 128, "blocks of at least 64 x 64");
+  static constexpr int SB = 64;               // weight rows (and tokens) of a wave's tile
+  static constexpr int SUB = B / SB;          // sub-blocks of rows per block row
+  static constexpr int KS = 32;               // contraction depth of a stage, = bytes of a tile row
+  static constexpr int KSL = B / KS;          // stages per stored block
+  static constexpr int TILE = SB * KS;        // 2 KiB
+  static constexpr int NI = TILE / 1024;      // wave-wide copy instructions per tile
+  static constexpr int OPS = 2 * NI;
+  static constexpr int STAGE = 2 * TILE;
+  static constexpr int NSTAGE = 4;
+  static constexpr int WAVE_LDS = NSTAGE * STAGE;
+  static constexpr size_t LDS_BYTES = 4 * (size_t)WAVE_LDS;  // 64 KiB: two workgroups per CU
+  __device__ static __forceinline__ int key(int row) { return (row >> 2) & 1; }
+};
+
+__device__ __forceinline__ void fp8_wait_vm(int outstanding) {
+  switch (outstanding) {
+    case 0: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0)); break;
+    case 4: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(4)); break;
+    case 8: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(8)); break;
+    case 12: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(12)); break;
+    default: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0)); break;  // more than needed is always safe
+  }
+}
+
+typedef long i64x2 __attribute__((ext_vector_type(2)));
+
+template <int B, bool KSPLIT>
+__global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
+  using C = Fp8Cfg<B>;
+  constexpr int NI = C::NI, NSTAGE = C::NSTAGE;
+  static_assert(C::OPS == 4, "fp8_wait_vm lists multiples of four");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  // Workgroup ids are dealt round-robin to the 8 XCDs: the token groups of one unit are given ids 8 apart,
+  // so they run on one XCD and the re-reads of the unit's weight tiles hit its L2.
+  const int blk = blockIdx.x, span = 8 * a.groups;
+  const int rem = blk % span;
+  const int unit = (blk / span) * 8 + (rem & 7);
+  if (unit >= a.n_units) return;  // whole workgroup, before any barrier
+  const int tg = rem >> 3;
+  const int rank = unit / C::SUB, si = unit % C::SUB;
+  const int r = a.row_order ? ld_idx(a.row_order, rank) : rank;
+  const int kb = ld_idx(a.row_ptr, r);
+  const int row_stages = (ld_idx(a.row_ptr, r + 1) - kb) * C::KSL;
+  // first token of this wave's tile; which stages of the row it walks
+  const int t0 = KSPLIT ? tg * C::SB : (tg * 4 + wave) * C::SB;
+  const int first = KSPLIT ? wave : 0, step = KSPLIT ? 4 : 1;
+  int n_stage = row_stages > first ? (row_stages - first + step - 1) / step : 0;
+  if (t0 >= a.T) {
+    if (!KSPLIT) return;  // a wave without tokens (no barrier in this mode)
+    n_stage = 0;
+  }
+  unsigned char* ring = smem + wave * C::WAVE_LDS;
+
+  // ---- per-lane constants -----------------------------------------------------------------------
+  // Copy side: instruction ni of a tile writes LDS bytes [ni*1024 + lane*16, +16) = position p = ni*64 + lane
+  // in 16-byte units = (tile row p / 2, slot p % 2); it fetches chunk slot ^ key(row) of that row.
+  uint32_t woff[NI], xoff[NI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) {
+    const int p = ni * 64 + lane, row = p >> 1, chunk = (p & 1) ^ C::key(row);
+    woff[ni] = (uint32_t)((si * C::SB + row) * B + chunk * 16);
+    int t = t0 + row;
+    t = t < a.T ? t : a.T - 1;  // rows past the last token re-read it; their results are never stored
+    t = t < 0 ? 0 : t;
+    xoff[ni] = (uint32_t)t * (uint32_t)a.ldx + (uint32_t)(chunk * 16);
+  }
+  // Fragment side: lane l reads the 16-byte chunk l / 32 of tile row 32 h + l % 32.
+  uint32_t foff[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int row = 32 * h + (lane & 31);
+    foff[h] = (uint32_t)(row * C::KS + (((lane >> 5) ^ C::key(row)) << 4));
+  }
+
+  f32x16 acc[2][2];  // [token half][row half]
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][nj][v] = 0.0f;
+
+  auto issue = [&](int s) {
+    const int gs = first + step * s;          // stage of the row: stored block gs / KSL, slice gs % KSL
+    const int q = kb + gs / C::KSL, ks = gs % C::KSL;
+    const int col = ld_idx(a.col_idx, q);
+    unsigned char* slot = ring + (s % NSTAGE) * C::STAGE;
+    const unsigned char* wsrc = a.vals + (int64_t)q * (B * B) + ks * C::KS;
+    const unsigned char* xsrc = a.X + (int64_t)col * B + ks * C::KS;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) BLAST_GLDS16(wsrc + woff[ni], slot + ni * 1024);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) BLAST_GLDS16(xsrc + xoff[ni], slot + C::TILE + ni * 1024);
+  };
+
+#pragma unroll 1
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < n_stage) issue(s);
+
+#pragma unroll 1
+  for (int s = 0; s < n_stage; ++s) {
+    // fragment reads of the previous stage have returned before its slot is handed back to the copier
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    if (s + NSTAGE - 1 < n_stage) issue(s + NSTAGE - 1);
+    // copies retire in issue order: "at most (stages issued after s) * OPS outstanding" = stage s has landed
+    const int later = (n_stage - 1 - s) < (NSTAGE - 1) ? (n_stage - 1 - s) : (NSTAGE - 1);
+    fp8_wait_vm(later * C::OPS);
+    asm volatile("" ::: "memory");
+    const unsigned char* slot = ring + (s % NSTAGE) * C::STAGE;
+    i64x2 fw[2], fx[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      fw[h] = *reinterpret_cast<const i64x2*>(slot + foff[h]);
+      fx[h] = *reinterpret_cast<const i64x2*>(slot + C::TILE + foff[h]);
+    }
+    // D[m][n] += sum_k A[m][k] B[k][n]: m = token, n = weight row; two instructions per 16-byte chunk
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj)
+          acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf8_bf8(fx[mi][e], fw[nj][e], acc[mi][nj], 0, 0, 0);
+    asm volatile("" ::: "memory");
+  }
+
+  // Result layout of a 32x32 tile: lane -> weight row n = lane % 32, register v -> token
+  // m = 8*(v/4) + 4*(lane/32) + v%4: a store instruction writes 32 consecutive rows of two tokens.
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int64_t row0 = (int64_t)r * B + si * C::SB;
+  auto store = [&](int mi, int nj, int v, float val) {
+    const int t = t0 + 32 * mi + 8 * (v >> 2) + 4 * lh + (v & 3);
+    if (t < a.T) {
+      const int64_t off = (int64_t)t * a.ldy + row0 + 32 * nj + l32;
+      if (a.y_bf16)
+        reinterpret_cast<uint16_t*>(a.Y)[off] = f32_to_bf16_rne(val);
+      else
+        reinterpret_cast<float*>(a.Y)[off] = val;
+    }
+  };
+  if (!KSPLIT) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) store(mi, nj, v, acc[mi][nj][v]);
+  } else {
+    // the four partial sums meet in LDS (the rings are free once every wave has left its loop); wave w then
+    // owns accumulator tile w: adds the four copies in a fixed order and stores
+    float (*red)[64][64] = reinterpret_cast<float (*)[64][64]>(smem);
+    static_assert(sizeof(float) * 4 * 64 * 64 <= C::LDS_BYTES, "the reduction reuses the ring memory");
+    __syncthreads();
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][(mi * 2 + nj) * 16 + v][lane] = acc[mi][nj][v];
+    __syncthreads();
+    const int mi = wave >> 1, nj = wave & 1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int id = wave * 16 + v;
+      store(mi, nj, v, ((red[0][id][lane] + red[1][id][lane]) + red[2][id][lane]) + red[3][id][lane]);
+    }
+  }
+}
+
+// Exact widening of an E5M2 code: it is the upper byte of an IEEE half.
+__device__ __forceinline__ float e5m2_to_f32(uint8_t c) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)((uint16_t)c << 8));
+}
+
+// Any block size, any strides: one workgroup per (block row, 64 tokens), plain fp32 multiply-adds from
+// global memory.  Serves b = 16 / 32, feature-major or unaligned operands.
+struct Fp8GenericArgs {
+  const int* row_ptr;
+  const int* col_idx;
+  const uint8_t* vals;
+  const uint8_t* X;
+  int64_t sxk, sxt;  // byte strides of X along features / tokens
+  void* Y;
+  int64_t syt, syi;  // element strides of Y along tokens / rows
+  int y_bf16;
+  int T, b;
+};
+
+__global__ __launch_bounds__(256) void k_spmm_fp8_generic(const Fp8GenericArgs a) {
+  const int r = blockIdx.x, t_base = blockIdx.y * 64;
+  const int b = a.b;
+  const int kb = a.row_ptr[r], ke = a.row_ptr[r + 1];
+  for (int idx = threadIdx.x; idx < b * 64; idx += blockDim.x) {
+    const int i = idx / 64, t = t_base + idx % 64;
+    if (t >= a.T) continue;
+    float s = 0.0f;
+    for (int q = kb; q < ke; ++q) {
+      const uint8_t* w = a.vals + ((int64_t)q * b + i) * b;
+      const uint8_t* x = a.X + (int64_t)a.col_idx[q] * b * a.sxk + (int64_t)t * a.sxt;
+      for (int j = 0; j < b; ++j) s = __builtin_fmaf(e5m2_to_f32(w[j]), e5m2_to_f32(x[(int64_t)j * a.sxk]), s);
+    }
+    const int64_t off = (int64_t)t * a.syt + ((int64_t)r * b + i) * a.syi;
+    if (a.y_bf16)
+      reinterpret_cast<uint16_t*>(a.Y)[off] = f32_to_bf16_rne(s);
+    else
+      reinterpret_cast<float*>(a.Y)[off] = s;
+  }
+}
+
+// bf16 -> E5M2, round to nearest, ties to the even mantissa, overflow to infinity; integer arithmetic on
+// the bit patterns (no dependence on a conversion instruction's rounding or saturation mode).
+__device__ __forceinline__ uint8_t bf16_to_e5m2(uint16_t h) {
+  const uint32_t sign = (h >> 8) & 0x80u;
+  const int e8 = (h >> 7) & 0xFF;
+  const uint32_t m7 = h & 0x7Fu;
+  if (e8 == 0xFF) return (uint8_t)(sign | (m7 ? 0x7Eu : 0x7Cu));  // nan / inf
+  if (e8 == 0) return (uint8_t)sign;                               // zero and bf16 subnormals (below 2^-126)
+  const int E = e8 - 127;
+  if (E >= -14) {
+    // normal: keep 2 of the 7 mantissa bits
+    uint32_t q = m7 >> 5;
+    const uint32_t rem = m7 & 31u;
+    if (rem > 16u || (rem == 16u && (q & 1u))) ++q;
+    int biased = E + 15;
+    if (q == 4u) {
+      q = 0u;
+      ++biased;
+    }
+    if (biased >= 31) return (uint8_t)(sign | 0x7Cu);
+    return (uint8_t)(sign | ((uint32_t)biased << 2) | q);
+  }
+  // subnormal target: the value in units of 2^-16 is (128 + m7) * 2^(E + 9), with E + 9 <= -6
+  const int sh = -(E + 9);
+  if (sh > 9) return (uint8_t)sign;  // below a quarter of the smallest subnormal
+  const uint32_t sig = 128u + m7;
+  uint32_t n = sig >> sh;
+  const uint32_t rem = sig & ((1u << sh) - 1u), half = 1u << (sh - 1);
+  if (rem > half || (rem == half && (n & 1u))) ++n;
+  return (uint8_t)(sign | n);  // n = 4 is the smallest normal: the carry is the right code
+}
+
+__global__ __launch_bounds__(256) void k_quantize_e5m2(const uint16_t* __restrict__ in, int64_t n,
+                                                       uint8_t* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = bf16_to_e5m2(in[i]);
+}
+
+}  // namespace blast_dev

@@ -116,6 +116,14 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     assert L.blast_pooled_topk_mask(None, 128, 128, 128, 64, 0.5, None, None, 0, None) == -1
     assert L.blast_pooled_topk_mask(None, 128, 128, 100, 64, 0.5, None, None, 0, None) == -2
     assert L.blast_pooled_topk_mask_workspace(128, 128, 64) >= 4 * 8
+    # E5M2 entry points
+    assert L.blast_quantize_e5m2(None, -1, None, None) == -1
+    assert L.blast_quantize_e5m2(None, 0, None, None) == 0
+    assert L.blast_quantize_e5m2(None, 8, None, None) == -1
+    assert L.blast_bsr_spmm_e5m2(None, None, None, 128, 0, 4, None, 128, 0, None) == -1
+    assert L.blast_bsr_spmm_e5m2(C.byref(g), None, None, 128, 0, 4, None, 256, 0, None) == -1  # Y null
+    assert L.blast_bsr_spmm_e5m2(C.byref(g), None, None, 128, 0, 0, None, 256, 0, None) == 0   # T == 0
+    assert L.blast_bsr_spmm_e5m2(C.byref(bad48), None, None, 96, 0, 4, None, 96, 0, None) == -3
     # pack: null outputs / bad ld are rejected up front
     nnz = C.c_int64(0)
     assert L.blast_bsr_pack(None, 128, 128, 128, 64, 0, None, 0.0, None, None, None, None, None, 0, 4, C.byref(nnz), None, None, 0, None) == -1

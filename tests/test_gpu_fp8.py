@@ -1,0 +1,140 @@
+"""GPU parity of the E5M2 path (Sec. 5.2): the quantiser is bit-exact against the oracle's, the product matches
+the oracle's fp64 product of the same E5M2 codes within the tolerances of the 16-bit path."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2507_03117_amd import synth
+from tests.helpers import bits_of, check_close, mask_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    import torch
+
+    assert torch.cuda.is_available()
+    from paper_2507_03117_amd import api as _api
+
+    _api.lib()
+    return _api
+
+
+def _f32(bits):
+    return synth.bf16_bits_to_f32(bits)
+
+
+def test_quantize_every_bf16_pattern(api):
+    """All 65536 bf16 bit patterns: normals, subnormal targets, ties, overflow, infinities, NaN."""
+    import torch
+
+    allbits = np.arange(65536, dtype=np.uint16)
+    got = api.quantize_e5m2(to_dev(allbits)).cpu().numpy()
+    want = orc.e5m2_quantize(_f32(allbits))
+    nan = np.isnan(_f32(allbits))
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.all((got[nan] & 0x7C) == 0x7C) and np.all((got[nan] & 0x03) != 0)  # NaN stays NaN
+    torch.cuda.synchronize()
+
+
+def _case(api, rng, M, K, b, sparsity, T, w_std=0.05):
+    W = synth.gauss_bf16(rng, (M, K), w_std)
+    mask = synth.uniform_mask(rng, M // b, K // b, sparsity)
+    if M // b > 2:
+        mask[1, :] = 0
+    dev = api.bsr_pack(to_dev(W), b, mask=mask_dev(mask))
+    ref = orc.pack(W, b, mask)
+    x = synth.gauss_bf16(rng, (T, K), 1.0)
+    vals8 = api.quantize_e5m2(dev.vals[: max(dev.nnz, 1) * b * b].contiguous())
+    x8 = api.quantize_e5m2(to_dev(x))
+    v8_or = orc.e5m2_quantize(_f32(ref.vals))
+    x8_or = orc.e5m2_quantize(_f32(x))
+    assert np.array_equal(vals8.cpu().numpy()[: ref.nnz * b * b].reshape(ref.nnz, b, b), v8_or)
+    assert np.array_equal(x8.cpu().numpy(), x8_or)
+    return dev, ref, vals8, x8, v8_or, x8_or
+
+
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+@pytest.mark.parametrize("T", [1, 5, 64, 65, 128, 129, 300, 600])
+def test_spmm_e5m2_small(api, b, T):
+    import torch
+
+    rng = np.random.default_rng(9990 + b + T)
+    M, K = 6 * b, 4 * b
+    dev, ref, vals8, x8, v8_or, x8_or = _case(api, rng, M, K, b, 0.5, T)
+    y = api.bsr_spmm_e5m2(dev, vals8, x8, out=torch.full((T, M), float("nan"), device="cuda:0"))
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, orc.spmm_e5m2(ref, v8_or, x8_or), f"e5m2 b={b} T={T}")
+    assert not y.cpu().numpy()[:, b:2 * b].any()
+
+
+def test_spmm_e5m2_layouts_bf16_out_and_unaligned(api):
+    import torch
+
+    rng = np.random.default_rng(9995)
+    b, M, K, T = 64, 256, 192, 70
+    dev, ref, vals8, x8, v8_or, x8_or = _case(api, rng, M, K, b, 0.4, T)
+    want = orc.spmm_e5m2(ref, v8_or, x8_or)
+    yf = api.bsr_spmm_e5m2(dev, vals8, x8.t().contiguous(), layout=api.FEATURE_MAJOR)
+    torch.cuda.synchronize()
+    check_close(yf.cpu().numpy(), want, "e5m2 feature-major")
+    yb = api.bsr_spmm_e5m2(dev, vals8, x8, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    ybf = yb.float().cpu().numpy().T
+    assert np.all(np.abs(ybf - want) <= 2.0 ** -8 * np.abs(want) + 1e-2 * np.sqrt((want ** 2).mean()))
+    # a row pitch that is not a multiple of 16 bytes: plain kernel
+    big = torch.zeros((T, K + 5), dtype=torch.uint8, device="cuda:0")
+    big[:, :K] = x8
+    yu = api.bsr_spmm_e5m2(dev, vals8, big[:, :K])
+    torch.cuda.synchronize()
+    check_close(yu.cpu().numpy().T, want, "e5m2 unaligned")
+    # a pitch larger than the width, still aligned: tuned kernel
+    big2 = torch.zeros((T, K + 64), dtype=torch.uint8, device="cuda:0")
+    big2[:, :K] = x8
+    ys = api.bsr_spmm_e5m2(dev, vals8, big2[:, :K])
+    torch.cuda.synchronize()
+    check_close(ys.cpu().numpy().T, want, "e5m2 strided")
+
+
+def test_spmm_e5m2_exact_on_representable_data_and_dense_empty(api):
+    """Operands that are exact in E5M2 with integer-valued products: the device must match the oracle exactly,
+    whatever the order of the additions (covers the four-wave split and its reduction)."""
+    import torch
+
+    rng = np.random.default_rng(9996)
+    b, M, K = 64, 256, 1024
+    Wv = rng.choice([-2.0, -1.0, 0.0, 1.0, 2.0, 3.0], size=(M, K)).astype(np.float32)
+    W = synth.f32_to_bf16_bits(Wv)
+    for sparsity in (0.0, 0.7, 1.0):
+        mask = synth.uniform_mask(rng, M // b, K // b, sparsity)
+        dev = api.bsr_pack(to_dev(W), b, mask=mask_dev(mask))
+        ref = orc.pack(W, b, mask)
+        vals8 = api.quantize_e5m2(dev.vals[: max(dev.nnz, 1) * b * b].contiguous())
+        for T in (3, 100, 400):
+            x = synth.f32_to_bf16_bits(rng.choice([-1.0, 0.0, 1.0, 2.0], size=(T, K)).astype(np.float32))
+            y = api.bsr_spmm_e5m2(dev, vals8, api.quantize_e5m2(to_dev(x)))
+            torch.cuda.synchronize()
+            want = orc.spmm_e5m2(ref, orc.e5m2_quantize(_f32(ref.vals)), orc.e5m2_quantize(_f32(x)))
+            assert np.array_equal(y.cpu().numpy().T.astype(np.float64), want), (sparsity, T)
+
+
+def test_spmm_e5m2_llama1b_gate_full_size(api):
+    import torch
+
+    wl = synth.WORKLOADS["llama1b_b64_s90"]
+    lin = synth.make_mlp(wl).gate
+    b = wl.b
+    dev = api.bsr_pack(to_dev(lin.W), b, mask=mask_dev(lin.mask))
+    ref = orc.pack(lin.W, b, lin.mask)
+    vals8 = api.quantize_e5m2(dev.vals[: dev.nnz * b * b].contiguous())
+    v8_or = orc.e5m2_quantize(_f32(ref.vals))
+    assert np.array_equal(vals8.cpu().numpy().reshape(ref.nnz, b, b), v8_or)
+    for T in (1, 16, 2048):
+        x = synth.make_x(wl, T)
+        x8 = api.quantize_e5m2(to_dev(x))
+        y = api.bsr_spmm_e5m2(dev, vals8, x8)
+        torch.cuda.synchronize()
+        sel = np.arange(T) if T <= 64 else np.unique(np.concatenate(([0, T - 1], np.random.default_rng(T).choice(T, 46, replace=False))))
+        want = orc.spmm_e5m2(ref, v8_or, orc.e5m2_quantize(_f32(x[sel])))
+        check_close(y.cpu().numpy()[sel].T, want, f"e5m2 1B gate T={T}")
