@@ -319,6 +319,75 @@ def backward_products(workload: str, T: int, steps: int, warmup: int, cpu: bool)
     return out
 
 
+def e5m2_product(workload: str, tokens, steps: int, warmup: int, cpu: bool):
+    """The gate projection of the workload with both operands in E5M2 (Sec. 5.2 dtype) next to the bf16 product of
+    the same matrix, each timed between two hipEvents around `steps` launches; oracle timed on a token sample."""
+    import numpy as np
+    import torch
+
+    from paper_2507_03117_amd import api, synth
+    from tests.helpers import mask_dev, to_dev
+
+    wl = synth.WORKLOADS[workload]
+    lin = synth.make_mlp(wl).gate
+    b = wl.b
+    p = api.bsr_pack(to_dev(lin.W), b, mask=mask_dev(lin.mask)) if lin.mask is not None else \
+        api.bsr_pack(to_dev(lin.W), b, sparsity=lin.sparsity)
+    v8 = api.quantize_e5m2(p.vals[: p.nnz * b * b].contiguous())
+
+    def timed(fn, n, w):
+        for _ in range(w):
+            fn()
+        ev = Events(1)
+        hip, stream = ev.hip, C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        torch.cuda.synchronize()
+        hip.hipEventRecord(ev.triples[0][0], stream)
+        for _ in range(n):
+            fn()
+        hip.hipEventRecord(ev.triples[0][1], stream)
+        torch.cuda.synchronize()
+        ms = ev.elapsed(ev.triples[0][0], ev.triples[0][1]) / n
+        ev.destroy()
+        return ms
+
+    passes = []
+    for T in tokens:
+        x_h = synth.make_x(wl, T)
+        X = to_dev(x_h)
+        X8 = api.quantize_e5m2(X)
+        Y = torch.empty((T, wl.inter), dtype=torch.float32, device="cuda:0")
+        flops = 2.0 * b * b * T * p.nnz
+        ms16 = timed(lambda: api.bsr_spmm(p, X, out=Y), steps, warmup)
+        ms8 = timed(lambda: api.bsr_spmm_e5m2(p, v8, X8, out=Y), steps, warmup)
+        passes.append({"T": T, "bf16_ms": ms16, "e5m2_ms": ms8, "bf16_TFLOPs": flops / (ms16 * 1e-3) / 1e12,
+                       "e5m2_TFLOPs": flops / (ms8 * 1e-3) / 1e12,
+                       "e5m2_frac_mfma_fp8_peak": flops / (ms8 * 1e-3) / 1e12 / 5000.0})
+    out = {"workload": wl.name, "matrix": "gate (%d x %d)" % (wl.inter, wl.hidden), "block": b, "nnz_blocks": p.nnz,
+           "passes": passes}
+    if cpu:
+        from oracle import oracle as orc
+
+        T = max(tokens)
+        x_h = synth.make_x(wl, T)
+        sel = np.unique(np.concatenate(([0, T - 1], np.random.default_rng(3).choice(T, min(T, 62), replace=False))))
+        ref = orc.pack(lin.W, b, lin.mask) if lin.mask is not None else orc.pack_topk(lin.W, b, wl.sparsity)[0]
+        v8_or = orc.e5m2_quantize(synth.bf16_bits_to_f32(ref.vals))
+        x8_or = orc.e5m2_quantize(synth.bf16_bits_to_f32(x_h[sel]))
+        t0 = time.perf_counter()
+        y_or = orc.spmm_e5m2(ref, v8_or, x8_or)
+        sec = time.perf_counter() - t0
+        y = api.bsr_spmm_e5m2(p, v8, api.quantize_e5m2(to_dev(x_h)))
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy()[sel].astype(np.float64).T
+        out["cpu_baseline"] = {"value": 2.0 * b * b * sel.size * ref.nnz / sec / 1e12, "unit": "TFLOP/s", "seconds": sec,
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": "%d of %d tokens, all rows; dense masked fp64 loop on decoded codes" % (sel.size, T)}
+        out["parity_on_sample"] = {"rel_fro": float(np.linalg.norm(yh - y_or) / np.linalg.norm(y_or)),
+                                   "codes_identical": bool(np.array_equal(v8.cpu().numpy().reshape(v8_or.shape), v8_or))}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -332,6 +401,7 @@ def main():
                     help="skip the decode passes of the 405B-class layer (the case where weight bytes, not launch "
                          "latency, set the time)")
     ap.add_argument("--no-mlp2", action="store_true", help="skip the two-matrix MLP (GPT-2-shaped) passes")
+    ap.add_argument("--no-e5m2", action="store_true", help="skip the E5M2 product of the gate matrix")
     ap.add_argument("--no-backward", action="store_true", help="skip the backward-pass products of the gate matrix")
     ap.add_argument("--decode-tokens", default="", help="comma-separated decode token counts (default: the workload's)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
@@ -502,6 +572,10 @@ def main():
     if not args.no_backward and args.workload == "llama1b_b64_s90":
         torch.cuda.empty_cache()
         out["backward"] = backward_products(args.workload, T, args.steps, args.warmup, not args.no_cpu_baseline)
+
+    if not args.no_e5m2 and args.workload == "llama1b_b64_s90":
+        torch.cuda.empty_cache()
+        out["e5m2"] = e5m2_product(args.workload, (16, T), args.steps, args.warmup, not args.no_cpu_baseline)
 
     print(json.dumps(out))
 

@@ -5,11 +5,13 @@
 // organised like the stored-block-gradient kernel: a wave accumulates a 64-token x 64-row tile (2 x 2
 // register blocking of 32x32x16 matrix instructions) from a private ring of LDS stages filled by LDS-DMA
 // copies; there is no barrier in the loop, the wave's memory counter is the only synchronisation.
-//  - A stage is a 32-deep contraction slice: 64 weight rows x 32 bytes and 64 tokens x 32 bytes, 2 KiB each.
-//  - A lane reads one 16-byte chunk per operand row (16 contraction indices) and feeds its two halves to
-//    two matrix instructions; lanes 0-31 take the first chunk of a row, lanes 32-63 the second.  Both
+//  - A stage is a 64-deep contraction slice: 64 weight rows x 64 bytes and 64 tokens x 64 bytes, 4 KiB each
+//    (the L1 path is bound by cache lines requested, not bytes: 64-byte row segments are the widest a
+//    64 x 64 block offers, and a block's weight tile is then 4 KiB of whole lines).
+//  - A lane reads two 16-byte chunks per operand row (32 contraction indices) and feeds their four halves to
+//    four matrix instructions; lanes 0-31 take chunks 0 and 2 of a row, lanes 32-63 chunks 1 and 3.  Both
 //    operands use the same assignment, so every contraction index meets its partner exactly once.
-//  - The two chunks of a row are swapped in LDS for rows 4-7 of every 8 (on the global-address side of the
+//  - The four chunks of a row are XOR-swizzled in LDS by (row / 2) % 4 (on the global-address side of the
 //    copy): the eight rows one read cycle touches then cover all banks.
 // One byte per value halves every byte count of the bf16 kernels (HBM, L2 -> LDS, LDS -> registers) per
 // multiply-add, which is what bounds them.
@@ -38,29 +40,35 @@ struct Fp8Args {
   int groups;            // token groups per unit (256 tokens each without KSPLIT, 64 with)
 };
 
+#ifndef BLAST_FP8_NSTAGE
+#define BLAST_FP8_NSTAGE 2  // 16 KiB of ring per wave, 64 KiB per workgroup: two workgroups per CU (measured: three stages with one workgroup per CU are 20-30 % slower)
+#endif
+
 template <int B>
 struct Fp8Cfg {
   static_assert(B == 64 || B == 128, "blocks of at least 64 x 64");
   static constexpr int SB = 64;               // weight rows (and tokens) of a wave's tile
   static constexpr int SUB = B / SB;          // sub-blocks of rows per block row
-  static constexpr int KS = 32;               // contraction depth of a stage, = bytes of a tile row
+  static constexpr int KS = 64;               // contraction depth of a stage, = bytes of a tile row
   static constexpr int KSL = B / KS;          // stages per stored block
-  static constexpr int TILE = SB * KS;        // 2 KiB
+  static constexpr int CPR = KS / 16;         // 16-byte chunks per tile row
+  static constexpr int TILE = SB * KS;        // 4 KiB
   static constexpr int NI = TILE / 1024;      // wave-wide copy instructions per tile
   static constexpr int OPS = 2 * NI;
   static constexpr int STAGE = 2 * TILE;
-  static constexpr int NSTAGE = 4;
+  static constexpr int NSTAGE = BLAST_FP8_NSTAGE;
   static constexpr int WAVE_LDS = NSTAGE * STAGE;
-  static constexpr size_t LDS_BYTES = 4 * (size_t)WAVE_LDS;  // 64 KiB: two workgroups per CU
-  __device__ static __forceinline__ int key(int row) { return (row >> 2) & 1; }
+  static constexpr size_t LDS_BYTES = 4 * (size_t)WAVE_LDS;
+  __device__ static __forceinline__ int key(int row) { return (row >> 1) & 3; }
 };
+
 
 __device__ __forceinline__ void fp8_wait_vm(int outstanding) {
   switch (outstanding) {
     case 0: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0)); break;
-    case 4: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(4)); break;
     case 8: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(8)); break;
-    case 12: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(12)); break;
+    case 16: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(16)); break;
+    case 24: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(24)); break;
     default: __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0)); break;  // more than needed is always safe
   }
 }
@@ -71,7 +79,7 @@ template <int B, bool KSPLIT>
 __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
   using C = Fp8Cfg<B>;
   constexpr int NI = C::NI, NSTAGE = C::NSTAGE;
-  static_assert(C::OPS == 4, "fp8_wait_vm lists multiples of four");
+  static_assert(C::OPS == 8 && (NSTAGE - 1) * C::OPS <= 24, "fp8_wait_vm lists multiples of eight up to 24");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -98,24 +106,26 @@ __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
 
   // ---- per-lane constants -----------------------------------------------------------------------
   // Copy side: instruction ni of a tile writes LDS bytes [ni*1024 + lane*16, +16) = position p = ni*64 + lane
-  // in 16-byte units = (tile row p / 2, slot p % 2); it fetches chunk slot ^ key(row) of that row.
+  // in 16-byte units = (tile row p / 4, slot p % 4); it fetches chunk slot ^ key(row) of that row.
   uint32_t woff[NI], xoff[NI];
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
-    const int p = ni * 64 + lane, row = p >> 1, chunk = (p & 1) ^ C::key(row);
+    const int p = ni * 64 + lane, row = p / C::CPR, chunk = (p % C::CPR) ^ C::key(row);
     woff[ni] = (uint32_t)((si * C::SB + row) * B + chunk * 16);
     int t = t0 + row;
     t = t < a.T ? t : a.T - 1;  // rows past the last token re-read it; their results are never stored
     t = t < 0 ? 0 : t;
     xoff[ni] = (uint32_t)t * (uint32_t)a.ldx + (uint32_t)(chunk * 16);
   }
-  // Fragment side: lane l reads the 16-byte chunk l / 32 of tile row 32 h + l % 32.
-  uint32_t foff[2];
+  // Fragment side: lane l reads the 16-byte chunks l / 32 and l / 32 + 2 of tile row 32 h + l % 32.
+  uint32_t foff[2][2];
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int row = 32 * h + (lane & 31);
-    foff[h] = (uint32_t)(row * C::KS + (((lane >> 5) ^ C::key(row)) << 4));
-  }
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int row = 32 * h + (lane & 31);
+      foff[h][c] = (uint32_t)(row * C::KS + ((((lane >> 5) + 2 * c) ^ C::key(row)) << 4));
+    }
 
   f32x16 acc[2][2];  // [token half][row half]
 #pragma unroll
@@ -153,20 +163,24 @@ __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
     fp8_wait_vm(later * C::OPS);
     asm volatile("" ::: "memory");
     const unsigned char* slot = ring + (s % NSTAGE) * C::STAGE;
-    i64x2 fw[2], fx[2];
+    i64x2 fw[2][2], fx[2][2];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      fw[h] = *reinterpret_cast<const i64x2*>(slot + foff[h]);
-      fx[h] = *reinterpret_cast<const i64x2*>(slot + C::TILE + foff[h]);
-    }
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        fw[h][c] = *reinterpret_cast<const i64x2*>(slot + foff[h][c]);
+        fx[h][c] = *reinterpret_cast<const i64x2*>(slot + C::TILE + foff[h][c]);
+      }
     // D[m][n] += sum_k A[m][k] B[k][n]: m = token, n = weight row; two instructions per 16-byte chunk
 #pragma unroll
-    for (int e = 0; e < 2; ++e)
+    for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+      for (int e = 0; e < 2; ++e)
 #pragma unroll
-        for (int nj = 0; nj < 2; ++nj)
-          acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf8_bf8(fx[mi][e], fw[nj][e], acc[mi][nj], 0, 0, 0);
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int nj = 0; nj < 2; ++nj)
+            acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf8_bf8(fx[mi][c][e], fw[nj][c][e], acc[mi][nj], 0, 0, 0);
     asm volatile("" ::: "memory");
   }
 
