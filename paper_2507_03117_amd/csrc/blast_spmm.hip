@@ -78,6 +78,7 @@ struct ChunkPlan {
   const int* chunk_kb = nullptr;
   const int* chunk_ke = nullptr;
   int64_t max_chunks = 0;  // host-side upper bound of hdr[0]
+  int max_row_blocks = 0;  // stored blocks of the fullest block row
 };
 
 template <int B, bool DUAL, int TW, bool CHUNK>
@@ -236,10 +237,21 @@ int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, con
   // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
   if (a.x_vec && a.T > 0 && small_x && decode_applies<DUAL>(b, a, nnz)) {
+    // The decode kernel already spreads a block row over b/16 workgroups of four waves each, so a row of n
+    // blocks is n/4 block steps deep.  Chunks (a zero-fill launch plus atomics, about 8 us on the 405B-class
+    // gate matrix) only pay when that depth exceeds four times the average load of a workgroup slot
+    // (measured there: fullest row 128 blocks, 20.8 us without chunks against 28.8 us with; 416 blocks, 42.0
+    // against 23.3).
+    ChunkPlan dplan = plan;
+    if (dplan.hdr) {
+      double ref = (double)nnz * (b / 16) / (4.0 * 2.0 * cu_count());
+      if (ref < blast::kChunkBlocks) ref = blast::kChunkBlocks;
+      if ((double)dplan.max_row_blocks / 4.0 <= 4.0 * ref) dplan = ChunkPlan{};
+    }
     switch (b) {
-      case 32: return launch_decode<32, DUAL>(a, plan, stream);
-      case 64: return launch_decode<64, DUAL>(a, plan, stream);
-      case 128: return launch_decode<128, DUAL>(a, plan, stream);
+      case 32: return launch_decode<32, DUAL>(a, dplan, stream);
+      case 64: return launch_decode<64, DUAL>(a, dplan, stream);
+      case 128: return launch_decode<128, DUAL>(a, dplan, stream);
       default: break;
     }
   }
@@ -328,6 +340,7 @@ ChunkPlan plan_of(const blast_bsr_view* v, int64_t T) {
   p.chunk_kb = reinterpret_cast<const int*>(ab + L.chunk_kb_off);
   p.chunk_ke = reinterpret_cast<const int*>(ab + L.chunk_ke_off);
   p.max_chunks = nbr + v->nnz / blast::kChunkBlocks;
+  p.max_row_blocks = v->max_row_blocks;
   return p;
 }
 

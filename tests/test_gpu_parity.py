@@ -231,9 +231,12 @@ def test_spmm_strided_operands(api, b, T):
 
 
 @pytest.mark.parametrize("b,nbc,T", [(32, 70, 300), (64, 40, 520), (128, 36, 200), (64, 72, 300),
-                                     (32, 70, 9), (32, 70, 40), (64, 72, 1), (64, 72, 7), (64, 72, 16), (64, 72, 100), (128, 66, 3), (128, 66, 20)])
+                                     (32, 70, 9), (32, 70, 40), (64, 72, 1), (64, 72, 7), (64, 72, 16), (64, 72, 100), (128, 66, 3), (128, 66, 20),
+                                     # rows long enough for the decode kernel to take the chunk plan as well
+                                     (32, 300, 5), (64, 272, 2), (64, 272, 9), (64, 272, 33), (128, 260, 3), (128, 260, 20)])
 def test_spmm_heavy_rows_are_chunked(api, b, nbc, T):
-    """Rows with more than 16 stored blocks are cut into chunks that add their partial sums atomically."""
+    """Rows with more than 16 stored blocks are cut into chunks that add their partial sums atomically (at
+    decode token counts only when a row is more than 256 blocks long)."""
     import torch
 
     rng = np.random.default_rng(900 + b)
