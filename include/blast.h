@@ -188,7 +188,9 @@ size_t blast_pooled_topk_mask_workspace(int64_t rows, int64_t cols, int32_t b);
  * Never synchronises.  Errors: INVALID_ARG, HIP.
  *
  * blast_bsr_spmm_e5m2: Y = W~ X as in blast_bsr_spmm with both operands in E5M2 and fp32 accumulation.
- *   W          structure of the packed matrix (row_ptr, col_idx, row_order, nnz, b; W->vals is not read)
+ *   W          structure of the packed matrix (row_ptr, col_idx, row_order, aux, max_row_blocks, nnz, b;
+ *              W->vals is not read).  With fp32 output and few tokens, rows much longer than a chunk are
+ *              accumulated with atomic additions, as in blast_bsr_spmm.
  *   vals8      E5M2 block values, [W->nnz][b][b], one byte each, same order as W->vals
  *   X8, ldx    E5M2 activations, [T][cols] (token-major) or [cols][T], row pitch ldx bytes
  *   Y, ldy     as in blast_bsr_spmm (fp32 or bf16, same layout as X8)

@@ -9,14 +9,14 @@ using namespace blast_dev;
 
 namespace {
 
-template <int B, bool KSPLIT>
+template <int B, bool KSPLIT, bool CHUNK = false>
 int launch_fp8(Fp8Args a, hipStream_t stream) {
   using C = Fp8Cfg<B>;
   static bool lds_set[64] = {};
   int dev = 0;
   BLAST_HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64 || !lds_set[dev]) {
-    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_fp8<B, KSPLIT>),
+    BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_fp8<B, KSPLIT, CHUNK>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     if (dev >= 0 && dev < 64) lds_set[dev] = true;
   }
@@ -26,16 +26,50 @@ int launch_fp8(Fp8Args a, hipStream_t stream) {
   if (grid <= 0) return BLAST_OK;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
   a.groups = (int)groups;
-  k_spmm_fp8<B, KSPLIT><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(a);
+  if (CHUNK) {
+    // rows cut into several chunks are accumulated: clear them first (the kernel of the bf16 path; it only
+    // reads the output description, the row pointers and the plan)
+    StreamArgs sa{};
+    sa.t.m0.row_ptr = a.row_ptr;
+    sa.t.Y = a.Y;
+    sa.t.syt = a.ldy;
+    sa.t.syi = 1;
+    sa.t.T = a.T;
+    sa.hdr = a.hdr;
+    sa.chunk_row = a.chunk_row;
+    sa.chunk_kb = a.chunk_kb;
+    sa.chunk_ke = a.chunk_ke;
+    k_zero_shared_rows<B><<<dim3((unsigned)(a.n_units / C::SUB), (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
+    BLAST_LAUNCH_CHECK("k_zero_shared_rows");
+  }
+  k_spmm_fp8<B, KSPLIT, CHUNK><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(a);
   BLAST_LAUNCH_CHECK("k_spmm_fp8");
   return BLAST_OK;
 }
 
 template <int B>
-int launch_fp8_b(const Fp8Args& a, hipStream_t stream) {
+int launch_fp8_b(const Fp8Args& a, const blast_bsr_view* W, hipStream_t stream) {
   // up to two token tiles the stages of a row are dealt to the four waves (every wave streams weights);
   // beyond that a wave owns a token tile of its own and walks the whole row
-  if (a.T <= 128) return launch_fp8<B, true>(a, stream);
+  if (a.T <= 128) {
+    // A row of n blocks is n * (B / 64) / 4 stages deep per wave.  When the fullest row is deeper than four
+    // chunks' worth, take the packer's chunk plan (fp32 output only: chunks of a row add atomically).
+    if (W->aux && !a.y_bf16 && W->max_row_blocks > 4 * blast::kChunkBlocks) {
+      const int64_t nbr = W->rows / B, nbc = W->cols / B;
+      const blast::AuxLayout L = blast::aux_layout(nbr, nbc, W->nnz);
+      const char* ab = static_cast<const char*>(W->aux);
+      Fp8Args c = a;
+      c.hdr = reinterpret_cast<const int*>(ab + L.hdr_off);
+      c.chunk_row = reinterpret_cast<const int*>(ab + L.chunk_row_off);
+      c.chunk_kb = reinterpret_cast<const int*>(ab + L.chunk_kb_off);
+      c.chunk_ke = reinterpret_cast<const int*>(ab + L.chunk_ke_off);
+      const int64_t max_chunks = nbr + W->nnz / blast::kChunkBlocks;
+      if (max_chunks * (B / 64) > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
+      c.n_units = (int)(max_chunks * (B / 64));
+      return launch_fp8<B, true, true>(c, stream);
+    }
+    return launch_fp8<B, true>(a, stream);
+  }
   return launch_fp8<B, false>(a, stream);
 }
 
@@ -86,7 +120,7 @@ extern "C" int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8
     a.y_bf16 = y_dtype == BLAST_BF16 ? 1 : 0;
     a.T = (int)T;
     a.n_units = (int)(W->rows / b) * (b / 64);
-    return b == 64 ? launch_fp8_b<64>(a, stream) : launch_fp8_b<128>(a, stream);
+    return b == 64 ? launch_fp8_b<64>(a, W, stream) : launch_fp8_b<128>(a, W, stream);
   }
   Fp8GenericArgs g{};
   g.row_ptr = W->row_ptr;

@@ -19,6 +19,9 @@
 //    tile per wave; the four waves read the same weight tiles (L1 hits).
 //  - KSPLIT = true (up to a few token tiles): a workgroup owns (block row, sub-block, 64 tokens) and its
 //    four waves deal the stages among themselves; the partial sums are added in LDS in a fixed order.
+//    With CHUNK the unit is a chunk of at most 16 stored blocks from the packer's chunk plan instead of a
+//    whole block row; rows cut into several chunks add into a zeroed fp32 output atomically (a very long
+//    row would otherwise be the critical path of the launch).
 #pragma once
 #include "kern_common.h"
 #include "kern_stream.h"
@@ -36,8 +39,13 @@ struct Fp8Args {
   int64_t ldy;
   int y_bf16;
   int T;
-  int n_units;           // (block rows) * SUB
+  int n_units;           // (block rows, or chunk slots with CHUNK) * SUB
   int groups;            // token groups per unit (256 tokens each without KSPLIT, 64 with)
+  // chunk plan written by the packer (CHUNK instances only): hdr[0] = number of chunks
+  const int* hdr;
+  const int* chunk_row;  // block row of the chunk; bit 31 set when the row has several chunks
+  const int* chunk_kb;   // first stored block of the chunk
+  const int* chunk_ke;   // one past its last stored block
 };
 
 #ifndef BLAST_FP8_NSTAGE
@@ -75,8 +83,9 @@ __device__ __forceinline__ void fp8_wait_vm(int outstanding) {
 
 typedef long i64x2 __attribute__((ext_vector_type(2)));
 
-template <int B, bool KSPLIT>
+template <int B, bool KSPLIT, bool CHUNK = false>
 __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
+  static_assert(!CHUNK || KSPLIT, "the chunk plan serves the few-token form");
   using C = Fp8Cfg<B>;
   constexpr int NI = C::NI, NSTAGE = C::NSTAGE;
   static_assert(C::OPS == 8 && (NSTAGE - 1) * C::OPS <= 24, "fp8_wait_vm lists multiples of eight up to 24");
@@ -91,9 +100,20 @@ __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
   if (unit >= a.n_units) return;  // whole workgroup, before any barrier
   const int tg = rem >> 3;
   const int rank = unit / C::SUB, si = unit % C::SUB;
-  const int r = a.row_order ? ld_idx(a.row_order, rank) : rank;
-  const int kb = ld_idx(a.row_ptr, r);
-  const int row_stages = (ld_idx(a.row_ptr, r + 1) - kb) * C::KSL;
+  int r, kb, row_stages;
+  bool shared_row = false;
+  if (CHUNK) {
+    if (rank >= ld_idx(a.hdr, 0)) return;  // the grid is sized by an upper bound of the number of chunks
+    const int cr = ld_idx(a.chunk_row, rank);
+    r = cr & 0x7FFFFFFF;
+    shared_row = cr < 0;
+    kb = ld_idx(a.chunk_kb, rank);
+    row_stages = (ld_idx(a.chunk_ke, rank) - kb) * C::KSL;
+  } else {
+    r = a.row_order ? ld_idx(a.row_order, rank) : rank;
+    kb = ld_idx(a.row_ptr, r);
+    row_stages = (ld_idx(a.row_ptr, r + 1) - kb) * C::KSL;
+  }
   // first token of this wave's tile; which stages of the row it walks
   const int t0 = KSPLIT ? tg * C::SB : (tg * 4 + wave) * C::SB;
   const int first = KSPLIT ? wave : 0, step = KSPLIT ? 4 : 1;
@@ -192,7 +212,9 @@ __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
     const int t = t0 + 32 * mi + 8 * (v >> 2) + 4 * lh + (v & 3);
     if (t < a.T) {
       const int64_t off = (int64_t)t * a.ldy + row0 + 32 * nj + l32;
-      if (a.y_bf16)
+      if (CHUNK && shared_row)
+        atomicAdd(reinterpret_cast<float*>(a.Y) + off, val);  // fp32 output, zeroed before the launch
+      else if (a.y_bf16)
         reinterpret_cast<uint16_t*>(a.Y)[off] = f32_to_bf16_rne(val);
       else
         reinterpret_cast<float*>(a.Y)[off] = val;

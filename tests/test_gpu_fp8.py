@@ -138,3 +138,33 @@ def test_spmm_e5m2_llama1b_gate_full_size(api):
         sel = np.arange(T) if T <= 64 else np.unique(np.concatenate(([0, T - 1], np.random.default_rng(T).choice(T, 46, replace=False))))
         want = orc.spmm_e5m2(ref, v8_or, orc.e5m2_quantize(_f32(x[sel])))
         check_close(y.cpu().numpy()[sel].T, want, f"e5m2 1B gate T={T}")
+
+
+@pytest.mark.parametrize("b,nbc,T", [(64, 80, 1), (64, 80, 20), (64, 80, 100), (128, 70, 5), (128, 70, 128), (64, 80, 300)])
+def test_spmm_e5m2_heavy_rows(api, b, nbc, T):
+    """Rows much longer than a chunk: with few tokens and fp32 output the chunks of a row add atomically into
+    cleared rows (poisoned output, two calls in a row); bf16 output and many tokens take the unsplit forms."""
+    import torch
+
+    rng = np.random.default_rng(9997 + b + T)
+    nbr = 6
+    mask = synth.uniform_mask(rng, nbr, nbc, 0.9)
+    mask[0, :] = 1
+    mask[2, : (3 * nbc) // 4] = 1
+    mask[4, :] = 0
+    W = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.05)
+    dev = api.bsr_pack(to_dev(W), b, mask=mask_dev(mask))
+    ref = orc.pack(W, b, mask)
+    assert dev.max_row_blocks == nbc
+    x = synth.gauss_bf16(rng, (T, nbc * b), 1.0)
+    vals8 = api.quantize_e5m2(dev.vals[: dev.nnz * b * b].contiguous())
+    x8 = api.quantize_e5m2(to_dev(x))
+    want = orc.spmm_e5m2(ref, orc.e5m2_quantize(_f32(ref.vals)), orc.e5m2_quantize(_f32(x)))
+    for _ in range(2):
+        y = api.bsr_spmm_e5m2(dev, vals8, x8, out=torch.full((T, nbr * b), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, want, f"e5m2 heavy rows b={b} T={T}")
+    assert not y.cpu().numpy()[:, 4 * b:5 * b].any()
+    yb = api.bsr_spmm_e5m2(dev, vals8, x8, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert np.abs(yb.float().cpu().numpy().T - want).max() <= 2.0 ** -7 * np.abs(want).max()
