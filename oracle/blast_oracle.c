@@ -20,7 +20,19 @@
  *                     expand to dense, naive triple loop, fp64.
  *   - MLP           = Eq. (1): Y = W~down ( act(W~gate X) (.) (W~up X) ), with the
  *                     intermediate H rounded once to bf16 (the precision in which
- *                     it enters the second contraction on the device).
+ *                     it enters the second contraction on the device); the two-matrix
+ *                     form Y = W~2 act(W~1 X) of Sec. 2.1 with the same rounding.
+ *   - backward      = dX = W~^T dY and the gradient of the stored blocks, the entries
+ *                     of dY X^T on kept blocks (Sec. 3.2: one pruned matrix for
+ *                     forward and backward).
+ *   - mask update   = one generate_masks() round of blocked prune-and-grow and the
+ *                     cubic sparsity schedule, Eq. (2) (Sec. 3.2); block scores by
+ *                     2D average pooling of a sensitivity matrix (Sec. 3.3).
+ *   - E5M2          = the 8-bit floating-point type of Sec. 5.2: exact decode,
+ *                     round-to-nearest-even encode, the product on E5M2 operands.
+ * Every function is pinned by tests that do not go through the HIP library
+ * (closed forms, library routines, exact rational brute force, invariants); none
+ * is "parity unpinned".
  *
  * Readings of points the paper leaves open (kept identical in the HIP library
  * by specification, not by shared code):
