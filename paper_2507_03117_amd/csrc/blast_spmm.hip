@@ -71,6 +71,20 @@ int cu_count() {
   return cached[dev];
 }
 
+// Rows of an fp32 output that a later chunked product accumulates into; a launch before it can clear them
+// on the side (see DecArgs) and says so in `done`.
+struct ZeroJob {
+  const int* hdr = nullptr;
+  const int* chunk_row = nullptr;
+  const int* chunk_kb = nullptr;
+  const int* row_ptr = nullptr;
+  float* Y = nullptr;
+  int64_t syt = 0, syi = 0;
+  int T = 0;
+  int64_t max_chunks = 0;
+  bool done = false;
+};
+
 // Chunk plan of a packed matrix, as pointers into its aux buffer (null when it is not to be used).
 struct ChunkPlan {
   const int* hdr = nullptr;
@@ -79,6 +93,8 @@ struct ChunkPlan {
   const int* chunk_ke = nullptr;
   int64_t max_chunks = 0;  // host-side upper bound of hdr[0]
   int max_row_blocks = 0;  // stored blocks of the fullest block row
+  ZeroJob* zero_job = nullptr;  // a side job this launch may take along (decode launches only)
+  bool pre_zeroed = false;      // the shared rows of the output have been cleared by an earlier launch
 };
 
 template <int B, bool DUAL, int TW, bool CHUNK>
@@ -168,6 +184,22 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
   d.n_units = (int)units;
   d.groups = (int)groups;
+  int64_t total = grid;
+  if (plan.zero_job && plan.zero_job->hdr && plan.zero_job->max_chunks > 0 && grid + plan.zero_job->max_chunks <= INT32_MAX) {
+    ZeroJob& z = *plan.zero_job;
+    d.main_blocks = (int)grid;
+    d.z_blocks = (int)z.max_chunks;
+    d.z_hdr = z.hdr;
+    d.z_chunk_row = z.chunk_row;
+    d.z_chunk_kb = z.chunk_kb;
+    d.z_row_ptr = z.row_ptr;
+    d.z_Y = z.Y;
+    d.z_syt = z.syt;
+    d.z_syi = z.syi;
+    d.z_T = z.T;
+    total = grid + z.max_chunks;
+    z.done = true;
+  }
   using C = DecCfg<B, DUAL, NTT, XSMALL>;
   if constexpr (!DUAL && !CHUNK) {
     if (a.act >= 0) {  // single matrix with an activation on the output
@@ -175,7 +207,7 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
       if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, false, NTT, false, XSMALL, true>),
                                     C::LDS_BYTES, lds_set_post))
         return rc;
-      k_decode<B, false, NTT, false, XSMALL, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(d);
+      k_decode<B, false, NTT, false, XSMALL, true><<<dim3((unsigned)total), dim3(256), C::LDS_BYTES, stream>>>(d);
       BLAST_LAUNCH_CHECK("k_decode");
       return BLAST_OK;
     }
@@ -184,12 +216,12 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL>), C::LDS_BYTES,
                                 lds_set))
     return rc;
-  if (CHUNK) {
+  if (CHUNK && !plan.pre_zeroed) {
     StreamArgs sa{a, 0, -1, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
   }
-  k_decode<B, DUAL, NTT, CHUNK, XSMALL><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(d);
+  k_decode<B, DUAL, NTT, CHUNK, XSMALL><<<dim3((unsigned)total), dim3(256), C::LDS_BYTES, stream>>>(d);
   BLAST_LAUNCH_CHECK("k_decode");
   return BLAST_OK;
 }
@@ -206,12 +238,14 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
       return launch_decode_ntt<B, false, 2, true>(a, plan, stream);
     }
   }
+  ChunkPlan side{};  // no chunks; only the side job travels on
+  side.zero_job = plan.zero_job;
   if constexpr (B >= 64) {
-    if (a.T <= 512 / B) return launch_decode_ntt<B, DUAL, 1, false, true>(a, ChunkPlan{}, stream);
+    if (a.T <= 512 / B) return launch_decode_ntt<B, DUAL, 1, false, true>(a, side, stream);
   }
   // 128-wide blocks: two token tiles per slot would leave room for one workgroup per CU only
-  if (a.T <= 16 || B == 128) return launch_decode_ntt<B, DUAL, 1, false>(a, ChunkPlan{}, stream);
-  return launch_decode_ntt<B, DUAL, 2, false>(a, ChunkPlan{}, stream);  // groups of 32 tokens along gridDim.y
+  if (a.T <= 16 || B == 128) return launch_decode_ntt<B, DUAL, 1, false>(a, side, stream);
+  return launch_decode_ntt<B, DUAL, 2, false>(a, side, stream);  // groups of 32 tokens along gridDim.y
 }
 
 // Crossover with the streaming kernel, from token sweeps on the 1B-shaped MLP.  The decode kernel
@@ -246,7 +280,10 @@ int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, con
     if (dplan.hdr) {
       double ref = (double)nnz * (b / 16) / (4.0 * 2.0 * cu_count());
       if (ref < blast::kChunkBlocks) ref = blast::kChunkBlocks;
-      if ((double)dplan.max_row_blocks / 4.0 <= 4.0 * ref) dplan = ChunkPlan{};
+      if ((double)dplan.max_row_blocks / 4.0 <= 4.0 * ref) {
+        dplan = ChunkPlan{};
+        dplan.zero_job = plan.zero_job;
+      }
     }
     switch (b) {
       case 32: return launch_decode<32, DUAL>(a, dplan, stream);
@@ -427,7 +464,9 @@ int check_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blas
 // H = act(Wgate X) (.) (Wup X), or H = act(Wgate X) when Wup is null; bf16, strides given by (h_layout, ldh).
 int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const uint16_t* X, int64_t ldx,
                   int32_t x_layout, int64_t T, int32_t act, uint16_t* H, int64_t ldh, int32_t h_layout,
-                  hipStream_t stream) {
+                  hipStream_t stream, ZeroJob* side_job = nullptr) {
+  ChunkPlan side{};
+  side.zero_job = side_job;
   TileArgs g{};
   g.m0 = mat_of(Wgate);
   if (Wup) g.m1 = mat_of(Wup);
@@ -437,8 +476,8 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
   g.T = (int)T;
   g.nbr = (int)(Wgate->rows / Wgate->b);
   g.act = act;
-  if (!Wup) return dispatch_tile<false>(Wgate->b, g, Wgate->nnz, stream);
-  return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream);
+  if (!Wup) return dispatch_tile<false>(Wgate->b, g, Wgate->nnz, stream, side);
+  return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream, side);
 }
 
 // Every single-launch MLP gets its own token (never 0): a slot of the workspace says "published" only
@@ -564,10 +603,6 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
     if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
     return BLAST_OK;
   }
-  if (I > 0) {
-    if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream)) return rc;
-  }
-  if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));
   TileArgs d{};
   d.m0 = mat_of(Wdown);
   d.row_order = Wdown->row_order;
@@ -576,7 +611,30 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   d.T = (int)T;
   d.nbr = (int)(E / b);
   d.act = -1;
-  if (int rc = dispatch_tile<false>(b, d, Wdown->nnz, stream, plan_of(Wdown, T))) return rc;
+  ChunkPlan dplan = plan_of(Wdown, T);
+  // At decode token counts the rows of Y that the chunked second product accumulates into are cleared on
+  // the side by the first product's launch (extra workgroups of the same kernel) instead of by a launch
+  // of their own between the two products.
+  ZeroJob zj{};
+  if (dplan.hdr && y_dtype == BLAST_F32 && T <= kDecodeMaxTokens && I > 0) {
+    zj.hdr = dplan.hdr;
+    zj.chunk_row = dplan.chunk_row;
+    zj.chunk_kb = dplan.chunk_kb;
+    zj.row_ptr = Wdown->row_ptr;
+    zj.Y = static_cast<float*>(Y);
+    zj.syt = d.syt;
+    zj.syi = d.syi;
+    zj.T = (int)T;
+    zj.max_chunks = dplan.max_chunks;
+  }
+  if (I > 0) {
+    if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream,
+                               zj.hdr ? &zj : nullptr))
+      return rc;
+  }
+  if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));
+  dplan.pre_zeroed = zj.done;
+  if (int rc = dispatch_tile<false>(b, d, Wdown->nnz, stream, dplan)) return rc;
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
   return BLAST_OK;
 }

@@ -52,7 +52,31 @@ struct DecArgs {
   unsigned long long* slots;
   unsigned long long token;
   int* sync_err;         // set to 1 if a consumer gave up waiting (the result is then invalid)
+  // Side job of a launch (z_blocks > 0): workgroups [main_blocks, main_blocks + z_blocks) clear the fp32
+  // rows that a LATER chunked product will accumulate into (the rows of block rows cut into several
+  // chunks), so that product needs no clearing launch of its own.  One workgroup per chunk slot.
+  int main_blocks, z_blocks;
+  const int* z_hdr;
+  const int* z_chunk_row;
+  const int* z_chunk_kb;
+  const int* z_row_ptr;
+  float* z_Y;
+  int64_t z_syt, z_syi;
+  int z_T;
 };
+
+template <int B>
+__device__ __forceinline__ void decode_zero_job(const DecArgs& a, int ci) {
+  if (ci >= ld_idx(a.z_hdr, 0)) return;
+  const int cr = ld_idx(a.z_chunk_row, ci);
+  if (cr >= 0) return;  // a single-chunk row is stored, not accumulated
+  const int r = cr & 0x7FFFFFFF;
+  if (ld_idx(a.z_chunk_kb, ci) != ld_idx(a.z_row_ptr, r)) return;  // only the first chunk of the row clears
+  for (int e = threadIdx.x; e < a.z_T * B; e += 256) {
+    const int t = e / B, i = e % B;
+    a.z_Y[(int64_t)t * a.z_syt + ((int64_t)r * B + i) * a.z_syi] = 0.0f;
+  }
+}
 
 enum DecRole { kDecAlone = 0, kDecProducer = 1, kDecConsumer = 2 };
 constexpr int kDecMaxSpins = 1 << 19;  // polls of ~0.3 us each before a consumer gives up (never hang the GPU)
@@ -319,6 +343,10 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   // slices.  Workgroup ids are dealt round-robin to the 8 XCDs, so the token groups of one unit are
   // placed 8 ids apart: same XCD, dispatched together - the re-reads hit that XCD's L2.
   const int blk = blockIdx.x, span = 8 * a.groups;
+  if (a.z_blocks > 0 && blk >= a.main_blocks) {
+    decode_zero_job<B>(a, blk - a.main_blocks);
+    return;
+  }
   const int rem = blk % span;
   const int unit = (blk / span) * 8 + (rem & 7);
   if (unit >= a.n_units) return;

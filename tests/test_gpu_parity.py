@@ -552,3 +552,30 @@ def test_mlp2_topk_packed_gpt2_shape(api):
         y = api.sparse_mlp2(d1, d2, to_dev(x))
         torch.cuda.synchronize()
         check_close(y.cpu().numpy().T, orc.mlp2(r1, r2, x), f"mlp2 gpt2 shape T={T}")
+
+
+@pytest.mark.parametrize("T", [1, 20, 32, 40])
+def test_mlp_decode_with_a_very_long_down_row(api, T):
+    """A row of W_down long enough for the decode kernel to take the chunk plan: its output rows are cleared by
+    side workgroups of the gate/up launch (T <= 32) or by a launch of their own (above), into a poisoned Y."""
+    import torch
+
+    rng = np.random.default_rng(8600 + T)
+    b, E, nbi = 64, 256, 272
+    I = nbi * b
+    g, u, d = (synth.gauss_bf16(rng, s, 0.02) for s in ((I, E), (I, E), (E, I)))
+    mg, mu = (synth.uniform_mask(rng, nbi, E // b, 0.5) for _ in range(2))
+    md = synth.uniform_mask(rng, E // b, nbi, 0.9)
+    md[0, :] = 1   # 272 blocks: cut into 17 chunks
+    md[2, :] = 0   # an empty row beside it
+    dg, rg = pack_both(api, g, b, mask=mg)
+    du, ru = pack_both(api, u, b, mask=mu)
+    dd, rd = pack_both(api, d, b, mask=md)
+    assert dd.max_row_blocks == nbi
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    want = orc.mlp(rg, ru, rd, x)
+    for _ in range(2):
+        y = api.sparse_mlp(dg, du, dd, to_dev(x), out=torch.full((T, E), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, want, f"mlp long down row T={T}")
+    assert not y.cpu().numpy()[:, 2 * b:3 * b].any()
