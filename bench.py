@@ -43,8 +43,8 @@ MEASURED_TRAFFIC_BYTES = {
     ("gate_up", 2048): 62.96e6 + 34.46e6,
     ("mlp", 1): 10.51e6 + 0.03e6,
     ("mlp", 16): 12.49e6 + 0.41e6,
-    ("llama405b_b128_s95_zipf", 1): (175.58e6 + 0.11e6) + (88.61e6 + 0.13e6 + 0.11e6),
-    ("llama405b_b128_s95_zipf", 16): (181.33e6 + 1.70e6) + (112.36e6 + 2.01e6 + 0.11e6),
+    ("llama405b_b128_s95_zipf", 1): (175.63e6 + 0.12e6) + (88.61e6 + 0.13e6),
+    ("llama405b_b128_s95_zipf", 16): (181.42e6 + 1.92e6) + (112.35e6 + 2.01e6),
 }
 
 
