@@ -569,9 +569,14 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
     (void)hipGetLastError();
     cap = hipStreamCaptureStatusNone;
   }
+  // One launch saves a dispatch gap and the second kernel's ramp, a few microseconds; its smaller copy rings
+  // (producers and consumers share the CUs) cost bandwidth.  Measured with uniform masks and cold weights:
+  // about even up to 18 MB of stored blocks, 63 us against 55 us on the 405B-class layer (262 MB).
+  const int64_t stored_bytes = (Wgate->nnz + (Wup ? Wup->nnz : 0) + Wdown->nnz) * (int64_t)b * b * 2;
+  const bool fused_pays = stored_bytes <= ((int64_t)32 << 20);
   // (b >= 64: a token's slice of one block column of H then fills whole 128-byte lines, so a line is never
   // read by one consumer while the producers of a neighbouring column are still writing the rest of it)
-  if (I > 0 && T <= one_tile && cap == hipStreamCaptureStatusNone && (b == 64 || b == 128) &&
+  if (I > 0 && T <= one_tile && cap == hipStreamCaptureStatusNone && (b == 64 || b == 128) && fused_pays &&
       x_layout == BLAST_TOKEN_MAJOR && ldx % 8 == 0 &&
       blast::aligned(X, 16) && T * ldx * 2 < ((int64_t)1 << 32) && !plan_of(Wdown, T).hdr) {
     TileArgs g{}, d{};
