@@ -118,6 +118,7 @@ extern "C" int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8
     a.Y = Y;
     a.ldy = ldy;
     a.y_bf16 = y_dtype == BLAST_BF16 ? 1 : 0;
+    a.y_fast = ((int64_t)64 * ldy * 4 + ldy * 4 < ((int64_t)1 << 31)) ? 1 : 0;
     a.T = (int)T;
     a.n_units = (int)(W->rows / b) * (b / 64);
     return b == 64 ? launch_fp8_b<64>(a, W, stream) : launch_fp8_b<128>(a, W, stream);

@@ -38,6 +38,7 @@ struct Fp8Args {
   void* Y;               // token-major [T][rows], row pitch ldy elements
   int64_t ldy;
   int y_bf16;
+  int y_fast;            // 1: every byte offset inside a 64-token slab of Y fits 31 bits
   int T;
   int n_units;           // (block rows, or chunk slots with CHUNK) * SUB
   int groups;            // token groups per unit (256 tokens each without KSPLIT, 64 with)
@@ -221,6 +222,28 @@ __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
     }
   };
   if (!KSPLIT) {
+    if (t0 + C::SB <= a.T && a.y_fast) {
+      // Whole token tile: one 64-bit lane address, the token step as a uniform 32-bit product, no predication
+      // (a stored value then costs a conversion, an add and the store).
+      const uint32_t esz = a.y_bf16 ? 2u : 4u;
+      uint32_t pitch = (uint32_t)a.ldy * esz;
+      asm volatile("" : "+s"(pitch));  // keeps the multiples of the pitch out of long-lived registers
+      unsigned char* p0 = reinterpret_cast<unsigned char*>(a.Y) + ((int64_t)(t0 + 4 * lh) * a.ldy + row0 + l32) * esz;
+#pragma unroll
+      for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const uint32_t dt = 32 * mi + 8 * (v >> 2) + (v & 3);
+            unsigned char* pj = p0 + 32 * nj * esz + __builtin_amdgcn_readfirstlane(dt * pitch);
+            if (a.y_bf16)
+              *reinterpret_cast<uint16_t*>(pj) = f32_to_bf16_rne(acc[mi][nj][v]);
+            else
+              *reinterpret_cast<float*>(pj) = acc[mi][nj][v];
+          }
+      return;
+    }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
