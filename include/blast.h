@@ -140,6 +140,15 @@ int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, i
                    int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Dense form of a packed matrix: the pruned weight W_new that prune_weights() applies in the training loop of
+ * Sec. 3.2 (stored blocks copied to their places, zeros everywhere else; regrown blocks are zeros by
+ * construction).  The inverse of blast_bsr_pack on the kept blocks.
+ *   W, ldw      out, bf16 [rows][cols], row pitch ldw >= cols, ldw % 8 == 0, 16-byte aligned; fully overwritten
+ * Never synchronises.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, HIP.
+ */
+int blast_bsr_unpack(const blast_bsr_view* Wp, uint16_t* W, int64_t ldw, void* stream);
+
+/*
  * One mask update of blocked prune-and-grow (Sec. 3.2, the generate_masks() step of the training loop):
  *   S(W) = the blocks of W kept at `sparsity` by block Frobenius norm (same count, ranking and tie rule as
  *          BLAST_PACK_TOPK_FROBENIUS), S(G) = the same selection on the gradient G, D = S(G) \ S(W).

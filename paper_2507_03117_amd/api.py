@@ -26,7 +26,8 @@ EXPORTS = (
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
     "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm",
     "blast_generate_masks", "blast_generate_masks_workspace", "blast_sparsity_schedule",
-    "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_quantize_e5m2", "blast_bsr_spmm_e5m2", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
+    "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_quantize_e5m2", "blast_bsr_spmm_e5m2",
+    "blast_bsr_unpack", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
 
@@ -95,6 +96,8 @@ def lib():
         L.blast_quantize_e5m2.argtypes = [vp, i64, vp, vp]
         L.blast_bsr_spmm_e5m2.restype = C.c_int
         L.blast_bsr_spmm_e5m2.argtypes = [pv, vp, vp, i64, i32, i64, vp, i64, i32, vp]
+        L.blast_bsr_unpack.restype = C.c_int
+        L.blast_bsr_unpack.argtypes = [pv, vp, i64, vp]
         L.blast_bsr_transpose.restype = C.c_int
         L.blast_bsr_transpose.argtypes = [pv, vp, vp, vp, vp, vp, sz, C.POINTER(C.c_int32), vp]
         L.blast_bsr_sddmm.restype = C.c_int
@@ -233,6 +236,15 @@ def pooled_topk_mask(S: torch.Tensor, b: int, sparsity: float) -> torch.Tensor:
 def sparsity_schedule(i: int, m: int, d: int, s_init: float, s_max: float) -> float:
     """blast_sparsity_schedule: Eq. (2)."""
     return float(lib().blast_sparsity_schedule(int(i), int(m), int(d), float(s_init), float(s_max)))
+
+
+def bsr_unpack(W: PackedBsr, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_bsr_unpack: the dense pruned weight, bf16 [rows, cols], zeros outside the stored blocks."""
+    D = out if out is not None else torch.empty((W.rows, W.cols), dtype=torch.bfloat16, device=W.row_ptr.device)
+    assert D.is_cuda and D.dim() == 2 and D.stride(1) == 1 and D.element_size() == 2 and D.shape == (W.rows, W.cols)
+    v = W.view()
+    _check(lib().blast_bsr_unpack(C.byref(v), _ptr(D), D.stride(0), _stream()), "blast_bsr_unpack")
+    return D
 
 
 def quantize_e5m2(x: torch.Tensor) -> torch.Tensor:

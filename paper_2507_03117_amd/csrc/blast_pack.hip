@@ -368,6 +368,34 @@ __global__ __launch_bounds__(256) void k_transpose_blocks(const uint16_t* __rest
   for (int idx = threadIdx.x; idx < b * b; idx += blockDim.x) dst[idx] = tile[(idx % b) * pitch + idx / b];
 }
 
+// One workgroup per block of the dense matrix: copies the stored block there, or writes zeros where the
+// block row's column list (ascending) has no entry for it.
+__global__ __launch_bounds__(256) void k_unpack_blocks(const int* __restrict__ row_ptr, const int* __restrict__ col_idx,
+                                                       const uint16_t* __restrict__ vals, int nbc, int b,
+                                                       uint16_t* __restrict__ W, int64_t ldw) {
+  const int64_t blk = blockIdx.x;
+  const int br = (int)(blk / nbc), bc = (int)(blk % nbc);
+  int lo = row_ptr[br], hi = row_ptr[br + 1];
+  int k = -1;
+  while (lo < hi) {  // binary search for bc in [lo, hi)
+    const int mid = (lo + hi) >> 1;
+    const int c = col_idx[mid];
+    if (c == bc) {
+      k = mid;
+      break;
+    }
+    if (c < bc) lo = mid + 1; else hi = mid;
+  }
+  uint16_t* dst = W + (int64_t)br * b * ldw + (int64_t)bc * b;
+  const uint16_t* src = k >= 0 ? vals + (int64_t)k * b * b : nullptr;
+  const int cpr = b / 8, nchunks = b * cpr;
+  for (int c = threadIdx.x; c < nchunks; c += 256) {
+    const int i = c / cpr, j8 = c % cpr;
+    *reinterpret_cast<uint4*>(dst + (int64_t)i * ldw + j8 * 8) =
+        src ? *reinterpret_cast<const uint4*>(src + (int64_t)c * 8) : uint4{0u, 0u, 0u, 0u};
+  }
+}
+
 // out[i] = in[i]
 __global__ __launch_bounds__(256) void k_copy_i32(const int* __restrict__ in, int64_t n, int* __restrict__ out) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -731,5 +759,19 @@ extern "C" int blast_pooled_topk_mask(const float* S, int64_t lds, int64_t rows,
   BLAST_LAUNCH_CHECK("k_pooled_scores");
   k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, mask_out);
   BLAST_LAUNCH_CHECK("k_select_topk(pooled)");
+  return BLAST_OK;
+}
+
+// The dense form of a packed matrix: W_new of prune_weights() (BLaST Sec. 3.2), zeros outside the stored blocks.
+extern "C" int blast_bsr_unpack(const blast_bsr_view* Wp, uint16_t* W, int64_t ldw, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!Wp || !Wp->row_ptr || Wp->nnz < 0) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_shape(Wp->rows, Wp->cols, Wp->b)) return rc;
+  const int64_t nbr = Wp->rows / Wp->b, nbc = Wp->cols / Wp->b, n = nbr * nbc;
+  if (n == 0) return BLAST_OK;
+  if (!W || ldw < Wp->cols || ldw % 8 || !blast::aligned(W, 16)) return BLAST_ERR_INVALID_ARG;
+  if (Wp->nnz > 0 && (!Wp->col_idx || !Wp->vals || !blast::aligned(Wp->vals, 16))) return BLAST_ERR_INVALID_ARG;
+  k_unpack_blocks<<<dim3((unsigned)n), dim3(256), 0, stream>>>(Wp->row_ptr, Wp->col_idx, Wp->vals, (int)nbc, Wp->b, W, ldw);
+  BLAST_LAUNCH_CHECK("k_unpack_blocks");
   return BLAST_OK;
 }

@@ -116,6 +116,9 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     assert L.blast_pooled_topk_mask(None, 128, 128, 128, 64, 0.5, None, None, 0, None) == -1
     assert L.blast_pooled_topk_mask(None, 128, 128, 100, 64, 0.5, None, None, 0, None) == -2
     assert L.blast_pooled_topk_mask_workspace(128, 128, 64) >= 4 * 8
+    assert L.blast_bsr_unpack(None, None, 128, None) == -1
+    assert L.blast_bsr_unpack(C.byref(g), None, 128, None) == -1  # W null
+    assert L.blast_bsr_unpack(C.byref(bad48), None, 96, None) == -3
     # E5M2 entry points
     assert L.blast_quantize_e5m2(None, -1, None, None) == -1
     assert L.blast_quantize_e5m2(None, 0, None, None) == 0

@@ -136,3 +136,27 @@ def test_pooled_topk_mask_ties_and_pack(api):
     ref = orc.pack(W, b, want)
     torch.cuda.synchronize()
     assert dev.nnz == ref.nnz and np.array_equal(dev.col_idx.cpu().numpy()[: ref.nnz], ref.col_idx)
+
+
+@pytest.mark.parametrize("b", [16, 32, 64, 128])
+def test_unpack_is_the_inverse_of_pack(api, b):
+    """prune_weights(): the dense pruned weight equals W (.) mask bit for bit, regrown blocks are zero, and a
+    strided, poisoned destination is fully overwritten."""
+    import torch
+
+    rng = np.random.default_rng(9970 + b)
+    rows, cols = 6 * b, 5 * b
+    W = synth.gauss_bf16(rng, (rows, cols), 0.05)
+    mask = synth.uniform_mask(rng, rows // b, cols // b, 0.6)
+    mask[1, :] = 0
+    mask[2, 3] = 2  # a regrown block
+    dev = api.bsr_pack(to_dev(W), b, mask=mask_dev(mask))
+    ref = orc.pack(W, b, mask)
+    big = torch.full((rows, cols + 8), -1, dtype=torch.int16, device="cuda:0")
+    out = api.bsr_unpack(dev, out=big.view(torch.bfloat16)[:, :cols])
+    torch.cuda.synchronize()
+    got = bits_of(out)
+    assert np.array_equal(got, orc.unpack(ref))
+    keep = np.kron((mask == 1).astype(np.uint16), np.ones((b, b), dtype=np.uint16))
+    assert np.array_equal(got, W * keep)
+    assert np.all(big.cpu().numpy()[:, cols:] == -1)  # nothing written past the row width
