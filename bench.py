@@ -420,6 +420,9 @@ def main():
     from tests.helpers import mask_dev, to_dev
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    from paper_2507_03117_amd import build as hip_build
+
+    hip_build.ensure_built()
     api.lib()
     wl = synth.WORKLOADS[args.workload]
     assert wl.kind == "mlp"

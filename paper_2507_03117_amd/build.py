@@ -35,5 +35,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only if no library is there (tests, the smoke check and the benchmark call this; the binding itself
+    never builds and raises when the library is missing)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

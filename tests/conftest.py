@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the C-ABI HIP library)")
+    # the tests load what is built; only if nothing is, build once (hipcc cross-compiles without a GPU)
+    from paper_2507_03117_amd import build as hip_build
+
+    hip_build.ensure_built()
 
 
 def _has_gpu() -> bool:
