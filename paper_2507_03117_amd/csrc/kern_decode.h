@@ -82,10 +82,9 @@ enum DecRole { kDecAlone = 0, kDecProducer = 1, kDecConsumer = 2 };
 constexpr int kDecMaxSpins = 1 << 19;  // polls of ~0.3 us each before a consumer gives up (never hang the GPU)
 
 // XSMALL: the activation tile of a block holds only as many token rows as one copy instruction brings
-// (512 / B); valid when T does not exceed that.  It shrinks a ring slot, hence allows a deeper ring or
-// more workgroups per CU at the token counts that matter most for decoding.
-// FUSED: the instance runs inside the single-launch MLP, where a smaller ring lets the producer and the
-// consumer workgroups of one layer be resident together.
+// (512 / B); valid when T does not exceed that.  It shrinks a ring slot, hence allows more workgroups
+// per CU at the token counts that matter most for decoding.
+// FUSED: the instance runs inside the single-launch MLP (same ring; kept as a separate configuration point).
 template <int B, bool DUAL, int NTT, bool XSMALL = false, bool FUSED = false>
 struct DecCfg {
   static_assert(!XSMALL || (NTT == 1 && B >= 64), "small activation tiles: one token group, at least 8 chunks per row");
@@ -98,7 +97,10 @@ struct DecCfg {
   static constexpr int XB = XR * B * 2;                   // its bytes
   static constexpr int NIX = XB / 1024;                   // copy instructions per activation tile
   static constexpr int SLOT = SLB + XB;
-  static constexpr int NSLOT = FUSED ? ((B == 128) ? 2 : 3) : ((B == 128) ? (XSMALL ? 3 : 2) : ((NTT == 1) ? 4 : 3));
+  // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
+  // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
+  // the small activation tile, four at b = 64), and every extra slot costs residents.
+  static constexpr int NSLOT = 2;
   static constexpr int OPS = NI + NIX;        // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * NSLOT * SLOT;
