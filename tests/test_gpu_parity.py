@@ -579,3 +579,29 @@ def test_mlp_decode_with_a_very_long_down_row(api, T):
         torch.cuda.synchronize()
         check_close(y.cpu().numpy().T, want, f"mlp long down row T={T}")
     assert not y.cpu().numpy()[:, 2 * b:3 * b].any()
+
+
+@pytest.mark.parametrize("T", [3, 20])
+def test_mlp2_decode_with_a_very_long_second_row(api, T):
+    """Two-matrix form of the case above: the first product (with its activation) carries the side workgroups
+    that clear the rows the chunked second product accumulates into."""
+    import torch
+
+    rng = np.random.default_rng(8700 + T)
+    b, E, nbi = 64, 256, 272
+    I = nbi * b
+    w1, w2 = (synth.gauss_bf16(rng, s, 0.03) for s in ((I, E), (E, I)))
+    m1 = synth.uniform_mask(rng, nbi, E // b, 0.5)
+    m2 = synth.uniform_mask(rng, E // b, nbi, 0.9)
+    m2[1, :] = 1
+    m2[3, :] = 0
+    d1, r1 = pack_both(api, w1, b, mask=m1)
+    d2, r2 = pack_both(api, w2, b, mask=m2)
+    assert d2.max_row_blocks == nbi
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    want = orc.mlp2(r1, r2, x, activation="gelu")
+    for _ in range(2):
+        y = api.sparse_mlp2(d1, d2, to_dev(x), act="gelu", out=torch.full((T, E), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, want, f"mlp2 long second row T={T}")
+    assert not y.cpu().numpy()[:, 3 * b:4 * b].any()
