@@ -5,7 +5,12 @@
  * pruning + packing of a weight matrix into a block-compressed format
  * (Sec. 3.2, Sec. 3.4.1), the block-sparse matrix product built on it
  * (Sec. 3.4, Listing 2) and the fused block-sparse SwiGLU MLP (Eq. (1),
- * Sec. 3.4.3).
+ * Sec. 3.4.3).  Around that path it also holds the two-matrix MLP of the
+ * GPT-2 family (Sec. 4), the two backward products of a block-sparse weight
+ * (Sec. 3.2, Sec. 3.4.1), the mask update of the prune-and-grow step with its sparsity
+ * schedule (Sec. 3.2, Sec. 3.3, Algorithm 1), the pooled top-k mask used for
+ * post-training sparsification (Sec. 3.3) and the product on 8-bit E5M2
+ * operands (Sec. 5.2).
  *
  * Conventions
  *  - Weights are `out x in`, row-major, like a linear layer's weight: W is
