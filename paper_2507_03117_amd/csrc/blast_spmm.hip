@@ -159,7 +159,7 @@ int launch_stream(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
   return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, stream);
 }
 
-template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL = false>
+template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL = 0>
 int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   DecArgs d{};
   d.m0 = a.m0;
@@ -232,7 +232,10 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
     // rows cut into chunks accumulate with fp32 atomics: only for fp32 output without an activation
     if (plan.hdr && !a.y_bf16 && a.act < 0) {
       if constexpr (B >= 64) {
-        if (a.T <= 512 / B) return launch_decode_ntt<B, false, 1, true, true>(a, plan, stream);
+        if (a.T <= 512 / B) return launch_decode_ntt<B, false, 1, true, 1>(a, plan, stream);
+      }
+      if constexpr (B == 128) {
+        if (a.T <= 8) return launch_decode_ntt<B, false, 1, true, 2>(a, plan, stream);
       }
       if (a.T <= 16 || B == 128) return launch_decode_ntt<B, false, 1, true>(a, plan, stream);
       return launch_decode_ntt<B, false, 2, true>(a, plan, stream);
@@ -240,8 +243,12 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
   }
   ChunkPlan side{};  // no chunks; only the side job travels on
   side.zero_job = plan.zero_job;
+  // the smallest activation tile that holds T token rows: 512 / B rows, at b = 128 also twice that
   if constexpr (B >= 64) {
-    if (a.T <= 512 / B) return launch_decode_ntt<B, DUAL, 1, false, true>(a, side, stream);
+    if (a.T <= 512 / B) return launch_decode_ntt<B, DUAL, 1, false, 1>(a, side, stream);
+  }
+  if constexpr (B == 128) {
+    if (a.T <= 8) return launch_decode_ntt<B, DUAL, 1, false, 2>(a, side, stream);
   }
   // 128-wide blocks: two token tiles per slot would leave room for one workgroup per CU only
   if (a.T <= 16 || B == 128) return launch_decode_ntt<B, DUAL, 1, false>(a, side, stream);
@@ -488,7 +495,7 @@ unsigned long long next_token() {
   return counter.fetch_add(0x9E3779B97F4A7C15ull) | 1ull;
 }
 
-template <int B, int NTT, bool XSMALL, bool GATED>
+template <int B, int NTT, int XSMALL, bool GATED>
 int launch_mlp_decode(const DecArgs& p, const DecArgs& c, hipStream_t stream) {
   using CP = DecCfg<B, GATED, NTT, XSMALL, true>;  // the producer's footprint is never below the consumer's
   static bool lds_set[64] = {};

@@ -81,19 +81,21 @@ __device__ __forceinline__ void decode_zero_job(const DecArgs& a, int ci) {
 enum DecRole { kDecAlone = 0, kDecProducer = 1, kDecConsumer = 2 };
 constexpr int kDecMaxSpins = 1 << 19;  // polls of ~0.3 us each before a consumer gives up (never hang the GPU)
 
-// XSMALL: the activation tile of a block holds only as many token rows as one copy instruction brings
-// (512 / B); valid when T does not exceed that.  It shrinks a ring slot, hence allows more workgroups
-// per CU at the token counts that matter most for decoding.
+// XSMALL > 0: the activation tile of a block holds only as many token rows as XSMALL copy instructions
+// bring (XSMALL * 512 / B); valid when T does not exceed that.  It shrinks a ring slot, hence allows more
+// workgroups per CU at the token counts that matter most for decoding, and it lowers the activation bytes
+// that travel with every weight slice.
 // FUSED: the instance runs inside the single-launch MLP (same ring; kept as a separate configuration point).
-template <int B, bool DUAL, int NTT, bool XSMALL = false, bool FUSED = false>
+template <int B, bool DUAL, int NTT, int XSMALL = 0, bool FUSED = false>
 struct DecCfg {
-  static_assert(!XSMALL || (NTT == 1 && B >= 64), "small activation tiles: one token group, at least 8 chunks per row");
+  static_assert(!XSMALL || (NTT == 1 && B >= 64 && XSMALL * 512 / B < 16),
+                "small activation tiles: one token group, at least 8 chunks per row, fewer than 16 token rows");
   static constexpr int SLICES = B / 16;       // 16-row slices per block row
   static constexpr int KST = B / 32;          // 32-wide k-steps per block
   static constexpr int SLB = 16 * B * 2;      // bytes of one 16-row slice of a block (= of a 16-token activation tile)
   static constexpr int NI = SLB / 1024;       // wave-wide copy instructions per slice
   static constexpr int CPRW = B / 8;          // 16-byte chunks per row
-  static constexpr int XR = XSMALL ? 512 / B : 16 * NTT;  // token rows of the activation tile
+  static constexpr int XR = XSMALL ? XSMALL * 512 / B : 16 * NTT;  // token rows of the activation tile
   static constexpr int XB = XR * B * 2;                   // its bytes
   static constexpr int NIX = XB / 1024;                   // copy instructions per activation tile
   static constexpr int SLOT = SLB + XB;
@@ -116,7 +118,7 @@ struct DecCfg {
 // producer publishes its slice of H, the consumer waits for the slices of H its blocks will read).
 // POST: a single-matrix product whose sums go through the activation a.act before they are stored (the
 // first half of a two-matrix MLP).
-template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL, int ROLE, bool POST = false>
+template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL, int ROLE, bool POST = false>
 __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, const int t_base, unsigned char* smem) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
   static_assert(!POST || (!DUAL && !CHUNK), "an activation on the output needs complete sums of a single matrix");
@@ -338,7 +340,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   }
 }
 
-template <int B, bool DUAL, int NTT, bool CHUNK, bool XSMALL, bool POST = false>
+template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL, bool POST = false>
 __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // More tokens than one tile holds mean more workgroups per unit, each re-reading the unit's weight
@@ -359,7 +361,7 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
 // (args `p`; H = act(G) (.) U with GATED, H = act(W1 X) without), workgroups [n_units, n_units + c.n_units)
 // the last projection (args `c`, whose X is that H).  A consumer only ever waits for producers, which wait for nothing and have lower
 // workgroup ids, hence are dispatched first: the wait always ends (and is bounded besides).
-template <int B, int NTT, bool XSMALL, bool GATED = true>
+template <int B, int NTT, int XSMALL, bool GATED = true>
 __global__ __launch_bounds__(256) void k_mlp_decode(const DecArgs p, const DecArgs c) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int blk = blockIdx.x;

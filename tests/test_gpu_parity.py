@@ -160,6 +160,20 @@ def test_spmm_small_shapes(api, b, T):
     assert not yh[:, b:2 * b].any()  # empty block row is written as exact zeros
 
 
+@pytest.mark.parametrize("b", [64, 128])
+@pytest.mark.parametrize("T", [4, 5, 8, 9, 16])
+def test_spmm_token_counts_around_the_small_activation_tiles(api, b, T):
+    """The decode kernel copies activation tiles of 4, 8 or 16 token rows depending on T and b: every
+    boundary, on both sides, with distinct values in every token row."""
+    import torch
+
+    w, mask, x = synth.small_case(1500 + b + T, 6 * b, 7 * b, b, 0.45, T, empty_rows=(2,), full_rows=(4,))
+    dev, ref = pack_both(api, w, b, mask=mask)
+    y = api.bsr_spmm(dev, to_dev(x))
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, orc.spmm(ref, x), f"spmm b={b} T={T}")
+
+
 @pytest.mark.parametrize("b,T", [(32, 5), (64, 70), (128, 33)])
 def test_spmm_feature_major_and_bf16_out(api, b, T):
     import torch
