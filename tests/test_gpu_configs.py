@@ -104,6 +104,7 @@ def test_llama405b_zipf_mlp(api):
     wl = synth.WORKLOADS["llama405b_b128_s95_zipf"]
     # decode passes of the same layer (the bandwidth-bound case bench.py reports), then its prefill pass
     _run_mlp(api, wl.name, 1, 1, expect_nnz=2662)
+    _run_mlp(api, wl.name, 6, 3)  # the 8-row activation tile of 128-wide blocks, rows cut into chunks
     _run_mlp(api, wl.name, 16, 3)
     _run_mlp(api, wl.name, 2048, 8, expect_nnz=2662)
     # the load-balance stress is real: some block rows are full, the median row is nearly empty
