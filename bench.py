@@ -570,7 +570,7 @@ def main():
     if not args.no_large_decode and args.workload == "llama1b_b64_s90":
         del sets
         torch.cuda.empty_cache()
-        out["decode_hbm_bound"] = decode_sweep("llama405b_b128_s95_zipf", (1, 16), 30, 5)
+        out["decode_hbm_bound"] = decode_sweep("llama405b_b128_s95_zipf", (1, 8, 16), 30, 5)
 
     if not args.no_mlp2 and args.workload == "llama1b_b64_s90":
         torch.cuda.empty_cache()
