@@ -384,6 +384,54 @@ def test_mlp_one_launch_reuses_workspace(api, b, T):
         check_close(y.cpu().numpy().T, orc.mlp(rg, ru, rd, x), f"one launch b={b} T={T} call {rep}")
 
 
+@pytest.mark.parametrize("T", [3, 40, 300])
+def test_mlp_from_two_host_threads_on_two_streams(api, T):
+    """Calls on distinct streams from distinct host threads, each with its own output and workspace, may
+    overlap on the GPU (the single-launch form at T = 3 included: its slots live in the call's workspace)."""
+    import threading
+
+    import torch
+
+    b, E, I = 64, 256, 512
+    cases = []
+    for seed in (3300, 3301):
+        rng = np.random.default_rng(seed + T)
+        g, u, d = (synth.gauss_bf16(rng, s, 0.05) for s in ((I, E), (I, E), (E, I)))
+        mg, mu = (synth.uniform_mask(rng, I // b, E // b, 0.5) for _ in range(2))
+        md = synth.uniform_mask(rng, E // b, I // b, 0.5)
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        packs = [pack_both(api, w, b, mask=m) for w, m in ((g, mg), (u, mu), (d, md))]
+        (dg, rg), (du, ru), (dd, rd) = packs
+        cases.append(dict(dev=(dg, du, dd), x=to_dev(x), want=orc.mlp(rg, ru, rd, x),
+                          ws=torch.empty(max(api.mlp_workspace_bytes(dg, du, dd, T), 256), dtype=torch.uint8, device="cuda:0"),
+                          out=torch.empty((T, E), dtype=torch.float32, device="cuda:0"), got=[], err=None))
+    torch.cuda.synchronize()
+
+    def worker(c):
+        try:
+            st = torch.cuda.Stream()  # default priority
+            with torch.cuda.stream(st):
+                for _ in range(20):
+                    c["out"].fill_(float("nan"))
+                    api.sparse_mlp(*c["dev"], c["x"], out=c["out"], ws=c["ws"])
+                    c["got"].append(c["out"].clone())
+            st.synchronize()
+        except Exception as e:  # surfaced in the main thread
+            c["err"] = e
+
+    threads = [threading.Thread(target=worker, args=(c,)) for c in cases]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for k, c in enumerate(cases):
+        assert c["err"] is None, c["err"]
+        assert len(c["got"]) == 20
+        for y in c["got"]:
+            check_close(y.cpu().numpy().T, c["want"], f"thread {k} T={T}")
+
+
 @pytest.mark.parametrize("T", [8, 300])
 def test_mlp_under_graph_capture(api, T):
     """The call records into a graph (no allocation, no synchronisation, no per-launch host state that a
