@@ -40,11 +40,12 @@ PEAK_HBM_GBS = 8000.0
 # Source: profiles/bench_llama1b_b64_s90_hbm_traffic.txt (read x2.0, write x1.0; counters sit between each XCD's
 # L2 and the fabric).  Keys: (kernel, tokens) of the default workload.
 MEASURED_TRAFFIC_BYTES = {
-    ("gate_up", 2048): 62.96e6 + 34.46e6,
-    ("mlp", 1): 10.51e6 + 0.03e6,
-    ("mlp", 16): 12.49e6 + 0.41e6,
+    ("gate_up", 2048): 62.96e6 + 34.49e6,
+    ("mlp", 1): 10.50e6 + 0.03e6,
+    ("mlp", 16): 12.56e6 + 0.41e6,
     ("llama405b_b128_s95_zipf", 1): (175.63e6 + 0.12e6) + (88.61e6 + 0.13e6),
-    ("llama405b_b128_s95_zipf", 16): (181.42e6 + 1.92e6) + (112.35e6 + 2.01e6),
+    ("llama405b_b128_s95_zipf", 8): (178.13e6 + 0.96e6) + (97.70e6 + 1.00e6),
+    ("llama405b_b128_s95_zipf", 16): (181.38e6 + 1.92e6) + (112.39e6 + 2.01e6),
 }
 
 
