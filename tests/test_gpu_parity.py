@@ -194,6 +194,37 @@ def test_spmm_feature_major_and_bf16_out(api, b, T):
     assert (np.abs(got - want) <= ulp).all()
 
 
+@pytest.mark.parametrize("T", [262143, 262145])
+def test_spmm_token_counts_on_both_sides_of_the_32_bit_offset_limit(api, T):
+    """The streaming kernel addresses the activations of one block column with 32-bit byte offsets: with 8192
+    features a token row is 16 KiB, so 262143 tokens are the most it takes and 262145 go to the kernel with
+    64-bit addressing.  Token rows repeat with a period (4099) that no power-of-two wrap maps onto itself."""
+    import torch
+
+    b, rows, cols, period = 64, 128, 8192, 4099
+    rng = np.random.default_rng(1700)
+    w = synth.gauss_bf16(rng, (rows, cols), 0.05)
+    mask = synth.uniform_mask(rng, rows // b, cols // b, 0.9)
+    mask[0, -1] = 1  # the last block column, where the offsets are largest
+    base = synth.gauss_bf16(rng, (period, cols), 1.0)
+    dev, ref = pack_both(api, w, b, mask=mask)
+    idx = torch.arange(T, device="cuda:0") % period
+    x = to_dev(base).index_select(0, idx)  # [T, cols] bf16, 4.3 GB
+    y = api.bsr_spmm(dev, x)
+    torch.cuda.synchronize()
+    sample = np.array([0, 1, 255, 256, 4098, 4099, 131071, 131072, 131073, T - 257, T - 256, T - 2, T - 1])
+    got = y[torch.from_numpy(sample).to("cuda:0")].cpu().numpy()
+    want = orc.spmm(ref, base[sample % period])  # [rows, n]
+    check_close(got.T, want, f"spmm T={T}")
+    # every token tile agrees with the tile one period of whole tiles earlier (same inputs, other addresses)
+    span = 256 * period
+    if T > span + 512:
+        assert torch.equal(y[span: span + 512], y[:512])
+        assert torch.equal(y[T - 300:], y[T - 300 - span: T - span])
+    del x, y
+    torch.cuda.empty_cache()
+
+
 def test_spmm_unaligned_token_major_uses_slow_loads(api):
     import torch
 
