@@ -89,6 +89,31 @@ def test_llama1b_mlp(api, T):
     _run_mlp(api, "llama1b_b64_s90", T, 64, expect_nnz=409)
 
 
+def test_llama1b_mlp_beyond_the_32_bit_offset_limit(api):
+    """262145 tokens: a token row of H is 16 KiB, so the second product's activations no longer fit the 32-bit
+    byte offsets of the streaming kernel and it takes the kernel with 64-bit addressing; the first product still
+    streams (X rows are 4 KiB) and writes 4.3 GB of H.  Token rows repeat with period 4099 (no power-of-two wrap
+    maps a row onto an equal one)."""
+    import torch
+
+    wl, packs = _packed(api, "llama1b_b64_s90")
+    (dg, rg), (du, ru), (dd, rd) = packs
+    T, period = 262145, 4099
+    base = synth.make_x(wl, period)
+    x = to_dev(base).index_select(0, torch.arange(T, device="cuda:0") % period)
+    y = api.sparse_mlp(dg, du, dd, x)
+    torch.cuda.synchronize()
+    sel = np.array([0, 255, 256, 4098, 4099, 131072, 131073, 262143, 262144])
+    got = y[torch.from_numpy(sel).to("cuda:0")].cpu().numpy()
+    check_close(got.T, orc.mlp(rg, ru, rd, np.ascontiguousarray(base[sel % period])), "1B MLP at 262145 tokens")
+    # equal token rows give equal output rows wherever they sit (an output element's sum does not depend on
+    # its place in a tile): every row against the one a period earlier, over the whole output
+    assert torch.equal(y[period:], y[:-period])
+    assert torch.isfinite(y).all()
+    del x, y
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("name,nnz", [("llama3b_b64_s70", 1843), ("llama3b_b64_s80", 1228), ("llama3b_b64_s90", 614),
                                       ("llama3b_b64_s95", 307)])
 def test_llama3b_topk_mlp(api, name, nnz):

@@ -216,11 +216,9 @@ def test_spmm_token_counts_on_both_sides_of_the_32_bit_offset_limit(api, T):
     got = y[torch.from_numpy(sample).to("cuda:0")].cpu().numpy()
     want = orc.spmm(ref, base[sample % period])  # [rows, n]
     check_close(got.T, want, f"spmm T={T}")
-    # every token tile agrees with the tile one period of whole tiles earlier (same inputs, other addresses)
-    span = 256 * period
-    if T > span + 512:
-        assert torch.equal(y[span: span + 512], y[:512])
-        assert torch.equal(y[T - 300:], y[T - 300 - span: T - span])
+    # equal token rows give equal output rows wherever they sit (an output element's sum does not depend on
+    # its place in a tile): every row against the one a period earlier, over the whole output
+    assert torch.equal(y[period:], y[:-period])
     del x, y
     torch.cuda.empty_cache()
 
