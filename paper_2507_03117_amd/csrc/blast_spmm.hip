@@ -299,6 +299,21 @@ int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, con
       default: break;
     }
   }
+  if (a.x_vec && a.T > 0 && !small_x && b >= 32) {
+    // More tokens than 32-bit offsets reach: the same kernels over token ranges that each fit (whole
+    // 256-token tiles, so no range ends inside a tile of the next one).
+    const int64_t range = (((int64_t)1 << 32) - 1) / (a.sxt * 2) / 256 * 256;
+    if (range >= 256) {
+      for (int64_t t0 = 0; t0 < a.T; t0 += range) {
+        TileArgs part = a;
+        part.T = (int)((a.T - t0 < range) ? a.T - t0 : range);
+        part.X = a.X + t0 * a.sxt;
+        part.Y = static_cast<char*>(a.Y) + t0 * a.syt * (a.y_bf16 ? 2 : 4);
+        if (int rc = dispatch_tile<DUAL>(b, part, nnz, stream, plan)) return rc;
+      }
+      return BLAST_OK;
+    }
+  }
   if (a.x_vec && a.T > 0 && small_x) {
     switch (b) {
       case 32: return launch_stream<32, DUAL>(a, plan, stream);

@@ -91,8 +91,8 @@ def test_llama1b_mlp(api, T):
 
 def test_llama1b_mlp_beyond_the_32_bit_offset_limit(api):
     """262145 tokens: a token row of H is 16 KiB, so the second product's activations no longer fit the 32-bit
-    byte offsets of the streaming kernel and it takes the kernel with 64-bit addressing; the first product still
-    streams (X rows are 4 KiB) and writes 4.3 GB of H.  Token rows repeat with period 4099 (no power-of-two wrap
+    byte offsets of one launch of the streaming kernel and the product is cut into two token ranges; the first
+    product still runs as one launch (X rows are 4 KiB) and writes 4.3 GB of H.  Token rows repeat with period 4099 (no power-of-two wrap
     maps a row onto an equal one)."""
     import torch
 

@@ -197,8 +197,8 @@ def test_spmm_feature_major_and_bf16_out(api, b, T):
 @pytest.mark.parametrize("T", [262143, 262145])
 def test_spmm_token_counts_on_both_sides_of_the_32_bit_offset_limit(api, T):
     """The streaming kernel addresses the activations of one block column with 32-bit byte offsets: with 8192
-    features a token row is 16 KiB, so 262143 tokens are the most it takes and 262145 go to the kernel with
-    64-bit addressing.  Token rows repeat with a period (4099) that no power-of-two wrap maps onto itself."""
+    features a token row is 16 KiB, so 262143 tokens are the most one launch takes and 262145 are cut into two
+    token ranges.  Token rows repeat with a period (4099) that no power-of-two wrap maps onto itself."""
     import torch
 
     b, rows, cols, period = 64, 128, 8192, 4099
