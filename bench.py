@@ -141,8 +141,10 @@ def time_mlp(api, torch, sets, x, T, steps, warmup, ws):
     return wall_ms, p1, p2, tot
 
 
-def decode_sweep(workload: str, tokens, steps: int, warmup: int):
-    """Decode-sized passes of another workload, packed here: list of per-token-count records."""
+def decode_sweep(workload: str, tokens, steps: int, warmup: int, time_pack: bool = False):
+    """Decode-sized passes of another workload, packed here: list of per-token-count records.
+    time_pack: also time block-norm pruning + packing of the gate matrix at the workload's sparsity (on a
+    matrix of this size the packer is bound by reading the dense weight once)."""
     import torch
 
     from paper_2507_03117_amd import api, synth
@@ -152,8 +154,21 @@ def decode_sweep(workload: str, tokens, steps: int, warmup: int):
     inp = synth.make_mlp(wl)
     b = wl.b
     packed = []
+    pack_rec = None
     for l in (inp.gate, inp.up, inp.down):
         w_ = to_dev(l.W)
+        if time_pack and pack_rec is None:
+            for _ in range(2):
+                api.bsr_pack(w_, b, sparsity=wl.sparsity)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                api.bsr_pack(w_, b, sparsity=wl.sparsity)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) / 5 * 1e3
+            dense = w_.numel() * 2
+            pack_rec = {"ms_gate_matrix_topk": ms, "dense_MB": dense / 1e6, "dense_GBps": dense / ms / 1e6,
+                        "frac_hbm": dense / ms / 1e6 / PEAK_HBM_GBS}
         packed.append(api.bsr_pack(w_, b, mask=mask_dev(l.mask), nnz_cap=int(l.mask.sum())) if l.mask is not None
                       else api.bsr_pack(w_, b, sparsity=l.sparsity))
         del w_
@@ -175,8 +190,11 @@ def decode_sweep(workload: str, tokens, steps: int, warmup: int):
                     "alg_MB": alg_bytes / 1e6, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
                     "GBps_events": alg_bytes / (tot * 1e-3) / 1e9,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, T))})
-    return {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
-            "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
+    rec = {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
+           "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
+    if pack_rec is not None:
+        rec["pack"] = pack_rec
+    return rec
 
 
 def two_matrix_mlp(workload: str, steps: int, warmup: int, cpu: bool):
@@ -571,7 +589,7 @@ def main():
     if not args.no_large_decode and args.workload == "llama1b_b64_s90":
         del sets
         torch.cuda.empty_cache()
-        out["decode_hbm_bound"] = decode_sweep("llama405b_b128_s95_zipf", (1, 8, 16), 30, 5)
+        out["decode_hbm_bound"] = decode_sweep("llama405b_b128_s95_zipf", (1, 8, 16), 30, 5, time_pack=True)
 
     if not args.no_mlp2 and args.workload == "llama1b_b64_s90":
         torch.cuda.empty_cache()
