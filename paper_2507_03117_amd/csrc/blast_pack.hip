@@ -113,27 +113,64 @@ __device__ __forceinline__ unsigned long long order_key(unsigned long long bits)
 // An 8-pass most-significant-digit radix select finds the n_keep-th largest
 // pattern; everything above it is kept, and of the entries equal to it the
 // first ones in index order fill the remaining quota.
+// The passes read the keys from global memory only until the keys that still share the selected prefix
+// fit in LDS (kSelectCand of them); those are then collected once and the remaining passes run on LDS.
+constexpr int kSelectCand = 4096;
+
 __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__ score, int64_t n, int64_t n_keep,
                                                       uint8_t* __restrict__ mask) {
+  __shared__ unsigned long long cand[kSelectCand];
   __shared__ unsigned hist[256];
   __shared__ unsigned long long s_prefix;
   __shared__ long long s_remaining;
   __shared__ int wave_tot[16];
   __shared__ long long s_running;
+  __shared__ long long s_eq_total;
+  __shared__ int s_ncand;  // < 0: the candidates are still the whole array
+  __shared__ int s_fill;
+  __shared__ unsigned s_h;
   const unsigned long long* key = reinterpret_cast<const unsigned long long*>(score);
+  const int lane = lane_id();
   if (threadIdx.x == 0) {
     s_prefix = 0ull;
     s_remaining = n_keep;
     s_running = 0;
+    s_eq_total = 0;
+    s_ncand = n <= kSelectCand ? (int)n : -1;
+    s_fill = 0;
+    s_h = 0u;
   }
+  if (n <= kSelectCand)
+    for (int i = threadIdx.x; i < (int)n; i += blockDim.x) cand[i] = order_key(key[i]);
   for (int pass = 7; pass >= 0; --pass) {
     if (threadIdx.x < 256) hist[threadIdx.x] = 0u;
     __syncthreads();
     const unsigned long long prefix = s_prefix;
     const unsigned long long himask = (pass == 7) ? 0ull : (~0ull << (8 * (pass + 1)));
-    for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
-      const unsigned long long k = order_key(key[i]);
-      if ((k & himask) == prefix) atomicAdd(&hist[(unsigned)(k >> (8 * pass)) & 255u], 1u);
+    const int ncand = s_ncand;
+    if (ncand >= 0) {
+      for (int i = threadIdx.x; i < ncand; i += blockDim.x) {
+        const unsigned long long k = cand[i];
+        if ((k & himask) == prefix) atomicAdd(&hist[(unsigned)(k >> (8 * pass)) & 255u], 1u);
+      }
+    } else {
+      // A thread adds a run of equal digits with one atomic: in the leading passes, where scores of similar
+      // magnitude all carry the same digit, every key would otherwise hit the same LDS word.
+      unsigned run_bin = 0u, run_len = 0u;
+#pragma unroll 8
+      for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
+        const unsigned long long k = order_key(key[i]);
+        if ((k & himask) == prefix) {
+          const unsigned bin = (unsigned)(k >> (8 * pass)) & 255u;
+          if (run_len != 0u && bin != run_bin) {
+            atomicAdd(&hist[run_bin], run_len);
+            run_len = 0u;
+          }
+          run_bin = bin;
+          ++run_len;
+        }
+      }
+      if (run_len != 0u) atomicAdd(&hist[run_bin], run_len);
     }
     __syncthreads();
     // Digit d of this pass: the bin where the count of larger digits, S(d), first satisfies
@@ -149,12 +186,45 @@ __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__
       if (threadIdx.x < 256 && (long long)larger < rem && rem <= (long long)larger + h) {
         s_remaining = rem - larger;
         s_prefix = prefix | ((unsigned long long)d << (8 * pass));
+        s_h = (unsigned)h;              // keys that share the prefix including this digit
+        if (pass == 0) s_eq_total = h;  // entries equal to the n_keep-th largest
       }
     }
     __syncthreads();
+    if (ncand < 0 && pass > 0 && s_h <= (unsigned)kSelectCand) {
+      // collect the keys that carry the new prefix (exactly s_h of them); their order does not matter
+      const unsigned long long newmask = ~0ull << (8 * pass), newprefix = s_prefix;
+      for (int64_t base = 0; base < n; base += 4 * (int64_t)blockDim.x) {
+        unsigned long long k[4];
+        bool in[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int64_t i = base + u * (int64_t)blockDim.x + threadIdx.x;
+          in[u] = i < n;
+          k[u] = in[u] ? order_key(key[i]) : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool take = in[u] && (k[u] & newmask) == newprefix;
+          const unsigned long long bal = __ballot(take);
+          int wbase = 0;
+          if (lane == 0 && bal != 0ull) wbase = atomicAdd(&s_fill, __popcll(bal));
+          wbase = __shfl(wbase, 0, kWave);
+          if (take) cand[wbase + __popcll(bal & ((1ull << lane) - 1ull))] = k[u];
+        }
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) s_ncand = s_fill;
+      __syncthreads();
+    }
   }
   const unsigned long long kth = s_prefix;
   const long long need_eq = s_remaining;
+  if (need_eq == s_eq_total) {
+    // every entry equal to the threshold is kept (always so when the scores are distinct): no ordering needed
+    for (int64_t i = threadIdx.x; i < n; i += blockDim.x) mask[i] = order_key(key[i]) >= kth ? 1 : 0;
+    return;
+  }
   for (int64_t base = 0; base < n; base += blockDim.x) {
     const int64_t i = base + threadIdx.x;
     const unsigned long long k = (i < n) ? order_key(key[i]) : 0ull;
@@ -259,17 +329,44 @@ __global__ __launch_bounds__(256) void k_merge_masks(const uint8_t* __restrict__
 // row_ptr2 (may be null) adds the populations of a second matrix with the same block rows.
 __global__ __launch_bounds__(256) void k_row_order(const int* __restrict__ row_ptr, const int* __restrict__ row_ptr2,
                                                    int nbr, int* __restrict__ row_order) {
+  // the populations pass through LDS in slabs: every thread compares its row with all of them
+  constexpr int kSlab = 2048;
+  __shared__ __attribute__((aligned(16))) int cnt[kSlab];
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= nbr) return;
-  int cr = row_ptr[r + 1] - row_ptr[r];
-  if (row_ptr2) cr += row_ptr2[r + 1] - row_ptr2[r];
-  int rank = 0;
-  for (int q = 0; q < nbr; ++q) {
-    int cq = row_ptr[q + 1] - row_ptr[q];
-    if (row_ptr2) cq += row_ptr2[q + 1] - row_ptr2[q];
-    rank += (cq > cr || (cq == cr && q < r)) ? 1 : 0;
+  int cr = 0;
+  if (r < nbr) {
+    cr = row_ptr[r + 1] - row_ptr[r];
+    if (row_ptr2) cr += row_ptr2[r + 1] - row_ptr2[r];
   }
-  row_order[rank] = r;
+  int rank = 0;
+  for (int base = 0; base < nbr; base += kSlab) {
+    const int m = nbr - base < kSlab ? nbr - base : kSlab;
+    __syncthreads();
+    for (int q = threadIdx.x; q < m; q += blockDim.x) {
+      int cq = row_ptr[base + q + 1] - row_ptr[base + q];
+      if (row_ptr2) cq += row_ptr2[base + q + 1] - row_ptr2[base + q];
+      cnt[q] = cq;
+    }
+    __syncthreads();
+    if (r < nbr) {
+      // four populations per LDS read, several reads in flight: a serial chain of single reads would cost
+      // one LDS round trip per row
+      int q = 0;
+#pragma unroll 4
+      for (; q + 4 <= m; q += 4) {
+        const int4 c4 = *reinterpret_cast<const int4*>(&cnt[q]);
+        rank += (c4.x > cr || (c4.x == cr && base + q < r)) ? 1 : 0;
+        rank += (c4.y > cr || (c4.y == cr && base + q + 1 < r)) ? 1 : 0;
+        rank += (c4.z > cr || (c4.z == cr && base + q + 2 < r)) ? 1 : 0;
+        rank += (c4.w > cr || (c4.w == cr && base + q + 3 < r)) ? 1 : 0;
+      }
+      for (; q < m; ++q) {
+        const int cq = cnt[q];
+        rank += (cq > cr || (cq == cr && base + q < r)) ? 1 : 0;
+      }
+    }
+  }
+  if (r < nbr) row_order[rank] = r;
 }
 
 // One workgroup per block column: its stored blocks by ascending block row; for
