@@ -131,6 +131,7 @@ __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__
   __shared__ unsigned s_h;
   const unsigned long long* key = reinterpret_cast<const unsigned long long*>(score);
   const int lane = lane_id();
+  const bool pairs_ok = (reinterpret_cast<uintptr_t>(score) & 15u) == 0;
   if (threadIdx.x == 0) {
     s_prefix = 0ull;
     s_remaining = n_keep;
@@ -157,9 +158,8 @@ __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__
       // A thread adds a run of equal digits with one atomic: in the leading passes, where scores of similar
       // magnitude all carry the same digit, every key would otherwise hit the same LDS word.
       unsigned run_bin = 0u, run_len = 0u;
-#pragma unroll 8
-      for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
-        const unsigned long long k = order_key(key[i]);
+      auto count = [&](unsigned long long raw) {
+        const unsigned long long k = order_key(raw);
         if ((k & himask) == prefix) {
           const unsigned bin = (unsigned)(k >> (8 * pass)) & 255u;
           if (run_len != 0u && bin != run_bin) {
@@ -169,7 +169,18 @@ __global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__
           run_bin = bin;
           ++run_len;
         }
+      };
+      // two keys per load, eight loads in flight: one workgroup walks the whole array, so the walk is
+      // bound by how many bytes it keeps in flight
+      const int64_t npair = pairs_ok ? n / 2 : 0;
+      const ulonglong2* key2 = reinterpret_cast<const ulonglong2*>(key);
+#pragma unroll 8
+      for (int64_t p = threadIdx.x; p < npair; p += blockDim.x) {
+        const ulonglong2 kk = key2[p];
+        count(kk.x);
+        count(kk.y);
       }
+      for (int64_t i = 2 * npair + threadIdx.x; i < n; i += blockDim.x) count(key[i]);
       if (run_len != 0u) atomicAdd(&hist[run_bin], run_len);
     }
     __syncthreads();
