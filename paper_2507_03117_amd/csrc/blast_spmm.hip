@@ -260,24 +260,44 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
 //  - up to 32 tokens the decode kernel always wins;
 //  - the single-matrix product stays ahead up to 256 tokens as long as those re-reads are small
 //    (the launch is latency bound; 13.8 us against 16.5 us at 256 tokens on a 3.3 MB matrix);
-//  - the gated product (two matrices, twice the blocks per workgroup) crosses over at about 40 tokens.
+//  - the gated product (two matrices, twice the blocks per workgroup) crosses over at about 64 tokens,
+//    unless its fullest block row is so long that the streaming kernel, which walks a whole row of the
+//    gated product in one workgroup (the activation needs complete sums, so the row cannot be cut), would
+//    spend longer on that one row than the decode kernel spends on everything (it deals a row's blocks to
+//    the four waves of b/16 workgroups).  Measured on the 405B-class layer with the Zipf mask (fullest joint
+//    row 256 blocks of 128 x 128): 183 us in the streaming kernel at 33-64 tokens, 0.7 us per block of that
+//    row; the decode kernel takes about 30 us per group of 16 tokens there (174 MB of blocks per group):
+//    89-97 us at 33-48 tokens, 122 us at 64.
 constexpr int kDecodeAlwaysTokens = 32;
 constexpr int kDecodeMaxTokens = 256;
 constexpr int64_t kDecodeMaxRereadBytes = (int64_t)64 << 20;
 
 template <bool DUAL>
-bool decode_applies(int b, const TileArgs& a, int64_t nnz) {
+bool decode_applies(int b, const TileArgs& a, int64_t nnz, int64_t max_row_blocks) {
   if (a.T <= kDecodeAlwaysTokens) return true;
-  if (DUAL || a.T > kDecodeMaxTokens) return false;
+  if (a.T > kDecodeMaxTokens) return false;
   const int64_t group = (b == 128) ? 16 : 32;
-  return nnz * b * b * 2 * ((a.T + group - 1) / group) <= kDecodeMaxRereadBytes;
+  const int64_t groups = (a.T + group - 1) / group;
+  const int64_t reread = nnz * b * b * 2 * groups;
+  if (DUAL) {
+    // small products are a chain of latencies either way; the decode kernel's chain is the shorter one for up
+    // to 64 tokens (1B / 3B shapes, b = 64: 17-19 us per MLP pass against 21-22 at 33-64 tokens; 8B shape,
+    // b = 128: 25-27 against 29-30 at 33-48 tokens; from 96 tokens on the streaming kernel is ahead)
+    if (groups <= (b == 128 ? 3 : 2) && reread <= kDecodeMaxRereadBytes) return true;
+    if (max_row_blocks <= 0 || groups > 8) return false;
+    const double row_us = (double)max_row_blocks * 0.7 * ((double)b * b / (128.0 * 128.0));  // streaming kernel, fullest row
+    const double all_us = (double)reread / 5.8e6;                                            // decode kernel, whole product
+    // only where that row is long against the fixed latencies of a launch (tens of microseconds)
+    return row_us >= 30.0 && all_us < row_us;
+  }
+  return reread <= kDecodeMaxRereadBytes;
 }
 
 template <bool DUAL>
 int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, const ChunkPlan& plan = ChunkPlan{}) {
   // the streaming kernel addresses activations with 32-bit byte offsets inside one column block
   const bool small_x = (int64_t)a.T * a.sxt * 2 < ((int64_t)1 << 32);
-  if (a.x_vec && a.T > 0 && small_x && decode_applies<DUAL>(b, a, nnz)) {
+  if (a.x_vec && a.T > 0 && small_x && decode_applies<DUAL>(b, a, nnz, plan.max_row_blocks)) {
     // The decode kernel already spreads a block row over b/16 workgroups of four waves each, so a row of n
     // blocks is n/4 block steps deep.  Chunks (a zero-fill launch plus atomics, about 8 us on the 405B-class
     // gate matrix) only pay when that depth exceeds four times the average load of a workgroup slot
@@ -489,6 +509,8 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
                   hipStream_t stream, ZeroJob* side_job = nullptr) {
   ChunkPlan side{};
   side.zero_job = side_job;
+  // upper bound of the fullest joint row (exact when the same row is the fullest of both matrices)
+  side.max_row_blocks = Wgate->max_row_blocks + (Wup ? Wup->max_row_blocks : 0);
   TileArgs g{};
   g.m0 = mat_of(Wgate);
   if (Wup) g.m1 = mat_of(Wup);

@@ -413,6 +413,29 @@ def test_mlp_one_launch_reuses_workspace(api, b, T):
         check_close(y.cpu().numpy().T, orc.mlp(rg, ru, rd, x), f"one launch b={b} T={T} call {rep}")
 
 
+@pytest.mark.parametrize("b,T", [(128, 40), (128, 100), (64, 200)])
+def test_mlp_with_a_gated_row_long_enough_to_stay_in_the_decode_kernel(api, b, T):
+    """Beyond 64 tokens the gated product normally streams; a block row that is full in both matrices keeps it
+    in the decode kernel, several token groups per unit (the streaming kernel would walk that row in one
+    workgroup)."""
+    import torch
+
+    E, I = (48 * b, 4 * b) if b == 128 else (180 * b, 4 * b)
+    rng = np.random.default_rng(3400 + b + T)
+    g, u = (synth.gauss_bf16(rng, (I, E), 0.02) for _ in range(2))
+    d = synth.gauss_bf16(rng, (E, I), 0.05)
+    mg, mu = (synth.uniform_mask(rng, I // b, E // b, 0.9) for _ in range(2))
+    mg[2, :] = 1
+    mu[2, :] = 1  # the full joint row
+    md = synth.uniform_mask(rng, E // b, I // b, 0.25)
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    (dg, rg), (du, ru), (dd, rd) = (pack_both(api, w, b, mask=m) for w, m in ((g, mg), (u, mu), (d, md)))
+    assert dg.max_row_blocks + du.max_row_blocks == 2 * (E // b)
+    y = api.sparse_mlp(dg, du, dd, to_dev(x))
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, orc.mlp(rg, ru, rd, x), f"long gated row b={b} T={T}")
+
+
 @pytest.mark.parametrize("T", [3, 40, 300])
 def test_mlp_from_two_host_threads_on_two_streams(api, T):
     """Calls on distinct streams from distinct host threads, each with its own output and workspace, may
