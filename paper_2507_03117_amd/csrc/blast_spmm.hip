@@ -237,7 +237,7 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
       if constexpr (B == 128) {
         if (a.T <= 8) return launch_decode_ntt<B, false, 1, true, 2>(a, plan, stream);
       }
-      if (a.T <= 16 || B == 128) return launch_decode_ntt<B, false, 1, true>(a, plan, stream);
+      if (a.T <= 16) return launch_decode_ntt<B, false, 1, true>(a, plan, stream);
       return launch_decode_ntt<B, false, 2, true>(a, plan, stream);
     }
   }
@@ -250,9 +250,9 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
   if constexpr (B == 128) {
     if (a.T <= 8) return launch_decode_ntt<B, DUAL, 1, false, 2>(a, side, stream);
   }
-  // 128-wide blocks: two token tiles per slot would leave room for one workgroup per CU only
-  if (a.T <= 16 || B == 128) return launch_decode_ntt<B, DUAL, 1, false>(a, side, stream);
-  return launch_decode_ntt<B, DUAL, 2, false>(a, side, stream);  // groups of 32 tokens along gridDim.y
+  if (a.T <= 16) return launch_decode_ntt<B, DUAL, 1, false>(a, side, stream);
+  // groups of 32 tokens along gridDim.y (128-wide blocks: with a single activation tile per wave, see DecCfg)
+  return launch_decode_ntt<B, DUAL, 2, false>(a, side, stream);
 }
 
 // Crossover with the streaming kernel, from token sweeps on the 1B-shaped MLP.  The decode kernel
@@ -266,8 +266,8 @@ int launch_decode(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) 
 //    spend longer on that one row than the decode kernel spends on everything (it deals a row's blocks to
 //    the four waves of b/16 workgroups).  Measured on the 405B-class layer with the Zipf mask (fullest joint
 //    row 256 blocks of 128 x 128): 183 us in the streaming kernel at 33-64 tokens, 0.7 us per block of that
-//    row; the decode kernel takes about 30 us per group of 16 tokens there (174 MB of blocks per group):
-//    89-97 us at 33-48 tokens, 122 us at 64.
+//    row; the decode kernel takes about 42 us per group of 32 tokens there (174 MB of blocks per group):
+//    84-93 us at 33-64 tokens, 120-127 us at 65-96, 168 us at 128.
 constexpr int kDecodeAlwaysTokens = 32;
 constexpr int kDecodeMaxTokens = 256;
 constexpr int64_t kDecodeMaxRereadBytes = (int64_t)64 << 20;
@@ -276,17 +276,17 @@ template <bool DUAL>
 bool decode_applies(int b, const TileArgs& a, int64_t nnz, int64_t max_row_blocks) {
   if (a.T <= kDecodeAlwaysTokens) return true;
   if (a.T > kDecodeMaxTokens) return false;
-  const int64_t group = (b == 128) ? 16 : 32;
+  const int64_t group = 32;  // tokens per unit of the decode kernel beyond 16 tokens
   const int64_t groups = (a.T + group - 1) / group;
   const int64_t reread = nnz * b * b * 2 * groups;
   if (DUAL) {
     // small products are a chain of latencies either way; the decode kernel's chain is the shorter one for up
     // to 64 tokens (1B / 3B shapes, b = 64: 17-19 us per MLP pass against 21-22 at 33-64 tokens; 8B shape,
-    // b = 128: 25-27 against 29-30 at 33-48 tokens; from 96 tokens on the streaming kernel is ahead)
-    if (groups <= (b == 128 ? 3 : 2) && reread <= kDecodeMaxRereadBytes) return true;
+    // b = 128: 25-28 against 29-32; from 96 tokens on the streaming kernel is ahead)
+    if (groups <= 2 && reread <= kDecodeMaxRereadBytes) return true;
     if (max_row_blocks <= 0 || groups > 8) return false;
     const double row_us = (double)max_row_blocks * 0.7 * ((double)b * b / (128.0 * 128.0));  // streaming kernel, fullest row
-    const double all_us = (double)reread / 5.8e6;                                            // decode kernel, whole product
+    const double all_us = (double)reread / 4.1e6;                                            // decode kernel, whole product
     // only where that row is long against the fixed latencies of a launch (tens of microseconds)
     return row_us >= 30.0 && all_us < row_us;
   }

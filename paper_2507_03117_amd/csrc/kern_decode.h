@@ -99,13 +99,19 @@ struct DecCfg {
   static constexpr int XB = XR * B * 2;                   // its bytes
   static constexpr int NIX = XB / 1024;                   // copy instructions per activation tile
   static constexpr int SLOT = SLB + XB;
+  // XONE: one activation tile per wave instead of one per slot.  A block's fragments are moved to registers
+  // before the next block's activation tile is copied over them, so only the weight slices need two slots.
+  // Used where two 16-token tiles per slot would otherwise leave room for a single workgroup per CU
+  // (b = 128 with 32 tokens per unit).
+  static constexpr bool XONE = !XSMALL && NTT == 2 && B == 128;
   // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
   // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
   // the small activation tile, four at b = 64), and every extra slot costs residents.
   static constexpr int NSLOT = 2;
+  static constexpr int WAVE_LDS = XONE ? NSLOT * SLB + XB : NSLOT * SLOT;
   static constexpr int OPS = NI + NIX;        // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;
-  static constexpr int RING_LDS = 4 * NSLOT * SLOT;
+  static constexpr int RING_LDS = 4 * WAVE_LDS;
   static constexpr int RED_LDS = 3 * NM * NTT * 4 * 64 * 4;
   static constexpr size_t LDS_BYTES = (size_t)RING_LDS + RED_LDS;
   static_assert(SLB % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
@@ -131,7 +137,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   const int q = unit % C::SLICES;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63, l16 = lane & 15, g = lane >> 4;
-  unsigned char* ring = smem + wave * (NSLOT * C::SLOT);
+  unsigned char* ring = smem + wave * C::WAVE_LDS;
 
   int r, kb0, n0, kb1 = 0, n1 = 0;
   bool shared_row = false;
@@ -191,19 +197,34 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   }
 
   // ---- ring -----------------------------------------------------------------------------
-  auto issue = [&](int j) {
+  // where block j's weight slice and activation tile live in this wave's part of the ring
+  auto wslot = [&](int j) { return ring + (j % NSLOT) * (C::XONE ? C::SLB : C::SLOT); };
+  auto xslot = [&](int j) { return C::XONE ? ring + NSLOT * C::SLB : ring + (j % NSLOT) * C::SLOT + C::SLB; };
+  auto locate = [&](int j, const unsigned char*& wblk, const unsigned char*& xcol) {
     const int i = wave + 4 * j;
     const bool second = DUAL && i >= n0;
     const MatDev& m = second ? a.m1 : a.m0;
     const int k = second ? kb1 + (i - n0) : kb0 + i;
-    const int col = ld_idx(m.col_idx, k);
-    unsigned char* slot = ring + (j % NSLOT) * C::SLOT;
-    const unsigned char* wblk = reinterpret_cast<const unsigned char*>(m.vals) + (int64_t)k * (B * B * 2);
+    wblk = reinterpret_cast<const unsigned char*>(m.vals) + (int64_t)k * (B * B * 2);
+    xcol = reinterpret_cast<const unsigned char*>(a.X) + (int64_t)ld_idx(m.col_idx, k) * (B * 2);
+  };
+  auto issue_w = [&](int j) {
+    const unsigned char *wblk, *xcol;
+    locate(j, wblk, xcol);
+    unsigned char* dst = wslot(j);
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) BLAST_GLDS16(wblk + woff[ni], slot + ni * 1024);
-    const unsigned char* xcol = reinterpret_cast<const unsigned char*>(a.X) + (int64_t)col * (B * 2);
+    for (int ni = 0; ni < NI; ++ni) BLAST_GLDS16(wblk + woff[ni], dst + ni * 1024);
+  };
+  auto issue_x = [&](int j) {
+    const unsigned char *wblk, *xcol;
+    locate(j, wblk, xcol);
+    unsigned char* dst = xslot(j);
 #pragma unroll
-    for (int xi = 0; xi < C::NIX; ++xi) BLAST_GLDS16(xcol + xoff[xi], slot + C::SLB + xi * 1024);
+    for (int xi = 0; xi < C::NIX; ++xi) BLAST_GLDS16(xcol + xoff[xi], dst + xi * 1024);
+  };
+  auto issue = [&](int j) {
+    issue_w(j);
+    issue_x(j);
   };
 
   if (ROLE == kDecConsumer) {
@@ -245,6 +266,51 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     asm volatile("" ::: "memory");
   }
 
+  if constexpr (C::XONE) {
+    static_assert(!C::XONE || NSLOT == 2, "the single activation tile is written for two weight slots");
+    if (cnt > 0) issue(0);
+#pragma unroll 1
+    for (int j = 0; j < cnt; ++j) {
+      const bool more = j + 1 < cnt;
+      // The other weight slot is free: its fragments went to registers an iteration ago.  Copies retire in
+      // issue order (..., W j, X j, W j+1), so "at most NI outstanding" means block j has landed whole.
+      if (more) {
+        issue_w(j + 1);
+        __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(NI));
+      } else {
+        __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
+      }
+      asm volatile("" ::: "memory");
+      const unsigned char* ws = wslot(j);
+      const unsigned char* xs = xslot(j);
+      bf16x8 wf[KST], xf[KST][NTT];
+#pragma unroll
+      for (int s = 0; s < KST; ++s) {
+        wf[s] = *reinterpret_cast<const bf16x8*>(ws + foff[s]);
+#pragma unroll
+        for (int tt = 0; tt < NTT; ++tt) xf[s][tt] = *reinterpret_cast<const bf16x8*>(xs + C::SLB * tt + fxoff[s]);
+      }
+      // the fragments are in registers before the next activation tile is copied over this one
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      asm volatile("" ::: "memory");
+      if (more) issue_x(j + 1);
+      const bool second = DUAL && (wave + 4 * j) >= n0;
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < KST; ++s) {
+        const bf16x8 w0 = second ? zero : wf[s];
+#pragma unroll
+        for (int tt = 0; tt < NTT; ++tt) {
+          acc[0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s][tt], w0, acc[0][tt], 0, 0, 0);
+          if (DUAL) {
+            const bf16x8 w1 = second ? wf[s] : zero;
+            acc[NM - 1][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s][tt], w1, acc[NM - 1][tt], 0, 0, 0);
+          }
+        }
+      }
+      asm volatile("" ::: "memory");
+    }
+  } else {
 #pragma unroll 1
   for (int j = 0; j < NSLOT - 1; ++j)
     if (j < cnt) issue(j);
@@ -266,7 +332,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     else
       __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
     asm volatile("" ::: "memory");
-    const unsigned char* slot = ring + (j % NSLOT) * C::SLOT;
+    const unsigned char* slot = wslot(j);
     const bool second = DUAL && (wave + 4 * j) >= n0;
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     // Straight-line on purpose: a block of the other matrix multiplies a zeroed operand instead of
@@ -287,6 +353,8 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
       }
     }
     asm volatile("" ::: "memory");
+  }
+
   }
 
   // ---- the four partial sums meet in LDS ---------------------------------------------------
