@@ -131,6 +131,8 @@ def test_llama405b_zipf_mlp(api):
     _run_mlp(api, wl.name, 1, 1, expect_nnz=2662)
     _run_mlp(api, wl.name, 6, 3)  # the 8-row activation tile of 128-wide blocks, rows cut into chunks
     _run_mlp(api, wl.name, 16, 3)
+    _run_mlp(api, wl.name, 24, 3)  # 32-token units with one activation tile per wave, rows cut into chunks
+    _run_mlp(api, wl.name, 70, 3)  # the full gate/up row keeps the gated product in the decode kernel, three groups
     _run_mlp(api, wl.name, 2048, 8, expect_nnz=2662)
     # the load-balance stress is real: some block rows are full, the median row is nearly empty
     _, packs = _packed(api, wl.name)
