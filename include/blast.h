@@ -55,6 +55,8 @@ extern "C" {
 
 #define BLAST_TOKEN_MAJOR 0   /* element (k, t) at X[t*ld + k]: the [tokens, features] activation tensor */
 #define BLAST_FEATURE_MAJOR 1 /* element (k, t) at X[k*ld + t] */
+#define BLAST_COLUMN_GROUPS_64 2 /* E5M2 activations only: element (k, t) at X8[((k/64)*T + t)*64 + k%64], written by
+                                   blast_quantize_e5m2_groups; ld is ignored */
 
 #define BLAST_F32 0
 #define BLAST_BF16 1
@@ -201,18 +203,26 @@ size_t blast_pooled_topk_mask_workspace(int64_t rows, int64_t cols, int32_t b);
  * (W->vals, nnz*b*b values: the structure arrays are shared with the bf16 form) and activations alike.
  * Never synchronises.  Errors: INVALID_ARG, HIP.
  *
+ * blast_quantize_e5m2_groups: the same conversion for a token-major bf16 activation X[T][K] (row pitch ldx
+ * elements, K a multiple of 64), written in column groups of 64 features: out[((k/64)*T + t)*64 + k%64], T*K bytes,
+ * 16-byte aligned.  In this layout a token's share of a 64-wide contraction slice and the next token's are one
+ * 128-byte line, which is what the product kernel's copies fetch (token-major E5M2 rows give it half a line per
+ * token: an MI355X layout choice, not the paper's).  Never synchronises.  Errors: INVALID_ARG, HIP.
+ *
  * blast_bsr_spmm_e5m2: Y = W~ X as in blast_bsr_spmm with both operands in E5M2 and fp32 accumulation.
  *   W          structure of the packed matrix (row_ptr, col_idx, row_order, aux, max_row_blocks, nnz, b;
  *              W->vals is not read).  With fp32 output and few tokens, rows much longer than a chunk are
  *              accumulated with atomic additions, as in blast_bsr_spmm.
  *   vals8      E5M2 block values, [W->nnz][b][b], one byte each, same order as W->vals
- *   X8, ldx    E5M2 activations, [T][cols] (token-major) or [cols][T], row pitch ldx bytes
- *   Y, ldy     as in blast_bsr_spmm (fp32 or bf16, same layout as X8)
+ *   X8, ldx    E5M2 activations, [T][cols] (token-major) or [cols][T], row pitch ldx bytes; or
+ *              BLAST_COLUMN_GROUPS_64 (b >= 64, X8 16-byte aligned, ldx ignored)
+ *   Y, ldy     as in blast_bsr_spmm (fp32 or bf16, same layout as X8; token-major for column groups)
  * The tuned kernel needs b >= 64, token-major operands, 16-byte aligned pointers and ldx % 16 == 0; other
  * cases take a plain kernel.  Never synchronises, allocates nothing.
  * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, HIP.
  */
 int blast_quantize_e5m2(const uint16_t* in_bf16, int64_t n, uint8_t* out, void* stream);
+int blast_quantize_e5m2_groups(const uint16_t* X_bf16, int64_t ldx, int64_t T, int64_t K, uint8_t* out, void* stream);
 int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8, const uint8_t* X8, int64_t ldx, int32_t x_layout,
                         int64_t T, void* Y, int64_t ldy, int32_t y_dtype, void* stream);
 

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libblast_hip.so")
 
 PACK_MASK, PACK_TOPK_FROBENIUS = 0, 1
-TOKEN_MAJOR, FEATURE_MAJOR = 0, 1
+TOKEN_MAJOR, FEATURE_MAJOR, COLUMN_GROUPS_64 = 0, 1, 2
 F32, BF16 = 0, 1
 ACT = {"silu": 0, "gelu": 1, "relu": 2}
 
@@ -26,7 +26,8 @@ EXPORTS = (
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
     "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm",
     "blast_generate_masks", "blast_generate_masks_workspace", "blast_sparsity_schedule",
-    "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_quantize_e5m2", "blast_bsr_spmm_e5m2",
+    "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_quantize_e5m2", "blast_quantize_e5m2_groups",
+    "blast_bsr_spmm_e5m2",
     "blast_bsr_unpack", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
 )
 
@@ -94,6 +95,8 @@ def lib():
         L.blast_pooled_topk_mask_workspace.argtypes = [i64, i64, i32]
         L.blast_quantize_e5m2.restype = C.c_int
         L.blast_quantize_e5m2.argtypes = [vp, i64, vp, vp]
+        L.blast_quantize_e5m2_groups.restype = C.c_int
+        L.blast_quantize_e5m2_groups.argtypes = [vp, i64, i64, i64, vp, vp]
         L.blast_bsr_spmm_e5m2.restype = C.c_int
         L.blast_bsr_spmm_e5m2.argtypes = [pv, vp, vp, i64, i32, i64, vp, i64, i32, vp]
         L.blast_bsr_unpack.restype = C.c_int
@@ -255,19 +258,33 @@ def quantize_e5m2(x: torch.Tensor) -> torch.Tensor:
     return out
 
 
+def quantize_e5m2_groups(x: torch.Tensor) -> torch.Tensor:
+    """blast_quantize_e5m2_groups: token-major bf16 [T, K] -> uint8 E5M2 codes in column groups, [K/64, T, 64]."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.element_size() == 2 and x.shape[1] % 64 == 0
+    T, K = x.shape
+    out = torch.empty((K // 64, T, 64), dtype=torch.uint8, device=x.device)
+    _check(lib().blast_quantize_e5m2_groups(_ptr(x), x.stride(0), T, K, _ptr(out), _stream()),
+           "blast_quantize_e5m2_groups")
+    return out
+
+
 def bsr_spmm_e5m2(W: PackedBsr, vals8: torch.Tensor, X8: torch.Tensor, *, layout: int = TOKEN_MAJOR,
                   out_dtype: torch.dtype = torch.float32, out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """blast_bsr_spmm_e5m2: Y = W * X with E5M2 block values `vals8` (quantize_e5m2(W.vals)) and E5M2 activations."""
-    assert X8.is_cuda and X8.dim() == 2 and X8.stride(1) == 1 and X8.dtype == torch.uint8
+    """blast_bsr_spmm_e5m2: Y = W * X with E5M2 block values `vals8` (quantize_e5m2(W.vals)) and E5M2 activations
+    (token-major, feature-major, or the [K/64, T, 64] tensor of quantize_e5m2_groups with layout=COLUMN_GROUPS_64)."""
+    assert X8.is_cuda and X8.dtype == torch.uint8
     assert vals8.dtype == torch.uint8 and vals8.numel() >= W.nnz * W.b * W.b
-    if layout == TOKEN_MAJOR:
-        T, K = X8.shape
+    if layout == COLUMN_GROUPS_64:
+        assert X8.dim() == 3 and X8.is_contiguous() and X8.shape[2] == 64
+        T, K = X8.shape[1], X8.shape[0] * 64
     else:
-        K, T = X8.shape
+        assert X8.dim() == 2 and X8.stride(1) == 1
+        T, K = X8.shape if layout == TOKEN_MAJOR else (X8.shape[1], X8.shape[0])
     assert K == W.cols
-    Y = out if out is not None else _alloc_out(W.rows, T, layout, out_dtype, X8.device)
+    Y = out if out is not None else _alloc_out(W.rows, T, TOKEN_MAJOR if layout == COLUMN_GROUPS_64 else layout,
+                                               out_dtype, X8.device)
     v = W.view()
-    _check(lib().blast_bsr_spmm_e5m2(C.byref(v), _ptr(vals8), _ptr(X8), X8.stride(0), layout, T, _ptr(Y), Y.stride(0),
+    _check(lib().blast_bsr_spmm_e5m2(C.byref(v), _ptr(vals8), _ptr(X8), X8.stride(-2), layout, T, _ptr(Y), Y.stride(0),
                                      BF16 if Y.dtype == torch.bfloat16 else F32, _stream()), "blast_bsr_spmm_e5m2")
     return Y
 

@@ -87,6 +87,19 @@ extern "C" int blast_quantize_e5m2(const uint16_t* in_bf16, int64_t n, uint8_t* 
   return BLAST_OK;
 }
 
+extern "C" int blast_quantize_e5m2_groups(const uint16_t* X_bf16, int64_t ldx, int64_t T, int64_t K, uint8_t* out,
+                                          void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (T < 0 || K < 0 || K % 64 != 0) return BLAST_ERR_INVALID_ARG;
+  if (T == 0 || K == 0) return BLAST_OK;
+  if (!X_bf16 || !out || ldx < K || !blast::aligned(out, 16)) return BLAST_ERR_INVALID_ARG;
+  const int64_t blocks = (T * (K / 8) + 255) / 256;
+  if (blocks > INT32_MAX) return BLAST_ERR_INVALID_ARG;
+  k_quantize_e5m2_groups<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(X_bf16, ldx, T, K, out);
+  BLAST_LAUNCH_CHECK("k_quantize_e5m2_groups");
+  return BLAST_OK;
+}
+
 extern "C" int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8, const uint8_t* X8, int64_t ldx,
                                    int32_t x_layout, int64_t T, void* Y, int64_t ldy, int32_t y_dtype,
                                    void* stream_) {
@@ -96,17 +109,24 @@ extern "C" int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8
   if (!blast::supported_block(W->b)) return BLAST_ERR_UNSUPPORTED_BLOCK;
   if (W->rows % W->b || W->cols % W->b) return BLAST_ERR_SHAPE;
   if (W->rows / W->b > INT32_MAX / 4 || W->cols / W->b > INT32_MAX / 4) return BLAST_ERR_INVALID_ARG;
-  if (x_layout != BLAST_TOKEN_MAJOR && x_layout != BLAST_FEATURE_MAJOR) return BLAST_ERR_INVALID_ARG;
+  if (x_layout != BLAST_TOKEN_MAJOR && x_layout != BLAST_FEATURE_MAJOR && x_layout != BLAST_COLUMN_GROUPS_64)
+    return BLAST_ERR_INVALID_ARG;
   if (y_dtype != BLAST_F32 && y_dtype != BLAST_BF16) return BLAST_ERR_INVALID_ARG;
   if (T < 0 || T > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
   if (T == 0 || W->rows == 0) return BLAST_OK;
-  const bool tm = x_layout == BLAST_TOKEN_MAJOR;
+  const bool cg = x_layout == BLAST_COLUMN_GROUPS_64;  // activations in column groups; the output is token-major
+  const bool tm = x_layout == BLAST_TOKEN_MAJOR || cg;
   if (!Y || ldy < (tm ? W->rows : T)) return BLAST_ERR_INVALID_ARG;
-  if (W->cols > 0 && (!X8 || ldx < (tm ? W->cols : T))) return BLAST_ERR_INVALID_ARG;
+  if (W->cols > 0 && (!X8 || (!cg && ldx < (tm ? W->cols : T)))) return BLAST_ERR_INVALID_ARG;
   if (W->nnz > 0 && (!W->col_idx || !vals8)) return BLAST_ERR_INVALID_ARG;
   const int b = W->b;
-  const bool fast = tm && b >= 64 && ldx % 16 == 0 && blast::aligned(X8, 16) && blast::aligned(vals8, 16) &&
-                    T * ldx < ((int64_t)1 << 32);
+  if (cg) {
+    // only the tiled kernel reads this layout: 64-wide groups need b >= 64, offsets inside a group 32 bits
+    if (b < 64 || !blast::aligned(X8, 16) || !blast::aligned(vals8, 16) || T * 64 >= ((int64_t)1 << 32))
+      return BLAST_ERR_INVALID_ARG;
+  }
+  const bool fast = cg || (tm && b >= 64 && ldx % 16 == 0 && blast::aligned(X8, 16) && blast::aligned(vals8, 16) &&
+                           T * ldx < ((int64_t)1 << 32));
   if (fast) {
     Fp8Args a{};
     a.row_ptr = W->row_ptr;
@@ -114,7 +134,8 @@ extern "C" int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8
     a.row_order = W->row_order;
     a.vals = vals8;
     a.X = X8;
-    a.ldx = ldx;
+    a.ldx = cg ? 64 : ldx;
+    a.x_cg = cg ? T * 64 : 0;
     a.Y = Y;
     a.ldy = ldy;
     a.y_bf16 = y_dtype == BLAST_BF16 ? 1 : 0;

@@ -33,8 +33,9 @@ struct Fp8Args {
   const int* col_idx;
   const int* row_order;  // may be null
   const uint8_t* vals;   // [nnz][b][b] E5M2
-  const uint8_t* X;      // token-major [T][cols] E5M2, row pitch ldx bytes (multiple of 16)
+  const uint8_t* X;      // token-major [T][cols] E5M2, row pitch ldx bytes (multiple of 16); or column groups, see x_cg
   int64_t ldx;
+  int64_t x_cg;          // 0: token-major.  Else X is [cols/64][T][64]: bytes between two column groups (ldx = 64)
   void* Y;               // token-major [T][rows], row pitch ldy elements
   int64_t ldy;
   int y_bf16;
@@ -162,7 +163,9 @@ __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
     const int col = ld_idx(a.col_idx, q);
     unsigned char* slot = ring + (s % NSTAGE) * C::STAGE;
     const unsigned char* wsrc = a.vals + (int64_t)q * (B * B) + ks * C::KS;
-    const unsigned char* xsrc = a.X + (int64_t)col * B + ks * C::KS;
+    // column groups of 64: one token's share of a stage is a whole row of the group, so the copy instructions
+    // fetch whole 128-byte lines (two tokens each) instead of the 64-byte half of a line per token
+    const unsigned char* xsrc = a.x_cg ? a.X + ((int64_t)col * C::KSL + ks) * a.x_cg : a.X + (int64_t)col * B + ks * C::KS;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) BLAST_GLDS16(wsrc + woff[ni], slot + ni * 1024);
 #pragma unroll
@@ -348,6 +351,21 @@ __global__ __launch_bounds__(256) void k_quantize_e5m2(const uint16_t* __restric
                                                        uint8_t* __restrict__ out) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) out[i] = bf16_to_e5m2(in[i]);
+}
+
+// Token-major bf16 [T][K] (row pitch ld elements) -> E5M2 in column groups of 64: out[(k/64) T + t][k%64].
+// One thread converts 8 consecutive features: a 16-byte read, an 8-byte write.
+__global__ __launch_bounds__(256) void k_quantize_e5m2_groups(const uint16_t* __restrict__ in, int64_t ld, int64_t T,
+                                                              int64_t K, uint8_t* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // over T * K / 8
+  const int64_t per_row = K / 8;
+  if (i >= T * per_row) return;
+  const int64_t t = i / per_row, k = (i % per_row) * 8;
+  const uint16_t* src = in + t * ld + k;
+  unsigned long long packed = 0ull;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) packed |= (unsigned long long)bf16_to_e5m2(src[j]) << (8 * j);
+  *reinterpret_cast<unsigned long long*>(out + ((k / 64) * T + t) * 64 + (k % 64)) = packed;
 }
 
 }  // namespace blast_dev

@@ -123,6 +123,10 @@ def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     assert L.blast_quantize_e5m2(None, -1, None, None) == -1
     assert L.blast_quantize_e5m2(None, 0, None, None) == 0
     assert L.blast_quantize_e5m2(None, 8, None, None) == -1
+    assert L.blast_quantize_e5m2_groups(None, 128, 4, 100, None, None) == -1  # K not a multiple of 64
+    assert L.blast_quantize_e5m2_groups(None, 128, 0, 128, None, None) == 0
+    assert L.blast_quantize_e5m2_groups(None, 128, 4, 128, None, None) == -1   # null pointers
+    assert L.blast_bsr_spmm_e5m2(C.byref(g), None, None, 128, 3, 4, None, 256, 0, None) == -1  # layout enum
     assert L.blast_bsr_spmm_e5m2(None, None, None, 128, 0, 4, None, 128, 0, None) == -1
     assert L.blast_bsr_spmm_e5m2(C.byref(g), None, None, 128, 0, 4, None, 256, 0, None) == -1  # Y null
     assert L.blast_bsr_spmm_e5m2(C.byref(g), None, None, 128, 0, 0, None, 256, 0, None) == 0   # T == 0

@@ -69,6 +69,62 @@ def test_spmm_e5m2_small(api, b, T):
     assert not y.cpu().numpy()[:, b:2 * b].any()
 
 
+@pytest.mark.parametrize("b", [64, 128])
+@pytest.mark.parametrize("T", [1, 5, 65, 129, 300])
+def test_spmm_e5m2_column_groups(api, b, T):
+    """Activations quantised into column groups of 64 features: the codes are the token-major ones, permuted
+    (bit for bit), and the product equals the oracle's on the plain codes; also from a strided bf16 source, with
+    bf16 output, and with rows long enough for the chunk plan."""
+    import torch
+
+    rng = np.random.default_rng(9700 + b + T)
+    M, K = 3 * b, 80 * 64
+    W = synth.gauss_bf16(rng, (M, K), 0.05)
+    mask = synth.uniform_mask(rng, M // b, K // b, 0.6)
+    mask[1, :] = 0
+    mask[2, :] = 1  # a full row: 80 or 40 blocks
+    dev = api.bsr_pack(to_dev(W), b, mask=mask_dev(mask))
+    ref = orc.pack(W, b, mask)
+    x = synth.gauss_bf16(rng, (T, K), 1.0)
+    vals8 = api.quantize_e5m2(dev.vals[: dev.nnz * b * b].contiguous())
+    v8_or = orc.e5m2_quantize(_f32(ref.vals))
+    x8_or = orc.e5m2_quantize(_f32(x))
+    xg = api.quantize_e5m2_groups(to_dev(x))
+    assert xg.shape == (K // 64, T, 64)
+    assert np.array_equal(xg.cpu().numpy(), x8_or.reshape(T, K // 64, 64).transpose(1, 0, 2))
+    # the same from a source with a row pitch
+    wide = torch.zeros((T, K + 24), dtype=torch.bfloat16, device="cuda:0")
+    wide[:, :K] = to_dev(x)
+    assert torch.equal(api.quantize_e5m2_groups(wide[:, :K]), xg)
+    want = orc.spmm_e5m2(ref, v8_or, x8_or)
+    y = api.bsr_spmm_e5m2(dev, vals8, xg, layout=api.COLUMN_GROUPS_64, out=torch.full((T, M), float("nan"), device="cuda:0"))
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, want, f"e5m2 column groups b={b} T={T}")
+    assert not y.cpu().numpy()[:, b:2 * b].any()
+    # token-major codes give the same sums in the same order
+    y_tm = api.bsr_spmm_e5m2(dev, vals8, api.quantize_e5m2(to_dev(x)))
+    if T > 128:  # (with few tokens and long rows the token-major call adds chunks atomically, in any order)
+        assert torch.equal(y, y_tm)
+    yb = api.bsr_spmm_e5m2(dev, vals8, xg, layout=api.COLUMN_GROUPS_64, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    got = synth.bf16_bits_to_f32(bits_of(yb)).astype(np.float64).T
+    # one bf16 ulp of the value, plus the fp32 accumulation error of 5120 terms where the sum is near zero
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -7 + 1e-4 * np.sqrt((want ** 2).mean()))
+
+
+def test_spmm_e5m2_column_groups_rejects_small_blocks(api):
+    import torch
+
+    rng = np.random.default_rng(5)
+    W = synth.gauss_bf16(rng, (64, 128), 0.05)
+    dev = api.bsr_pack(to_dev(W), 32, sparsity=0.5)
+    vals8 = api.quantize_e5m2(dev.vals[: dev.nnz * 32 * 32].contiguous())
+    xg = api.quantize_e5m2_groups(to_dev(synth.gauss_bf16(rng, (4, 128), 1.0)))
+    with pytest.raises(api.BlastError):
+        api.bsr_spmm_e5m2(dev, vals8, xg, layout=api.COLUMN_GROUPS_64)
+    torch.cuda.synchronize()
+
+
 def test_spmm_e5m2_layouts_bf16_out_and_unaligned(api):
     import torch
 
@@ -138,6 +194,9 @@ def test_spmm_e5m2_llama1b_gate_full_size(api):
         sel = np.arange(T) if T <= 64 else np.unique(np.concatenate(([0, T - 1], np.random.default_rng(T).choice(T, 46, replace=False))))
         want = orc.spmm_e5m2(ref, v8_or, orc.e5m2_quantize(_f32(x[sel])))
         check_close(y.cpu().numpy()[sel].T, want, f"e5m2 1B gate T={T}")
+        yg = api.bsr_spmm_e5m2(dev, vals8, api.quantize_e5m2_groups(to_dev(x)), layout=api.COLUMN_GROUPS_64)
+        torch.cuda.synchronize()
+        check_close(yg.cpu().numpy()[sel].T, want, f"e5m2 1B gate, column groups, T={T}")
 
 
 @pytest.mark.parametrize("b,nbc,T", [(64, 80, 1), (64, 80, 20), (64, 80, 100), (128, 70, 5), (128, 70, 128), (64, 80, 300)])
