@@ -80,7 +80,7 @@ extern "C" int blast_quantize_e5m2(const uint16_t* in_bf16, int64_t n, uint8_t* 
   if (n < 0) return BLAST_ERR_INVALID_ARG;
   if (n == 0) return BLAST_OK;
   if (!in_bf16 || !out) return BLAST_ERR_INVALID_ARG;
-  const int64_t blocks = (n + 255) / 256;
+  const int64_t blocks = ((n + 7) / 8 + 255) / 256;
   if (blocks > INT32_MAX) return BLAST_ERR_INVALID_ARG;
   k_quantize_e5m2<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(in_bf16, n, out);
   BLAST_LAUNCH_CHECK("k_quantize_e5m2");

@@ -347,10 +347,25 @@ __device__ __forceinline__ uint8_t bf16_to_e5m2(uint16_t h) {
   return (uint8_t)(sign | n);  // n = 4 is the smallest normal: the carry is the right code
 }
 
+// One thread converts 8 consecutive values (a 16-byte read and an 8-byte write when both pointers allow it).
 __global__ __launch_bounds__(256) void k_quantize_e5m2(const uint16_t* __restrict__ in, int64_t n,
                                                        uint8_t* __restrict__ out) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = bf16_to_e5m2(in[i]);
+  const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (i0 >= n) return;
+  const bool wide = ((reinterpret_cast<uintptr_t>(in) & 15u) | (reinterpret_cast<uintptr_t>(out) & 7u)) == 0 && i0 + 8 <= n;
+  if (wide) {
+    const uint4 v = *reinterpret_cast<const uint4*>(in + i0);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    unsigned long long packed = 0ull;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      packed |= (unsigned long long)bf16_to_e5m2((uint16_t)(w[j] & 0xFFFFu)) << (16 * j);
+      packed |= (unsigned long long)bf16_to_e5m2((uint16_t)(w[j] >> 16)) << (16 * j + 8);
+    }
+    *reinterpret_cast<unsigned long long*>(out + i0) = packed;
+  } else {
+    for (int64_t i = i0; i < n && i < i0 + 8; ++i) out[i] = bf16_to_e5m2(in[i]);
+  }
 }
 
 // Token-major bf16 [T][K] (row pitch ld elements) -> E5M2 in column groups of 64: out[(k/64) T + t][k%64].

@@ -36,6 +36,11 @@ def test_quantize_every_bf16_pattern(api):
     assert np.array_equal(got[~nan], want[~nan])
     assert np.all((got[nan] & 0x7C) == 0x7C) and np.all((got[nan] & 0x03) != 0)  # NaN stays NaN
     torch.cuda.synchronize()
+    # a source that is only 2-byte aligned and a length that is no multiple of 8: same codes
+    part = api.quantize_e5m2(to_dev(allbits)[5:65531]).cpu().numpy()
+    assert np.array_equal(part, got[5:65531])
+    tail = api.quantize_e5m2(to_dev(allbits)[:1003]).cpu().numpy()
+    assert np.array_equal(tail, got[:1003])
 
 
 def _case(api, rng, M, K, b, sparsity, T, w_std=0.05):
