@@ -126,6 +126,36 @@ def test_pack_topk_ties_and_zero_blocks(api):
         assert np.array_equal(dev.col_idx.cpu().numpy()[: ref.nnz], ref.col_idx)
 
 
+@pytest.mark.parametrize("sparsity", [0.5, 0.9, 0.999])
+def test_pack_topk_many_blocks(api, sparsity):
+    """26624 blocks: the selection walks global memory until the keys that share the selected prefix fit in LDS
+    (4096), collects them and finishes there."""
+    rng = np.random.default_rng(210)
+    b, rows, cols = 16, 2048, 3328
+    W = synth.gauss_bf16(rng, (rows, cols), 0.02)
+    dev, ref = pack_both(api, W, b, sparsity=sparsity)
+    assert ref.nnz == orc.n_keep((rows // b) * (cols // b), sparsity)
+    check_aux(dev, ref)
+
+
+@pytest.mark.parametrize("sparsity", [0.3, 0.75])
+def test_pack_topk_many_blocks_with_massive_ties(api, sparsity):
+    """26624 blocks with only three distinct scores: the tied keys never fit in LDS, every pass runs over global
+    memory, and the threshold is a tie that the index order has to cut (lower linear index wins)."""
+    rng = np.random.default_rng(211)
+    b, nbr, nbc = 16, 128, 208
+    proto = synth.gauss_bf16(rng, (3, b, b), 0.02)
+    which = rng.integers(0, 3, size=(nbr, nbc))
+    W = np.ascontiguousarray(proto[which].transpose(0, 2, 1, 3).reshape(nbr * b, nbc * b))
+    ref_mask, _ = orc.topk_mask(orc.block_scores(W, b), sparsity)
+    ref = orc.pack(W, b, ref_mask)
+    dev = api.bsr_pack(to_dev(W), b, sparsity=sparsity)
+    assert dev.nnz == ref.nnz
+    assert np.array_equal(dev.row_ptr.cpu().numpy(), ref.row_ptr)
+    assert np.array_equal(dev.col_idx.cpu().numpy()[: ref.nnz], ref.col_idx)
+    assert np.array_equal(bits_of(dev.vals)[: ref.nnz * b * b].reshape(ref.nnz, b, b), ref.vals)
+
+
 def test_pack_strided_weight_and_capacity_error(api):
     import torch
 
