@@ -117,8 +117,14 @@ __device__ __forceinline__ unsigned long long order_key(unsigned long long bits)
 // fit in LDS (kSelectCand of them); those are then collected once and the remaining passes run on LDS.
 constexpr int kSelectCand = 4096;
 
-__global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__ score, int64_t n, int64_t n_keep,
-                                                      uint8_t* __restrict__ mask) {
+// Workgroup 1 of a two-workgroup launch selects from a second score array into a second mask (the mask update
+// of prune-and-grow ranks the weight and the gradient at the same sparsity: the two selections run side by side).
+__global__ __launch_bounds__(1024) void k_select_topk(const double* __restrict__ score0, int64_t n, int64_t n_keep,
+                                                      uint8_t* __restrict__ mask0,
+                                                      const double* __restrict__ score1 = nullptr,
+                                                      uint8_t* __restrict__ mask1 = nullptr) {
+  const double* __restrict__ score = blockIdx.x == 0 ? score0 : score1;
+  uint8_t* __restrict__ mask = blockIdx.x == 0 ? mask0 : mask1;
   __shared__ unsigned long long cand[kSelectCand];
   __shared__ unsigned hist[256];
   __shared__ unsigned long long s_prefix;
@@ -787,7 +793,7 @@ extern "C" int blast_bsr_transpose(const blast_bsr_view* W, int32_t* row_ptr_t, 
 extern "C" size_t blast_generate_masks_workspace(int64_t rows, int64_t cols, int32_t b) {
   if (check_shape(rows, cols, b) != BLAST_OK) return 0;
   const size_t n = (size_t)(rows / b) * (size_t)(cols / b);
-  return blast::align_up(8 * (n > 0 ? n : 1), 256) + 2 * blast::align_up(n > 0 ? n : 1, 256);
+  return 2 * blast::align_up(8 * (n > 0 ? n : 1), 256) + 2 * blast::align_up(n > 0 ? n : 1, 256);
 }
 
 extern "C" int blast_generate_masks(const uint16_t* W, int64_t ldw, const uint16_t* G, int64_t ldg, int64_t rows,
@@ -806,7 +812,8 @@ extern "C" int blast_generate_masks(const uint16_t* W, int64_t ldw, const uint16
     return BLAST_ERR_WORKSPACE;
   char* wsb = static_cast<char*>(ws);
   double* scores = reinterpret_cast<double*>(wsb);
-  uint8_t* mw = reinterpret_cast<uint8_t*>(wsb + blast::align_up(8 * (size_t)n, 256));
+  double* scores_g = reinterpret_cast<double*>(wsb + blast::align_up(8 * (size_t)n, 256));
+  uint8_t* mw = reinterpret_cast<uint8_t*>(wsb + 2 * blast::align_up(8 * (size_t)n, 256));
   uint8_t* mg = mw + blast::align_up((size_t)n, 256);
   const dim3 per_elem((unsigned)((n + 255) / 256));
   if (n_keep == 0 || n_keep == n) {  // nothing survives and nothing regrows, or everything is kept by W itself
@@ -816,12 +823,10 @@ extern "C" int blast_generate_masks(const uint16_t* W, int64_t ldw, const uint16
   }
   k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(W, ldw, (int)nbc, b, scores);
   BLAST_LAUNCH_CHECK("k_block_scores(W)");
-  k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, mw);
-  BLAST_LAUNCH_CHECK("k_select_topk(W)");
-  k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(G, ldg, (int)nbc, b, scores);
+  k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(G, ldg, (int)nbc, b, scores_g);
   BLAST_LAUNCH_CHECK("k_block_scores(G)");
-  k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, mg);
-  BLAST_LAUNCH_CHECK("k_select_topk(G)");
+  k_select_topk<<<dim3(2), dim3(1024), 0, stream>>>(scores, n, n_keep, mw, scores_g, mg);
+  BLAST_LAUNCH_CHECK("k_select_topk(W, G)");
   k_merge_masks<<<per_elem, dim3(256), 0, stream>>>(mw, mg, n, mask_out);
   BLAST_LAUNCH_CHECK("k_merge_masks");
   return BLAST_OK;
