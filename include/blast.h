@@ -8,7 +8,7 @@
  * Sec. 3.4.3).  Around that path it also holds the two-matrix MLP of the
  * GPT-2 family (Sec. 4), the two backward products of a block-sparse weight
  * (Sec. 3.2, Sec. 3.4.1), the mask update of the prune-and-grow step with its sparsity
- * schedule (Sec. 3.2, Sec. 3.3, Algorithm 1), the pooled top-k mask used for
+ * schedule (Sec. 3.2: Listing 1 and Eq. (2)), the pooled top-k mask used for
  * post-training sparsification (Sec. 3.3) and the product on 8-bit E5M2
  * operands (Sec. 5.2).
  *
@@ -20,12 +20,21 @@
  *    paper notes the two orientations are mirror images (Sec. 3.4.1).
  *  - bf16 values travel as uint16_t bit patterns.
  *  - Unless a parameter says HOST, every pointer is a DEVICE pointer into memory
- *    owned by the caller.  The library never allocates or frees device memory,
- *    keeps no global state, and only enqueues work on the given stream
- *    (`stream` is a hipStream_t passed as void*; NULL = the default stream).
- *  - Every call returns 0 (BLAST_OK) or a negative error code.  When an error is
- *    returned nothing has been enqueued, except where stated for
- *    BLAST_ERR_CAPACITY and BLAST_ERR_HIP.
+ *    owned by the caller.  The library never allocates or frees device memory
+ *    and only enqueues work on the given stream (`stream` is a hipStream_t
+ *    passed as void*; NULL = the default stream).
+ *  - State the library keeps for the life of the process: a counter that hands
+ *    every single-launch MLP call its own 64-bit token; per-device caches of the
+ *    compute-unit count, of which kernels have had their dynamic-LDS limit raised
+ *    (all atomics: host threads may race on them); one small pinned host buffer per host thread that has called
+ *    blast_bsr_pack (hipHostMalloc, never freed); the last HIP error text per
+ *    host thread.
+ *  - Every call returns 0 (BLAST_OK) or a negative error code.  Argument errors
+ *    (INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE) are found before anything
+ *    is enqueued.  BLAST_ERR_HIP can come from any launch of a call that enqueues
+ *    several (the two products of the MLP, the token ranges of a very long
+ *    activation, the packer's passes): the launches before it stay enqueued and
+ *    the outputs are then undefined.  BLAST_ERR_CAPACITY: see blast_bsr_pack.
  *  - Buffers must stay alive and unmodified until the stream has executed the
  *    enqueued work.  Calls on distinct streams may run concurrently from
  *    different host threads as long as their output/workspace buffers differ.

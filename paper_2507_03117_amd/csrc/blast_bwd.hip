@@ -23,13 +23,13 @@ int cu_count_bwd() {
 template <int B>
 int launch_sddmm(SddmmArgs a, hipStream_t stream) {
   using C = SdCfg<B>;
-  static bool lds_set[64] = {};
+  static blast::DeviceFlags lds_set;
   int dev = 0;
   BLAST_HIP_TRY(hipGetDevice(&dev));
-  if (dev < 0 || dev >= 64 || !lds_set[dev]) {
+  if (!lds_set.test(dev)) {
     BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sddmm<B>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-    if (dev >= 0 && dev < 64) lds_set[dev] = true;
+    lds_set.set(dev);
   }
   const int64_t sub_units = (int64_t)a.nnz * C::SUB * C::SUB;
   // Token chunks across workgroups (on top of the four waves of a workgroup): only when there are fewer

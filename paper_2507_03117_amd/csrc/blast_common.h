@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/blast.h"
 
 namespace blast {
@@ -45,6 +47,16 @@ inline AuxLayout aux_layout(int64_t nbr, int64_t nbc, int64_t nnz) {
   L.bytes = L.csc_blk_off + align_up(sizeof(int32_t) * (size_t)nnz, 16);
   return L;
 }
+
+// One flag per device, set once something per-device has been done.  Host threads may race on it: the
+// worst outcome is that the (idempotent) action runs twice.
+struct DeviceFlags {
+  std::atomic<bool> done[64];
+  bool test(int dev) const { return dev >= 0 && dev < 64 && done[dev].load(std::memory_order_acquire); }
+  void set(int dev) {
+    if (dev >= 0 && dev < 64) done[dev].store(true, std::memory_order_release);
+  }
+};
 
 }  // namespace blast
 

@@ -12,13 +12,13 @@ namespace {
 template <int B, bool KSPLIT, bool CHUNK = false>
 int launch_fp8(Fp8Args a, hipStream_t stream) {
   using C = Fp8Cfg<B>;
-  static bool lds_set[64] = {};
+  static blast::DeviceFlags lds_set;
   int dev = 0;
   BLAST_HIP_TRY(hipGetDevice(&dev));
-  if (dev < 0 || dev >= 64 || !lds_set[dev]) {
+  if (!lds_set.test(dev)) {
     BLAST_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_fp8<B, KSPLIT, CHUNK>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-    if (dev >= 0 && dev < 64) lds_set[dev] = true;
+    lds_set.set(dev);
   }
   const int64_t tokens_per_group = KSPLIT ? 64 : 256;
   const int64_t groups = (a.T + tokens_per_group - 1) / tokens_per_group;

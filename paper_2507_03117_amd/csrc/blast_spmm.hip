@@ -25,13 +25,12 @@ namespace {
 
 // Raises a kernel's dynamic-LDS limit once per device (the attribute is per device; setting it again
 // is harmless, so a race between host threads only repeats the call).
-int ensure_lds_limit(const void* kernel, size_t bytes, bool (&done)[64]) {
+int ensure_lds_limit(const void* kernel, size_t bytes, blast::DeviceFlags& done) {
   int dev = 0;
   BLAST_HIP_TRY(hipGetDevice(&dev));
-  const bool tracked = dev >= 0 && dev < 64;
-  if (tracked && done[dev]) return BLAST_OK;
+  if (done.test(dev)) return BLAST_OK;
   BLAST_HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-  if (tracked) done[dev] = true;
+  done.set(dev);
   return BLAST_OK;
 }
 
@@ -44,7 +43,7 @@ int launch_tile(TileArgs a, hipStream_t stream) {
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
   if constexpr (!DUAL) {
     if (a.act >= 0) {  // single matrix with an activation on the output
-      static bool lds_set_post[64] = {};
+      static blast::DeviceFlags lds_set_post;
       if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_tile<B, false, true>), C::LDS_BYTES, lds_set_post))
         return rc;
       k_spmm_tile<B, false, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(a);
@@ -52,7 +51,7 @@ int launch_tile(TileArgs a, hipStream_t stream) {
       return BLAST_OK;
     }
   }
-  static bool lds_set[64] = {};
+  static blast::DeviceFlags lds_set;
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_tile<B, DUAL>), C::LDS_BYTES, lds_set)) return rc;
   k_spmm_tile<B, DUAL><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(a);
   BLAST_LAUNCH_CHECK("k_spmm_tile");
@@ -60,15 +59,15 @@ int launch_tile(TileArgs a, hipStream_t stream) {
 }
 
 int cu_count() {
-  static int cached[64] = {0};
+  static std::atomic<int> cached[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached[dev];
+  return n;
 }
 
 // Rows of an fp32 output that a later chunked product accumulates into; a launch before it can clear them
@@ -119,7 +118,7 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
   }
   if constexpr (!DUAL && !CHUNK) {
     if (a.act >= 0) {  // single matrix with an activation on the output
-      static bool lds_set_post[64] = {};
+      static blast::DeviceFlags lds_set_post;
       if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, false, TW, false, true>), C::LDS_BYTES,
                                     lds_set_post))
         return rc;
@@ -128,7 +127,7 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
       return BLAST_OK;
     }
   }
-  static bool lds_set[64] = {};
+  static blast::DeviceFlags lds_set;
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK>), C::LDS_BYTES, lds_set))
     return rc;
   k_spmm_stream<B, DUAL, TW, CHUNK><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
@@ -203,7 +202,7 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   using C = DecCfg<B, DUAL, NTT, XSMALL>;
   if constexpr (!DUAL && !CHUNK) {
     if (a.act >= 0) {  // single matrix with an activation on the output
-      static bool lds_set_post[64] = {};
+      static blast::DeviceFlags lds_set_post;
       if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, false, NTT, false, XSMALL, true>),
                                     C::LDS_BYTES, lds_set_post))
         return rc;
@@ -212,7 +211,7 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
       return BLAST_OK;
     }
   }
-  static bool lds_set[64] = {};
+  static blast::DeviceFlags lds_set;
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL>), C::LDS_BYTES,
                                 lds_set))
     return rc;
@@ -535,7 +534,7 @@ unsigned long long next_token() {
 template <int B, int NTT, int XSMALL, bool GATED>
 int launch_mlp_decode(const DecArgs& p, const DecArgs& c, hipStream_t stream) {
   using CP = DecCfg<B, GATED, NTT, XSMALL, true>;  // the producer's footprint is never below the consumer's
-  static bool lds_set[64] = {};
+  static blast::DeviceFlags lds_set;
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_mlp_decode<B, NTT, XSMALL, GATED>), CP::LDS_BYTES,
                                 lds_set))
     return rc;
