@@ -26,9 +26,11 @@
  *  - State the library keeps for the life of the process: a counter that hands
  *    every single-launch MLP call its own 64-bit token; per-device caches of the
  *    compute-unit count, of which kernels have had their dynamic-LDS limit raised
- *    (all atomics: host threads may race on them); one small pinned host buffer per host thread that has called
+ *    and of the address of the scratch array below (all atomics: host threads may
+ *    race on them); one small pinned host buffer per host thread that has called
  *    blast_bsr_pack (hipHostMalloc, never freed); the last HIP error text per
- *    host thread.
+ *    host thread; and, on every GPU the library is loaded on, the device array of
+ *    BLAST_STATIC_SCRATCH_BYTES behind blast_sparse_mlp_static.
  *  - Every call returns 0 (BLAST_OK) or a negative error code.  Argument errors
  *    (INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE) are found before anything
  *    is enqueued.  BLAST_ERR_HIP can come from any launch of a call that enqueues
@@ -335,6 +337,26 @@ int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, con
                      int32_t y_dtype, void* ws, size_t ws_bytes, void* stream);
 int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
                                int64_t T, size_t* ws_bytes /* HOST */);
+
+/*
+ * blast_sparse_mlp for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without ws),
+ * same kernels, same results and errors as blast_sparse_mlp; the scratch (H, hand-over slots, status words)
+ * lives in a device array of BLAST_STATIC_SCRATCH_BYTES that the library owns: every GPU the library runs on
+ * holds one such array from the moment the library is loaded until the process ends.  The call allocates and
+ * frees nothing.
+ *   limit   the scratch needed, blast_sparse_mlp_workspace(), must not exceed blast_sparse_mlp_static_limit()
+ *           (= BLAST_STATIC_SCRATCH_BYTES; about 2 * T * I bytes): otherwise BLAST_ERR_WORKSPACE and nothing
+ *           is enqueued.  The Llama-3.2-1B-shaped layer (I = 8192) fits up to T = 2048.
+ *   sharing every call on one GPU uses that GPU's one array: calls that may overlap in time on the same GPU
+ *           (different streams, different host threads) race on it and must be serialised by the caller.
+ *           Nothing in the array needs clearing between calls and nothing in it outlives a call.
+ */
+#define BLAST_STATIC_SCRATCH_BYTES ((size_t)36 << 20)
+int blast_sparse_mlp_static(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
+                            const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y,
+                            int64_t ldy, int32_t y_dtype, void* stream);
+size_t blast_sparse_mlp_static_limit(void);
 
 /*
  * Two-matrix MLP (Sec. 2.1: an MLP block has two or three weight matrices; Sec. 3.4.3: two projections

@@ -29,6 +29,7 @@ EXPORTS = (
     "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_quantize_e5m2", "blast_quantize_e5m2_groups",
     "blast_bsr_spmm_e5m2",
     "blast_bsr_unpack", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
+    "blast_sparse_mlp_static", "blast_sparse_mlp_static_limit",
 )
 
 
@@ -77,6 +78,10 @@ def lib():
         L.blast_bsr_spmm_workspace.argtypes = [pv, i64, C.POINTER(sz)]
         L.blast_sparse_mlp.restype = C.c_int
         L.blast_sparse_mlp.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
+        L.blast_sparse_mlp_static.restype = C.c_int
+        L.blast_sparse_mlp_static.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp]
+        L.blast_sparse_mlp_static_limit.restype = sz
+        L.blast_sparse_mlp_static_limit.argtypes = []
         L.blast_sparse_mlp_workspace.restype = C.c_int
         L.blast_sparse_mlp_workspace.argtypes = [pv, pv, pv, i64, C.POINTER(sz)]
         L.blast_sparse_mlp2.restype = C.c_int
@@ -378,6 +383,19 @@ def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor,
     else:
         _check(L.blast_sparse_mlp_events(*args, events), "blast_sparse_mlp_events")
     return Y
+
+
+def sparse_mlp_static(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor, out: torch.Tensor, *,
+                      layout: int = TOKEN_MAJOR, act: str = "silu") -> torch.Tensor:
+    """blast_sparse_mlp_static: blast_sparse_mlp with the scratch in the library's own device array; the
+    caller passes the output tensor, nothing is allocated on the way."""
+    T, K, ldx = _layout_dims(X, layout)
+    assert K == gate.cols
+    vg, vu, vd = gate.view(), up.view(), down.view()
+    _check(lib().blast_sparse_mlp_static(C.byref(vg), C.byref(vu), C.byref(vd), _ptr(X), ldx, layout, T, ACT[act],
+                                         _ptr(out), out.stride(0), BF16 if out.dtype == torch.bfloat16 else F32,
+                                         _stream()), "blast_sparse_mlp_static")
+    return out
 
 
 class PreparedCall:

@@ -697,6 +697,48 @@ extern "C" int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_vie
                      static_cast<hipStream_t>(stream_), nullptr);
 }
 
+// ---- entry point for callers that cannot allocate ---------------------------------------------------
+// Same work as blast_sparse_mlp, with the scratch (H, the publication slots of the single-launch form and
+// the status words) in a device array that belongs to the library instead of a caller's workspace.
+constexpr size_t kStaticScratchBytes = BLAST_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+// Device address of `scratch` on the current device, looked up once per device (the array's name is only a
+// host-side handle; every GPU holds its own copy at its own address).
+int static_scratch(void** out) {
+  static std::atomic<void*> addr[64];
+  int dev = 0;
+  BLAST_HIP_TRY(hipGetDevice(&dev));
+  const bool tracked = dev >= 0 && dev < 64;
+  void* p = tracked ? addr[dev].load(std::memory_order_acquire) : nullptr;
+  if (!p) {
+    BLAST_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return BLAST_ERR_HIP;
+    if (tracked) addr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return BLAST_OK;
+}
+
+}  // namespace
+
+extern "C" size_t blast_sparse_mlp_static_limit(void) { return kStaticScratchBytes; }
+
+extern "C" int blast_sparse_mlp_static(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
+                                       const blast_bsr_view* Wdown, const uint16_t* X, int64_t ldx, int32_t x_layout,
+                                       int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype, void* stream_) {
+  if (!Wup) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype)) return rc;
+  if (T == 0 || Wgate->cols == 0) return BLAST_OK;
+  if (mlp_workspace_bytes(Wgate->rows, T) > kStaticScratchBytes) return BLAST_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (int rc = static_scratch(&ws)) return rc;
+  return enqueue_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, kStaticScratchBytes,
+                     static_cast<hipStream_t>(stream_), nullptr);
+}
+
 extern "C" int blast_sparse_mlp2(const blast_bsr_view* W1, const blast_bsr_view* W2, const uint16_t* X, int64_t ldx,
                                  int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype,
                                  void* ws, size_t ws_bytes, void* stream_) {

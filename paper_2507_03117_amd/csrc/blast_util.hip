@@ -22,7 +22,7 @@ extern "C" const char* blast_strerror(int code) {
     case BLAST_ERR_SHAPE: return "shape error (rows/cols not a multiple of the block size, or inconsistent MLP matrices)";
     case BLAST_ERR_UNSUPPORTED_BLOCK: return "unsupported block size (expected 16, 32, 64 or 128)";
     case BLAST_ERR_CAPACITY: return "nnz_cap is smaller than the number of kept blocks";
-    case BLAST_ERR_WORKSPACE: return "workspace or aux buffer missing, misaligned or too small";
+    case BLAST_ERR_WORKSPACE: return "workspace or aux buffer missing, misaligned or too small (blast_sparse_mlp_static: the call needs more scratch than the library's array holds)";
     case BLAST_ERR_HIP:
       snprintf(g_msg, sizeof(g_msg), "HIP runtime error: %s", g_hip_text[0] ? g_hip_text : "(no detail recorded)");
       return g_msg;
