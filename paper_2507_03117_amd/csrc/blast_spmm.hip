@@ -96,22 +96,36 @@ struct ChunkPlan {
   bool pre_zeroed = false;      // the shared rows of the output have been cleared by an earlier launch
 };
 
-template <int B, bool DUAL, int TW, bool CHUNK>
-int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
-  using C = StreamCfg<B, TW>;
+// An XCD's L2 (4 MB) keeps the slab of activations of the token tiles it works on only while that slab is a
+// few megabytes.  Beyond that every stored block fetches its activation tile from the memory side whatever the
+// schedule does, and what is left to save is the weights: with a block row pinned to one XCD they leave the
+// memory side once instead of once per XCD (measured on the 405B-class layer, 16384 / 53248 features wide: 3.6
+// and 2.2 GB per launch cross the fabric with token tiles pinned, at the 6 - 7.5 TB/s it delivers).
+constexpr int64_t kRowPinnedSlabBytes = (int64_t)6 << 20;
+
+template <int B, bool DUAL, int TW, bool CHUNK, int NW = 4>
+int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipStream_t stream) {
+  using C = StreamCfg<B, TW, NW>;
   a.ntt = (a.T + C::TT - 1) / C::TT;
-  const int64_t n_items = (int64_t)a.ntt * (CHUNK ? plan.max_chunks : (int64_t)a.nbr);
+  const int64_t n_rows = CHUNK ? plan.max_chunks : (int64_t)a.nbr;
+  const int64_t n_items = (int64_t)a.ntt * n_rows;
   if (n_items <= 0) return BLAST_OK;
   if (n_items > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
   int shift = -1;
   for (int q = 0; q < 31; ++q)
     if ((1 << q) == a.ntt) shift = q;
-  StreamArgs sa{a, (int)n_items, shift, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
   int64_t grid = (n_items + 7) / 8 * 8;
   const int64_t resident = (int64_t)cu_count() * C::WG_PER_CU / 8 * 8;
   if (grid > resident) grid = resident;
   // a workgroup keeps the descriptors of its items one per lane: at most 64 rounds
   if (grid * 64 < n_items) grid = ((n_items + 63) / 64 + 7) / 8 * 8;
+  // row-pinned schedule: every token tile of a row on one XCD, side by side
+  int row_pinned = 0;
+  const int64_t slab = ((int64_t)a.ntt + 7) / 8 * C::TT * k_features * 2;
+  if (B == 128 && slab > kRowPinnedSlabBytes && grid == resident && a.ntt <= grid / 8 && (grid / 8) % a.ntt == 0 &&
+      n_rows / 8 + 1 <= 64 * ((grid / 8) / a.ntt))
+    row_pinned = 1;
+  StreamArgs sa{a, (int)n_items, shift, row_pinned, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
   if (CHUNK) {
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
@@ -119,43 +133,49 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, hipStream_t stream) {
   if constexpr (!DUAL && !CHUNK) {
     if (a.act >= 0) {  // single matrix with an activation on the output
       static blast::DeviceFlags lds_set_post;
-      if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, false, TW, false, true>), C::LDS_BYTES,
-                                    lds_set_post))
+      if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, false, TW, false, true, NW>),
+                                    C::LDS_BYTES, lds_set_post))
         return rc;
-      k_spmm_stream<B, false, TW, false, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
+      k_spmm_stream<B, false, TW, false, true, NW><<<dim3((unsigned)grid), dim3(64 * NW), C::LDS_BYTES, stream>>>(sa);
       BLAST_LAUNCH_CHECK("k_spmm_stream");
       return BLAST_OK;
     }
   }
   static blast::DeviceFlags lds_set;
-  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK>), C::LDS_BYTES, lds_set))
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK, false, NW>),
+                                C::LDS_BYTES, lds_set))
     return rc;
-  k_spmm_stream<B, DUAL, TW, CHUNK><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(sa);
+  k_spmm_stream<B, DUAL, TW, CHUNK, false, NW><<<dim3((unsigned)grid), dim3(64 * NW), C::LDS_BYTES, stream>>>(sa);
   BLAST_LAUNCH_CHECK("k_spmm_stream");
   return BLAST_OK;
 }
 
 template <int B, bool DUAL, bool CHUNK>
-int launch_stream_c(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
+int launch_stream_c(const TileArgs& a, const ChunkPlan& plan, int64_t k_features, hipStream_t stream) {
   if constexpr (B == 128) {
-    return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, stream);
+    // 256-token x 128-row tiles (eight waves, one workgroup per CU) once they fill the chip; below that,
+    // 128-token tiles in four-wave workgroups, two per CU
+    const int64_t n_rows = CHUNK ? plan.max_chunks : (int64_t)a.nbr;
+    const int64_t wide_items = (int64_t)((a.T + 255) / 256) * n_rows;
+    if (wide_items >= (int64_t)cu_count()) return launch_stream_tw<B, DUAL, 4, CHUNK, 8>(a, plan, k_features, stream);
+    return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, k_features, stream);
   } else if constexpr (B == 64) {
     // 128-token tiles when 256-token tiles would leave workgroup slots empty
     const int64_t wide_items = (int64_t)((a.T + 255) / 256) * a.nbr;
-    if (wide_items < (int64_t)cu_count() * 2) return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, stream);
-    return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, stream);
+    if (wide_items < (int64_t)cu_count() * 2) return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, k_features, stream);
+    return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, k_features, stream);
   } else {
-    return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, stream);
+    return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, k_features, stream);
   }
 }
 
 template <int B, bool DUAL>
-int launch_stream(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
+int launch_stream(const TileArgs& a, const ChunkPlan& plan, int64_t k_features, hipStream_t stream) {
   if constexpr (!DUAL) {
     // rows cut into chunks accumulate with fp32 atomics: only for fp32 output without an activation
-    if (plan.hdr && !a.y_bf16 && a.act < 0) return launch_stream_c<B, false, true>(a, plan, stream);
+    if (plan.hdr && !a.y_bf16 && a.act < 0) return launch_stream_c<B, false, true>(a, plan, k_features, stream);
   }
-  return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, stream);
+  return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, k_features, stream);
 }
 
 template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL = 0>
@@ -216,7 +236,7 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
                                 lds_set))
     return rc;
   if (CHUNK && !plan.pre_zeroed) {
-    StreamArgs sa{a, 0, -1, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
+    StreamArgs sa{a, 0, -1, 0, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
   }
@@ -335,9 +355,9 @@ int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, con
   }
   if (a.x_vec && a.T > 0 && small_x) {
     switch (b) {
-      case 32: return launch_stream<32, DUAL>(a, plan, stream);
-      case 64: return launch_stream<64, DUAL>(a, plan, stream);
-      case 128: return launch_stream<128, DUAL>(a, plan, stream);
+      case 32: return launch_stream<32, DUAL>(a, plan, a.kdim, stream);
+      case 64: return launch_stream<64, DUAL>(a, plan, a.kdim, stream);
+      case 128: return launch_stream<128, DUAL>(a, plan, a.kdim, stream);
       default: break;
     }
   }
@@ -449,6 +469,7 @@ extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_
   set_y(a, Y, ldy, x_layout, y_dtype);
   a.T = (int)T;
   a.nbr = (int)(W->rows / W->b);
+  a.kdim = W->cols;
   a.act = -1;
   return dispatch_tile<false>(W->b, a, W->nnz, stream, plan_of(W, T));
 }
@@ -518,6 +539,7 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
   set_y(g, H, ldh, h_layout, BLAST_BF16);
   g.T = (int)T;
   g.nbr = (int)(Wgate->rows / Wgate->b);
+  g.kdim = Wgate->cols;
   g.act = act;
   if (!Wup) return dispatch_tile<false>(Wgate->b, g, Wgate->nnz, stream, side);
   return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream, side);
@@ -658,6 +680,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   set_y(d, Y, ldy, x_layout, y_dtype);
   d.T = (int)T;
   d.nbr = (int)(E / b);
+  d.kdim = I;
   d.act = -1;
   ChunkPlan dplan = plan_of(Wdown, T);
   // At decode token counts the rows of Y that the chunked second product accumulates into are cleared on

@@ -24,6 +24,7 @@ struct TileArgs {
   int y_bf16;
   int T;
   int nbr;               // block rows of the output
+  int64_t kdim;          // features contracted over (columns of the matrix); host-side scheduling only
   int ntt;               // token tiles
   int act;               // gated product: the activation of the gate; single matrix: < 0 none, else applied to the output
   int x_vec;             // 1: 16-byte loads of X are legal (sxk == 1, aligned)

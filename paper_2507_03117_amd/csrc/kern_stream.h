@@ -29,12 +29,17 @@ namespace blast_dev {
 // TW = waves along the token dimension (4: 256-token tiles, 2: 128-token tiles).  Wide tiles read each
 // weight block once per 256 tokens; narrow tiles double the number of items, which matters when a
 // matrix has fewer (block row, token tile) pairs than the chip has workgroup slots.
-template <int B, int TW>
+// NW = waves of a workgroup (4, or 8 for 128-wide blocks: a 256-token x 128-row output tile, one workgroup
+// per CU, so that a weight slice is copied once per 256 tokens and 85 flop are done per byte copied
+// instead of 64).
+template <int B, int TW, int NW = 4>
 struct StreamCfg {
   static_assert(TW == 2 || TW == 4, "two or four waves along tokens");
-  static_assert(B / (4 / TW) >= 32, "a wave needs at least 32 weight rows");
+  static_assert(NW == 4 || NW == 8, "four or eight waves");
+  static_assert(B / (NW / TW) >= 32, "a wave needs at least 32 weight rows");
+  static constexpr int NWAVE = NW;
   static constexpr int TOKW = TW;                  // waves along tokens
-  static constexpr int ROWW = 4 / TOKW;            // waves along weight rows
+  static constexpr int ROWW = NW / TOKW;           // waves along weight rows
   static constexpr int WT_ROW = B / ROWW;          // weight rows per wave
   static constexpr int NI = WT_ROW / 32;
   static constexpr int MI = 2;
@@ -49,19 +54,22 @@ struct StreamCfg {
   static constexpr int W_BYTES = B * ROW_BYTES;
   static constexpr int X_BYTES = TT * ROW_BYTES;
   static constexpr int STAGE = W_BYTES + X_BYTES;
-  // as many stages as fit in half of a CU's LDS (two workgroups per CU), at most 4
-  static constexpr int NSTAGE_FIT = (80 * 1024) / STAGE;
+  // as many stages as fit in a workgroup's share of a CU's LDS (two four-wave workgroups per CU, or one
+  // eight-wave workgroup), at most 4
+  static constexpr int NSTAGE_FIT = ((NW == 8 ? 160 : 80) * 1024) / STAGE;
   static constexpr int NSTAGE = NSTAGE_FIT >= 4 ? 4 : (NSTAGE_FIT >= 2 ? NSTAGE_FIT : 2);
   static constexpr int W_INSTR = W_BYTES / 1024;
   static constexpr int X_INSTR = X_BYTES / 1024;
-  static constexpr int WQ = (W_INSTR + 3) / 4;     // copy instructions per wave and step (weights)
-  static constexpr int XQ = X_INSTR / 4;           // (activations)
+  static constexpr int WQ = (W_INSTR + NW - 1) / NW;  // copy instructions per wave and step (weights)
+  static constexpr int XQ = X_INSTR / NW;             // (activations)
+  static_assert(X_INSTR % NW == 0, "the activation copies divide evenly among the waves");
   static constexpr int LPS = WQ + XQ;              // copies per thread and step
   static constexpr int KSTEPS = KS / 16;
   static constexpr int KEY_MOD = (CPR >= 8) ? 8 : CPR;
   static constexpr int KEY_DIV = 8 / KEY_MOD;
   static constexpr size_t LDS_BYTES = (size_t)NSTAGE * STAGE;
-  static constexpr int WG_PER_CU = (2 * LDS_BYTES <= 160 * 1024) ? 2 : 1;
+  static constexpr int WG_PER_CU = (NW == 4 && 2 * LDS_BYTES <= 160 * 1024) ? 2 : 1;
+  static constexpr int WAVES_PER_SIMD = WG_PER_CU * NW / 4;
   __device__ static __forceinline__ int key(int row) { return (row / KEY_DIV) % KEY_MOD; }
 };
 
@@ -69,6 +77,13 @@ struct StreamArgs {
   TileArgs t;
   int n_items;    // nbr * ntt (without a chunk plan)
   int ntt_shift;  // log2(ntt) when ntt is a power of two, else -1
+  // Which items meet on an XCD (workgroup w runs on XCD w % 8, whose L2 its copies go through):
+  // 0: a token tile stays on one XCD (its slab of activations is re-read from that L2, every XCD streams
+  //    every weight block);
+  // 1: a block row stays on one XCD, all its token tiles running side by side (every weight block leaves the
+  //    memory side once; for activations too wide for an L2 to keep a slab of them anyway).  Needs
+  //    (gridDim.x / 8) % ntt == 0.
+  int row_pinned;
   // chunk plan written by the packer (CHUNK instances only): hdr[0] = number of chunks
   const int* hdr;
   const int* chunk_row;  // block row of the chunk; bit 31 set when the row has several chunks
@@ -111,37 +126,102 @@ struct ItemTable {
   int n_rounds; // uniform: rounds of this workgroup
 };
 
+#define BLAST_LANE(v, j) __builtin_amdgcn_readlane((v), (j))
+
+// Fills the descriptor of one item from its rank in the schedule (row_order, or the chunk plan) and its token tile.
+template <bool DUAL, bool CHUNK>
+__device__ __forceinline__ void describe_item(const StreamArgs& sa, int rank, int tile, ItemTable& t) {
+  const TileArgs& a = sa.t;
+  t.tile = tile;
+  if (CHUNK) {
+    t.r = sa.chunk_row[rank];
+    t.k0 = sa.chunk_kb[rank];
+    t.e0 = sa.chunk_ke[rank];
+  } else {
+    t.r = a.row_order ? a.row_order[rank] : rank;
+    t.k0 = a.m0.row_ptr[t.r];
+    t.e0 = a.m0.row_ptr[t.r + 1];
+    if (DUAL) {
+      t.k1 = a.m1.row_ptr[t.r];
+      t.e1 = a.m1.row_ptr[t.r + 1];
+    }
+  }
+  if (t.k0 < t.e0) t.c0 = a.m0.col_idx[t.k0];
+  if (DUAL && t.k1 < t.e1) t.c1 = a.m1.col_idx[t.k1];
+}
+
 template <bool DUAL, bool CHUNK>
 __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n_items, int w, int G, int lane) {
   const TileArgs& a = sa.t;
   ItemTable t{};
-  const int it = item_of(w, lane, G);
-  const bool ok = it < n_items;
-  int rank = 0;
-  if (ok) split_item(it, a.ntt, sa.ntt_shift, rank, t.tile);
-  if (ok) {
-    if (CHUNK) {
-      t.r = sa.chunk_row[rank];
-      t.k0 = sa.chunk_kb[rank];
-      t.e0 = sa.chunk_ke[rank];
-    } else {
-      t.r = a.row_order ? a.row_order[rank] : rank;
-      t.k0 = a.m0.row_ptr[t.r];
-      t.e0 = a.m0.row_ptr[t.r + 1];
-      if (DUAL) {
-        t.k1 = a.m1.row_ptr[t.r];
-        t.e1 = a.m1.row_ptr[t.r + 1];
+  if (!sa.row_pinned) {
+    const int it = item_of(w, lane, G);
+    const bool ok = it < n_items;
+    int rank = 0, tile = 0;
+    if (ok) split_item(it, a.ntt, sa.ntt_shift, rank, tile);
+    if (ok) describe_item<DUAL, CHUNK>(sa, rank, tile, t);
+    // items of a workgroup grow with the round, so the valid rounds are a prefix
+    t.n_rounds = __builtin_popcountll(__ballot(ok));
+    return t;
+  }
+  // Row-pinned schedule.  The ranks (rows by population, fullest first) are dealt to the 8 XCDs in
+  // octets, every other octet mirrored; on an XCD, `nslot` groups of ntt workgroups (one per token tile)
+  // each take whole rows.  Which group takes which row is decided by every workgroup for itself, all
+  // arriving at the same answer: rows in order, each to the group with the least work so far (work = stored
+  // blocks + 2 for the output tile); with more than 64 rows per XCD, or more than 8 groups, rows are dealt
+  // round-robin, every other round mirrored.
+  const int n_rows = n_items / a.ntt;
+  const int x = w & 7, j = w >> 3, Gx = G >> 3;
+  const int nslot = Gx / a.ntt, slot = j / a.ntt, tile = j - slot * a.ntt;
+  const int octets = (n_rows + 7) >> 3;
+  auto rank_of = [&](int o) { return (o << 3) + ((o & 1) ? 7 - x : x); };
+  // rows of this XCD: octet o contributes rank_of(o) when that rank exists
+  int nrx = octets;
+  if (octets > 0 && rank_of(octets - 1) >= n_rows) --nrx;
+  int mine = -1;  // per lane: the position (in the XCD's list) of the lane-th row of this group
+  int n_mine = 0;
+  if (nrx <= 64 && nslot <= 8) {
+    int len = 0;
+    if (lane < nrx) {
+      const int rank = rank_of(lane);
+      if (CHUNK) {
+        len = sa.chunk_ke[rank] - sa.chunk_kb[rank];
+      } else {
+        const int r = a.row_order ? a.row_order[rank] : rank;
+        len = a.m0.row_ptr[r + 1] - a.m0.row_ptr[r];
+        if (DUAL) len += a.m1.row_ptr[r + 1] - a.m1.row_ptr[r];
+      }
+      len += 2;
+    }
+    int load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int k = 0; k < nrx; ++k) {
+      const int l = BLAST_LANE(len, k);
+      int best = 0, bl = load[0];
+#pragma unroll
+      for (int q = 1; q < 8; ++q)
+        if (q < nslot && load[q] < bl) {
+          bl = load[q];
+          best = q;
+        }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) load[q] += (q == best) ? l : 0;
+      if (best == slot) {
+        if (lane == n_mine) mine = k;
+        ++n_mine;
       }
     }
-    if (t.k0 < t.e0) t.c0 = a.m0.col_idx[t.k0];
-    if (DUAL && t.k1 < t.e1) t.c1 = a.m1.col_idx[t.k1];
+  } else {
+    // round-robin: round q of group `slot` takes position q * nslot + (q odd ? nslot - 1 - slot : slot)
+    const int pos = lane * nslot + ((lane & 1) ? nslot - 1 - slot : slot);
+    if (pos < nrx) mine = pos;
+    n_mine = __builtin_popcountll(__ballot(pos < nrx));
+    // positions grow with the round except across a mirrored boundary, where validity can only end:
+    // the valid rounds are a prefix
   }
-  // items of a workgroup grow with the round, so the valid rounds are a prefix
-  t.n_rounds = __builtin_popcountll(__ballot(ok));
+  if (mine >= 0) describe_item<DUAL, CHUNK>(sa, rank_of(mine), tile, t);
+  t.n_rounds = n_mine;
   return t;
 }
-
-#define BLAST_LANE(v, j) __builtin_amdgcn_readlane((v), (j))
 
 // Position of the loader in the flattened stream of steps, kept as running addresses so that the
 // common case (the next block of the same row) costs a handful of scalar additions: a "run" is the
@@ -162,11 +242,11 @@ struct Loader {
 // (block row, token tile); a row made of several chunks adds its partial sums into a zeroed fp32 output.
 // POST: a single-matrix product whose result goes through the activation a.act before it is stored
 // (the first half of a two-matrix MLP).
-template <int B, bool DUAL, int TW, bool CHUNK, bool POST = false>
-__global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_stream(const StreamArgs sa) {
+template <int B, bool DUAL, int TW, bool CHUNK, bool POST = false, int NW = 4>
+__global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) void k_spmm_stream(const StreamArgs sa) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
   static_assert(!POST || (!DUAL && !CHUNK), "an activation on the output needs complete sums of a single matrix");
-  using C = StreamCfg<B, TW>;
+  using C = StreamCfg<B, TW, NW>;
   const TileArgs& a = sa.t;
   const int n_items = CHUNK ? ld_idx(sa.hdr, 0) * a.ntt : sa.n_items;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -196,7 +276,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
   int winstr[C::WQ];
 #pragma unroll
   for (int q = 0; q < C::WQ; ++q) {
-    winstr[q] = (q * 4 + wave) % C::W_INSTR;  // with fewer than 4 instructions, waves duplicate each other
+    winstr[q] = (q * NW + wave) % C::W_INSTR;  // with fewer instructions than waves, waves duplicate each other
     const int row = winstr[q] * C::RPI + cp_rr;
     woff[q] = (uint32_t)(row * B + ((cp_slot ^ C::key(row)) << 3)) * 2u;
   }
@@ -207,7 +287,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     xoff_tile = tile;
 #pragma unroll
     for (int q = 0; q < C::XQ; ++q) {
-      const int row = (q * 4 + wave) * C::RPI + cp_rr;
+      const int row = (q * NW + wave) * C::RPI + cp_rr;
       int t = tile * C::TT + row;
       t = t < a.T ? t : a.T - 1;  // clamp: rows past T are never stored
       xoff[q] = ((uint32_t)t * sxt32 + (uint32_t)((cp_slot ^ C::key(row)) << 3)) * 2u;
@@ -261,7 +341,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     }
   };
   // Issues the copies of the loader's current step and moves it one step on.
-  int ahead = 0;  // steps issued and not yet consumed
+  int ahead = 0;  // steps issued whose stage the multiplying side has not entered yet
   auto issue_next = [&]() {
     unsigned char* st = smem + ld.stage_off;
     const unsigned char* wblk = ld.wptr + ld.slice * (C::KS * 2);
@@ -270,7 +350,7 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     const unsigned char* xcol =
         reinterpret_cast<const unsigned char*>(a.X) + (int64_t)ld.c * (B * 2) + ld.slice * (C::KS * 2);
 #pragma unroll
-    for (int q = 0; q < C::XQ; ++q) BLAST_GLDS16(xcol + xoff[q], st + C::W_BYTES + (q * 4 + wave) * 1024);
+    for (int q = 0; q < C::XQ; ++q) BLAST_GLDS16(xcol + xoff[q], st + C::W_BYTES + (q * NW + wave) * 1024);
     ld.stage_off = (ld.stage_off + C::STAGE == (uint32_t)C::LDS_BYTES) ? 0u : ld.stage_off + C::STAGE;
     ++ahead;
     if (C::NSLICE > 1) {
@@ -287,16 +367,111 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     }
   };
   next_run();
+  // Two ways of running the ring.  With three or more stages (PIPE) every stage starts with a step in it and
+  // the stream is software-pipelined at the grain of a k-step, see do_step.  With two stages the step that
+  // refills a stage is issued before the wait for the current step's copies, two barriers per step: during
+  // that wait two steps are then in flight instead of one, which matters more than the second barrier
+  // (measured on the 1B- and 3B-shaped products, b = 64: 3 % faster than the pipelined form with two stages).
+  constexpr bool PIPE = C::NSTAGE >= 3;
 #pragma unroll 1
-  for (int p = 0; p < C::NSTAGE - 1; ++p)
+  for (int p = 0; p < (PIPE ? C::NSTAGE : C::NSTAGE - 1); ++p)
     if (ld.valid) issue_next();
 
-  // One step of the stream: wait for its data, let another step's copies go, multiply.
+  // Steps this workgroup will multiply (the consumer's view of the stream's length).
+  int steps_left = 0;
+  if (PIPE) {
+    for (int q = 0; q < tab.n_rounds; ++q) {
+      steps_left += (BLAST_LANE(tab.e0, q) - BLAST_LANE(tab.k0, q)) * C::NSLICE;
+      if (DUAL) steps_left += (BLAST_LANE(tab.e1, q) - BLAST_LANE(tab.k1, q)) * C::NSLICE;
+    }
+  }
+
+  // Operand fragments of one 16-wide k-step: MI token fragments, NI weight-row fragments.
+  struct Frag {
+    bf16x8 x[C::MI], w[C::NI];
+  };
+  auto read_frag = [&](Frag& f, const unsigned char* st, int kk) {
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+      f.x[mi] = *reinterpret_cast<const bf16x8*>(st + C::W_BYTES + a_row0 + mi * 32 * C::ROW_BYTES + frag_off[kk]);
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+      f.w[ni] = *reinterpret_cast<const bf16x8*>(st + b_row0 + ni * 32 * C::ROW_BYTES + frag_off[kk]);
+  };
+  auto mma = [&](f32x16 (&acc)[C::MI][C::NI], const Frag& f) {
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.x[mi], f.w[ni], acc[mi][ni], 0, 0, 0);
+  };
+  // A fragment read follows every matrix instruction: the wait for the fragments of this k-step then sits
+  // in front of its first matrix instruction, where only reads issued a whole k-step ago are outstanding.
+  auto pair_reads_with_mma = [&]() {
+#pragma unroll
+    for (int i = 0; i < C::MI * C::NI; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < C::MI + C::NI) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+  };
+
   uint32_t cstage_off = 0;
-  auto do_step = [&](f32x16 (&acc)[C::MI][C::NI]) {
+  Frag cur;
+  if (PIPE && steps_left > 0) {
+    if (ahead == C::NSTAGE)
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT((C::NSTAGE - 1) * C::LPS));
+    else
+      __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
+    __builtin_amdgcn_s_barrier();  // everyone's copies of the first step have landed
+    asm volatile("" ::: "memory");
+    read_frag(cur, smem, 0);
+    --ahead;  // from here on: steps issued beyond the one being multiplied
+  }
+  // PIPE: while the matrix instructions of one k-step run, the fragments of the next are on their way from
+  // LDS, and `cur` always holds the fragments of the k-step that is multiplied next - at a step boundary
+  // those of the first k-step of the following stage, across items too.  One barrier per step, placed before
+  // the step's last k-step: by then every wave has issued the matrix work of the earlier k-steps, which keeps
+  // the matrix cores fed while the waves meet.
+  auto do_step_pipe = [&](f32x16 (&acc)[C::MI][C::NI]) {
+    const unsigned char* st = smem + cstage_off;
+    cstage_off = (cstage_off + C::STAGE == (uint32_t)C::LDS_BYTES) ? 0u : cstage_off + C::STAGE;
+    Frag nxt;
+#pragma unroll
+    for (int kk = 0; kk + 1 < C::KSTEPS; ++kk) {
+      read_frag(nxt, st, kk + 1);
+      mma(acc, cur);
+      pair_reads_with_mma();
+      cur = nxt;
+    }
+    // Every read of this stage has been issued; once they have returned the stage can be handed back.
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    --steps_left;
+    if (steps_left > 0) {
+      // Copies retire in issue order, so "at most (steps issued after the next one) * LPS outstanding"
+      // means the next step's copies have landed (stores of an epilogue can only make the wait stricter).
+      // In the steady state NSTAGE-1 steps are issued beyond this one; the tail waits for all.
+      if (ahead == C::NSTAGE - 1)
+        __builtin_amdgcn_s_waitcnt(BLAST_VMCNT((C::NSTAGE - 2) * C::LPS));
+      else
+        __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
+      // everyone's copies of the next step have landed, and everyone has left this step's stage
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      read_frag(nxt, smem + cstage_off, 0);
+      --ahead;
+    }
+    mma(acc, cur);
+    pair_reads_with_mma();
+    cur = nxt;
+    asm volatile("" ::: "memory");
+    // the stage this step was multiplied out of takes the step NSTAGE further down the stream
+    if (steps_left > 0 && ld.valid) issue_next();
+  };
+  // Two stages: wait for the step's data, let another step's copies go, multiply.
+  auto do_step_two = [&](f32x16 (&acc)[C::MI][C::NI]) {
     // The stage that the previous step was multiplied out of is refilled first (once every wave has
-    // left it), so that the copies of NSTAGE steps are in flight while this step's are awaited: with
-    // two stages that is twice the bytes in flight of issuing after the wait, for one more barrier.
+    // left it), so that the copies of NSTAGE steps are in flight while this step's are awaited.
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (ld.valid) issue_next();
@@ -311,25 +486,11 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     asm volatile("" ::: "memory");
     const unsigned char* st = smem + cstage_off;
     cstage_off = (cstage_off + C::STAGE == (uint32_t)C::LDS_BYTES) ? 0u : cstage_off + C::STAGE;
-    const unsigned char* Ws = st;
-    const unsigned char* Xs = st + C::W_BYTES;
-    bf16x8 af[C::KSTEPS][C::MI], bfg[C::KSTEPS][C::NI];
+    Frag f[C::KSTEPS];
 #pragma unroll
-    for (int kk = 0; kk < C::KSTEPS; ++kk) {
+    for (int kk = 0; kk < C::KSTEPS; ++kk) read_frag(f[kk], st, kk);
 #pragma unroll
-      for (int mi = 0; mi < C::MI; ++mi)
-        af[kk][mi] = *reinterpret_cast<const bf16x8*>(Xs + a_row0 + mi * 32 * C::ROW_BYTES + frag_off[kk]);
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-        bfg[kk][ni] = *reinterpret_cast<const bf16x8*>(Ws + b_row0 + ni * 32 * C::ROW_BYTES + frag_off[kk]);
-    }
-#pragma unroll
-    for (int kk = 0; kk < C::KSTEPS; ++kk)
-#pragma unroll
-      for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < C::NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][mi], bfg[kk][ni], acc[mi][ni], 0, 0, 0);
+    for (int kk = 0; kk < C::KSTEPS; ++kk) mma(acc, f[kk]);
     // Shape of the schedule inside this block: the fragment reads of the first two k-steps go out
     // together, then every matrix instruction is paired with one read of the later k-steps, so that
     // LDS latency hides behind matrix work instead of being waited for read by read.
@@ -344,6 +505,12 @@ __global__ __launch_bounds__(256, (StreamCfg<B, TW>::WG_PER_CU)) void k_spmm_str
     __builtin_amdgcn_sched_group_barrier(0x008, kMfma - (kReads - kLead), 0);
     asm volatile("" ::: "memory");
     --ahead;
+  };
+  auto do_step = [&](f32x16 (&acc)[C::MI][C::NI]) {
+    if constexpr (PIPE)
+      do_step_pipe(acc);
+    else
+      do_step_two(acc);
   };
 
   // ---- compute: item by item -------------------------------------------------------------

@@ -24,6 +24,21 @@ def bits_of(t) -> np.ndarray:
     return t.cpu().numpy().view(np.uint16)
 
 
+def stratified_tokens(T, n_sample, tile=128, boundary=256):
+    """Token sample for the oracle: the first and the last token, one seeded draw from every `tile` tokens (every
+    token tile of every kernel holds a checked token), both sides of every multiple of `boundary` (the seams between
+    token tiles), topped up with uniform draws to n_sample."""
+    rng = np.random.default_rng(T)
+    sel = {0, T - 1}
+    for t0 in range(0, T, tile):
+        sel.add(int(rng.integers(t0, min(t0 + tile, T))))
+    for e in range(boundary, T, boundary):
+        sel.update((e - 1, e))
+    if len(sel) < n_sample:
+        sel.update(int(t) for t in rng.choice(T, size=n_sample - len(sel), replace=False))
+    return np.array(sorted(sel))
+
+
 # north_star tolerances: relative Frobenius error <= 1e-3, max elementwise error <= 1e-2 * RMS(oracle)
 REL_FRO = 1e-3
 MAX_ABS_RMS = 1e-2

@@ -10,7 +10,7 @@ import pytest
 
 from oracle import oracle as orc
 from paper_2507_03117_amd import synth
-from tests.helpers import bits_of, check_close, mask_dev, to_dev
+from tests.helpers import bits_of, check_close, mask_dev, stratified_tokens, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -59,21 +59,6 @@ def _packed(api, name):
         inp = synth.make_mlp(wl)
         _CACHE[name] = (wl, [_pack_pair(api, l, wl.b) for l in (inp.gate, inp.up, inp.down)])
     return _CACHE[name]
-
-
-def stratified_tokens(T, n_sample, tile=128, boundary=256):
-    """Token sample for the oracle: the first and the last token, one seeded draw from every `tile` tokens (every
-    token tile of every kernel holds a checked token), both sides of every multiple of `boundary` (the seams between
-    token tiles), topped up with uniform draws to n_sample."""
-    rng = np.random.default_rng(T)
-    sel = {0, T - 1}
-    for t0 in range(0, T, tile):
-        sel.add(int(rng.integers(t0, min(t0 + tile, T))))
-    for e in range(boundary, T, boundary):
-        sel.update((e - 1, e))
-    if len(sel) < n_sample:
-        sel.update(int(t) for t in rng.choice(T, size=n_sample - len(sel), replace=False))
-    return np.array(sorted(sel))
 
 
 def _run_mlp(api, name, T, n_sample, expect_nnz=None):
