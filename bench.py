@@ -1,33 +1,34 @@
 #!/usr/bin/env python3
 """Benchmark of the fused block-sparse SwiGLU MLP on one MI355X.
 
-A step = one pass of the MLP of Eq. (1) (gate/up products, activation, down
-product; output written) through the C ABI over one synthetic batch already
-resident in HBM.  Packing is done once before the timed region, like loading a
-checkpoint; its throughput is reported separately in "pack".
+A step = one pass of the MLP of Eq. (1) (gate/up products, activation, down product; output written) through
+the C ABI over one synthetic batch already resident in HBM.  Packing is done once before the timed region, like
+loading a checkpoint.
 
-Workload (benchmark configs[1]): Llama-3.2-1B-shaped MLP, hidden 2048,
-intermediate 8192, 64x64 blocks, 90 % uniform-random block sparsity.  The
-headline `value` is the prefill case T = 2048 (effective TFLOP/s on stored
-blocks); the decode token counts 1, 16, 128 are timed the same way and reported
-under "decode" as algorithmic HBM GB/s.
+Headline workload: the largest single-GPU configuration, the 405B-class layer (hidden 16384, intermediate 53248,
+128x128 blocks, 95 % block sparsity, Zipf-skewed rows) at 2048 tokens; `value` is its effective TFLOP/s on stored
+blocks.  The other configurations (single linear; 1B-shaped MLP at 1/16/128/2048 tokens; 3B-shaped sparsity sweep at
+4096 tokens; 8B-shaped decode; 405B-class decode) are timed the same way and reported as compact rows under
+"configs": prefill rows against the bf16 MFMA peak, decode rows as algorithmic HBM GB/s against the HBM peak.
 
-Timing: the K steps are timed twice.  Eagerly: the loop calls blast_sparse_mlp, every tenth
-step instrumented with HIP events (blast_sparse_mlp_events) for the per-phase and roofline
-figures.  And as one replay of a HIP graph that holds the same K calls; the headline `value`
-is the faster of the two ("config.launch" says which; normally the graph), both are reported
-in "launch_modes".
+Launch mode: the K steps are recorded once into a HIP graph (rotating weight copies) and replayed; `ms_per_step` is
+the median of three timed replays of those K steps.  The same K calls issued eagerly from Python are reported beside
+it ("eager").  If capture fails the eager figure is the headline and "launch" says so.
 
-Cold-HBM protocol: every step uses a different copy of the packed block values
-(>= 768 MB in rotation), so no step re-reads weights still sitting in the
-256 MB last-level cache.
+Cold-HBM protocol: every step uses a different copy of the packed block values (>= 768 MB in rotation), so no step
+re-reads weights still sitting in the 256 MB last-level cache.
+
+`roofline.traffic` is read at run time from the rocprofv3 counter summaries under profiles/ (lines starting with
+"traffic_bytes"), keyed by workload, token count and kernel; null when no summary covers the timed kernel.
 """
 from __future__ import annotations
 
 import argparse
 import ctypes as C
+import glob
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -37,19 +38,25 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
+HEADLINE = "llama405b_b128_s95_zipf"
 
-# HBM bytes per launch sequence from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), scaled by the
-# factor a plain copy kernel of known size reads on the same counters.  Filled from profiles/*.txt.
-# Source: profiles/bench_llama1b_b64_s90_hbm_traffic.txt (read x2.0, write x1.0; counters sit between each XCD's
-# L2 and the fabric).  Keys: (kernel, tokens) of the default workload.
-MEASURED_TRAFFIC_BYTES = {
-    ("gate_up", 2048): 62.96e6 + 34.49e6,
-    ("mlp", 1): 10.50e6 + 0.03e6,
-    ("mlp", 16): 12.56e6 + 0.41e6,
-    ("llama405b_b128_s95_zipf", 1): (175.63e6 + 0.12e6) + (88.61e6 + 0.13e6),
-    ("llama405b_b128_s95_zipf", 8): (178.13e6 + 0.96e6) + (97.70e6 + 1.00e6),
-    ("llama405b_b128_s95_zipf", 16): (181.38e6 + 1.92e6) + (112.39e6 + 2.01e6),
-}
+
+def profile_traffic(workload: str, tokens: int, kernel: str):
+    """HBM-side bytes per launch of `kernel` from the tracked counter summaries, or None.  A summary line reads
+    traffic_bytes | <workload> | T=<tokens> | <kernel> | fetch=<bytes> | write=<bytes> | <file it came from>."""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path):
+            if not line.startswith("traffic_bytes"):
+                continue
+            f = [x.strip() for x in line.split("|")]
+            if len(f) >= 6 and f[1] == workload and f[2] == "T=%d" % tokens and f[3] == kernel:
+                return {"bytes": float(f[4].split("=")[1]) + float(f[5].split("=")[1]),
+                        "source": os.path.relpath(path, ROOT)}
+    return None
+
+
+def sig(x, n=4):
+    return None if x is None else float("%.*g" % (n, x))
 
 
 def hip_runtime():
@@ -105,83 +112,38 @@ def rotated_copies(p, n_copies):
     return out
 
 
-EVENT_EVERY = 10  # steps between two instrumented steps of the timed loop
+
+def event_pair():
+    ev = Events(1)
+    ev.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+    return ev
 
 
-def time_mlp(api, torch, sets, x, T, steps, warmup, ws):
-    """Returns (wall ms per step, mean ms of phase 1, mean ms of phase 2, mean ms of the pass from events).
-
-    The timed loop calls blast_sparse_mlp; every EVENT_EVERY-th step goes through blast_sparse_mlp_events
-    instead, which records three hipEvents on the launch stream (each record costs the stream about 2.5 us,
-    so instrumenting every step would inflate the per-step wall time by more than a tenth at these sizes)."""
-    E = sets[0][2].rows
-    y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
-    marked = list(range(0, steps, EVENT_EVERY))
-    ev = Events(len(marked))
-    n = len(sets)
-    # arguments marshalled once per (weight set, event triple): the timed loop is one foreign call per step
-    plain = [api.prepare_sparse_mlp(g, u, d, x, y, ws) for g, u, d in sets]
-    calls = []
-    for i in range(steps):
-        if i % EVENT_EVERY == 0:
-            g, u, d = sets[(warmup + i) % n]
-            calls.append(api.prepare_sparse_mlp(g, u, d, x, y, ws, events=ev.triples[i // EVENT_EVERY]))
-        else:
-            calls.append(plain[(warmup + i) % n])
+def time_eager(torch, calls, steps, warmup):
+    """Wall ms per step of `steps` prepared calls issued from this thread, after `warmup` untimed ones."""
+    n = len(calls)
     for i in range(warmup):
-        plain[i % n]()
+        calls[i % n]()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for call in calls:
-        call()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    k = len(marked)
-    p1 = sum(ev.elapsed(t[0], t[1]) for t in ev.triples) / k
-    p2 = sum(ev.elapsed(t[1], t[2]) for t in ev.triples) / k
-    tot = sum(ev.elapsed(t[0], t[2]) for t in ev.triples) / k
-    ev.destroy()
-    return wall_ms, p1, p2, tot
-
-
-def time_gated_kernel(api, torch, sets, x, T, steps, warmup):
-    """Mean duration of the dominant kernel on its own: `steps` launches of the gate/up product + activation
-    (blast_bsr_gated_spmm, rotating weight copies) back to back between two hipEvents on the launch stream.
-    The interval per launch is the kernel plus the dispatch gap to the next one, without the event records
-    that the per-pass brackets of blast_sparse_mlp_events add around every phase."""
-    I = sets[0][0].rows
-    H = torch.empty((T, I), dtype=torch.bfloat16, device="cuda:0")
-    n = len(sets)
-    for i in range(warmup):
-        api.bsr_gated_spmm(sets[i % n][0], sets[i % n][1], x, out=H)
-    ev = Events(1)
-    hip, stream = ev.hip, C.c_void_p(torch.cuda.current_stream().cuda_stream)
-    hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
-    torch.cuda.synchronize()
-    hip.hipEventRecord(ev.triples[0][0], stream)
     for i in range(steps):
-        g, u, _ = sets[(warmup + i) % n]
-        api.bsr_gated_spmm(g, u, x, out=H)
-    hip.hipEventRecord(ev.triples[0][1], stream)
+        calls[(warmup + i) % n]()
     torch.cuda.synchronize()
-    ms = ev.elapsed(ev.triples[0][0], ev.triples[0][1]) / steps
-    ev.destroy()
-    return ms
+    return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def graph_time_mlp(api, torch, sets, x, T, steps, warmup):
-    """The same K steps recorded once into a HIP graph (rotating weight copies, fixed activation, output and
-    workspace buffers) and replayed: wall ms per step of one timed replay, after one untimed replay (K >= W
-    warm steps).  None if the capture is refused."""
+def time_graph(torch, make_calls, steps, warmup, replays=3):
+    """The same `steps` calls recorded once into a HIP graph and replayed: median wall ms per step over `replays`
+    timed replays (one untimed replay first).  make_calls() builds the prepared calls on the capture stream's
+    buffers.  None if the capture is refused."""
     try:
-        E = sets[0][2].rows
-        n = len(sets)
         st = torch.cuda.Stream()  # default priority
         torch.cuda.synchronize()
         with torch.cuda.stream(st):
-            y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
-            ws = torch.empty(max(api.mlp_workspace_bytes(*sets[0], T), 256), dtype=torch.uint8, device="cuda:0")
-            calls = [api.prepare_sparse_mlp(g, u, d, x, y, ws) for g, u, d in sets]
+            calls = make_calls()
+            n = len(calls)
+            for i in range(min(warmup, 2 * n)):
+                calls[i % n]()
             st.synchronize()
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=st):
@@ -189,72 +151,121 @@ def graph_time_mlp(api, torch, sets, x, T, steps, warmup):
                     calls[(warmup + i) % n]()
             graph.replay()
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            graph.replay()
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3 / steps
+            times = []
+            for _ in range(replays):
+                t0 = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                times.append((time.perf_counter() - t0) * 1e3 / steps)
         del graph
-        return ms
+        return statistics.median(times)
     except Exception as e:  # the eager figure stands
         print("graph replay not measured: %r" % (e,), file=sys.stderr)
         return None
 
 
-def decode_sweep(workload: str, tokens, steps: int, warmup: int, time_pack: bool = False):
-    """Decode-sized passes of another workload, packed here: list of per-token-count records.
-    time_pack: also time block-norm pruning + packing of the gate matrix at the workload's sparsity (on a
-    matrix of this size the packer is bound by reading the dense weight once)."""
-    import torch
+def time_gated_kernel(api, torch, sets, x, T, steps, warmup):
+    """Mean duration of the dominant kernel on its own: `steps` launches of the gate/up product + activation
+    (blast_bsr_gated_spmm, rotating weight copies) back to back between two hipEvents on the launch stream."""
+    I = sets[0][0].rows
+    H = torch.empty((T, I), dtype=torch.bfloat16, device="cuda:0")
+    n = len(sets)
+    for i in range(warmup):
+        api.bsr_gated_spmm(sets[i % n][0], sets[i % n][1], x, out=H)
+    ev = event_pair()
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ev.hip.hipEventRecord(ev.triples[0][0], stream)
+    for i in range(steps):
+        g, u, _ = sets[(warmup + i) % n]
+        api.bsr_gated_spmm(g, u, x, out=H)
+    ev.hip.hipEventRecord(ev.triples[0][1], stream)
+    torch.cuda.synchronize()
+    ms = ev.elapsed(ev.triples[0][0], ev.triples[0][1]) / steps
+    ev.destroy()
+    return ms
 
-    from paper_2507_03117_amd import api, synth
+
+class Layer:
+    """One workload packed on the device (and, on request, by the oracle), with rotated weight copies."""
+
+    def __init__(self, name, api, torch, synth, want_oracle=False):
+        from tests.helpers import mask_dev, to_dev
+
+        self.wl = wl = synth.WORKLOADS[name]
+        self.api, self.torch, self.synth = api, torch, synth
+        inp = synth.make_mlp(wl)
+        b = wl.b
+        packed = []
+        self.ref = []
+        for l in (inp.gate, inp.up, inp.down):
+            w_ = to_dev(l.W)
+            packed.append(api.bsr_pack(w_, b, mask=mask_dev(l.mask), nnz_cap=int(l.mask.sum())) if l.mask is not None
+                          else api.bsr_pack(w_, b, sparsity=l.sparsity))
+            del w_
+            if want_oracle:
+                from oracle import oracle as orc
+
+                self.ref.append(orc.pack(l.W, b, l.mask) if l.mask is not None else orc.pack_topk(l.W, b, l.sparsity)[0])
+        del inp
+        g, u, d = packed
+        self.g, self.u, self.d = api.with_joint_row_order(g, u), u, d
+        self.nnz = g.nnz + u.nnz + d.nnz
+        self.w_bytes = self.nnz * b * b * 2
+        n_copies = max(2, -(-768 * 1024 * 1024 // self.w_bytes))
+        self.sets = list(zip(rotated_copies(self.g, n_copies), rotated_copies(u, n_copies), rotated_copies(d, n_copies)))
+
+    def x(self, T):
+        from tests.helpers import to_dev
+
+        return to_dev(self.synth.make_x(self.wl, T))
+
+    def time(self, T, steps, warmup):
+        """(graph ms per pass or None, eager ms per pass) at T tokens."""
+        api, torch = self.api, self.torch
+        x = self.x(T)
+        E = self.wl.hidden
+
+        def make_calls():
+            y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
+            ws = torch.empty(max(api.mlp_workspace_bytes(self.g, self.u, self.d, T), 256), dtype=torch.uint8, device="cuda:0")
+            return [api.prepare_sparse_mlp(g, u, d, x, y, ws) for g, u, d in self.sets]
+
+        eager = time_eager(torch, make_calls(), steps, warmup)
+        graph = time_graph(torch, make_calls, steps, warmup)
+        return graph, eager
+
+    def row(self, T, steps, warmup):
+        """Compact record: [workload, T, us per pass (graph replay; eager if capture failed), us eager, bound,
+        achieved (TFLOP/s on stored blocks or algorithmic GB/s), fraction of the MI355X peak]."""
+        graph, eager = self.time(T, steps, warmup)
+        ms = graph if graph is not None else eager
+        wl, b = self.wl, self.wl.b
+        if T >= 512:
+            ach = 2.0 * b * b * T * self.nnz / (ms * 1e-3) / 1e12
+            return [wl.name, T, sig(ms * 1e3), sig(eager * 1e3), "mfma", sig(ach), sig(ach / PEAK_BF16_TFLOPS, 3)]
+        alg = self.w_bytes + 4 * self.nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
+        ach = alg / (ms * 1e-3) / 1e9
+        return [wl.name, T, sig(ms * 1e3), sig(eager * 1e3), "hbm", sig(ach), sig(ach / PEAK_HBM_GBS, 3)]
+
+
+def linear_row(api, torch, synth, steps, warmup):
+    """Configuration 1: the single block-sparse linear layer (latency-bound correctness case), timed like the rest."""
     from tests.helpers import mask_dev, to_dev
 
-    wl = synth.WORKLOADS[workload]
-    inp = synth.make_mlp(wl)
-    b = wl.b
-    packed = []
-    pack_rec = None
-    for l in (inp.gate, inp.up, inp.down):
-        w_ = to_dev(l.W)
-        if time_pack and pack_rec is None:
-            for _ in range(2):
-                api.bsr_pack(w_, b, sparsity=wl.sparsity)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(5):
-                api.bsr_pack(w_, b, sparsity=wl.sparsity)
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) / 5 * 1e3
-            dense = w_.numel() * 2
-            pack_rec = {"ms_gate_matrix_topk": ms, "dense_MB": dense / 1e6, "dense_GBps": dense / ms / 1e6,
-                        "frac_hbm": dense / ms / 1e6 / PEAK_HBM_GBS}
-        packed.append(api.bsr_pack(w_, b, mask=mask_dev(l.mask), nnz_cap=int(l.mask.sum())) if l.mask is not None
-                      else api.bsr_pack(w_, b, sparsity=l.sparsity))
-        del w_
-    del inp
-    g, u, d = packed
-    g = api.with_joint_row_order(g, u)
-    nnz = g.nnz + u.nnz + d.nnz
-    w_bytes = nnz * b * b * 2
-    n_copies = max(2, -(-768 * 1024 * 1024 // w_bytes))
-    sets = list(zip(rotated_copies(g, n_copies), rotated_copies(u, n_copies), rotated_copies(d, n_copies)))
-    out = []
-    for T in tokens:
-        x = to_dev(synth.make_x(wl, T))
-        ws = torch.empty(max(api.mlp_workspace_bytes(g, u, d, T), 256), dtype=torch.uint8, device="cuda:0")
-        wall_ms, p1, p2, tot = time_mlp(api, torch, sets, x, T, steps, warmup, ws)
-        alg_bytes = w_bytes + 4 * nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
-        gbs = alg_bytes / (wall_ms * 1e-3) / 1e9  # wall clock of the timed loop
-        out.append({"T": T, "ms_per_step": wall_ms, "ms_events": tot, "ms_gate_up": p1, "ms_down": p2,
-                    "alg_MB": alg_bytes / 1e6, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
-                    "GBps_events": alg_bytes / (tot * 1e-3) / 1e9,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, T))})
-    rec = {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b, "sparsity": wl.sparsity,
-           "mask": wl.mask_kind, "nnz_blocks": nnz, "weight_copies_in_rotation": n_copies, "passes": out}
-    if pack_rec is not None:
-        rec["pack"] = pack_rec
-    return rec
-
+    wl = synth.WORKLOADS["linear_1024x4096_b32_s90"]
+    lin = synth.make_linear(wl)
+    p = api.bsr_pack(to_dev(lin.W), wl.b, mask=mask_dev(lin.mask))
+    T = wl.tokens[0]
+    x = to_dev(synth.make_x(wl, T))
+    y = torch.empty((T, wl.inter), dtype=torch.float32, device="cuda:0")
+    fn = lambda: api.bsr_spmm(p, x, out=y)
+    eager = time_eager(torch, [fn], steps, warmup)
+    graph = time_graph(torch, lambda: [fn], steps, warmup)
+    ms = graph if graph is not None else eager
+    alg = p.nnz * wl.b * wl.b * 2 + 2 * wl.hidden * T + 4 * wl.inter * T
+    ach = alg / (ms * 1e-3) / 1e9
+    return [wl.name, T, sig(ms * 1e3), sig(eager * 1e3), "hbm", sig(ach), sig(ach / PEAK_HBM_GBS, 3)]
 
 def two_matrix_mlp(workload: str, steps: int, warmup: int, cpu: bool):
     """Y = W2 act(W1 X) (GELU) on a GPT-2-shaped block: wall-clock time per pass at the workload's token
@@ -473,25 +484,18 @@ def e5m2_product(workload: str, tokens, steps: int, warmup: int, cpu: bool):
     return out
 
 
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama1b_b64_s90")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--tokens", type=int, default=2048, help="token count of the headline step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--no-large-decode", action="store_true",
-                    help="skip the decode passes of the 405B-class layer (the case where weight bytes, not launch "
-                         "latency, set the time)")
-    ap.add_argument("--no-mlp2", action="store_true", help="skip the two-matrix MLP (GPT-2-shaped) passes")
-    ap.add_argument("--no-e5m2", action="store_true", help="skip the E5M2 product of the gate matrix")
-    ap.add_argument("--no-backward", action="store_true", help="skip the backward-pass products of the gate matrix")
-    ap.add_argument("--decode-tokens", default="", help="comma-separated decode token counts (default: the workload's)")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
-    ap.add_argument("--copies", type=int, default=0,
-                    help="weight copies in rotation (0 = enough for 768 MB: cold HBM; 1 = warm caches)")
+    ap.add_argument("--no-configs", action="store_true", help="time the headline workload only")
+    ap.add_argument("--extras", action="store_true",
+                    help="also: packer and mask-update times, two-matrix MLP, backward products, E5M2 product")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -502,40 +506,128 @@ def main():
     import torch
 
     from paper_2507_03117_amd import api, synth
-    from tests.helpers import mask_dev, to_dev
+    from tests.helpers import check_close, stratified_tokens
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     from paper_2507_03117_amd import build as hip_build
 
     hip_build.ensure_built()
     api.lib()
-    wl = synth.WORKLOADS[args.workload]
-    assert wl.kind == "mlp"
+    cpu = not args.no_cpu_baseline
+    T = args.tokens
+
+    # ---- headline ---------------------------------------------------------------------------------
+    L = Layer(args.workload, api, torch, synth, want_oracle=cpu)
+    wl, b = L.wl, L.wl.b
+    graph_ms, eager_ms = L.time(T, args.steps, args.warmup)
+    step_ms = graph_ms if graph_ms is not None else eager_ms
+    flops = 2.0 * b * b * T * L.nnz
+    tflops = flops / (step_ms * 1e-3) / 1e12
+    alg_bytes = L.w_bytes + 4 * L.nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
+    prefill = T >= 512
+    if prefill:
+        # dominant kernel: the gated gate/up product (2/3 of the stored blocks), timed on its own with events
+        gu_ms = time_gated_kernel(api, torch, L.sets, L.x(T), T, max(10, args.steps // 2), 3)
+        gu_tf = 2.0 * b * b * T * (L.g.nnz + L.u.nnz) / (gu_ms * 1e-3) / 1e12
+        kname = "k_spmm_stream<%d,dual> (gate/up + activation)" % b
+        tr = profile_traffic(wl.name, T, "gate_up")
+        roofline = {"bound": "mfma", "kernel": kname, "achieved": sig(gu_tf), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": sig(gu_tf / PEAK_BF16_TFLOPS, 3), "kernel_ms": sig(gu_ms),
+                    "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None}
+    else:
+        gbs = alg_bytes / (step_ms * 1e-3) / 1e9
+        tr = profile_traffic(wl.name, T, "mlp")
+        roofline = {"bound": "hbm", "kernel": "whole MLP pass", "achieved": sig(gbs), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": sig(gbs / PEAK_HBM_GBS, 3), "kernel_ms": sig(step_ms),
+                    "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None}
+    out = {
+        "metric": "fused BSR MLP effective TFLOP/s (stored blocks) + HBM GB/s vs roofline at 90-95% sparsity",
+        "value": sig(tflops, 5), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sig(step_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "tokens": T, "hidden": wl.hidden, "intermediate": wl.inter, "block": b,
+                   "sparsity": wl.sparsity, "mask": wl.mask_kind, "nnz_blocks": L.nnz, "x_layout": "token_major",
+                   "y_dtype": "f32", "weight_copies_in_rotation": len(L.sets),
+                   "launch": "hip_graph_replay, median of 3" if graph_ms is not None else "eager"},
+        "frac_mfma_peak": sig(tflops / PEAK_BF16_TFLOPS, 3), "eager_ms_per_step": sig(eager_ms, 5),
+        "alg_GBps": sig(alg_bytes / (step_ms * 1e-3) / 1e9), "roofline": roofline,
+    }
+
+    if cpu:
+        from oracle import oracle as orc
+
+        sel = stratified_tokens(T, 8) if T > 8 else np.arange(T)
+        xs = synth.make_x(wl, T)
+        t0 = time.perf_counter()
+        y_or = orc.mlp(*L.ref, np.ascontiguousarray(xs[sel]))
+        sec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sig(2.0 * b * b * sel.size * L.nnz / sec / 1e12), "unit": "TFLOP/s",
+                               "cores": orc.num_threads(), "kind": "oracle", "seconds": sig(sec),
+                               "sample": "%d of %d tokens (every 128-token tile, both sides of every 256-token seam), "
+                                         "all rows; dense masked fp64 loop" % (sel.size, T)}
+        # the same sample doubles as a parity check of the timed launch configuration
+        y = api.sparse_mlp(L.g, L.u, L.d, L.x(T))
+        torch.cuda.synchronize()
+        fro, mx = check_close(y.cpu().numpy()[sel].T, y_or, "bench parity")
+        out["parity_on_sample"] = {"rel_fro": sig(fro, 3), "max_abs_over_rms": sig(mx, 3)}
+        del y, y_or
+        L.ref = []
+
+    # ---- the other configurations -----------------------------------------------------------------
+    if not args.no_configs and args.workload == HEADLINE:
+        rows = []
+        dsteps = max(args.steps, 100)
+        for Td in (1, 16):  # the same layer at decode token counts: weight bytes, not launches, set the time
+            rows.append(L.row(Td, dsteps, args.warmup))
+        del L
+        torch.cuda.empty_cache()
+        rows.insert(0, linear_row(api, torch, synth, dsteps, args.warmup))
+        for name, toks, st in (("llama1b_b64_s90", (1, 16, 128, 2048), dsteps),
+                               ("llama3b_b64_s70", (4096,), args.steps), ("llama3b_b64_s80", (4096,), args.steps),
+                               ("llama3b_b64_s90", (4096,), args.steps), ("llama3b_b64_s95", (4096,), args.steps),
+                               ("llama8b_b128_s95", (1, 8, 32), dsteps)):
+            Lc = Layer(name, api, torch, synth)
+            for Tc in toks:
+                rows.append(Lc.row(Tc, st if Tc < 512 else args.steps, args.warmup))
+            del Lc
+            torch.cuda.empty_cache()
+        out["configs_columns"] = ["workload", "tokens", "us_graph", "us_eager", "bound", "TFLOPs|GBps", "frac_peak"]
+        out["configs"] = rows
+
+    if args.extras:
+        torch.cuda.empty_cache()
+        out["extras"] = {
+            "two_matrix_mlp": two_matrix_mlp("gpt2xl_b64_s80", args.steps, args.warmup, cpu),
+            "backward": backward_products("llama1b_b64_s90", 2048, args.steps, args.warmup, cpu),
+            "e5m2": e5m2_product("llama1b_b64_s90", (16, 2048), args.steps, args.warmup, cpu),
+            "pack": pack_times(api, torch, synth, cpu),
+        }
+
+    print(json.dumps(out, separators=(",", ":")))
+
+
+def pack_times(api, torch, synth, cpu):
+    """Block-norm pruning + packing (three matrices of the 1B-shaped layer, scoring mode) and one mask update of
+    blocked prune-and-grow on its gate matrix."""
+    import numpy as np
+
+    from tests.helpers import to_dev
+
+    wl = synth.WORKLOADS["llama1b_b64_s90"]
     inp = synth.make_mlp(wl)
     b = wl.b
-
-    # ---- pack once (timed separately) ------------------------------------------------------
-    def pack(lin):
-        if lin.mask is not None:
-            return api.bsr_pack(to_dev(lin.W), b, mask=mask_dev(lin.mask))
-        return api.bsr_pack(to_dev(lin.W), b, sparsity=lin.sparsity)
-
     dW = [to_dev(l.W) for l in (inp.gate, inp.up, inp.down)]
-    dM = [mask_dev(l.mask) if l.mask is not None else None for l in (inp.gate, inp.up, inp.down)]
-    packed = []
-    for w_, m_, l in zip(dW, dM, (inp.gate, inp.up, inp.down)):
-        packed.append(api.bsr_pack(w_, b, mask=m_, nnz_cap=int(l.mask.sum())) if m_ is not None
-                      else api.bsr_pack(w_, b, sparsity=l.sparsity))
+    reps = 5
+    for w_ in dW:
+        api.bsr_pack(w_, b, sparsity=wl.sparsity)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    reps = 5
     for _ in range(reps):
-        for w_, l in zip(dW, (inp.gate, inp.up, inp.down)):
-            api.bsr_pack(w_, b, sparsity=l.sparsity)  # the scoring mode: reads every dense weight once
+        for w_ in dW:
+            api.bsr_pack(w_, b, sparsity=wl.sparsity)  # the scoring mode: reads every dense weight once
     torch.cuda.synchronize()
     pack_ms = (time.perf_counter() - t0) * 1e3 / reps
     dense_bytes = sum(int(w_.numel()) * 2 for w_ in dW)
-    # one prune-and-grow mask update of the gate matrix (reads W and a gradient-shaped tensor once each)
     g_h = synth.gauss_bf16(np.random.default_rng(synth.BASE_SEED + 5), inp.gate.W.shape, 1e-3)
     dG = to_dev(g_h)
     api.generate_masks(dW[0], dG, b, wl.sparsity)
@@ -545,144 +637,18 @@ def main():
         api.generate_masks(dW[0], dG, b, wl.sparsity)
     torch.cuda.synchronize()
     masks_ms = (time.perf_counter() - t0) * 1e3 / reps
-    masks_bytes = 2 * int(dW[0].numel()) * 2
-    masks_cpu = None
-    if not args.no_cpu_baseline:
+    rec = {"ms_three_matrices_topk": pack_ms, "dense_GBps": dense_bytes / (pack_ms * 1e-3) / 1e9,
+           "frac_hbm": dense_bytes / (pack_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+           "generate_masks_ms_gate_matrix": masks_ms}
+    if cpu:
         from oracle import oracle as orc
 
         t0 = time.perf_counter()
         m_or = orc.generate_masks(inp.gate.W, g_h, b, wl.sparsity)
-        masks_cpu = {"seconds": time.perf_counter() - t0, "kind": "oracle", "cores": 1,
-                     "sample": "the whole gate matrix and gradient",
-                     "identical_to_device": bool(np.array_equal(m_or, api.generate_masks(dW[0], dG, b, wl.sparsity).cpu().numpy()))}
-    del dW, dG
-    g, u, d = packed
-    g = api.with_joint_row_order(g, u)
-    nnz = g.nnz + u.nnz + d.nnz
-    w_bytes = nnz * b * b * 2
-    n_copies = args.copies if args.copies > 0 else max(2, -(-768 * 1024 * 1024 // w_bytes))
-    sets = list(zip(rotated_copies(g, n_copies), rotated_copies(u, n_copies), rotated_copies(d, n_copies)))
-
-    def run_T(T, steps, warmup, warm_caches=False):
-        x = to_dev(synth.make_x(wl, T))
-        ws = torch.empty(max(api.mlp_workspace_bytes(g, u, d, T), 256), dtype=torch.uint8, device="cuda:0")
-        # warm_caches: one copy of the weights, re-read from the caches by every pass (a cache-bandwidth figure)
-        wall_ms, p1, p2, tot = time_mlp(api, torch, sets[:1] if warm_caches else sets, x, T, steps, warmup, ws)
-        flops = 2.0 * b * b * T * nnz
-        alg_bytes = w_bytes + 4 * nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
-        return dict(T=T, ms_per_step=wall_ms, ms_events=tot, ms_gate_up=p1, ms_down=p2, flops=flops,
-                    alg_bytes=alg_bytes)
-
-    T = args.tokens
-    head = run_T(T, args.steps, args.warmup)
-    eager_ms = head["ms_per_step"]
-    # The headline step time: the K steps replayed from one HIP graph (launch-bound loops belong in graphs on
-    # this hardware: the two kernels of a pass then follow each other without the host in between) or the eager
-    # loop's, whichever way of launching the same K steps is faster here.  Both are reported.
-    graph_ms = graph_time_mlp(api, torch, sets, to_dev(synth.make_x(wl, T)), T, args.steps, args.warmup) if T > 256 else None
-    use_graph = graph_ms is not None and graph_ms <= eager_ms
-    step_ms = graph_ms if use_graph else eager_ms
-    tflops = head["flops"] / (step_ms * 1e-3) / 1e12
-
-    # roofline of the dominant kernel (gate/up product + activation: 2/3 of the stored blocks)
-    gu_flops = 2.0 * b * b * T * (g.nnz + u.nnz)
-    mfma_bound = T >= 512
-    if mfma_bound:
-        # the kernel's own duration: back-to-back launches between two events (the bracket of a phase inside a
-        # pass, phases_ms, also holds two event records and reads about 4 us more)
-        gu_ms = time_gated_kernel(api, torch, sets, to_dev(synth.make_x(wl, T)), T, args.steps, args.warmup)
-        gu_tflops = gu_flops / (gu_ms * 1e-3) / 1e12
-        roofline = dict(bound="mfma", kernel="k_spmm_stream<%d,dual> (gate/up + activation)" % b, achieved=gu_tflops,
-                        peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=gu_tflops / PEAK_BF16_TFLOPS,
-                        avg_kernel_ms=gu_ms, avg_ms_inside_a_pass=head["ms_gate_up"], traffic=MEASURED_TRAFFIC_BYTES.get(("gate_up", T)) if args.workload == "llama1b_b64_s90" else None)
-    else:
-        gbs = head["alg_bytes"] / (head["ms_events"] * 1e-3) / 1e9
-        roofline = dict(bound="hbm", kernel="whole MLP pass (event interval)", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=gbs / PEAK_HBM_GBS, avg_kernel_ms=head["ms_events"],
-                        traffic=MEASURED_TRAFFIC_BYTES.get(("mlp", T)))
-
-    out = {
-        "metric": "fused BSR MLP effective TFLOP/s (stored blocks only), prefill T=%d" % T,
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "hidden": wl.hidden, "intermediate": wl.inter, "block": b,
-                   "sparsity": wl.sparsity, "mask": wl.mask_kind, "tokens": T, "nnz_blocks": nnz,
-                   "x_layout": "token_major", "y_dtype": "f32", "weight_copies_in_rotation": n_copies,
-                   "launch": "hip_graph_replay" if use_graph else "eager"},
-        "launch_modes": {"eager_ms_per_step": eager_ms, "eager_TFLOPs": head["flops"] / (eager_ms * 1e-3) / 1e12,
-                         "graph_replay_ms_per_step": graph_ms},
-        "frac_of_mfma_peak": tflops / PEAK_BF16_TFLOPS,
-        "phases_ms": {"gate_up_act": head["ms_gate_up"], "down": head["ms_down"], "pass_events": head["ms_events"]},
-        "roofline": roofline,
-        "pack": {"ms_three_matrices_topk": pack_ms, "dense_GBps": dense_bytes / (pack_ms * 1e-3) / 1e9,
-                 "frac_hbm": dense_bytes / (pack_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                 "generate_masks": {"ms_gate_matrix": masks_ms, "GBps": masks_bytes / (masks_ms * 1e-3) / 1e9,
-                                    "frac_hbm": masks_bytes / (masks_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                    "cpu_baseline": masks_cpu}},
-    }
-
-    if not args.no_decode:
-        dec = []
-        dec_T = [int(t) for t in args.decode_tokens.split(",") if t] or [t for t in wl.tokens if t <= 128]
-        for Td in dec_T:
-            r = run_T(Td, max(args.steps, 100), args.warmup)
-            gbs = r["alg_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9  # wall clock of the timed loop
-            warm = run_T(Td, max(args.steps, 100), args.warmup, warm_caches=True)
-            dec.append({"T": Td, "ms_per_step": r["ms_per_step"], "ms_events": r["ms_events"],
-                        "ms_gate_up": r["ms_gate_up"], "ms_down": r["ms_down"], "alg_MB": r["alg_bytes"] / 1e6,
-                        "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
-                        "GBps_events": r["alg_bytes"] / (r["ms_events"] * 1e-3) / 1e9,
-                        "warm_caches": {"ms_per_step": warm["ms_per_step"], "ms_events": warm["ms_events"],
-                                        "GBps_cache": r["alg_bytes"] / (warm["ms_per_step"] * 1e-3) / 1e9},
-                        "traffic": MEASURED_TRAFFIC_BYTES.get(("mlp", Td)) if args.workload == "llama1b_b64_s90" else None,
-                        "TFLOPs": r["flops"] / (r["ms_events"] * 1e-3) / 1e12})
-        out["decode"] = dec
-
-    if not args.no_cpu_baseline:
-        from oracle import oracle as orc
-
-        Ts = min(args.cpu_sample_tokens, T)
-        rg = orc.pack(inp.gate.W, b, inp.gate.mask) if inp.gate.mask is not None else orc.pack_topk(inp.gate.W, b, wl.sparsity)[0]
-        ru = orc.pack(inp.up.W, b, inp.up.mask) if inp.up.mask is not None else orc.pack_topk(inp.up.W, b, wl.sparsity)[0]
-        rd = orc.pack(inp.down.W, b, inp.down.mask) if inp.down.mask is not None else orc.pack_topk(inp.down.W, b, wl.sparsity)[0]
-        xs = synth.make_x(wl, T)[:Ts]
-        t0 = time.perf_counter()
-        y_or = orc.mlp(rg, ru, rd, np.ascontiguousarray(xs))
-        sec = time.perf_counter() - t0
-        out["cpu_baseline"] = {
-            "value": 2.0 * b * b * Ts * nnz / sec / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(),
-            "kind": "oracle", "seconds": sec,
-            "sample": "first %d of %d tokens, all rows; dense masked fp64 triple loop (it also multiplies the zeros)" % (Ts, T),
-        }
-        # the same sample doubles as a parity check of the timed launch configuration
-        x = to_dev(synth.make_x(wl, T))
-        y = api.sparse_mlp(g, u, d, x)
-        torch.cuda.synchronize()
-        yh = y[:Ts].cpu().numpy().astype(np.float64).T
-        out["parity_on_sample"] = {
-            "rel_fro": float(np.linalg.norm(yh - y_or) / np.linalg.norm(y_or)),
-            "max_abs_over_rms": float(np.abs(yh - y_or).max() / np.sqrt((y_or ** 2).mean())),
-        }
-
-    if not args.no_large_decode and args.workload == "llama1b_b64_s90":
-        del sets
-        torch.cuda.empty_cache()
-        out["decode_hbm_bound"] = decode_sweep("llama405b_b128_s95_zipf", (1, 8, 16), 30, 5, time_pack=True)
-
-    if not args.no_mlp2 and args.workload == "llama1b_b64_s90":
-        torch.cuda.empty_cache()
-        out["two_matrix_mlp"] = two_matrix_mlp("gpt2xl_b64_s80", args.steps, args.warmup, not args.no_cpu_baseline)
-
-    if not args.no_backward and args.workload == "llama1b_b64_s90":
-        torch.cuda.empty_cache()
-        out["backward"] = backward_products(args.workload, T, args.steps, args.warmup, not args.no_cpu_baseline)
-
-    if not args.no_e5m2 and args.workload == "llama1b_b64_s90":
-        torch.cuda.empty_cache()
-        out["e5m2"] = e5m2_product(args.workload, (16, T), args.steps, args.warmup, not args.no_cpu_baseline)
-
-    print(json.dumps(out))
+        rec["generate_masks_cpu_baseline"] = {
+            "seconds": time.perf_counter() - t0, "kind": "oracle", "cores": 1, "sample": "the whole gate matrix and gradient",
+            "identical_to_device": bool(np.array_equal(m_or, api.generate_masks(dW[0], dG, b, wl.sparsity).cpu().numpy()))}
+    return rec
 
 
 if __name__ == "__main__":
