@@ -326,9 +326,12 @@ int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_byte
  *                      need no initialisation and mean nothing afterwards; two calls that may overlap in
  *                      time (different streams) need different workspaces.
  * Up to one token tile (T <= 32, or 16 for b = 128) with token-major, 16-byte aligned X and at most 32 MB of
- * stored blocks in the three matrices the whole of Eq. (1) runs as one kernel launch: the workgroups of the second product wait inside the kernel until the slices of
- * H they read have been published (a bounded wait; should it ever expire, their output rows are NaN).
- * While `stream` is being captured into a graph the two-launch form is recorded instead.
+ * stored blocks in the three matrices the whole of Eq. (1) runs as one kernel launch: the workgroups of the second
+ * product wait inside the kernel until the slices of H they read have been published by the workgroups of the first
+ * (a bounded wait; should it ever expire, their output rows are NaN and blast_sparse_mlp_status reports it).  The
+ * hand-over state lives in the workspace and sets itself up: the workspace still needs no initialisation.  The call
+ * can be recorded into a HIP graph like any other; replays tell themselves apart through an epoch that the kernel
+ * advances in the workspace.
  * Never synchronises.  Errors: INVALID_ARG, SHAPE (including inconsistent I/E/b between the three
  * matrices), UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */
@@ -337,6 +340,32 @@ int blast_sparse_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, con
                      int32_t y_dtype, void* ws, size_t ws_bytes, void* stream);
 int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
                                int64_t T, size_t* ws_bytes /* HOST */);
+
+/*
+ * Status of the in-kernel hand-over of the single-launch form (see blast_sparse_mlp) for the workspace a call
+ * used: *status = 0 when every wait ended normally (or no single-launch call has used the workspace at this
+ * shape), 1 when a workgroup of the second product gave up waiting for H (its output rows are NaN), 2 when
+ * a wave gave up waiting for the set-up of the control block.  A nonzero status is cleared by the call.
+ *   Wgate, T   the first matrix and the token count of the calls in question (they fix where the control
+ *              block sits in the workspace)
+ *   ws         the workspace those calls used; NULL = the library's own scratch (blast_sparse_mlp_static)
+ *   status     HOST, out
+ * Waits for `stream`.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
+ */
+int blast_sparse_mlp_status(const blast_bsr_view* Wgate, int64_t T, const void* ws, size_t ws_bytes,
+                            int32_t* status /* HOST */, void* stream);
+
+/*
+ * Diagnostic form of blast_sparse_mlp for testing the failure handling of the hand-over from the host, with
+ * every kernel still exiting normally: `spin_limit` (>= 1) replaces the number of polls after which a wait gives
+ * up, and a nonzero `withhold_publication` makes the workgroups of the first product compute H without
+ * publishing it, so that every wait of the second product expires.  Outside the single-launch form the two
+ * extra arguments have no effect.  Same arguments, results and errors as blast_sparse_mlp otherwise.
+ */
+int blast_sparse_mlp_handover_test(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
+                                   const blast_bsr_view* Wdown, const uint16_t* X, int64_t ldx, int32_t x_layout,
+                                   int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                                   size_t ws_bytes, void* stream, int32_t spin_limit, int32_t withhold_publication);
 
 /*
  * blast_sparse_mlp for callers that cannot allocate device memory or hand over a workspace: code under HIP
@@ -363,7 +392,7 @@ size_t blast_sparse_mlp_static_limit(void);
  * with an element-wise nonlinearity between them, fused into the first product):
  *   H = bf16(act(W1 X)),  Y = W2 H.
  * W1 is I x E, W2 is E x I, both packed with the same block size.  Arithmetic, layouts, workspace rules,
- * the single-launch form for one token tile, graph-capture behaviour and errors are those of
+ * the single-launch form for one token tile and errors are those of
  * blast_sparse_mlp (with W1 in the place of Wgate and no Wup); an empty block row of W1 gives a zero
  * row of H since act(0) = 0 for all three activations.
  */

@@ -29,7 +29,8 @@ EXPORTS = (
     "blast_pooled_topk_mask", "blast_pooled_topk_mask_workspace", "blast_quantize_e5m2", "blast_quantize_e5m2_groups",
     "blast_bsr_spmm_e5m2",
     "blast_bsr_unpack", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
-    "blast_sparse_mlp_static", "blast_sparse_mlp_static_limit",
+    "blast_sparse_mlp_static", "blast_sparse_mlp_static_limit", "blast_sparse_mlp_status",
+    "blast_sparse_mlp_handover_test",
 )
 
 
@@ -78,6 +79,10 @@ def lib():
         L.blast_bsr_spmm_workspace.argtypes = [pv, i64, C.POINTER(sz)]
         L.blast_sparse_mlp.restype = C.c_int
         L.blast_sparse_mlp.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp, sz, vp]
+        L.blast_sparse_mlp_status.restype = C.c_int
+        L.blast_sparse_mlp_status.argtypes = [pv, i64, vp, sz, C.POINTER(i32), vp]
+        L.blast_sparse_mlp_handover_test.restype = C.c_int
+        L.blast_sparse_mlp_handover_test.argtypes = L.blast_sparse_mlp.argtypes + [i32, i32]
         L.blast_sparse_mlp_static.restype = C.c_int
         L.blast_sparse_mlp_static.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp]
         L.blast_sparse_mlp_static_limit.restype = sz
@@ -383,6 +388,16 @@ def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor,
     else:
         _check(L.blast_sparse_mlp_events(*args, events), "blast_sparse_mlp_events")
     return Y
+
+
+def sparse_mlp_status(gate: PackedBsr, T: int, ws: Optional[torch.Tensor]) -> int:
+    """blast_sparse_mlp_status: 0 = every in-kernel wait of the single-launch form ended normally; ws=None asks
+    about the library's own scratch (sparse_mlp_static).  Waits for the current stream."""
+    vg = gate.view()
+    st = C.c_int32(-1)
+    _check(lib().blast_sparse_mlp_status(C.byref(vg), T, _ptr(ws), ws.numel() if ws is not None else 0, C.byref(st),
+                                         _stream()), "blast_sparse_mlp_status")
+    return int(st.value)
 
 
 def sparse_mlp_static(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor, out: torch.Tensor, *,

@@ -477,10 +477,17 @@ extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_
 namespace {
 
 // H in bf16, token-major [T][I]; then the publication slots of the single-launch form (one 64-bit word
-// per 16 rows of H) and two status words
-size_t mlp_workspace_bytes(int64_t I, int64_t T) {
-  return blast::align_up((size_t)T * (size_t)I * 2, 256) + blast::align_up((size_t)(I / 16) * 8, 256) + 256;
-}
+// per 16 rows of H) and the control block of the hand-over: signature, epoch, status word, arrival counters
+size_t mlp_h_bytes(int64_t I, int64_t T) { return blast::align_up((size_t)T * (size_t)I * 2, 256); }
+size_t mlp_slot_bytes(int64_t I) { return blast::align_up((size_t)(I / 16) * 8, 256); }
+size_t mlp_workspace_bytes(int64_t I, int64_t T) { return mlp_h_bytes(I, T) + mlp_slot_bytes(I) + kCtlBytes; }
+constexpr size_t kCtlStatusOffset = 16;  // byte offset of the status word inside the control block
+
+// Knobs of the hand-over inside the single-launch form; the defaults are what every ordinary call uses.
+struct HandoverKnobs {
+  int max_spins = kDecMaxSpins;
+  int withhold = 0;
+};
 
 }  // namespace
 
@@ -545,9 +552,10 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
   return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream, side);
 }
 
-// Every single-launch MLP gets its own token (never 0): a slot of the workspace says "published" only
-// when it holds the token of the running launch, so the slots need no clearing between launches and no
-// initialisation (a stale or random word equals a fresh 64-bit token with probability 2^-64).
+// Every single-launch MLP call gets its own token (never 0), which the kernel mixes with an epoch it keeps in
+// the workspace: a slot says "published" only when it holds the token of the running launch, so the slots
+// need no clearing between launches and no initialisation (a stale or random word equals a fresh 64-bit
+// token with probability 2^-64), and a call recorded into a graph differs from replay to replay in the epoch.
 unsigned long long next_token() {
   static std::atomic<unsigned long long> counter{0x243F6A8885A308D3ull};
   return counter.fetch_add(0x9E3779B97F4A7C15ull) | 1ull;
@@ -571,8 +579,8 @@ int launch_mlp_decode(const DecArgs& p, const DecArgs& c, hipStream_t stream) {
 // decode kernel's fast path anyway and no row of Wdown is cut into chunks.
 template <int B, bool GATED>
 int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
-                       const TileArgs& g, const TileArgs& d, uint16_t* H, unsigned long long* slots, int* err,
-                       hipStream_t stream) {
+                       const TileArgs& g, const TileArgs& d, uint16_t* H, unsigned long long* slots,
+                       unsigned long long* ctl, const HandoverKnobs& knobs, hipStream_t stream) {
   DecArgs p{}, c{};
   p.m0 = g.m0;
   p.m1 = g.m1;
@@ -589,7 +597,10 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
   p.groups = 1;
   p.slots = slots;
   p.token = next_token();
-  p.sync_err = err;
+  p.ctl = ctl;
+  p.max_spins = knobs.max_spins;
+  p.withhold = knobs.withhold;
+  p.sync_err = reinterpret_cast<int*>(reinterpret_cast<char*>(ctl) + kCtlStatusOffset);
   c.m0 = d.m0;
   c.row_order = d.row_order;
   c.X = H;
@@ -604,7 +615,17 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
   c.groups = 1;
   c.slots = slots;
   c.token = p.token;
-  c.sync_err = err;
+  c.ctl = ctl;
+  c.max_spins = knobs.max_spins;
+  c.withhold = knobs.withhold;
+  c.sync_err = p.sync_err;
+  p.total_waves = c.total_waves = (p.n_units + c.n_units) * 4;
+  {  // a launch adds 2^shift to each of the 64 arrival counters: the smallest power of two >= the largest group
+    const int largest = (p.total_waves + kCtlGroups - 1) / kCtlGroups;
+    int shift = 0;
+    while ((1 << shift) < largest) ++shift;
+    p.ctl_shift = c.ctl_shift = shift;
+  }
   (void)Wup;
   if constexpr (B >= 64) {
     if (g.T <= 512 / B) return launch_mlp_decode<B, 1, true, GATED>(p, c, stream);
@@ -616,7 +637,8 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
 
 int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
                 const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy,
-                int32_t y_dtype, void* ws, size_t ws_bytes, hipStream_t stream, void* const* events) {
+                int32_t y_dtype, void* ws, size_t ws_bytes, hipStream_t stream, void* const* events,
+                const HandoverKnobs& knobs = HandoverKnobs{}) {
   if (int rc = check_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype)) return rc;
   const int64_t I = Wgate->rows, E = Wgate->cols;
   const int32_t b = Wgate->b;
@@ -627,13 +649,6 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
 
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[0]), stream));
   const int64_t one_tile = (b == 128) ? 16 : 32;
-  // A captured launch would carry its token into every replay of the graph, and a replay would then find the
-  // slots of the previous replay already "published": while capturing, the two-launch form is recorded.
-  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(stream, &cap) != hipSuccess) {
-    (void)hipGetLastError();
-    cap = hipStreamCaptureStatusNone;
-  }
   // One launch saves a dispatch gap and the second kernel's ramp, a few microseconds; its smaller copy rings
   // (producers and consumers share the CUs) cost bandwidth.  Measured with uniform masks and cold weights:
   // about even up to 18 MB of stored blocks, 63 us against 55 us on the 405B-class layer (262 MB).
@@ -641,7 +656,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   const bool fused_pays = stored_bytes <= ((int64_t)32 << 20);
   // (b >= 64: a token's slice of one block column of H then fills whole 128-byte lines, so a line is never
   // read by one consumer while the producers of a neighbouring column are still writing the rest of it)
-  if (I > 0 && T <= one_tile && cap == hipStreamCaptureStatusNone && (b == 64 || b == 128) && fused_pays &&
+  if (I > 0 && T <= one_tile && (b == 64 || b == 128) && fused_pays && (I / 16 + E / 16) * 4 < INT32_MAX / 2 &&
       x_layout == BLAST_TOKEN_MAJOR && ldx % 8 == 0 &&
       blast::aligned(X, 16) && T * ldx * 2 < ((int64_t)1 << 32) && !plan_of(Wdown, T).hdr) {
     TileArgs g{}, d{};
@@ -656,18 +671,17 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
     set_y(d, Y, ldy, x_layout, y_dtype);
     d.T = (int)T;
     char* wsb = static_cast<char*>(ws);
-    const size_t h_bytes = blast::align_up((size_t)T * (size_t)I * 2, 256);
-    unsigned long long* slots = reinterpret_cast<unsigned long long*>(wsb + h_bytes);
-    int* err = reinterpret_cast<int*>(wsb + h_bytes + blast::align_up((size_t)(I / 16) * 8, 256));
+    unsigned long long* slots = reinterpret_cast<unsigned long long*>(wsb + mlp_h_bytes(I, T));
+    unsigned long long* ctl = reinterpret_cast<unsigned long long*>(wsb + mlp_h_bytes(I, T) + mlp_slot_bytes(I));
     // one kernel does both phases: events[1] falls before it
     if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));
     int rc;
     if (Wup) {
-      rc = (b == 64) ? enqueue_mlp_decode<64, true>(Wgate, Wup, Wdown, g, d, H, slots, err, stream)
-                     : enqueue_mlp_decode<128, true>(Wgate, Wup, Wdown, g, d, H, slots, err, stream);
+      rc = (b == 64) ? enqueue_mlp_decode<64, true>(Wgate, Wup, Wdown, g, d, H, slots, ctl, knobs, stream)
+                     : enqueue_mlp_decode<128, true>(Wgate, Wup, Wdown, g, d, H, slots, ctl, knobs, stream);
     } else {
-      rc = (b == 64) ? enqueue_mlp_decode<64, false>(Wgate, Wup, Wdown, g, d, H, slots, err, stream)
-                     : enqueue_mlp_decode<128, false>(Wgate, Wup, Wdown, g, d, H, slots, err, stream);
+      rc = (b == 64) ? enqueue_mlp_decode<64, false>(Wgate, Wup, Wdown, g, d, H, slots, ctl, knobs, stream)
+                     : enqueue_mlp_decode<128, false>(Wgate, Wup, Wdown, g, d, H, slots, ctl, knobs, stream);
     }
     if (rc) return rc;
     if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
@@ -760,6 +774,51 @@ extern "C" int blast_sparse_mlp_static(const blast_bsr_view* Wgate, const blast_
   if (int rc = static_scratch(&ws)) return rc;
   return enqueue_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, kStaticScratchBytes,
                      static_cast<hipStream_t>(stream_), nullptr);
+}
+
+extern "C" int blast_sparse_mlp_handover_test(const blast_bsr_view* Wgate, const blast_bsr_view* Wup,
+                                              const blast_bsr_view* Wdown, const uint16_t* X, int64_t ldx,
+                                              int32_t x_layout, int64_t T, int32_t act, void* Y, int64_t ldy,
+                                              int32_t y_dtype, void* ws, size_t ws_bytes, void* stream_,
+                                              int32_t spin_limit, int32_t withhold_publication) {
+  if (!Wup || spin_limit < 1) return BLAST_ERR_INVALID_ARG;
+  HandoverKnobs knobs;
+  knobs.max_spins = spin_limit;
+  knobs.withhold = withhold_publication ? 1 : 0;
+  return enqueue_mlp(Wgate, Wup, Wdown, X, ldx, x_layout, T, act, Y, ldy, y_dtype, ws, ws_bytes,
+                     static_cast<hipStream_t>(stream_), nullptr, knobs);
+}
+
+extern "C" int blast_sparse_mlp_status(const blast_bsr_view* Wgate, int64_t T, const void* ws, size_t ws_bytes,
+                                       int32_t* status, void* stream_) {
+  if (int rc = check_view(Wgate)) return rc;
+  if (T < 0 || !status) return BLAST_ERR_INVALID_ARG;
+  *status = 0;
+  const int64_t I = Wgate->rows;
+  const void* base = ws;
+  size_t have = ws_bytes;
+  if (!base) {  // the library's own scratch array (blast_sparse_mlp_static)
+    void* p = nullptr;
+    if (int rc = static_scratch(&p)) return rc;
+    base = p;
+    have = kStaticScratchBytes;
+  }
+  if (have < mlp_workspace_bytes(I, T) || !blast::aligned(base, 256)) return BLAST_ERR_WORKSPACE;
+  const char* ctl = static_cast<const char*>(base) + mlp_h_bytes(I, T) + mlp_slot_bytes(I);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  BLAST_HIP_TRY(hipStreamSynchronize(stream));
+  unsigned long long sig = 0;
+  BLAST_HIP_TRY(hipMemcpy(&sig, ctl, sizeof(sig), hipMemcpyDeviceToHost));
+  // the signature carries the wave count of the launch shape in its low bits
+  if ((sig ^ kCtlReady) >> 32) return BLAST_OK;  // no single-launch call has used this workspace at this shape
+  int32_t word = 0;
+  BLAST_HIP_TRY(hipMemcpy(&word, ctl + kCtlStatusOffset, sizeof(word), hipMemcpyDeviceToHost));
+  *status = word;
+  if (word != 0) {
+    const int32_t zero = 0;
+    BLAST_HIP_TRY(hipMemcpy(const_cast<char*>(ctl) + kCtlStatusOffset, &zero, sizeof(zero), hipMemcpyHostToDevice));
+  }
+  return BLAST_OK;
 }
 
 extern "C" int blast_sparse_mlp2(const blast_bsr_view* W1, const blast_bsr_view* W2, const uint16_t* X, int64_t ldx,

@@ -48,10 +48,17 @@ struct DecArgs {
   const int* chunk_kb;   // first stored block of the chunk
   const int* chunk_ke;   // one past its last stored block
   // single-launch MLP only: one 64-bit slot per (block row of H, 16-row slice); the producer of that
-  // slice stores `token` there once its part of H is visible device-wide, consumers wait for it
+  // slice stores the launch's token there once its part of H is visible device-wide, consumers wait for it.
+  // The token is `token` (drawn on the host, one per call) mixed with the epoch kept in ctl[1], see
+  // handover_token(): a replay of a captured call differs from the previous replay in the epoch.
   unsigned long long* slots;
   unsigned long long token;
-  int* sync_err;         // set to 1 if a consumer gave up waiting (the result is then invalid)
+  unsigned long long* ctl;  // control block in the workspace (kCtlBytes): signature, epoch, status, arrival counters
+  int total_waves;          // waves of the whole launch
+  int ctl_shift;            // log2 of what a launch adds to each arrival counter (a power of two >= the largest group)
+  int max_spins;            // polls before a wait gives up (never hang the GPU)
+  int withhold;             // diagnostic: producers compute H but do not publish it
+  int* sync_err;            // status word: kHandoverTimedOut / kHandoverInitTimedOut once a wait has given up
   // Side job of a launch (z_blocks > 0): workgroups [main_blocks, main_blocks + z_blocks) clear the fp32
   // rows that a LATER chunked product will accumulate into (the rows of block rows cut into several
   // chunks), so that product needs no clearing launch of its own.  One workgroup per chunk slot.
@@ -80,6 +87,106 @@ __device__ __forceinline__ void decode_zero_job(const DecArgs& a, int ci) {
 
 enum DecRole { kDecAlone = 0, kDecProducer = 1, kDecConsumer = 2 };
 constexpr int kDecMaxSpins = 1 << 19;  // polls of ~0.3 us each before a consumer gives up (never hang the GPU)
+constexpr unsigned long long kCtlReady = 0xB1A57C7100D0C0DEull;  // the control block has been set up
+constexpr unsigned long long kCtlBusy = 0xB1A57C71B0057EEDull;   // a wave is setting it up right now
+constexpr int kHandoverTimedOut = 1, kHandoverInitTimedOut = 2;
+
+constexpr int kCtlGroups = 64;        // arrival counters, each in a 128-byte line of its own
+constexpr int kCtlLineWords = 16;     // 64-bit words per line
+// Control block of the single-launch form, in 64-bit words (kCtlBytes bytes of the workspace):
+//   [0] signature  [2] status (low 32 bits)  [(2 + g) * kCtlLineWords], g < kCtlGroups: arrival counters
+constexpr int kCtlGroupWord0 = 2 * kCtlLineWords;
+constexpr int kCtlBytes = (2 + kCtlGroups) * kCtlLineWords * 8;
+
+// Every wave of a single-launch MLP calls handover_peek first thing, handover_begin once it needs the token
+// and handover_leave as its last act.
+//
+// The token of a launch is the call's host-drawn token mixed with an epoch that must change from launch to
+// launch on the same workspace (a call recorded into a graph is replayed with the same arguments).  The
+// epoch is not stored anywhere: it is read off an arrival counter.  Wave number n belongs to group n % 64
+// and, when it leaves, adds 1 to its group's counter - the group's first wave adds the rest up to a power
+// of two P as well, so that a launch adds exactly P to every counter.  A counter therefore stays inside
+// [epoch * P, (epoch + 1) * P) from the first to the last wave of a launch, whichever waves have already
+// left, and counter >> log2(P) is the same number for every wave of the launch and one more for the next
+// launch.  Nobody waits for anybody, no addition returns a value, and no address takes more than a few dozen
+// additions per launch.  Launches on one workspace are ordered by their stream (overlapping calls need
+// different workspaces), and what a launch added is visible when the next one starts.
+//
+// The control block needs no initialisation by the caller: a wave that does not find the signature of its
+// launch shape (the number of waves is part of it) claims the set-up with a compare-and-swap on whatever it
+// found there; the winner clears the counters and the status word, waits for those stores to be
+// acknowledged and writes the signature; every other wave polls for the signature (the winner is running
+// and waits for nothing, so that wait ends; it is bounded besides).
+struct HandoverPeek {
+  unsigned long long sig, count;
+};
+struct Handover {
+  unsigned long long token;  // of this launch, the same in every wave
+  unsigned long long add;    // what this wave adds to its group's counter when it leaves
+  int group;
+};
+__device__ __forceinline__ int handover_group() { return (blockIdx.x * 4 + (threadIdx.x >> 6)) % kCtlGroups; }
+
+// The signature as the scalar cache sees it (a stale value only sends the wave down the slow path of
+// handover_begin) and this wave's counter read past the caches (a value from any moment of this launch
+// gives the same epoch; one cached before the set-up of the control block would not).  Issued first thing
+// in a wave, used later.
+__device__ __forceinline__ HandoverPeek handover_peek(const DecArgs& a) {
+  const __attribute__((address_space(4))) unsigned long long* c =
+      reinterpret_cast<const __attribute__((address_space(4))) unsigned long long*>(reinterpret_cast<uintptr_t>(a.ctl));
+  return HandoverPeek{c[0], __hip_atomic_load(a.ctl + kCtlGroupWord0 + handover_group() * kCtlLineWords, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT)};
+}
+
+__device__ __forceinline__ Handover handover_begin(const DecArgs& a, const HandoverPeek& pk) {
+  Handover h{};
+  const int wave_id = blockIdx.x * 4 + (threadIdx.x >> 6);
+  h.group = wave_id % kCtlGroups;
+  const int group_size = a.total_waves / kCtlGroups + (h.group < a.total_waves % kCtlGroups ? 1 : 0);
+  h.add = wave_id < kCtlGroups ? (1ull << a.ctl_shift) - (unsigned long long)group_size + 1ull : 1ull;
+  const unsigned long long ready = kCtlReady ^ (unsigned long long)(unsigned)a.total_waves;
+  unsigned long long count = pk.count;
+  if (pk.sig != ready) {
+    if ((threadIdx.x & 63) == 0) {
+      unsigned long long m = __hip_atomic_load(a.ctl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (m != ready) {
+        bool won = false;
+        if (m != kCtlBusy)
+          won = __hip_atomic_compare_exchange_strong(a.ctl, &m, kCtlBusy, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        if (won) {
+          for (int i = 1; i < kCtlBytes / 8; i += (i < kCtlLineWords ? 1 : kCtlLineWords))
+            __hip_atomic_store(a.ctl + i, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));  // all acknowledged before the signature appears
+          asm volatile("" ::: "memory");
+          __hip_atomic_store(a.ctl, ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+          int spins = 0;
+          while (__hip_atomic_load(a.ctl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != ready) {
+            if (++spins > a.max_spins) {
+              __hip_atomic_store(a.sync_err, kHandoverInitTimedOut, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+          }
+        }
+      }
+    }
+    // the counter has just been cleared (waves that have left since may have added to it): read it afresh
+    count = __hip_atomic_load(a.ctl + kCtlGroupWord0 + h.group * kCtlLineWords, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  const unsigned long long epoch = count >> a.ctl_shift;
+  const unsigned elo = __builtin_amdgcn_readfirstlane((unsigned)epoch);
+  const unsigned ehi = __builtin_amdgcn_readfirstlane((unsigned)(epoch >> 32));
+  h.token = (a.token ^ ((((unsigned long long)ehi << 32) | elo) * 0x9E3779B97F4A7C15ull)) | 1ull;
+  return h;
+}
+
+__device__ __forceinline__ void handover_leave(const DecArgs& a, const Handover& h) {
+  if ((threadIdx.x & 63) == 0)
+    (void)__hip_atomic_fetch_add(a.ctl + kCtlGroupWord0 + h.group * kCtlLineWords, h.add, __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // XSMALL > 0: the activation tile of a block holds only as many token rows as XSMALL copy instructions
 // bring (XSMALL * 512 / B); valid when T does not exceed that.  It shrinks a ring slot, hence allows more
@@ -141,6 +248,9 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
 
   int r, kb0, n0, kb1 = 0, n1 = 0;
   bool shared_row = false;
+  Handover hand{};  // single-launch MLP only
+  HandoverPeek peek{};
+  if (ROLE != kDecAlone) peek = handover_peek(a);
   if (CHUNK) {
     const int ci = unit / C::SLICES;
     if (ci >= ld_idx(a.hdr, 0)) return;  // the grid is sized by an upper bound of the number of chunks
@@ -238,17 +348,19 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) warm ^= *reinterpret_cast<const uint32_t*>(wblk + woff[ni]);
     }
+    hand = handover_begin(a, peek);
+    const unsigned long long token = hand.token;
     bool gave_up = false;
 #pragma unroll 1
-    for (int j = 0; j < cnt; ++j) {
+    for (int j = 0; j < cnt && !gave_up; ++j) {
       const int col = ld_idx(a.m0.col_idx, kb0 + wave + 4 * j);
       const unsigned long long* sl = a.slots + (int64_t)col * C::SLICES;
       int spins = 0;
       for (;;) {
         const unsigned long long v =
-            lane < C::SLICES ? __hip_atomic_load(sl + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.token;
-        if (__ballot(v != a.token) == 0) break;
-        if (++spins > kDecMaxSpins) {
+            lane < C::SLICES ? __hip_atomic_load(sl + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : token;
+        if (__ballot(v != token) == 0) break;
+        if (++spins > a.max_spins) {
           gave_up = true;
           break;
         }
@@ -256,8 +368,8 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
       }
     }
     if (gave_up) {
-      // never observed; if it happens the output rows of this unit become NaN instead of plausible numbers
-      if (lane == 0) __hip_atomic_store(a.sync_err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // the output rows of this unit become NaN instead of plausible numbers, and the status word says why
+      if (lane == 0) __hip_atomic_store(a.sync_err, kHandoverTimedOut, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
       for (int tt = 0; tt < NTT; ++tt) acc[0][tt] = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
     }
@@ -266,9 +378,11 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     asm volatile("" ::: "memory");
   }
 
+  // a producer draws the launch's token while its first copies are in flight; it needs it only to publish
   if constexpr (C::XONE) {
     static_assert(!C::XONE || NSLOT == 2, "the single activation tile is written for two weight slots");
     if (cnt > 0) issue(0);
+    if (ROLE == kDecProducer) hand = handover_begin(a, peek);
 #pragma unroll 1
     for (int j = 0; j < cnt; ++j) {
       const bool more = j + 1 < cnt;
@@ -314,6 +428,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
 #pragma unroll 1
   for (int j = 0; j < NSLOT - 1; ++j)
     if (j < cnt) issue(j);
+  if (ROLE == kDecProducer) hand = handover_begin(a, peek);
 
 #pragma unroll 1
   for (int j = 0; j < cnt; ++j) {
@@ -367,7 +482,10 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
         for (int j = 0; j < 4; ++j) red[wave - 1][m][tt][j][lane] = acc[m][tt][j];
   }
   __syncthreads();
-  if (wave > 0) return;
+  if (wave > 0) {
+    if (ROLE != kDecAlone) handover_leave(a, hand);
+    return;
+  }
 #pragma unroll
   for (int m = 0; m < NM; ++m)
 #pragma unroll
@@ -403,9 +521,10 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     // all of this wave's stores have been acknowledged before the slot says so
     __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
     asm volatile("" ::: "memory");
-    if (lane == 0)
-      __hip_atomic_store(a.slots + (int64_t)r * C::SLICES + q, a.token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0 && !a.withhold)
+      __hip_atomic_store(a.slots + (int64_t)r * C::SLICES + q, hand.token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  if (ROLE != kDecAlone) handover_leave(a, hand);
 }
 
 template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL, bool POST = false>
