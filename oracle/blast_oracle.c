@@ -456,3 +456,49 @@ void oracle_spmm_e5m2(int64_t rows, int64_t cols, int32_t b, const int32_t* row_
     }
   free(Wd);
 }
+
+/* Y = W~ X with the stored block values in E5M2 and the activations in bf16 (weights in the 8-bit type of
+ * Sec. 5.2, activations in the 16-bit type: every code is decoded exactly, the dense masked product is taken
+ * in fp64).  X element (k,t) lives at X[k*sxk + t*sxt]. */
+void oracle_spmm_e5m2w(int64_t rows, int64_t cols, int32_t b, const int32_t* row_ptr, const int32_t* col_idx,
+                       const uint8_t* vals8, const uint16_t* X, int64_t sxk, int64_t sxt, int64_t T,
+                       double* Y /* [rows][T] */) {
+  int64_t nbr = rows / b;
+  double* Wd = (double*)calloc((size_t)(rows * cols > 0 ? rows * cols : 1), sizeof(double));
+  for (int64_t br = 0; br < nbr; ++br)
+    for (int64_t k = row_ptr[br]; k < row_ptr[br + 1]; ++k)
+      for (int32_t i = 0; i < b; ++i)
+        for (int32_t j = 0; j < b; ++j)
+          Wd[(br * b + i) * cols + (int64_t)col_idx[k] * b + j] = oracle_e5m2_to_f64(vals8[(k * b + i) * b + j]);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t t = 0; t < T; ++t) {
+      double s = 0.0;
+      for (int64_t k = 0; k < cols; ++k) s += Wd[i * cols + k] * bf16_to_f64(X[k * sxk + t * sxt]);
+      Y[i * T + t] = s;
+    }
+  free(Wd);
+}
+
+/* Eq. (1) with the three weights stored in E5M2 (Sec. 5.2) and everything else as in oracle_mlp:
+ * G = W~g X, U = W~u X from the decoded codes and the bf16 activations, H = bf16(act(G) * U), Y = W~d H.
+ * H_bits (may be NULL) receives the rounded intermediate, [I][T]. */
+void oracle_mlp_e5m2w(int64_t E, int64_t I, int32_t b,
+                      const int32_t* g_row_ptr, const int32_t* g_col_idx, const uint8_t* g_vals8,
+                      const int32_t* u_row_ptr, const int32_t* u_col_idx, const uint8_t* u_vals8,
+                      const int32_t* d_row_ptr, const int32_t* d_col_idx, const uint8_t* d_vals8,
+                      const uint16_t* X, int64_t sxk, int64_t sxt, int64_t T, int32_t act,
+                      double* Y /* [E][T] */, uint16_t* H_bits /* [I][T] or NULL */) {
+  size_t it = (size_t)I * (size_t)T;
+  double* G = (double*)malloc(sizeof(double) * (it ? it : 1));
+  double* U = (double*)malloc(sizeof(double) * (it ? it : 1));
+  uint16_t* H = (uint16_t*)malloc(sizeof(uint16_t) * (it ? it : 1));
+  oracle_spmm_e5m2w(I, E, b, g_row_ptr, g_col_idx, g_vals8, X, sxk, sxt, T, G);
+  oracle_spmm_e5m2w(I, E, b, u_row_ptr, u_col_idx, u_vals8, X, sxk, sxt, T, U);
+  for (size_t p = 0; p < it; ++p) H[p] = f32_to_bf16_rne((float)(oracle_act(act, G[p]) * U[p]));
+  oracle_spmm_e5m2w(E, I, b, d_row_ptr, d_col_idx, d_vals8, H, T, 1, T, Y);
+  if (H_bits) memcpy(H_bits, H, sizeof(uint16_t) * it);
+  free(G);
+  free(U);
+  free(H);
+}

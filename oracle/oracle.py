@@ -54,6 +54,10 @@ def lib():
         L.oracle_sparsity_schedule.argtypes = [i64, i64, i64, dbl, dbl]
         L.oracle_pooled_scores.restype = None
         L.oracle_pooled_scores.argtypes = [vp, i64, i64, i64, i32, vp]
+        L.oracle_spmm_e5m2w.restype = None
+        L.oracle_spmm_e5m2w.argtypes = [i64, i64, i32, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.oracle_mlp_e5m2w.restype = None
+        L.oracle_mlp_e5m2w.argtypes = [i64, i64, i32] + [vp] * 9 + [vp, i64, i64, i64, i32, vp, vp]
         L.oracle_e5m2_to_f64.restype = dbl
         L.oracle_e5m2_to_f64.argtypes = [C.c_uint8]
         L.oracle_f64_to_e5m2.restype = C.c_uint8
@@ -281,3 +285,30 @@ def spmm_e5m2(w: Bsr, vals8: np.ndarray, X8: np.ndarray, layout: str = "token_ma
     Y = np.zeros((w.rows, T), dtype=np.float64)
     lib().oracle_spmm_e5m2(w.rows, w.cols, w.b, _p(w.row_ptr), _p(w.col_idx), _p(vals8), _p(X8), sxk, sxt, T, _p(Y))
     return Y
+
+
+def spmm_e5m2w(w: Bsr, vals8: np.ndarray, X: np.ndarray, layout: str = "token_major") -> np.ndarray:
+    """Y = W~ X with E5M2 block values `vals8` [nnz, b, b] on the structure of `w` and bf16 activations: fp64 [rows, T]."""
+    vals8 = np.ascontiguousarray(vals8, dtype=np.uint8)
+    assert vals8.shape == (w.nnz, w.b, w.b)
+    K, T, sxk, sxt = _x_strides(X, layout)
+    assert K == w.cols
+    Y = np.zeros((w.rows, T), dtype=np.float64)
+    lib().oracle_spmm_e5m2w(w.rows, w.cols, w.b, _p(w.row_ptr), _p(w.col_idx), _p(vals8), _p(X), sxk, sxt, T, _p(Y))
+    return Y
+
+
+def mlp_e5m2w(gate: Bsr, g8: np.ndarray, up: Bsr, u8: np.ndarray, down: Bsr, d8: np.ndarray, X: np.ndarray,
+              layout: str = "token_major", activation: str = "silu", return_h: bool = False):
+    """Eq. (1) with the three weights given as E5M2 codes on the structures of gate / up / down, bf16 activations
+    and bf16 intermediate: Y fp64 [E, T] (and H bf16 bits [I, T] if asked)."""
+    K, T, sxk, sxt = _x_strides(X, layout)
+    E, I, b = gate.cols, gate.rows, gate.b
+    assert K == E and up.rows == I and up.cols == E and down.rows == E and down.cols == I
+    g8, u8, d8 = (np.ascontiguousarray(v, dtype=np.uint8) for v in (g8, u8, d8))
+    assert g8.shape == (gate.nnz, b, b) and u8.shape == (up.nnz, b, b) and d8.shape == (down.nnz, b, b)
+    Y = np.zeros((E, T), dtype=np.float64)
+    H = np.zeros((I, T), dtype=np.uint16) if return_h else None
+    lib().oracle_mlp_e5m2w(E, I, b, _p(gate.row_ptr), _p(gate.col_idx), _p(g8), _p(up.row_ptr), _p(up.col_idx), _p(u8),
+                           _p(down.row_ptr), _p(down.col_idx), _p(d8), _p(X), sxk, sxt, T, ACT[activation], _p(Y), _p(H))
+    return (Y, H) if return_h else Y

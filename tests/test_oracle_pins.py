@@ -727,3 +727,55 @@ def test_spmm_e5m2_equals_numpy_on_decoded_values():
     pp = orc.pack(Wp, b, mask)
     assert np.array_equal(orc.spmm_e5m2(pp, orc.e5m2_quantize(f64(pp.vals).astype(np.float32)), orc.e5m2_quantize(Xp)),
                           orc.spmm(pp, synth.f32_to_bf16_bits(Xp)))
+
+
+def _dense_from_codes(p, vals8):
+    """Dense masked matrix from E5M2 codes, decoded through numpy's float16 (a code is the upper byte of a half)."""
+    b = p.b
+    Wd = np.zeros((p.rows, p.cols))
+    rr = np.repeat(np.arange(p.rows // b), np.diff(p.row_ptr))
+    for q in range(p.nnz):
+        blk = (vals8[q].astype(np.uint16) << 8).view(np.float16).astype(np.float64)
+        Wd[rr[q] * b:(rr[q] + 1) * b, p.col_idx[q] * b:(p.col_idx[q] + 1) * b] = blk
+    return Wd
+
+
+def test_e5m2_weight_product_and_mlp_equal_numpy_on_decoded_weights():
+    """Weights in E5M2, activations and the intermediate in bf16 (the decode form of the 8-bit run of Sec. 5.2):
+    the product against numpy on weights decoded independently (float16 view), the MLP against the dense
+    formula with a bit-equal intermediate, and against the bf16 MLP when the weights are exact in E5M2."""
+    rng = np.random.default_rng(73)
+    E, I, b, T = 64, 96, 16, 5
+    Ws = [synth.gauss_bf16(rng, s, 0.3) for s in ((I, E), (I, E), (E, I))]
+    ms = [synth.uniform_mask(rng, r // b, c // b, 0.5) for r, c in ((I, E), (I, E), (E, I))]
+    ms[0][1, :] = 0
+    ps = [orc.pack(w, b, m) for w, m in zip(Ws, ms)]
+    v8 = [orc.e5m2_quantize(f64(p.vals).astype(np.float32)) for p in ps]
+    X = synth.gauss_bf16(rng, (T, E), 1.0)
+    Xf = f64(X)
+    # single product
+    Y = orc.spmm_e5m2w(ps[0], v8[0], X)
+    np.testing.assert_allclose(Y, _dense_from_codes(ps[0], v8[0]) @ Xf.T, rtol=1e-12, atol=1e-15)
+    assert not Y[b:2 * b].any()
+    assert np.array_equal(Y, orc.spmm_e5m2w(ps[0], v8[0], np.ascontiguousarray(X.T), layout="feature_major"))
+    # quantisation moved the weights: the 8-bit product differs from the 16-bit one, by about a mantissa step
+    Y16 = orc.spmm(ps[0], X)
+    rel = np.linalg.norm(Y - Y16) / np.linalg.norm(Y16)
+    assert 1e-3 < rel < 0.15
+    # MLP: dense formula on the decoded weights, intermediate rounded once to bf16
+    Wg, Wu, Wd = (_dense_from_codes(p, v) for p, v in zip(ps, v8))
+    G, U = Wg @ Xf.T, Wu @ Xf.T
+    h = (G / (1.0 + np.exp(-G)) * U).astype(np.float32)
+    Hb = synth.f32_to_bf16_bits(h)
+    Yw, H = orc.mlp_e5m2w(ps[0], v8[0], ps[1], v8[1], ps[2], v8[2], X, return_h=True)
+    assert np.array_equal(H, Hb)
+    np.testing.assert_allclose(Yw, Wd @ f64(Hb), rtol=1e-12, atol=1e-15)
+    assert not f64(H[b:2 * b]).any()  # an empty gate row: zeros (of either sign)
+    # weights that are exact in E5M2: the same numbers as the bf16 MLP, bit for bit
+    Wx = [synth.f32_to_bf16_bits(rng.choice([-1.0, -0.5, 0.0, 0.25, 0.5, 1.5], size=w.shape).astype(np.float32)) for w in Ws]
+    px = [orc.pack(w, b, m) for w, m in zip(Wx, ms)]
+    vx = [orc.e5m2_quantize(f64(p.vals).astype(np.float32)) for p in px]
+    assert np.array_equal(orc.mlp_e5m2w(px[0], vx[0], px[1], vx[1], px[2], vx[2], X), orc.mlp(px[0], px[1], px[2], X))
+    for act in ("gelu", "relu"):
+        assert np.array_equal(orc.mlp_e5m2w(px[0], vx[0], px[1], vx[1], px[2], vx[2], X, activation=act),
+                              orc.mlp(px[0], px[1], px[2], X, activation=act))
