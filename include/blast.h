@@ -238,6 +238,30 @@ int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8, const uin
                         int64_t T, void* Y, int64_t ldy, int32_t y_dtype, void* stream);
 
 /*
+ * Fused gated MLP with the three weights stored in E5M2 (Sec. 5.2 reports the kernel in float8_e5m2; at decode
+ * token counts the pass is bound by reading the stored blocks once, and one byte per weight halves those
+ * bytes).  Activations and the intermediate stay in bf16:
+ *   G = W~gate X, U = W~up X with every E5M2 code widened exactly to bf16, fp32 accumulation;
+ *   H = bf16(act(G) * U), one rounding; Y = W~down H, fp32 accumulation (Eq. (1)).
+ * That is blast_sparse_mlp on the dequantised weights, with half the weight traffic.
+ *   Wgate/Wup/Wdown   structure of the packed matrices (row_ptr, col_idx, row_order, nnz, b; vals is not read);
+ *                     b = 64 or 128
+ *   gate8/up8/down8   E5M2 block values, [nnz][b][b], one byte each, in the order of the view's vals
+ *                     (blast_quantize_e5m2 of it), 16-byte aligned
+ *   X, ldx            token-major bf16 activations [T][E], ldx % 8 == 0, 16-byte aligned; T * ldx * 2 and
+ *                     T * I * 2 below 2^32 (the call is meant for decode token counts; any such T is correct)
+ *   Y, ldy, y_dtype   token-major [T][E], fp32 or bf16
+ *   ws                at least blast_sparse_mlp_e5m2w_workspace() bytes (H), 256-byte aligned
+ * Two launches, no in-kernel hand-over, rows are never split into chunks.  Never synchronises.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK (b other than 64 / 128), WORKSPACE, HIP.
+ */
+int blast_sparse_mlp_e5m2w(const blast_bsr_view* Wgate, const uint8_t* gate8, const blast_bsr_view* Wup,
+                           const uint8_t* up8, const blast_bsr_view* Wdown, const uint8_t* down8, const uint16_t* X,
+                           int64_t ldx, int64_t T, int32_t act, void* Y, int64_t ldy, int32_t y_dtype, void* ws,
+                           size_t ws_bytes, void* stream);
+int blast_sparse_mlp_e5m2w_workspace(const blast_bsr_view* Wgate, int64_t T, size_t* ws_bytes /* HOST */);
+
+/*
  * Packed transpose.  Sec. 3.2: the pruned matrix is the one used in forward AND backward propagation;
  * Sec. 3.4 / 3.4.1: which compressed format suits depends on the side the sparse matrix is multiplied
  * from, and the kernel for the other side is the symmetric one.  This call builds, from a packed W~

@@ -30,7 +30,7 @@ EXPORTS = (
     "blast_bsr_spmm_e5m2",
     "blast_bsr_unpack", "blast_bsr_gated_spmm", "blast_bsr_joint_row_order",
     "blast_sparse_mlp_static", "blast_sparse_mlp_static_limit", "blast_sparse_mlp_status",
-    "blast_sparse_mlp_handover_test",
+    "blast_sparse_mlp_handover_test", "blast_sparse_mlp_e5m2w", "blast_sparse_mlp_e5m2w_workspace",
 )
 
 
@@ -83,6 +83,10 @@ def lib():
         L.blast_sparse_mlp_status.argtypes = [pv, i64, vp, sz, C.POINTER(i32), vp]
         L.blast_sparse_mlp_handover_test.restype = C.c_int
         L.blast_sparse_mlp_handover_test.argtypes = L.blast_sparse_mlp.argtypes + [i32, i32]
+        L.blast_sparse_mlp_e5m2w.restype = C.c_int
+        L.blast_sparse_mlp_e5m2w.argtypes = [pv, vp, pv, vp, pv, vp, vp, i64, i64, i32, vp, i64, i32, vp, sz, vp]
+        L.blast_sparse_mlp_e5m2w_workspace.restype = C.c_int
+        L.blast_sparse_mlp_e5m2w_workspace.argtypes = [pv, i64, C.POINTER(sz)]
         L.blast_sparse_mlp_static.restype = C.c_int
         L.blast_sparse_mlp_static.argtypes = [pv, pv, pv, vp, i64, i32, i64, i32, vp, i64, i32, vp]
         L.blast_sparse_mlp_static_limit.restype = sz
@@ -387,6 +391,28 @@ def sparse_mlp(gate: PackedBsr, up: PackedBsr, down: PackedBsr, X: torch.Tensor,
         _check(L.blast_sparse_mlp(*args), "blast_sparse_mlp")
     else:
         _check(L.blast_sparse_mlp_events(*args, events), "blast_sparse_mlp_events")
+    return Y
+
+
+def sparse_mlp_e5m2w(gate: PackedBsr, gate8: torch.Tensor, up: PackedBsr, up8: torch.Tensor, down: PackedBsr,
+                     down8: torch.Tensor, X: torch.Tensor, *, act: str = "silu", out_dtype: torch.dtype = torch.float32,
+                     out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """blast_sparse_mlp_e5m2w: the gated MLP with E5M2 block values (quantize_e5m2 of each matrix's vals),
+    token-major bf16 activations."""
+    L = lib()
+    T, K, ldx = _layout_dims(X, TOKEN_MAJOR)
+    assert K == gate.cols
+    for v8, m in ((gate8, gate), (up8, up), (down8, down)):
+        assert v8.is_cuda and v8.dtype == torch.uint8 and v8.numel() >= m.nnz * m.b * m.b
+    Y = out if out is not None else _alloc_out(down.rows, T, TOKEN_MAJOR, out_dtype, X.device)
+    vg, vu, vd = gate.view(), up.view(), down.view()
+    if ws is None:
+        wsb = C.c_size_t(0)
+        _check(L.blast_sparse_mlp_e5m2w_workspace(C.byref(vg), T, C.byref(wsb)), "blast_sparse_mlp_e5m2w_workspace")
+        ws = torch.empty(max(int(wsb.value), 256), dtype=torch.uint8, device=X.device)
+    _check(L.blast_sparse_mlp_e5m2w(C.byref(vg), _ptr(gate8), C.byref(vu), _ptr(up8), C.byref(vd), _ptr(down8), _ptr(X),
+                                    ldx, T, ACT[act], _ptr(Y), Y.stride(0), BF16 if Y.dtype == torch.bfloat16 else F32,
+                                    _ptr(ws), ws.numel(), _stream()), "blast_sparse_mlp_e5m2w")
     return Y
 
 

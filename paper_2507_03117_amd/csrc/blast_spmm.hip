@@ -153,11 +153,12 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
 template <int B, bool DUAL, bool CHUNK>
 int launch_stream_c(const TileArgs& a, const ChunkPlan& plan, int64_t k_features, hipStream_t stream) {
   if constexpr (B == 128) {
-    // 256-token x 128-row tiles (eight waves, one workgroup per CU) once they fill the chip; below that,
-    // 128-token tiles in four-wave workgroups, two per CU
+    // 256-token x 128-row tiles (eight waves, one workgroup per CU) once every CU gets at least two of them;
+    // below that, 128-token tiles in four-wave workgroups, two per CU (8B-shaped down projection at 2048
+    // tokens, 256 wide tiles: 24.9 against 28.2 us)
     const int64_t n_rows = CHUNK ? plan.max_chunks : (int64_t)a.nbr;
     const int64_t wide_items = (int64_t)((a.T + 255) / 256) * n_rows;
-    if (wide_items >= (int64_t)cu_count()) return launch_stream_tw<B, DUAL, 4, CHUNK, 8>(a, plan, k_features, stream);
+    if (wide_items >= 2 * (int64_t)cu_count()) return launch_stream_tw<B, DUAL, 4, CHUNK, 8>(a, plan, k_features, stream);
     return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, k_features, stream);
   } else if constexpr (B == 64) {
     // 128-token tiles when 256-token tiles would leave workgroup slots empty
@@ -819,6 +820,107 @@ extern "C" int blast_sparse_mlp_status(const blast_bsr_view* Wgate, int64_t T, c
     BLAST_HIP_TRY(hipMemcpy(const_cast<char*>(ctl) + kCtlStatusOffset, &zero, sizeof(zero), hipMemcpyHostToDevice));
   }
   return BLAST_OK;
+}
+
+// ---- E5M2 weights, bf16 activations: the decode form of the 8-bit run (Sec. 5.2) ------------------------
+namespace {
+
+template <int B, bool DUAL, int NTT, int XSMALL>
+int launch_decode_w8_ntt(const TileArgs& a, hipStream_t stream) {
+  DecArgs d{};
+  d.m0 = a.m0;
+  d.m1 = a.m1;
+  d.row_order = a.row_order;
+  d.X = a.X;
+  d.sxt = a.sxt;
+  d.Y = a.Y;
+  d.syt = a.syt;
+  d.syi = a.syi;
+  d.y_bf16 = a.y_bf16;
+  d.T = a.T;
+  d.act = a.act;
+  const int64_t units = (int64_t)a.nbr * (B / 16);
+  if (units <= 0) return BLAST_OK;
+  const int64_t groups = (a.T + NTT * 16 - 1) / (NTT * 16);
+  const int64_t grid = (units + 7) / 8 * 8 * groups;
+  if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
+  d.n_units = (int)units;
+  d.groups = (int)groups;
+  using C = DecCfg<B, DUAL, NTT, XSMALL, false, true>;
+  static blast::DeviceFlags lds_set;
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, false, XSMALL, false, true>),
+                                C::LDS_BYTES, lds_set))
+    return rc;
+  k_decode<B, DUAL, NTT, false, XSMALL, false, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(d);
+  BLAST_LAUNCH_CHECK("k_decode (E5M2 weights)");
+  return BLAST_OK;
+}
+
+template <int B, bool DUAL>
+int launch_decode_w8(const TileArgs& a, hipStream_t stream) {
+  // the smallest activation tile that holds T token rows, as in launch_decode
+  if (a.T <= 512 / B) return launch_decode_w8_ntt<B, DUAL, 1, 1>(a, stream);
+  if constexpr (B == 128) {
+    if (a.T <= 8) return launch_decode_w8_ntt<B, DUAL, 1, 2>(a, stream);
+  }
+  if (a.T <= 16) return launch_decode_w8_ntt<B, DUAL, 1, 0>(a, stream);
+  return launch_decode_w8_ntt<B, DUAL, 2, 0>(a, stream);
+}
+
+}  // namespace
+
+extern "C" int blast_sparse_mlp_e5m2w_workspace(const blast_bsr_view* Wgate, int64_t T, size_t* ws_bytes) {
+  if (int rc = check_view(Wgate)) return rc;
+  if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
+  *ws_bytes = mlp_h_bytes(Wgate->rows, T);
+  return BLAST_OK;
+}
+
+extern "C" int blast_sparse_mlp_e5m2w(const blast_bsr_view* Wgate, const uint8_t* gate8, const blast_bsr_view* Wup,
+                                      const uint8_t* up8, const blast_bsr_view* Wdown, const uint8_t* down8,
+                                      const uint16_t* X, int64_t ldx, int64_t T, int32_t act, void* Y, int64_t ldy,
+                                      int32_t y_dtype, void* ws, size_t ws_bytes, void* stream_) {
+  if (!Wup) return BLAST_ERR_INVALID_ARG;
+  if (int rc = check_mlp(Wgate, Wup, Wdown, X, ldx, BLAST_TOKEN_MAJOR, T, act, Y, ldy, y_dtype)) return rc;
+  const int64_t I = Wgate->rows, E = Wgate->cols;
+  const int32_t b = Wgate->b;
+  if (b != 64 && b != 128) return BLAST_ERR_UNSUPPORTED_BLOCK;
+  if ((Wgate->nnz > 0 && !gate8) || (Wup->nnz > 0 && !up8) || (Wdown->nnz > 0 && !down8)) return BLAST_ERR_INVALID_ARG;
+  if (!blast::aligned(gate8, 16) || !blast::aligned(up8, 16) || !blast::aligned(down8, 16)) return BLAST_ERR_INVALID_ARG;
+  if (T == 0 || E == 0) return BLAST_OK;
+  // the copies address a block column of the activations with 32-bit byte offsets and fetch 16 bytes at a time
+  if (ldx % 8 != 0 || !blast::aligned(X, 16) || T * ldx * 2 >= ((int64_t)1 << 32) || T * I * 2 >= ((int64_t)1 << 32))
+    return BLAST_ERR_INVALID_ARG;
+  const size_t need = mlp_h_bytes(I, T);
+  if (need > 0 && (!ws || ws_bytes < need || !blast::aligned(ws, 256))) return BLAST_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  uint16_t* H = static_cast<uint16_t*>(ws);
+  TileArgs g{};
+  g.m0 = mat_of(Wgate);
+  g.m0.vals8 = gate8;
+  g.m1 = mat_of(Wup);
+  g.m1.vals8 = up8;
+  g.row_order = Wgate->row_order;
+  set_x(g, X, ldx, BLAST_TOKEN_MAJOR);
+  set_y(g, H, I, BLAST_TOKEN_MAJOR, BLAST_BF16);
+  g.T = (int)T;
+  g.nbr = (int)(I / b);
+  g.kdim = E;
+  g.act = act;
+  TileArgs d{};
+  d.m0 = mat_of(Wdown);
+  d.m0.vals8 = down8;
+  d.row_order = Wdown->row_order;
+  set_x(d, H, I, BLAST_TOKEN_MAJOR);
+  set_y(d, Y, ldy, BLAST_TOKEN_MAJOR, y_dtype);
+  d.T = (int)T;
+  d.nbr = (int)(E / b);
+  d.kdim = I;
+  d.act = -1;
+  if (I > 0) {
+    if (int rc = (b == 64) ? launch_decode_w8<64, true>(g, stream) : launch_decode_w8<128, true>(g, stream)) return rc;
+  }
+  return (b == 64) ? launch_decode_w8<64, false>(d, stream) : launch_decode_w8<128, false>(d, stream);
 }
 
 extern "C" int blast_sparse_mlp2(const blast_bsr_view* W1, const blast_bsr_view* W2, const uint16_t* X, int64_t ldx,

@@ -12,6 +12,7 @@ struct MatDev {
   const int* row_ptr;
   const int* col_idx;
   const uint16_t* vals;
+  const uint8_t* vals8 = nullptr;  // E5M2 codes of the same blocks (kernels instantiated for one-byte weights)
 };
 
 struct TileArgs {

@@ -85,6 +85,22 @@ __device__ __forceinline__ void decode_zero_job(const DecArgs& a, int ci) {
   }
 }
 
+// Eight E5M2 codes -> eight bf16 values, exactly: a code is the upper byte of an IEEE half; the half is widened
+// to fp32 by the hardware conversion (which takes care of subnormals, infinities and NaN) and a value with two
+// mantissa bits survives the cut to the upper 16 bits of the fp32 unchanged.
+__device__ __forceinline__ bf16x8 e5m2x8_to_bf16x8(uint2 raw) {
+  typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+  u16x8 out;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const unsigned word = i < 4 ? raw.x : raw.y;
+    const unsigned short half_bits = (unsigned short)(((word >> (8 * (i & 3))) & 0xFFu) << 8);
+    const float f = (float)__builtin_bit_cast(_Float16, half_bits);
+    out[i] = (unsigned short)(__builtin_bit_cast(unsigned, f) >> 16);
+  }
+  return __builtin_bit_cast(bf16x8, out);
+}
+
 enum DecRole { kDecAlone = 0, kDecProducer = 1, kDecConsumer = 2 };
 constexpr int kDecMaxSpins = 1 << 19;  // polls of ~0.3 us each before a consumer gives up (never hang the GPU)
 constexpr unsigned long long kCtlReady = 0xB1A57C7100D0C0DEull;  // the control block has been set up
@@ -193,19 +209,25 @@ __device__ __forceinline__ void handover_leave(const DecArgs& a, const Handover&
 // workgroups per CU at the token counts that matter most for decoding, and it lowers the activation bytes
 // that travel with every weight slice.
 // FUSED: the instance runs inside the single-launch MLP (same ring; kept as a separate configuration point).
-template <int B, bool DUAL, int NTT, int XSMALL = 0, bool FUSED = false>
+// W8: the stored block values are E5M2 codes, one byte each (MatDev::vals8); a weight slice is half the
+// bytes, its fragments are widened to bf16 (exactly) on the way into the matrix instruction.
+template <int B, bool DUAL, int NTT, int XSMALL = 0, bool FUSED = false, bool W8 = false>
 struct DecCfg {
+  static_assert(!W8 || B >= 64, "one-byte weights: at least one whole copy instruction per slice");
   static_assert(!XSMALL || (NTT == 1 && B >= 64 && XSMALL * 512 / B < 16),
                 "small activation tiles: one token group, at least 8 chunks per row, fewer than 16 token rows");
   static constexpr int SLICES = B / 16;       // 16-row slices per block row
   static constexpr int KST = B / 32;          // 32-wide k-steps per block
-  static constexpr int SLB = 16 * B * 2;      // bytes of one 16-row slice of a block (= of a 16-token activation tile)
-  static constexpr int NI = SLB / 1024;       // wave-wide copy instructions per slice
-  static constexpr int CPRW = B / 8;          // 16-byte chunks per row
+  static constexpr int SLB = 16 * B * 2;      // bytes of a 16-token activation tile (and of a 16-row slice of bf16 weights)
+  static constexpr int WEB = W8 ? 1 : 2;      // bytes per stored weight
+  static constexpr int SLW = 16 * B * WEB;    // bytes of one 16-row slice of a block
+  static constexpr int NI = SLW / 1024;       // wave-wide copy instructions per slice
+  static constexpr int CPRW = B / 8;          // 16-byte chunks per row (bf16)
+  static constexpr int CPRW8 = B / 16;        // 16-byte chunks per row of one-byte weights
   static constexpr int XR = XSMALL ? XSMALL * 512 / B : 16 * NTT;  // token rows of the activation tile
   static constexpr int XB = XR * B * 2;                   // its bytes
   static constexpr int NIX = XB / 1024;                   // copy instructions per activation tile
-  static constexpr int SLOT = SLB + XB;
+  static constexpr int SLOT = SLW + XB;
   // XONE: one activation tile per wave instead of one per slot.  A block's fragments are moved to registers
   // before the next block's activation tile is copied over them, so only the weight slices need two slots.
   // Used where two 16-token tiles per slot would otherwise leave room for a single workgroup per CU
@@ -215,15 +237,17 @@ struct DecCfg {
   // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
   // the small activation tile, four at b = 64), and every extra slot costs residents.
   static constexpr int NSLOT = 2;
-  static constexpr int WAVE_LDS = XONE ? NSLOT * SLB + XB : NSLOT * SLOT;
+  static constexpr int WAVE_LDS = XONE ? NSLOT * SLW + XB : NSLOT * SLOT;
   static constexpr int OPS = NI + NIX;        // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * WAVE_LDS;
   static constexpr int RED_LDS = 3 * NM * NTT * 4 * 64 * 4;
   static constexpr size_t LDS_BYTES = (size_t)RING_LDS + RED_LDS;
-  static_assert(SLB % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
+  static_assert(SLW % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
   // swizzle key of a row (mod 16): distinct for rows that would otherwise share banks
   __device__ static __forceinline__ int key(int row) { return ((row & 15) / (16 / (CPRW < 16 ? CPRW : 16))) % CPRW; }
+  // the same for rows of one-byte weights (B bytes per row: two rows of b = 64 share the 32 banks)
+  __device__ static __forceinline__ int key8(int row) { return (B == 64 ? (row >> 1) : row) % CPRW8; }
 };
 
 // The work of one workgroup: unit = (block row or chunk, 16-row slice), tokens [t_base, t_base + 16 NTT).
@@ -231,14 +255,15 @@ struct DecCfg {
 // producer publishes its slice of H, the consumer waits for the slices of H its blocks will read).
 // POST: a single-matrix product whose sums go through the activation a.act before they are stored (the
 // first half of a two-matrix MLP).
-template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL, int ROLE, bool POST = false>
+template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL, int ROLE, bool POST = false, bool W8 = false>
 __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, const int t_base, unsigned char* smem) {
+  static_assert(!W8 || ROLE == kDecAlone, "one-byte weights run as ordinary launches");
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
   static_assert(!POST || (!DUAL && !CHUNK), "an activation on the output needs complete sums of a single matrix");
   static_assert(ROLE == kDecAlone || (ROLE == kDecProducer && !CHUNK && (DUAL || POST)) ||
                     (ROLE == kDecConsumer && !DUAL && !CHUNK && !POST),
                 "producers compute the activated intermediate, consumers a plain product");
-  using C = DecCfg<B, DUAL, NTT, XSMALL, ROLE != kDecAlone>;
+  using C = DecCfg<B, DUAL, NTT, XSMALL, ROLE != kDecAlone, W8>;
   constexpr int KST = C::KST, NM = C::NM, NI = C::NI, NSLOT = C::NSLOT;
   float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::RING_LDS);
   const int q = unit % C::SLICES;
@@ -286,8 +311,13 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   uint32_t woff[NI], xoff[C::NIX];
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
-    const int p = ni * 64 + lane, row = p / C::CPRW, slot = p % C::CPRW;
-    woff[ni] = (uint32_t)(q * C::SLB + row * (B * 2) + ((slot ^ C::key(row)) << 4));
+    if (W8) {
+      const int p = ni * 64 + lane, row = p / C::CPRW8, slot = p % C::CPRW8;
+      woff[ni] = (uint32_t)(q * C::SLW + row * B + ((slot ^ C::key8(row)) << 4));
+    } else {
+      const int p = ni * 64 + lane, row = p / C::CPRW, slot = p % C::CPRW;
+      woff[ni] = (uint32_t)(q * C::SLB + row * (B * 2) + ((slot ^ C::key(row)) << 4));
+    }
   }
 #pragma unroll
   for (int xi = 0; xi < C::NIX; ++xi) {
@@ -302,20 +332,32 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   const int xrow = XSMALL ? (l16 % C::XR) : l16;
 #pragma unroll
   for (int s = 0; s < KST; ++s) {
-    foff[s] = (uint32_t)(l16 * (B * 2) + (((4 * s + g) ^ C::key(l16)) << 4));
+    // one-byte weights: the 8 values of k-step s, lane group g are bytes 32 s + 8 g ... of the row, i.e. half
+    // g % 2 of the 16-byte chunk 2 s + g / 2
+    foff[s] = W8 ? (uint32_t)(l16 * B + (((2 * s + (g >> 1)) ^ C::key8(l16)) << 4) + ((g & 1) << 3))
+                 : (uint32_t)(l16 * (B * 2) + (((4 * s + g) ^ C::key(l16)) << 4));
     fxoff[s] = (uint32_t)(xrow * (B * 2) + (((4 * s + g) ^ C::key(xrow)) << 4));
   }
+  // a weight fragment from its LDS image
+  auto wfrag = [&](const unsigned char* p) -> bf16x8 {
+    if constexpr (W8) {
+      return e5m2x8_to_bf16x8(*reinterpret_cast<const uint2*>(p));
+    } else {
+      return *reinterpret_cast<const bf16x8*>(p);
+    }
+  };
 
   // ---- ring -----------------------------------------------------------------------------
   // where block j's weight slice and activation tile live in this wave's part of the ring
-  auto wslot = [&](int j) { return ring + (j % NSLOT) * (C::XONE ? C::SLB : C::SLOT); };
-  auto xslot = [&](int j) { return C::XONE ? ring + NSLOT * C::SLB : ring + (j % NSLOT) * C::SLOT + C::SLB; };
+  auto wslot = [&](int j) { return ring + (j % NSLOT) * (C::XONE ? C::SLW : C::SLOT); };
+  auto xslot = [&](int j) { return C::XONE ? ring + NSLOT * C::SLW : ring + (j % NSLOT) * C::SLOT + C::SLW; };
   auto locate = [&](int j, const unsigned char*& wblk, const unsigned char*& xcol) {
     const int i = wave + 4 * j;
     const bool second = DUAL && i >= n0;
     const MatDev& m = second ? a.m1 : a.m0;
     const int k = second ? kb1 + (i - n0) : kb0 + i;
-    wblk = reinterpret_cast<const unsigned char*>(m.vals) + (int64_t)k * (B * B * 2);
+    wblk = W8 ? m.vals8 + (int64_t)k * (B * B)
+              : reinterpret_cast<const unsigned char*>(m.vals) + (int64_t)k * (B * B * 2);
     xcol = reinterpret_cast<const unsigned char*>(a.X) + (int64_t)ld_idx(m.col_idx, k) * (B * 2);
   };
   auto issue_w = [&](int j) {
@@ -400,7 +442,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
       bf16x8 wf[KST], xf[KST][NTT];
 #pragma unroll
       for (int s = 0; s < KST; ++s) {
-        wf[s] = *reinterpret_cast<const bf16x8*>(ws + foff[s]);
+        wf[s] = wfrag(ws + foff[s]);
 #pragma unroll
         for (int tt = 0; tt < NTT; ++tt) xf[s][tt] = *reinterpret_cast<const bf16x8*>(xs + C::SLB * tt + fxoff[s]);
       }
@@ -455,11 +497,11 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     // instructions are not the bottleneck at these token counts).
 #pragma unroll
     for (int s = 0; s < KST; ++s) {
-      const bf16x8 wf = *reinterpret_cast<const bf16x8*>(slot + foff[s]);
+      const bf16x8 wf = wfrag(slot + foff[s]);
       const bf16x8 w0 = second ? zero : wf;
 #pragma unroll
       for (int tt = 0; tt < NTT; ++tt) {
-        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(slot + C::SLB * (1 + tt) + fxoff[s]);
+        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(slot + C::SLW + C::SLB * tt + fxoff[s]);
         acc[0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, w0, acc[0][tt], 0, 0, 0);
         if (DUAL) {
           const bf16x8 w1 = second ? wf : zero;
@@ -527,7 +569,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   if (ROLE != kDecAlone) handover_leave(a, hand);
 }
 
-template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL, bool POST = false>
+template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL, bool POST = false, bool W8 = false>
 __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // More tokens than one tile holds mean more workgroups per unit, each re-reading the unit's weight
@@ -541,7 +583,7 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
   const int rem = blk % span;
   const int unit = (blk / span) * 8 + (rem & 7);
   if (unit >= a.n_units) return;
-  decode_unit<B, DUAL, NTT, CHUNK, XSMALL, kDecAlone, POST>(a, unit, (rem >> 3) * (NTT * 16), smem);
+  decode_unit<B, DUAL, NTT, CHUNK, XSMALL, kDecAlone, POST, W8>(a, unit, (rem >> 3) * (NTT * 16), smem);
 }
 
 // Single-launch MLP for one token tile (T <= 16 NTT): workgroups [0, n_units) compute H slice by slice

@@ -232,3 +232,107 @@ def test_spmm_e5m2_heavy_rows(api, b, nbc, T):
     yb = api.bsr_spmm_e5m2(dev, vals8, x8, out_dtype=torch.bfloat16)
     torch.cuda.synchronize()
     assert np.abs(yb.float().cpu().numpy().T - want).max() <= 2.0 ** -7 * np.abs(want).max()
+
+
+# ---- E5M2 weights, bf16 activations: the decode form of the gated MLP ----
+
+def _w8_layer(api, rng, E, I, b, sparsity, masks=None):
+    Ws = [synth.gauss_bf16(rng, s, 0.05) for s in ((I, E), (I, E), (E, I))]
+    if masks is None:
+        masks = [synth.uniform_mask(rng, r // b, c // b, sparsity) for r, c in ((I, E), (I, E), (E, I))]
+        if I // b > 2:
+            masks[0][1, :] = 0   # an empty gate row: zero rows of H
+            masks[2][:, 2] = 0   # rows of H nobody reads
+        if E // b > 1:
+            masks[2][1, :] = 0   # an empty row of the down projection
+    dev = [api.bsr_pack(to_dev(w), b, mask=mask_dev(m)) for w, m in zip(Ws, masks)]
+    ref = [orc.pack(w, b, m) for w, m in zip(Ws, masks)]
+    dev8 = [api.quantize_e5m2(d.vals[: max(d.nnz, 1) * b * b].contiguous()) for d in dev]
+    ref8 = [orc.e5m2_quantize(_f32(r.vals)) for r in ref]
+    for d8, r8, r in zip(dev8, ref8, ref):
+        assert np.array_equal(d8.cpu().numpy()[: r.nnz * b * b].reshape(r.nnz, b, b), r8)
+    return dev, dev8, ref, ref8
+
+
+@pytest.mark.parametrize("b", [64, 128])
+@pytest.mark.parametrize("T", [1, 4, 5, 8, 9, 16, 17, 32, 33, 70])
+def test_mlp_with_e5m2_weights_small(api, b, T):
+    import torch
+
+    rng = np.random.default_rng(5200 + b + T)
+    E, I = 4 * b, 6 * b
+    dev, dev8, ref, ref8 = _w8_layer(api, rng, E, I, b, 0.5)
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    y_or = orc.mlp_e5m2w(ref[0], ref8[0], ref[1], ref8[1], ref[2], ref8[2], x)
+    y = api.sparse_mlp_e5m2w(dev[0], dev8[0], dev[1], dev8[1], dev[2], dev8[2], to_dev(x),
+                             out=torch.full((T, E), float("nan"), device="cuda:0"))
+    torch.cuda.synchronize()
+    yh = y.cpu().numpy()
+    check_close(yh.T, y_or, f"E5M2-weight mlp b={b} T={T}")
+    assert not yh[:, b:2 * b].any()
+    # bf16 output and another activation
+    yb = api.sparse_mlp_e5m2w(dev[0], dev8[0], dev[1], dev8[1], dev[2], dev8[2], to_dev(x), act="gelu",
+                              out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    yg = orc.mlp_e5m2w(ref[0], ref8[0], ref[1], ref8[1], ref[2], ref8[2], x, activation="gelu")
+    assert np.abs(yb.float().cpu().numpy().T - yg).max() <= 2.0 ** -7 * np.abs(yg).max() + 1e-6
+
+
+def test_e5m2_weight_conversion_covers_every_code(api):
+    """A block whose 4096 values run through all 256 codes that are finite (subnormals included): the widening to
+    bf16 inside the kernel is exact, so an identity-like activation picks every code out unchanged."""
+    import torch
+
+    b, T = 64, 64
+    codes = np.array([c for c in range(256) if (c & 0x7C) != 0x7C], dtype=np.uint8)  # finite codes
+    vals = np.resize(codes, b * b).reshape(1, b, b)
+    dec = orc.e5m2_decode(vals.ravel()).reshape(b, b)
+    # gate = up = down structure: one stored block at (0, 0) of a 64 x 64 matrix; X = identity picks columns
+    mask = np.ones((1, 1), dtype=np.uint8)
+    W = synth.f32_to_bf16_bits(dec.astype(np.float32))  # exact: every E5M2 value is a bf16 value
+    dev = api.bsr_pack(to_dev(W), b, mask=mask_dev(mask))
+    ref = orc.pack(W, b, mask)
+    d8 = api.quantize_e5m2(dev.vals[: b * b].contiguous())
+    assert np.array_equal(d8.cpu().numpy().reshape(1, b, b), vals)
+    x = synth.f32_to_bf16_bits(np.eye(b, dtype=np.float32))
+    y = api.sparse_mlp_e5m2w(dev, d8, dev, d8, dev, d8, to_dev(x), act="relu")
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, orc.mlp_e5m2w(ref, vals, ref, vals, ref, vals, x, activation="relu"), "all codes")
+
+
+@pytest.mark.parametrize("name,T", [("llama1b_b64_s90", 1), ("llama1b_b64_s90", 16), ("llama8b_b128_s95", 1),
+                                    ("llama8b_b128_s95", 32)])
+def test_mlp_with_e5m2_weights_at_decode_configs(api, name, T):
+    import torch
+
+    wl = synth.WORKLOADS[name]
+    inp = synth.make_mlp(wl)
+    rng = np.random.default_rng(5300 + T)
+    dev = [api.bsr_pack(to_dev(l.W), wl.b, mask=mask_dev(l.mask)) for l in (inp.gate, inp.up, inp.down)]
+    ref = [orc.pack(l.W, wl.b, l.mask) for l in (inp.gate, inp.up, inp.down)]
+    dev8 = [api.quantize_e5m2(d.vals[: d.nnz * wl.b * wl.b].contiguous()) for d in dev]
+    ref8 = [orc.e5m2_quantize(_f32(r.vals)) for r in ref]
+    x = synth.make_x(wl, T)
+    y = api.sparse_mlp_e5m2w(dev[0], dev8[0], dev[1], dev8[1], dev[2], dev8[2], to_dev(x),
+                             out=torch.full((T, wl.hidden), float("nan"), device="cuda:0"))
+    torch.cuda.synchronize()
+    fro, mx = check_close(y.cpu().numpy().T, orc.mlp_e5m2w(ref[0], ref8[0], ref[1], ref8[1], ref[2], ref8[2], x),
+                          f"{name} E5M2 weights T={T}")
+    print(f"{name} E5M2 weights T={T}: rel_fro={fro:.2e} max_abs/rms={mx:.2e}")
+
+
+def test_e5m2_weight_mlp_argument_errors(api):
+    import ctypes as C
+
+    L = api.lib()
+    v = api.BsrView(64, 64, 32, 0, 0, None, None, None, None, None)
+    dummy = (C.c_int32 * 4)()
+    v.row_ptr = C.cast(dummy, C.c_void_p)
+    # b = 32 is not served by this call
+    assert L.blast_sparse_mlp_e5m2w(C.byref(v), None, C.byref(v), None, C.byref(v), None, None, 64, 0, 0, None, 64, 0,
+                                    None, 0, None) == -3
+    wsb = C.c_size_t(0)
+    v64 = api.BsrView(128, 128, 64, 0, 0, v.row_ptr, None, None, None, None)
+    assert L.blast_sparse_mlp_e5m2w_workspace(C.byref(v64), 16, C.byref(wsb)) == 0 and wsb.value == 16 * 128 * 2
+    assert L.blast_sparse_mlp_e5m2w(C.byref(v64), None, None, None, C.byref(v64), None, None, 128, 4, 0, None, 128, 0,
+                                    None, 0, None) == -1  # no up matrix

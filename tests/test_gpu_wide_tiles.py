@@ -1,9 +1,9 @@
 """GPU parity of the prefill kernel's 256-token x 128-row tiles (eight-wave workgroups, b = 128) and of its two
 schedules: token tiles pinned to an XCD, and block rows pinned to an XCD with the rows dealt to groups of
 workgroups by accumulated work.  The shapes are the smallest that reach those code paths: the wide tile needs
-at least as many (block row, 256-token tile) pairs as the chip has compute units, the row-pinned schedule an
-activation slab of more than 6 MB per XCD (16384 features), a token-tile count that divides 32, and - for the
-work-balanced dealing - at most 8 groups per XCD and 64 rows per XCD."""
+twice as many (block row, 256-token tile) pairs as the chip has compute units, the row-pinned schedule an
+activation slab of more than 6 MiB per XCD (12800 features here), a token-tile count that divides 32, and - for
+the work-balanced dealing - at most 8 groups per XCD and 64 rows per XCD."""
 import numpy as np
 import pytest
 
@@ -54,13 +54,13 @@ def _pack(api, w, b, mask):
 
 # (block rows, block columns, tokens): what the case reaches
 SPMM_CASES = [
-    (70, 6, 1030),    # wide tile, token tiles pinned, ragged last tile (5 tiles: 32 % 5 != 0)
-    (72, 128, 1024),  # row-pinned: 4 tiles, 8 groups per XCD, 9 rows per XCD, every other octet mirrored
-    (72, 128, 1000),  # the same with a ragged last tile
-    (75, 128, 2048),  # row-pinned: 8 tiles, 4 groups; 75 rows: the last octet is partial
-    (40, 128, 4096),  # row-pinned: 16 tiles, 2 groups
-    (136, 128, 512),  # row-pinned: 2 tiles, 16 groups per XCD: rows dealt round-robin
-    (72, 128, 2304),  # 9 tiles do not divide 32: falls back to pinned token tiles
+    (110, 6, 1290),   # wide tile, token tiles pinned, ragged last tile (6 tiles: 32 % 6 != 0)
+    (130, 100, 1024),  # row-pinned: 4 tiles, 8 groups per XCD, 17 rows per XCD, every other octet mirrored
+    (130, 100, 1000),  # the same with a ragged last tile
+    (75, 100, 2048),  # row-pinned: 8 tiles, 4 groups; 75 rows: the last octet is partial
+    (40, 100, 4096),  # row-pinned: 16 tiles, 2 groups
+    (260, 100, 512),  # row-pinned: 2 tiles, 16 groups per XCD: rows dealt round-robin
+    (72, 100, 2304),  # 9 tiles do not divide 32: falls back to pinned token tiles
 ]
 
 
@@ -92,7 +92,7 @@ def test_spmm_wide_tiles(api, nbr, nbc, T):
     print(f"wide spmm {nbr}x{nbc} T={T}: rel_fro={fro:.2e} max_abs/rms={mx:.2e} on {sel.size} tokens")
 
 
-@pytest.mark.parametrize("nbi,nbe,T", [(72, 128, 1024), (75, 128, 2048), (70, 6, 1030), (136, 128, 512)])
+@pytest.mark.parametrize("nbi,nbe,T", [(130, 100, 1024), (75, 100, 2048), (110, 6, 1290), (260, 100, 512)])
 def test_mlp_wide_tiles(api, nbi, nbe, T):
     """Gated product and down projection on the wide tile: I = nbi * 128, E = nbe * 128."""
     import torch
