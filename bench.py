@@ -55,6 +55,10 @@ def profile_traffic(workload: str, tokens: int, kernel: str):
     return None
 
 
+def short(name):
+    return name.replace("llama", "")
+
+
 def sig(x, n=4):
     return None if x is None else float("%.*g" % (n, x))
 
@@ -243,10 +247,33 @@ class Layer:
         wl, b = self.wl, self.wl.b
         if T >= 512:
             ach = 2.0 * b * b * T * self.nnz / (ms * 1e-3) / 1e12
-            return [wl.name, T, sig(ms * 1e3), sig(eager * 1e3), "mfma", sig(ach), sig(ach / PEAK_BF16_TFLOPS, 3)]
+            return [short(wl.name), T, sig(ms * 1e3), sig(eager * 1e3), "mfma", sig(ach), sig(ach / PEAK_BF16_TFLOPS, 3)]
         alg = self.w_bytes + 4 * self.nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
         ach = alg / (ms * 1e-3) / 1e9
-        return [wl.name, T, sig(ms * 1e3), sig(eager * 1e3), "hbm", sig(ach), sig(ach / PEAK_HBM_GBS, 3)]
+        return [short(wl.name), T, sig(ms * 1e3), sig(eager * 1e3), "hbm", sig(ach), sig(ach / PEAK_HBM_GBS, 3)]
+
+    def row_e5m2w(self, T, steps, warmup):
+        """The same pass with the three weights in E5M2 (blast_sparse_mlp_e5m2w, two launches): algorithmic bytes
+        count one byte per stored weight."""
+        api, torch = self.api, self.torch
+        b, wl = self.wl.b, self.wl
+        x = self.x(T)
+        n8 = max(2, -(-768 * 1024 * 1024 // (self.w_bytes // 2)))
+        base = [api.quantize_e5m2(m.vals[: m.nnz * b * b].contiguous()) for m in (self.g, self.u, self.d)]
+        sets8 = [base] + [[v.clone() for v in base] for _ in range(n8 - 1)]
+
+        def make_calls():
+            y = torch.empty((T, wl.hidden), dtype=torch.float32, device="cuda:0")
+            ws = torch.empty(max(T * wl.inter * 2, 256), dtype=torch.uint8, device="cuda:0")
+            return [(lambda v=v: api.sparse_mlp_e5m2w(self.g, v[0], self.u, v[1], self.d, v[2], x, out=y, ws=ws))
+                    for v in sets8]
+
+        eager = time_eager(torch, make_calls(), steps, warmup)
+        graph = time_graph(torch, make_calls, steps, warmup)
+        ms = graph if graph is not None else eager
+        alg = self.w_bytes // 2 + 4 * self.nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
+        ach = alg / (ms * 1e-3) / 1e9
+        return [short(wl.name) + "+e5m2w", T, sig(ms * 1e3), sig(eager * 1e3), "hbm", sig(ach), sig(ach / PEAK_HBM_GBS, 3)]
 
 
 def linear_row(api, torch, synth, steps, warmup):
@@ -265,7 +292,7 @@ def linear_row(api, torch, synth, steps, warmup):
     ms = graph if graph is not None else eager
     alg = p.nnz * wl.b * wl.b * 2 + 2 * wl.hidden * T + 4 * wl.inter * T
     ach = alg / (ms * 1e-3) / 1e9
-    return [wl.name, T, sig(ms * 1e3), sig(eager * 1e3), "hbm", sig(ach), sig(ach / PEAK_HBM_GBS, 3)]
+    return [short(wl.name), T, sig(ms * 1e3), sig(eager * 1e3), "hbm", sig(ach), sig(ach / PEAK_HBM_GBS, 3)]
 
 def two_matrix_mlp(workload: str, steps: int, warmup: int, cpu: bool):
     """Y = W2 act(W1 X) (GELU) on a GPT-2-shaped block: wall-clock time per pass at the workload's token
@@ -579,6 +606,7 @@ def main():
         dsteps = max(args.steps, 100)
         for Td in (1, 16):  # the same layer at decode token counts: weight bytes, not launches, set the time
             rows.append(L.row(Td, dsteps, args.warmup))
+        rows.append(L.row_e5m2w(1, dsteps, args.warmup))
         del L
         torch.cuda.empty_cache()
         rows.insert(0, linear_row(api, torch, synth, dsteps, args.warmup))
@@ -589,9 +617,12 @@ def main():
             Lc = Layer(name, api, torch, synth)
             for Tc in toks:
                 rows.append(Lc.row(Tc, st if Tc < 512 else args.steps, args.warmup))
+            if name in ("llama1b_b64_s90", "llama8b_b128_s95"):  # E5M2 weights at the decode token counts
+                for Tc in ((1, 16) if name == "llama1b_b64_s90" else (1, 32)):
+                    rows.append(Lc.row_e5m2w(Tc, st, args.warmup))
             del Lc
             torch.cuda.empty_cache()
-        out["configs_columns"] = ["workload", "tokens", "us_graph", "us_eager", "bound", "TFLOPs|GBps", "frac_peak"]
+        out["configs_columns"] = ["workload(llama*)", "tokens", "us_graph", "us_eager", "bound", "TFLOPs|GBps", "frac_peak"]
         out["configs"] = rows
 
     if args.extras:

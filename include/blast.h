@@ -244,7 +244,8 @@ int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8, const uin
  *   G = W~gate X, U = W~up X with every E5M2 code widened exactly to bf16, fp32 accumulation;
  *   H = bf16(act(G) * U), one rounding; Y = W~down H, fp32 accumulation (Eq. (1)).
  * That is blast_sparse_mlp on the dequantised weights, with half the weight traffic.
- *   Wgate/Wup/Wdown   structure of the packed matrices (row_ptr, col_idx, row_order, nnz, b; vals is not read);
+ *   Wgate/Wup/Wdown   structure of the packed matrices (row_ptr, col_idx, row_order, aux, max_row_blocks, nnz, b; vals is
+ *                     not read);
  *                     b = 64 or 128
  *   gate8/up8/down8   E5M2 block values, [nnz][b][b], one byte each, in the order of the view's vals
  *                     (blast_quantize_e5m2 of it), 16-byte aligned
@@ -252,7 +253,8 @@ int blast_bsr_spmm_e5m2(const blast_bsr_view* W, const uint8_t* vals8, const uin
  *                     T * I * 2 below 2^32 (the call is meant for decode token counts; any such T is correct)
  *   Y, ldy, y_dtype   token-major [T][E], fp32 or bf16
  *   ws                at least blast_sparse_mlp_e5m2w_workspace() bytes (H), 256-byte aligned
- * Two launches, no in-kernel hand-over, rows are never split into chunks.  Never synchronises.
+ * Two launches, no in-kernel hand-over; with fp32 output a very full row of Wdown (see max_row_blocks) is cut
+ * into chunks that add into cleared rows, as in blast_bsr_spmm.  Never synchronises.
  * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK (b other than 64 / 128), WORKSPACE, HIP.
  */
 int blast_sparse_mlp_e5m2w(const blast_bsr_view* Wgate, const uint8_t* gate8, const blast_bsr_view* Wup,

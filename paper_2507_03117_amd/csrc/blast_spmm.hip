@@ -825,8 +825,8 @@ extern "C" int blast_sparse_mlp_status(const blast_bsr_view* Wgate, int64_t T, c
 // ---- E5M2 weights, bf16 activations: the decode form of the 8-bit run (Sec. 5.2) ------------------------
 namespace {
 
-template <int B, bool DUAL, int NTT, int XSMALL>
-int launch_decode_w8_ntt(const TileArgs& a, hipStream_t stream) {
+template <int B, bool DUAL, int NTT, int XSMALL, bool CHUNK>
+int launch_decode_w8_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   DecArgs d{};
   d.m0 = a.m0;
   d.m1 = a.m1;
@@ -839,7 +839,11 @@ int launch_decode_w8_ntt(const TileArgs& a, hipStream_t stream) {
   d.y_bf16 = a.y_bf16;
   d.T = a.T;
   d.act = a.act;
-  const int64_t units = (int64_t)a.nbr * (B / 16);
+  d.hdr = plan.hdr;
+  d.chunk_row = plan.chunk_row;
+  d.chunk_kb = plan.chunk_kb;
+  d.chunk_ke = plan.chunk_ke;
+  const int64_t units = (CHUNK ? plan.max_chunks : (int64_t)a.nbr) * (B / 16);
   if (units <= 0) return BLAST_OK;
   const int64_t groups = (a.T + NTT * 16 - 1) / (NTT * 16);
   const int64_t grid = (units + 7) / 8 * 8 * groups;
@@ -848,23 +852,42 @@ int launch_decode_w8_ntt(const TileArgs& a, hipStream_t stream) {
   d.groups = (int)groups;
   using C = DecCfg<B, DUAL, NTT, XSMALL, false, true>;
   static blast::DeviceFlags lds_set;
-  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, false, XSMALL, false, true>),
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL, false, true>),
                                 C::LDS_BYTES, lds_set))
     return rc;
-  k_decode<B, DUAL, NTT, false, XSMALL, false, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(d);
+  if (CHUNK) {  // rows cut into several chunks are accumulated: clear them first
+    StreamArgs sa{a, 0, -1, 0, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
+    k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
+    BLAST_LAUNCH_CHECK("k_zero_shared_rows");
+  }
+  k_decode<B, DUAL, NTT, CHUNK, XSMALL, false, true><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(d);
   BLAST_LAUNCH_CHECK("k_decode (E5M2 weights)");
   return BLAST_OK;
 }
 
-template <int B, bool DUAL>
-int launch_decode_w8(const TileArgs& a, hipStream_t stream) {
+template <int B, bool DUAL, bool CHUNK>
+int launch_decode_w8_c(const TileArgs& a, const ChunkPlan& plan, hipStream_t stream) {
   // the smallest activation tile that holds T token rows, as in launch_decode
-  if (a.T <= 512 / B) return launch_decode_w8_ntt<B, DUAL, 1, 1>(a, stream);
+  if (a.T <= 512 / B) return launch_decode_w8_ntt<B, DUAL, 1, 1, CHUNK>(a, plan, stream);
   if constexpr (B == 128) {
-    if (a.T <= 8) return launch_decode_w8_ntt<B, DUAL, 1, 2>(a, stream);
+    if (a.T <= 8) return launch_decode_w8_ntt<B, DUAL, 1, 2, CHUNK>(a, plan, stream);
   }
-  if (a.T <= 16) return launch_decode_w8_ntt<B, DUAL, 1, 0>(a, stream);
-  return launch_decode_w8_ntt<B, DUAL, 2, 0>(a, stream);
+  if (a.T <= 16) return launch_decode_w8_ntt<B, DUAL, 1, 0, CHUNK>(a, plan, stream);
+  return launch_decode_w8_ntt<B, DUAL, 2, 0, CHUNK>(a, plan, stream);
+}
+
+// `plan`: the chunk plan of the matrix (single matrix, fp32 output only); taken under the rule of the bf16
+// decode path: when the fullest row, dealt to four waves, is deeper than four times a workgroup slot's share.
+template <int B, bool DUAL>
+int launch_decode_w8(const TileArgs& a, int64_t nnz, const ChunkPlan& plan, hipStream_t stream) {
+  if constexpr (!DUAL) {
+    if (plan.hdr && !a.y_bf16 && a.T <= kDecodeMaxTokens) {
+      double ref = (double)nnz * (B / 16) / (4.0 * 2.0 * cu_count());
+      if (ref < blast::kChunkBlocks) ref = blast::kChunkBlocks;
+      if ((double)plan.max_row_blocks / 4.0 > 4.0 * ref) return launch_decode_w8_c<B, false, true>(a, plan, stream);
+    }
+  }
+  return launch_decode_w8_c<B, DUAL, false>(a, ChunkPlan{}, stream);
 }
 
 }  // namespace
@@ -918,9 +941,14 @@ extern "C" int blast_sparse_mlp_e5m2w(const blast_bsr_view* Wgate, const uint8_t
   d.kdim = I;
   d.act = -1;
   if (I > 0) {
-    if (int rc = (b == 64) ? launch_decode_w8<64, true>(g, stream) : launch_decode_w8<128, true>(g, stream)) return rc;
+    const int64_t nnz_gu = Wgate->nnz + Wup->nnz;
+    if (int rc = (b == 64) ? launch_decode_w8<64, true>(g, nnz_gu, ChunkPlan{}, stream)
+                           : launch_decode_w8<128, true>(g, nnz_gu, ChunkPlan{}, stream))
+      return rc;
   }
-  return (b == 64) ? launch_decode_w8<64, false>(d, stream) : launch_decode_w8<128, false>(d, stream);
+  const ChunkPlan dplan = plan_of(Wdown, T);
+  return (b == 64) ? launch_decode_w8<64, false>(d, Wdown->nnz, dplan, stream)
+                   : launch_decode_w8<128, false>(d, Wdown->nnz, dplan, stream);
 }
 
 extern "C" int blast_sparse_mlp2(const blast_bsr_view* W1, const blast_bsr_view* W2, const uint16_t* X, int64_t ldx,

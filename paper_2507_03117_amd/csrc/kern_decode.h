@@ -236,7 +236,9 @@ struct DecCfg {
   // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
   // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
   // the small activation tile, four at b = 64), and every extra slot costs residents.
-  static constexpr int NSLOT = 2;
+  // One-byte weights halve a slice: where a slot stays within 4 KiB the ring is four slots deep, so that the
+  // bytes in flight per wave - what the HBM bandwidth reached follows - are those of the bf16 form.
+  static constexpr int NSLOT = (W8 && SLOT <= 4096) ? 4 : 2;
   static constexpr int WAVE_LDS = XONE ? NSLOT * SLW + XB : NSLOT * SLOT;
   static constexpr int OPS = NI + NIX;        // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;

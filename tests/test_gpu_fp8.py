@@ -336,3 +336,30 @@ def test_e5m2_weight_mlp_argument_errors(api):
     assert L.blast_sparse_mlp_e5m2w_workspace(C.byref(v64), 16, C.byref(wsb)) == 0 and wsb.value == 16 * 128 * 2
     assert L.blast_sparse_mlp_e5m2w(C.byref(v64), None, None, None, C.byref(v64), None, None, 128, 4, 0, None, 128, 0,
                                     None, 0, None) == -1  # no up matrix
+
+
+@pytest.mark.parametrize("b,nbi,T", [(64, 272, 1), (64, 272, 20), (128, 260, 5), (128, 260, 40)])
+def test_mlp_with_e5m2_weights_and_a_very_long_down_row(api, b, nbi, T):
+    """A row of W_down long enough for the chunk plan: its chunks add into rows cleared by a launch of their own
+    (fp32 output, poisoned Y); the bf16 output of the same layer takes whole rows."""
+    import torch
+
+    rng = np.random.default_rng(5400 + b + T)
+    E, I = 4 * b, nbi * b
+    mg, mu = (synth.uniform_mask(rng, nbi, E // b, 0.5) for _ in range(2))
+    md = synth.uniform_mask(rng, E // b, nbi, 0.9)
+    md[0, :] = 1   # nbi blocks: cut into chunks of 16
+    md[2, :] = 0   # an empty row beside it
+    dev, dev8, ref, ref8 = _w8_layer(api, rng, E, I, b, 0.0, masks=[mg, mu, md])
+    assert dev[2].max_row_blocks == nbi
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    want = orc.mlp_e5m2w(ref[0], ref8[0], ref[1], ref8[1], ref[2], ref8[2], x)
+    for _ in range(2):
+        y = api.sparse_mlp_e5m2w(dev[0], dev8[0], dev[1], dev8[1], dev[2], dev8[2], to_dev(x),
+                                 out=torch.full((T, E), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, want, f"E5M2-weight mlp, long down row b={b} T={T}")
+    assert not y.cpu().numpy()[:, 2 * b:3 * b].any()
+    yb = api.sparse_mlp_e5m2w(dev[0], dev8[0], dev[1], dev8[1], dev[2], dev8[2], to_dev(x), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert np.abs(yb.float().cpu().numpy().T - want).max() <= 2.0 ** -7 * np.abs(want).max() + 1e-6
