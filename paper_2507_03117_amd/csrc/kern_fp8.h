@@ -3,13 +3,14 @@
 //
 // Same loop as the bf16 product (Sec. 3.4: every output tile walks the stored blocks of its block row),
 // organised like the stored-block-gradient kernel: a wave accumulates a 64-token x 64-row tile (2 x 2
-// register blocking of 32x32x16 matrix instructions) from a private ring of LDS stages filled by LDS-DMA
-// copies; there is no barrier in the loop, the wave's memory counter is the only synchronisation.
+// register blocking of 32x32x64 matrix instructions of the f8f6f4 family, which run at twice the rate of the
+// 16-bit ones) from a private ring of LDS stages filled by LDS-DMA copies; there is no barrier in the loop,
+// the wave's memory counter is the only synchronisation.
 //  - A stage is a 64-deep contraction slice: 64 weight rows x 64 bytes and 64 tokens x 64 bytes, 4 KiB each
 //    (the L1 path is bound by cache lines requested, not bytes: 64-byte row segments are the widest a
 //    64 x 64 block offers, and a block's weight tile is then 4 KiB of whole lines).
-//  - A lane reads two 16-byte chunks per operand row (32 contraction indices) and feeds their four halves to
-//    four matrix instructions; lanes 0-31 take chunks 0 and 2 of a row, lanes 32-63 chunks 1 and 3.  Both
+//  - A lane reads two 16-byte chunks per operand row (32 contraction indices), the operand of one 64-deep
+//    matrix instruction; lanes 0-31 take chunks 0 and 2 of a row, lanes 32-63 chunks 1 and 3.  Both
 //    operands use the same assignment, so every contraction index meets its partner exactly once.
 //  - The four chunks of a row are XOR-swizzled in LDS by (row / 2) % 4 (on the global-address side of the
 //    copy): the eight rows one read cycle touches then cover all banks.
@@ -195,16 +196,24 @@ __global__ __launch_bounds__(256) void k_spmm_fp8(const Fp8Args a) {
         fw[h][c] = *reinterpret_cast<const i64x2*>(slot + foff[h][c]);
         fx[h][c] = *reinterpret_cast<const i64x2*>(slot + C::TILE + foff[h][c]);
       }
-    // D[m][n] += sum_k A[m][k] B[k][n]: m = token, n = weight row; two instructions per 16-byte chunk
+    // D[m][n] += sum_k A[m][k] B[k][n]: m = token, n = weight row.  One 64-deep matrix instruction of the
+    // f8f6f4 family per 32 x 32 tile and stage (twice the rate of the 16-deep E5M2 instruction): a lane hands
+    // over its 32 bytes of the row - the same two chunks on both operands, so whatever contraction index the
+    // hardware gives byte j of lane half h, it meets its partner.  Formats: E5M2 (code 1) on both sides; the
+    // block scales the instruction takes are all 2^0 (E8M0 code 127 in every byte).
+    typedef int v8i __attribute__((ext_vector_type(8)));
+    struct Pair {
+      i64x2 lo, hi;
+    };
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-      for (int e = 0; e < 2; ++e)
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-          for (int nj = 0; nj < 2; ++nj)
-            acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf8_bf8(fx[mi][c][e], fw[nj][c][e], acc[mi][nj], 0, 0, 0);
+      for (int nj = 0; nj < 2; ++nj) {
+        const v8i ax = __builtin_bit_cast(v8i, (Pair{fx[mi][0], fx[mi][1]}));
+        const v8i bw = __builtin_bit_cast(v8i, (Pair{fw[nj][0], fw[nj][1]}));
+        acc[mi][nj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bw, acc[mi][nj], 1, 1, 0, 0x7F7F7F7F, 0,
+                                                                       0x7F7F7F7F);
+      }
     asm volatile("" ::: "memory");
   }
 
