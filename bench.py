@@ -190,6 +190,27 @@ def time_gated_kernel(api, torch, sets, x, T, steps, warmup):
     return ms
 
 
+def time_phases_in_pass(api, torch, sets, x, T, E, steps, warmup):
+    """(gate/up ms, down ms) inside whole MLP passes: `steps` eager blast_sparse_mlp_events calls (rotating
+    weight copies), each recording an event on the launch stream before the gate/up launch, between the two
+    products and after the down product; means of the two intervals."""
+    y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
+    g0, u0, d0 = sets[0]
+    ws = torch.empty(max(api.mlp_workspace_bytes(g0, u0, d0, T), 256), dtype=torch.uint8, device="cuda:0")
+    ev = Events(steps)
+    n = len(sets)
+    for i in range(warmup):
+        api.sparse_mlp(*sets[i % n], x, out=y, ws=ws)
+    torch.cuda.synchronize()
+    for i in range(steps):
+        api.sparse_mlp(*sets[(warmup + i) % n], x, out=y, ws=ws, events=ev.triples[i])
+    torch.cuda.synchronize()
+    gu = statistics.fmean(ev.elapsed(t[0], t[1]) for t in ev.triples)
+    dn = statistics.fmean(ev.elapsed(t[1], t[2]) for t in ev.triples)
+    ev.destroy()
+    return gu, dn
+
+
 class Layer:
     """One workload packed on the device (and, on request, by the oracle), with rotated weight copies."""
 
@@ -553,13 +574,17 @@ def main():
     alg_bytes = L.w_bytes + 4 * L.nnz + 2 * wl.hidden * T + 4 * wl.hidden * T
     prefill = T >= 512
     if prefill:
-        # dominant kernel: the gated gate/up product (2/3 of the stored blocks), timed on its own with events
-        gu_ms = time_gated_kernel(api, torch, L.sets, L.x(T), T, max(10, args.steps // 2), 3)
+        # dominant kernel: the gated gate/up product (2/3 of the stored blocks), bracketed by events inside
+        # whole passes (where it follows the down product of the pass before), and on its own back to back
+        ksteps = max(10, args.steps // 2)
+        gu_ms, dn_ms = time_phases_in_pass(api, torch, L.sets, L.x(T), T, wl.hidden, ksteps, 3)
+        gu_alone_ms = time_gated_kernel(api, torch, L.sets, L.x(T), T, ksteps, 3)
         gu_tf = 2.0 * b * b * T * (L.g.nnz + L.u.nnz) / (gu_ms * 1e-3) / 1e12
         kname = "k_spmm_stream<%d,dual> (gate/up + activation)" % b
         tr = profile_traffic(wl.name, T, "gate_up")
         roofline = {"bound": "mfma", "kernel": kname, "achieved": sig(gu_tf), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": sig(gu_tf / PEAK_BF16_TFLOPS, 3), "kernel_ms": sig(gu_ms),
+                    "frac": sig(gu_tf / PEAK_BF16_TFLOPS, 3), "kernel_ms": sig(gu_ms), "down_kernel_ms": sig(dn_ms),
+                    "kernel_ms_back_to_back_alone": sig(gu_alone_ms),
                     "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None}
     else:
         gbs = alg_bytes / (step_ms * 1e-3) / 1e9
