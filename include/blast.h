@@ -143,8 +143,10 @@ int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, do
  *   nnz_out     HOST, receives the number of stored blocks (also on BLAST_ERR_CAPACITY)
  *   max_row_blocks_out  HOST, may be NULL: stored blocks of the fullest block row (0 without aux).  Copy it
  *               into blast_bsr_view.max_row_blocks: with `aux`, block rows of more than 16 blocks are cut into
- *               chunks of 16, and the product schedules chunks instead of rows when that row would otherwise
- *               be the critical path of the launch (the load balance Sec. 3.4.1 asks of the launch grid).
+ *               chunks of 16 (and, in a second plan for the many-token kernels, rows of more than 64 blocks
+ *               into chunks of 64), and the product schedules chunks instead of rows when that row would
+ *               otherwise be the critical path of the launch (the load balance Sec. 3.4.1 asks of the
+ *               launch grid).
  *   ws          scratch of at least the ws_bytes reported by blast_bsr_pack_bound, 16-byte aligned
  *
  * The call synchronises `stream` once (to learn nnz); when it returns BLAST_OK

@@ -417,54 +417,74 @@ __global__ __launch_bounds__(256) void k_fill_csc(const uint8_t* __restrict__ ma
   }
 }
 
-// Single workgroup: cut the block rows, in schedule order, into chunks of at most `chunk` blocks.
-// hdr = {n_chunks, max_row_blocks, chunk, 0}.  An empty row still gets one (empty) chunk: its output has
-// to be written.
+// Where one chunk plan goes.
+struct PlanOut {
+  int chunk;        // blocks per chunk, at most
+  int* hdr;         // {n_chunks, max_row_blocks, chunk, 0}
+  int* chunk_row;
+  int* chunk_kb;
+  int* chunk_ke;
+  int64_t cap;
+};
+
+// Single workgroup: cut the block rows, in schedule order, into chunks of at most `chunk` blocks, once per
+// requested plan.  An empty row still gets one (empty) chunk: its output has to be written.
 __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row_ptr, const int* __restrict__ row_order,
-                                                     int nbr, int chunk, int* __restrict__ hdr,
-                                                     int* __restrict__ chunk_row, int* __restrict__ chunk_kb,
-                                                     int* __restrict__ chunk_ke, int64_t chunk_cap,
+                                                     int nbr, PlanOut narrow, PlanOut wide,
                                                      int* __restrict__ max_row_out) {
   __shared__ int wave_tot[16];
   __shared__ int s_running, s_heavy;
-  if (threadIdx.x == 0) {
-    s_running = 0;
-    s_heavy = 0;
-  }
-  __syncthreads();
-  for (int base = 0; base < nbr; base += blockDim.x) {
-    const int rank = base + threadIdx.x;
-    int r = 0, kb = 0, ke = 0, nch = 0;
-    if (rank < nbr) {
-      r = row_order[rank];
-      kb = row_ptr[r];
-      ke = row_ptr[r + 1];
-      nch = (ke - kb + chunk - 1) / chunk;
-      if (nch < 1) nch = 1;
-      atomicMax(&s_heavy, ke - kb);
+  for (int which = 0; which < 2; ++which) {
+    const PlanOut o = which ? wide : narrow;
+    const int chunk = o.chunk;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      s_running = 0;
+      s_heavy = 0;
     }
-    int total;
-    const int first = s_running + block_exscan(nch, wave_tot, total);
-    for (int j = 0; j < nch; ++j) {
-      const int64_t e = (int64_t)first + j;
-      if (e < chunk_cap) {
-        chunk_row[e] = r | (nch > 1 ? (int)0x80000000u : 0);
-        const int b0 = kb + j * chunk;
-        chunk_kb[e] = b0;
-        chunk_ke[e] = (b0 + chunk < ke) ? b0 + chunk : ke;
+    __syncthreads();
+    for (int base = 0; base < nbr; base += blockDim.x) {
+      const int rank = base + threadIdx.x;
+      int r = 0, kb = 0, ke = 0, nch = 0;
+      if (rank < nbr) {
+        r = row_order[rank];
+        kb = row_ptr[r];
+        ke = row_ptr[r + 1];
+        nch = (ke - kb + chunk - 1) / chunk;
+        if (nch < 1) nch = 1;
+        atomicMax(&s_heavy, ke - kb);
       }
+      int total;
+      const int first = s_running + block_exscan(nch, wave_tot, total);
+      for (int j = 0; j < nch; ++j) {
+        const int64_t e = (int64_t)first + j;
+        if (e < o.cap) {
+          o.chunk_row[e] = r | (nch > 1 ? (int)0x80000000u : 0);
+          const int b0 = kb + j * chunk;
+          o.chunk_kb[e] = b0;
+          o.chunk_ke[e] = (b0 + chunk < ke) ? b0 + chunk : ke;
+        }
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) s_running += total;
+      __syncthreads();
     }
-    __syncthreads();
-    if (threadIdx.x == 0) s_running += total;
-    __syncthreads();
+    if (threadIdx.x == 0) {
+      o.hdr[0] = s_running;
+      o.hdr[1] = s_heavy;
+      if (which == 0) *max_row_out = s_heavy;  // next to nnz, so that one copy brings both to the host
+      o.hdr[2] = chunk;
+      o.hdr[3] = 0;
+    }
   }
-  if (threadIdx.x == 0) {
-    hdr[0] = s_running;
-    hdr[1] = s_heavy;
-    *max_row_out = s_heavy;  // next to nnz, so that one copy brings both to the host
-    hdr[2] = chunk;
-    hdr[3] = 0;
-  }
+}
+
+// Both plans of a matrix, placed in its aux buffer.
+inline void plan_outputs(char* ab, const blast::AuxLayout& A, PlanOut& narrow, PlanOut& wide) {
+  narrow = PlanOut{blast::kChunkBlocks, reinterpret_cast<int*>(ab + A.hdr_off), reinterpret_cast<int*>(ab + A.chunk_row_off),
+                   reinterpret_cast<int*>(ab + A.chunk_kb_off), reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap};
+  wide = PlanOut{blast::kWideChunkBlocks, reinterpret_cast<int*>(ab + A.whdr_off), reinterpret_cast<int*>(ab + A.wchunk_row_off),
+                 reinterpret_cast<int*>(ab + A.wchunk_kb_off), reinterpret_cast<int*>(ab + A.wchunk_ke_off), A.wchunk_cap};
 }
 
 // One workgroup per stored block of the transposed matrix: block e of the output is the transpose of
@@ -642,19 +662,15 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   // The schedule and the chunk plan depend on the populations only: they are written before the
   // synchronisation so that the longest row's length comes back to the host with nnz.
   int host_vals[2] = {0, 0};
-  int* hdr_dev = nullptr;
   if (nbr > 0) {
     k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, nullptr, (int)nbr, row_order);
     BLAST_LAUNCH_CHECK("k_row_order");
   }
   if (aux) {
     char* ab = static_cast<char*>(aux);
-    hdr_dev = reinterpret_cast<int*>(ab + A.hdr_off);
-    k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr, row_order, (int)nbr, blast::kChunkBlocks, hdr_dev,
-                                                     reinterpret_cast<int*>(ab + A.chunk_row_off),
-                                                     reinterpret_cast<int*>(ab + A.chunk_kb_off),
-                                                     reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap,
-                                                     nnz_dev + 1);
+    PlanOut narrow, wide;
+    plan_outputs(ab, A, narrow, wide);
+    k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr, row_order, (int)nbr, narrow, wide, nnz_dev + 1);
     BLAST_LAUNCH_CHECK("k_chunk_plan");
   }
   // The two scalars come back through a small pinned buffer (one per host thread, allocated on first use
@@ -763,11 +779,9 @@ extern "C" int blast_bsr_transpose(const blast_bsr_view* W, int32_t* row_ptr_t, 
   if (aux_t) {
     char* at = static_cast<char*>(aux_t);
     int* hdr = reinterpret_cast<int*>(at + At.hdr_off);
-    k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr_t, row_order_t, (int)nbc, blast::kChunkBlocks, hdr,
-                                                     reinterpret_cast<int*>(at + At.chunk_row_off),
-                                                     reinterpret_cast<int*>(at + At.chunk_kb_off),
-                                                     reinterpret_cast<int*>(at + At.chunk_ke_off), At.chunk_cap,
-                                                     hdr + 1);
+    PlanOut narrow, wide;
+    plan_outputs(at, At, narrow, wide);
+    k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr_t, row_order_t, (int)nbc, narrow, wide, hdr + 1);
     BLAST_LAUNCH_CHECK("k_chunk_plan(transpose)");
     // the column-grouped index of the transpose is the row-grouped one of the input
     k_copy_i32<<<blocks_for(nbr + 1), dim3(256), 0, stream>>>(W->row_ptr, nbr + 1,

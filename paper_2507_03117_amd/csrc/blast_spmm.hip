@@ -91,6 +91,12 @@ struct ChunkPlan {
   const int* chunk_kb = nullptr;
   const int* chunk_ke = nullptr;
   int64_t max_chunks = 0;  // host-side upper bound of hdr[0]
+  // the same rows in chunks of kWideChunkBlocks, for the streaming kernels
+  const int* w_hdr = nullptr;
+  const int* w_chunk_row = nullptr;
+  const int* w_chunk_kb = nullptr;
+  const int* w_chunk_ke = nullptr;
+  int64_t w_max_chunks = 0;
   int max_row_blocks = 0;  // stored blocks of the fullest block row
   ZeroJob* zero_job = nullptr;  // a side job this launch may take along (decode launches only)
   bool pre_zeroed = false;      // the shared rows of the output have been cleared by an earlier launch
@@ -174,7 +180,16 @@ template <int B, bool DUAL>
 int launch_stream(const TileArgs& a, const ChunkPlan& plan, int64_t k_features, hipStream_t stream) {
   if constexpr (!DUAL) {
     // rows cut into chunks accumulate with fp32 atomics: only for fp32 output without an activation
-    if (plan.hdr && !a.y_bf16 && a.act < 0) return launch_stream_c<B, false, true>(a, plan, k_features, stream);
+    if (plan.w_hdr && !a.y_bf16 && a.act < 0) {
+      ChunkPlan wide{};
+      wide.hdr = plan.w_hdr;
+      wide.chunk_row = plan.w_chunk_row;
+      wide.chunk_kb = plan.w_chunk_kb;
+      wide.chunk_ke = plan.w_chunk_ke;
+      wide.max_chunks = plan.w_max_chunks;
+      wide.max_row_blocks = plan.max_row_blocks;
+      return launch_stream_c<B, false, true>(a, wide, k_features, stream);
+    }
   }
   return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, k_features, stream);
 }
@@ -439,6 +454,13 @@ ChunkPlan plan_of(const blast_bsr_view* v, int64_t T) {
   p.chunk_kb = reinterpret_cast<const int*>(ab + L.chunk_kb_off);
   p.chunk_ke = reinterpret_cast<const int*>(ab + L.chunk_ke_off);
   p.max_chunks = nbr + v->nnz / blast::kChunkBlocks;
+  if (v->max_row_blocks > blast::kWideChunkBlocks) {  // otherwise every row is one wide chunk: no plan needed
+    p.w_hdr = reinterpret_cast<const int*>(ab + L.whdr_off);
+    p.w_chunk_row = reinterpret_cast<const int*>(ab + L.wchunk_row_off);
+    p.w_chunk_kb = reinterpret_cast<const int*>(ab + L.wchunk_kb_off);
+    p.w_chunk_ke = reinterpret_cast<const int*>(ab + L.wchunk_ke_off);
+    p.w_max_chunks = nbr + v->nnz / blast::kWideChunkBlocks;
+  }
   p.max_row_blocks = v->max_row_blocks;
   return p;
 }

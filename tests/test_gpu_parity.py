@@ -40,36 +40,39 @@ def pack_both(api, W, b, mask=None, sparsity=None):
     return dev, ref
 
 
-CHUNK = 16  # blocks per chunk of the packer's chunk plan
+CHUNK = 16  # blocks per chunk of the packer's chunk plan (decode kernels)
+WIDE_CHUNK = 64  # ... of its second plan (streaming kernels)
 
 
 def check_aux(dev, ref):
-    """aux = chunk plan (rows in schedule order cut into chunks of <= 16 blocks) followed by the
-    column-grouped index (the same blocks by column, then ascending row)."""
+    """aux = two chunk plans (rows in schedule order cut into chunks of <= 16 and of <= 64 blocks) followed by
+    the column-grouped index (the same blocks by column, then ascending row)."""
     nbr, nbc = ref.rows // ref.b, ref.cols // ref.b
     aux = dev.aux.cpu().numpy()
     a16 = lambda x: (x + 15) // 16 * 16
-    cap = nbr + (nbr * nbc) // CHUNK + 1
-    hdr = aux[:16].view(np.int32)
-    off = 16
-    chunk_row = aux[off: off + 4 * cap].view(np.int32)
-    off += a16(4 * cap)
-    chunk_kb = aux[off: off + 4 * cap].view(np.int32)
-    off += a16(4 * cap)
-    chunk_ke = aux[off: off + 4 * cap].view(np.int32)
-    off += a16(4 * cap)
-    # expected plan, written from the definition
-    exp = []
     cnt = np.diff(ref.row_ptr)
-    for r in ref.row_order:
-        kb, ke = int(ref.row_ptr[r]), int(ref.row_ptr[r + 1])
-        nch = max(1, -(-(ke - kb) // CHUNK))
-        for j in range(nch):
-            exp.append((int(r), nch > 1, kb + j * CHUNK, min(kb + (j + 1) * CHUNK, ke)))
-    assert hdr[0] == len(exp) and hdr[1] == (int(cnt.max()) if cnt.size else 0) == dev.max_row_blocks and hdr[2] == CHUNK
-    n = len(exp)
-    assert [(int(c) & 0x7FFFFFFF, int(c) < 0, int(a), int(b_)) for c, a, b_ in
-            zip(chunk_row[:n], chunk_kb[:n], chunk_ke[:n])] == exp
+    off = 0
+    for chunk in (CHUNK, WIDE_CHUNK):
+        cap = nbr + (nbr * nbc) // chunk + 1
+        hdr = aux[off: off + 16].view(np.int32)
+        off += 16
+        chunk_row = aux[off: off + 4 * cap].view(np.int32)
+        off += a16(4 * cap)
+        chunk_kb = aux[off: off + 4 * cap].view(np.int32)
+        off += a16(4 * cap)
+        chunk_ke = aux[off: off + 4 * cap].view(np.int32)
+        off += a16(4 * cap)
+        # expected plan, written from the definition
+        exp = []
+        for r in ref.row_order:
+            kb, ke = int(ref.row_ptr[r]), int(ref.row_ptr[r + 1])
+            nch = max(1, -(-(ke - kb) // chunk))
+            for j in range(nch):
+                exp.append((int(r), nch > 1, kb + j * chunk, min(kb + (j + 1) * chunk, ke)))
+        assert hdr[0] == len(exp) and hdr[1] == (int(cnt.max()) if cnt.size else 0) == dev.max_row_blocks and hdr[2] == chunk
+        n = len(exp)
+        assert [(int(c) & 0x7FFFFFFF, int(c) < 0, int(a), int(b_)) for c, a, b_ in
+                zip(chunk_row[:n], chunk_kb[:n], chunk_ke[:n])] == exp
     col_ptr = aux[off: off + 4 * (nbc + 1)].view(np.int32)
     off += a16(4 * (nbc + 1))
     csc_row = aux[off: off + 4 * ref.nnz].view(np.int32)
@@ -306,10 +309,12 @@ def test_spmm_strided_operands(api, b, T):
 @pytest.mark.parametrize("b,nbc,T", [(32, 70, 300), (64, 40, 520), (128, 36, 200), (64, 72, 300),
                                      (32, 70, 9), (32, 70, 40), (64, 72, 1), (64, 72, 7), (64, 72, 16), (64, 72, 100), (128, 66, 3), (128, 66, 20),
                                      # rows long enough for the decode kernel to take the chunk plan as well
-                                     (32, 300, 5), (64, 272, 2), (64, 272, 9), (64, 272, 33), (128, 260, 3), (128, 260, 20)])
+                                     (32, 300, 5), (64, 272, 2), (64, 272, 9), (64, 272, 33), (128, 260, 3), (128, 260, 20),
+                                     # many tokens: the streaming kernels take the rows in chunks of 64 blocks
+                                     (32, 300, 300), (64, 272, 300), (128, 200, 600), (128, 129, 1030)])
 def test_spmm_heavy_rows_are_chunked(api, b, nbc, T):
     """Rows with more than 16 stored blocks are cut into chunks that add their partial sums atomically (at
-    decode token counts only when a row is more than 256 blocks long)."""
+    decode token counts only when a row is more than 256 blocks long; at many tokens in chunks of 64)."""
     import torch
 
     rng = np.random.default_rng(900 + b)
