@@ -232,6 +232,13 @@ struct DecCfg {
   // before the next block's activation tile is copied over them, so only the weight slices need two slots.
   // Used where two 16-token tiles per slot would otherwise leave room for a single workgroup per CU
   // (b = 128 with 32 tokens per unit).
+  // WREG: the weight fragments go from memory straight into registers (each lane fetches the 16 bytes it feeds
+  // the matrix instruction with), no LDS for them.  Used by the single-launch MLP at b = 128: with weight
+  // slots in LDS only three of its workgroups fit a CU (46 KiB each), so a layer of a thousand units ran in
+  // two rounds and the consumers, dispatched last, started microseconds late (8B-shaped layer, one token: 768
+  // resident of 1152).  The activation tile keeps one LDS tile per wave.  (Activation fragments in registers as
+  // well were measured: 112 VGPRs, four waves per SIMD, and the second round is back.)
+  static constexpr bool WREG = FUSED && B == 128 && !W8 && NTT == 1;
   static constexpr bool XONE = !XSMALL && NTT == 2 && B == 128;
   // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
   // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
@@ -239,7 +246,7 @@ struct DecCfg {
   // One-byte weights halve a slice: where a slot stays within 4 KiB the ring is four slots deep, so that the
   // bytes in flight per wave - what the HBM bandwidth reached follows - are those of the bf16 form.
   static constexpr int NSLOT = (W8 && SLOT <= 4096) ? 4 : 2;
-  static constexpr int WAVE_LDS = XONE ? NSLOT * SLW + XB : NSLOT * SLOT;
+  static constexpr int WAVE_LDS = WREG ? XB : (XONE ? NSLOT * SLW + XB : NSLOT * SLOT);
   static constexpr int OPS = NI + NIX;        // copy instructions per block and wave
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * WAVE_LDS;
@@ -352,7 +359,9 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   // ---- ring -----------------------------------------------------------------------------
   // where block j's weight slice and activation tile live in this wave's part of the ring
   auto wslot = [&](int j) { return ring + (j % NSLOT) * (C::XONE ? C::SLW : C::SLOT); };
-  auto xslot = [&](int j) { return C::XONE ? ring + NSLOT * C::SLW : ring + (j % NSLOT) * C::SLOT + C::SLW; };
+  auto xslot = [&](int j) {
+    return C::WREG ? ring : (C::XONE ? ring + NSLOT * C::SLW : ring + (j % NSLOT) * C::SLOT + C::SLW);
+  };
   auto locate = [&](int j, const unsigned char*& wblk, const unsigned char*& xcol) {
     const int i = wave + 4 * j;
     const bool second = DUAL && i >= n0;
@@ -395,14 +404,19 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     hand = handover_begin(a, peek);
     const unsigned long long token = hand.token;
     bool gave_up = false;
+    // One poll covers the slots of 64 / SLICES blocks: lane -> (block jb + lane / SLICES, slice lane % SLICES).
+    // Polling block after block would cost a round trip to the memory side per block even when every
+    // slice has long been published.
+    constexpr int kPerPoll = 64 / C::SLICES;
 #pragma unroll 1
-    for (int j = 0; j < cnt && !gave_up; ++j) {
-      const int col = ld_idx(a.m0.col_idx, kb0 + wave + 4 * j);
-      const unsigned long long* sl = a.slots + (int64_t)col * C::SLICES;
+    for (int jb = 0; jb < cnt && !gave_up; jb += kPerPoll) {
+      const int jj = jb + lane / C::SLICES;
+      const bool mine = jj < cnt;
+      const int col = mine ? a.m0.col_idx[kb0 + wave + 4 * jj] : 0;
+      const unsigned long long* sl = a.slots + (int64_t)col * C::SLICES + (lane % C::SLICES);
       int spins = 0;
       for (;;) {
-        const unsigned long long v =
-            lane < C::SLICES ? __hip_atomic_load(sl + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : token;
+        const unsigned long long v = mine ? __hip_atomic_load(sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : token;
         if (__ballot(v != token) == 0) break;
         if (++spins > a.max_spins) {
           gave_up = true;
@@ -423,7 +437,61 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   }
 
   // a producer draws the launch's token while its first copies are in flight; it needs it only to publish
-  if constexpr (C::XONE) {
+  if constexpr (C::WREG) {
+    // Fragment (k-step s, lane group g) of weight row l16 = bytes [(4 s + g) * 16, +16) of that row.  Two
+    // register sets take turns: the fragments of the next block are on their way while one block is
+    // multiplied (a third set was measured and changes nothing: with at most a few blocks per wave the time
+    // is the memory's, not the ring's).  The activation tile still goes through LDS, one tile per wave,
+    // copied a block ahead.
+    bf16x8 w0s[KST], w1s[KST];
+    const uint32_t wg0 = (uint32_t)(q * C::SLB + l16 * (B * 2) + g * 16);
+    auto load_w = [&](bf16x8 (&dst)[KST], int j) {
+      const unsigned char *wblk, *xcol;
+      locate(j, wblk, xcol);
+#pragma unroll
+      for (int s = 0; s < KST; ++s) dst[s] = *reinterpret_cast<const bf16x8*>(wblk + wg0 + s * 64);
+      asm volatile("" ::: "memory");  // issued here, not later
+    };
+    if (cnt > 0) load_w(w0s, 0);
+    if (cnt > 1) load_w(w1s, 1);
+    if (cnt > 0) issue_x(0);
+    if (ROLE == kDecProducer) hand = handover_begin(a, peek);
+    // Requests retire in issue order: W 0, W 1, X 0, and then per block j: X j+1, W j+2.  When block j
+    // starts, the only requests younger than its activation tile are the KST loads of W j+1 (j >= 1).
+    auto block = [&](bf16x8 (&wcur)[KST], int j) {
+      if (j >= 1 && j + 1 < cnt)
+        __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(KST));
+      else
+        __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
+      asm volatile("" ::: "memory");
+      const unsigned char* xs = xslot(j);
+      bf16x8 xf[KST];
+#pragma unroll
+      for (int s = 0; s < KST; ++s) xf[s] = *reinterpret_cast<const bf16x8*>(xs + fxoff[s]);
+      // the fragments are in registers before the next activation tile is copied over this one
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      asm volatile("" ::: "memory");
+      if (j + 1 < cnt) issue_x(j + 1);
+      const bool second = DUAL && (wave + 4 * j) >= n0;
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < KST; ++s) {
+        const bf16x8 wg = second ? zero : wcur[s];
+        acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s], wg, acc[0][0], 0, 0, 0);
+        if (DUAL) {
+          const bf16x8 wu = second ? wcur[s] : zero;
+          acc[NM - 1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s], wu, acc[NM - 1][0], 0, 0, 0);
+        }
+      }
+      asm volatile("" ::: "memory");
+      if (j + 2 < cnt) load_w(wcur, j + 2);
+    };
+#pragma unroll 1
+    for (int j = 0; j < cnt; j += 2) {
+      block(w0s, j);
+      if (j + 1 < cnt) block(w1s, j + 1);
+    }
+  } else if constexpr (C::XONE) {
     static_assert(!C::XONE || NSLOT == 2, "the single activation tile is written for two weight slots");
     if (cnt > 0) issue(0);
     if (ROLE == kDecProducer) hand = handover_begin(a, peek);
