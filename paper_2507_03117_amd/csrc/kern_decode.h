@@ -390,9 +390,11 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     issue_x(j);
   };
 
-  if (ROLE == kDecConsumer) {
-    // Pull this wave's weight slices towards the L2 while H is still being produced (they do not depend
-    // on it), then wait until every slice of H that its blocks read has been published.
+  // Consumers: called once the copies of the first block's weights are on their way and before the first copy
+  // of H.  Pulls the wave's other weight slices towards the L2 while H is still being produced (they do not
+  // depend on it), then waits until every slice of H that its blocks read has been published.
+  auto wait_for_h = [&]() {
+    if (ROLE != kDecConsumer) return;
     uint32_t warm = 0;
 #pragma unroll 1
     for (int j = 0; j < cnt; ++j) {
@@ -434,7 +436,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     // keeps the warming loads alive; the value never matches
     if (warm == 0x9E3779B9u && a.T < 0) a.sync_err[1] = 1;
     asm volatile("" ::: "memory");
-  }
+  };
 
   // a producer draws the launch's token while its first copies are in flight; it needs it only to publish
   if constexpr (C::WREG) {
@@ -454,6 +456,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     };
     if (cnt > 0) load_w(w0s, 0);
     if (cnt > 1) load_w(w1s, 1);
+    wait_for_h();
     if (cnt > 0) issue_x(0);
     if (ROLE == kDecProducer) hand = handover_begin(a, peek);
     // Requests retire in issue order: W 0, W 1, X 0, and then per block j: X j+1, W j+2.  When block j
@@ -493,7 +496,9 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
     }
   } else if constexpr (C::XONE) {
     static_assert(!C::XONE || NSLOT == 2, "the single activation tile is written for two weight slots");
-    if (cnt > 0) issue(0);
+    if (cnt > 0) issue_w(0);
+    wait_for_h();
+    if (cnt > 0) issue_x(0);
     if (ROLE == kDecProducer) hand = handover_begin(a, peek);
 #pragma unroll 1
     for (int j = 0; j < cnt; ++j) {
@@ -537,9 +542,18 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
       asm volatile("" ::: "memory");
     }
   } else {
+  if constexpr (ROLE == kDecConsumer) {
+    // the first block's weights are copied while the wait lasts (two slots: one block ahead, so the order
+    // W 0, X 0, W 1, X 1, ... that the waits below count on is kept)
+    static_assert(ROLE != kDecConsumer || NSLOT == 2, "the split first step is written for one block ahead");
+    if (cnt > 0) issue_w(0);
+    wait_for_h();
+    if (cnt > 0) issue_x(0);
+  } else {
 #pragma unroll 1
-  for (int j = 0; j < NSLOT - 1; ++j)
-    if (j < cnt) issue(j);
+    for (int j = 0; j < NSLOT - 1; ++j)
+      if (j < cnt) issue(j);
+  }
   if (ROLE == kDecProducer) hand = handover_begin(a, peek);
 
 #pragma unroll 1
