@@ -393,6 +393,13 @@ def test_mlp_small(api, b, T):
     _mlp_case(api, 3000 + b + T, 4 * b, 6 * b, b, 0.5, T)
 
 
+@pytest.mark.parametrize("b,T", [(64, 1), (64, 8), (64, 16), (64, 29), (128, 1), (128, 4), (128, 9), (128, 16)])
+def test_mlp_one_launch_with_many_blocks_per_wave(api, b, T):
+    """Rows of 14-28 stored blocks in both products of the single-launch form: every wave walks several blocks,
+    so its ring (b = 64) or its two register sets (b = 128) go round more than once."""
+    _mlp_case(api, 3050 + b + T, 20 * b, 24 * b, b, 0.3, T)
+
+
 @pytest.mark.parametrize("act", ["silu", "gelu", "relu"])
 def test_mlp_activations_and_layouts(api, act):
     _mlp_case(api, 3100, 256, 512, 64, 0.6, 37, act=act)
