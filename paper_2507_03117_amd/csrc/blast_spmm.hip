@@ -81,6 +81,7 @@ struct ZeroJob {
   int64_t syt = 0, syi = 0;
   int T = 0;
   int64_t max_chunks = 0;
+  bool wide = false;  // the plan is the streaming kernels' (chunks of kWideChunkBlocks), else the decode kernels'
   bool done = false;
 };
 
@@ -132,7 +133,20 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
       n_rows / 8 + 1 <= 64 * ((grid / 8) / a.ntt))
     row_pinned = 1;
   StreamArgs sa{a, (int)n_items, shift, row_pinned, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
-  if (CHUNK) {
+  if (!CHUNK && plan.zero_job && plan.zero_job->hdr && plan.zero_job->wide && !plan.zero_job->done) {
+    // a later chunked product's rows are cleared by this launch on the side
+    ZeroJob& z = *plan.zero_job;
+    sa.z_hdr = z.hdr;
+    sa.z_chunk_row = z.chunk_row;
+    sa.z_chunk_kb = z.chunk_kb;
+    sa.z_row_ptr = z.row_ptr;
+    sa.z_Y = z.Y;
+    sa.z_syt = z.syt;
+    sa.z_syi = z.syi;
+    sa.z_T = z.T;
+    z.done = true;
+  }
+  if (CHUNK && !plan.pre_zeroed) {
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
   }
@@ -188,10 +202,13 @@ int launch_stream(const TileArgs& a, const ChunkPlan& plan, int64_t k_features, 
       wide.chunk_ke = plan.w_chunk_ke;
       wide.max_chunks = plan.w_max_chunks;
       wide.max_row_blocks = plan.max_row_blocks;
+      wide.pre_zeroed = plan.pre_zeroed;
       return launch_stream_c<B, false, true>(a, wide, k_features, stream);
     }
   }
-  return launch_stream_c<B, DUAL, false>(a, ChunkPlan{}, k_features, stream);
+  ChunkPlan side{};  // no chunks; only the side job travels on
+  side.zero_job = plan.zero_job;
+  return launch_stream_c<B, DUAL, false>(a, side, k_features, stream);
 }
 
 template <int B, bool DUAL, int NTT, bool CHUNK, int XSMALL = 0>
@@ -220,7 +237,8 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   d.n_units = (int)units;
   d.groups = (int)groups;
   int64_t total = grid;
-  if (plan.zero_job && plan.zero_job->hdr && plan.zero_job->max_chunks > 0 && grid + plan.zero_job->max_chunks <= INT32_MAX) {
+  if (plan.zero_job && plan.zero_job->hdr && !plan.zero_job->wide && plan.zero_job->max_chunks > 0 &&
+      grid + plan.zero_job->max_chunks <= INT32_MAX) {
     ZeroJob& z = *plan.zero_job;
     d.main_blocks = (int)grid;
     d.z_blocks = (int)z.max_chunks;
@@ -723,17 +741,26 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   // At decode token counts the rows of Y that the chunked second product accumulates into are cleared on
   // the side by the first product's launch (extra workgroups of the same kernel) instead of by a launch
   // of their own between the two products.
+  // Beyond them the streaming kernels do the same with the rows of their own (64-block) plan.
   ZeroJob zj{};
   if (dplan.hdr && y_dtype == BLAST_F32 && T <= kDecodeMaxTokens && I > 0) {
     zj.hdr = dplan.hdr;
     zj.chunk_row = dplan.chunk_row;
     zj.chunk_kb = dplan.chunk_kb;
+    zj.max_chunks = dplan.max_chunks;
+  } else if (dplan.w_hdr && y_dtype == BLAST_F32 && T > kDecodeMaxTokens && I > 0) {
+    zj.hdr = dplan.w_hdr;
+    zj.chunk_row = dplan.w_chunk_row;
+    zj.chunk_kb = dplan.w_chunk_kb;
+    zj.max_chunks = dplan.w_max_chunks;
+    zj.wide = true;
+  }
+  if (zj.hdr) {
     zj.row_ptr = Wdown->row_ptr;
     zj.Y = static_cast<float*>(Y);
     zj.syt = d.syt;
     zj.syi = d.syi;
     zj.T = (int)T;
-    zj.max_chunks = dplan.max_chunks;
   }
   if (I > 0) {
     if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream,

@@ -89,6 +89,16 @@ struct StreamArgs {
   const int* chunk_row;  // block row of the chunk; bit 31 set when the row has several chunks
   const int* chunk_kb;   // first stored block of the chunk
   const int* chunk_ke;   // one past its last stored block
+  // Side job (z_hdr != null): before its own work this launch clears the fp32 rows that a LATER chunked
+  // product accumulates into (the block rows cut into several chunks of that product's plan), so that
+  // product needs no clearing launch of its own.  Units of (chunk slot, 64 tokens), dealt to all workgroups.
+  const int* z_hdr;
+  const int* z_chunk_row;
+  const int* z_chunk_kb;
+  const int* z_row_ptr;
+  float* z_Y;
+  int64_t z_syt, z_syi;
+  int z_T;
 };
 
 // item -> (rank in the row schedule, token tile) without an integer division in the common case
@@ -238,6 +248,39 @@ struct Loader {
   bool valid;
 };
 
+// The side job of StreamArgs: every lane looks at one unit (chunk slot, slab of 64 tokens) of the later
+// product's plan, units being dealt to the workgroups round-robin; the units that are the first chunk of a
+// row made of several chunks are then cleared by the whole workgroup, one after the other.
+template <int B, int NTHREADS>
+__device__ __forceinline__ void stream_zero_side(const StreamArgs& sa, int w, int G, int lane) {
+  const int n_chunks = ld_idx(sa.z_hdr, 0);
+  const int slabs = (sa.z_T + 63) >> 6;
+  const int64_t total = (int64_t)n_chunks * slabs;
+  for (int64_t base = 0; base < total; base += (int64_t)G * 64) {
+    const int64_t u = base + (int64_t)lane * G + w;
+    int r = -1, slab = 0;
+    if (u < total) {
+      const int ci = (int)(u / slabs);
+      slab = (int)(u - (int64_t)ci * slabs);
+      const int cr = sa.z_chunk_row[ci];
+      if (cr < 0) {  // a row made of several chunks ...
+        const int row = cr & 0x7FFFFFFF;
+        if (sa.z_chunk_kb[ci] == sa.z_row_ptr[row]) r = row;  // ... and this is its first chunk
+      }
+    }
+    unsigned long long todo = __ballot(r >= 0);
+    while (todo) {
+      const int l = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int rr = BLAST_LANE(r, l), t0 = BLAST_LANE(slab, l) * 64;
+      for (int e = threadIdx.x; e < 64 * B; e += NTHREADS) {
+        const int t = t0 + e / B, i = e % B;
+        if (t < sa.z_T) sa.z_Y[(int64_t)t * sa.z_syt + ((int64_t)rr * B + i) * sa.z_syi] = 0.0f;
+      }
+    }
+  }
+}
+
 // CHUNK: the items are (chunk of a block row, token tile) pairs from the packer's chunk plan instead of
 // (block row, token tile); a row made of several chunks adds its partial sums into a zeroed fp32 output.
 // POST: a single-matrix product whose result goes through the activation a.act before it is stored
@@ -293,6 +336,7 @@ __global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) vo
       xoff[q] = ((uint32_t)t * sxt32 + (uint32_t)((cp_slot ^ C::key(row)) << 3)) * 2u;
     }
   };
+  if (sa.z_hdr) stream_zero_side<B, 64 * NW>(sa, w, G, lane);
   const ItemTable tab = load_item_table<DUAL, CHUNK>(sa, n_items, w, G, lane);
 
   Loader ld;

@@ -710,10 +710,11 @@ def test_mlp2_topk_packed_gpt2_shape(api):
         check_close(y.cpu().numpy().T, orc.mlp2(r1, r2, x), f"mlp2 gpt2 shape T={T}")
 
 
-@pytest.mark.parametrize("T", [1, 20, 32, 40])
+@pytest.mark.parametrize("T", [1, 20, 32, 40, 300, 700])
 def test_mlp_decode_with_a_very_long_down_row(api, T):
-    """A row of W_down long enough for the decode kernel to take the chunk plan: its output rows are cleared by
-    side workgroups of the gate/up launch (T <= 32) or by a launch of their own (above), into a poisoned Y."""
+    """A row of W_down long enough for the chunk plans: its output rows are cleared on the side by the gate/up
+    launch (decode kernel: extra workgroups; streaming kernel, many tokens: every workgroup before its own
+    work) or by a launch of their own (in between), into a poisoned Y."""
     import torch
 
     rng = np.random.default_rng(8600 + T)
