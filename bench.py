@@ -618,12 +618,11 @@ def main():
             Lc = Layer(name, api, torch, synth)
             for Tc in toks:
                 rows.append(Lc.row(Tc, st if Tc < 512 else args.steps, args.warmup))
-            if name in ("llama1b_b64_s90", "llama8b_b128_s95"):  # E5M2 weights at the decode token counts
-                for Tc in ((1, 16) if name == "llama1b_b64_s90" else (1, 32)):
-                    rows.append(Lc.row_e5m2w(Tc, st, args.warmup))
+            if name in ("llama1b_b64_s90", "llama8b_b128_s95"):  # E5M2 weights, one token
+                rows.append(Lc.row_e5m2w(1, st, args.warmup))
             del Lc
             torch.cuda.empty_cache()
-        out["configs_columns"] = ["workload(llama*)", "tokens", "us_graph", "us_eager", "bound", "TFLOPs|GBps", "frac_peak"]
+        out["configs_columns"] = ["llama*", "T", "us_graph", "us_eager", "bound", "TFLOPs|GBps", "frac"]
         out["configs"] = rows
 
     if args.extras:
