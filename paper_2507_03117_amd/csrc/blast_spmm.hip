@@ -672,8 +672,7 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
     if (g.T <= 512 / B) return launch_mlp_decode<B, 1, true, GATED>(p, c, stream);
   }
   if (g.T <= 16) return launch_mlp_decode<B, 1, false, GATED>(p, c, stream);
-  if constexpr (B != 128) return launch_mlp_decode<B, 2, false, GATED>(p, c, stream);
-  return BLAST_ERR_INVALID_ARG;
+  return launch_mlp_decode<B, 2, false, GATED>(p, c, stream);
 }
 
 int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
@@ -689,7 +688,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   uint16_t* H = static_cast<uint16_t*>(ws);
 
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[0]), stream));
-  const int64_t one_tile = (b == 128) ? 16 : 32;
+  const int64_t one_tile = 32;
   // One launch saves a dispatch gap and the second kernel's ramp, a few microseconds; its smaller copy rings
   // (producers and consumers share the CUs) cost bandwidth.  Measured with uniform masks and cold weights:
   // about even up to 18 MB of stored blocks, 63 us against 55 us on the 405B-class layer (262 MB).

@@ -238,7 +238,7 @@ struct DecCfg {
   // two rounds and the consumers, dispatched last, started microseconds late (8B-shaped layer, one token: 768
   // resident of 1152).  The activation tile keeps one LDS tile per wave.  (Activation fragments in registers as
   // well were measured: 112 VGPRs, four waves per SIMD, and the second round is back.)
-  static constexpr bool WREG = FUSED && B == 128 && !W8 && NTT == 1;
+  static constexpr bool WREG = FUSED && B == 128 && !W8;
   static constexpr bool XONE = !XSMALL && NTT == 2 && B == 128;
   // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
   // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
@@ -251,7 +251,12 @@ struct DecCfg {
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * WAVE_LDS;
   static constexpr int RED_LDS = 3 * NM * NTT * 4 * 64 * 4;
-  static constexpr size_t LDS_BYTES = (size_t)RING_LDS + RED_LDS;
+  // RED_ALIAS: the buffer in which the four partial sums meet lies over the activation tiles, which are done
+  // with by then (32 tokens per unit in the register form: 32 + 12 KiB would leave room for three workgroups
+  // per CU, 32 KiB leaves room for five)
+  static constexpr bool RED_ALIAS = WREG && NTT == 2;
+  static constexpr int RED_OFF = RED_ALIAS ? 0 : RING_LDS;
+  static constexpr size_t LDS_BYTES = RED_ALIAS ? (size_t)(RING_LDS > RED_LDS ? RING_LDS : RED_LDS) : (size_t)RING_LDS + RED_LDS;
   static_assert(SLW % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
   // swizzle key of a row (mod 16): distinct for rows that would otherwise share banks
   __device__ static __forceinline__ int key(int row) { return ((row & 15) / (16 / (CPRW < 16 ? CPRW : 16))) % CPRW; }
@@ -274,7 +279,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
                 "producers compute the activated intermediate, consumers a plain product");
   using C = DecCfg<B, DUAL, NTT, XSMALL, ROLE != kDecAlone, W8>;
   constexpr int KST = C::KST, NM = C::NM, NI = C::NI, NSLOT = C::NSLOT;
-  float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::RING_LDS);
+  float (*red)[NM][NTT][4][64] = reinterpret_cast<float (*)[NM][NTT][4][64]>(smem + C::RED_OFF);
   const int q = unit % C::SLICES;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63, l16 = lane & 15, g = lane >> 4;
@@ -468,9 +473,11 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
         __builtin_amdgcn_s_waitcnt(BLAST_VMCNT(0));
       asm volatile("" ::: "memory");
       const unsigned char* xs = xslot(j);
-      bf16x8 xf[KST];
+      bf16x8 xf[KST][NTT];
 #pragma unroll
-      for (int s = 0; s < KST; ++s) xf[s] = *reinterpret_cast<const bf16x8*>(xs + fxoff[s]);
+      for (int s = 0; s < KST; ++s)
+#pragma unroll
+        for (int tt = 0; tt < NTT; ++tt) xf[s][tt] = *reinterpret_cast<const bf16x8*>(xs + C::SLB * tt + fxoff[s]);
       // the fragments are in registers before the next activation tile is copied over this one
       __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
       asm volatile("" ::: "memory");
@@ -480,10 +487,13 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
 #pragma unroll
       for (int s = 0; s < KST; ++s) {
         const bf16x8 wg = second ? zero : wcur[s];
-        acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s], wg, acc[0][0], 0, 0, 0);
-        if (DUAL) {
-          const bf16x8 wu = second ? wcur[s] : zero;
-          acc[NM - 1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s], wu, acc[NM - 1][0], 0, 0, 0);
+#pragma unroll
+        for (int tt = 0; tt < NTT; ++tt) {
+          acc[0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s][tt], wg, acc[0][tt], 0, 0, 0);
+          if (DUAL) {
+            const bf16x8 wu = second ? wcur[s] : zero;
+            acc[NM - 1][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[s][tt], wu, acc[NM - 1][tt], 0, 0, 0);
+          }
         }
       }
       asm volatile("" ::: "memory");
@@ -599,6 +609,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   }
 
   // ---- the four partial sums meet in LDS ---------------------------------------------------
+  if constexpr (C::RED_ALIAS) __syncthreads();  // every wave has read its last activation tile
   if (wave > 0) {
 #pragma unroll
     for (int m = 0; m < NM; ++m)
