@@ -353,7 +353,7 @@ int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_byte
  *   ws, ws_bytes       at least blast_sparse_mlp_workspace() bytes, 256-byte aligned.  Scratch: its contents
  *                      need no initialisation and mean nothing afterwards; two calls that may overlap in
  *                      time (different streams) need different workspaces.
- * Up to one token tile (T <= 32) with token-major, 16-byte aligned X and at most 32 MB of
+ * Up to one token tile (T <= 32; 64 for b = 64) with token-major, 16-byte aligned X and at most 32 MB of
  * stored blocks in the three matrices the whole of Eq. (1) runs as one kernel launch: the workgroups of the second
  * product wait inside the kernel until the slices of H they read have been published by the workgroups of the first
  * (a bounded wait; should it ever expire, their output rows are NaN and blast_sparse_mlp_status reports it).  The

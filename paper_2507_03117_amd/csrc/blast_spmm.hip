@@ -635,7 +635,6 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
   p.T = g.T;
   p.act = g.act;
   p.n_units = (int)(Wgate->rows / B) * (B / 16);
-  p.groups = 1;
   p.slots = slots;
   p.token = next_token();
   p.ctl = ctl;
@@ -653,13 +652,13 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
   c.T = d.T;
   c.act = -1;
   c.n_units = (int)(Wdown->rows / B) * (B / 16);
-  c.groups = 1;
   c.slots = slots;
   c.token = p.token;
   c.ctl = ctl;
   c.max_spins = knobs.max_spins;
   c.withhold = knobs.withhold;
   c.sync_err = p.sync_err;
+  p.groups = c.groups = 1;
   p.total_waves = c.total_waves = (p.n_units + c.n_units) * 4;
   {  // a launch adds 2^shift to each of the 64 arrival counters: the smallest power of two >= the largest group
     const int largest = (p.total_waves + kCtlGroups - 1) / kCtlGroups;
@@ -672,7 +671,9 @@ int enqueue_mlp_decode(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
     if (g.T <= 512 / B) return launch_mlp_decode<B, 1, true, GATED>(p, c, stream);
   }
   if (g.T <= 16) return launch_mlp_decode<B, 1, false, GATED>(p, c, stream);
-  return launch_mlp_decode<B, 2, false, GATED>(p, c, stream);
+  if (g.T <= 32) return launch_mlp_decode<B, 2, false, GATED>(p, c, stream);
+  if constexpr (B == 64) return launch_mlp_decode<B, 4, false, GATED>(p, c, stream);
+  return BLAST_ERR_INVALID_ARG;
 }
 
 int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blast_bsr_view* Wdown,
@@ -688,7 +689,7 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   uint16_t* H = static_cast<uint16_t*>(ws);
 
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[0]), stream));
-  const int64_t one_tile = 32;
+  const int64_t one_tile = (b == 64) ? 64 : 32;  // 64-token units exist for 64-wide blocks only
   // One launch saves a dispatch gap and the second kernel's ramp, a few microseconds; its smaller copy rings
   // (producers and consumers share the CUs) cost bandwidth.  Measured with uniform masks and cold weights:
   // about even up to 18 MB of stored blocks, 63 us against 55 us on the 405B-class layer (262 MB).

@@ -238,7 +238,7 @@ struct DecCfg {
   // two rounds and the consumers, dispatched last, started microseconds late (8B-shaped layer, one token: 768
   // resident of 1152).  The activation tile keeps one LDS tile per wave.  (Activation fragments in registers as
   // well were measured: 112 VGPRs, four waves per SIMD, and the second round is back.)
-  static constexpr bool WREG = FUSED && B == 128 && !W8;
+  static constexpr bool WREG = FUSED && !W8 && (B == 128 || NTT == 4);
   static constexpr bool XONE = !XSMALL && NTT == 2 && B == 128;
   // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
   // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
@@ -254,7 +254,7 @@ struct DecCfg {
   // RED_ALIAS: the buffer in which the four partial sums meet lies over the activation tiles, which are done
   // with by then (32 tokens per unit in the register form: 32 + 12 KiB would leave room for three workgroups
   // per CU, 32 KiB leaves room for five)
-  static constexpr bool RED_ALIAS = WREG && NTT == 2;
+  static constexpr bool RED_ALIAS = WREG && NTT >= 2;
   static constexpr int RED_OFF = RED_ALIAS ? 0 : RING_LDS;
   static constexpr size_t LDS_BYTES = RED_ALIAS ? (size_t)(RING_LDS > RED_LDS ? RING_LDS : RED_LDS) : (size_t)RING_LDS + RED_LDS;
   static_assert(SLW % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
@@ -683,8 +683,11 @@ __global__ __launch_bounds__(256) void k_decode(const DecArgs a) {
 
 // Single-launch MLP for one token tile (T <= 16 NTT): workgroups [0, n_units) compute H slice by slice
 // (args `p`; H = act(G) (.) U with GATED, H = act(W1 X) without), workgroups [n_units, n_units + c.n_units)
-// the last projection (args `c`, whose X is that H).  A consumer only ever waits for producers, which wait for nothing and have lower
-// workgroup ids, hence are dispatched first: the wait always ends (and is bounded besides).
+// the last projection (args `c`, whose X is that H).  A consumer only ever waits for producers, which wait for
+// nothing and have lower workgroup ids, hence are dispatched first: the wait always ends (and is bounded
+// besides).  The grid is exactly p.n_units + c.n_units: every wave takes part in the arrival count.  (Two
+// token tiles per launch, each with slots of its own, were measured on the 1B-shaped layer at 65-128
+// tokens: 20.8-21.6 us against 19.4 for two launches - twice the workgroups no longer fit the chip at once.)
 template <int B, int NTT, int XSMALL, bool GATED = true>
 __global__ __launch_bounds__(256) void k_mlp_decode(const DecArgs p, const DecArgs c) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];

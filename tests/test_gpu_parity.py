@@ -393,8 +393,8 @@ def test_mlp_small(api, b, T):
     _mlp_case(api, 3000 + b + T, 4 * b, 6 * b, b, 0.5, T)
 
 
-@pytest.mark.parametrize("b,T", [(64, 1), (64, 8), (64, 16), (64, 29), (128, 1), (128, 4), (128, 9), (128, 16), (128, 21),
-                                 (128, 32)])
+@pytest.mark.parametrize("b,T", [(64, 1), (64, 8), (64, 16), (64, 29), (64, 50), (64, 64), (64, 65),
+                                 (128, 1), (128, 4), (128, 9), (128, 16), (128, 21), (128, 32)])
 def test_mlp_one_launch_with_many_blocks_per_wave(api, b, T):
     """Rows of 14-28 stored blocks in both products of the single-launch form: every wave walks several blocks,
     so its ring (b = 64) or its two register sets (b = 128) go round more than once."""
@@ -435,7 +435,7 @@ def test_joint_row_order(api):
     assert torch.equal(h1.view(torch.int16), h2.view(torch.int16))
 
 
-@pytest.mark.parametrize("b,T", [(64, 1), (64, 16), (64, 29), (128, 3), (128, 16), (128, 27)])
+@pytest.mark.parametrize("b,T", [(64, 1), (64, 16), (64, 29), (64, 60), (128, 3), (128, 16), (128, 27)])
 def test_mlp_one_launch_reuses_workspace(api, b, T):
     """The single-launch form hands H over inside the kernel through the caller's workspace: calls that
     reuse one workspace with different activations must each see their own H (no stale slots or lines)."""
