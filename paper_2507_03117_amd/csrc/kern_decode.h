@@ -85,18 +85,20 @@ __device__ __forceinline__ void decode_zero_job(const DecArgs& a, int ci) {
   }
 }
 
-// Eight E5M2 codes -> eight bf16 values, exactly: a code is the upper byte of an IEEE half; the half is widened
-// to fp32 by the hardware conversion (which takes care of subnormals, infinities and NaN) and a value with two
-// mantissa bits survives the cut to the upper 16 bits of the fp32 unchanged.
+// Eight E5M2 codes -> eight bf16 values, exactly: the hardware conversion of the 8-bit type with 5 exponent bits
+// (on gfx950 the format of Sec. 5.2: subnormals, infinities and NaN as in the upper byte of an IEEE half) widens
+// two codes to fp32 at a time, and a value with two mantissa bits passes the conversion to bf16 unchanged.
 __device__ __forceinline__ bf16x8 e5m2x8_to_bf16x8(uint2 raw) {
-  typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
-  u16x8 out;
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 out;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const unsigned word = i < 4 ? raw.x : raw.y;
-    const unsigned short half_bits = (unsigned short)(((word >> (8 * (i & 3))) & 0xFFu) << 8);
-    const float f = (float)__builtin_bit_cast(_Float16, half_bits);
-    out[i] = (unsigned short)(__builtin_bit_cast(unsigned, f) >> 16);
+  for (int i = 0; i < 4; ++i) {
+    const unsigned word = i < 2 ? raw.x : raw.y;
+    const f32x2 f = (i & 1) ? __builtin_amdgcn_cvt_pk_f32_bf8(word, true) : __builtin_amdgcn_cvt_pk_f32_bf8(word, false);
+    const bf16x2 h = {static_cast<__bf16>(f[0]), static_cast<__bf16>(f[1])};
+    out[i] = __builtin_bit_cast(unsigned, h);
   }
   return __builtin_bit_cast(bf16x8, out);
 }
@@ -251,10 +253,11 @@ struct DecCfg {
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * WAVE_LDS;
   static constexpr int RED_LDS = 3 * NM * NTT * 4 * 64 * 4;
-  // RED_ALIAS: the buffer in which the four partial sums meet lies over the activation tiles, which are done
-  // with by then (32 tokens per unit in the register form: 32 + 12 KiB would leave room for three workgroups
-  // per CU, 32 KiB leaves room for five)
-  static constexpr bool RED_ALIAS = WREG && NTT >= 2;
+  // RED_ALIAS: the buffer in which the four partial sums meet lies over the ring, which every wave is done
+  // with by then (a barrier in front of it).  Where it decides how many workgroups fit a CU: 32 tokens per
+  // unit in the register form (32 + 12 KiB: three workgroups, 32 KiB: five), and one-byte weights with their
+  // four-slot rings (b = 128: 48 + 6 KiB: two workgroups, 48 KiB: three).
+  static constexpr bool RED_ALIAS = (WREG && NTT >= 2) || W8;
   static constexpr int RED_OFF = RED_ALIAS ? 0 : RING_LDS;
   static constexpr size_t LDS_BYTES = RED_ALIAS ? (size_t)(RING_LDS > RED_LDS ? RING_LDS : RED_LDS) : (size_t)RING_LDS + RED_LDS;
   static_assert(SLW % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
@@ -609,7 +612,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   }
 
   // ---- the four partial sums meet in LDS ---------------------------------------------------
-  if constexpr (C::RED_ALIAS) __syncthreads();  // every wave has read its last activation tile
+  if constexpr (C::RED_ALIAS) __syncthreads();  // every wave has read the last of its ring
   if (wave > 0) {
 #pragma unroll
     for (int m = 0; m < NM; ++m)
