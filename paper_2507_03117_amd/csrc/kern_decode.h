@@ -253,13 +253,13 @@ struct DecCfg {
   static constexpr int NM = DUAL ? 2 : 1;
   static constexpr int RING_LDS = 4 * WAVE_LDS;
   static constexpr int RED_LDS = 3 * NM * NTT * 4 * 64 * 4;
-  // RED_ALIAS: the buffer in which the four partial sums meet lies over the ring, which every wave is done
-  // with by then (a barrier in front of it).  Where it decides how many workgroups fit a CU: 32 tokens per
-  // unit in the register form (32 + 12 KiB: three workgroups, 32 KiB: five), and one-byte weights with their
-  // four-slot rings (b = 128: 48 + 6 KiB: two workgroups, 48 KiB: three).
-  static constexpr bool RED_ALIAS = (WREG && NTT >= 2) || W8;
-  static constexpr int RED_OFF = RED_ALIAS ? 0 : RING_LDS;
-  static constexpr size_t LDS_BYTES = RED_ALIAS ? (size_t)(RING_LDS > RED_LDS ? RING_LDS : RED_LDS) : (size_t)RING_LDS + RED_LDS;
+  // The buffer in which the four partial sums meet lies over the ring, which every wave is done with by then (a
+  // barrier in front of it): every kilobyte counts towards how many workgroups fit a CU.  Measured where it
+  // decides that number: 32-token units of the single launch at b = 64 (60 -> 48 KiB, three workgroups per CU,
+  // the whole 1B-shaped launch resident: 13.2 -> 11.5 us), one-byte weights with their four-slot rings at
+  // b = 128 (54 -> 48 KiB, three instead of two: 42.6 -> 37.7 us on the 405B-class layer with a uniform mask).
+  static constexpr int RED_OFF = 0;
+  static constexpr size_t LDS_BYTES = (size_t)(RING_LDS > RED_LDS ? RING_LDS : RED_LDS);
   static_assert(SLW % 1024 == 0 && (NSLOT - 1) * OPS < 64, "copy granularity / counter range");
   // swizzle key of a row (mod 16): distinct for rows that would otherwise share banks
   __device__ static __forceinline__ int key(int row) { return ((row & 15) / (16 / (CPRW < 16 ? CPRW : 16))) % CPRW; }
@@ -612,7 +612,7 @@ __device__ __forceinline__ void decode_unit(const DecArgs& a, const int unit, co
   }
 
   // ---- the four partial sums meet in LDS ---------------------------------------------------
-  if constexpr (C::RED_ALIAS) __syncthreads();  // every wave has read the last of its ring
+  __syncthreads();  // every wave has read the last of its ring: the partial sums go over it
   if (wave > 0) {
 #pragma unroll
     for (int m = 0; m < NM; ++m)
