@@ -238,8 +238,11 @@ struct DecCfg {
   // the matrix instruction with), no LDS for them.  Used by the single-launch MLP at b = 128: with weight
   // slots in LDS only three of its workgroups fit a CU (46 KiB each), so a layer of a thousand units ran in
   // two rounds and the consumers, dispatched last, started microseconds late (8B-shaped layer, one token: 768
-  // resident of 1152).  The activation tile keeps one LDS tile per wave.  (Activation fragments in registers as
-  // well were measured: 112 VGPRs, four waves per SIMD, and the second round is back.)
+  // resident of 1152), and by its 64-token units at b = 64.  The activation tile keeps one LDS tile per wave.
+  // (Activation fragments in registers as well were measured: 112 VGPRs, four waves per SIMD, and the second
+  // round is back.)  Only where latency rules: the ordinary launches of a large layer are bound by bandwidth, and
+  // 16-byte loads scattered over 16 rows fetch less per request than the 1 KiB copies (405B-class layer, one
+  // token: 61 against 51 us; 16 tokens: 72 against 64).
   static constexpr bool WREG = FUSED && !W8 && (B == 128 || NTT == 4);
   static constexpr bool XONE = !XSMALL && NTT == 2 && B == 128;
   // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
