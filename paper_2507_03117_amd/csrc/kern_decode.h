@@ -15,11 +15,15 @@
 //    controls completely;
 //  - every wave owns a ring of NSLOT (slice + activation tile) slots in LDS: the
 //    copies of the next NSLOT-1 blocks are in flight while one block is
-//    multiplied; no other wave touches a wave's ring, so there is no barrier;
+//    multiplied; no other wave touches a wave's ring, so the loop has no barrier;
 //  - 16-byte chunks are XOR-swizzled inside their row on the global-address side
 //    of the copy, so that the operand-fragment reads do not pile onto one bank;
 //  - the products run on v_mfma_f32_16x16x32_bf16, 16 tokens per instruction;
-//  - the four partial sums meet in LDS; wave 0 applies the epilogue.
+//  - the four partial sums meet in LDS (in a buffer laid over the rings, behind the kernel's only
+//    barrier); wave 0 applies the epilogue;
+//  - the single-launch MLP's variants at b = 128 and for 64-token units load the weight fragments
+//    straight into registers instead (DecCfg::WREG): there the number of resident workgroups matters
+//    more than the shape of the requests.
 // Same arithmetic as the tile kernels: bf16 products, fp32 accumulation,
 // activation on the fp32 sums, one rounding to bf16 where the output is bf16.
 #pragma once
@@ -247,7 +251,8 @@ struct DecCfg {
   static constexpr bool XONE = !XSMALL && NTT == 2 && B == 128;
   // Two slots per wave: one block being multiplied, one in flight.  Deeper rings were measured and lose: what
   // hides the latency of the copies here is the number of resident workgroups (three per CU at b = 128 with
-  // the small activation tile, four at b = 64), and every extra slot costs residents.
+  // the small activation tile, four at b = 64, before the partial sums were laid over the ring; now one more
+  // each), and every extra slot costs residents.
   // One-byte weights halve a slice: where a slot stays within 4 KiB the ring is four slots deep, so that the
   // bytes in flight per wave - what the HBM bandwidth reached follows - are those of the bf16 form.
   static constexpr int NSLOT = (W8 && SLOT <= 4096) ? 4 : 2;
