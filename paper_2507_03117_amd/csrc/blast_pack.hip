@@ -420,11 +420,12 @@ __global__ __launch_bounds__(256) void k_fill_csc(const uint8_t* __restrict__ ma
 // Where one chunk plan goes.
 struct PlanOut {
   int chunk;        // blocks per chunk, at most
-  int* hdr;         // {n_chunks, max_row_blocks, chunk, 0}
+  int* hdr;         // {n_chunks, max_row_blocks, chunk, chunks of the rows that have several}
   int* chunk_row;
   int* chunk_kb;
   int* chunk_ke;
   int64_t cap;
+  int* row_slot;    // may be null: per row, its rank if it has several chunks, else -1
 };
 
 // Single workgroup: cut the block rows, in schedule order, into chunks of at most `chunk` blocks, once per
@@ -433,7 +434,7 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
                                                      int nbr, PlanOut narrow, PlanOut wide,
                                                      int* __restrict__ max_row_out) {
   __shared__ int wave_tot[16];
-  __shared__ int s_running, s_heavy;
+  __shared__ int s_running, s_heavy, s_split;
   for (int which = 0; which < 2; ++which) {
     const PlanOut o = which ? wide : narrow;
     const int chunk = o.chunk;
@@ -441,6 +442,7 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
     if (threadIdx.x == 0) {
       s_running = 0;
       s_heavy = 0;
+      s_split = 0;
     }
     __syncthreads();
     for (int base = 0; base < nbr; base += blockDim.x) {
@@ -453,6 +455,8 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
         nch = (ke - kb + chunk - 1) / chunk;
         if (nch < 1) nch = 1;
         atomicMax(&s_heavy, ke - kb);
+        if (nch > 1) atomicAdd(&s_split, nch);
+        if (o.row_slot) o.row_slot[r] = nch > 1 ? rank : -1;
       }
       int total;
       const int first = s_running + block_exscan(nch, wave_tot, total);
@@ -474,7 +478,7 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
       o.hdr[1] = s_heavy;
       if (which == 0) *max_row_out = s_heavy;  // next to nnz, so that one copy brings both to the host
       o.hdr[2] = chunk;
-      o.hdr[3] = 0;
+      o.hdr[3] = s_split;
     }
   }
 }
@@ -482,9 +486,11 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
 // Both plans of a matrix, placed in its aux buffer.
 inline void plan_outputs(char* ab, const blast::AuxLayout& A, PlanOut& narrow, PlanOut& wide) {
   narrow = PlanOut{blast::kChunkBlocks, reinterpret_cast<int*>(ab + A.hdr_off), reinterpret_cast<int*>(ab + A.chunk_row_off),
-                   reinterpret_cast<int*>(ab + A.chunk_kb_off), reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap};
+                   reinterpret_cast<int*>(ab + A.chunk_kb_off), reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap,
+                   reinterpret_cast<int*>(ab + A.row_slot_off)};
   wide = PlanOut{blast::kWideChunkBlocks, reinterpret_cast<int*>(ab + A.whdr_off), reinterpret_cast<int*>(ab + A.wchunk_row_off),
-                 reinterpret_cast<int*>(ab + A.wchunk_kb_off), reinterpret_cast<int*>(ab + A.wchunk_ke_off), A.wchunk_cap};
+                 reinterpret_cast<int*>(ab + A.wchunk_kb_off), reinterpret_cast<int*>(ab + A.wchunk_ke_off), A.wchunk_cap,
+                 nullptr};
 }
 
 // One workgroup per stored block of the transposed matrix: block e of the output is the transpose of

@@ -81,7 +81,7 @@ struct ZeroJob {
   int64_t syt = 0, syi = 0;
   int T = 0;
   int64_t max_chunks = 0;
-  bool wide = false;  // the plan is the streaming kernels' (chunks of kWideChunkBlocks), else the decode kernels'
+  bool wide = false;  // the plan is the one of kWideChunkBlocks (its cut rows are a subset of the other plan's)
   bool done = false;
 };
 
@@ -99,8 +99,21 @@ struct ChunkPlan {
   const int* w_chunk_ke = nullptr;
   int64_t w_max_chunks = 0;
   int max_row_blocks = 0;  // stored blocks of the fullest block row
-  ZeroJob* zero_job = nullptr;  // a side job this launch may take along (decode launches only)
-  bool pre_zeroed = false;      // the shared rows of the output have been cleared by an earlier launch
+  ZeroJob* zero_job = nullptr;  // a side job this launch may take along (decode launches: the first plan's only)
+  bool pre_zeroed = false;      // the shared rows of the output have been cleared by an earlier launch ...
+  bool zeroed_wide = false;     // ... those of the wide plan only (a subset of the other plan's)
+  bool stream_narrow = false;   // the streaming kernels take the chunks of kChunkBlocks too (few token tiles)
+  // long rows of a gated product cut into chunks (see StreamArgs)
+  const int* slot0 = nullptr;
+  const int* slot1 = nullptr;
+  float* SA = nullptr;
+  float* SB = nullptr;
+  int64_t ldA = 0, ldB = 0;
+  const int* hdr1 = nullptr;  // the second matrix' plan (the first one's is hdr, chunk_*)
+  const int* chunk_row1 = nullptr;
+  const int* chunk_kb1 = nullptr;
+  const int* chunk_ke1 = nullptr;
+  int64_t max_chunks1 = 0;
 };
 
 // An XCD's L2 (4 MB) keeps the slab of activations of the token tiles it works on only while that slab is a
@@ -110,11 +123,11 @@ struct ChunkPlan {
 // and 2.2 GB per launch cross the fabric with token tiles pinned, at the 6 - 7.5 TB/s it delivers).
 constexpr int64_t kRowPinnedSlabBytes = (int64_t)6 << 20;
 
-template <int B, bool DUAL, int TW, bool CHUNK, int NW = 4>
+template <int B, bool DUAL, int TW, bool CHUNK, int NW = 4, bool LONG = false>
 int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipStream_t stream) {
   using C = StreamCfg<B, TW, NW>;
   a.ntt = (a.T + C::TT - 1) / C::TT;
-  const int64_t n_rows = CHUNK ? plan.max_chunks : (int64_t)a.nbr;
+  const int64_t n_rows = CHUNK ? plan.max_chunks : (int64_t)a.nbr + (LONG ? plan.max_chunks + plan.max_chunks1 : 0);
   const int64_t n_items = (int64_t)a.ntt * n_rows;
   if (n_items <= 0) return BLAST_OK;
   if (n_items > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
@@ -130,10 +143,22 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
   int row_pinned = 0;
   const int64_t slab = ((int64_t)a.ntt + 7) / 8 * C::TT * k_features * 2;
   if (B == 128 && slab > kRowPinnedSlabBytes && grid == resident && a.ntt <= grid / 8 && (grid / 8) % a.ntt == 0 &&
-      n_rows / 8 + 1 <= 64 * ((grid / 8) / a.ntt))
+      n_rows / 8 + 1 <= 64 * ((grid / 8) / a.ntt) && !LONG)
     row_pinned = 1;
   StreamArgs sa{a, (int)n_items, shift, row_pinned, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
-  if (!CHUNK && plan.zero_job && plan.zero_job->hdr && plan.zero_job->wide && !plan.zero_job->done) {
+  if constexpr (LONG) {
+    sa.hdr1 = plan.hdr1;
+    sa.chunk_row1 = plan.chunk_row1;
+    sa.chunk_kb1 = plan.chunk_kb1;
+    sa.chunk_ke1 = plan.chunk_ke1;
+    sa.slot0 = plan.slot0;
+    sa.slot1 = plan.slot1;
+    sa.SA = plan.SA;
+    sa.SB = plan.SB;
+    sa.ldA = plan.ldA;
+    sa.ldB = plan.ldB;
+  }
+  if (!CHUNK && plan.zero_job && plan.zero_job->hdr && !plan.zero_job->done) {
     // a later chunked product's rows are cleared by this launch on the side
     ZeroJob& z = *plan.zero_job;
     sa.z_hdr = z.hdr;
@@ -146,11 +171,15 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
     sa.z_T = z.T;
     z.done = true;
   }
-  if (CHUNK && !plan.pre_zeroed) {
+  if constexpr (LONG) {
+    const int64_t most = plan.max_chunks > plan.max_chunks1 ? plan.max_chunks : plan.max_chunks1;
+    k_long_zero<B><<<dim3((unsigned)most, (unsigned)((a.T + 63) / 64), 2), dim3(256), 0, stream>>>(sa);
+    BLAST_LAUNCH_CHECK("k_long_zero");
+  } else if (CHUNK && !plan.pre_zeroed) {
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
   }
-  if constexpr (!DUAL && !CHUNK) {
+  if constexpr (!DUAL && !CHUNK && !LONG) {
     if (a.act >= 0) {  // single matrix with an activation on the output
       static blast::DeviceFlags lds_set_post;
       if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, false, TW, false, true, NW>),
@@ -162,11 +191,16 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
     }
   }
   static blast::DeviceFlags lds_set;
-  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK, false, NW>),
+  if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_stream<B, DUAL, TW, CHUNK, false, NW, LONG>),
                                 C::LDS_BYTES, lds_set))
     return rc;
-  k_spmm_stream<B, DUAL, TW, CHUNK, false, NW><<<dim3((unsigned)grid), dim3(64 * NW), C::LDS_BYTES, stream>>>(sa);
+  k_spmm_stream<B, DUAL, TW, CHUNK, false, NW, LONG><<<dim3((unsigned)grid), dim3(64 * NW), C::LDS_BYTES, stream>>>(sa);
   BLAST_LAUNCH_CHECK("k_spmm_stream");
+  if constexpr (LONG) {
+    k_long_finish<B><<<dim3((unsigned)a.nbr, (unsigned)((a.T + kLongFinishTokens - 1) / kLongFinishTokens)),
+                       dim3(256), 0, stream>>>(sa);
+    BLAST_LAUNCH_CHECK("k_long_finish");
+  }
   return BLAST_OK;
 }
 
@@ -178,12 +212,14 @@ int launch_stream_c(const TileArgs& a, const ChunkPlan& plan, int64_t k_features
     // tokens, 256 wide tiles: 24.9 against 28.2 us)
     const int64_t n_rows = CHUNK ? plan.max_chunks : (int64_t)a.nbr;
     const int64_t wide_items = (int64_t)((a.T + 255) / 256) * n_rows;
-    if (wide_items >= 2 * (int64_t)cu_count()) return launch_stream_tw<B, DUAL, 4, CHUNK, 8>(a, plan, k_features, stream);
+    if (wide_items >= 2 * (int64_t)cu_count())
+      return launch_stream_tw<B, DUAL, 4, CHUNK, 8>(a, plan, k_features, stream);
     return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, k_features, stream);
   } else if constexpr (B == 64) {
     // 128-token tiles when 256-token tiles would leave workgroup slots empty
     const int64_t wide_items = (int64_t)((a.T + 255) / 256) * a.nbr;
-    if (wide_items < (int64_t)cu_count() * 2) return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, k_features, stream);
+    if (wide_items < (int64_t)cu_count() * 2)
+      return launch_stream_tw<B, DUAL, 2, CHUNK>(a, plan, k_features, stream);
     return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, k_features, stream);
   } else {
     return launch_stream_tw<B, DUAL, 4, CHUNK>(a, plan, k_features, stream);
@@ -194,6 +230,17 @@ template <int B, bool DUAL>
 int launch_stream(const TileArgs& a, const ChunkPlan& plan, int64_t k_features, hipStream_t stream) {
   if constexpr (!DUAL) {
     // rows cut into chunks accumulate with fp32 atomics: only for fp32 output without an activation
+    if (plan.hdr && plan.stream_narrow && !a.y_bf16 && a.act < 0) {
+      ChunkPlan narrow{};
+      narrow.hdr = plan.hdr;
+      narrow.chunk_row = plan.chunk_row;
+      narrow.chunk_kb = plan.chunk_kb;
+      narrow.chunk_ke = plan.chunk_ke;
+      narrow.max_chunks = plan.max_chunks;
+      narrow.max_row_blocks = plan.max_row_blocks;
+      narrow.pre_zeroed = plan.pre_zeroed && !plan.zeroed_wide;
+      return launch_stream_c<B, false, true>(a, narrow, k_features, stream);
+    }
     if (plan.w_hdr && !a.y_bf16 && a.act < 0) {
       ChunkPlan wide{};
       wide.hdr = plan.w_hdr;
@@ -202,7 +249,7 @@ int launch_stream(const TileArgs& a, const ChunkPlan& plan, int64_t k_features, 
       wide.chunk_ke = plan.w_chunk_ke;
       wide.max_chunks = plan.w_max_chunks;
       wide.max_row_blocks = plan.max_row_blocks;
-      wide.pre_zeroed = plan.pre_zeroed;
+      wide.pre_zeroed = plan.pre_zeroed;  // either plan's rows cleared covers these
       return launch_stream_c<B, false, true>(a, wide, k_features, stream);
     }
   }
@@ -269,7 +316,7 @@ int launch_decode_ntt(const TileArgs& a, const ChunkPlan& plan, hipStream_t stre
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_decode<B, DUAL, NTT, CHUNK, XSMALL>), C::LDS_BYTES,
                                 lds_set))
     return rc;
-  if (CHUNK && !plan.pre_zeroed) {
+  if (CHUNK && !(plan.pre_zeroed && !plan.zeroed_wide)) {
     StreamArgs sa{a, 0, -1, 0, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
@@ -480,6 +527,11 @@ ChunkPlan plan_of(const blast_bsr_view* v, int64_t T) {
     p.w_max_chunks = nbr + v->nnz / blast::kWideChunkBlocks;
   }
   p.max_row_blocks = v->max_row_blocks;
+  {
+    // blocks per CU with 256-token tiles: below half a wide chunk, wide chunks are too coarse to balance
+    const double per_cu = (double)v->nnz * (double)tiles / cu_count();
+    p.stream_narrow = per_cu < blast::kWideChunkBlocks / 2;
+  }
   return p;
 }
 
@@ -524,6 +576,54 @@ size_t mlp_slot_bytes(int64_t I) { return blast::align_up((size_t)(I / 16) * 8, 
 size_t mlp_workspace_bytes(int64_t I, int64_t T) { return mlp_h_bytes(I, T) + mlp_slot_bytes(I) + kCtlBytes; }
 constexpr size_t kCtlStatusOffset = 16;  // byte offset of the status word inside the control block
 
+// ---- long rows of a gated product ---------------------------------------------------------------------
+// The gated product cannot cut a block row (the activation needs complete sums), so at a few hundred tokens
+// - one to four token tiles per row - the workgroup that walks the fullest joint row alone sets the time of
+// the launch when the row lengths are skewed.  There the rows that the first chunk plan of either matrix cuts
+// (more than kChunkBlocks stored blocks) are taken in chunks after all: the launch sums each side of such a
+// row into fp32 scratch (chunks with atomics), and a small launch after it applies the activation and writes
+// those rows of H (see StreamArgs).  Measured on the 405B-class layer with the Zipf mask (fullest rows: all
+// 128 blocks of gate or of up, 133 joint), gate/up product in microseconds without / with: 128 tokens 160 / 88,
+// 256: 199 / 123, 512: 275 / 217, 768: 323 / 350, 1024: 299 / 417.  With the rows dealt evenly the launch moves
+// 64 KB per block and 128-token tile at the 6.6 TB/s its copies get, which is what is left at 256 tokens
+// (103 us of the 123; 7 us each for clearing and finishing).
+constexpr int kLongMinTokens = 64;  // up to here the decode kernels are at least as fast (81 against 88 us at 64)
+
+// upper bound of the number of rows with more than kChunkBlocks stored blocks (0: none, or no plan at hand)
+int64_t long_slots(const blast_bsr_view* v) {
+  if (!v->aux || v->max_row_blocks <= blast::kChunkBlocks) return 0;
+  const int64_t nbr = v->rows / v->b, by_blocks = v->nnz / (blast::kChunkBlocks + 1);
+  return by_blocks < nbr ? by_blocks : nbr;
+}
+
+// gate sums and up sums, [T][slots * b] fp32 each, of the rows with a slot in this matrix
+size_t long_scratch_bytes(const blast_bsr_view* v, int64_t T) {
+  return blast::align_up(2 * (size_t)long_slots(v) * (size_t)v->b * (size_t)T * 4, 256);
+}
+
+// Where it pays (host-side estimate from the counts the views carry).
+bool long_rows_pay(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, int64_t T) {
+  if (!Wup || Wgate->b < 32) return false;
+  if (long_slots(Wgate) + long_slots(Wup) == 0) return false;
+  if (T <= kLongMinTokens) return false;
+  const int64_t tiles = (T + 127) / 128;
+  const double avg = (double)(Wgate->nnz + Wup->nnz) * (double)tiles / (2.0 * cu_count());
+  const int64_t fullest = Wgate->max_row_blocks > Wup->max_row_blocks ? Wgate->max_row_blocks : Wup->max_row_blocks;
+  return (double)fullest > 2.0 * avg + 2.0 * blast::kChunkBlocks;
+}
+
+// upper bound of the number of chunks of the cut rows: sum of ceil(len / chunk) over those rows, at most
+int64_t long_max_chunks(const blast_bsr_view* v) {
+  const int64_t slots = long_slots(v);
+  return slots ? v->nnz / blast::kChunkBlocks + slots : 0;
+}
+
+// scratch of the long-row path behind the MLP workspace proper (0 where the path is not taken)
+size_t mlp_long_bytes(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, int64_t T) {
+  if (!Wup || !long_rows_pay(Wgate, Wup, T)) return 0;
+  return long_scratch_bytes(Wgate, T) + long_scratch_bytes(Wup, T);
+}
+
 // Knobs of the hand-over inside the single-launch form; the defaults are what every ordinary call uses.
 struct HandoverKnobs {
   int max_spins = kDecMaxSpins;
@@ -538,7 +638,7 @@ extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const bla
   if (int rc = check_view(Wup)) return rc;
   if (int rc = check_view(Wdown)) return rc;
   if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
-  *ws_bytes = mlp_workspace_bytes(Wgate->rows, T);
+  *ws_bytes = mlp_workspace_bytes(Wgate->rows, T) + mlp_long_bytes(Wgate, Wup, T);
   return BLAST_OK;
 }
 
@@ -571,10 +671,59 @@ int check_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blas
   return BLAST_OK;
 }
 
+struct LongScratch {
+  float* SA = nullptr;  // indexed by the slots of the first matrix
+  float* SB = nullptr;  // by those of the second
+};
+
+template <int B>
+int enqueue_gated_long(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const TileArgs& g,
+                       const LongScratch& ls, ZeroJob* side_job, hipStream_t stream) {
+  ChunkPlan p{};
+  p.zero_job = side_job;
+  const blast_bsr_view* mats[2] = {Wgate, Wup};
+  for (int m = 0; m < 2; ++m) {
+    const blast_bsr_view* v = mats[m];
+    const int64_t slots = long_slots(v);
+    if (slots == 0) continue;
+    const blast::AuxLayout L = blast::aux_layout(v->rows / v->b, v->cols / v->b, v->nnz);
+    const char* ab = static_cast<const char*>(v->aux);
+    const int* row_slot = reinterpret_cast<const int*>(ab + L.row_slot_off);
+    const int* hdr = reinterpret_cast<const int*>(ab + L.hdr_off) + 3;  // the chunks of the cut rows head the plan
+    const int* chunk_row = reinterpret_cast<const int*>(ab + L.chunk_row_off);
+    const int* chunk_kb = reinterpret_cast<const int*>(ab + L.chunk_kb_off);
+    const int* chunk_ke = reinterpret_cast<const int*>(ab + L.chunk_ke_off);
+    const int64_t most = long_max_chunks(v);
+    if (m == 0) {
+      p.hdr = hdr;
+      p.chunk_row = chunk_row;
+      p.chunk_kb = chunk_kb;
+      p.chunk_ke = chunk_ke;
+      p.max_chunks = most;
+      p.slot0 = row_slot;
+      p.SA = ls.SA;
+      p.ldA = slots * B;
+    } else {
+      p.hdr1 = hdr;
+      p.chunk_row1 = chunk_row;
+      p.chunk_kb1 = chunk_kb;
+      p.chunk_ke1 = chunk_ke;
+      p.max_chunks1 = most;
+      p.slot1 = row_slot;
+      p.SB = ls.SB;
+      p.ldB = slots * B;
+    }
+  }
+  // 128-token tiles: more and shorter items
+  if constexpr (B >= 64) return launch_stream_tw<B, true, 2, false, 4, true>(g, p, g.kdim, stream);
+  return launch_stream_tw<B, true, 4, false, 4, true>(g, p, g.kdim, stream);
+}
+
 // H = act(Wgate X) (.) (Wup X), or H = act(Wgate X) when Wup is null; bf16, strides given by (h_layout, ldh).
+// `ls` (may be null): scratch for the long rows, long_scratch_bytes() per matrix.
 int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const uint16_t* X, int64_t ldx,
                   int32_t x_layout, int64_t T, int32_t act, uint16_t* H, int64_t ldh, int32_t h_layout,
-                  hipStream_t stream, ZeroJob* side_job = nullptr) {
+                  hipStream_t stream, ZeroJob* side_job = nullptr, const LongScratch* ls = nullptr) {
   ChunkPlan side{};
   side.zero_job = side_job;
   // upper bound of the fullest joint row (exact when the same row is the fullest of both matrices)
@@ -590,6 +739,14 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
   g.kdim = Wgate->cols;
   g.act = act;
   if (!Wup) return dispatch_tile<false>(Wgate->b, g, Wgate->nnz, stream, side);
+  if (ls && g.x_vec && T > 0 && (int64_t)T * g.sxt * 2 < ((int64_t)1 << 32) && long_rows_pay(Wgate, Wup, T)) {
+    switch (Wgate->b) {
+      case 32: return enqueue_gated_long<32>(Wgate, Wup, g, *ls, side_job, stream);
+      case 64: return enqueue_gated_long<64>(Wgate, Wup, g, *ls, side_job, stream);
+      case 128: return enqueue_gated_long<128>(Wgate, Wup, g, *ls, side_job, stream);
+      default: break;
+    }
+  }
   return dispatch_tile<true>(Wgate->b, g, Wgate->nnz + Wup->nnz, stream, side);
 }
 
@@ -741,9 +898,10 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
   // At decode token counts the rows of Y that the chunked second product accumulates into are cleared on
   // the side by the first product's launch (extra workgroups of the same kernel) instead of by a launch
   // of their own between the two products.
-  // Beyond them the streaming kernels do the same with the rows of their own (64-block) plan.
+  // Beyond them the streaming kernels do the same, with the rows of the plan that the second product will take
+  // (the first plan's rows include the other's, so clearing those serves either).
   ZeroJob zj{};
-  if (dplan.hdr && y_dtype == BLAST_F32 && T <= kDecodeMaxTokens && I > 0) {
+  if (dplan.hdr && y_dtype == BLAST_F32 && (T <= kDecodeMaxTokens || dplan.stream_narrow) && I > 0) {
     zj.hdr = dplan.hdr;
     zj.chunk_row = dplan.chunk_row;
     zj.chunk_kb = dplan.chunk_kb;
@@ -763,12 +921,22 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
     zj.T = (int)T;
   }
   if (I > 0) {
+    // room behind the workspace proper (blast_sparse_mlp_workspace asks for it where it pays): the long rows
+    // of the gated product are cut into chunks
+    LongScratch ls{};
+    const size_t extra = Wup ? mlp_long_bytes(Wgate, Wup, T) : 0;
+    const bool have_ls = extra > 0 && ws_bytes >= need + extra;
+    if (have_ls) {
+      ls.SA = reinterpret_cast<float*>(static_cast<char*>(ws) + need);
+      ls.SB = reinterpret_cast<float*>(static_cast<char*>(ws) + need + long_scratch_bytes(Wgate, T));
+    }
     if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream,
-                               zj.hdr ? &zj : nullptr))
+                               zj.hdr ? &zj : nullptr, have_ls ? &ls : nullptr))
       return rc;
   }
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));
   dplan.pre_zeroed = zj.done;
+  dplan.zeroed_wide = zj.wide;
   if (int rc = dispatch_tile<false>(b, d, Wdown->nnz, stream, dplan)) return rc;
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[2]), stream));
   return BLAST_OK;

@@ -99,7 +99,50 @@ struct StreamArgs {
   float* z_Y;
   int64_t z_syt, z_syi;
   int z_T;
+  // Long rows of a gated product (LONG instances).  A block row that the first chunk plan of a matrix cuts
+  // into several chunks has a slot in that matrix (the packer's row_slot, else -1); a row with a slot in
+  // either matrix is "deferred": the launch leaves its two complete fp32 sums (gate side, up side) in scratch
+  // and a small launch after it applies the activation and writes H.  The items of the launch are then
+  //   - the chunks of the first matrix' cut rows (the head of its plan: hdr points at their number),
+  //   - those of the second matrix (hdr1, chunk_*1),
+  //   - the block rows in schedule order: an ordinary row as ever; of a deferred row only the side that is
+  //     not cut, its sums stored to scratch.
+  // Chunks add into scratch cleared before the launch.  Scratch: SA for the rows with a slot in the first
+  // matrix, indexed by that slot, [2][T][ldA] fp32 (gate sums, then up sums), columns slot * B ...; SB for the
+  // rows with a slot in the second matrix only, indexed by that slot, [2][T][ldB].
+  const int* slot0;
+  const int* slot1;
+  float* SA;
+  float* SB;
+  int64_t ldA, ldB;
+  const int* hdr1;
+  const int* chunk_row1;
+  const int* chunk_kb1;
+  const int* chunk_ke1;
 };
+
+// number of chunks of a matrix' cut rows (hdr points at that count, or is null)
+__device__ __forceinline__ int long_chunks(const int* hdr) { return hdr ? ld_idx(hdr, 0) : 0; }
+
+// What a LONG item that is not an ordinary row does with its sums (ItemTable::c1; bit 31 of r marks such items
+// and the rest of r is the slot).
+constexpr int kLongSecond = 1;  // the blocks are the second matrix'
+constexpr int kLongUp = 2;      // destination: the up sums (else the gate sums)
+constexpr int kLongB = 4;       // destination in SB (else SA)
+constexpr int kLongAdd = 8;     // added atomically (a chunk), else stored
+constexpr int kLongNone = 16;   // nothing to do: both sides of the row are cut
+
+// where the sums of block row `row` of the second matrix go
+__device__ __forceinline__ void long_up_dest(const StreamArgs& sa, int row, int& slot, int& code) {
+  const int s0 = sa.slot0 ? sa.slot0[row] : -1;
+  if (s0 >= 0) {
+    slot = s0;
+    code = kLongSecond | kLongUp;
+  } else {
+    slot = sa.slot1[row];
+    code = kLongSecond | kLongUp | kLongB;
+  }
+}
 
 // item -> (rank in the row schedule, token tile) without an integer division in the common case
 __device__ __forceinline__ void split_item(int it, int ntt, int shift, int& rank, int& tile) {
@@ -139,11 +182,58 @@ struct ItemTable {
 #define BLAST_LANE(v, j) __builtin_amdgcn_readlane((v), (j))
 
 // Fills the descriptor of one item from its rank in the schedule (row_order, or the chunk plan) and its token tile.
-template <bool DUAL, bool CHUNK>
+template <bool DUAL, bool CHUNK, bool LONG>
 __device__ __forceinline__ void describe_item(const StreamArgs& sa, int rank, int tile, ItemTable& t) {
   const TileArgs& a = sa.t;
   t.tile = tile;
-  if (CHUNK) {
+  if constexpr (LONG) {
+    const int n0 = long_chunks(sa.hdr), n1 = long_chunks(sa.hdr1);
+    int slot = 0, code = 0;
+    bool special = true;
+    t.k1 = t.e1 = 0;
+    if (rank < n0) {  // a chunk of the first matrix
+      slot = sa.slot0[sa.chunk_row[rank] & 0x7FFFFFFF];
+      code = kLongAdd;
+      t.k0 = sa.chunk_kb[rank];
+      t.e0 = sa.chunk_ke[rank];
+    } else if (rank < n0 + n1) {  // of the second
+      const int ci = rank - n0;
+      long_up_dest(sa, sa.chunk_row1[ci] & 0x7FFFFFFF, slot, code);
+      code |= kLongAdd;
+      t.k0 = sa.chunk_kb1[ci];
+      t.e0 = sa.chunk_ke1[ci];
+    } else {
+      const int rr = rank - n0 - n1;
+      const int r = a.row_order ? a.row_order[rr] : rr;
+      const int s0 = sa.slot0 ? sa.slot0[r] : -1, s1 = sa.slot1 ? sa.slot1[r] : -1;
+      if (s0 < 0 && s1 < 0) {  // an ordinary row
+        special = false;
+        t.r = r;
+        t.k0 = a.m0.row_ptr[r];
+        t.e0 = a.m0.row_ptr[r + 1];
+        t.k1 = a.m1.row_ptr[r];
+        t.e1 = a.m1.row_ptr[r + 1];
+      } else if (s0 >= 0 && s1 >= 0) {
+        code = kLongNone;
+        t.k0 = t.e0 = 0;
+      } else if (s0 >= 0) {  // the up side is whole
+        long_up_dest(sa, r, slot, code);
+        t.k0 = a.m1.row_ptr[r];
+        t.e0 = a.m1.row_ptr[r + 1];
+      } else {  // the gate side is whole
+        slot = s1;
+        code = kLongB;
+        t.k0 = a.m0.row_ptr[r];
+        t.e0 = a.m0.row_ptr[r + 1];
+      }
+    }
+    if (special) {
+      t.r = slot | (int)0x80000000u;
+      t.c1 = code;
+      if (t.k0 < t.e0) t.c0 = ((code & kLongSecond) ? a.m1 : a.m0).col_idx[t.k0];
+      return;
+    }
+  } else if (CHUNK) {
     t.r = sa.chunk_row[rank];
     t.k0 = sa.chunk_kb[rank];
     t.e0 = sa.chunk_ke[rank];
@@ -160,7 +250,7 @@ __device__ __forceinline__ void describe_item(const StreamArgs& sa, int rank, in
   if (DUAL && t.k1 < t.e1) t.c1 = a.m1.col_idx[t.k1];
 }
 
-template <bool DUAL, bool CHUNK>
+template <bool DUAL, bool CHUNK, bool LONG>
 __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n_items, int w, int G, int lane) {
   const TileArgs& a = sa.t;
   ItemTable t{};
@@ -169,7 +259,7 @@ __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n
     const bool ok = it < n_items;
     int rank = 0, tile = 0;
     if (ok) split_item(it, a.ntt, sa.ntt_shift, rank, tile);
-    if (ok) describe_item<DUAL, CHUNK>(sa, rank, tile, t);
+    if (ok) describe_item<DUAL, CHUNK, LONG>(sa, rank, tile, t);
     // items of a workgroup grow with the round, so the valid rounds are a prefix
     t.n_rounds = __builtin_popcountll(__ballot(ok));
     return t;
@@ -228,7 +318,7 @@ __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n
     // positions grow with the round except across a mirrored boundary, where validity can only end:
     // the valid rounds are a prefix
   }
-  if (mine >= 0) describe_item<DUAL, CHUNK>(sa, rank_of(mine), tile, t);
+  if (mine >= 0) describe_item<DUAL, CHUNK, LONG>(sa, rank_of(mine), tile, t);
   t.n_rounds = n_mine;
   return t;
 }
@@ -285,13 +375,18 @@ __device__ __forceinline__ void stream_zero_side(const StreamArgs& sa, int w, in
 // (block row, token tile); a row made of several chunks adds its partial sums into a zeroed fp32 output.
 // POST: a single-matrix product whose result goes through the activation a.act before it is stored
 // (the first half of a two-matrix MLP).
-template <int B, bool DUAL, int TW, bool CHUNK, bool POST = false, int NW = 4>
+// LONG: the gated product with its long rows cut into chunks and finished by a later launch, see StreamArgs
+// (never with the row-pinned schedule).
+template <int B, bool DUAL, int TW, bool CHUNK, bool POST = false, int NW = 4, bool LONG = false>
 __global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) void k_spmm_stream(const StreamArgs sa) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
   static_assert(!POST || (!DUAL && !CHUNK), "an activation on the output needs complete sums of a single matrix");
+  static_assert(!LONG || (DUAL && !CHUNK), "long rows are a matter of the gated product");
   using C = StreamCfg<B, TW, NW>;
   const TileArgs& a = sa.t;
-  const int n_items = CHUNK ? ld_idx(sa.hdr, 0) * a.ntt : sa.n_items;
+  const int n_items = LONG    ? (long_chunks(sa.hdr) + long_chunks(sa.hdr1) + a.nbr) * a.ntt
+                      : CHUNK ? ld_idx(sa.hdr, 0) * a.ntt
+                              : sa.n_items;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int w = blockIdx.x, G = gridDim.x;
@@ -337,7 +432,7 @@ __global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) vo
     }
   };
   if (sa.z_hdr) stream_zero_side<B, 64 * NW>(sa, w, G, lane);
-  const ItemTable tab = load_item_table<DUAL, CHUNK>(sa, n_items, w, G, lane);
+  const ItemTable tab = load_item_table<DUAL, CHUNK, LONG>(sa, n_items, w, G, lane);
 
   Loader ld;
   ld.round = -1;
@@ -373,6 +468,9 @@ __global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) vo
         e = BLAST_LANE(tab.e0, ld.round);
         ld.c = BLAST_LANE(tab.c0, ld.round);
         m = &a.m0;
+        if constexpr (LONG) {
+          if (BLAST_LANE(tab.r, ld.round) < 0 && (BLAST_LANE(tab.c1, ld.round) & kLongSecond)) m = &a.m1;
+        }
       }
       if (k < e) {
         ld.rem = e - k;
@@ -574,6 +672,33 @@ __global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) vo
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc0[mi][ni][j] = 0.0f;
     for (int s = 0; s < n0; ++s) do_step(acc0);
+    if constexpr (LONG) {
+      if (rr < 0) {  // a chunk, or the whole side of a deferred row: the sums go to scratch as they are
+        const int code = BLAST_LANE(tab.c1, round);
+        if (code & kLongNone) continue;
+        const int64_t ld = (code & kLongB) ? sa.ldB : sa.ldA;
+        float* S = ((code & kLongB) ? sa.SB : sa.SA) + ((code & kLongUp) ? (int64_t)a.T * ld : 0);
+        const bool add = (code & kLongAdd) != 0;
+        const int tokb = t0 + tw * 64 + 4 * lh;
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni) {
+          float* p0 = S + (int64_t)tokb * ld + (int64_t)(rr & 0x7FFFFFFF) * B + rw * C::WT_ROW + ni * 32 + l32;
+#pragma unroll
+          for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const int dt = mi * 32 + 8 * (j / 4) + (j % 4);
+              if (tokb + dt < a.T) {
+                if (add)
+                  atomicAdd(p0 + (int64_t)dt * ld, acc0[mi][ni][j]);
+                else
+                  p0[(int64_t)dt * ld] = acc0[mi][ni][j];
+              }
+            }
+        }
+        continue;
+      }
+    }
     if (DUAL) {
       f32x16 acc1[C::MI][C::NI];
 #pragma unroll
@@ -712,6 +837,65 @@ __global__ __launch_bounds__(256) void k_zero_shared_rows(const StreamArgs sa) {
   for (int e = threadIdx.x; e < 64 * B; e += 256) {
     const int t = t0 + e / B, i = e % B;
     if (t < a.T) Y[(int64_t)t * a.syt + ((int64_t)r * B + i) * a.syi] = 0.0f;
+  }
+}
+
+// Before a LONG launch: zeroes the scratch that its chunks add into.
+// Grid: x = upper bound of the number of chunks of a matrix' cut rows, y = slabs of 64 tokens, z = matrix.
+template <int B>
+__global__ __launch_bounds__(256) void k_long_zero(const StreamArgs sa) {
+  const TileArgs& a = sa.t;
+  const bool second = blockIdx.z != 0;
+  const int ci = blockIdx.x;
+  if (ci >= long_chunks(second ? sa.hdr1 : sa.hdr)) return;
+  const int r = ld_idx(second ? sa.chunk_row1 : sa.chunk_row, ci) & 0x7FFFFFFF;
+  // only the first chunk of the row zeroes
+  if (ld_idx(second ? sa.chunk_kb1 : sa.chunk_kb, ci) != ld_idx(second ? a.m1.row_ptr : a.m0.row_ptr, r)) return;
+  int slot, code = 0;
+  if (second)
+    long_up_dest(sa, r, slot, code);
+  else
+    slot = sa.slot0[r];
+  const int64_t ld = (code & kLongB) ? sa.ldB : sa.ldA;
+  float* S = ((code & kLongB) ? sa.SB : sa.SA) + ((code & kLongUp) ? (int64_t)a.T * ld : 0);
+  const int t0 = blockIdx.y * 64;
+  for (int e = threadIdx.x; e < 64 * B; e += 256) {
+    const int t = t0 + e / B, i = e % B;
+    if (t < a.T) S[(int64_t)t * ld + (int64_t)slot * B + i] = 0.0f;
+  }
+}
+
+// After a LONG launch: H = act(gate sums) * (up sums) for the deferred rows.
+// Grid: x = block rows, y = slabs of kLongFinishTokens tokens.
+constexpr int kLongFinishTokens = 16;
+template <int B>
+__global__ __launch_bounds__(256) void k_long_finish(const StreamArgs sa) {
+  const TileArgs& a = sa.t;
+  const int r = blockIdx.x;
+  const int s0 = sa.slot0 ? ld_idx(sa.slot0, r) : -1, s1 = sa.slot1 ? ld_idx(sa.slot1, r) : -1;
+  if (s0 < 0 && s1 < 0) return;
+  const int64_t ld = s0 >= 0 ? sa.ldA : sa.ldB;
+  const float* G = (s0 >= 0 ? sa.SA : sa.SB) + (int64_t)(s0 >= 0 ? s0 : s1) * B;
+  const float* U = G + (int64_t)a.T * ld;
+  uint16_t* H = reinterpret_cast<uint16_t*>(a.Y);
+  const int t0 = blockIdx.y * kLongFinishTokens;
+  // eight elements per thread at a time, all loads first
+  constexpr int kBatch = 8, kElems = kLongFinishTokens * B;
+  for (int e0 = threadIdx.x; e0 < kElems; e0 += 256 * kBatch) {
+    float gv[kBatch], uv[kBatch];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int e = e0 + q * 256, t = t0 + e / B, i = e % B;
+      const bool ok = e < kElems && t < a.T;
+      gv[q] = ok ? __builtin_nontemporal_load(G + (int64_t)t * ld + i) : 0.0f;
+      uv[q] = ok ? __builtin_nontemporal_load(U + (int64_t)t * ld + i) : 0.0f;
+    }
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int e = e0 + q * 256, t = t0 + e / B, i = e % B;
+      if (e < kElems && t < a.T)
+        H[(int64_t)t * a.syt + ((int64_t)r * B + i) * a.syi] = f32_to_bf16_rne(apply_act(a.act, gv[q]) * uv[q]);
+    }
   }
 }
 

@@ -128,7 +128,12 @@ def test_llama405b_zipf_mlp(api):
     _run_mlp(api, wl.name, 6, 3)  # the 8-row activation tile of 128-wide blocks, rows cut into chunks
     _run_mlp(api, wl.name, 16, 3)
     _run_mlp(api, wl.name, 24, 3)  # 32-token units with one activation tile per wave, rows cut into chunks
-    _run_mlp(api, wl.name, 70, 3)  # the full gate/up row keeps the gated product in the decode kernel, three groups
+    _run_mlp(api, wl.name, 60, 3)  # the gated product in the decode kernel, two groups of 32 tokens
+    # beyond 64 tokens: the long gate/up rows cut into chunks and finished by a launch of their own, the down
+    # product in its 16-block chunks
+    _run_mlp(api, wl.name, 70, 3)
+    _run_mlp(api, wl.name, 256, 4)
+    _run_mlp(api, wl.name, 400, 4)
     _run_mlp(api, wl.name, 2048, 8, expect_nnz=2662)
     # the load-balance stress is real: some block rows are full, the median row is nearly empty
     _, packs = _packed(api, wl.name)

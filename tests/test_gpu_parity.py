@@ -45,8 +45,9 @@ WIDE_CHUNK = 64  # ... of its second plan (streaming kernels)
 
 
 def check_aux(dev, ref):
-    """aux = two chunk plans (rows in schedule order cut into chunks of <= 16 and of <= 64 blocks) followed by
-    the column-grouped index (the same blocks by column, then ascending row)."""
+    """aux = two chunk plans (rows in schedule order cut into chunks of <= 16 and of <= 64 blocks), the dense
+    numbering of the rows that the first plan cuts, then the column-grouped index (the same blocks by column,
+    then ascending row)."""
     nbr, nbc = ref.rows // ref.b, ref.cols // ref.b
     aux = dev.aux.cpu().numpy()
     a16 = lambda x: (x + 15) // 16 * 16
@@ -70,9 +71,18 @@ def check_aux(dev, ref):
             for j in range(nch):
                 exp.append((int(r), nch > 1, kb + j * chunk, min(kb + (j + 1) * chunk, ke)))
         assert hdr[0] == len(exp) and hdr[1] == (int(cnt.max()) if cnt.size else 0) == dev.max_row_blocks and hdr[2] == chunk
+        n_split = sum(1 for e in exp if e[1])
+        assert hdr[3] == n_split and all(e[1] for e in exp[:n_split])  # the cut rows' chunks head the plan
         n = len(exp)
         assert [(int(c) & 0x7FFFFFFF, int(c) < 0, int(a), int(b_)) for c, a, b_ in
                 zip(chunk_row[:n], chunk_kb[:n], chunk_ke[:n])] == exp
+    row_slot = aux[off: off + 4 * nbr].view(np.int32)
+    off += a16(4 * nbr)
+    exp_slot = np.full(nbr, -1, dtype=np.int32)
+    for rank, r in enumerate(ref.row_order):
+        if cnt[r] > CHUNK:
+            exp_slot[r] = rank
+    assert np.array_equal(row_slot, exp_slot)
     col_ptr = aux[off: off + 4 * (nbc + 1)].view(np.int32)
     off += a16(4 * (nbc + 1))
     csc_row = aux[off: off + 4 * ref.nnz].view(np.int32)
@@ -737,6 +747,99 @@ def test_mlp_decode_with_a_very_long_down_row(api, T):
         torch.cuda.synchronize()
         check_close(y.cpu().numpy().T, want, f"mlp long down row T={T}")
     assert not y.cpu().numpy()[:, 2 * b:3 * b].any()
+
+
+def long_row_case(rng, b, nbi=12, nbc=48):
+    """Gate/up masks with block rows that the 16-block chunk plan cuts - in gate only, in up only, in both, barely
+    (17 and 20 blocks) - next to empty and ordinary rows; a uniform down mask.  The weights of a block row are
+    scaled by its length, so that every row of H is of order one: bf16 rounds H on both sides, and one rounding
+    that falls the other way in an entry of 20 among entries of 0.1 would alone exceed the tolerance on Y."""
+    E, I = nbc * b, nbi * b
+    d = synth.gauss_bf16(rng, (E, I), 0.02)
+    mg, mu = (synth.uniform_mask(rng, nbi, nbc, 0.9) for _ in range(2))
+    md = synth.uniform_mask(rng, nbc, nbi, 0.6)
+    mg[0, :], mu[0, :] = 1, 0
+    mu[0, 5:8] = 1
+    mg[1, :], mu[1, :] = 0, 1
+    mg[1, 40:42] = 1
+    mg[2, :], mu[2, :] = 1, 1
+    mg[3, :], mu[3, :] = 0, 0
+    mg[3, 3:23], mu[3, 30:47] = 1, 1
+    mg[4, :], mu[4, :] = 0, 1
+    mg[5, :], mu[5, :] = 0, 0
+    g, u = (synth.f32_to_bf16_bits((rng.standard_normal((I, E)) *
+                                    np.repeat(0.8 / np.sqrt(np.maximum(m.sum(1), 1) * b), b)[:, None]).astype(np.float32))
+            for m in (mg, mu))
+    return E, I, (g, u, d), (mg, mu, md)
+
+
+def long_scratch_bytes(packed, b, T):
+    """fp32 scratch the MLP workspace carries for the cut rows of gate and up: two arrays of T x (slots * b) per
+    matrix, slots = the most rows that can hold more than 16 of the matrix' blocks."""
+    total = 0
+    for m in packed:
+        slots = min(m.rows // b, m.nnz // (CHUNK + 1)) if m.max_row_blocks > CHUNK else 0
+        total += -(-(2 * slots * b * T * 4) // 256) * 256
+    return total
+
+
+@pytest.mark.parametrize("b,T", [(32, 100), (64, 65), (64, 200), (64, 700), (128, 129), (128, 300)])
+def test_mlp_with_long_gate_and_up_rows(api, b, T):
+    """Beyond the decode kernels' token counts the cut rows of a skewed gated product are summed in chunks into
+    scratch and finished by a launch of their own; the workspace query asks for that scratch exactly there."""
+    import torch
+
+    rng = np.random.default_rng(8800 + b + T)
+    E, I, (g, u, d), (mg, mu, md) = long_row_case(rng, b)
+    dg, rg = pack_both(api, g, b, mask=mg)
+    du, ru = pack_both(api, u, b, mask=mu)
+    dd, rd = pack_both(api, d, b, mask=md)
+    dgj = api.with_joint_row_order(dg, du)
+    a256 = lambda n: -(-n // 256) * 256
+    for gate in (dg, dgj):
+        small = api.mlp_workspace_bytes(gate, du, dd, 64)   # decode range: no scratch
+        want_ws = small - a256(64 * I * 2) + a256(T * I * 2) + long_scratch_bytes((dg, du), b, T)
+        assert api.mlp_workspace_bytes(gate, du, dd, T) == want_ws and want_ws > small
+    x = synth.gauss_bf16(rng, (T, E), 1.0)
+    want = orc.mlp(rg, ru, rd, x)
+    for gate in (dg, dgj, dgj):
+        y = api.sparse_mlp(gate, du, dd, to_dev(x), out=torch.full((T, E), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, want, f"mlp long gate/up rows b={b} T={T}")
+    # without the scratch (a workspace sized for the plain path) the same call takes the plain path
+    ws = torch.empty(a256(T * I * 2) + small - a256(64 * I * 2), dtype=torch.uint8, device="cuda:0")
+    y = api.sparse_mlp(dgj, du, dd, to_dev(x), out=torch.full((T, E), float("nan"), device="cuda:0"), ws=ws)
+    torch.cuda.synchronize()
+    check_close(y.cpu().numpy().T, want, f"mlp long gate/up rows, plain workspace b={b} T={T}")
+
+
+def test_mlp_with_long_rows_graph_replay(api):
+    """The three launches of the long-row path (clear, product, finish) recorded once and replayed on new inputs."""
+    import torch
+
+    rng = np.random.default_rng(8900)
+    b, T = 64, 150
+    E, I, (g, u, d), (mg, mu, md) = long_row_case(rng, b)
+    dg, rg = pack_both(api, g, b, mask=mg)
+    du, ru = pack_both(api, u, b, mask=mu)
+    dd, rd = pack_both(api, d, b, mask=md)
+    dg = api.with_joint_row_order(dg, du)
+    xs = torch.zeros((T, E), dtype=torch.bfloat16, device="cuda:0")
+    y = torch.empty((T, E), dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(api.mlp_workspace_bytes(dg, du, dd, T), dtype=torch.uint8, device="cuda:0")
+    api.sparse_mlp(dg, du, dd, xs, out=y, ws=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        api.sparse_mlp(dg, du, dd, xs, out=y, ws=ws)
+    for rep in range(3):
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        xs.copy_(to_dev(x))
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, orc.mlp(rg, ru, rd, x), f"mlp long rows graph replay {rep}")
 
 
 @pytest.mark.parametrize("T", [3, 20])
