@@ -333,7 +333,7 @@ int blast_bsr_joint_row_order(const blast_bsr_view* A, const blast_bsr_view* B, 
  *   ws, ws_bytes       at least blast_bsr_spmm_workspace() bytes (may be 0 -> ws may be NULL).
  * When W carries `aux` and a very full block row (see max_row_blocks), that row's chunks add their partial
  * sums into an fp32 Y with atomics in no fixed order: such rows are reproducible up to fp32 rounding of that
- * sum only (bf16 output never takes that path).
+ * sum only (bf16 output and the gated product never take that path).
  * Never synchronises.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */
 int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T, void* Y,
@@ -362,9 +362,11 @@ int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_byte
  * advances in the workspace.
  * Beyond 64 tokens, when Wgate or Wup carries `aux` and a block row so full that walking it alone would take
  * several times the average share of a workgroup (the load balance Sec. 3.4.1 asks for), the rows of more than
- * 16 blocks are summed in chunks into fp32 scratch behind H (atomics in no fixed order, as above) and H's rows
- * of those block rows are written by a launch of their own; blast_sparse_mlp_workspace() includes that scratch
- * exactly when the path applies, and a call handed the smaller workspace of the plain path takes the plain path.
+ * 16 blocks are summed chunk by chunk into fp32 scratch behind H and H's rows of those block rows are written by a
+ * launch of their own, which adds a row's chunks in a fixed order (the result is reproducible, but such a row's
+ * fp32 sums are rounded differently from a row walked in one piece); blast_sparse_mlp_workspace() includes that
+ * scratch exactly when the path applies, and a call handed the smaller workspace of the plain path takes the
+ * plain path.
  * Never synchronises.  Errors: INVALID_ARG, SHAPE (including inconsistent I/E/b between the three
  * matrices), UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */

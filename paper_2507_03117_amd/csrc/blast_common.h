@@ -37,12 +37,13 @@ constexpr int kWideChunkBlocks = 64;
 //   wide chunk plan:       the same with kWideChunkBlocks: whdr[4] | wchunk_row[wcap] | wchunk_kb[wcap] | wchunk_ke[wcap]
 //   row_slot[NBr]:         for a row with several chunks in the first plan, its rank in the schedule order
 //                          (0, 1, ... : a dense numbering of those rows), else -1
+//   row_chunk0[NBr]:       for such a row the index of its first chunk in the first plan, else -1
 //   column-grouped index:  col_ptr[NBc+1] | csc_row[nnz] | csc_blk[nnz]
 // The buffer is sized with nnz = nnz_cap; the arrays are placed with the actual nnz.
 struct AuxLayout {
   size_t hdr_off, chunk_row_off, chunk_kb_off, chunk_ke_off;
   size_t whdr_off, wchunk_row_off, wchunk_kb_off, wchunk_ke_off;
-  size_t row_slot_off, col_ptr_off, csc_row_off, csc_blk_off, bytes;
+  size_t row_slot_off, row_chunk0_off, col_ptr_off, csc_row_off, csc_blk_off, bytes;
   int64_t chunk_cap, wchunk_cap;
 };
 inline AuxLayout aux_layout(int64_t nbr, int64_t nbc, int64_t nnz) {
@@ -60,7 +61,8 @@ inline AuxLayout aux_layout(int64_t nbr, int64_t nbc, int64_t nnz) {
   L.wchunk_kb_off = L.wchunk_row_off + wb;
   L.wchunk_ke_off = L.wchunk_kb_off + wb;
   L.row_slot_off = L.wchunk_ke_off + wb;
-  L.col_ptr_off = L.row_slot_off + align_up(sizeof(int32_t) * (size_t)nbr, 16);
+  L.row_chunk0_off = L.row_slot_off + align_up(sizeof(int32_t) * (size_t)nbr, 16);
+  L.col_ptr_off = L.row_chunk0_off + align_up(sizeof(int32_t) * (size_t)nbr, 16);
   L.csc_row_off = L.col_ptr_off + align_up(sizeof(int32_t) * (size_t)(nbc + 1), 16);
   L.csc_blk_off = L.csc_row_off + align_up(sizeof(int32_t) * (size_t)nnz, 16);
   L.bytes = L.csc_blk_off + align_up(sizeof(int32_t) * (size_t)nnz, 16);

@@ -426,6 +426,7 @@ struct PlanOut {
   int* chunk_ke;
   int64_t cap;
   int* row_slot;    // may be null: per row, its rank if it has several chunks, else -1
+  int* row_chunk0;  // may be null: per row, the index of its first chunk if it has several, else -1
 };
 
 // Single workgroup: cut the block rows, in schedule order, into chunks of at most `chunk` blocks, once per
@@ -460,6 +461,7 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
       }
       int total;
       const int first = s_running + block_exscan(nch, wave_tot, total);
+      if (rank < nbr && o.row_chunk0) o.row_chunk0[r] = nch > 1 ? first : -1;
       for (int j = 0; j < nch; ++j) {
         const int64_t e = (int64_t)first + j;
         if (e < o.cap) {
@@ -487,10 +489,10 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
 inline void plan_outputs(char* ab, const blast::AuxLayout& A, PlanOut& narrow, PlanOut& wide) {
   narrow = PlanOut{blast::kChunkBlocks, reinterpret_cast<int*>(ab + A.hdr_off), reinterpret_cast<int*>(ab + A.chunk_row_off),
                    reinterpret_cast<int*>(ab + A.chunk_kb_off), reinterpret_cast<int*>(ab + A.chunk_ke_off), A.chunk_cap,
-                   reinterpret_cast<int*>(ab + A.row_slot_off)};
+                   reinterpret_cast<int*>(ab + A.row_slot_off), reinterpret_cast<int*>(ab + A.row_chunk0_off)};
   wide = PlanOut{blast::kWideChunkBlocks, reinterpret_cast<int*>(ab + A.whdr_off), reinterpret_cast<int*>(ab + A.wchunk_row_off),
                  reinterpret_cast<int*>(ab + A.wchunk_kb_off), reinterpret_cast<int*>(ab + A.wchunk_ke_off), A.wchunk_cap,
-                 nullptr};
+                 nullptr, nullptr};
 }
 
 // One workgroup per stored block of the transposed matrix: block e of the output is the transpose of

@@ -106,9 +106,12 @@ struct ChunkPlan {
   // long rows of a gated product cut into chunks (see StreamArgs)
   const int* slot0 = nullptr;
   const int* slot1 = nullptr;
-  float* SA = nullptr;
-  float* SB = nullptr;
-  int64_t ldA = 0, ldB = 0;
+  const int* chunk0_0 = nullptr;
+  const int* chunk0_1 = nullptr;
+  float* P0 = nullptr;
+  float* P1 = nullptr;
+  float* W0 = nullptr;
+  float* W1 = nullptr;
   const int* hdr1 = nullptr;  // the second matrix' plan (the first one's is hdr, chunk_*)
   const int* chunk_row1 = nullptr;
   const int* chunk_kb1 = nullptr;
@@ -143,7 +146,7 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
   int row_pinned = 0;
   const int64_t slab = ((int64_t)a.ntt + 7) / 8 * C::TT * k_features * 2;
   if (B == 128 && slab > kRowPinnedSlabBytes && grid == resident && a.ntt <= grid / 8 && (grid / 8) % a.ntt == 0 &&
-      n_rows / 8 + 1 <= 64 * ((grid / 8) / a.ntt) && !LONG)
+      n_rows / 8 + 1 <= 64 * ((grid / 8) / a.ntt))
     row_pinned = 1;
   StreamArgs sa{a, (int)n_items, shift, row_pinned, plan.hdr, plan.chunk_row, plan.chunk_kb, plan.chunk_ke};
   if constexpr (LONG) {
@@ -153,10 +156,12 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
     sa.chunk_ke1 = plan.chunk_ke1;
     sa.slot0 = plan.slot0;
     sa.slot1 = plan.slot1;
-    sa.SA = plan.SA;
-    sa.SB = plan.SB;
-    sa.ldA = plan.ldA;
-    sa.ldB = plan.ldB;
+    sa.chunk0_0 = plan.chunk0_0;
+    sa.chunk0_1 = plan.chunk0_1;
+    sa.P0 = plan.P0;
+    sa.P1 = plan.P1;
+    sa.W0 = plan.W0;
+    sa.W1 = plan.W1;
   }
   if (!CHUNK && plan.zero_job && plan.zero_job->hdr && !plan.zero_job->done) {
     // a later chunked product's rows are cleared by this launch on the side
@@ -171,11 +176,7 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
     sa.z_T = z.T;
     z.done = true;
   }
-  if constexpr (LONG) {
-    const int64_t most = plan.max_chunks > plan.max_chunks1 ? plan.max_chunks : plan.max_chunks1;
-    k_long_zero<B><<<dim3((unsigned)most, (unsigned)((a.T + 63) / 64), 2), dim3(256), 0, stream>>>(sa);
-    BLAST_LAUNCH_CHECK("k_long_zero");
-  } else if (CHUNK && !plan.pre_zeroed) {
+  if (CHUNK && !plan.pre_zeroed) {
     k_zero_shared_rows<B><<<dim3((unsigned)plan.max_chunks, (unsigned)((a.T + 63) / 64)), dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_zero_shared_rows");
   }
@@ -197,7 +198,8 @@ int launch_stream_tw(TileArgs a, const ChunkPlan& plan, int64_t k_features, hipS
   k_spmm_stream<B, DUAL, TW, CHUNK, false, NW, LONG><<<dim3((unsigned)grid), dim3(64 * NW), C::LDS_BYTES, stream>>>(sa);
   BLAST_LAUNCH_CHECK("k_spmm_stream");
   if constexpr (LONG) {
-    k_long_finish<B><<<dim3((unsigned)a.nbr, (unsigned)((a.T + kLongFinishTokens - 1) / kLongFinishTokens)),
+    k_long_finish<B><<<dim3((unsigned)((a.nbr + kLongFinishRows - 1) / kLongFinishRows),
+                            (unsigned)((a.T + kLongFinishTokens - 1) / kLongFinishTokens)),
                        dim3(256), 0, stream>>>(sa);
     BLAST_LAUNCH_CHECK("k_long_finish");
   }
@@ -580,14 +582,16 @@ constexpr size_t kCtlStatusOffset = 16;  // byte offset of the status word insid
 // The gated product cannot cut a block row (the activation needs complete sums), so at a few hundred tokens
 // - one to four token tiles per row - the workgroup that walks the fullest joint row alone sets the time of
 // the launch when the row lengths are skewed.  There the rows that the first chunk plan of either matrix cuts
-// (more than kChunkBlocks stored blocks) are taken in chunks after all: the launch sums each side of such a
-// row into fp32 scratch (chunks with atomics), and a small launch after it applies the activation and writes
-// those rows of H (see StreamArgs).  Measured on the 405B-class layer with the Zipf mask (fullest rows: all
-// 128 blocks of gate or of up, 133 joint), gate/up product in microseconds without / with: 128 tokens 160 / 88,
-// 256: 199 / 123, 512: 275 / 217, 768: 323 / 350, 1024: 299 / 417.  With the rows dealt evenly the launch moves
-// 64 KB per block and 128-token tile at the 6.6 TB/s its copies get, which is what is left at 256 tokens
-// (103 us of the 123; 7 us each for clearing and finishing).
+// (more than kChunkBlocks stored blocks) are taken in chunks after all: the launch stores the fp32 sums of
+// every chunk, and of the side of such a row that is not cut, in scratch slices of their own, and a small
+// launch after it adds the slices of a row in plan order, applies the activation and writes those rows of H
+// (see StreamArgs; no atomics, the result does not depend on the schedule).  Measured on the 405B-class layer
+// with the Zipf mask (fullest rows: all 128 blocks of gate or of up, 133 joint), gate/up product in
+// microseconds without / with: 128 tokens 160 / 90, 256: 199 / 125, 384: 264 / 187, 512: 275 / 198,
+// 640: 317 / 272, 768: 325 / 296; at 1024 tokens 300 / 349 (the chunks' fp32 slices are written and read
+// again, 64 us of the launch at 2048 tokens, and the finishing launch reads them at 2-2.5 TB/s only).
 constexpr int kLongMinTokens = 64;  // up to here the decode kernels are at least as fast (81 against 88 us at 64)
+constexpr int kLongWideTokens = 384;  // 512 tokens: 198 us with 256-token tiles (row-pinned schedule), 218 with 128-token tiles
 
 // upper bound of the number of rows with more than kChunkBlocks stored blocks (0: none, or no plan at hand)
 int64_t long_slots(const blast_bsr_view* v) {
@@ -596,9 +600,16 @@ int64_t long_slots(const blast_bsr_view* v) {
   return by_blocks < nbr ? by_blocks : nbr;
 }
 
-// gate sums and up sums, [T][slots * b] fp32 each, of the rows with a slot in this matrix
+// upper bound of the number of chunks of the cut rows: sum of ceil(len / chunk) over those rows, at most
+int64_t long_max_chunks(const blast_bsr_view* v) {
+  const int64_t slots = long_slots(v);
+  return slots ? v->nnz / blast::kChunkBlocks + slots : 0;
+}
+
+// fp32 scratch of one matrix in the long-row path, [chunks + slots][T][b]: a slice per chunk of its cut rows,
+// and a slice per cut row for the whole side of that row in the other matrix
 size_t long_scratch_bytes(const blast_bsr_view* v, int64_t T) {
-  return blast::align_up(2 * (size_t)long_slots(v) * (size_t)v->b * (size_t)T * 4, 256);
+  return blast::align_up((size_t)(long_max_chunks(v) + long_slots(v)) * (size_t)v->b * (size_t)T * 4, 256);
 }
 
 // Where it pays (host-side estimate from the counts the views carry).
@@ -606,16 +617,12 @@ bool long_rows_pay(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, int64
   if (!Wup || Wgate->b < 32) return false;
   if (long_slots(Wgate) + long_slots(Wup) == 0) return false;
   if (T <= kLongMinTokens) return false;
-  const int64_t tiles = (T + 127) / 128;
-  const double avg = (double)(Wgate->nnz + Wup->nnz) * (double)tiles / (2.0 * cu_count());
+  // the fullest row of either matrix (a lower bound of the fullest joint row) against the blocks a CU gets when
+  // the product is dealt evenly, in 256-token tiles
+  const int64_t tiles = (T + 255) / 256;
+  const double avg = (double)(Wgate->nnz + Wup->nnz) * (double)tiles / cu_count();
   const int64_t fullest = Wgate->max_row_blocks > Wup->max_row_blocks ? Wgate->max_row_blocks : Wup->max_row_blocks;
-  return (double)fullest > 2.0 * avg + 2.0 * blast::kChunkBlocks;
-}
-
-// upper bound of the number of chunks of the cut rows: sum of ceil(len / chunk) over those rows, at most
-int64_t long_max_chunks(const blast_bsr_view* v) {
-  const int64_t slots = long_slots(v);
-  return slots ? v->nnz / blast::kChunkBlocks + slots : 0;
+  return fullest >= 2 * blast::kChunkBlocks && (double)fullest > 1.75 * avg;
 }
 
 // scratch of the long-row path behind the MLP workspace proper (0 where the path is not taken)
@@ -671,9 +678,11 @@ int check_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const blas
   return BLAST_OK;
 }
 
+static_assert(kLongChunk == blast::kChunkBlocks, "the long-row launch works from the first chunk plan");
+
 struct LongScratch {
-  float* SA = nullptr;  // indexed by the slots of the first matrix
-  float* SB = nullptr;  // by those of the second
+  float* S0 = nullptr;  // long_scratch_bytes() of the first matrix: its chunk slices, then its rows' other sides
+  float* S1 = nullptr;  // of the second
 };
 
 template <int B>
@@ -689,6 +698,7 @@ int enqueue_gated_long(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
     const blast::AuxLayout L = blast::aux_layout(v->rows / v->b, v->cols / v->b, v->nnz);
     const char* ab = static_cast<const char*>(v->aux);
     const int* row_slot = reinterpret_cast<const int*>(ab + L.row_slot_off);
+    const int* row_chunk0 = reinterpret_cast<const int*>(ab + L.row_chunk0_off);
     const int* hdr = reinterpret_cast<const int*>(ab + L.hdr_off) + 3;  // the chunks of the cut rows head the plan
     const int* chunk_row = reinterpret_cast<const int*>(ab + L.chunk_row_off);
     const int* chunk_kb = reinterpret_cast<const int*>(ab + L.chunk_kb_off);
@@ -701,8 +711,9 @@ int enqueue_gated_long(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
       p.chunk_ke = chunk_ke;
       p.max_chunks = most;
       p.slot0 = row_slot;
-      p.SA = ls.SA;
-      p.ldA = slots * B;
+      p.chunk0_0 = row_chunk0;
+      p.P0 = ls.S0;
+      p.W0 = ls.S0 + most * g.T * B;
     } else {
       p.hdr1 = hdr;
       p.chunk_row1 = chunk_row;
@@ -710,11 +721,15 @@ int enqueue_gated_long(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
       p.chunk_ke1 = chunk_ke;
       p.max_chunks1 = most;
       p.slot1 = row_slot;
-      p.SB = ls.SB;
-      p.ldB = slots * B;
+      p.chunk0_1 = row_chunk0;
+      p.P1 = ls.S1;
+      p.W1 = ls.S1 + most * g.T * B;
     }
   }
-  // 128-token tiles: more and shorter items
+  // 128-token tiles (more and shorter items) up to kLongWideTokens, the eight-wave 256-token tile beyond
+  if constexpr (B == 128) {
+    if (g.T > kLongWideTokens) return launch_stream_tw<B, true, 4, false, 8, true>(g, p, g.kdim, stream);
+  }
   if constexpr (B >= 64) return launch_stream_tw<B, true, 2, false, 4, true>(g, p, g.kdim, stream);
   return launch_stream_tw<B, true, 4, false, 4, true>(g, p, g.kdim, stream);
 }
@@ -927,8 +942,8 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
     const size_t extra = Wup ? mlp_long_bytes(Wgate, Wup, T) : 0;
     const bool have_ls = extra > 0 && ws_bytes >= need + extra;
     if (have_ls) {
-      ls.SA = reinterpret_cast<float*>(static_cast<char*>(ws) + need);
-      ls.SB = reinterpret_cast<float*>(static_cast<char*>(ws) + need + long_scratch_bytes(Wgate, T));
+      ls.S0 = reinterpret_cast<float*>(static_cast<char*>(ws) + need);
+      ls.S1 = reinterpret_cast<float*>(static_cast<char*>(ws) + need + long_scratch_bytes(Wgate, T));
     }
     if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream,
                                zj.hdr ? &zj : nullptr, have_ls ? &ls : nullptr))

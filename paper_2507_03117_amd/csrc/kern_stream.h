@@ -101,48 +101,41 @@ struct StreamArgs {
   int z_T;
   // Long rows of a gated product (LONG instances).  A block row that the first chunk plan of a matrix cuts
   // into several chunks has a slot in that matrix (the packer's row_slot, else -1); a row with a slot in
-  // either matrix is "deferred": the launch leaves its two complete fp32 sums (gate side, up side) in scratch
-  // and a small launch after it applies the activation and writes H.  The items of the launch are then
+  // either matrix is "deferred": the launch leaves fp32 sums of its two sides (gate, up) in scratch and a
+  // small launch after it adds them up, applies the activation and writes H.  The items of the launch are
   //   - the chunks of the first matrix' cut rows (the head of its plan: hdr points at their number),
   //   - those of the second matrix (hdr1, chunk_*1),
   //   - the block rows in schedule order: an ordinary row as ever; of a deferred row only the side that is
-  //     not cut, its sums stored to scratch.
-  // Chunks add into scratch cleared before the launch.  Scratch: SA for the rows with a slot in the first
-  // matrix, indexed by that slot, [2][T][ldA] fp32 (gate sums, then up sums), columns slot * B ...; SB for the
-  // rows with a slot in the second matrix only, indexed by that slot, [2][T][ldB].
+  //     not cut.
+  // Every chunk stores its sums in a slice of its own (no atomics, nothing to clear): P0 / P1, indexed by
+  // the chunk's place in the plan of the first / second matrix.  A side that is whole goes to W0 (the up
+  // side of a row cut in the first matrix only, indexed by the row's slot there) or W1 (the gate side of a
+  // row cut in the second matrix only, indexed by its slot there).  All four are fp32 [index][T][B]: the
+  // tile an item stores is one contiguous piece.
   const int* slot0;
   const int* slot1;
-  float* SA;
-  float* SB;
-  int64_t ldA, ldB;
+  const int* chunk0_0;  // first chunk of a cut row in the first matrix' plan (the packer's row_chunk0)
+  const int* chunk0_1;
+  float* P0;
+  float* P1;
+  float* W0;
+  float* W1;
   const int* hdr1;
   const int* chunk_row1;
   const int* chunk_kb1;
   const int* chunk_ke1;
 };
 
+constexpr int kLongChunk = 16;  // blocks per chunk of the plan that the LONG launch works from
+
 // number of chunks of a matrix' cut rows (hdr points at that count, or is null)
 __device__ __forceinline__ int long_chunks(const int* hdr) { return hdr ? ld_idx(hdr, 0) : 0; }
 
 // What a LONG item that is not an ordinary row does with its sums (ItemTable::c1; bit 31 of r marks such items
-// and the rest of r is the slot).
+// and the rest of r is the index in the destination).
 constexpr int kLongSecond = 1;  // the blocks are the second matrix'
-constexpr int kLongUp = 2;      // destination: the up sums (else the gate sums)
-constexpr int kLongB = 4;       // destination in SB (else SA)
-constexpr int kLongAdd = 8;     // added atomically (a chunk), else stored
-constexpr int kLongNone = 16;   // nothing to do: both sides of the row are cut
-
-// where the sums of block row `row` of the second matrix go
-__device__ __forceinline__ void long_up_dest(const StreamArgs& sa, int row, int& slot, int& code) {
-  const int s0 = sa.slot0 ? sa.slot0[row] : -1;
-  if (s0 >= 0) {
-    slot = s0;
-    code = kLongSecond | kLongUp;
-  } else {
-    slot = sa.slot1[row];
-    code = kLongSecond | kLongUp | kLongB;
-  }
-}
+constexpr int kLongP = 2;       // destination P0 / P1 (a chunk), else W0 / W1 (a whole side); which: kLongSecond
+constexpr int kLongNone = 4;    // nothing to do: both sides of the row are cut
 
 // item -> (rank in the row schedule, token tile) without an integer division in the common case
 __device__ __forceinline__ void split_item(int it, int ntt, int shift, int& rank, int& tile) {
@@ -188,20 +181,19 @@ __device__ __forceinline__ void describe_item(const StreamArgs& sa, int rank, in
   t.tile = tile;
   if constexpr (LONG) {
     const int n0 = long_chunks(sa.hdr), n1 = long_chunks(sa.hdr1);
-    int slot = 0, code = 0;
+    int index = 0, code = 0;
     bool special = true;
     t.k1 = t.e1 = 0;
     if (rank < n0) {  // a chunk of the first matrix
-      slot = sa.slot0[sa.chunk_row[rank] & 0x7FFFFFFF];
-      code = kLongAdd;
+      index = rank;
+      code = kLongP;
       t.k0 = sa.chunk_kb[rank];
       t.e0 = sa.chunk_ke[rank];
     } else if (rank < n0 + n1) {  // of the second
-      const int ci = rank - n0;
-      long_up_dest(sa, sa.chunk_row1[ci] & 0x7FFFFFFF, slot, code);
-      code |= kLongAdd;
-      t.k0 = sa.chunk_kb1[ci];
-      t.e0 = sa.chunk_ke1[ci];
+      index = rank - n0;
+      code = kLongP | kLongSecond;
+      t.k0 = sa.chunk_kb1[index];
+      t.e0 = sa.chunk_ke1[index];
     } else {
       const int rr = rank - n0 - n1;
       const int r = a.row_order ? a.row_order[rr] : rr;
@@ -216,19 +208,20 @@ __device__ __forceinline__ void describe_item(const StreamArgs& sa, int rank, in
       } else if (s0 >= 0 && s1 >= 0) {
         code = kLongNone;
         t.k0 = t.e0 = 0;
-      } else if (s0 >= 0) {  // the up side is whole
-        long_up_dest(sa, r, slot, code);
+      } else if (s0 >= 0) {  // the up side is whole: W0[s0]
+        index = s0;
+        code = kLongSecond;
         t.k0 = a.m1.row_ptr[r];
         t.e0 = a.m1.row_ptr[r + 1];
-      } else {  // the gate side is whole
-        slot = s1;
-        code = kLongB;
+      } else {  // the gate side is whole: W1[s1]
+        index = s1;
+        code = 0;
         t.k0 = a.m0.row_ptr[r];
         t.e0 = a.m0.row_ptr[r + 1];
       }
     }
     if (special) {
-      t.r = slot | (int)0x80000000u;
+      t.r = index | (int)0x80000000u;
       t.c1 = code;
       if (t.k0 < t.e0) t.c0 = ((code & kLongSecond) ? a.m1 : a.m0).col_idx[t.k0];
       return;
@@ -250,6 +243,20 @@ __device__ __forceinline__ void describe_item(const StreamArgs& sa, int rank, in
   if (DUAL && t.k1 < t.e1) t.c1 = a.m1.col_idx[t.k1];
 }
 
+// Stored blocks that item `rank` of a LONG launch multiplies (see StreamArgs for the numbering).
+__device__ __forceinline__ int long_item_blocks(const StreamArgs& sa, int rank) {
+  const TileArgs& a = sa.t;
+  const int n0 = long_chunks(sa.hdr), n1 = long_chunks(sa.hdr1);
+  if (rank < n0) return sa.chunk_ke[rank] - sa.chunk_kb[rank];
+  if (rank < n0 + n1) return sa.chunk_ke1[rank - n0] - sa.chunk_kb1[rank - n0];
+  const int rr = rank - n0 - n1;
+  const int r = a.row_order ? a.row_order[rr] : rr;
+  int len = 0;
+  if (!(sa.slot0 && sa.slot0[r] >= 0)) len += a.m0.row_ptr[r + 1] - a.m0.row_ptr[r];
+  if (!(sa.slot1 && sa.slot1[r] >= 0)) len += a.m1.row_ptr[r + 1] - a.m1.row_ptr[r];
+  return len;
+}
+
 template <bool DUAL, bool CHUNK, bool LONG>
 __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n_items, int w, int G, int lane) {
   const TileArgs& a = sa.t;
@@ -268,8 +275,8 @@ __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n
   // octets, every other octet mirrored; on an XCD, `nslot` groups of ntt workgroups (one per token tile)
   // each take whole rows.  Which group takes which row is decided by every workgroup for itself, all
   // arriving at the same answer: rows in order, each to the group with the least work so far (work = stored
-  // blocks + 2 for the output tile); with more than 64 rows per XCD, or more than 8 groups, rows are dealt
-  // round-robin, every other round mirrored.
+  // blocks + 2 for the output tile); with more rows per XCD than are dealt that way, or more than 8 groups,
+  // rows are dealt round-robin, every other round mirrored.
   const int n_rows = n_items / a.ntt;
   const int x = w & 7, j = w >> 3, Gx = G >> 3;
   const int nslot = Gx / a.ntt, slot = j / a.ntt, tile = j - slot * a.ntt;
@@ -280,31 +287,44 @@ __device__ __forceinline__ ItemTable load_item_table(const StreamArgs& sa, int n
   if (octets > 0 && rank_of(octets - 1) >= n_rows) --nrx;
   int mine = -1;  // per lane: the position (in the XCD's list) of the lane-th row of this group
   int n_mine = 0;
-  if (nrx <= 64 && nslot <= 8) {
-    int len = 0;
-    if (lane < nrx) {
-      const int rank = rank_of(lane);
-      if (CHUNK) {
+  // (LONG: up to 128 rows per XCD, the lengths two per lane, and no group is given more than the 64 rows a
+  // descriptor table holds)
+  constexpr int kDealt = LONG ? 128 : 64;
+  if (nrx <= kDealt && nslot <= 8 && (nrx <= 64 || nslot >= 2)) {
+    auto length_at = [&](int pos) {
+      const int rank = rank_of(pos);
+      int len;
+      if (LONG) {
+        len = long_item_blocks(sa, rank);
+      } else if (CHUNK) {
         len = sa.chunk_ke[rank] - sa.chunk_kb[rank];
       } else {
         const int r = a.row_order ? a.row_order[rank] : rank;
         len = a.m0.row_ptr[r + 1] - a.m0.row_ptr[r];
         if (DUAL) len += a.m1.row_ptr[r + 1] - a.m1.row_ptr[r];
       }
-      len += 2;
-    }
+      return len + 2;
+    };
+    int len = 0, len_hi = 0;
+    if (lane < nrx) len = length_at(lane);
+    if (LONG && lane + 64 < nrx) len_hi = length_at(lane + 64);
     int load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int k = 0; k < nrx; ++k) {
-      const int l = BLAST_LANE(len, k);
+      const int l = (LONG && k >= 64) ? BLAST_LANE(len_hi, k - 64) : BLAST_LANE(len, k);
       int best = 0, bl = load[0];
+      if (LONG && cnt[0] >= 64) bl = 0x7FFFFFFF;
 #pragma unroll
       for (int q = 1; q < 8; ++q)
-        if (q < nslot && load[q] < bl) {
+        if (q < nslot && load[q] < bl && !(LONG && cnt[q] >= 64)) {
           bl = load[q];
           best = q;
         }
 #pragma unroll
-      for (int q = 0; q < 8; ++q) load[q] += (q == best) ? l : 0;
+      for (int q = 0; q < 8; ++q) {
+        load[q] += (q == best) ? l : 0;
+        if (LONG) cnt[q] += (q == best) ? 1 : 0;
+      }
       if (best == slot) {
         if (lane == n_mine) mine = k;
         ++n_mine;
@@ -375,8 +395,7 @@ __device__ __forceinline__ void stream_zero_side(const StreamArgs& sa, int w, in
 // (block row, token tile); a row made of several chunks adds its partial sums into a zeroed fp32 output.
 // POST: a single-matrix product whose result goes through the activation a.act before it is stored
 // (the first half of a two-matrix MLP).
-// LONG: the gated product with its long rows cut into chunks and finished by a later launch, see StreamArgs
-// (never with the row-pinned schedule).
+// LONG: the gated product with its long rows cut into chunks and finished by a later launch, see StreamArgs.
 template <int B, bool DUAL, int TW, bool CHUNK, bool POST = false, int NW = 4, bool LONG = false>
 __global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) void k_spmm_stream(const StreamArgs sa) {
   static_assert(!(DUAL && CHUNK), "the activation needs complete sums: the gated product is never split");
@@ -676,24 +695,20 @@ __global__ __launch_bounds__(64 * NW, (StreamCfg<B, TW, NW>::WAVES_PER_SIMD)) vo
       if (rr < 0) {  // a chunk, or the whole side of a deferred row: the sums go to scratch as they are
         const int code = BLAST_LANE(tab.c1, round);
         if (code & kLongNone) continue;
-        const int64_t ld = (code & kLongB) ? sa.ldB : sa.ldA;
-        float* S = ((code & kLongB) ? sa.SB : sa.SA) + ((code & kLongUp) ? (int64_t)a.T * ld : 0);
-        const bool add = (code & kLongAdd) != 0;
+        // whole up side -> W0, whole gate side -> W1 (each indexed by the slot in the matrix that is cut)
+        const bool second = (code & kLongSecond) != 0;
+        float* S = (code & kLongP) ? (second ? sa.P1 : sa.P0) : (second ? sa.W0 : sa.W1);
+        S += (int64_t)(rr & 0x7FFFFFFF) * a.T * B;
         const int tokb = t0 + tw * 64 + 4 * lh;
 #pragma unroll
         for (int ni = 0; ni < C::NI; ++ni) {
-          float* p0 = S + (int64_t)tokb * ld + (int64_t)(rr & 0x7FFFFFFF) * B + rw * C::WT_ROW + ni * 32 + l32;
+          float* p0 = S + (int64_t)tokb * B + rw * C::WT_ROW + ni * 32 + l32;
 #pragma unroll
           for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
               const int dt = mi * 32 + 8 * (j / 4) + (j % 4);
-              if (tokb + dt < a.T) {
-                if (add)
-                  atomicAdd(p0 + (int64_t)dt * ld, acc0[mi][ni][j]);
-                else
-                  p0[(int64_t)dt * ld] = acc0[mi][ni][j];
-              }
+              if (tokb + dt < a.T) p0[dt * B] = acc0[mi][ni][j];
             }
         }
         continue;
@@ -840,61 +855,76 @@ __global__ __launch_bounds__(256) void k_zero_shared_rows(const StreamArgs sa) {
   }
 }
 
-// Before a LONG launch: zeroes the scratch that its chunks add into.
-// Grid: x = upper bound of the number of chunks of a matrix' cut rows, y = slabs of 64 tokens, z = matrix.
-template <int B>
-__global__ __launch_bounds__(256) void k_long_zero(const StreamArgs sa) {
-  const TileArgs& a = sa.t;
-  const bool second = blockIdx.z != 0;
-  const int ci = blockIdx.x;
-  if (ci >= long_chunks(second ? sa.hdr1 : sa.hdr)) return;
-  const int r = ld_idx(second ? sa.chunk_row1 : sa.chunk_row, ci) & 0x7FFFFFFF;
-  // only the first chunk of the row zeroes
-  if (ld_idx(second ? sa.chunk_kb1 : sa.chunk_kb, ci) != ld_idx(second ? a.m1.row_ptr : a.m0.row_ptr, r)) return;
-  int slot, code = 0;
-  if (second)
-    long_up_dest(sa, r, slot, code);
-  else
-    slot = sa.slot0[r];
-  const int64_t ld = (code & kLongB) ? sa.ldB : sa.ldA;
-  float* S = ((code & kLongB) ? sa.SB : sa.SA) + ((code & kLongUp) ? (int64_t)a.T * ld : 0);
-  const int t0 = blockIdx.y * 64;
-  for (int e = threadIdx.x; e < 64 * B; e += 256) {
-    const int t = t0 + e / B, i = e % B;
-    if (t < a.T) S[(int64_t)t * ld + (int64_t)slot * B + i] = 0.0f;
-  }
-}
-
-// After a LONG launch: H = act(gate sums) * (up sums) for the deferred rows.
-// Grid: x = block rows, y = slabs of kLongFinishTokens tokens.
-constexpr int kLongFinishTokens = 16;
+// After a LONG launch: H = act(gate sums) * (up sums) for the deferred rows, each side either whole or the
+// sum of the row's chunks, added in the order of the plan.
+// Grid: x = groups of kLongFinishRows block rows, y = slabs of kLongFinishTokens tokens.  (A workgroup lives
+// for at least the latency of the loads that tell it whether a row is deferred: one workgroup looks at several
+// rows, so that the many rows that are not cost little.)
+constexpr int kLongFinishTokens = 8, kLongFinishRows = 8;
 template <int B>
 __global__ __launch_bounds__(256) void k_long_finish(const StreamArgs sa) {
   const TileArgs& a = sa.t;
-  const int r = blockIdx.x;
-  const int s0 = sa.slot0 ? ld_idx(sa.slot0, r) : -1, s1 = sa.slot1 ? ld_idx(sa.slot1, r) : -1;
-  if (s0 < 0 && s1 < 0) return;
-  const int64_t ld = s0 >= 0 ? sa.ldA : sa.ldB;
-  const float* G = (s0 >= 0 ? sa.SA : sa.SB) + (int64_t)(s0 >= 0 ? s0 : s1) * B;
-  const float* U = G + (int64_t)a.T * ld;
+  int s0v[kLongFinishRows], s1v[kLongFinishRows];
+#pragma unroll
+  for (int q = 0; q < kLongFinishRows; ++q) {
+    const int r = blockIdx.x * kLongFinishRows + q;
+    s0v[q] = (r < a.nbr && sa.slot0) ? ld_idx(sa.slot0, r) : -1;
+    s1v[q] = (r < a.nbr && sa.slot1) ? ld_idx(sa.slot1, r) : -1;
+  }
   uint16_t* H = reinterpret_cast<uint16_t*>(a.Y);
-  const int t0 = blockIdx.y * kLongFinishTokens;
-  // eight elements per thread at a time, all loads first
-  constexpr int kBatch = 8, kElems = kLongFinishTokens * B;
-  for (int e0 = threadIdx.x; e0 < kElems; e0 += 256 * kBatch) {
-    float gv[kBatch], uv[kBatch];
-#pragma unroll
-    for (int q = 0; q < kBatch; ++q) {
-      const int e = e0 + q * 256, t = t0 + e / B, i = e % B;
-      const bool ok = e < kElems && t < a.T;
-      gv[q] = ok ? __builtin_nontemporal_load(G + (int64_t)t * ld + i) : 0.0f;
-      uv[q] = ok ? __builtin_nontemporal_load(U + (int64_t)t * ld + i) : 0.0f;
+  const int64_t slice = (int64_t)a.T * B;  // values of one chunk's or one side's sums
+  // A thread takes four neighbouring rows of one token, 16 bytes per load; kAhead chunks of each side per
+  // round, the loads of a round first.  Every load is unconditional (indices clamped, the surplus multiplied
+  // by zero), so that they leave back to back.
+  constexpr int kAhead = 8, kQuads = kLongFinishTokens * B / 4;
+  const int e = threadIdx.x * 4;
+  const bool mine = threadIdx.x < kQuads && blockIdx.y * kLongFinishTokens + e / B < a.T;
+  const int t = mine ? blockIdx.y * kLongFinishTokens + e / B : 0, i = mine ? e % B : 0;
+  using f32x4 = __attribute__((ext_vector_type(4))) float;
+#pragma unroll 1
+  for (int q = 0; q < kLongFinishRows; ++q) {
+    const int s0 = s0v[q], s1 = s1v[q];
+    if (s0 < 0 && s1 < 0) continue;
+    const int r = blockIdx.x * kLongFinishRows + q;
+    // gate side: the chunks of the row in P0, or the whole side in W1; up side: chunks in P1, or W0
+    const float* G;
+    const float* U;
+    int nG = 1, nU = 1;
+    if (s0 >= 0) {
+      G = sa.P0 + ld_idx(sa.chunk0_0, r) * slice;
+      nG = (ld_idx(a.m0.row_ptr, r + 1) - ld_idx(a.m0.row_ptr, r) + kLongChunk - 1) / kLongChunk;
+    } else {
+      G = sa.W1 + s1 * slice;
     }
+    if (s1 >= 0) {
+      U = sa.P1 + ld_idx(sa.chunk0_1, r) * slice;
+      nU = (ld_idx(a.m1.row_ptr, r + 1) - ld_idx(a.m1.row_ptr, r) + kLongChunk - 1) / kLongChunk;
+    } else {
+      U = sa.W0 + s0 * slice;
+    }
+    G += (int64_t)t * B + i;
+    U += (int64_t)t * B + i;
+    f32x4 gv = {0.0f, 0.0f, 0.0f, 0.0f}, uv = gv;
+    const int nmax = nG > nU ? nG : nU;
+    for (int c0 = 0; c0 < nmax; c0 += kAhead) {
+      f32x4 gl[kAhead], ul[kAhead];
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q) {
-      const int e = e0 + q * 256, t = t0 + e / B, i = e % B;
-      if (e < kElems && t < a.T)
-        H[(int64_t)t * a.syt + ((int64_t)r * B + i) * a.syi] = f32_to_bf16_rne(apply_act(a.act, gv[q]) * uv[q]);
+      for (int cc = 0; cc < kAhead; ++cc) {
+        const int c = c0 + cc;
+        gl[cc] = *reinterpret_cast<const f32x4*>(G + (c < nG ? c : nG - 1) * slice);
+        ul[cc] = *reinterpret_cast<const f32x4*>(U + (c < nU ? c : nU - 1) * slice);
+      }
+#pragma unroll
+      for (int cc = 0; cc < kAhead; ++cc) {  // in the order of the plan
+        const int c = c0 + cc;
+        if (c < nG) gv += gl[cc];
+        if (c < nU) uv += ul[cc];
+      }
+    }
+    if (mine) {
+      uint16_t* h = H + (int64_t)t * a.syt + ((int64_t)r * B + i) * a.syi;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) h[k * a.syi] = f32_to_bf16_rne(apply_act(a.act, gv[k]) * uv[k]);
     }
   }
 }

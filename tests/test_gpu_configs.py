@@ -133,7 +133,8 @@ def test_llama405b_zipf_mlp(api):
     # product in its 16-block chunks
     _run_mlp(api, wl.name, 70, 3)
     _run_mlp(api, wl.name, 256, 4)
-    _run_mlp(api, wl.name, 400, 4)
+    _run_mlp(api, wl.name, 400, 4)  # 256-token tiles, a block row's tiles side by side on one XCD
+    _run_mlp(api, wl.name, 700, 4)  # three tiles: not that schedule
     _run_mlp(api, wl.name, 2048, 8, expect_nnz=2662)
     # the load-balance stress is real: some block rows are full, the median row is nearly empty
     _, packs = _packed(api, wl.name)

@@ -46,7 +46,7 @@ WIDE_CHUNK = 64  # ... of its second plan (streaming kernels)
 
 def check_aux(dev, ref):
     """aux = two chunk plans (rows in schedule order cut into chunks of <= 16 and of <= 64 blocks), the dense
-    numbering of the rows that the first plan cuts, then the column-grouped index (the same blocks by column,
+    numbering of the rows that the first plan cuts and the index of their first chunk, then the column-grouped index (the same blocks by column,
     then ascending row)."""
     nbr, nbc = ref.rows // ref.b, ref.cols // ref.b
     aux = dev.aux.cpu().numpy()
@@ -83,6 +83,14 @@ def check_aux(dev, ref):
         if cnt[r] > CHUNK:
             exp_slot[r] = rank
     assert np.array_equal(row_slot, exp_slot)
+    row_chunk0 = aux[off: off + 4 * nbr].view(np.int32)
+    off += a16(4 * nbr)
+    exp_chunk0, at = np.full(nbr, -1, dtype=np.int32), 0
+    for r in ref.row_order:
+        if cnt[r] > CHUNK:
+            exp_chunk0[r] = at
+        at += max(1, -(-int(cnt[r]) // CHUNK))
+    assert np.array_equal(row_chunk0, exp_chunk0)
     col_ptr = aux[off: off + 4 * (nbc + 1)].view(np.int32)
     off += a16(4 * (nbc + 1))
     csc_row = aux[off: off + 4 * ref.nnz].view(np.int32)
@@ -774,19 +782,22 @@ def long_row_case(rng, b, nbi=12, nbc=48):
 
 
 def long_scratch_bytes(packed, b, T):
-    """fp32 scratch the MLP workspace carries for the cut rows of gate and up: two arrays of T x (slots * b) per
-    matrix, slots = the most rows that can hold more than 16 of the matrix' blocks."""
+    """fp32 scratch the MLP workspace carries for the cut rows of gate and up, per matrix T x b values for every
+    chunk of a cut row and for every cut row (the whole side of that row in the other matrix), counted by their
+    upper bounds: slots = the most rows that can hold more than 16 of the matrix' blocks, chunks <= nnz/16 + slots."""
     total = 0
     for m in packed:
         slots = min(m.rows // b, m.nnz // (CHUNK + 1)) if m.max_row_blocks > CHUNK else 0
-        total += -(-(2 * slots * b * T * 4) // 256) * 256
+        chunks = m.nnz // CHUNK + slots if slots else 0
+        total += -(-((chunks + slots) * b * T * 4) // 256) * 256
     return total
 
 
 @pytest.mark.parametrize("b,T", [(32, 100), (64, 65), (64, 200), (64, 700), (128, 129), (128, 300)])
 def test_mlp_with_long_gate_and_up_rows(api, b, T):
-    """Beyond the decode kernels' token counts the cut rows of a skewed gated product are summed in chunks into
-    scratch and finished by a launch of their own; the workspace query asks for that scratch exactly there."""
+    """Beyond the decode kernels' token counts the cut rows of a skewed gated product are summed chunk by chunk
+    into scratch and finished by a launch of their own; the workspace query asks for that scratch exactly there.
+    No atomics: two calls give the same bits."""
     import torch
 
     rng = np.random.default_rng(8800 + b + T)
@@ -802,10 +813,13 @@ def test_mlp_with_long_gate_and_up_rows(api, b, T):
         assert api.mlp_workspace_bytes(gate, du, dd, T) == want_ws and want_ws > small
     x = synth.gauss_bf16(rng, (T, E), 1.0)
     want = orc.mlp(rg, ru, rd, x)
+    seen = []
     for gate in (dg, dgj, dgj):
         y = api.sparse_mlp(gate, du, dd, to_dev(x), out=torch.full((T, E), float("nan"), device="cuda:0"))
         torch.cuda.synchronize()
         check_close(y.cpu().numpy().T, want, f"mlp long gate/up rows b={b} T={T}")
+        seen.append(y)
+    assert torch.equal(seen[1], seen[2])
     # without the scratch (a workspace sized for the plain path) the same call takes the plain path
     ws = torch.empty(a256(T * I * 2) + small - a256(64 * I * 2), dtype=torch.uint8, device="cuda:0")
     y = api.sparse_mlp(dgj, du, dd, to_dev(x), out=torch.full((T, E), float("nan"), device="cuda:0"), ws=ws)
@@ -814,7 +828,7 @@ def test_mlp_with_long_gate_and_up_rows(api, b, T):
 
 
 def test_mlp_with_long_rows_graph_replay(api):
-    """The three launches of the long-row path (clear, product, finish) recorded once and replayed on new inputs."""
+    """The launches of the long-row path (product, finish) recorded once and replayed on new inputs."""
     import torch
 
     rng = np.random.default_rng(8900)
