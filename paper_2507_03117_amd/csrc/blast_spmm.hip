@@ -730,8 +730,11 @@ int enqueue_gated_long(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
   if constexpr (B == 128) {
     if (g.T > kLongWideTokens) return launch_stream_tw<B, true, 4, false, 8, true>(g, p, g.kdim, stream);
   }
-  if constexpr (B >= 64) return launch_stream_tw<B, true, 2, false, 4, true>(g, p, g.kdim, stream);
-  return launch_stream_tw<B, true, 4, false, 4, true>(g, p, g.kdim, stream);
+  if constexpr (B >= 64) {
+    return launch_stream_tw<B, true, 2, false, 4, true>(g, p, g.kdim, stream);
+  } else {
+    return launch_stream_tw<B, true, 4, false, 4, true>(g, p, g.kdim, stream);
+  }
 }
 
 // H = act(Wgate X) (.) (Wup X), or H = act(Wgate X) when Wup is null; bf16, strides given by (h_layout, ldh).
