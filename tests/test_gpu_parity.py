@@ -6,7 +6,7 @@ import pytest
 
 from oracle import oracle as orc
 from paper_2507_03117_amd import synth
-from tests.helpers import bits_of, check_close, mask_dev, to_dev
+from tests.helpers import bits_of, check_close, long_row_case, long_scratch_bytes, mask_dev, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -755,42 +755,6 @@ def test_mlp_decode_with_a_very_long_down_row(api, T):
         torch.cuda.synchronize()
         check_close(y.cpu().numpy().T, want, f"mlp long down row T={T}")
     assert not y.cpu().numpy()[:, 2 * b:3 * b].any()
-
-
-def long_row_case(rng, b, nbi=12, nbc=48):
-    """Gate/up masks with block rows that the 16-block chunk plan cuts - in gate only, in up only, in both, barely
-    (17 and 20 blocks) - next to empty and ordinary rows; a uniform down mask.  The weights of a block row are
-    scaled by its length, so that every row of H is of order one: bf16 rounds H on both sides, and one rounding
-    that falls the other way in an entry of 20 among entries of 0.1 would alone exceed the tolerance on Y."""
-    E, I = nbc * b, nbi * b
-    d = synth.gauss_bf16(rng, (E, I), 0.02)
-    mg, mu = (synth.uniform_mask(rng, nbi, nbc, 0.9) for _ in range(2))
-    md = synth.uniform_mask(rng, nbc, nbi, 0.6)
-    mg[0, :], mu[0, :] = 1, 0
-    mu[0, 5:8] = 1
-    mg[1, :], mu[1, :] = 0, 1
-    mg[1, 40:42] = 1
-    mg[2, :], mu[2, :] = 1, 1
-    mg[3, :], mu[3, :] = 0, 0
-    mg[3, 3:23], mu[3, 30:47] = 1, 1
-    mg[4, :], mu[4, :] = 0, 1
-    mg[5, :], mu[5, :] = 0, 0
-    g, u = (synth.f32_to_bf16_bits((rng.standard_normal((I, E)) *
-                                    np.repeat(0.8 / np.sqrt(np.maximum(m.sum(1), 1) * b), b)[:, None]).astype(np.float32))
-            for m in (mg, mu))
-    return E, I, (g, u, d), (mg, mu, md)
-
-
-def long_scratch_bytes(packed, b, T):
-    """fp32 scratch the MLP workspace carries for the cut rows of gate and up, per matrix T x b values for every
-    chunk of a cut row and for every cut row (the whole side of that row in the other matrix), counted by their
-    upper bounds: slots = the most rows that can hold more than 16 of the matrix' blocks, chunks <= nnz/16 + slots."""
-    total = 0
-    for m in packed:
-        slots = min(m.rows // b, m.nnz // (CHUNK + 1)) if m.max_row_blocks > CHUNK else 0
-        chunks = m.nnz // CHUNK + slots if slots else 0
-        total += -(-((chunks + slots) * b * T * 4) // 256) * 256
-    return total
 
 
 @pytest.mark.parametrize("b,T", [(32, 100), (64, 65), (64, 200), (64, 700), (128, 129), (128, 300)])
