@@ -149,15 +149,30 @@ int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32_t mode, do
  *               launch grid).
  *   ws          scratch of at least the ws_bytes reported by blast_bsr_pack_bound, 16-byte aligned
  *
- * The call synchronises `stream` once (to learn nnz); when it returns BLAST_OK
- * the remaining work is enqueued, not necessarily finished.
- * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, CAPACITY (row_ptr has
- * been written, col_idx/vals/row_order/aux have not), HIP.
+ * The call enqueues all its work and then synchronises `stream` once (to return nnz and max_row_blocks): when
+ * it returns, the outputs are complete and ws may be reused.
+ * Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, CAPACITY (row_ptr and row_order are complete,
+ * col_idx/vals hold the first nnz_cap blocks, the column-grouped index in aux has not been written), HIP.
  */
 int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
                    const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx, uint16_t* vals,
                    int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap, int64_t* nnz_out,
                    int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * blast_bsr_pack without the synchronisation, for re-packing many matrices in a row (Sec. 3.2: every
+ * step_size iterations the masks of all layers are regenerated and all weights are packed again).  Same
+ * arguments and outputs, except:
+ *   result      out [2] int32, 8-byte aligned, DEVICE: {number of stored blocks, stored blocks of the fullest
+ *               block row (0 without aux)}; the caller reads it after synchronising, once for all matrices.
+ * Only enqueues.  ws belongs to the call until the stream has passed its work; calls on the same stream may
+ * share one ws (the larger of their sizes).  When result[0] > nnz_cap the outputs are as blast_bsr_pack
+ * leaves them on BLAST_ERR_CAPACITY.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
+ */
+int blast_bsr_pack_enqueue(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
+                           const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx,
+                           uint16_t* vals, int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap,
+                           int32_t* result, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Dense form of a packed matrix: the pruned weight W_new that prune_weights() applies in the training loop of

@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 ACT = {"silu": 0, "gelu": 1, "relu": 2}
 
 EXPORTS = (
-    "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack",
+    "blast_strerror", "blast_n_keep", "blast_bsr_aux_bytes", "blast_bsr_pack_bound", "blast_bsr_pack", "blast_bsr_pack_enqueue",
     "blast_bsr_spmm", "blast_bsr_spmm_workspace", "blast_sparse_mlp", "blast_sparse_mlp_workspace",
     "blast_sparse_mlp_events", "blast_sparse_mlp2", "blast_sparse_mlp2_workspace", "blast_bsr_transpose", "blast_bsr_sddmm",
     "blast_generate_masks", "blast_generate_masks_workspace", "blast_sparsity_schedule",
@@ -73,6 +73,9 @@ def lib():
         L.blast_bsr_pack.restype = C.c_int
         L.blast_bsr_pack.argtypes = [vp, i64, i64, i64, i32, i32, vp, dbl, vp, vp, vp, vp, vp, sz, i64,
                                      C.POINTER(i64), C.POINTER(i32), vp, sz, vp]
+        L.blast_bsr_pack_enqueue.restype = C.c_int
+        L.blast_bsr_pack_enqueue.argtypes = [vp, i64, i64, i64, i32, i32, vp, dbl, vp, vp, vp, vp, vp, sz, i64,
+                                             vp, vp, sz, vp]
         L.blast_bsr_spmm.restype = C.c_int
         L.blast_bsr_spmm.argtypes = [pv, vp, i64, i32, i64, vp, i64, i32, vp, sz, vp]
         L.blast_bsr_spmm_workspace.restype = C.c_int
@@ -205,9 +208,59 @@ def bsr_pack(W: torch.Tensor, b: int, *, mask: Optional[torch.Tensor] = None, sp
     rc = L.blast_bsr_pack(_ptr(W), W.stride(0), rows, cols, b, mode, _ptr(mask), s, _ptr(row_ptr), _ptr(col_idx),
                           _ptr(vals), _ptr(row_order), _ptr(aux), aux_bytes if with_aux else 0, cap_v, C.byref(nnz),
                           C.byref(heavy), _ptr(ws), ws.numel(), _stream())
-    _check(rc, "blast_bsr_pack")
-    torch.cuda.current_stream().synchronize()  # ws is released on return
+    _check(rc, "blast_bsr_pack")  # (the call has synchronised the stream: ws can go)
     return PackedBsr(rows, cols, b, int(nnz.value), row_ptr, col_idx, vals, row_order, aux, int(heavy.value))
+
+
+def bsr_pack_many(Ws, b: int, *, masks=None, sparsity: Optional[float] = None, with_aux: bool = True):
+    """blast_bsr_pack_enqueue for every matrix of `Ws` (same block size; `masks` a list of block masks, or one
+    `sparsity` for the scoring mode), one shared scratch buffer, one synchronisation at the end: the re-packing
+    of all the weights of a model after a mask update."""
+    L = lib()
+    assert (masks is None) != (sparsity is None), "give exactly one of masks / sparsity"
+    mode = PACK_MASK if masks is not None else PACK_TOPK_FROBENIUS
+    s = 0.0 if sparsity is None else float(sparsity)
+    if not Ws:
+        return []
+    dev = Ws[0].device
+    bounds = []
+    for W in Ws:
+        assert W.is_cuda and W.dim() == 2 and W.stride(1) == 1 and W.element_size() == 2
+        cap, auxb, wsb = C.c_int64(0), C.c_size_t(0), C.c_size_t(0)
+        _check(L.blast_bsr_pack_bound(W.shape[0], W.shape[1], b, mode, s, C.byref(cap), C.byref(auxb), C.byref(wsb)),
+               "blast_bsr_pack_bound")
+        bounds.append((int(cap.value), int(auxb.value), int(wsb.value)))
+    ws = torch.empty(max(w for _, _, w in bounds), dtype=torch.uint8, device=dev)
+    result = torch.empty((len(Ws), 2), dtype=torch.int32, device=dev)
+    stream = _stream()
+    out = []
+    for i, W in enumerate(Ws):
+        rows, cols = W.shape
+        cap_v, aux_bytes, _ = bounds[i]
+        mask = masks[i] if masks is not None else None
+        if mask is not None:
+            assert mask.is_cuda and mask.dtype == torch.uint8 and mask.is_contiguous()
+        nbr = rows // b
+        o1 = (nbr + 1 + 3) // 4 * 4  # the three index arrays share one allocation, each 16-byte aligned
+        o2 = o1 + (max(nbr, 1) + 3) // 4 * 4
+        idx = torch.empty(o2 + max(cap_v, 1), dtype=torch.int32, device=dev)
+        row_ptr, row_order, col_idx = idx[:nbr + 1], idx[o1:o1 + max(nbr, 1)], idx[o2:]
+        vals = torch.empty(max(cap_v, 1) * b * b, dtype=torch.int16, device=dev)
+        aux = torch.empty(max(aux_bytes, 16), dtype=torch.uint8, device=dev) if with_aux else None
+        rc = L.blast_bsr_pack_enqueue(_ptr(W), W.stride(0), rows, cols, b, mode, _ptr(mask), s, _ptr(row_ptr),
+                                      _ptr(col_idx), _ptr(vals), _ptr(row_order), _ptr(aux),
+                                      aux_bytes if with_aux else 0, cap_v, result.data_ptr() + 8 * i, _ptr(ws),
+                                      ws.numel(), stream)
+        _check(rc, "blast_bsr_pack_enqueue")
+        out.append([rows, cols, row_ptr, col_idx, vals, row_order, aux, cap_v])
+    res = result.cpu()  # synchronises: every matrix is complete, ws can go
+    packed = []
+    for i, (rows, cols, row_ptr, col_idx, vals, row_order, aux, cap_v) in enumerate(out):
+        nnz, heavy = int(res[i, 0]), int(res[i, 1])
+        if nnz > cap_v:
+            _check(-4, "blast_bsr_pack_enqueue")
+        packed.append(PackedBsr(rows, cols, b, nnz, row_ptr, col_idx, vals, row_order, aux, heavy))
+    return packed
 
 
 def with_joint_row_order(gate: PackedBsr, up: PackedBsr) -> PackedBsr:

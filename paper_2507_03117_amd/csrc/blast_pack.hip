@@ -18,9 +18,20 @@ constexpr int kWave = 64;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
+// Workgroup barrier.  LDS_ONLY: only the workgroup's LDS traffic is ordered - global stores still in flight are
+// not waited for (the plain barrier waits for their acknowledgement, a trip to the memory side every time).
+template <bool LDS_ONLY>
+__device__ __forceinline__ void wg_barrier() {
+  if (LDS_ONLY)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else
+    __syncthreads();
+}
+
 // Exclusive scan of one int per thread over the whole workgroup (blockDim.x a
 // multiple of 64, at most 1024).  `wave_tot` is LDS scratch of >= 16 ints.
 // Returns the exclusive prefix; `total` receives the workgroup sum.
+template <bool LDS_ONLY = false>
 __device__ __forceinline__ int block_exscan(int v, int* wave_tot, int& total) {
   const int lane = lane_id(), wave = threadIdx.x / kWave, nw = blockDim.x / kWave;
   int inc = v;
@@ -29,9 +40,9 @@ __device__ __forceinline__ int block_exscan(int v, int* wave_tot, int& total) {
     int o = __shfl_up(inc, d, kWave);
     if (lane >= d) inc += o;
   }
-  __syncthreads();  // protect wave_tot from the previous use
+  wg_barrier<LDS_ONLY>();  // protect wave_tot from the previous use
   if (lane == kWave - 1) wave_tot[wave] = inc;
-  __syncthreads();
+  wg_barrier<LDS_ONLY>();
   int base = 0, tot = 0;
   for (int w = 0; w < nw; ++w) {
     int t = wave_tot[w];
@@ -98,6 +109,11 @@ __global__ __launch_bounds__(256) void k_pooled_scores(const float* __restrict__
 }
 
 __global__ void k_fill_u8(uint8_t* p, int64_t n, uint8_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+__global__ void k_fill_i32(int* p, int64_t n, int v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
@@ -317,11 +333,13 @@ __global__ __launch_bounds__(256) void k_fill_cols(const uint8_t* __restrict__ m
 
 // One workgroup per stored block: copy its b x b values, row-major, 16 bytes per lane.  A block whose mask
 // code is 2 (regrown, BLaST Sec. 3.2) is stored as zeros: it joins the structure without changing the product.
+// (The grid is sized by the capacity: workgroups past the number of stored blocks leave.)
 __global__ __launch_bounds__(256) void k_gather_blocks(const uint16_t* __restrict__ W, int64_t ldw, int b,
                                                        const int* __restrict__ col_idx, const int* __restrict__ blk_row,
                                                        const uint8_t* __restrict__ mask, int nbc,
-                                                       uint16_t* __restrict__ vals) {
+                                                       uint16_t* __restrict__ vals, const int* __restrict__ nnz_dev) {
   const int64_t k = blockIdx.x;
+  if (k >= *nnz_dev) return;
   const int64_t br = blk_row[k], bc = col_idx[k];
   const uint16_t* src = W + br * b * ldw + bc * b;
   uint16_t* dst = vals + k * b * b;
@@ -388,11 +406,19 @@ __global__ __launch_bounds__(256) void k_row_order(const int* __restrict__ row_p
 
 // One workgroup per block column: its stored blocks by ascending block row; for
 // each, the block row and the position k of the block in vals / col_idx.
+// csc_blk null: it follows csc_row at the next 16-byte boundary after nnz entries, nnz read from nnz_dev (the
+// layout of the aux buffer; nothing is written when nnz exceeds the capacity).
 __global__ __launch_bounds__(256) void k_fill_csc(const uint8_t* __restrict__ mask, int nbr, int nbc,
                                                   const int* __restrict__ row_ptr, const int* __restrict__ col_idx,
                                                   const int* __restrict__ col_ptr, int* __restrict__ csc_row,
-                                                  int* __restrict__ csc_blk, int64_t nnz_cap) {
+                                                  int* __restrict__ csc_blk, int64_t nnz_cap,
+                                                  const int* __restrict__ nnz_dev) {
   __shared__ int wave_tot[16];
+  if (!csc_blk) {
+    const int64_t nnz = *nnz_dev;
+    if (nnz > nnz_cap) return;
+    csc_blk = csc_row + (nnz + 3) / 4 * 4;
+  }
   const int c = blockIdx.x;
   const int start = col_ptr[c];
   int running = 0;
@@ -429,13 +455,15 @@ struct PlanOut {
   int* row_chunk0;  // may be null: per row, the index of its first chunk if it has several, else -1
 };
 
-// Single workgroup: cut the block rows, in schedule order, into chunks of at most `chunk` blocks, once per
-// requested plan.  An empty row still gets one (empty) chunk: its output has to be written.
-__global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row_ptr, const int* __restrict__ row_order,
-                                                     int nbr, PlanOut narrow, PlanOut wide,
-                                                     int* __restrict__ max_row_out) {
-  __shared__ int wave_tot[16];
-  __shared__ int s_running, s_heavy, s_split;
+// Cuts the block rows, in schedule order, into chunks of at most `chunk` blocks, once per requested plan; run by
+// every thread of one workgroup.  An empty row still gets one (empty) chunk: its output has to be written.
+// `sh` is LDS scratch of 3 ints.
+__device__ __forceinline__ void chunk_plans(const int* row_ptr, const int* row_order, int nbr, const PlanOut& narrow,
+                                            const PlanOut& wide, int* __restrict__ max_row_out, int* wave_tot,
+                                            int* sh) {
+  int& s_running = sh[0];
+  int& s_heavy = sh[1];
+  int& s_split = sh[2];
   for (int which = 0; which < 2; ++which) {
     const PlanOut o = which ? wide : narrow;
     const int chunk = o.chunk;
@@ -485,6 +513,15 @@ __global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row
   }
 }
 
+// Single workgroup: both chunk plans of a matrix.
+__global__ __launch_bounds__(1024) void k_chunk_plan(const int* __restrict__ row_ptr, const int* __restrict__ row_order,
+                                                     int nbr, PlanOut narrow, PlanOut wide,
+                                                     int* __restrict__ max_row_out) {
+  __shared__ int wave_tot[16];
+  __shared__ int sh[3];
+  chunk_plans(row_ptr, row_order, nbr, narrow, wide, max_row_out, wave_tot, sh);
+}
+
 // Both plans of a matrix, placed in its aux buffer.
 inline void plan_outputs(char* ab, const blast::AuxLayout& A, PlanOut& narrow, PlanOut& wide) {
   narrow = PlanOut{blast::kChunkBlocks, reinterpret_cast<int*>(ab + A.hdr_off), reinterpret_cast<int*>(ab + A.chunk_row_off),
@@ -493,6 +530,340 @@ inline void plan_outputs(char* ab, const blast::AuxLayout& A, PlanOut& narrow, P
   wide = PlanOut{blast::kWideChunkBlocks, reinterpret_cast<int*>(ab + A.whdr_off), reinterpret_cast<int*>(ab + A.wchunk_row_off),
                  reinterpret_cast<int*>(ab + A.wchunk_kb_off), reinterpret_cast<int*>(ab + A.wchunk_ke_off), A.wchunk_cap,
                  nullptr, nullptr};
+}
+
+// ---- small matrices: selection and every index array in one workgroup ----
+//
+// A layer-sized matrix has a few thousand blocks; scored, the rest of the packing is a few thousand integer
+// operations, and as a dozen dependent launches it costs a dozen launch latencies.  For at most kSmallN blocks
+// (and at most 1024 block rows and block columns) one workgroup does it all: a thread owns `per` consecutive
+// blocks in row-major order and keeps their keys in registers; the mask, the position of every stored block and
+// the per-line populations live in LDS.  The workgroup's 16 waves share one compute unit, so what the kernel
+// costs is instructions per thread: no integer division per block, both scans of a pair in one (two 16-bit
+// counts in one word: no sum here exceeds kSmallN + 1024), barriers that do not wait for global stores.
+constexpr int kSmallPer = 8;
+constexpr int kSmallN = 1024 * kSmallPer;
+static_assert(kSmallN + 1024 < 65536, "two counts share a 32-bit word");
+static_assert((blast::kChunkBlocks & (blast::kChunkBlocks - 1)) == 0 &&
+              (blast::kWideChunkBlocks & (blast::kWideChunkBlocks - 1)) == 0, "chunk sizes are powers of two");
+
+struct SmallOut {
+  int* row_ptr;
+  int* col_idx;
+  int* blk_row;
+  int* row_order;
+  uint8_t* mask_out;  // may be null (the caller's mask is the mask)
+  int* col_ptr;       // null without aux
+  int* csc_row;       // csc_blk follows at the next 16-byte boundary after nnz entries
+  int* scalars;       // {nnz, max_row_blocks}
+  int64_t nnz_cap;
+};
+
+template <bool TOPK>
+__global__ __launch_bounds__(1024) void k_pack_small(const double* __restrict__ score,
+                                                     const uint8_t* __restrict__ mask_in, int nbr, int nbc,
+                                                     long long n_keep, SmallOut o, PlanOut narrow, PlanOut wide) {
+  __shared__ int kpos[kSmallN];  // position of a stored block in col_idx / vals, by row-major block index
+  __shared__ uint8_t m[kSmallN];
+  __shared__ __attribute__((aligned(16))) int rcnt[1024];
+  __shared__ int ccnt[1024];
+  __shared__ int rptr[1025];
+  __shared__ int rord[1024];
+  __shared__ unsigned hist[256];
+  __shared__ int wave_tot[16];
+  __shared__ int sh[3];
+  __shared__ unsigned long long s_prefix, s_kth;
+  __shared__ long long s_remaining;
+  __shared__ unsigned s_h;
+  const int tid = threadIdx.x, lane = lane_id();
+  const int n = nbr * nbc;
+  const int per = (n + 1023) >> 10;  // blocks per thread (uniform); the loops below are unrolled to kSmallPer
+  const int e0 = tid * per;
+  rcnt[tid] = 0;
+  ccnt[tid] = 0;
+  unsigned keep = 0u;  // bit j: block e0 + j is kept
+  if (TOPK) {
+    unsigned long long key[kSmallPer];
+#pragma unroll
+    for (int j = 0; j < kSmallPer; ++j)
+      key[j] = (j < per && e0 + j < n) ? order_key(reinterpret_cast<const unsigned long long*>(score)[e0 + j]) : 0ull;
+    if (n_keep <= 0 || n_keep >= n) {
+#pragma unroll
+      for (int j = 0; j < kSmallPer; ++j) keep |= (j < per && e0 + j < n && n_keep > 0) ? 1u << j : 0u;
+    } else {
+      // Most-significant-digit radix select of the n_keep-th largest key.  Scores of one matrix share their
+      // leading bits (sign, exponent, often the first mantissa bits), and a digit that every key carries would
+      // send every count to one LDS word: the bits above the highest one in which any two keys differ are taken
+      // as they are, the passes start below them, eight bits at a time, and stop as soon as a single key
+      // carries the selected prefix.
+      unsigned long long diff = 0ull;
+      const unsigned long long key0 = order_key(reinterpret_cast<const unsigned long long*>(score)[0]);
+#pragma unroll
+      for (int j = 0; j < kSmallPer; ++j)
+        if (j < per && e0 + j < n) diff |= key[j] ^ key0;
+#pragma unroll
+      for (int d = kWave / 2; d > 0; d >>= 1) diff |= __shfl_xor(diff, d, kWave);
+      if (tid == 0) s_kth = 0ull;
+      wg_barrier<true>();
+      if (lane == 0 && diff != 0ull) atomicOr(&s_kth, diff);
+      wg_barrier<true>();
+      diff = s_kth;
+      int fixed = diff == 0ull ? 0 : 64 - __clzll(diff);  // bits at and above this position are decided
+      unsigned long long prefix = fixed == 64 ? 0ull : (key0 >> fixed) << fixed;
+      long long rem = n_keep;
+      unsigned eq_total = (unsigned)n;  // keys that carry the decided bits
+      while (fixed > 0) {
+        const int sft = fixed > 8 ? fixed - 8 : 0, width = fixed - sft;
+        if (tid < 256) hist[tid] = 0u;
+        wg_barrier<true>();
+#pragma unroll
+        for (int j = 0; j < kSmallPer; ++j) {
+          if (j < per) {
+            const bool in = e0 + j < n && (fixed == 64 || (key[j] >> fixed) == (prefix >> fixed));
+            if (in) atomicAdd(&hist[(unsigned)(key[j] >> sft) & ((1u << width) - 1u)], 1u);
+          }
+        }
+        wg_barrier<true>();
+        if (tid < kWave) {
+          // lane l looks at bins 255 - 4l ... 252 - 4l; `larger` = keys in bins above the one looked at
+          unsigned h4[4], sum = 0u;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            h4[u] = hist[255 - 4 * lane - u];
+            sum += h4[u];
+          }
+          unsigned inc = sum;
+#pragma unroll
+          for (int d = 1; d < kWave; d <<= 1) {
+            const unsigned v = __shfl_up(inc, d, kWave);
+            if (lane >= d) inc += v;
+          }
+          long long larger = (long long)(inc - sum);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const long long h = h4[u];
+            if (larger < rem && rem <= larger + h) {
+              s_remaining = rem - larger;
+              s_prefix = prefix | ((unsigned long long)(255 - 4 * lane - u) << sft);
+              s_h = (unsigned)h;
+            }
+            larger += h;
+          }
+        }
+        wg_barrier<true>();
+        prefix = s_prefix;
+        rem = s_remaining;
+        eq_total = s_h;
+        fixed = sft;
+        if (eq_total == 1u && fixed > 0) {
+#pragma unroll
+          for (int j = 0; j < kSmallPer; ++j)
+            if (j < per && e0 + j < n && (key[j] >> fixed) == (prefix >> fixed)) s_kth = key[j];
+          wg_barrier<true>();
+          prefix = s_kth;
+          break;
+        }
+      }
+      const unsigned long long kth = prefix;
+      if (rem == (long long)eq_total) {
+#pragma unroll
+        for (int j = 0; j < kSmallPer; ++j) keep |= (j < per && e0 + j < n && key[j] >= kth) ? 1u << j : 0u;
+      } else {
+        // of the keys equal to the threshold the first `rem` in index order are kept
+        int neq = 0;
+#pragma unroll
+        for (int j = 0; j < kSmallPer; ++j) neq += (j < per && e0 + j < n && key[j] == kth) ? 1 : 0;
+        int total;
+        long long pos = block_exscan<true>(neq, wave_tot, total);
+#pragma unroll
+        for (int j = 0; j < kSmallPer; ++j) {
+          if (j < per && e0 + j < n) {
+            const bool eq = key[j] == kth;
+            if (key[j] > kth || (eq && pos < rem)) keep |= 1u << j;
+            pos += eq ? 1 : 0;
+          }
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kSmallPer; ++j) keep |= (j < per && e0 + j < n && mask_in[e0 + j] != 0) ? 1u << j : 0u;
+  }
+
+  // stored blocks in row-major order: the position of a block is the number of kept blocks before it
+  int nnz;
+  int k = block_exscan<true>(__popc(keep), wave_tot, nnz);  // (its barriers also cover the clearing of rcnt / ccnt)
+  {
+    int r = e0 / nbc, c = e0 - r * nbc;
+#pragma unroll
+    for (int j = 0; j < kSmallPer; ++j) {
+      if (j < per && e0 + j < n) {
+        const bool kp = (keep >> j) & 1u;
+        m[e0 + j] = kp ? 1 : 0;
+        if (o.mask_out) o.mask_out[e0 + j] = kp ? 1 : 0;
+        if (kp) {
+          kpos[e0 + j] = k;
+          if (k < o.nnz_cap) {
+            o.col_idx[k] = c;
+            o.blk_row[k] = r;
+          }
+          atomicAdd(&rcnt[r], 1);
+          atomicAdd(&ccnt[c], 1);
+          ++k;
+        }
+        if (++c == nbc) {
+          c = 0;
+          ++r;
+        }
+      }
+    }
+  }
+  wg_barrier<true>();
+
+  // row pointers and column pointers: one scan of both populations
+  {
+    const int v = (tid < nbr ? rcnt[tid] : 0) | ((tid < nbc ? ccnt[tid] : 0) << 16);
+    int total;
+    const int ex = block_exscan<true>(v, wave_tot, total);
+    if (tid < nbr) {
+      rptr[tid] = ex & 0xFFFF;
+      o.row_ptr[tid] = ex & 0xFFFF;
+    }
+    if (o.col_ptr && tid < nbc) o.col_ptr[tid] = ex >> 16;
+    if (tid == 0) {
+      rptr[nbr] = nnz;
+      o.row_ptr[nbr] = nnz;
+      if (o.col_ptr) o.col_ptr[nbc] = nnz;
+      o.scalars[0] = nnz;
+      if (!o.col_ptr) o.scalars[1] = 0;
+    }
+  }
+  // schedule: rows by population, descending, stable.  P threads share a row, each comparing it with a
+  // contiguous part of the rows (four populations per LDS read; the array is zero beyond nbr, which never counts).
+  {
+    const int pl = 31 - __clz(1024 / nbr);         // log2 P, P = largest power of two <= 1024 / nbr ...
+    const int lp = pl > 6 ? 6 : pl, P = 1 << lp;   // ... and <= 64, so that the P threads sit in one wave
+    const int r = tid >> lp, part = tid & (P - 1);
+    const int len = (((nbr + P - 1) >> lp) + 3) & ~3;
+    const int cr = r < nbr ? rcnt[r] : 0;
+    int rank = 0;
+    const int q0 = part * len;
+#pragma unroll 4
+    for (int q = q0; q < q0 + len; q += 4) {
+      const int4 c4 = *reinterpret_cast<const int4*>(&rcnt[q]);
+      rank += (c4.x > cr || (c4.x == cr && q < r)) ? 1 : 0;
+      rank += (c4.y > cr || (c4.y == cr && q + 1 < r)) ? 1 : 0;
+      rank += (c4.z > cr || (c4.z == cr && q + 2 < r)) ? 1 : 0;
+      rank += (c4.w > cr || (c4.w == cr && q + 3 < r)) ? 1 : 0;
+    }
+    for (int d = P >> 1; d > 0; d >>= 1) rank += __shfl_xor(rank, d, kWave);
+    if (r < nbr && part == 0) {
+      rord[rank] = r;
+      o.row_order[rank] = r;
+    }
+  }
+  wg_barrier<true>();
+  if (!o.col_ptr) return;
+
+  // both chunk plans: rows in schedule order, cut into chunks of at most 16 / 64 blocks (an empty row still gets
+  // one chunk: its output has to be written)
+  {
+    if (tid == 0) {
+      sh[0] = 0;  // fullest row
+      sh[1] = 0;  // chunks of the rows that the first plan cuts
+      sh[2] = 0;  // ... the second plan
+    }
+    wg_barrier<true>();
+    constexpr int ls0 = __builtin_ctz(blast::kChunkBlocks), ls1 = __builtin_ctz(blast::kWideChunkBlocks);
+    int r = 0, kb = 0, ke = 0, n0 = 0, n1 = 0;
+    if (tid < nbr) {
+      r = rord[tid];
+      kb = rptr[r];
+      ke = rptr[r + 1];
+      n0 = (ke - kb + (1 << ls0) - 1) >> ls0;
+      n1 = (ke - kb + (1 << ls1) - 1) >> ls1;
+      n0 = n0 < 1 ? 1 : n0;
+      n1 = n1 < 1 ? 1 : n1;
+      atomicMax(&sh[0], ke - kb);
+      if (n0 > 1) atomicAdd(&sh[1], n0);
+      if (n1 > 1) atomicAdd(&sh[2], n1);
+      narrow.row_slot[r] = n0 > 1 ? tid : -1;
+    }
+    int total;
+    const int first = block_exscan<true>(n0 | (n1 << 16), wave_tot, total);
+    if (tid < nbr) {
+      const int f0 = first & 0xFFFF, f1 = first >> 16;
+      narrow.row_chunk0[r] = n0 > 1 ? f0 : -1;
+      for (int j = 0; j < n0; ++j) {
+        const int e = f0 + j, b0 = kb + (j << ls0);
+        if (e < narrow.cap) {
+          narrow.chunk_row[e] = r | (n0 > 1 ? (int)0x80000000u : 0);
+          narrow.chunk_kb[e] = b0;
+          narrow.chunk_ke[e] = (b0 + (1 << ls0) < ke) ? b0 + (1 << ls0) : ke;
+        }
+      }
+      for (int j = 0; j < n1; ++j) {
+        const int e = f1 + j, b0 = kb + (j << ls1);
+        if (e < wide.cap) {
+          wide.chunk_row[e] = r | (n1 > 1 ? (int)0x80000000u : 0);
+          wide.chunk_kb[e] = b0;
+          wide.chunk_ke[e] = (b0 + (1 << ls1) < ke) ? b0 + (1 << ls1) : ke;
+        }
+      }
+    }
+    if (tid == 0) {
+      const int heavy = sh[0];
+      narrow.hdr[0] = total & 0xFFFF;
+      narrow.hdr[1] = heavy;
+      narrow.hdr[2] = 1 << ls0;
+      narrow.hdr[3] = sh[1];
+      wide.hdr[0] = total >> 16;
+      wide.hdr[1] = heavy;
+      wide.hdr[2] = 1 << ls1;
+      wide.hdr[3] = sh[2];
+      o.scalars[1] = heavy;
+    }
+  }
+
+  // column-grouped index: the same count with the blocks taken in column-major order
+  if (nnz > o.nnz_cap) return;
+  {
+    int* csc_blk = o.csc_row + (nnz + 3) / 4 * 4;
+    unsigned keep_c = 0u;
+    const int c0 = e0 / nbr, r0 = e0 - c0 * nbr;
+    {
+      int r = r0, at = r0 * nbc + c0;
+#pragma unroll
+      for (int j = 0; j < kSmallPer; ++j) {
+        if (j < per && e0 + j < n) {
+          keep_c |= m[at] ? 1u << j : 0u;
+          at += nbc;
+          if (++r == nbr) {
+            r = 0;
+            at = at - n + 1;  // top of the next column
+          }
+        }
+      }
+    }
+    int total;
+    int e = block_exscan<true>(__popc(keep_c), wave_tot, total);
+    int r = r0, at = r0 * nbc + c0;
+#pragma unroll
+    for (int j = 0; j < kSmallPer; ++j) {
+      if (j < per && e0 + j < n) {
+        if ((keep_c >> j) & 1u) {
+          o.csc_row[e] = r;
+          csc_blk[e] = kpos[at];
+          ++e;
+        }
+        at += nbc;
+        if (++r == nbr) {
+          r = 0;
+          at = at - n + 1;
+        }
+      }
+    }
+  }
 }
 
 // One workgroup per stored block of the transposed matrix: block e of the output is the transpose of
@@ -614,14 +985,19 @@ extern "C" int blast_bsr_pack_bound(int64_t rows, int64_t cols, int32_t b, int32
   return BLAST_OK;
 }
 
-extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
-                              const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx,
-                              uint16_t* vals, int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap,
-                              int64_t* nnz_out, int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream_) {
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
+namespace {
+
+// Validates the arguments of a packing call and enqueues all of its work.  The two result scalars {number of
+// stored blocks, stored blocks of the fullest row} are left at *scalars_out (device memory: `result` when the
+// caller gave one, else a slot of the workspace); n_keep_out gets the number of blocks the scoring mode keeps
+// (-1 in mask mode).
+int pack_enqueue(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
+                 const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx, uint16_t* vals,
+                 int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap, int32_t* result, void* ws,
+                 size_t ws_bytes, hipStream_t stream, int** scalars_out) {
   if (mode != BLAST_PACK_MASK && mode != BLAST_PACK_TOPK_FROBENIUS) return BLAST_ERR_INVALID_ARG;
   if (int rc = check_shape(rows, cols, b)) return rc;
-  if (!row_ptr || !nnz_out || nnz_cap < 0) return BLAST_ERR_INVALID_ARG;
+  if (!row_ptr || nnz_cap < 0) return BLAST_ERR_INVALID_ARG;
   const int64_t nbr = rows / b, nbc = cols / b, n = nbr * nbc;
   if (n > 0 && (!W || ldw < cols || ldw % 8 || !blast::aligned(W, 16))) return BLAST_ERR_INVALID_ARG;
   if (mode == BLAST_PACK_MASK && n > 0 && !block_mask) return BLAST_ERR_INVALID_ARG;
@@ -636,53 +1012,122 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
   if (!ws || ws_bytes < L.bytes || !blast::aligned(ws, 16)) return BLAST_ERR_WORKSPACE;
   const blast::AuxLayout A = blast::aux_layout(nbr, nbc, nnz_cap);
   if (aux && (aux_bytes < A.bytes || !blast::aligned(aux, 16))) return BLAST_ERR_WORKSPACE;
+  const int64_t gather_grid = (mode == BLAST_PACK_TOPK_FROBENIUS && n_keep < nnz_cap) ? n_keep : nnz_cap;
+  if (gather_grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
 
   char* wsb = static_cast<char*>(ws);
   double* scores = reinterpret_cast<double*>(wsb + L.scores_off);
   int* rcnt = reinterpret_cast<int*>(wsb + L.rcnt_off);
   int* ccnt = reinterpret_cast<int*>(wsb + L.ccnt_off);
   int* blk_row = reinterpret_cast<int*>(wsb + L.blk_row_off);
-  int* nnz_dev = reinterpret_cast<int*>(wsb + L.scalars_off);
+  int* nnz_dev = result ? result : reinterpret_cast<int*>(wsb + L.scalars_off);
+  *scalars_out = nnz_dev;
   const uint8_t* mask = block_mask;
+  uint8_t* m = mode == BLAST_PACK_TOPK_FROBENIUS ? reinterpret_cast<uint8_t*>(wsb + L.mask_off) : nullptr;
+  if (m) mask = m;
+  char* ab = static_cast<char*>(aux);
+  PlanOut narrow{}, wide{};
+  if (aux) plan_outputs(ab, A, narrow, wide);
+  int* col_ptr = aux ? reinterpret_cast<int*>(ab + A.col_ptr_off) : nullptr;  // (this offset does not depend on nnz)
+  int* csc_row = aux ? reinterpret_cast<int*>(ab + A.csc_row_off) : nullptr;
+  const bool scored = mode == BLAST_PACK_TOPK_FROBENIUS && n > 0 && n_keep > 0 && n_keep < n;
+  if (scored) {
+    k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(W, ldw, (int)nbc, b, scores);
+    BLAST_LAUNCH_CHECK("k_block_scores");
+  }
 
-  if (mode == BLAST_PACK_TOPK_FROBENIUS) {
-    uint8_t* m = reinterpret_cast<uint8_t*>(wsb + L.mask_off);
-    mask = m;
-    if (n > 0) {
-      if (n_keep == 0 || n_keep == n) {
+  if (n > 0 && n <= kSmallN && nbr <= 1024 && nbc <= 1024) {
+    // selection, row pointers, column indices, schedule, chunk plans and column-grouped index: one launch
+    const SmallOut o{row_ptr, col_idx, blk_row, row_order, m, col_ptr, csc_row, nnz_dev, nnz_cap};
+    if (mode == BLAST_PACK_TOPK_FROBENIUS)
+      k_pack_small<true><<<dim3(1), dim3(1024), 0, stream>>>(scores, nullptr, (int)nbr, (int)nbc, (long long)n_keep, o,
+                                                             narrow, wide);
+    else
+      k_pack_small<false><<<dim3(1), dim3(1024), 0, stream>>>(nullptr, mask, (int)nbr, (int)nbc, 0ll, o, narrow, wide);
+    BLAST_LAUNCH_CHECK("k_pack_small");
+  } else {
+    if (m && n > 0) {
+      if (!scored) {
         k_fill_u8<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(m, n, n_keep == n ? 1 : 0);
         BLAST_LAUNCH_CHECK("k_fill_u8");
       } else {
-        k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(W, ldw, (int)nbc, b, scores);
-        BLAST_LAUNCH_CHECK("k_block_scores");
         k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, m);
         BLAST_LAUNCH_CHECK("k_select_topk");
       }
     }
+    if (nbr > 0) {
+      k_line_counts<<<dim3((unsigned)((nbr + 3) / 4)), dim3(256), 0, stream>>>(mask, (int)nbr, (int)nbc, nbc, 1, rcnt);
+      BLAST_LAUNCH_CHECK("k_line_counts(rows)");
+    }
+    k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(rcnt, (int)nbr, row_ptr, nnz_dev);
+    BLAST_LAUNCH_CHECK("k_exscan(rows)");
+    if (nbr > 0) {
+      k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, nullptr, (int)nbr, row_order);
+      BLAST_LAUNCH_CHECK("k_row_order");
+    }
+    if (aux) {
+      k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr, row_order, (int)nbr, narrow, wide, nnz_dev + 1);
+      BLAST_LAUNCH_CHECK("k_chunk_plan");
+    } else {
+      k_fill_i32<<<dim3(1), dim3(64), 0, stream>>>(nnz_dev + 1, 1, 0);
+      BLAST_LAUNCH_CHECK("k_fill_i32");
+    }
+    if (nbr > 0) {
+      k_fill_cols<<<dim3((unsigned)nbr), dim3(256), 0, stream>>>(mask, (int)nbc, row_ptr, col_idx, blk_row, nnz_cap);
+      BLAST_LAUNCH_CHECK("k_fill_cols");
+    }
+    if (aux) {
+      if (nbc > 0 && nbr > 0) {
+        k_line_counts<<<dim3((unsigned)((nbc + 3) / 4)), dim3(256), 0, stream>>>(mask, (int)nbc, (int)nbr, 1, nbc, ccnt);
+        BLAST_LAUNCH_CHECK("k_line_counts(cols)");
+      } else if (nbc > 0) {
+        k_fill_i32<<<dim3((unsigned)((nbc + 255) / 256)), dim3(256), 0, stream>>>(ccnt, nbc, 0);
+        BLAST_LAUNCH_CHECK("k_fill_i32(cols)");
+      }
+      k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(ccnt, (int)nbc, col_ptr, nullptr);
+      BLAST_LAUNCH_CHECK("k_exscan(cols)");
+      if (nbc > 0 && nbr > 0 && nnz_cap > 0) {
+        k_fill_csc<<<dim3((unsigned)nbc), dim3(256), 0, stream>>>(mask, (int)nbr, (int)nbc, row_ptr, col_idx, col_ptr,
+                                                                  csc_row, nullptr, nnz_cap, nnz_dev);
+        BLAST_LAUNCH_CHECK("k_fill_csc");
+      }
+    }
   }
+  // Nothing needs the number of stored blocks on the host: the gather's grid is the capacity (workgroups past
+  // the device's count leave), and the column-grouped index is placed by the device's count.
+  if (gather_grid > 0) {
+    k_gather_blocks<<<dim3((unsigned)gather_grid), dim3(256), 0, stream>>>(W, ldw, b, col_idx, blk_row, mask, (int)nbc,
+                                                                         vals, nnz_dev);
+    BLAST_LAUNCH_CHECK("k_gather_blocks");
+  }
+  return BLAST_OK;
+}
 
-  if (nbr > 0) {
-    k_line_counts<<<dim3((unsigned)((nbr + 3) / 4)), dim3(256), 0, stream>>>(mask, (int)nbr, (int)nbc, nbc, 1, rcnt);
-    BLAST_LAUNCH_CHECK("k_line_counts(rows)");
-  }
-  k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(rcnt, (int)nbr, row_ptr, nnz_dev);
-  BLAST_LAUNCH_CHECK("k_exscan(rows)");
-  // The schedule and the chunk plan depend on the populations only: they are written before the
-  // synchronisation so that the longest row's length comes back to the host with nnz.
-  int host_vals[2] = {0, 0};
-  if (nbr > 0) {
-    k_row_order<<<dim3((unsigned)((nbr + 255) / 256)), dim3(256), 0, stream>>>(row_ptr, nullptr, (int)nbr, row_order);
-    BLAST_LAUNCH_CHECK("k_row_order");
-  }
-  if (aux) {
-    char* ab = static_cast<char*>(aux);
-    PlanOut narrow, wide;
-    plan_outputs(ab, A, narrow, wide);
-    k_chunk_plan<<<dim3(1), dim3(1024), 0, stream>>>(row_ptr, row_order, (int)nbr, narrow, wide, nnz_dev + 1);
-    BLAST_LAUNCH_CHECK("k_chunk_plan");
-  }
+}  // namespace
+
+extern "C" int blast_bsr_pack_enqueue(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b,
+                                      int32_t mode, const uint8_t* block_mask, double sparsity, int32_t* row_ptr,
+                                      int32_t* col_idx, uint16_t* vals, int32_t* row_order, void* aux, size_t aux_bytes,
+                                      int64_t nnz_cap, int32_t* result, void* ws, size_t ws_bytes, void* stream_) {
+  if (!result || !blast::aligned(result, 8)) return BLAST_ERR_INVALID_ARG;
+  int* scalars = nullptr;
+  return pack_enqueue(W, ldw, rows, cols, b, mode, block_mask, sparsity, row_ptr, col_idx, vals, row_order, aux,
+                      aux_bytes, nnz_cap, result, ws, ws_bytes, static_cast<hipStream_t>(stream_), &scalars);
+}
+
+extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, int32_t b, int32_t mode,
+                              const uint8_t* block_mask, double sparsity, int32_t* row_ptr, int32_t* col_idx,
+                              uint16_t* vals, int32_t* row_order, void* aux, size_t aux_bytes, int64_t nnz_cap,
+                              int64_t* nnz_out, int32_t* max_row_blocks_out, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!nnz_out) return BLAST_ERR_INVALID_ARG;
+  int* scalars = nullptr;
+  if (int rc = pack_enqueue(W, ldw, rows, cols, b, mode, block_mask, sparsity, row_ptr, col_idx, vals, row_order, aux,
+                            aux_bytes, nnz_cap, nullptr, ws, ws_bytes, stream, &scalars))
+    return rc;
   // The two scalars come back through a small pinned buffer (one per host thread, allocated on first use
   // and kept): a copy into pageable memory costs the call tens of microseconds more.
+  int host_vals[2] = {0, 0};
   static thread_local int* pinned = nullptr;
   if (!pinned) {
     void* p = nullptr;
@@ -693,43 +1138,13 @@ extern "C" int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int6
     }
   }
   int* landing = pinned ? pinned : host_vals;
-  BLAST_HIP_TRY(hipMemcpyAsync(landing, nnz_dev, (aux ? 2 : 1) * sizeof(int), hipMemcpyDeviceToHost, stream));
+  BLAST_HIP_TRY(hipMemcpyAsync(landing, scalars, 2 * sizeof(int), hipMemcpyDeviceToHost, stream));
   BLAST_HIP_TRY(hipStreamSynchronize(stream));
   host_vals[0] = landing[0];
-  if (aux) host_vals[1] = landing[1];
-  const int nnz_host = host_vals[0];
-  *nnz_out = nnz_host;
+  host_vals[1] = landing[1];
+  *nnz_out = host_vals[0];
   if (max_row_blocks_out) *max_row_blocks_out = aux ? host_vals[1] : 0;
-  if (nnz_host > nnz_cap) return BLAST_ERR_CAPACITY;
-
-  if (nbr > 0) {
-    k_fill_cols<<<dim3((unsigned)nbr), dim3(256), 0, stream>>>(mask, (int)nbc, row_ptr, col_idx, blk_row, nnz_cap);
-    BLAST_LAUNCH_CHECK("k_fill_cols");
-  }
-  if (nnz_host > 0) {
-    k_gather_blocks<<<dim3((unsigned)nnz_host), dim3(256), 0, stream>>>(W, ldw, b, col_idx, blk_row, mask, (int)nbc, vals);
-    BLAST_LAUNCH_CHECK("k_gather_blocks");
-  }
-  if (aux) {
-    char* ab = static_cast<char*>(aux);
-    const blast::AuxLayout An = blast::aux_layout(nbr, nbc, nnz_host);  // the index is placed by the actual nnz
-    int* col_ptr = reinterpret_cast<int*>(ab + An.col_ptr_off);
-    int* csc_row = reinterpret_cast<int*>(ab + An.csc_row_off);
-    int* csc_blk = reinterpret_cast<int*>(ab + An.csc_blk_off);
-    if (nbc > 0 && nbr > 0) {
-      k_line_counts<<<dim3((unsigned)((nbc + 3) / 4)), dim3(256), 0, stream>>>(mask, (int)nbc, (int)nbr, 1, nbc, ccnt);
-      BLAST_LAUNCH_CHECK("k_line_counts(cols)");
-    } else if (nbc > 0) {
-      BLAST_HIP_TRY(hipMemsetAsync(ccnt, 0, sizeof(int) * (size_t)nbc, stream));
-    }
-    k_exscan<<<dim3(1), dim3(1024), 0, stream>>>(ccnt, (int)nbc, col_ptr, nullptr);
-    BLAST_LAUNCH_CHECK("k_exscan(cols)");
-    if (nbc > 0 && nnz_host > 0) {
-      k_fill_csc<<<dim3((unsigned)nbc), dim3(256), 0, stream>>>(mask, (int)nbr, (int)nbc, row_ptr, col_idx, col_ptr,
-                                                                csc_row, csc_blk, nnz_cap);
-      BLAST_LAUNCH_CHECK("k_fill_csc");
-    }
-  }
+  if (host_vals[0] > nnz_cap) return BLAST_ERR_CAPACITY;
   return BLAST_OK;
 }
 

@@ -194,6 +194,63 @@ def test_pack_strided_weight_and_capacity_error(api):
     torch.cuda.synchronize()
 
 
+def _assert_packed_equal(dev, ref, b):
+    assert dev.nnz == ref.nnz
+    assert np.array_equal(dev.row_ptr.cpu().numpy(), ref.row_ptr)
+    assert np.array_equal(dev.col_idx.cpu().numpy()[: ref.nnz], ref.col_idx)
+    assert np.array_equal(bits_of(dev.vals)[: ref.nnz * b * b].reshape(ref.nnz, b, b), ref.vals)
+    assert np.array_equal(dev.row_order.cpu().numpy()[: ref.row_order.size], ref.row_order)
+    assert dev.max_row_blocks == int(np.diff(ref.row_ptr).max())
+    check_aux(dev, ref)
+
+
+@pytest.mark.parametrize("nbr,nbc", [(64, 128), (1, 8192), (8192, 1), (1024, 8), (3, 1024), (65, 128), (2, 1100),
+                                     (1025, 4)])
+def test_pack_single_workgroup_limits(api, nbr, nbc):
+    """Up to 8192 blocks with at most 1024 block rows and columns one workgroup writes every index array; the cases
+    sit on both sides of each of the three limits."""
+    rng = np.random.default_rng(220 + nbr)
+    b = 16
+    W = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.02)
+    dev, ref = pack_both(api, W, b, sparsity=0.9)
+    _assert_packed_equal(dev, ref, b)
+    mask = synth.uniform_mask(rng, nbr, nbc, 0.8)
+    dev, ref = pack_both(api, W, b, mask=mask)
+    _assert_packed_equal(dev, ref, b)
+
+
+@pytest.mark.parametrize("sparsity", [0.3, 0.75, 0.97])
+def test_pack_single_workgroup_massive_ties(api, sparsity):
+    """6400 blocks with three distinct scores: the threshold is a tie that the index order cuts."""
+    rng = np.random.default_rng(212)
+    b, nbr, nbc = 16, 64, 100
+    proto = synth.gauss_bf16(rng, (3, b, b), 0.02)
+    which = rng.integers(0, 3, size=(nbr, nbc))
+    W = np.ascontiguousarray(proto[which].transpose(0, 2, 1, 3).reshape(nbr * b, nbc * b))
+    ref_mask, _ = orc.topk_mask(orc.block_scores(W, b), sparsity)
+    ref = orc.pack(W, b, ref_mask)
+    dev = api.bsr_pack(to_dev(W), b, sparsity=sparsity)
+    _assert_packed_equal(dev, ref, b)
+
+
+def test_pack_many_matches_single_calls(api):
+    """blast_bsr_pack_enqueue: three matrices of different shapes packed back to back with one shared scratch
+    buffer and one synchronisation, in both modes; one of them takes the many-launch path."""
+    rng = np.random.default_rng(230)
+    b = 32
+    shapes = [(128 * b, 32 * b), (32 * b, 128 * b), (96 * b, 100 * b)]
+    Ws = [synth.gauss_bf16(rng, sh, 0.02) for sh in shapes]
+    devs = api.bsr_pack_many([to_dev(W) for W in Ws], b, sparsity=0.9)
+    for W, dev in zip(Ws, devs):
+        ref, _, gap = orc.pack_topk(W, b, 0.9)
+        assert gap > 1e-9
+        _assert_packed_equal(dev, ref, b)
+    masks = [synth.uniform_mask(rng, sh[0] // b, sh[1] // b, 0.85) for sh in shapes]
+    devs = api.bsr_pack_many([to_dev(W) for W in Ws], b, masks=[mask_dev(m) for m in masks])
+    for W, m, dev in zip(Ws, masks, devs):
+        _assert_packed_equal(dev, orc.pack(W, b, m), b)
+
+
 # ------------------------------------------------------------------ SpMM
 @pytest.mark.parametrize("b", [16, 32, 64, 128])
 @pytest.mark.parametrize("T", [1, 3, 17, 64, 100, 300])
