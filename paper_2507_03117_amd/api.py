@@ -214,8 +214,9 @@ def bsr_pack(W: torch.Tensor, b: int, *, mask: Optional[torch.Tensor] = None, sp
 
 def bsr_pack_many(Ws, b: int, *, masks=None, sparsity: Optional[float] = None, with_aux: bool = True):
     """blast_bsr_pack_enqueue for every matrix of `Ws` (same block size; `masks` a list of block masks, or one
-    `sparsity` for the scoring mode), one shared scratch buffer, one synchronisation at the end: the re-packing
-    of all the weights of a model after a mask update."""
+    `sparsity` for the scoring mode): the re-packing of all the weights of a model after a mask update.  One
+    allocation holds the outputs of all matrices, one scratch buffer serves them in turn, and the host
+    synchronises once, at the end; the tensors of the results are views into that allocation."""
     L = lib()
     assert (masks is None) != (sparsity is None), "give exactly one of masks / sparsity"
     mode = PACK_MASK if masks is not None else PACK_TOPK_FROBENIUS
@@ -223,40 +224,47 @@ def bsr_pack_many(Ws, b: int, *, masks=None, sparsity: Optional[float] = None, w
     if not Ws:
         return []
     dev = Ws[0].device
-    bounds = []
+    cap, auxb, wsb = C.c_int64(0), C.c_size_t(0), C.c_size_t(0)
+    total, ws_max, plans = 0, 0, []
     for W in Ws:
         assert W.is_cuda and W.dim() == 2 and W.stride(1) == 1 and W.element_size() == 2
-        cap, auxb, wsb = C.c_int64(0), C.c_size_t(0), C.c_size_t(0)
-        _check(L.blast_bsr_pack_bound(W.shape[0], W.shape[1], b, mode, s, C.byref(cap), C.byref(auxb), C.byref(wsb)),
-               "blast_bsr_pack_bound")
-        bounds.append((int(cap.value), int(auxb.value), int(wsb.value)))
-    ws = torch.empty(max(w for _, _, w in bounds), dtype=torch.uint8, device=dev)
-    result = torch.empty((len(Ws), 2), dtype=torch.int32, device=dev)
-    stream = _stream()
-    out = []
-    for i, W in enumerate(Ws):
         rows, cols = W.shape
-        cap_v, aux_bytes, _ = bounds[i]
+        _check(L.blast_bsr_pack_bound(rows, cols, b, mode, s, C.byref(cap), C.byref(auxb), C.byref(wsb)),
+               "blast_bsr_pack_bound")
+        cap_v, aux_bytes, nbr = int(cap.value), int(auxb.value), rows // b
+        ws_max = max(ws_max, int(wsb.value))
+        sizes = (4 * (nbr + 1), 4 * max(nbr, 1), 4 * max(cap_v, 1), max(aux_bytes, 16) if with_aux else 0,
+                 2 * max(cap_v, 1) * b * b)
+        offs = []
+        for nbytes in sizes:  # row_ptr, row_order, col_idx, aux, vals: each on a 256-byte boundary
+            offs.append(total)
+            total += (nbytes + 255) // 256 * 256
+        plans.append((rows, cols, cap_v, aux_bytes, sizes, offs))
+    arena = torch.empty(total, dtype=torch.uint8, device=dev)
+    ws = torch.empty(ws_max, dtype=torch.uint8, device=dev)
+    result = torch.empty((len(Ws), 2), dtype=torch.int32, device=dev)
+    base, ws_p, res_p, stream = arena.data_ptr(), ws.data_ptr(), result.data_ptr(), _stream()
+    for i, W in enumerate(Ws):
+        rows, cols, cap_v, aux_bytes, sizes, (o_rp, o_ro, o_ci, o_aux, o_vals) = plans[i]
         mask = masks[i] if masks is not None else None
         if mask is not None:
             assert mask.is_cuda and mask.dtype == torch.uint8 and mask.is_contiguous()
-        nbr = rows // b
-        o1 = (nbr + 1 + 3) // 4 * 4  # the three index arrays share one allocation, each 16-byte aligned
-        o2 = o1 + (max(nbr, 1) + 3) // 4 * 4
-        idx = torch.empty(o2 + max(cap_v, 1), dtype=torch.int32, device=dev)
-        row_ptr, row_order, col_idx = idx[:nbr + 1], idx[o1:o1 + max(nbr, 1)], idx[o2:]
-        vals = torch.empty(max(cap_v, 1) * b * b, dtype=torch.int16, device=dev)
-        aux = torch.empty(max(aux_bytes, 16), dtype=torch.uint8, device=dev) if with_aux else None
-        rc = L.blast_bsr_pack_enqueue(_ptr(W), W.stride(0), rows, cols, b, mode, _ptr(mask), s, _ptr(row_ptr),
-                                      _ptr(col_idx), _ptr(vals), _ptr(row_order), _ptr(aux),
-                                      aux_bytes if with_aux else 0, cap_v, result.data_ptr() + 8 * i, _ptr(ws),
-                                      ws.numel(), stream)
+        rc = L.blast_bsr_pack_enqueue(W.data_ptr(), W.stride(0), rows, cols, b, mode,
+                                      None if mask is None else mask.data_ptr(), s, base + o_rp, base + o_ci,
+                                      base + o_vals, base + o_ro, base + o_aux if with_aux else None,
+                                      aux_bytes if with_aux else 0, cap_v, res_p + 8 * i, ws_p, ws_max, stream)
         _check(rc, "blast_bsr_pack_enqueue")
-        out.append([rows, cols, row_ptr, col_idx, vals, row_order, aux, cap_v])
-    res = result.cpu()  # synchronises: every matrix is complete, ws can go
+    # the views are made while the device works
+    i32 = arena.view(torch.int32)
+    out = []
+    for rows, cols, cap_v, aux_bytes, sizes, (o_rp, o_ro, o_ci, o_aux, o_vals) in plans:
+        nbr = rows // b
+        out.append((i32[o_rp // 4:o_rp // 4 + nbr + 1], i32[o_ci // 4:o_ci // 4 + max(cap_v, 1)],
+                    arena[o_vals:o_vals + sizes[4]].view(torch.int16), i32[o_ro // 4:o_ro // 4 + max(nbr, 1)],
+                    arena[o_aux:o_aux + sizes[3]] if with_aux else None))
+    res = result.cpu().tolist()  # synchronises: every matrix is complete, ws can go
     packed = []
-    for i, (rows, cols, row_ptr, col_idx, vals, row_order, aux, cap_v) in enumerate(out):
-        nnz, heavy = int(res[i, 0]), int(res[i, 1])
+    for (rows, cols, cap_v, *_), (row_ptr, col_idx, vals, row_order, aux), (nnz, heavy) in zip(plans, out, res):
         if nnz > cap_v:
             _check(-4, "blast_bsr_pack_enqueue")
         packed.append(PackedBsr(rows, cols, b, nnz, row_ptr, col_idx, vals, row_order, aux, heavy))
