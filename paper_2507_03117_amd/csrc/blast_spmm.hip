@@ -18,6 +18,7 @@
 #include "kern_tile.h"
 #include "kern_stream.h"
 #include "kern_decode.h"
+#include "kern_b16.h"
 
 using namespace blast_dev;
 
@@ -55,6 +56,58 @@ int launch_tile(TileArgs a, hipStream_t stream) {
   if (int rc = ensure_lds_limit(reinterpret_cast<const void*>(&k_spmm_tile<B, DUAL>), C::LDS_BYTES, lds_set)) return rc;
   k_spmm_tile<B, DUAL><<<dim3((unsigned)grid), dim3(256), C::LDS_BYTES, stream>>>(a);
   BLAST_LAUNCH_CHECK("k_spmm_tile");
+  return BLAST_OK;
+}
+
+// 16 x 16 blocks, token-major 16-byte-aligned activations: pairs of blocks on the 32-deep matrix instruction,
+// operands straight from global memory.  A wave takes 16, 32 or 64 tokens of one block row.
+int cu_count();
+
+template <bool DUAL, bool POST, int NS, bool SPLIT>
+int launch_b16_ns(TileArgs a, int y_vec, hipStream_t stream) {
+  a.ntt = (a.T + 16 * NS - 1) / (16 * NS);
+  const int64_t items = (int64_t)a.ntt * a.nbr;
+  const int64_t grid = SPLIT ? items : (items + 3) / 4;
+  if (grid <= 0) return BLAST_OK;
+  if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
+  k_spmm_b16<DUAL, POST, NS, SPLIT><<<dim3((unsigned)grid), dim3(256), 0, stream>>>(a, y_vec);
+  BLAST_LAUNCH_CHECK("k_spmm_b16");
+  return BLAST_OK;
+}
+
+// A wave takes 16, 32 or 64 tokens of a block row.  While that makes fewer than eight waves per CU, a workgroup
+// shares one (block row, token tile) and its waves deal the row's blocks: 1B-shaped layer, 128 tokens,
+// 31 -> 19 us per MLP pass, 512 tokens 39 -> 32.
+template <bool DUAL, bool POST>
+int launch_b16_t(const TileArgs& a, int y_vec, hipStream_t stream) {
+  if (a.T <= 16) return launch_b16_ns<DUAL, POST, 1, true>(a, y_vec, stream);
+  if (a.T <= 32) return launch_b16_ns<DUAL, POST, 2, true>(a, y_vec, stream);
+  if ((int64_t)((a.T + 63) / 64) * a.nbr < 8 * cu_count()) return launch_b16_ns<DUAL, POST, 4, true>(a, y_vec, stream);
+  return launch_b16_ns<DUAL, POST, 4, false>(a, y_vec, stream);
+}
+
+template <bool DUAL>
+int launch_b16(const TileArgs& a, hipStream_t stream) {
+  const int y_vec = a.y_grp16 || (a.syi == 1 && a.syt % 4 == 0 && blast::aligned(a.Y, a.y_bf16 ? 8 : 16));
+  if constexpr (!DUAL) {
+    if (a.act >= 0) return launch_b16_t<false, true>(a, y_vec, stream);  // an activation on the output
+  }
+  return launch_b16_t<DUAL, false>(a, y_vec, stream);
+}
+
+// From this many tokens on, a product with 16-wide blocks reads its activations from column groups of 16
+// features ([K/16][T][16], see kern_b16.h) when the caller's workspace has room for the regrouped copy.
+constexpr int64_t kGroup16MinTokens = 33;
+size_t group16_bytes(int64_t K, int64_t T) { return blast::align_up((size_t)K * (size_t)T * 2, 256); }
+bool group16_applies(int32_t b, int32_t x_layout, const void* X, int64_t ldx, int64_t T) {
+  return b == 16 && T >= kGroup16MinTokens && x_layout == BLAST_TOKEN_MAJOR && ldx % 8 == 0 && blast::aligned(X, 16);
+}
+int enqueue_group16(const uint16_t* X, int64_t ldx, int64_t T, int64_t K, uint16_t* Xg, hipStream_t stream) {
+  const int64_t nbc = K / 16;
+  if (T <= 0 || nbc <= 0) return BLAST_OK;
+  if ((nbc + 7) / 8 > 65535) return BLAST_ERR_INVALID_ARG;
+  k_group16<<<dim3((unsigned)((T + 15) / 16), (unsigned)((nbc + 7) / 8)), dim3(256), 0, stream>>>(X, ldx, (int)T, (int)nbc, Xg);
+  BLAST_LAUNCH_CHECK("k_group16");
   return BLAST_OK;
 }
 
@@ -444,6 +497,7 @@ int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, con
       default: break;
     }
   }
+  if (b == 16 && (a.x_vec || a.x_grp16) && a.T > 0) return launch_b16<DUAL>(a, stream);
   switch (b) {
     case 16: return launch_tile<16, DUAL>(a, stream);
     case 32: return launch_tile<32, DUAL>(a, stream);
@@ -542,14 +596,14 @@ ChunkPlan plan_of(const blast_bsr_view* v, int64_t T) {
 extern "C" int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_bytes) {
   if (int rc = check_view(W)) return rc;
   if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
-  *ws_bytes = 0;
+  // 16-wide blocks at many tokens: room for the activations regrouped by block column (optional: without it the
+  // product reads the caller's tensor as it lies)
+  *ws_bytes = (W->b == 16 && T >= kGroup16MinTokens) ? group16_bytes(W->cols, T) : 0;
   return BLAST_OK;
 }
 
 extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_t ldx, int32_t x_layout, int64_t T,
                               void* Y, int64_t ldy, int32_t y_dtype, void* ws, size_t ws_bytes, void* stream_) {
-  (void)ws;
-  (void)ws_bytes;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (int rc = check_view(W)) return rc;
   if (T < 0 || T > INT32_MAX / 2) return BLAST_ERR_INVALID_ARG;
@@ -566,6 +620,13 @@ extern "C" int blast_bsr_spmm(const blast_bsr_view* W, const uint16_t* X, int64_
   a.nbr = (int)(W->rows / W->b);
   a.kdim = W->cols;
   a.act = -1;
+  if (group16_applies(W->b, x_layout, X, ldx, T) && ws && blast::aligned(ws, 16) &&
+      ws_bytes >= group16_bytes(W->cols, T)) {
+    uint16_t* Xg = static_cast<uint16_t*>(ws);
+    if (int rc = enqueue_group16(X, ldx, T, W->cols, Xg, stream)) return rc;
+    a.X = Xg;
+    a.x_grp16 = 1;
+  }
   return dispatch_tile<false>(W->b, a, W->nnz, stream, plan_of(W, T));
 }
 
@@ -645,7 +706,8 @@ extern "C" int blast_sparse_mlp_workspace(const blast_bsr_view* Wgate, const bla
   if (int rc = check_view(Wup)) return rc;
   if (int rc = check_view(Wdown)) return rc;
   if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
-  *ws_bytes = mlp_workspace_bytes(Wgate->rows, T) + mlp_long_bytes(Wgate, Wup, T);
+  *ws_bytes = mlp_workspace_bytes(Wgate->rows, T) + mlp_long_bytes(Wgate, Wup, T) +
+              ((Wgate->b == 16 && T >= kGroup16MinTokens) ? group16_bytes(Wgate->cols, T) : 0);
   return BLAST_OK;
 }
 
@@ -654,7 +716,8 @@ extern "C" int blast_sparse_mlp2_workspace(const blast_bsr_view* W1, const blast
   if (int rc = check_view(W1)) return rc;
   if (int rc = check_view(W2)) return rc;
   if (T < 0 || !ws_bytes) return BLAST_ERR_INVALID_ARG;
-  *ws_bytes = mlp_workspace_bytes(W1->rows, T);
+  *ws_bytes = mlp_workspace_bytes(W1->rows, T) +
+              ((W1->b == 16 && T >= kGroup16MinTokens) ? group16_bytes(W1->cols, T) : 0);
   return BLAST_OK;
 }
 
@@ -741,7 +804,8 @@ int enqueue_gated_long(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, c
 // `ls` (may be null): scratch for the long rows, long_scratch_bytes() per matrix.
 int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const uint16_t* X, int64_t ldx,
                   int32_t x_layout, int64_t T, int32_t act, uint16_t* H, int64_t ldh, int32_t h_layout,
-                  hipStream_t stream, ZeroJob* side_job = nullptr, const LongScratch* ls = nullptr) {
+                  hipStream_t stream, ZeroJob* side_job = nullptr, const LongScratch* ls = nullptr,
+                  const uint16_t* Xg16 = nullptr, bool h_grp16 = false) {
   ChunkPlan side{};
   side.zero_job = side_job;
   // upper bound of the fullest joint row (exact when the same row is the fullest of both matrices)
@@ -756,6 +820,11 @@ int enqueue_gated(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const 
   g.nbr = (int)(Wgate->rows / Wgate->b);
   g.kdim = Wgate->cols;
   g.act = act;
+  if (Xg16) {  // 16-wide blocks: X regrouped by block column, H kept that way
+    g.X = Xg16;
+    g.x_grp16 = 1;
+  }
+  g.y_grp16 = h_grp16 ? 1 : 0;
   if (!Wup) return dispatch_tile<false>(Wgate->b, g, Wgate->nnz, stream, side);
   if (ls && g.x_vec && T > 0 && (int64_t)T * g.sxt * 2 < ((int64_t)1 << 32) && long_rows_pay(Wgate, Wup, T)) {
     switch (Wgate->b) {
@@ -948,8 +1017,17 @@ int enqueue_mlp(const blast_bsr_view* Wgate, const blast_bsr_view* Wup, const bl
       ls.S0 = reinterpret_cast<float*>(static_cast<char*>(ws) + need);
       ls.S1 = reinterpret_cast<float*>(static_cast<char*>(ws) + need + long_scratch_bytes(Wgate, T));
     }
+    // 16-wide blocks at many tokens: X is regrouped by block column behind the workspace proper (where the
+    // caller left room for it), and H is written and read in the same form
+    const uint16_t* Xg16 = nullptr;
+    if (group16_applies(b, x_layout, X, ldx, T) && ws_bytes >= need + extra + group16_bytes(E, T)) {
+      uint16_t* xg = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + need + extra);
+      if (int rc = enqueue_group16(X, ldx, T, E, xg, stream)) return rc;
+      Xg16 = xg;
+      d.x_grp16 = 1;
+    }
     if (int rc = enqueue_gated(Wgate, Wup, X, ldx, x_layout, T, act, H, I, BLAST_TOKEN_MAJOR, stream,
-                               zj.hdr ? &zj : nullptr, have_ls ? &ls : nullptr))
+                               zj.hdr ? &zj : nullptr, have_ls ? &ls : nullptr, Xg16, Xg16 != nullptr))
       return rc;
   }
   if (events) BLAST_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(events[1]), stream));

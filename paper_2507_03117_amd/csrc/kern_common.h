@@ -30,6 +30,8 @@ struct TileArgs {
   int act;               // gated product: the activation of the gate; single matrix: < 0 none, else applied to the output
   int x_vec;             // 1: 16-byte loads of X are legal (sxk == 1, aligned)
   int y_fast;            // 1: syi == 1 and every byte offset inside a 256-token slab of Y fits 31 bits
+  int x_grp16;           // 16-wide blocks only: X is stored in column groups of 16 features, [kdim/16][T][16]
+  int y_grp16;           // ... and so is Y, [rows/16][T][16]
 };
 
 // Index arrays are read-only for the lifetime of a launch: reading them through the

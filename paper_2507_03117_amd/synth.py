@@ -148,6 +148,8 @@ class Workload:
 WORKLOADS: Dict[str, Workload] = {
     "linear_1024x4096_b32_s90": Workload("linear_1024x4096_b32_s90", 0, "linear", 4096, 1024, 32, 0.90, "uniform", (64,)),
     "llama1b_b64_s90": Workload("llama1b_b64_s90", 1, "mlp", 2048, 8192, 64, 0.90, "uniform", (1, 16, 128, 2048)),
+    # the same layer with the smallest block size of the paper's block-size sweeps (same seed: same dense weights)
+    "llama1b_b16_s90": Workload("llama1b_b16_s90", 1, "mlp", 2048, 8192, 16, 0.90, "uniform", (1, 16, 128, 2048)),
     "llama3b_b64_s70": Workload("llama3b_b64_s70", 2, "mlp", 3072, 8192, 64, 0.70, "topk", (4096,)),
     "llama3b_b64_s80": Workload("llama3b_b64_s80", 2, "mlp", 3072, 8192, 64, 0.80, "topk", (4096,)),
     "llama3b_b64_s90": Workload("llama3b_b64_s90", 2, "mlp", 3072, 8192, 64, 0.90, "topk", (4096,)),
