@@ -522,7 +522,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="time the headline workload only")
     ap.add_argument("--extras", action="store_true",
-                    help="also: packer and mask-update times, two-matrix MLP, backward products, E5M2 product")
+                    help="also: packer and mask-update times, two-matrix MLP, backward products, E5M2 product, 16-wide blocks")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -632,9 +632,20 @@ def main():
             "backward": backward_products("llama1b_b64_s90", 2048, args.steps, args.warmup, cpu),
             "e5m2": e5m2_product("llama1b_b64_s90", (16, 2048), args.steps, args.warmup, cpu),
             "pack": pack_times(api, torch, synth, cpu),
+            "block16": block16_rows(api, torch, synth, args.steps, args.warmup),
         }
 
     print(json.dumps(out, separators=(",", ":")))
+
+
+def block16_rows(api, torch, synth, steps, warmup):
+    """The 1B-shaped layer with 16 x 16 blocks (the smallest block size of the paper's block-size sweeps), same dense
+    weights and sparsity as the 64-wide configuration: rows as in `configs`."""
+    Lc = Layer("llama1b_b16_s90", api, torch, synth)
+    rows = [Lc.row(Tc, max(steps, 100) if Tc < 512 else steps, warmup) for Tc in (1, 16, 128, 2048)]
+    del Lc
+    torch.cuda.empty_cache()
+    return rows
 
 
 def pack_times(api, torch, synth, cpu):

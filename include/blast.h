@@ -345,7 +345,11 @@ int blast_bsr_joint_row_order(const blast_bsr_view* A, const blast_bsr_view* B, 
  *   T                  number of tokens (columns of X), >= 0; T == 0 is a no-op.
  *   Y, ldy, y_dtype    output rows x T in the SAME layout as X; fp32 (BLAST_F32) or bf16 (BLAST_BF16,
  *                      rounded to nearest even from the fp32 accumulator).
- *   ws, ws_bytes       at least blast_bsr_spmm_workspace() bytes (may be 0 -> ws may be NULL).
+ *   ws, ws_bytes       scratch of blast_bsr_spmm_workspace() bytes, 16-byte aligned.  Nonzero only for 16 x 16
+ *                      blocks from 33 tokens on: there the activations are first regrouped by block column
+ *                      ([cols/16][T][16], so that the 16 tokens x 16 features a block multiplies are 512
+ *                      consecutive bytes instead of 16 pieces of 32); a call with less (or NULL) reads X as it
+ *                      lies, with identical results.
  * When W carries `aux` and a very full block row (see max_row_blocks), that row's chunks add their partial
  * sums into an fp32 Y with atomics in no fixed order: such rows are reproducible up to fp32 rounding of that
  * sum only (bf16 output and the gated product never take that path).
@@ -382,6 +386,9 @@ int blast_bsr_spmm_workspace(const blast_bsr_view* W, int64_t T, size_t* ws_byte
  * fp32 sums are rounded differently from a row walked in one piece); blast_sparse_mlp_workspace() includes that
  * scratch exactly when the path applies, and a call handed the smaller workspace of the plain path takes the
  * plain path.
+ * With 16 x 16 blocks, from 33 tokens on, blast_sparse_mlp_workspace() also includes room for X regrouped by
+ * block column (see blast_bsr_spmm); H is then kept in the same form.  A call handed the smaller workspace reads
+ * X as it lies.
  * Never synchronises.  Errors: INVALID_ARG, SHAPE (including inconsistent I/E/b between the three
  * matrices), UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */
