@@ -63,36 +63,40 @@ int launch_tile(TileArgs a, hipStream_t stream) {
 // operands straight from global memory.  A wave takes 16, 32 or 64 tokens of one block row.
 int cu_count();
 
-template <bool DUAL, bool POST, int NS, bool SPLIT>
+template <bool DUAL, bool POST, int NS, bool SPLIT, int NW = 4>
 int launch_b16_ns(TileArgs a, int y_vec, hipStream_t stream) {
   a.ntt = (a.T + 16 * NS - 1) / (16 * NS);
   const int64_t items = (int64_t)a.ntt * a.nbr;
   const int64_t grid = SPLIT ? items : (items + 3) / 4;
   if (grid <= 0) return BLAST_OK;
   if (grid > INT32_MAX) return BLAST_ERR_INVALID_ARG;
-  k_spmm_b16<DUAL, POST, NS, SPLIT><<<dim3((unsigned)grid), dim3(256), 0, stream>>>(a, y_vec);
+  k_spmm_b16<DUAL, POST, NS, SPLIT, NW><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(a, y_vec);
   BLAST_LAUNCH_CHECK("k_spmm_b16");
   return BLAST_OK;
 }
 
 // A wave takes 16, 32 or 64 tokens of a block row.  While that makes fewer than eight waves per CU, a workgroup
 // shares one (block row, token tile) and its waves deal the row's blocks: 1B-shaped layer, 128 tokens,
-// 31 -> 19 us per MLP pass, 512 tokens 39 -> 32.
+// 31 -> 19 us per MLP pass, 512 tokens 39 -> 32.  Up to 16 tokens, rows of more than 16 pairs on average go to
+// sixteen waves instead of four (the 1B-shaped down projection: 128 rows of 51 blocks).
 template <bool DUAL, bool POST>
-int launch_b16_t(const TileArgs& a, int y_vec, hipStream_t stream) {
-  if (a.T <= 16) return launch_b16_ns<DUAL, POST, 1, true>(a, y_vec, stream);
+int launch_b16_t(const TileArgs& a, int64_t nnz, int y_vec, hipStream_t stream) {
+  if (a.T <= 16) {
+    if (nnz > (int64_t)32 * a.nbr) return launch_b16_ns<DUAL, POST, 1, true, 16>(a, y_vec, stream);
+    return launch_b16_ns<DUAL, POST, 1, true>(a, y_vec, stream);
+  }
   if (a.T <= 32) return launch_b16_ns<DUAL, POST, 2, true>(a, y_vec, stream);
   if ((int64_t)((a.T + 63) / 64) * a.nbr < 8 * cu_count()) return launch_b16_ns<DUAL, POST, 4, true>(a, y_vec, stream);
   return launch_b16_ns<DUAL, POST, 4, false>(a, y_vec, stream);
 }
 
 template <bool DUAL>
-int launch_b16(const TileArgs& a, hipStream_t stream) {
+int launch_b16(const TileArgs& a, int64_t nnz, hipStream_t stream) {
   const int y_vec = a.y_grp16 || (a.syi == 1 && a.syt % 4 == 0 && blast::aligned(a.Y, a.y_bf16 ? 8 : 16));
   if constexpr (!DUAL) {
-    if (a.act >= 0) return launch_b16_t<false, true>(a, y_vec, stream);  // an activation on the output
+    if (a.act >= 0) return launch_b16_t<false, true>(a, nnz, y_vec, stream);  // an activation on the output
   }
-  return launch_b16_t<DUAL, false>(a, y_vec, stream);
+  return launch_b16_t<DUAL, false>(a, nnz, y_vec, stream);
 }
 
 // From this many tokens on, a product with 16-wide blocks reads its activations from column groups of 16
@@ -497,7 +501,7 @@ int dispatch_tile(int b, const TileArgs& a, int64_t nnz, hipStream_t stream, con
       default: break;
     }
   }
-  if (b == 16 && (a.x_vec || a.x_grp16) && a.T > 0) return launch_b16<DUAL>(a, stream);
+  if (b == 16 && (a.x_vec || a.x_grp16) && a.T > 0) return launch_b16<DUAL>(a, nnz, stream);
   switch (b) {
     case 16: return launch_tile<16, DUAL>(a, stream);
     case 32: return launch_tile<32, DUAL>(a, stream);

@@ -78,10 +78,10 @@ __device__ __forceinline__ void b16_row(const TileArgs& a, const MatDev& m, int 
   }
 }
 
-// Adds the four waves' partial sums; every wave calls it, wave 0 returns with the totals.
-template <int NS>
+// Adds the waves' partial sums; every wave calls it, wave 0 returns with the totals (added in wave order).
+template <int NS, int NW>
 __device__ __forceinline__ void b16_join(f32x4_b16 (&acc)[NS]) {
-  __shared__ f32x4_b16 part[3][NS][64];
+  __shared__ f32x4_b16 part[NW - 1][NS][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (wave != 0) {
 #pragma unroll
@@ -90,7 +90,9 @@ __device__ __forceinline__ void b16_join(f32x4_b16 (&acc)[NS]) {
   __syncthreads();
   if (wave == 0) {
 #pragma unroll
-    for (int s = 0; s < NS; ++s) acc[s] += (part[0][s][lane] + part[1][s][lane]) + part[2][s][lane];
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int w = 0; w < NW - 1; ++w) acc[s] += part[w][s][lane];
   }
 }
 
@@ -98,11 +100,12 @@ __device__ __forceinline__ void b16_join(f32x4_b16 (&acc)[NS]) {
 // bf16-or-fp32 act(W0 x) * (W1 x); POST: one matrix, the activation on its output.
 // y_vec: the four rows of a lane can be stored with one 16-byte (fp32) / 8-byte (bf16) store (always so for a
 // grouped output).
-// SPLIT (decode token counts): the whole workgroup owns one (block row, token tile), its four waves deal the
-// row's pairs among themselves and the partial sums meet in LDS - there are too few rows to fill the chip with a
-// wave each, and a row walked by one wave is a chain of dependent loads.
-template <bool DUAL, bool POST, int NS, bool SPLIT = false>
-__global__ __launch_bounds__(256) void k_spmm_b16(const TileArgs a, const int y_vec) {
+// SPLIT (decode token counts): the whole workgroup owns one (block row, token tile), its NW waves (4 or 16) deal
+// the row's pairs among themselves and the partial sums meet in LDS - there are too few rows to fill the chip
+// with a wave each, and a row walked by one wave is a chain of dependent loads.
+template <bool DUAL, bool POST, int NS, bool SPLIT = false, int NW = 4>
+__global__ __launch_bounds__(NW * 64) void k_spmm_b16(const TileArgs a, const int y_vec) {
+  static_assert(SPLIT || NW == 4, "without SPLIT a workgroup is four independent waves");
   static_assert(!(POST && DUAL), "an activation on the output belongs to the single-matrix product");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t item = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
@@ -123,22 +126,22 @@ __global__ __launch_bounds__(256) void k_spmm_b16(const TileArgs a, const int y_
   f32x4_b16 acc0[NS];
 #pragma unroll
   for (int s = 0; s < NS; ++s) acc0[s] = f32x4_b16{0.f, 0.f, 0.f, 0.f};
-  b16_row<NS>(a, a.m0, r, xrow, cstride, acc0, SPLIT ? wave : 0, SPLIT ? 4 : 1);
+  b16_row<NS>(a, a.m0, r, xrow, cstride, acc0, SPLIT ? wave : 0, SPLIT ? NW : 1);
   if (DUAL) {
     f32x4_b16 acc1[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) acc1[s] = f32x4_b16{0.f, 0.f, 0.f, 0.f};
-    b16_row<NS>(a, a.m1, r, xrow, cstride, acc1, SPLIT ? wave : 0, SPLIT ? 4 : 1);
-    if (SPLIT) b16_join<NS>(acc1);
+    b16_row<NS>(a, a.m1, r, xrow, cstride, acc1, SPLIT ? wave : 0, SPLIT ? NW : 1);
+    if (SPLIT) b16_join<NS, NW>(acc1);
     if (SPLIT) __syncthreads();  // the buffer is used again for the first matrix
-    if (SPLIT) b16_join<NS>(acc0);
+    if (SPLIT) b16_join<NS, NW>(acc0);
     if (SPLIT && wave != 0) return;
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc0[s][j] = apply_act(a.act, acc0[s][j]) * acc1[s][j];
   } else if (SPLIT) {
-    b16_join<NS>(acc0);
+    b16_join<NS, NW>(acc0);
     if (wave != 0) return;
   }
   if (POST) {

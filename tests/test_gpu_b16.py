@@ -65,6 +65,36 @@ def test_spmm_every_block_count_and_tile_edge(api, T):
     assert np.all(np.abs(got - want) <= np.maximum(np.abs(want), 1e-30) * 2.0 ** -7 + 1e-12)
 
 
+@pytest.mark.parametrize("T", [1, 7, 16])
+@pytest.mark.parametrize("gated", [False, True])
+def test_long_rows_at_decode_token_counts(api, T, gated):
+    """Rows of 30-80 blocks at up to 16 tokens: sixteen waves deal a row's pairs (some get none, one gets the
+    odd last block) and their partial sums are added in LDS."""
+    import torch
+
+    rng = np.random.default_rng(1650 + T)
+    counts = [80, 33, 47, 0, 61]
+    nbc = 80
+    w = synth.gauss_bf16(rng, (len(counts) * B, nbc * B), 0.02)
+    x = synth.gauss_bf16(rng, (T, nbc * B), 1.0)
+    dev, ref = _pack(api, w, _rows_with_counts(rng, counts, nbc))
+    if not gated:
+        y = api.bsr_spmm(dev, to_dev(x), out=torch.full((T, len(counts) * B), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, orc.spmm(ref, x), f"b=16 long rows T={T}")
+        return
+    w2 = synth.gauss_bf16(rng, (len(counts) * B, nbc * B), 0.02)
+    dev2, ref2 = _pack(api, w2, _rows_with_counts(rng, counts[::-1], nbc))
+    h = api.bsr_gated_spmm(dev, dev2, to_dev(x))
+    torch.cuda.synchronize()
+    rd = orc.pack(synth.gauss_bf16(rng, (nbc * B, len(counts) * B), 0.05), B,
+                  synth.uniform_mask(rng, nbc, len(counts), 0.5))
+    _, h_or = orc.mlp(ref, ref2, rd, x, return_h=True)
+    got = synth.bf16_bits_to_f32(bits_of(h)).astype(np.float64).T
+    want = synth.bf16_bits_to_f32(h_or).astype(np.float64)
+    assert (np.abs(got - want) <= np.abs(want) * 2.0 ** -7 + 1e-5 * np.sqrt((want ** 2).mean())).all()
+
+
 @pytest.mark.parametrize("T", [5, 40, 130])
 def test_spmm_strided_and_unaligned_operands(api, T):
     """Outputs whose row pitch or address rules out the 16-byte stores take the element-wise stores of the same
