@@ -62,9 +62,17 @@ __device__ __forceinline__ double sq_bf16_pair(uint32_t w) {
 
 // One workgroup per block: squared Frobenius norm in fp64.  The summation tree
 // depends only on b, so equal blocks get equal scores wherever they sit.
+// blockIdx.y == 1: a second matrix of the same shape (the gradient of the mask update) into a second score array.
 __global__ __launch_bounds__(256) void k_block_scores(const uint16_t* __restrict__ W, int64_t ldw, int nbc, int b,
-                                                      double* __restrict__ score) {
+                                                      double* __restrict__ score,
+                                                      const uint16_t* __restrict__ W1 = nullptr, int64_t ldw1 = 0,
+                                                      double* __restrict__ score1 = nullptr) {
   __shared__ double red[256];
+  if (blockIdx.y == 1) {
+    W = W1;
+    ldw = ldw1;
+    score = score1;
+  }
   const int64_t blk = blockIdx.x;
   const int64_t br = blk / nbc, bc = blk % nbc;
   const uint16_t* base = W + br * b * ldw + bc * b;
@@ -547,42 +555,30 @@ static_assert(kSmallN + 1024 < 65536, "two counts share a 32-bit word");
 static_assert((blast::kChunkBlocks & (blast::kChunkBlocks - 1)) == 0 &&
               (blast::kWideChunkBlocks & (blast::kWideChunkBlocks - 1)) == 0, "chunk sizes are powers of two");
 
-struct SmallOut {
-  int* row_ptr;
-  int* col_idx;
-  int* blk_row;
-  int* row_order;
-  uint8_t* mask_out;  // may be null (the caller's mask is the mask)
-  int* col_ptr;       // null without aux
-  int* csc_row;       // csc_blk follows at the next 16-byte boundary after nnz entries
-  int* scalars;       // {nnz, max_row_blocks}
-  int64_t nnz_cap;
+// LDS scratch of select_small.
+struct SelectShared {
+  unsigned hist[256];
+  int wave_tot[16];
+  unsigned long long prefix, kth;
+  long long remaining;
+  unsigned h;
 };
 
-template <bool TOPK>
-__global__ __launch_bounds__(1024) void k_pack_small(const double* __restrict__ score,
-                                                     const uint8_t* __restrict__ mask_in, int nbr, int nbc,
-                                                     long long n_keep, SmallOut o, PlanOut narrow, PlanOut wide) {
-  __shared__ int kpos[kSmallN];  // position of a stored block in col_idx / vals, by row-major block index
-  __shared__ uint8_t m[kSmallN];
-  __shared__ __attribute__((aligned(16))) int rcnt[1024];
-  __shared__ int ccnt[1024];
-  __shared__ int rptr[1025];
-  __shared__ int rord[1024];
-  __shared__ unsigned hist[256];
-  __shared__ int wave_tot[16];
-  __shared__ int sh[3];
-  __shared__ unsigned long long s_prefix, s_kth;
-  __shared__ long long s_remaining;
-  __shared__ unsigned s_h;
+// Exact selection of the n_keep highest of n <= kSmallN scores by one workgroup of 1024 threads: thread t owns
+// scores t * per ... t * per + per - 1 (per = ceil(n / 1024)) and returns their keep flags (bit j: score
+// t * per + j is kept).  Equal scores are kept in index order.
+__device__ __forceinline__ unsigned select_small(const double* __restrict__ score, int n, long long n_keep, int per,
+                                                 SelectShared& sh) {
   const int tid = threadIdx.x, lane = lane_id();
-  const int n = nbr * nbc;
-  const int per = (n + 1023) >> 10;  // blocks per thread (uniform); the loops below are unrolled to kSmallPer
   const int e0 = tid * per;
-  rcnt[tid] = 0;
-  ccnt[tid] = 0;
-  unsigned keep = 0u;  // bit j: block e0 + j is kept
-  if (TOPK) {
+  unsigned* hist = sh.hist;
+  int* wave_tot = sh.wave_tot;
+  unsigned long long& s_prefix = sh.prefix;
+  unsigned long long& s_kth = sh.kth;
+  long long& s_remaining = sh.remaining;
+  unsigned& s_h = sh.h;
+  unsigned keep = 0u;
+  {
     unsigned long long key[kSmallPer];
 #pragma unroll
     for (int j = 0; j < kSmallPer; ++j)
@@ -685,6 +681,70 @@ __global__ __launch_bounds__(1024) void k_pack_small(const double* __restrict__ 
         }
       }
     }
+  }
+  return keep;
+}
+
+// One workgroup: mask[i] = 1 for the n_keep highest of n <= kSmallN scores, else 0.
+__global__ __launch_bounds__(1024) void k_select_small(const double* __restrict__ score, int n, long long n_keep,
+                                                       uint8_t* __restrict__ mask) {
+  __shared__ SelectShared ssh;
+  const int per = (n + 1023) >> 10, e0 = threadIdx.x * per;
+  const unsigned keep = select_small(score, n, n_keep, per, ssh);
+#pragma unroll
+  for (int j = 0; j < kSmallPer; ++j)
+    if (j < per && e0 + j < n) mask[e0 + j] = (keep >> j) & 1u;
+}
+
+// One workgroup: the mask update of prune-and-grow on n <= kSmallN blocks - both selections and their merge
+// (1 where the weight's selection keeps the block, 2 where only the gradient's does, else 0).
+__global__ __launch_bounds__(1024) void k_masks_small(const double* __restrict__ score_w,
+                                                      const double* __restrict__ score_g, int n, long long n_keep,
+                                                      uint8_t* __restrict__ mask) {
+  __shared__ SelectShared ssh;
+  const int per = (n + 1023) >> 10, e0 = threadIdx.x * per;
+  const unsigned keep_w = select_small(score_w, n, n_keep, per, ssh);
+  wg_barrier<true>();  // the scratch is used again
+  const unsigned keep_g = select_small(score_g, n, n_keep, per, ssh);
+#pragma unroll
+  for (int j = 0; j < kSmallPer; ++j)
+    if (j < per && e0 + j < n) mask[e0 + j] = ((keep_w >> j) & 1u) ? 1 : (((keep_g >> j) & 1u) ? 2 : 0);
+}
+
+struct SmallOut {
+  int* row_ptr;
+  int* col_idx;
+  int* blk_row;
+  int* row_order;
+  uint8_t* mask_out;  // may be null (the caller's mask is the mask)
+  int* col_ptr;       // null without aux
+  int* csc_row;       // csc_blk follows at the next 16-byte boundary after nnz entries
+  int* scalars;       // {nnz, max_row_blocks}
+  int64_t nnz_cap;
+};
+
+template <bool TOPK>
+__global__ __launch_bounds__(1024) void k_pack_small(const double* __restrict__ score,
+                                                     const uint8_t* __restrict__ mask_in, int nbr, int nbc,
+                                                     long long n_keep, SmallOut o, PlanOut narrow, PlanOut wide) {
+  __shared__ int kpos[kSmallN];  // position of a stored block in col_idx / vals, by row-major block index
+  __shared__ uint8_t m[kSmallN];
+  __shared__ __attribute__((aligned(16))) int rcnt[1024];
+  __shared__ int ccnt[1024];
+  __shared__ int rptr[1025];
+  __shared__ int rord[1024];
+  __shared__ SelectShared ssh;
+  __shared__ int sh[3];
+  int* wave_tot = ssh.wave_tot;
+  const int tid = threadIdx.x;
+  const int n = nbr * nbc;
+  const int per = (n + 1023) >> 10;  // blocks per thread (uniform); the loops below are unrolled to kSmallPer
+  const int e0 = tid * per;
+  rcnt[tid] = 0;
+  ccnt[tid] = 0;
+  unsigned keep = 0u;  // bit j: block e0 + j is kept
+  if (TOPK) {
+    keep = select_small(score, n, n_keep, per, ssh);
   } else {
 #pragma unroll
     for (int j = 0; j < kSmallPer; ++j) keep |= (j < per && e0 + j < n && mask_in[e0 + j] != 0) ? 1u << j : 0u;
@@ -1258,10 +1318,13 @@ extern "C" int blast_generate_masks(const uint16_t* W, int64_t ldw, const uint16
     BLAST_LAUNCH_CHECK("k_fill_u8");
     return BLAST_OK;
   }
-  k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(W, ldw, (int)nbc, b, scores);
-  BLAST_LAUNCH_CHECK("k_block_scores(W)");
-  k_block_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(G, ldg, (int)nbc, b, scores_g);
-  BLAST_LAUNCH_CHECK("k_block_scores(G)");
+  k_block_scores<<<dim3((unsigned)n, 2), dim3(256), 0, stream>>>(W, ldw, (int)nbc, b, scores, G, ldg, scores_g);
+  BLAST_LAUNCH_CHECK("k_block_scores(W, G)");
+  if (n <= kSmallN) {  // both selections and the merge in one workgroup
+    k_masks_small<<<dim3(1), dim3(1024), 0, stream>>>(scores, scores_g, (int)n, (long long)n_keep, mask_out);
+    BLAST_LAUNCH_CHECK("k_masks_small");
+    return BLAST_OK;
+  }
   k_select_topk<<<dim3(2), dim3(1024), 0, stream>>>(scores, n, n_keep, mw, scores_g, mg);
   BLAST_LAUNCH_CHECK("k_select_topk(W, G)");
   k_merge_masks<<<per_elem, dim3(256), 0, stream>>>(mw, mg, n, mask_out);
@@ -1307,6 +1370,11 @@ extern "C" int blast_pooled_topk_mask(const float* S, int64_t lds, int64_t rows,
   double* scores = static_cast<double*>(ws);
   k_pooled_scores<<<dim3((unsigned)n), dim3(256), 0, stream>>>(S, lds, (int)nbc, b, scores);
   BLAST_LAUNCH_CHECK("k_pooled_scores");
+  if (n <= kSmallN) {
+    k_select_small<<<dim3(1), dim3(1024), 0, stream>>>(scores, (int)n, (long long)n_keep, mask_out);
+    BLAST_LAUNCH_CHECK("k_select_small(pooled)");
+    return BLAST_OK;
+  }
   k_select_topk<<<dim3(1), dim3(1024), 0, stream>>>(scores, n, n_keep, mask_out);
   BLAST_LAUNCH_CHECK("k_select_topk(pooled)");
   return BLAST_OK;
