@@ -151,6 +151,35 @@ def test_gated_product_matches_the_oracles_intermediate(api, T, act):
     assert not got[2 * B:3 * B].any() and not got[5 * B:6 * B].any()
 
 
+def test_mlp_random_shapes(api):
+    """Twenty seeded random 16-wide-block MLPs (random sizes, sparsities, token counts, activations): Y against the
+    oracle.  Token counts from 33 on go through the regrouped activations, and once more with a workspace that
+    has no room for them."""
+    import torch
+
+    rng = np.random.default_rng(1900)
+    for case in range(20):
+        E, I = int(rng.integers(1, 24)) * B, int(rng.integers(1, 40)) * B
+        T = int(rng.choice([1, 3, 16, 17, 32, 33, 64, 65, 100, 257]))
+        s = float(rng.choice([0.0, 0.3, 0.7, 0.9]))
+        act = str(rng.choice(["silu", "gelu", "relu"]))
+        g, u, d = (synth.gauss_bf16(rng, sh, 0.05) for sh in ((I, E), (I, E), (E, I)))
+        mg, mu = (synth.uniform_mask(rng, I // B, E // B, s) for _ in range(2))
+        md = synth.uniform_mask(rng, E // B, I // B, s)
+        x = synth.gauss_bf16(rng, (T, E), 1.0)
+        (dg, rg), (du, ru), (dd, rd) = _pack(api, g, mg), _pack(api, u, mu), _pack(api, d, md)
+        y_or = orc.mlp(rg, ru, rd, x, activation=act)
+        y = api.sparse_mlp(dg, du, dd, to_dev(x), act=act, out=torch.full((T, E), float("nan"), device="cuda:0"))
+        torch.cuda.synchronize()
+        check_close(y.cpu().numpy().T, y_or, f"b=16 mlp case {case}: E={E} I={I} T={T} s={s} {act}")
+        if T >= 33:  # a workspace without room for the regrouped X: the same kernels on the token-major tensor
+            small = api.mlp_workspace_bytes(dg, du, dd, T) - (2 * E * T + 255) // 256 * 256
+            yb = api.sparse_mlp(dg, du, dd, to_dev(x), act=act,
+                                ws=torch.empty(small, dtype=torch.uint8, device="cuda:0"))
+            torch.cuda.synchronize()
+            check_close(yb.cpu().numpy().T, y_or, f"b=16 mlp case {case}, small workspace")
+
+
 @pytest.mark.parametrize("T", [1, 16, 128, 2048])
 def test_llama1b_b16_mlp(api, T):
     """The 1B-shaped layer with 16 x 16 blocks at 90 %: 6553 blocks per matrix, about 13 per block row."""

@@ -233,6 +233,28 @@ def test_pack_single_workgroup_massive_ties(api, sparsity):
     _assert_packed_equal(dev, ref, b)
 
 
+def test_pack_random_shapes(api):
+    """Forty seeded random block grids on both sides of the single-workgroup limits, random sparsities, both
+    modes: every index array against the oracle."""
+    rng = np.random.default_rng(240)
+    b = 16
+    done = 0
+    while done < 40:
+        nbr = int(rng.integers(1, 1300)) if rng.random() < 0.3 else int(rng.integers(1, 140))
+        nbc = int(rng.integers(1, 1300)) if rng.random() < 0.3 else int(rng.integers(1, 140))
+        if nbr * nbc > 20000:
+            continue
+        done += 1
+        s = float(rng.choice([0.0, 0.37, 0.5, 0.8, 0.93, 0.99, 1.0]))
+        W = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.02)
+        mask = synth.uniform_mask(rng, nbr, nbc, s)
+        dev, ref = pack_both(api, W, b, mask=mask)
+        _assert_packed_equal(dev, ref, b)
+        ref_t, _, gap = orc.pack_topk(W, b, s)
+        if gap > 1e-9:
+            _assert_packed_equal(api.bsr_pack(to_dev(W), b, sparsity=s), ref_t, b)
+
+
 def test_pack_many_matches_single_calls(api):
     """blast_bsr_pack_enqueue: three matrices of different shapes packed back to back with one shared scratch
     buffer and one synchronisation, in both modes; one of them takes the many-launch path."""
