@@ -165,7 +165,8 @@ int blast_bsr_pack(const uint16_t* W, int64_t ldw, int64_t rows, int64_t cols, i
  * arguments and outputs, except:
  *   result      out [2] int32, 8-byte aligned, DEVICE: {number of stored blocks, stored blocks of the fullest
  *               block row (0 without aux)}; the caller reads it after synchronising, once for all matrices.
- * Only enqueues.  ws belongs to the call until the stream has passed its work; calls on the same stream may
+ * Only enqueues kernels (no copies, no memsets): the call can be recorded into a HIP graph and replayed on a
+ * weight whose values change.  ws belongs to the call until the stream has passed its work; calls on the same stream may
  * share one ws (the larger of their sizes).  When result[0] > nnz_cap the outputs are as blast_bsr_pack
  * leaves them on BLAST_ERR_CAPACITY.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED_BLOCK, WORKSPACE, HIP.
  */

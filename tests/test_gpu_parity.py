@@ -273,6 +273,63 @@ def test_pack_many_matches_single_calls(api):
         _assert_packed_equal(dev, orc.pack(W, b, m), b)
 
 
+@pytest.mark.parametrize("shape", [(128, 32), (170, 100)])
+def test_pack_enqueue_replays_from_a_graph(api, shape):
+    """blast_bsr_pack_enqueue only enqueues kernels, so the re-packing of a weight whose values change (the mask
+    update of every step_size iterations) can be recorded once and replayed: three replays on three different
+    weights, with eager work in between, each against the oracle.  Both the single-workgroup path and the
+    many-launch path."""
+    import ctypes as C
+
+    import torch
+
+    rng = np.random.default_rng(250 + shape[0])
+    b, (nbr, nbc), s = 32, shape, 0.85
+    L = api.lib()
+    cap, auxb, wsb = C.c_int64(0), C.c_size_t(0), C.c_size_t(0)
+    assert L.blast_bsr_pack_bound(nbr * b, nbc * b, b, api.PACK_TOPK_FROBENIUS, s, C.byref(cap), C.byref(auxb),
+                                  C.byref(wsb)) == 0
+    dev = "cuda:0"
+    W = torch.zeros((nbr * b, nbc * b), dtype=torch.bfloat16, device=dev)
+    row_ptr = torch.empty(nbr + 1, dtype=torch.int32, device=dev)
+    col_idx = torch.empty(cap.value, dtype=torch.int32, device=dev)
+    vals = torch.empty(cap.value * b * b, dtype=torch.int16, device=dev)
+    row_order = torch.empty(nbr, dtype=torch.int32, device=dev)
+    aux = torch.empty(auxb.value, dtype=torch.uint8, device=dev)
+    ws = torch.empty(wsb.value, dtype=torch.uint8, device=dev)
+    result = torch.zeros(2, dtype=torch.int32, device=dev)
+
+    def enqueue():
+        rc = L.blast_bsr_pack_enqueue(W.data_ptr(), W.stride(0), nbr * b, nbc * b, b, api.PACK_TOPK_FROBENIUS, None, s,
+                                      row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr(), row_order.data_ptr(),
+                                      aux.data_ptr(), auxb.value, cap.value, result.data_ptr(), ws.data_ptr(),
+                                      wsb.value, C.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue()  # (warm-up outside the capture)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    for rep in range(3):
+        w = synth.gauss_bf16(rng, (nbr * b, nbc * b), 0.02)
+        ref, _, gap = orc.pack_topk(w, b, s)
+        assert gap > 1e-9
+        W.copy_(to_dev(w))
+        row_ptr.fill_(-1)
+        col_idx.fill_(-1)
+        result.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert result.cpu().tolist() == [ref.nnz, int(np.diff(ref.row_ptr).max())]
+        packed = api.PackedBsr(nbr * b, nbc * b, b, ref.nnz, row_ptr, col_idx, vals, row_order, aux,
+                               int(np.diff(ref.row_ptr).max()))
+        _assert_packed_equal(packed, ref, b)
+
+
 # ------------------------------------------------------------------ SpMM
 @pytest.mark.parametrize("b", [16, 32, 64, 128])
 @pytest.mark.parametrize("T", [1, 3, 17, 64, 100, 300])
