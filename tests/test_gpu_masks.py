@@ -43,6 +43,29 @@ def test_generate_masks_matches_oracle(api, b, rows, cols, s):
         assert (want == 2).any() and (want == 1).any() and (want == 0).any()
 
 
+def test_generate_masks_and_pooled_selection_beyond_one_workgroup(api):
+    """26624 blocks: more than one workgroup selects from (8192), so the mask update runs its two selections side
+    by side over global memory and merges them in a launch of its own, and the pooled selection takes the same
+    select."""
+    import torch
+
+    rng = np.random.default_rng(9750)
+    b, rows, cols, s = 16, 2048, 3328, 0.9
+    W, G = synth.gauss_bf16(rng, (rows, cols), 0.02), synth.gauss_bf16(rng, (rows, cols), 1e-3)
+    assert _gaps_ok(W, b, s) and _gaps_ok(G, b, s), "selection hangs on rounding: reseed"
+    m = api.generate_masks(to_dev(W), to_dev(G), b, s)
+    torch.cuda.synchronize()
+    want = orc.generate_masks(W, G, b, s)
+    assert np.array_equal(m.cpu().numpy(), want)
+    assert (want == 2).any() and (want == 1).any() and (want == 0).any()
+    S = (rng.standard_normal((rows, cols)) * 1e-3).astype(np.float32)
+    want, gap = orc.pooled_topk_mask(S, b, s)
+    assert gap > 1e-9, "selection hangs on rounding: reseed"
+    m = api.pooled_topk_mask(torch.from_numpy(S).to("cuda:0"), b, s)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy(), want)
+
+
 def test_generate_masks_ties_and_equal_gradient(api):
     import torch
 
