@@ -559,7 +559,7 @@ def main():
         settle = max(args.warmup, int(30.0 / max(step_ms, 1e-3)) + 1)  # about 30 ms of passes
         gu_ms, dn_ms = time_phases_in_pass(api, torch, L.sets, L.x(T), T, wl.hidden, ksteps, settle)
         gu_tf = 2.0 * b * b * T * (L.g.nnz + L.u.nnz) / (gu_ms * 1e-3) / 1e12
-        kname = "k_spmm_stream<%d,dual> (gate/up + activation)" % b
+        kname = ("k_spmm_b16<dual>" if b == 16 else "k_spmm_stream<%d,dual>" % b) + " (gate/up + activation)"
         tr = profile_traffic(wl.name, T, "gate_up")
         roofline = {"bound": "mfma", "kernel": kname, "achieved": sig(gu_tf), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": sig(gu_tf / PEAK_BF16_TFLOPS, 3), "kernel_ms": sig(gu_ms), "down_kernel_ms": sig(dn_ms),
