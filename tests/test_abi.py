@@ -60,6 +60,30 @@ def test_pack_bound_and_errors():
     assert L.blast_bsr_aux_bytes(8192, 2048, 64, 4096) >= 4 * (32 + 1 + 2 * 4096)
 
 
+def test_pack_argument_errors_return_before_any_launch():
+    """blast_bsr_pack and blast_bsr_pack_enqueue check every argument before they touch the GPU."""
+    L = api.lib()
+    nnz, heavy = C.c_int64(0), C.c_int32(0)
+    buf = (C.c_int64 * 8)()  # (stands in for device pointers: no call below gets as far as using them)
+    p = C.cast(buf, C.c_void_p)
+    common = (p, 128, 128, 128, 64, api.PACK_MASK, p, 0.0, p, p, p, p, None, 0, 4)
+    assert L.blast_bsr_pack(*common, None, C.byref(heavy), p, 1 << 20, None) == -1  # nnz_out missing
+    assert L.blast_bsr_pack(*common, C.byref(nnz), C.byref(heavy), None, 0, None) == -5  # no workspace
+    assert L.blast_bsr_pack(p, 128, 130, 128, 64, 0, p, 0.0, p, p, p, p, None, 0, 4, C.byref(nnz), None, p, 1 << 20,
+                            None) == -2  # rows not a multiple of b
+    assert L.blast_bsr_pack(p, 64, 128, 128, 64, 0, p, 0.0, p, p, p, p, None, 0, 4, C.byref(nnz), None, p, 1 << 20,
+                            None) == -1  # row pitch shorter than a row
+    assert L.blast_bsr_pack(p, 128, 128, 128, 64, 0, None, 0.0, p, p, p, p, None, 0, 4, C.byref(nnz), None, p, 1 << 20,
+                            None) == -1  # mask mode without a mask
+    assert L.blast_bsr_pack(p, 128, 128, 128, 64, 1, None, 1.5, p, p, p, p, None, 0, 4, C.byref(nnz), None, p, 1 << 20,
+                            None) == -1  # sparsity out of range
+    assert L.blast_bsr_pack_enqueue(*common, None, p, 1 << 20, None) == -1  # result missing
+    assert L.blast_bsr_pack_enqueue(*common, C.c_void_p(p.value + 4), p, 1 << 20, None) == -1  # result misaligned
+    assert L.blast_bsr_pack_enqueue(*common, p, None, 0, None) == -5  # no workspace
+    assert L.blast_bsr_pack_enqueue(p, 128, 128, 128, 48, 0, p, 0.0, p, p, p, p, None, 0, 4, p, p, 1 << 20, None) == -3
+    assert L.blast_bsr_pack_enqueue(p, 128, 128, 128, 64, 0, p, 0.0, p, p, p, p, p, 8, 4, p, p, 1 << 20, None) == -5  # aux too small
+
+
 def test_spmm_and_mlp_argument_errors_return_before_any_launch():
     L = api.lib()
     v = api.BsrView(128, 128, 64, 0, 0, None, None, None, None, None)
