@@ -592,7 +592,7 @@ def main():
         sec = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": sig(2.0 * b * b * sel.size * L.nnz / sec / 1e12), "unit": "TFLOP/s",
                                "cores": orc.num_threads(), "kind": "oracle", "seconds": sig(sec),
-                               "sample": "%d of %d tokens (every token tile and tile seam), all rows" % (sel.size, T)}
+                               "sample": "%d of %d tokens (all tiles and seams), all rows" % (sel.size, T)}
         # the same sample doubles as a parity check of the timed launch configuration
         y = api.sparse_mlp(L.g, L.u, L.d, L.x(T))
         torch.cuda.synchronize()
@@ -622,7 +622,7 @@ def main():
                 rows.append(Lc.row_e5m2w(1, st, args.warmup))
             del Lc
             torch.cuda.empty_cache()
-        out["configs_columns"] = ["llama*", "T", "us_graph", "us_eager", "bound", "TFLOPs|GBps", "frac"]
+        out["configs_columns"] = ["llama*", "T", "us_graph", "us_eager", "bound", "TFLOPs|GBps", "frac"]  # of the peak
         out["configs"] = rows
 
     if args.extras:
