@@ -633,9 +633,49 @@ def main():
             "e5m2": e5m2_product("llama1b_b64_s90", (16, 2048), args.steps, args.warmup, cpu),
             "pack": pack_times(api, torch, synth, cpu),
             "block16": block16_rows(api, torch, synth, args.steps, args.warmup),
+            "dense_context": dense_context(api, torch, synth),
         }
 
     print(json.dumps(out, separators=(",", ":")))
+
+
+def dense_context(api, torch, synth):
+    """Context only (the paper quotes its MLP results as speedups over dense library GEMMs, Sec. 5.2): the dense
+    MLP of the same shape - three torch.matmul calls (hipBLASLt) and the activation on random bf16 weights - timed on
+    the same GPU next to the block-sparse pass.  Not part of the product path and not a target."""
+    out = []
+    for name, T in (("llama405b_b128_s95_zipf", 2048), ("llama3b_b64_s70", 4096), ("llama1b_b64_s90", 2048)):
+        wl = synth.WORKLOADS[name]
+        E, I = wl.hidden, wl.inter
+        Lc = Layer(name, api, torch, synth)
+        graph, eager = Lc.time(T, 20, 10)
+        sparse_ms = graph if graph is not None else eager
+        del Lc
+        torch.cuda.empty_cache()
+        wg, wu = (torch.randn((I, E), device="cuda:0", dtype=torch.bfloat16) * 0.02 for _ in range(2))
+        wd = torch.randn((E, I), device="cuda:0", dtype=torch.bfloat16) * 0.02
+        x = torch.randn((T, E), device="cuda:0", dtype=torch.bfloat16)
+
+        def dense():
+            return (torch.nn.functional.silu(x @ wg.t()) * (x @ wu.t())) @ wd.t()
+
+        for _ in range(3):
+            dense()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            dense()
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / reps
+        out.append({"workload": name, "T": T, "sparse_ms": sig(sparse_ms), "dense_torch_matmul_ms": sig(dense_ms),
+                    "dense_TFLOPs": sig(6.0 * E * I * T / (dense_ms * 1e-3) / 1e12),
+                    "speedup_over_dense": sig(dense_ms / sparse_ms, 3)})
+        del wg, wu, wd, x
+        torch.cuda.empty_cache()
+    return out
 
 
 def block16_rows(api, torch, synth, steps, warmup):
