@@ -675,6 +675,37 @@ def dense_context(api, torch, synth):
                     "speedup_over_dense": sig(dense_ms / sparse_ms, 3)})
         del wg, wu, wd, x
         torch.cuda.empty_cache()
+    # the single product at the shape of the paper's largest kernel comparison (Sec. 5.2: Seq 1024, Emb 32768,
+    # N = 4 Emb, 95 % sparsity), 128-wide blocks, uniform mask
+    import numpy as np
+
+    b, T, K, N = 128, 1024, 32768, 131072
+    W = torch.randn((N, K), device="cuda:0", dtype=torch.bfloat16) * 0.02
+    mask = torch.from_numpy(synth.uniform_mask(np.random.default_rng(synth.BASE_SEED + 9), N // b, K // b, 0.95)).to("cuda:0")
+    p = api.bsr_pack(W, b, mask=mask, nnz_cap=int(mask.sum().item()))
+    x = torch.randn((T, K), device="cuda:0", dtype=torch.bfloat16)
+    y = torch.empty((T, N), device="cuda:0", dtype=torch.bfloat16)
+
+    def timed(fn, reps=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    sparse_ms = timed(lambda: api.bsr_spmm(p, x, out=y))
+    dense_ms = timed(lambda: torch.matmul(x, W.t(), out=y))
+    out.append({"workload": "spmm %dx%d b%d s95 uniform" % (N, K, b), "T": T, "sparse_ms": sig(sparse_ms),
+                "sparse_TFLOPs": sig(2.0 * b * b * T * p.nnz / (sparse_ms * 1e-3) / 1e12),
+                "dense_torch_matmul_ms": sig(dense_ms), "dense_TFLOPs": sig(2.0 * N * K * T / (dense_ms * 1e-3) / 1e12),
+                "speedup_over_dense": sig(dense_ms / sparse_ms, 3)})
+    del W, p, x, y, mask
+    torch.cuda.empty_cache()
     return out
 
 
