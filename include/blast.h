@@ -432,9 +432,12 @@ int blast_sparse_mlp_handover_test(const blast_bsr_view* Wgate, const blast_bsr_
  * lives in a device array of BLAST_STATIC_SCRATCH_BYTES that the library owns: every GPU the library runs on
  * holds one such array from the moment the library is loaded until the process ends.  The call allocates and
  * frees nothing.
- *   limit   the scratch needed, blast_sparse_mlp_workspace(), must not exceed blast_sparse_mlp_static_limit()
- *           (= BLAST_STATIC_SCRATCH_BYTES; about 2 * T * I bytes): otherwise BLAST_ERR_WORKSPACE and nothing
- *           is enqueued.  The Llama-3.2-1B-shaped layer (I = 8192) fits up to T = 2048.
+ *   limit   the scratch the call cannot do without - H, the hand-over slots and the status words, about
+ *           2 * T * I bytes - must not exceed blast_sparse_mlp_static_limit() (= BLAST_STATIC_SCRATCH_BYTES):
+ *           otherwise BLAST_ERR_WORKSPACE and nothing is enqueued.  The optional parts that
+ *           blast_sparse_mlp_workspace() adds (sums of long rows, regrouped activations of 16 x 16 blocks) are
+ *           used when the array has room for them and left out otherwise, as with a caller's smaller workspace.
+ *           The Llama-3.2-1B-shaped layer (I = 8192) fits up to T = 2048.
  *   sharing every call on one GPU uses that GPU's one array: calls that may overlap in time on the same GPU
  *           (different streams, different host threads) race on it and must be serialised by the caller.
  *           Nothing in the array needs clearing between calls and nothing in it outlives a call.
